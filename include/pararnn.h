@@ -1,0 +1,153 @@
+/*
+ * pararnn.h -- C ABI of the MI355X (gfx950) implementation of the
+ * sequence-parallel application of a nonlinear RNN (ParaRNN, arXiv 2510.21450).
+ *
+ * The library applies h_l = f(h_{l-1}, u_l), l = 1..L (Sec. 2, Eq. (1)) to all
+ * L timesteps at once: the L equations are stacked into one nonlinear system
+ * (Eq. (2)) and solved with Newton's method (Eq. (3), Alg. 1a); every Newton
+ * iteration evaluates residuals and Jacobians for all timesteps in parallel
+ * and solves the block bi-diagonal linear system with a prefix scan over
+ * affine maps (the role of Alg. 1b).  The backward pass is the matching
+ * reverse scan with transposed Jacobians (Eq. (6)).
+ *
+ * All data pointers are DEVICE pointers unless stated otherwise.  The caller
+ * owns every buffer; the library allocates nothing, keeps no state between
+ * calls and only enqueues work on the given HIP stream (hipStream_t passed as
+ * void*, NULL = the default stream).  Results are valid once the stream has
+ * been synchronised.  Calls that share a workspace must be ordered on one
+ * stream.
+ *
+ * Layouts (H is always the contiguous axis):
+ *   u          [B][L][G][H]  pre-activations u_l = B x_l + b of the G gates
+ *   h, dL_dh   [B][L][S][H]  states / loss gradients, S values per channel
+ *   h0, dL_dh0 [B][S][H]
+ *   params     always fp32.  Diagonal cells: [2][G][H] = recurrent weights,
+ *              then biases.  Dense cell: W[H][H] row-major.
+ * Gate order: GRU (z, r, c); LSTM (i, f, o, g).  LSTM state order (c, h).
+ */
+#ifndef PARARNN_H
+#define PARARNN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Cells.  G gates, S state values per channel.
+ *  GRU_DIAG   (G=3,S=1): Sec. 3, Eq. (7a) with diagonal A_* (Eq. (9)):
+ *             z = sig(a_z h + u_z + b_z), r = sig(a_r h + u_r + b_r),
+ *             c = tanh(a_c (r h) + u_c + b_c), h' = (1-z) h + z c.
+ *             Jacobian: Eq. (8a), a scalar per channel.
+ *  LSTM_DIAG  (G=4,S=2): i,f,o = sig(w_* h + u_* + b_*), g = tanh(w_g h + u_g + b_g),
+ *             c' = f c + i g, h' = o tanh(c').  2x2 Jacobian block per channel
+ *             (the structure of Eq. (8b)).
+ *  TANH_DENSE (G=1,S=1): h' = tanh(W h + u), dense Jacobian diag(1-h'^2) W
+ *             (the generic dense case of Sec. 2.1).
+ *  LINEAR_DIAG(G=1,S=1): h' = a h + u + b, the linear SSM of the footnote in
+ *             Sec. 2; used to test that one Newton solve is exact. */
+typedef enum {
+    PARARNN_GRU_DIAG = 0,
+    PARARNN_LSTM_DIAG = 1,
+    PARARNN_TANH_DENSE = 2,
+    PARARNN_LINEAR_DIAG = 3
+} pararnn_cell_t;
+
+/* Storage type of u, h0, h, dL_dh, dL_du, dL_dh0.  With BF16 all arithmetic,
+ * the Newton iterate, scan carries and dL_dparams stay fp32; the iterate is
+ * rounded to bf16 (nearest-even) once, when h is written. */
+typedef enum { PARARNN_F32 = 0, PARARNN_BF16 = 1 } pararnn_dtype_t;
+
+typedef enum {
+    PARARNN_OK = 0,
+    PARARNN_NOT_CONVERGED = 1,       /* device status only: max_iter reached */
+    PARARNN_INVALID_ARG = 2,
+    PARARNN_WORKSPACE_TOO_SMALL = 3,
+    PARARNN_HIP_ERROR = 4,
+    PARARNN_NONFINITE = 5,           /* device status only: max|dh| became inf/nan */
+    PARARNN_UNSUPPORTED = 6,         /* valid request the library has no kernel for */
+    PARARNN_INTERNAL = 7             /* device status only: a bounded wait ran out */
+} pararnn_status_t;
+
+/* Human-readable name of a status code (static string, host). */
+const char *pararnn_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int pararnn_version(void);
+
+/* Gates G and state values S of a cell; -1 for an unknown cell. */
+int pararnn_cell_gates(int cell);
+int pararnn_cell_state(int cell);
+
+/* Bytes of device workspace pararnn_forward (backward = 0) or
+ * pararnn_backward (backward = 1) needs for this problem; 0 on invalid
+ * arguments.  The workspace needs 256-byte alignment and no initialisation. */
+size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int backward);
+
+/*
+ * Forward: solve Eq. (2) by Newton iterations (Alg. 1a).
+ *   initial guess   h^0_l = f(h0, u_l) for every l (App. A; f(0, x_l) when h0 = 0)
+ *   iteration k     r_l = f(h^{k-1}_{l-1}, u_l) - h^{k-1}_l,
+ *                   J_l = df/dh at (h^{k-1}_{l-1}, u_l)        (Eq. (3))
+ *                   delta_l = J_l delta_{l-1} + r_l, delta_0 = 0 (Eq. (4), as a
+ *                   prefix scan over affine maps (A2,b2)o(A1,b1) = (A2A1, A2b1+b2))
+ *                   h^k = h^{k-1} + delta;  m_k = max |delta| over the whole batch
+ *   stop            when m_k <= tol (checked on the device after the update;
+ *                   no host synchronisation per iteration) or k = max_iter.
+ *
+ *   params, u, h0   inputs; h0 may be NULL (= zeros, the paper's h_0 = 0)
+ *   tol             absolute tolerance on max|delta h|; tol < 0 runs exactly
+ *                   max_iter iterations (the paper's fixed N_its) with status OK
+ *   max_iter        >= 0; 0 returns the initial guess
+ *   h               out [B][L][S][H]; on NOT_CONVERGED the last iterate
+ *   iters           out, DEVICE int32[2] = {iterations performed (number of
+ *                   linear solves), device status (OK / NOT_CONVERGED /
+ *                   NONFINITE / INTERNAL)}
+ *   delta_trace     optional DEVICE float[max_iter]: m_k of each performed
+ *                   iteration (entries past iters are left untouched); or NULL
+ *   workspace       DEVICE scratch of at least pararnn_workspace_bytes(.., 0)
+ * Returns PARARNN_OK when everything was enqueued, else the host-detectable
+ * error (INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR); on error
+ * nothing useful has been written.
+ */
+int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0,
+                    int B, int L, int H, float tol, int max_iter, void *h, int *iters,
+                    float *delta_trace, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward: the adjoint recurrence of Eq. (6) at the forward result h,
+ *   lam_L = g_L,  lam_{l-1} = J_l^T lam_l + g_{l-1},  J_l = df/dh at (h_{l-1}, u_l),
+ * evaluated as one reverse prefix scan, plus the step-local gradients
+ *   dL_du_l = (df/du_l)^T lam_l,  dL_dparams = sum_{b,l} (df/dparams)^T lam_l,
+ *   dL_dh0 = J_1^T lam_1.
+ *
+ *   h               the converged forward output (same layout/dtype as forward's h)
+ *   dL_dh           g, [B][L][S][H]; for the LSTM it covers both c and h
+ *   dL_du           out [B][L][G][H]
+ *   dL_dparams      out fp32, same shape as params; overwritten, not accumulated
+ *   dL_dh0          out [B][S][H], or NULL
+ *   workspace       DEVICE scratch of at least pararnn_workspace_bytes(.., 1)
+ * Same return convention as pararnn_forward.
+ */
+int pararnn_backward(int cell, int dtype, const float *params, const void *u, const void *h0,
+                     const void *h, const void *dL_dh, int B, int L, int H, void *dL_du,
+                     float *dL_dparams, void *dL_dh0, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/*
+ * The linear solve on its own (the operation Alg. 1b performs), for testing
+ * and profiling the scan without a cell: delta_l = J_l delta_{l-1} + r_l,
+ * delta_0 = 0 (reverse = 0), or the adjoint
+ * lam_l = J_{l+1}^T lam_{l+1} + r_l, lam_{L+1} = 0 (reverse = 1).
+ *   kind   0: diagonal, J [B][L][H];  1: 2x2 blocks, J [B][L][2][2][H] with
+ *          J[p][q] = d(out_p)/d(in_q);  r, delta [B][L][S][H], fp32
+ *   workspace as for pararnn_forward of a cell with that structure
+ *          (GRU_DIAG for kind 0, LSTM_DIAG for kind 1).
+ */
+int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, int B, int L, int H,
+                        float *delta, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARARNN_H */

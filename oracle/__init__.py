@@ -1,0 +1,166 @@
+"""Python access to the CPU oracle (oracle/pararnn_oracle.c) through ctypes.
+
+Test infrastructure only: imported by tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py, never by the product package.  Arrays are numpy,
+C-contiguous, in the oracle's precision (float64 by default; `precision="f32"`
+selects the second build of the same C file, used to inspect fp32 iteration
+traces).  Argument marshalling only: all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "pararnn_oracle.c")
+_LIBS = {}
+
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3}
+STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 5: "NONFINITE"}
+JAC_KIND = {"diag": 0, "block2": 1, "dense": 2}
+
+
+def _lib_path(precision):
+    return os.path.join(_DIR, f"liboracle_{precision}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile the oracle with gcc: -O2, no fast-math, OpenMP over the batch."""
+    for precision, real in (("f64", "double"), ("f32", "float")):
+        out = _lib_path(precision)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
+               f"-DREAL={real}", "-o", out, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    _LIBS.clear()
+
+
+def _lib(precision="f64"):
+    if precision not in _LIBS:
+        build()
+        lib = ctypes.CDLL(_lib_path(precision))
+        assert lib.oracle_real_bytes() == (8 if precision == "f64" else 4)
+        _LIBS[precision] = lib
+    return _LIBS[precision]
+
+
+def _np_t(precision):
+    return np.float64 if precision == "f64" else np.float32
+
+
+def _c(a, precision):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=_np_t(precision))
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def dims(cell: str):
+    lib = _lib()
+    return lib.oracle_gates(CELLS[cell]), lib.oracle_state(CELLS[cell])
+
+
+def num_threads() -> int:
+    return _lib().oracle_num_threads()
+
+
+def cell_step(cell, params, hp, u, precision="f64"):
+    """f(hp, u) for one timestep: hp [S][H], u [G][H] -> [S][H]."""
+    lib = _lib(precision)
+    hp_a, hp_p = _c(hp, precision)
+    H = hp_a.shape[-1]
+    _, pp = _c(params, precision)
+    _, up = _c(u, precision)
+    out = np.empty_like(hp_a)
+    lib.oracle_cell_step(CELLS[cell], H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def cell_jacobian(cell, params, hp, u, precision="f64"):
+    """J = df/dh at (hp, u): diag [H]; lstm [2][2][H]; dense [H][H]."""
+    lib = _lib(precision)
+    hp_a, hp_p = _c(hp, precision)
+    H = hp_a.shape[-1]
+    _, pp = _c(params, precision)
+    _, up = _c(u, precision)
+    shape = {"gru_diag": (H,), "linear_diag": (H,), "lstm_diag": (2, 2, H), "tanh_dense": (H, H)}[cell]
+    out = np.empty(shape, dtype=_np_t(precision))
+    lib.oracle_cell_jacobian(CELLS[cell], H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def seq_unroll(cell, params, u, h0=None, precision="f64"):
+    """Eq. (1). u [B][L][G][H] -> h [B][L][S][H]."""
+    lib = _lib(precision)
+    u_a, up = _c(u, precision)
+    B, L, G, H = u_a.shape
+    S = lib.oracle_state(CELLS[cell])
+    assert G == lib.oracle_gates(CELLS[cell])
+    _, pp = _c(params, precision)
+    _h0, h0p = _c(h0, precision)
+    h = np.empty((B, L, S, H), dtype=_np_t(precision))
+    lib.oracle_seq_unroll(CELLS[cell], B, L, H, pp, up, h0p, h.ctypes.data_as(ctypes.c_void_p))
+    return h
+
+
+def _solver(name, kind, J, r, precision):
+    lib = _lib(precision)
+    r_a, rp = _c(r, precision)
+    L = r_a.shape[0]
+    H = r_a.shape[-1]
+    _J, Jp = _c(J, precision)
+    d = np.empty_like(r_a)
+    getattr(lib, name)(JAC_KIND[kind], L, H, Jp, rp, d.ctypes.data_as(ctypes.c_void_p))
+    return d
+
+
+def forward_substitution(kind, J, r, precision="f64"):
+    """Eq. (4) on one sequence. J [L][...], r [L][S][H] (or [L][H]) -> delta."""
+    return _solver("oracle_forward_substitution", kind, J, r, precision)
+
+
+def parallel_reduce(kind, J, r, precision="f64"):
+    """Alg. 1b on one sequence; same arguments as forward_substitution."""
+    return _solver("oracle_parallel_reduce", kind, J, r, precision)
+
+
+def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64"):
+    """Alg. 1a with Eq. (4). Returns (h, iters, status, trace[iters])."""
+    lib = _lib(precision)
+    u_a, up = _c(u, precision)
+    B, L, G, H = u_a.shape
+    S = lib.oracle_state(CELLS[cell])
+    _, pp = _c(params, precision)
+    _h0, h0p = _c(h0, precision)
+    h = np.empty((B, L, S, H), dtype=_np_t(precision))
+    iters = ctypes.c_int(0)
+    trace = np.zeros(max(max_iter, 1), dtype=_np_t(precision))
+    real = ctypes.c_double if precision == "f64" else ctypes.c_float
+    lib.oracle_newton.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 3 + [real, ctypes.c_int,
+                                  ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
+    st = lib.oracle_newton(CELLS[cell], B, L, H, pp, up, h0p, tol, max_iter,
+                           h.ctypes.data_as(ctypes.c_void_p), ctypes.byref(iters),
+                           trace.ctypes.data_as(ctypes.c_void_p))
+    return h, iters.value, st, trace[:iters.value].copy()
+
+
+def backward(cell, params, u, h0, h, g, precision="f64"):
+    """Eq. (6) + step-local chain rule. Returns (du, dparams, dh0)."""
+    lib = _lib(precision)
+    u_a, up = _c(u, precision)
+    B, L, G, H = u_a.shape
+    S = lib.oracle_state(CELLS[cell])
+    p_a, pp = _c(params, precision)
+    _h0, h0p = _c(h0, precision)
+    _h, hp = _c(h, precision)
+    _g, gp = _c(g, precision)
+    du = np.empty_like(u_a)
+    dparams = np.empty_like(p_a)
+    dh0 = np.empty((B, S, H), dtype=_np_t(precision))
+    lib.oracle_backward(CELLS[cell], B, L, H, pp, up, h0p, hp, gp,
+                        du.ctypes.data_as(ctypes.c_void_p), dparams.ctypes.data_as(ctypes.c_void_p),
+                        dh0.ctypes.data_as(ctypes.c_void_p))
+    return du, dparams, dh0

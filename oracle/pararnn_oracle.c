@@ -1,0 +1,498 @@
+/*
+ * CPU oracle for the sequence-parallel application of a nonlinear RNN.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * sequential implementation of what the method computes, used only by the
+ * tests, the smoke check and the benchmark's CPU-baseline leg.  It shares no
+ * code, header, table or helper with the HIP library and neither side
+ * includes or links the other.
+ *
+ * What it follows (ParaRNN, arXiv 2510.21450):
+ *   - Sec. 2, Eq. (1): the recurrence h_l = f(h_{l-1}, x_l)       -> oracle_seq_unroll
+ *   - Sec. 2, Eq. (3) + Alg. 1a: Newton on the stacked system     -> oracle_newton
+ *   - Sec. 2, Eq. (4): forward substitution of the linearised,
+ *     block bi-diagonal system                                    -> oracle_forward_substitution
+ *   - Sec. 2, Alg. 1b: the naive parallel reduction               -> oracle_parallel_reduce
+ *   - Sec. 2, Eq. (6): the backward (adjoint) recurrence          -> oracle_backward
+ *   - Sec. 3, Eq. (7a) with the diagonal weights of Eq. (9): GRU  -> cell 0
+ *   - Sec. 3, Eq. (8a): its Jacobian                              -> oracle_cell_jacobian
+ *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
+ *
+ * Precision: REAL is double unless the file is compiled with -DREAL=float
+ * (a second build used only to look at fp32 iteration traces).
+ *
+ * Layouts (H contiguous): u [B][L][G][H]; h, g [B][L][S][H]; h0 [B][S][H];
+ * params for the diagonal cells [2][G][H] (recurrent weights, then biases),
+ * for the dense cell W[H][H] row-major.  Gate order GRU (z,r,c), LSTM
+ * (i,f,o,g); LSTM state order (c,h).
+ *
+ * Parity pins: every function here is checked by tests that do not call it to
+ * produce their own expected value (closed forms, finite differences, brute
+ * force of Eq. (5), invariants); none is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#ifndef REAL
+#define REAL double
+#endif
+
+enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3 };
+enum { ST_OK = 0, ST_NOT_CONVERGED = 1, ST_INVALID = 2, ST_NONFINITE = 5 };
+enum { JAC_DIAG = 0, JAC_BLOCK2 = 1, JAC_DENSE = 2 };
+
+static REAL sigmoid(REAL x) { return (REAL)1 / ((REAL)1 + (REAL)exp(-(double)x)); }
+static REAL tanh_r(REAL x) { return (REAL)tanh((double)x); }
+
+int oracle_real_bytes(void) { return (int)sizeof(REAL); }
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+int oracle_gates(int cell)
+{
+    switch (cell) {
+    case CELL_GRU_DIAG: return 3;
+    case CELL_LSTM_DIAG: return 4;
+    case CELL_TANH_DENSE: return 1;
+    case CELL_LINEAR_DIAG: return 1;
+    }
+    return -1;
+}
+
+int oracle_state(int cell) { return cell == CELL_LSTM_DIAG ? 2 : (cell >= 0 && cell <= 3 ? 1 : -1); }
+
+int oracle_jac_kind(int cell)
+{
+    if (cell == CELL_LSTM_DIAG) return JAC_BLOCK2;
+    if (cell == CELL_TANH_DENSE) return JAC_DENSE;
+    return JAC_DIAG;
+}
+
+/* number of REALs one Jacobian J_l occupies */
+static size_t jac_size(int kind, int H)
+{
+    if (kind == JAC_DIAG) return (size_t)H;
+    if (kind == JAC_BLOCK2) return (size_t)4 * H;       /* [2][2][H] */
+    return (size_t)H * H;                               /* [H][H] row-major */
+}
+
+static size_t param_count(int cell, int H)
+{
+    if (cell == CELL_TANH_DENSE) return (size_t)H * H;
+    return (size_t)2 * oracle_gates(cell) * H;
+}
+
+/* ------------------------------------------------------------------ cells */
+
+/* One application of the recurrence step f, Eq. (1).
+ * hp: previous state [S][H]; u: pre-activations [G][H]; out: new state [S][H]. */
+void oracle_cell_step(int cell, int H, const REAL *params, const REAL *hp, const REAL *u, REAL *out)
+{
+    int j;
+    if (cell == CELL_GRU_DIAG) {
+        /* Eq. (7a) with A_* = diag(a_*) (Eq. (9)) and u = B x + b precomputed;
+         * an extra bias b_* is part of params. */
+        const REAL *a = params, *b = params + 3 * H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hp[j];
+            REAL z = sigmoid(a[0 * H + j] * h + u[0 * H + j] + b[0 * H + j]);
+            REAL r = sigmoid(a[1 * H + j] * h + u[1 * H + j] + b[1 * H + j]);
+            REAL c = tanh_r(a[2 * H + j] * (r * h) + u[2 * H + j] + b[2 * H + j]);
+            out[j] = ((REAL)1 - z) * h + z * c;
+        }
+    } else if (cell == CELL_LSTM_DIAG) {
+        /* LSTM-style cell of the benchmark: separate input and forget gates,
+         * all gates read h_{l-1} through diagonal weights; state (c,h). */
+        const REAL *w = params, *b = params + 4 * H;
+        const REAL *cp = hp, *hh = hp + H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hh[j];
+            REAL i = sigmoid(w[0 * H + j] * h + u[0 * H + j] + b[0 * H + j]);
+            REAL f = sigmoid(w[1 * H + j] * h + u[1 * H + j] + b[1 * H + j]);
+            REAL o = sigmoid(w[2 * H + j] * h + u[2 * H + j] + b[2 * H + j]);
+            REAL g = tanh_r(w[3 * H + j] * h + u[3 * H + j] + b[3 * H + j]);
+            REAL cn = f * cp[j] + i * g;
+            out[j] = cn;
+            out[H + j] = o * tanh_r(cn);
+        }
+    } else if (cell == CELL_TANH_DENSE) {
+        /* generic dense-Jacobian cell: h' = tanh(W h + u) (Sec. 2.1) */
+        int i;
+        for (i = 0; i < H; ++i) {
+            REAL s = u[i];
+            for (j = 0; j < H; ++j) s += params[(size_t)i * H + j] * hp[j];
+            out[i] = tanh_r(s);
+        }
+    } else {
+        /* linear SSM of the footnote in Sec. 2: f = a h + u (+ b) */
+        for (j = 0; j < H; ++j) out[j] = params[j] * hp[j] + u[j] + params[H + j];
+    }
+}
+
+/* Jacobian of f with respect to the previous state, evaluated at (hp, u).
+ * This is the J_l of Eq. (3): the derivative of equation l with respect to
+ * its own input h_{l-1}.  Layout by kind: diag [H]; block2 [2][2][H] with
+ * J[p][q] = d(out_p)/d(in_q), p,q in (c,h); dense [H][H] row-major. */
+void oracle_cell_jacobian(int cell, int H, const REAL *params, const REAL *hp, const REAL *u, REAL *J)
+{
+    int j;
+    if (cell == CELL_GRU_DIAG) {
+        /* Eq. (8a) with diagonal A_*: every factor is a per-channel scalar. */
+        const REAL *a = params, *b = params + 3 * H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hp[j];
+            REAL z = sigmoid(a[0 * H + j] * h + u[0 * H + j] + b[0 * H + j]);
+            REAL r = sigmoid(a[1 * H + j] * h + u[1 * H + j] + b[1 * H + j]);
+            REAL c = tanh_r(a[2 * H + j] * (r * h) + u[2 * H + j] + b[2 * H + j]);
+            REAL dz = z * ((REAL)1 - z), dr = r * ((REAL)1 - r), dc = (REAL)1 - c * c;
+            J[j] = ((REAL)1 - z) + (c - h) * dz * a[0 * H + j]
+                 + z * dc * a[2 * H + j] * (r + h * dr * a[1 * H + j]);
+        }
+    } else if (cell == CELL_LSTM_DIAG) {
+        const REAL *w = params, *b = params + 4 * H;
+        const REAL *cp = hp, *hh = hp + H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hh[j], c = cp[j];
+            REAL i = sigmoid(w[0 * H + j] * h + u[0 * H + j] + b[0 * H + j]);
+            REAL f = sigmoid(w[1 * H + j] * h + u[1 * H + j] + b[1 * H + j]);
+            REAL o = sigmoid(w[2 * H + j] * h + u[2 * H + j] + b[2 * H + j]);
+            REAL g = tanh_r(w[3 * H + j] * h + u[3 * H + j] + b[3 * H + j]);
+            REAL t = tanh_r(f * c + i * g);
+            REAL Jch = c * f * ((REAL)1 - f) * w[1 * H + j] + g * i * ((REAL)1 - i) * w[0 * H + j]
+                     + i * ((REAL)1 - g * g) * w[3 * H + j];
+            J[0 * H + j] = f;                                          /* dc'/dc */
+            J[1 * H + j] = Jch;                                        /* dc'/dh */
+            J[2 * H + j] = o * ((REAL)1 - t * t) * f;                  /* dh'/dc */
+            J[3 * H + j] = t * o * ((REAL)1 - o) * w[2 * H + j] + o * ((REAL)1 - t * t) * Jch; /* dh'/dh */
+        }
+    } else if (cell == CELL_TANH_DENSE) {
+        int i;
+        for (i = 0; i < H; ++i) {
+            REAL s = u[i], d;
+            for (j = 0; j < H; ++j) s += params[(size_t)i * H + j] * hp[j];
+            d = tanh_r(s);
+            d = (REAL)1 - d * d;
+            for (j = 0; j < H; ++j) J[(size_t)i * H + j] = d * params[(size_t)i * H + j];
+        }
+    } else {
+        for (j = 0; j < H; ++j) J[j] = params[j];
+    }
+}
+
+/* y = J x for one Jacobian of the given kind; x, y are [S][H]. */
+static void jac_apply(int kind, int H, const REAL *J, const REAL *x, REAL *y)
+{
+    int i, j;
+    if (kind == JAC_DIAG) {
+        for (j = 0; j < H; ++j) y[j] = J[j] * x[j];
+    } else if (kind == JAC_BLOCK2) {
+        for (j = 0; j < H; ++j) {
+            REAL xc = x[j], xh = x[H + j];
+            y[j] = J[0 * H + j] * xc + J[1 * H + j] * xh;
+            y[H + j] = J[2 * H + j] * xc + J[3 * H + j] * xh;
+        }
+    } else {
+        for (i = 0; i < H; ++i) {
+            REAL s = 0;
+            for (j = 0; j < H; ++j) s += J[(size_t)i * H + j] * x[j];
+            y[i] = s;
+        }
+    }
+}
+
+/* C = A B for two Jacobians of the same kind */
+static void jac_mul(int kind, int H, const REAL *A, const REAL *Bm, REAL *C)
+{
+    int i, j, k;
+    if (kind == JAC_DIAG) {
+        for (j = 0; j < H; ++j) C[j] = A[j] * Bm[j];
+    } else if (kind == JAC_BLOCK2) {
+        for (j = 0; j < H; ++j) {
+            REAL a00 = A[0 * H + j], a01 = A[1 * H + j], a10 = A[2 * H + j], a11 = A[3 * H + j];
+            REAL b00 = Bm[0 * H + j], b01 = Bm[1 * H + j], b10 = Bm[2 * H + j], b11 = Bm[3 * H + j];
+            C[0 * H + j] = a00 * b00 + a01 * b10;
+            C[1 * H + j] = a00 * b01 + a01 * b11;
+            C[2 * H + j] = a10 * b00 + a11 * b10;
+            C[3 * H + j] = a10 * b01 + a11 * b11;
+        }
+    } else {
+        for (i = 0; i < H; ++i)
+            for (j = 0; j < H; ++j) {
+                REAL s = 0;
+                for (k = 0; k < H; ++k) s += A[(size_t)i * H + k] * Bm[(size_t)k * H + j];
+                C[(size_t)i * H + j] = s;
+            }
+    }
+}
+
+/* ------------------------------------------------- sequential application */
+
+/* Eq. (1): h_l = f(h_{l-1}, u_l), l = 1..L, from h0 (NULL = zeros). */
+void oracle_seq_unroll(int cell, int B, int L, int H, const REAL *params, const REAL *u,
+                       const REAL *h0, REAL *h)
+{
+    const int G = oracle_gates(cell), S = oracle_state(cell);
+    int b;
+#pragma omp parallel for schedule(static)
+    for (b = 0; b < B; ++b) {
+        REAL *zero = (REAL *)calloc((size_t)S * H, sizeof(REAL));
+        int l;
+        for (l = 0; l < L; ++l) {
+            const REAL *hp = l == 0 ? (h0 ? h0 + (size_t)b * S * H : zero)
+                                    : h + ((size_t)b * L + (l - 1)) * S * H;
+            oracle_cell_step(cell, H, params, hp, u + ((size_t)b * L + l) * G * H,
+                             h + ((size_t)b * L + l) * S * H);
+        }
+        free(zero);
+    }
+}
+
+/* ----------------------------------------------- linear solvers, one sequence */
+
+/* Eq. (4): delta_l = J_l delta_{l-1} + r_l with delta_0 = 0 (row 1 of Eq. (3)
+ * has no sub-diagonal block).  J [L][jac_size], r and delta [L][S*H]. */
+void oracle_forward_substitution(int kind, int L, int H, const REAL *J, const REAL *r, REAL *delta)
+{
+    const int S = kind == JAC_BLOCK2 ? 2 : 1;
+    const size_t n = (size_t)S * H, js = jac_size(kind, H);
+    int l;
+    size_t j;
+    for (l = 0; l < L; ++l) {
+        if (l == 0) {
+            for (j = 0; j < n; ++j) delta[j] = r[j];
+        } else {
+            jac_apply(kind, H, J + (size_t)l * js, delta + (size_t)(l - 1) * n, delta + (size_t)l * n);
+            for (j = 0; j < n; ++j) delta[(size_t)l * n + j] += r[(size_t)l * n + j];
+        }
+    }
+}
+
+/* Alg. 1b, the naive parallel reduction: A_l = -J_l, delta_l = r_l, then for
+ * i = 0..ceil(log2 L)-1 every equation l >= 2^i (0-based) is reduced with the
+ * one 2^i before it:  delta_l -= A_l delta_{l-2^i};  A_l = -A_l A_{l-2^i}.
+ * The partner index is read as l - 2^i (the printed "+1" would pair an
+ * equation with itself at i = 0).  The first equation has no sub-diagonal
+ * block, so its A is zero.  The "parfor" is honoured by reading only values
+ * of the previous step (two buffers). */
+void oracle_parallel_reduce(int kind, int L, int H, const REAL *J, const REAL *r, REAL *delta)
+{
+    const int S = kind == JAC_BLOCK2 ? 2 : 1;
+    const size_t n = (size_t)S * H, js = jac_size(kind, H);
+    REAL *A = (REAL *)malloc(sizeof(REAL) * js * L), *A2 = (REAL *)malloc(sizeof(REAL) * js * L);
+    REAL *d = (REAL *)malloc(sizeof(REAL) * n * L), *d2 = (REAL *)malloc(sizeof(REAL) * n * L);
+    REAL *tmp = (REAL *)malloc(sizeof(REAL) * (js > n ? js : n));
+    size_t j;
+    int l;
+    long stride;
+    for (j = 0; j < js * (size_t)L; ++j) A[j] = -J[j];
+    for (j = 0; j < js; ++j) A[j] = 0;
+    memcpy(d, r, sizeof(REAL) * n * L);
+    for (stride = 1; stride < L; stride *= 2) {
+        memcpy(A2, A, sizeof(REAL) * js * L);
+        memcpy(d2, d, sizeof(REAL) * n * L);
+        for (l = (int)stride; l < L; ++l) {
+            const REAL *Al = A + (size_t)l * js;
+            jac_apply(kind, H, Al, d + (size_t)(l - stride) * n, tmp);
+            for (j = 0; j < n; ++j) d2[(size_t)l * n + j] = d[(size_t)l * n + j] - tmp[j];
+            jac_mul(kind, H, Al, A + (size_t)(l - stride) * js, tmp);
+            for (j = 0; j < js; ++j) A2[(size_t)l * js + j] = -tmp[j];
+        }
+        { REAL *t = A; A = A2; A2 = t; }
+        { REAL *t = d; d = d2; d2 = t; }
+    }
+    memcpy(delta, d, sizeof(REAL) * n * L);
+    free(A); free(A2); free(d); free(d2); free(tmp);
+}
+
+/* ------------------------------------------------------------------ Newton */
+
+static REAL nanmax(REAL m, REAL a) { return (a > m || a != a) ? a : m; }
+
+/* Alg. 1a with Eq. (4) as the inner solver.
+ *   h^0_l = f(h0, u_l) for all l                        (App. A; reduces to
+ *                                                        f(0, x_l) for h0 = 0)
+ *   for k = 1..max_iter:
+ *       J_l = df/dh (h^{k-1}_{l-1}, u_l),  r_l = f(h^{k-1}_{l-1}, u_l) - h^{k-1}_l
+ *       delta = forward substitution;  h^k = h^{k-1} + delta
+ *       m_k = max |delta| over the whole batch;  stop when m_k <= tol
+ * tol < 0: run exactly max_iter iterations.  trace (or NULL) receives m_k.
+ * iters = number of linear solves performed.  Returns the status. */
+int oracle_newton(int cell, int B, int L, int H, const REAL *params, const REAL *u, const REAL *h0,
+                  REAL tol, int max_iter, REAL *h, int *iters, REAL *trace)
+{
+    const int G = oracle_gates(cell), S = oracle_state(cell), kind = oracle_jac_kind(cell);
+    const size_t n = (size_t)S * H, js = jac_size(kind, H);
+    int b, k, status;
+    if (G < 0 || B < 1 || L < 1 || H < 1 || max_iter < 0) return ST_INVALID;
+
+#pragma omp parallel for schedule(static)
+    for (b = 0; b < B; ++b) {
+        REAL *zero = (REAL *)calloc(n, sizeof(REAL));
+        const REAL *hstart = h0 ? h0 + (size_t)b * n : zero;
+        int l;
+        for (l = 0; l < L; ++l)
+            oracle_cell_step(cell, H, params, hstart, u + ((size_t)b * L + l) * G * H,
+                             h + ((size_t)b * L + l) * n);
+        free(zero);
+    }
+
+    *iters = 0;
+    status = tol < 0 ? ST_OK : ST_NOT_CONVERGED;
+    for (k = 1; k <= max_iter; ++k) {
+        REAL *mb = (REAL *)calloc((size_t)B, sizeof(REAL));
+        REAL m = 0;
+#pragma omp parallel for schedule(static)
+        for (b = 0; b < B; ++b) {
+            REAL *zero = (REAL *)calloc(n, sizeof(REAL));
+            REAL *J = (REAL *)malloc(sizeof(REAL) * js * L);
+            REAL *r = (REAL *)malloc(sizeof(REAL) * n * L);
+            REAL *d = (REAL *)malloc(sizeof(REAL) * n * L);
+            REAL *hb = h + (size_t)b * L * n;
+            REAL mm = 0;
+            int l;
+            size_t j;
+            for (l = 0; l < L; ++l) {
+                const REAL *hp = l == 0 ? (h0 ? h0 + (size_t)b * n : zero) : hb + (size_t)(l - 1) * n;
+                const REAL *ul = u + ((size_t)b * L + l) * G * H;
+                oracle_cell_step(cell, H, params, hp, ul, r + (size_t)l * n);
+                for (j = 0; j < n; ++j) r[(size_t)l * n + j] -= hb[(size_t)l * n + j];
+                oracle_cell_jacobian(cell, H, params, hp, ul, J + (size_t)l * js);
+            }
+            oracle_forward_substitution(kind, L, H, J, r, d);
+            for (j = 0; j < n * (size_t)L; ++j) {
+                hb[j] += d[j];
+                mm = nanmax(mm, (REAL)fabs((double)d[j]));
+            }
+            mb[b] = mm;
+            free(zero); free(J); free(r); free(d);
+        }
+        for (b = 0; b < B; ++b) m = nanmax(m, mb[b]);
+        free(mb);
+        *iters = k;
+        if (trace) trace[k - 1] = m;
+        if (!(m - m == 0)) { status = ST_NONFINITE; break; }   /* inf or nan */
+        if (tol >= 0 && m <= tol) { status = ST_OK; break; }
+    }
+    return status;
+}
+
+/* ----------------------------------------------------------------- backward */
+
+/* Eq. (6): with lam_L = g_L, for l = L..1
+ *     (step-local chain rule through f at (h_{l-1}, u_l) with incoming lam_l)
+ *     du_l = (df/du_l)^T lam_l,  dparams += (df/dparams)^T lam_l,
+ *     lam_{l-1} = J_l^T lam_l + g_{l-1}
+ * h is the forward result; dh0 (or NULL) receives J_1^T lam_1.
+ * The step-local derivatives are reverse-mode differentiation of the cell
+ * written out by hand; the paper obtains them from autograd. */
+void oracle_backward(int cell, int B, int L, int H, const REAL *params, const REAL *u,
+                     const REAL *h0, const REAL *h, const REAL *g, REAL *du, REAL *dparams, REAL *dh0)
+{
+    const int G = oracle_gates(cell), S = oracle_state(cell);
+    const size_t n = (size_t)S * H, np = param_count(cell, H);
+    REAL *dpb = (REAL *)calloc(np * (size_t)B, sizeof(REAL));
+    int b;
+    size_t q;
+#pragma omp parallel for schedule(static)
+    for (b = 0; b < B; ++b) {
+        REAL *zero = (REAL *)calloc(n, sizeof(REAL));
+        REAL *lam = (REAL *)malloc(sizeof(REAL) * n), *lprev = (REAL *)malloc(sizeof(REAL) * n);
+        REAL *dp = dpb + (size_t)b * np;
+        int l, j;
+        memcpy(lam, g + ((size_t)b * L + (L - 1)) * n, sizeof(REAL) * n);
+        for (l = L - 1; l >= 0; --l) {
+            const REAL *hp = l == 0 ? (h0 ? h0 + (size_t)b * n : zero) : h + ((size_t)b * L + (l - 1)) * n;
+            const REAL *ul = u + ((size_t)b * L + l) * G * H;
+            REAL *dul = du + ((size_t)b * L + l) * G * H;
+            if (cell == CELL_GRU_DIAG) {
+                const REAL *a = params, *bb = params + 3 * H;
+                for (j = 0; j < H; ++j) {
+                    REAL hh = hp[j], lm = lam[j];
+                    REAL z = sigmoid(a[0 * H + j] * hh + ul[0 * H + j] + bb[0 * H + j]);
+                    REAL r = sigmoid(a[1 * H + j] * hh + ul[1 * H + j] + bb[1 * H + j]);
+                    REAL c = tanh_r(a[2 * H + j] * (r * hh) + ul[2 * H + j] + bb[2 * H + j]);
+                    /* h' = (1-z) h + z c */
+                    REAL d_z = lm * (c - hh), d_c = lm * z, d_h = lm * ((REAL)1 - z);
+                    REAL d_pc = d_c * ((REAL)1 - c * c);          /* through tanh */
+                    REAL d_rh = d_pc * a[2 * H + j];              /* through a_c (r h) */
+                    REAL d_r = d_rh * hh, d_pr, d_pz;
+                    d_h += d_rh * r;
+                    d_pr = d_r * r * ((REAL)1 - r);               /* through sigmoid */
+                    d_h += d_pr * a[1 * H + j];
+                    d_pz = d_z * z * ((REAL)1 - z);
+                    d_h += d_pz * a[0 * H + j];
+                    dul[0 * H + j] = d_pz; dul[1 * H + j] = d_pr; dul[2 * H + j] = d_pc;
+                    dp[0 * H + j] += d_pz * hh; dp[1 * H + j] += d_pr * hh; dp[2 * H + j] += d_pc * (r * hh);
+                    dp[3 * H + j] += d_pz; dp[4 * H + j] += d_pr; dp[5 * H + j] += d_pc;
+                    lprev[j] = d_h;
+                }
+            } else if (cell == CELL_LSTM_DIAG) {
+                const REAL *w = params, *bb = params + 4 * H;
+                for (j = 0; j < H; ++j) {
+                    REAL c = hp[j], hh = hp[H + j], lc = lam[j], lh = lam[H + j];
+                    REAL i = sigmoid(w[0 * H + j] * hh + ul[0 * H + j] + bb[0 * H + j]);
+                    REAL f = sigmoid(w[1 * H + j] * hh + ul[1 * H + j] + bb[1 * H + j]);
+                    REAL o = sigmoid(w[2 * H + j] * hh + ul[2 * H + j] + bb[2 * H + j]);
+                    REAL gg = tanh_r(w[3 * H + j] * hh + ul[3 * H + j] + bb[3 * H + j]);
+                    REAL t = tanh_r(f * c + i * gg);
+                    /* h' = o t,  c' = f c + i g */
+                    REAL d_o = lh * t, d_cn = lc + lh * o * ((REAL)1 - t * t);
+                    REAL d_f = d_cn * c, d_i = d_cn * gg, d_g = d_cn * i;
+                    REAL d_pi = d_i * i * ((REAL)1 - i), d_pf = d_f * f * ((REAL)1 - f);
+                    REAL d_po = d_o * o * ((REAL)1 - o), d_pg = d_g * ((REAL)1 - gg * gg);
+                    dul[0 * H + j] = d_pi; dul[1 * H + j] = d_pf; dul[2 * H + j] = d_po; dul[3 * H + j] = d_pg;
+                    dp[0 * H + j] += d_pi * hh; dp[1 * H + j] += d_pf * hh;
+                    dp[2 * H + j] += d_po * hh; dp[3 * H + j] += d_pg * hh;
+                    dp[4 * H + j] += d_pi; dp[5 * H + j] += d_pf; dp[6 * H + j] += d_po; dp[7 * H + j] += d_pg;
+                    lprev[j] = d_cn * f;
+                    lprev[H + j] = d_pi * w[0 * H + j] + d_pf * w[1 * H + j] + d_po * w[2 * H + j]
+                                 + d_pg * w[3 * H + j];
+                }
+            } else if (cell == CELL_TANH_DENSE) {
+                const REAL *hl = h + ((size_t)b * L + l) * n;
+                int i;
+                for (j = 0; j < H; ++j) lprev[j] = 0;
+                for (i = 0; i < H; ++i) {
+                    REAL d_pre = lam[i] * ((REAL)1 - hl[i] * hl[i]);   /* h_l = tanh(pre) */
+                    dul[i] = d_pre;
+                    for (j = 0; j < H; ++j) {
+                        dp[(size_t)i * H + j] += d_pre * hp[j];
+                        lprev[j] += params[(size_t)i * H + j] * d_pre;
+                    }
+                }
+            } else {
+                for (j = 0; j < H; ++j) {
+                    dul[j] = lam[j];
+                    dp[j] += lam[j] * hp[j];
+                    dp[H + j] += lam[j];
+                    lprev[j] = params[j] * lam[j];
+                }
+            }
+            if (l > 0) {
+                const REAL *gp = g + ((size_t)b * L + (l - 1)) * n;
+                for (j = 0; j < (int)n; ++j) lam[j] = lprev[j] + gp[j];
+            } else if (dh0) {
+                memcpy(dh0 + (size_t)b * n, lprev, sizeof(REAL) * n);
+            }
+        }
+        free(zero); free(lam); free(lprev);
+    }
+    for (q = 0; q < np; ++q) {
+        REAL s = 0;
+        for (b = 0; b < B; ++b) s += dpb[(size_t)b * np + q];
+        dparams[q] = s;
+    }
+    free(dpb);
+}
