@@ -1,0 +1,151 @@
+"""ctypes binding: one Python function per entry point of include/pararnn.h,
+same names without the prefix.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libpararnn.so")
+
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3}
+DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR",
+          5: "NONFINITE", 6: "UNSUPPORTED", 7: "INTERNAL"}
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_21450_amd.build` "
+                      "(there is no CPU fallback)")
+
+_lib = ctypes.CDLL(_LIB_PATH)
+_vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+_lib.pararnn_status_string.restype = ctypes.c_char_p
+_lib.pararnn_status_string.argtypes = [_i]
+_lib.pararnn_version.restype = _i
+_lib.pararnn_cell_gates.argtypes = [_i]
+_lib.pararnn_cell_state.argtypes = [_i]
+_lib.pararnn_workspace_bytes.restype = _sz
+_lib.pararnn_workspace_bytes.argtypes = [_i] * 6
+_lib.pararnn_forward.restype = _i
+_lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.pararnn_backward.restype = _i
+_lib.pararnn_backward.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.pararnn_affine_scan.restype = _i
+_lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def version() -> int:
+    return _lib.pararnn_version()
+
+
+def status_string(code: int) -> str:
+    return _lib.pararnn_status_string(code).decode()
+
+
+def cell_dims(cell: str):
+    """(gates G, state values S) of a cell."""
+    c = CELLS[cell]
+    return _lib.pararnn_cell_gates(c), _lib.pararnn_cell_state(c)
+
+
+def workspace_bytes(cell: str, dtype, B: int, L: int, H: int, backward: bool = False) -> int:
+    return _lib.pararnn_workspace_bytes(CELLS[cell], DTYPES[dtype], B, L, H, int(backward))
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _check(t, name, dtype, shape=None):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _workspace(nbytes, device, workspace):
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def _raise(code, what):
+    if code != 0:
+        raise RuntimeError(f"{what} failed: {status_string(code)} ({code})")
+
+
+def forward(cell: str, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, trace: bool = False,
+            workspace=None, stream=None, out=None):
+    """pararnn_forward.  u [B][L][G][H] (fp32 or bf16), params fp32.
+    Returns (h, iters, delta_trace): iters is a DEVICE int32[2] tensor
+    {iterations, status} (no synchronisation happens here), delta_trace a
+    device float[max_iter] tensor or None."""
+    G, S = cell_dims(cell)
+    B, L, Gu, H = u.shape
+    dt = u.dtype
+    _check(u, "u", dt, (B, L, G, H))
+    _check(params, "params", torch.float32)
+    if h0 is not None:
+        _check(h0, "h0", dt, (B, S, H))
+    h = torch.empty((B, L, S, H), dtype=dt, device=u.device) if out is None else out
+    _check(h, "h", dt, (B, L, S, H))
+    iters = torch.empty(2, dtype=torch.int32, device=u.device)
+    tr = torch.zeros(max(max_iter, 1), dtype=torch.float32, device=u.device) if trace else None
+    ws = _workspace(workspace_bytes(cell, dt, B, L, H, False), u.device, workspace)
+    code = _lib.pararnn_forward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol, max_iter,
+                                _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, "pararnn_forward")
+    return h, iters, tr
+
+
+def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None):
+    """pararnn_backward.  Returns (dL_du, dL_dparams, dL_dh0 or None)."""
+    G, S = cell_dims(cell)
+    B, L, Gu, H = u.shape
+    dt = u.dtype
+    _check(u, "u", dt, (B, L, G, H))
+    _check(params, "params", torch.float32)
+    _check(h, "h", dt, (B, L, S, H))
+    _check(dL_dh, "dL_dh", dt, (B, L, S, H))
+    if h0 is not None:
+        _check(h0, "h0", dt, (B, S, H))
+    du = torch.empty_like(u)
+    dparams = torch.empty_like(params)
+    dh0 = torch.empty((B, S, H), dtype=dt, device=u.device) if want_dh0 else None
+    ws = _workspace(workspace_bytes(cell, dt, B, L, H, True), u.device, workspace)
+    code = _lib.pararnn_backward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), _ptr(h), _ptr(dL_dh),
+                                 B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, "pararnn_backward")
+    return du, dparams, dh0
+
+
+def affine_scan(J, r, reverse: bool = False, workspace=None, stream=None):
+    """pararnn_affine_scan.  J [B][L][H] (diagonal) or [B][L][2][2][H]; r
+    [B][L][S][H] or [B][L][H].  Returns delta with r's shape."""
+    kind = 0 if J.dim() == 3 else 1
+    B, L = r.shape[0], r.shape[1]
+    H = r.shape[-1]
+    _check(J, "J", torch.float32, (B, L, H) if kind == 0 else (B, L, 2, 2, H))
+    _check(r, "r", torch.float32)
+    delta = torch.empty_like(r)
+    cell = "gru_diag" if kind == 0 else "lstm_diag"
+    ws = _workspace(workspace_bytes(cell, torch.float32, B, L, H, False), r.device, workspace)
+    code = _lib.pararnn_affine_scan(kind, int(reverse), _ptr(J), _ptr(r), B, L, H, _ptr(delta), _ptr(ws),
+                                    ws.numel(), _stream(stream))
+    _raise(code, "pararnn_affine_scan")
+    return delta

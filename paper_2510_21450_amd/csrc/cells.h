@@ -1,0 +1,180 @@
+// Per-channel cell arithmetic for the diagonal and 2x2-block paths.
+//
+// Every function works on ONE channel: p[] holds that channel's PR parameter
+// rows ([2][G]: recurrent weights then biases), hp[] the previous state (S
+// values), u[] the G pre-activations.  J is row-major S x S with
+// J[p*S+q] = d(out_p)/d(in_q).
+//
+// Backward (Sec. 2, Eq. (6)): bwd_prep returns J and NC coefficients from which
+// bwd_emit maps the incoming adjoint lam (dL/d state_l) to dL/du_l and adds this
+// step's contribution to the PR parameter-gradient accumulators.
+#pragma once
+#include "common.h"
+
+namespace pararnn {
+
+// Sec. 3, Eq. (7a) with the diagonal weights of Eq. (9); Jacobian Eq. (8a).
+struct GruDiag {
+    static constexpr int G = 3, S = 1, PR = 6, NC = 5;
+
+    __device__ __forceinline__ static void gates(const float *p, float h, const float *u, float &z,
+                                                 float &r, float &rh, float &c)
+    {
+        z = fast_sigmoid(fmaf(p[0], h, u[0] + p[3]));
+        r = fast_sigmoid(fmaf(p[1], h, u[1] + p[4]));
+        rh = r * h;
+        c = fast_tanh(fmaf(p[2], rh, u[2] + p[5]));
+    }
+
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    {
+        float z, r, rh, c;
+        gates(p, hp[0], u, z, r, rh, c);
+        F[0] = fmaf(z, c - hp[0], hp[0]);
+    }
+
+    // k_z = (c-h) z(1-z), k_c = z (1-c^2), k_r = k_c a_c h r(1-r) are df/du_z,
+    // df/du_c, df/du_r;  J = (1-z) + a_z k_z + a_c r k_c + a_r k_r  (Eq. (8a)).
+    __device__ __forceinline__ static void coefs(const float *p, float h, const float *u, float &F,
+                                                 float &J, float &kz, float &kr, float &kc, float &rh)
+    {
+        float z, r, c;
+        gates(p, h, u, z, r, rh, c);
+        const float cmh = c - h, omz = 1.0f - z;
+        F = fmaf(z, cmh, h);
+        kz = cmh * (z * omz);
+        kc = z * fmaf(-c, c, 1.0f);
+        const float ackc = p[2] * kc;
+        kr = ackc * (rh * (1.0f - r));
+        J = fmaf(p[0], kz, omz);
+        J = fmaf(ackc, r, J);
+        J = fmaf(p[1], kr, J);
+    }
+
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    {
+        float kz, kr, kc, rh;
+        coefs(p, hp[0], u, F[0], J[0], kz, kr, kc, rh);
+    }
+
+    __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
+                                                    float *J, float *k)
+    {
+        float F;
+        coefs(p, hp[0], u, F, J[0], k[0], k[1], k[2], k[4]);
+        k[3] = hp[0];
+    }
+
+    __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
+    {
+        du[0] = lam[0] * k[0];
+        du[1] = lam[0] * k[1];
+        du[2] = lam[0] * k[2];
+        acc[0] = fmaf(du[0], k[3], acc[0]);
+        acc[1] = fmaf(du[1], k[3], acc[1]);
+        acc[2] = fmaf(du[2], k[4], acc[2]);
+        acc[3] += du[0];
+        acc[4] += du[1];
+        acc[5] += du[2];
+    }
+};
+
+// LSTM-style cell with separate input/forget gates that all read h_{l-1}
+// through diagonal weights; state (c, h); 2x2 Jacobian block per channel (the
+// block structure of Eq. (8b)).
+struct LstmDiag {
+    static constexpr int G = 4, S = 2, PR = 8, NC = 6;
+
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    {
+        const float h = hp[1];
+        const float i = fast_sigmoid(fmaf(p[0], h, u[0] + p[4]));
+        const float f = fast_sigmoid(fmaf(p[1], h, u[1] + p[5]));
+        const float o = fast_sigmoid(fmaf(p[2], h, u[2] + p[6]));
+        const float g = fast_tanh(fmaf(p[3], h, u[3] + p[7]));
+        F[0] = fmaf(f, hp[0], i * g);
+        F[1] = o * fast_tanh(F[0]);
+    }
+
+    // k[0..3] = d c'/d u_{i,f,g-slot order i,f,o,g} with k[2] = d h'/d u_o,
+    // k[4] = o (1 - tanh(c')^2) = d h'/d c', k[5] = h.
+    __device__ __forceinline__ static void coefs(const float *p, const float *hp, const float *u, float *F,
+                                                 float *J, float *k)
+    {
+        const float c = hp[0], h = hp[1];
+        const float i = fast_sigmoid(fmaf(p[0], h, u[0] + p[4]));
+        const float f = fast_sigmoid(fmaf(p[1], h, u[1] + p[5]));
+        const float o = fast_sigmoid(fmaf(p[2], h, u[2] + p[6]));
+        const float g = fast_tanh(fmaf(p[3], h, u[3] + p[7]));
+        const float cn = fmaf(f, c, i * g);
+        const float t = fast_tanh(cn);
+        F[0] = cn;
+        F[1] = o * t;
+        k[0] = g * (i * (1.0f - i));
+        k[1] = c * (f * (1.0f - f));
+        k[2] = t * (o * (1.0f - o));
+        k[3] = i * fmaf(-g, g, 1.0f);
+        k[4] = o * fmaf(-t, t, 1.0f);
+        k[5] = h;
+        const float jch = fmaf(k[0], p[0], fmaf(k[1], p[1], k[3] * p[3]));
+        J[0] = f;
+        J[1] = jch;
+        J[2] = k[4] * f;
+        J[3] = fmaf(k[2], p[2], k[4] * jch);
+    }
+
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    {
+        float k[NC];
+        coefs(p, hp, u, F, J, k);
+    }
+
+    __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
+                                                    float *J, float *k)
+    {
+        float F[2];
+        coefs(p, hp, u, F, J, k);
+    }
+
+    __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
+    {
+        const float dcn = fmaf(lam[1], k[4], lam[0]);
+        du[0] = dcn * k[0];
+        du[1] = dcn * k[1];
+        du[2] = lam[1] * k[2];
+        du[3] = dcn * k[3];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            acc[g] = fmaf(du[g], k[5], acc[g]);
+            acc[4 + g] += du[g];
+        }
+    }
+};
+
+// Linear SSM of the footnote in Sec. 2: f = a h + u + b, J = a.
+struct LinearDiag {
+    static constexpr int G = 1, S = 1, PR = 2, NC = 1;
+
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    {
+        F[0] = fmaf(p[0], hp[0], u[0] + p[1]);
+    }
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    {
+        step(p, hp, u, F);
+        J[0] = p[0];
+    }
+    __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *, float *J, float *k)
+    {
+        J[0] = p[0];
+        k[0] = hp[0];
+    }
+    __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
+    {
+        du[0] = lam[0];
+        acc[0] = fmaf(lam[0], k[0], acc[0]);
+        acc[1] += lam[0];
+    }
+};
+
+}  // namespace pararnn

@@ -1,0 +1,123 @@
+// Shared device helpers of the ParaRNN HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pararnn {
+
+constexpr int kWave = 64;
+
+// Device-side control block at the start of the workspace.
+struct Ctrl {
+    unsigned int ticket;     // next tile of the running launch
+    unsigned int done;       // workgroups that finished the running launch
+    unsigned int gmax_bits;  // max |delta| of the running iteration (fp32 bits, >= 0)
+    int stop;                // set once the solve has ended; later launches return at once
+    int iters;
+    int status;
+    unsigned int pad[2];
+};
+
+// status values mirrored from pararnn.h (device code does not include it)
+constexpr int kStOk = 0, kStNotConverged = 1, kStNonFinite = 5, kStInternal = 7;
+
+// Tile flag protocol of the cross-workgroup carry: flag = epoch * 4 + state.
+constexpr unsigned int kFlagAgg = 1;   // tile aggregate (A, b) published
+constexpr unsigned int kFlagIncl = 2;  // inclusive value (delta at the tile's end) published
+// polls of one predecessor before a tile gives up (reports kStInternal, uses a
+// zero carry) so that every wave terminates whatever happens
+constexpr unsigned int kSpinLimit = 1u << 24;
+
+// ---------------------------------------------------------------- bf16 <-> fp32
+__device__ __forceinline__ float bf16_to_f32(unsigned short v)
+{
+    return __uint_as_float(((unsigned int)v) << 16);
+}
+
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ unsigned short f32_to_bf16(float f)
+{
+    unsigned int x = __float_as_uint(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((x >> 16) | 0x40u);
+    x += 0x7fffu + ((x >> 16) & 1u);
+    return (unsigned short)(x >> 16);
+}
+
+// ------------------------------------------------------ vectors of VEC channels
+template <int VEC> struct VecF;  // VEC fp32 values, loaded/stored as one access
+template <> struct VecF<1> { using type = float; };
+template <> struct VecF<2> { using type = float2; };
+template <> struct VecF<4> { using type = float4; };
+template <int VEC> struct VecH;  // VEC bf16 values
+template <> struct VecH<1> { using type = unsigned short; };
+template <> struct VecH<2> { using type = unsigned int; };
+template <> struct VecH<4> { using type = uint2; };
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(const float *p, float (&out)[VEC])
+{
+    typename VecF<VEC>::type v = *reinterpret_cast<const typename VecF<VEC>::type *>(p);
+    const float *f = reinterpret_cast<const float *>(&v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) out[i] = f[i];
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(const unsigned short *p, float (&out)[VEC])
+{
+    typename VecH<VEC>::type v = *reinterpret_cast<const typename VecH<VEC>::type *>(p);
+    const unsigned short *s = reinterpret_cast<const unsigned short *>(&v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) out[i] = bf16_to_f32(s[i]);
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *p, const float (&in)[VEC])
+{
+    typename VecF<VEC>::type v;
+    float *f = reinterpret_cast<float *>(&v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) f[i] = in[i];
+    *reinterpret_cast<typename VecF<VEC>::type *>(p) = v;
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(unsigned short *p, const float (&in)[VEC])
+{
+    typename VecH<VEC>::type v;
+    unsigned short *s = reinterpret_cast<unsigned short *>(&v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s[i] = f32_to_bf16(in[i]);
+    *reinterpret_cast<typename VecH<VEC>::type *>(p) = v;
+}
+
+// ------------------------------------------------------------------- fast math
+// v_exp_f32 / v_rcp_f32 (1 ulp each).  Saturation is exact: exp2 -> 0 or inf,
+// rcp(inf) = 0.
+__device__ __forceinline__ float fast_sigmoid(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+
+__device__ __forceinline__ float fast_tanh(float x)
+{
+    // 1 - 2 / (1 + e^{2x}); absolute error ~1e-7 everywhere
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
+}
+
+// max that keeps a NaN once seen (fmaxf would drop it)
+__device__ __forceinline__ float nanmax(float m, float a) { return (a > m || a != a) ? a : m; }
+
+// --------------------------------------------------- agent-scope flag accesses
+__device__ __forceinline__ unsigned int flag_load(const unsigned int *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void flag_store(unsigned int *p, unsigned int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+
+}  // namespace pararnn

@@ -1,0 +1,31 @@
+// Host-side launch interface between the C ABI and the per-cell kernel
+// instantiations (each cell / storage type is compiled in its own file).
+#pragma once
+#include "scan_kernels.h"
+
+namespace pararnn {
+
+struct TileCfg {
+    int vec;  // channels per lane
+    int c;    // timesteps per thread
+    int w;    // waves per workgroup
+};
+
+// tile shapes compiled for every cell (C, W); T = C * W timesteps per tile
+#define PARARNN_TILE_SHAPES(X) X(4, 8) X(8, 8)
+// channels per lane compiled for every cell
+#define PARARNN_VECS(X) X(1) X(2) X(4)
+
+template <class Cell, typename UT> struct Kernels {
+    static hipError_t init_guess(int vec, const FwdArgs &a, hipStream_t st);
+    static hipError_t newton_iter(const TileCfg &cfg, const FwdArgs &a, hipStream_t st);
+    static hipError_t backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st);
+};
+
+hipError_t launch_reset(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0,
+                        hipStream_t st);
+hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t st);
+hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st);
+int device_cu_count();
+
+}  // namespace pararnn

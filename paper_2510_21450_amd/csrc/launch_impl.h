@@ -1,0 +1,94 @@
+// Definitions of Kernels<Cell, UT>; included only by the inst_*.hip files.
+#pragma once
+#include "launch.h"
+
+namespace pararnn {
+
+// workgroups of a persistent launch: what fits on the device at once
+template <typename K> static int persistent_grid(K kernel, int threads, int n_tiles)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1)
+        per_cu = 1;
+    const long long cap = (long long)per_cu * device_cu_count();
+    return (int)(n_tiles < cap ? n_tiles : cap);
+}
+
+// static LDS of the backward kernel must stay within 64 KiB
+template <class Cell, int VEC, int W> constexpr bool backward_fits_lds()
+{
+    constexpr int S = Cell::S, SS = S * S, PRX = Cell::PR > 0 ? Cell::PR : 1;
+    constexpr int rows = (SS + S) > PRX ? (SS + S) : PRX;
+    return (size_t)(W * rows + S) * kWave * VEC * sizeof(float) + 16 <= 65536;
+}
+
+template <class Cell, typename UT>
+hipError_t Kernels<Cell, UT>::init_guess(int vec, const FwdArgs &a, hipStream_t st)
+{
+    if constexpr (IsRaw<Cell>::value) {
+        return hipErrorInvalidValue;
+    } else {
+        const size_t n = (size_t)a.g.B * a.g.L * (a.g.H / vec);
+        size_t blocks = (n + 255) / 256;
+        const size_t cap = (size_t)device_cu_count() * 32;
+        if (blocks > cap) blocks = cap;
+#define PARARNN_CASE(V)                                                                       \
+    if (vec == V) {                                                                           \
+        hipLaunchKernelGGL((init_guess_kernel<Cell, V, UT>), dim3((unsigned)blocks), dim3(256), 0, st, a); \
+        return hipGetLastError();                                                             \
+    }
+        PARARNN_VECS(PARARNN_CASE)
+#undef PARARNN_CASE
+        return hipErrorInvalidValue;
+    }
+}
+
+template <class Cell, typename UT>
+hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, hipStream_t st)
+{
+#define PARARNN_CASE2(V, C, W)                                                                 \
+    if (cfg.vec == V && cfg.c == C && cfg.w == W) {                                            \
+        static int grid_cap = 0; /* per instantiation */                                       \
+        auto kern = newton_iter_kernel<Cell, V, C, W, UT>;                                     \
+        if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);               \
+        const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                      \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
+        return hipGetLastError();                                                              \
+    }
+#define PARARNN_CASE_V1(C, W) PARARNN_CASE2(1, C, W)
+#define PARARNN_CASE_V2(C, W) PARARNN_CASE2(2, C, W)
+#define PARARNN_CASE_V4(C, W) PARARNN_CASE2(4, C, W)
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V1)
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V2)
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V4)
+#undef PARARNN_CASE2
+    return hipErrorInvalidValue;
+}
+
+template <class Cell, typename UT>
+hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st)
+{
+#define PARARNN_CASE2(V, C, W)                                                                 \
+    if (cfg.vec == V && cfg.c == C && cfg.w == W) {                                            \
+        if constexpr (backward_fits_lds<Cell, V, W>()) {                                       \
+            static int grid_cap = 0;                                                           \
+            auto kern = backward_kernel<Cell, V, C, W, UT>;                                    \
+            if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \
+            const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                  \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
+            return hipGetLastError();                                                          \
+        } else {                                                                               \
+            return hipErrorInvalidValue;                                                       \
+        }                                                                                      \
+    }
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V1)
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V2)
+    PARARNN_TILE_SHAPES(PARARNN_CASE_V4)
+#undef PARARNN_CASE2
+#undef PARARNN_CASE_V1
+#undef PARARNN_CASE_V2
+#undef PARARNN_CASE_V4
+    return hipErrorInvalidValue;
+}
+
+}  // namespace pararnn

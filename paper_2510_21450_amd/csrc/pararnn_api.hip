@@ -1,0 +1,315 @@
+// C ABI of the library (see include/pararnn.h): argument checks, workspace
+// layout, tile-shape choice and the enqueue sequence.  No kernel code here.
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <initializer_list>
+
+#include "../../include/pararnn.h"
+#include "dense.h"
+#include "launch.h"
+
+using namespace pararnn;
+
+namespace {
+
+struct CellInfo { int G, S, PR; };
+
+bool cell_info(int cell, CellInfo *ci)
+{
+    switch (cell) {
+    case PARARNN_GRU_DIAG: *ci = {3, 1, 6}; return true;
+    case PARARNN_LSTM_DIAG: *ci = {4, 2, 8}; return true;
+    case PARARNN_TANH_DENSE: *ci = {1, 1, 0}; return true;
+    case PARARNN_LINEAR_DIAG: *ci = {1, 1, 2}; return true;
+    }
+    return false;
+}
+
+size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Tile shape for a problem: channels per lane as wide as divisibility and
+// pointer alignment allow, capped per kernel by its register footprint.
+// PARARNN_TILE="vec,c,w" overrides it (tuning aid; the combination must be one
+// that is compiled in).
+TileCfg choose_tile(int cell_kind, bool backward, int H, int align_elems)
+{
+    int vmax = 1;
+    if (H % 4 == 0 && align_elems >= 4) vmax = 4;
+    else if (H % 2 == 0 && align_elems >= 2) vmax = 2;
+    int want = 4;
+    if (cell_kind == PARARNN_LSTM_DIAG || backward) want = 2;
+    TileCfg cfg;
+    cfg.vec = want < vmax ? want : vmax;
+    cfg.c = 4;
+    cfg.w = 8;
+    static int ov[3] = {-1, 0, 0};
+    if (ov[0] == -1) {
+        ov[0] = 0;
+        const char *e = getenv("PARARNN_TILE");
+        int v, c, w;
+        if (e && sscanf(e, "%d,%d,%d", &v, &c, &w) == 3) { ov[0] = v; ov[1] = c; ov[2] = w; }
+    }
+    if (ov[0] > 0 && ov[0] <= vmax) { cfg.vec = ov[0]; cfg.c = ov[1]; cfg.w = ov[2]; }
+    return cfg;
+}
+
+struct Layout {
+    ScanGeom g;
+    TileCfg cfg;
+    size_t off_flags, off_rec, off_bnd, off_iter, off_part, total;
+};
+
+// Workspace: [Ctrl | flags | tile records | boundary rows | fp32 iterate (bf16 forward) |
+// parameter-gradient partials (backward)]
+Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems)
+{
+    Layout lo;
+    lo.cfg = choose_tile(cell_kind, backward, H, align_elems);
+    const int CW = kWave * lo.cfg.vec, T = lo.cfg.c * lo.cfg.w;
+    ScanGeom &g = lo.g;
+    g.B = B; g.L = L; g.H = H; g.T = T;
+    g.n_lt = (L + T - 1) / T;
+    g.n_cg = (H + CW - 1) / CW;
+    g.n_groups = B * g.n_cg;
+    g.n_tiles = g.n_groups * g.n_lt;
+    const size_t REC = (size_t)ci.S * ci.S + 2 * ci.S;
+    size_t off = round256(sizeof(Ctrl));
+    lo.off_flags = off; off += round256((size_t)g.n_tiles * sizeof(unsigned int));
+    lo.off_rec = off;   off += round256((size_t)g.n_tiles * REC * CW * sizeof(float));
+    lo.off_bnd = off;
+    if (!backward) off += round256((size_t)2 * g.n_lt * B * ci.S * H * sizeof(float));
+    lo.off_iter = off;
+    if (!backward && dtype == PARARNN_BF16) off += round256((size_t)B * L * ci.S * H * sizeof(float));
+    lo.off_part = off;
+    if (backward) off += round256((size_t)g.n_lt * B * ci.PR * H * sizeof(float));
+    lo.total = off;
+    return lo;
+}
+
+bool dims_ok(int B, int L, int H)
+{
+    if (B < 1 || L < 1 || H < 1) return false;
+    // keep every element count inside size_t/int ranges the kernels assume
+    const double n = (double)B * (double)L * (double)H;
+    return n < 3.0e10 && (double)B * H < 2.0e9 && L < (1 << 30);
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// widest vector (in elements of size esz: 4, 2 or 1) every pointer in the list allows; NULL allows any
+int align_elems(size_t esz, std::initializer_list<const void *> ptrs)
+{
+    int a = 4;
+    for (const void *p : ptrs) {
+        if (!p) continue;
+        const int here = aligned(p, 4 * esz) ? 4 : aligned(p, 2 * esz) ? 2 : 1;
+        if (here < a) a = here;
+    }
+    return a;
+}
+
+template <class Cell>
+int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hipStream_t st, void *h,
+                 int status0, int max_iter)
+{
+    char *ws = reinterpret_cast<char *>(a.ctrl);
+    hipError_t e = launch_reset(a.ctrl, a.flags, (size_t)lo.g.n_tiles, a.iters_out, status0, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    const bool bf = dtype == PARARNN_BF16;
+    a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
+    e = bf ? Kernels<Cell, unsigned short>::init_guess(lo.cfg.vec, a, st) : Kernels<Cell, float>::init_guess(lo.cfg.vec, a, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    for (int k = 1; k <= max_iter; ++k) {
+        a.k = k;
+        e = bf ? Kernels<Cell, unsigned short>::newton_iter(lo.cfg, a, st) : Kernels<Cell, float>::newton_iter(lo.cfg, a, st);
+        if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+    }
+    if (bf) {
+        e = launch_store_bf16(a.hit, h, (size_t)lo.g.B * lo.g.L * ci.S * lo.g.H, st);
+        if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    }
+    return PARARNN_OK;
+}
+
+template <class Cell>
+int backward_diag(const CellInfo &ci, int dtype, const Layout &lo, BwdArgs &a, hipStream_t st, float *dparams)
+{
+    hipError_t e = launch_reset(a.ctrl, a.flags, (size_t)lo.g.n_tiles, nullptr, 0, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    e = dtype == PARARNN_BF16 ? Kernels<Cell, unsigned short>::backward(lo.cfg, a, st)
+                              : Kernels<Cell, float>::backward(lo.cfg, a, st);
+    if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+    e = launch_param_reduce(a.part, dparams, lo.g.n_lt * lo.g.B, ci.PR * lo.g.H, st);
+    return e == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pararnn_status_string(int status)
+{
+    switch (status) {
+    case PARARNN_OK: return "OK";
+    case PARARNN_NOT_CONVERGED: return "NOT_CONVERGED";
+    case PARARNN_INVALID_ARG: return "INVALID_ARG";
+    case PARARNN_WORKSPACE_TOO_SMALL: return "WORKSPACE_TOO_SMALL";
+    case PARARNN_HIP_ERROR: return "HIP_ERROR";
+    case PARARNN_NONFINITE: return "NONFINITE";
+    case PARARNN_UNSUPPORTED: return "UNSUPPORTED";
+    case PARARNN_INTERNAL: return "INTERNAL";
+    }
+    return "UNKNOWN";
+}
+
+int pararnn_version(void) { return 100; }
+
+int pararnn_cell_gates(int cell)
+{
+    CellInfo ci;
+    return cell_info(cell, &ci) ? ci.G : -1;
+}
+
+int pararnn_cell_state(int cell)
+{
+    CellInfo ci;
+    return cell_info(cell, &ci) ? ci.S : -1;
+}
+
+size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int backward)
+{
+    CellInfo ci;
+    if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
+    if (cell == PARARNN_TANH_DENSE) return dense_workspace_bytes(dtype, B, L, H, backward);
+    // the size must not depend on pointer alignment: take the larger (vec = 1) footprint when they differ
+    size_t need = 0;
+    for (int al = 1; al <= 4; al *= 2) {
+        const Layout lo = make_layout(cell, ci, dtype, B, L, H, backward != 0, al);
+        if (lo.total > need) need = lo.total;
+    }
+    return need;
+}
+
+int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
+                    int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
+                    size_t workspace_bytes, void *hip_stream)
+{
+    CellInfo ci;
+    if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16)) return PARARNN_INVALID_ARG;
+    if (!dims_ok(B, L, H) || max_iter < 0 || !params || !u || !h || !iters || !workspace) return PARARNN_INVALID_ARG;
+    if (tol != tol) return PARARNN_INVALID_ARG;
+    if (!aligned(workspace, 256) || !aligned(params, 4) || !aligned(iters, 4)) return PARARNN_INVALID_ARG;
+    const size_t esz = dtype == PARARNN_BF16 ? 2 : 4;
+    if (!aligned(u, esz) || !aligned(h, esz) || (h0 && !aligned(h0, esz))) return PARARNN_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int status0 = tol < 0.0f ? PARARNN_OK : PARARNN_NOT_CONVERGED;
+
+    if (cell == PARARNN_TANH_DENSE)
+        return dense_forward(dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace,
+                             workspace_bytes, st);
+
+    int al = align_elems(esz, {u, h, h0});
+    const int alp = align_elems(4, {params});
+    if (alp < al) al = alp;
+    const Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al);
+    if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    FwdArgs a;
+    memset(&a, 0, sizeof(a));
+    a.g = lo.g;
+    a.params = params; a.u = u; a.h0 = h0; a.jac = nullptr;
+    a.bnd = reinterpret_cast<float *>(ws + lo.off_bnd);
+    a.rec = reinterpret_cast<float *>(ws + lo.off_rec);
+    a.flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    a.ctrl = reinterpret_cast<Ctrl *>(ws);
+    a.iters_out = iters; a.trace = delta_trace;
+    a.k = 0; a.max_iter = max_iter; a.tol = tol;
+    switch (cell) {
+    case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
+    case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
+    case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
+    }
+    return PARARNN_INVALID_ARG;
+}
+
+int pararnn_backward(int cell, int dtype, const float *params, const void *u, const void *h0, const void *h,
+                     const void *dL_dh, int B, int L, int H, void *dL_du, float *dL_dparams, void *dL_dh0,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    CellInfo ci;
+    if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16)) return PARARNN_INVALID_ARG;
+    if (!dims_ok(B, L, H) || !params || !u || !h || !dL_dh || !dL_du || !dL_dparams || !workspace)
+        return PARARNN_INVALID_ARG;
+    const size_t esz = dtype == PARARNN_BF16 ? 2 : 4;
+    if (!aligned(workspace, 256) || !aligned(params, 4) || !aligned(dL_dparams, 4) || !aligned(u, esz) ||
+        !aligned(h, esz) || !aligned(dL_dh, esz) || !aligned(dL_du, esz) || (h0 && !aligned(h0, esz)) ||
+        (dL_dh0 && !aligned(dL_dh0, esz)))
+        return PARARNN_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (cell == PARARNN_TANH_DENSE) return PARARNN_UNSUPPORTED;
+
+    int al = align_elems(esz, {u, h, h0, dL_dh, dL_du, dL_dh0});
+    const int alp = align_elems(4, {params, dL_dparams});
+    if (alp < al) al = alp;
+    const Layout lo = make_layout(cell, ci, dtype, B, L, H, true, al);
+    if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    BwdArgs a;
+    memset(&a, 0, sizeof(a));
+    a.g = lo.g;
+    a.params = params; a.u = u; a.h0 = h0; a.h = h; a.gl = dL_dh; a.jac = nullptr;
+    a.du = dL_du; a.dh0 = dL_dh0;
+    a.part = reinterpret_cast<float *>(ws + lo.off_part);
+    a.rec = reinterpret_cast<float *>(ws + lo.off_rec);
+    a.flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    a.ctrl = reinterpret_cast<Ctrl *>(ws);
+    switch (cell) {
+    case PARARNN_GRU_DIAG: return backward_diag<GruDiag>(ci, dtype, lo, a, st, dL_dparams);
+    case PARARNN_LSTM_DIAG: return backward_diag<LstmDiag>(ci, dtype, lo, a, st, dL_dparams);
+    case PARARNN_LINEAR_DIAG: return backward_diag<LinearDiag>(ci, dtype, lo, a, st, dL_dparams);
+    }
+    return PARARNN_INVALID_ARG;
+}
+
+int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, int B, int L, int H, float *delta,
+                        void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if ((kind != 0 && kind != 1) || !dims_ok(B, L, H) || !J || !r || !delta || !workspace) return PARARNN_INVALID_ARG;
+    if (!aligned(workspace, 256) || !aligned(J, 4) || !aligned(r, 4) || !aligned(delta, 4)) return PARARNN_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    CellInfo ci = kind == 0 ? CellInfo{1, 1, 0} : CellInfo{2, 2, 0};
+    const int al = align_elems(4, {J, r, delta});
+    const Layout lo = make_layout(kind == 0 ? PARARNN_GRU_DIAG : PARARNN_LSTM_DIAG, ci, PARARNN_F32, B, L, H,
+                                  reverse != 0, al);
+    if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    Ctrl *ctrl = reinterpret_cast<Ctrl *>(ws);
+    unsigned int *flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    // a device int[2] for the (unused) iteration result lives in the control block's padding
+    int *scratch_iters = reinterpret_cast<int *>(&ctrl->pad[0]);
+    hipError_t e = launch_reset(ctrl, flags, (size_t)lo.g.n_tiles, nullptr, 0, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    if (!reverse) {
+        FwdArgs a;
+        memset(&a, 0, sizeof(a));
+        a.g = lo.g; a.u = r; a.jac = J; a.hit = delta;
+        a.rec = reinterpret_cast<float *>(ws + lo.off_rec); a.flags = flags; a.ctrl = ctrl;
+        a.bnd = nullptr; a.iters_out = scratch_iters; a.trace = nullptr;
+        a.k = 1; a.max_iter = 1; a.tol = -1.0f;
+        e = kind == 0 ? Kernels<RawScan<1>, float>::newton_iter(lo.cfg, a, st)
+                      : Kernels<RawScan<2>, float>::newton_iter(lo.cfg, a, st);
+    } else {
+        BwdArgs a;
+        memset(&a, 0, sizeof(a));
+        a.g = lo.g; a.gl = r; a.jac = J; a.du = delta; a.dh0 = nullptr; a.part = nullptr;
+        a.rec = reinterpret_cast<float *>(ws + lo.off_rec); a.flags = flags; a.ctrl = ctrl;
+        e = kind == 0 ? Kernels<RawScan<1>, float>::backward(lo.cfg, a, st)
+                      : Kernels<RawScan<2>, float>::backward(lo.cfg, a, st);
+    }
+    if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+    return PARARNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,877 @@
+// Fused Newton-iteration kernel and fused backward kernel for cells with a
+// diagonal (S = 1) or 2x2-block (S = 2) Jacobian.
+//
+// Work decomposition (one "tile" = CW = 64*VEC channels of one sequence x
+// T = C*W consecutive timesteps):
+//   lane   -> VEC adjacent channels (H is the contiguous axis, so a wave reads
+//             rows of 256*VEC bytes: fully coalesced, no cross-lane traffic)
+//   thread -> C consecutive timesteps, reduced sequentially in registers
+//             (thread-level forward substitution of the paper's App. D.2)
+//   wave   -> W waves of a workgroup take consecutive chunks; their chunk
+//             aggregates are combined through LDS
+//   grid   -> tiles along L are chained by a decoupled look-back: a tile
+//             publishes its aggregate affine map (A, b), then walks back over
+//             its predecessors until it meets one whose inclusive value
+//             (delta at the tile's end) is known.  Tiles are handed out by an
+//             atomic ticket, channel groups fastest, so a tile's predecessors
+//             have always started before it and every wait terminates.
+// The affine maps compose as (A2,b2) o (A1,b1) = (A2 A1, A2 b1 + b2); because
+// delta_0 = 0 the inclusive value of a tile is just a state vector.
+//
+// Nothing but u, the iterate and the new iterate crosses HBM per Newton
+// iteration: residual, Jacobian, scan, update and max|delta| are fused.
+#pragma once
+#include "cells.h"
+
+namespace pararnn {
+
+// test/profiling "cell": J and r come from memory (pararnn_affine_scan)
+template <int S_> struct RawScan {
+    static constexpr int G = S_, S = S_, PR = 0, NC = 1;
+    static constexpr bool kRaw = true;
+};
+template <class Cell, class = void> struct IsRaw { static constexpr bool value = false; };
+template <class Cell> struct IsRaw<Cell, decltype((void)Cell::kRaw)> { static constexpr bool value = true; };
+
+struct ScanGeom {
+    int B, L, H;
+    int T;         // timesteps per tile
+    int n_lt;      // tiles along L
+    int n_cg;      // channel groups per sequence
+    int n_groups;  // B * n_cg
+    int n_tiles;   // n_groups * n_lt
+};
+
+struct FwdArgs {
+    ScanGeom g;
+    const float *params;
+    const void *u;       // [B][L][G][H], fp32 or bf16
+    const void *h0;      // [B][S][H] in u's type, or NULL
+    const float *jac;    // raw scans only: [B][L][S*S][H]
+    float *hit;          // fp32 iterate [B][L][S][H], updated in place
+    float *bnd;          // [2][n_lt][B][S][H]: iterate at each tile's last step
+    float *rec;          // tile records [n_groups][n_lt][S*S + 2S][CW]
+    unsigned int *flags; // [n_groups][n_lt]
+    Ctrl *ctrl;
+    int *iters_out;      // device int[2]
+    float *trace;        // device float[max_iter] or NULL
+    int k;               // Newton iteration (1-based); also the flag epoch
+    int max_iter;
+    float tol;
+};
+
+struct BwdArgs {
+    ScanGeom g;
+    const float *params;
+    const void *u;
+    const void *h0;
+    const void *h;       // forward result [B][L][S][H] in storage type
+    const void *gl;      // dL/dh [B][L][S][H]
+    const float *jac;    // raw scans only
+    void *du;            // out [B][L][G][H]
+    void *dh0;           // out [B][S][H] or NULL
+    float *part;         // parameter-gradient partials [n_lt][B][PR][H]
+    float *rec;
+    unsigned int *flags;
+    Ctrl *ctrl;
+};
+
+// ------------------------------------------------------------ small matrix ops
+// y = A x (S x S times S)
+template <int S>
+__device__ __forceinline__ void mat_vec(const float *A, const float *x, float *y)
+{
+    if constexpr (S == 1) {
+        y[0] = A[0] * x[0];
+    } else {
+        y[0] = fmaf(A[0], x[0], A[1] * x[1]);
+        y[1] = fmaf(A[2], x[0], A[3] * x[1]);
+    }
+}
+// y = A x + b
+template <int S>
+__device__ __forceinline__ void affine(const float *A, const float *x, const float *b, float *y)
+{
+    if constexpr (S == 1) {
+        y[0] = fmaf(A[0], x[0], b[0]);
+    } else {
+        const float y0 = fmaf(A[0], x[0], fmaf(A[1], x[1], b[0]));
+        const float y1 = fmaf(A[2], x[0], fmaf(A[3], x[1], b[1]));
+        y[0] = y0;
+        y[1] = y1;
+    }
+}
+// C = A B
+template <int S>
+__device__ __forceinline__ void mat_mul(const float *A, const float *Bm, float *Cm)
+{
+    if constexpr (S == 1) {
+        Cm[0] = A[0] * Bm[0];
+    } else {
+        const float c0 = fmaf(A[0], Bm[0], A[1] * Bm[2]);
+        const float c1 = fmaf(A[0], Bm[1], A[1] * Bm[3]);
+        const float c2 = fmaf(A[2], Bm[0], A[3] * Bm[2]);
+        const float c3 = fmaf(A[2], Bm[1], A[3] * Bm[3]);
+        Cm[0] = c0; Cm[1] = c1; Cm[2] = c2; Cm[3] = c3;
+    }
+}
+template <int S> __device__ __forceinline__ void set_identity(float *A)
+{
+    if constexpr (S == 1) { A[0] = 1.0f; } else { A[0] = 1.0f; A[1] = 0.0f; A[2] = 0.0f; A[3] = 1.0f; }
+}
+template <int S> __device__ __forceinline__ void transpose_inplace(float *A)
+{
+    if constexpr (S == 2) { const float t = A[1]; A[1] = A[2]; A[2] = t; }
+}
+
+// (accA, accB) <- (J, r) o (accA, accB): apply one more step after the prefix
+template <int S>
+__device__ __forceinline__ void push_step(const float *J, const float *r, float *accA, float *accB)
+{
+    affine<S>(J, accB, r, accB);
+    mat_mul<S>(J, accA, accA);
+}
+
+// Cross-workgroup carry: value entering tile `lt` of chain `grp`, obtained by
+// walking over the predecessors in direction `dir` (-1: towards l = 0, used by
+// the forward scan; +1: towards l = L, used by the reverse scan).  Called by
+// all 64 lanes of one wave; lane handles VEC channels.  Returns false when a
+// bounded wait ran out (carry is then zero).
+template <int S, int VEC>
+__device__ __forceinline__ bool lookback(const float *rec_base, const unsigned int *flags_base, int n_lt,
+                                         int grp, int lt, int dir, unsigned int epoch, int lane,
+                                         float (&carry)[S][VEC])
+{
+    constexpr int SS = S * S, CW = kWave * VEC, REC = SS + 2 * S;
+    float LA[VEC][SS], LB[VEC][S];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        set_identity<S>(LA[v]);
+#pragma unroll
+        for (int s = 0; s < S; ++s) LB[v][s] = 0.0f;
+    }
+    int j = lt + dir;
+    for (;;) {
+        const unsigned int *fj = flags_base + (size_t)grp * n_lt + j;
+        unsigned int f = 0, spins = 0;
+        for (;;) {
+            f = __builtin_amdgcn_readfirstlane(flag_load(fj));
+            if ((f >> 2) == epoch) break;
+            if (++spins >= kSpinLimit) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if ((f >> 2) != epoch) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                for (int s = 0; s < S; ++s) carry[s][v] = 0.0f;
+            return false;
+        }
+        fence_acquire();
+        const float *rj = rec_base + ((size_t)grp * n_lt + j) * (REC * CW) + lane * VEC;
+        if ((f & 3u) == kFlagIncl) {
+            float inc[S][VEC];
+#pragma unroll
+            for (int s = 0; s < S; ++s) load_vec<VEC>(rj + (SS + S + s) * CW, inc[s]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float x[S], y[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) x[s] = inc[s][v];
+                affine<S>(LA[v], x, LB[v], y);
+#pragma unroll
+                for (int s = 0; s < S; ++s) carry[s][v] = y[s];
+            }
+            return true;
+        }
+        float Aj[SS][VEC], bj[S][VEC];
+#pragma unroll
+        for (int e = 0; e < SS; ++e) load_vec<VEC>(rj + e * CW, Aj[e]);
+#pragma unroll
+        for (int s = 0; s < S; ++s) load_vec<VEC>(rj + (SS + s) * CW, bj[s]);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float A1[SS], b1[S];
+#pragma unroll
+            for (int e = 0; e < SS; ++e) A1[e] = Aj[e][v];
+#pragma unroll
+            for (int s = 0; s < S; ++s) b1[s] = bj[s][v];
+            affine<S>(LA[v], b1, LB[v], LB[v]);   // LB = LA b_j + LB
+            mat_mul<S>(LA[v], A1, LA[v]);         // LA = LA A_j
+        }
+        j += dir;
+        if (j < 0 || j >= n_lt) {   // ran past the end of the chain: value there is 0
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                for (int s = 0; s < S; ++s) carry[s][v] = LB[v][s];
+            return true;
+        }
+    }
+}
+
+// Publish this tile's aggregate or inclusive value.  All lanes of the wave
+// store their channels, the wave-wide release fence orders them before the
+// flag that one lane sets afterwards.
+template <int N, int VEC>
+__device__ __forceinline__ void publish(float *rec_rows, const float (&val)[N][VEC], unsigned int *flag,
+                                        unsigned int value, int lane)
+{
+    constexpr int CW = kWave * VEC;
+#pragma unroll
+    for (int e = 0; e < N; ++e) store_vec<VEC>(rec_rows + e * CW + lane * VEC, val[e]);
+    fence_release();
+    if (lane == 0) flag_store(flag, value);
+}
+
+__device__ __forceinline__ float wave_nanmax(float m)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = nanmax(m, __shfl_xor(m, off, 64));
+    return m;
+}
+
+// ======================================================================
+// One Newton iteration (Alg. 1a body): residual + Jacobian (Eq. (3)), prefix
+// scan of Eq. (4), update, max|delta|, and the device-side stopping test.
+// ======================================================================
+template <class Cell, int VEC, int C, int W, typename UT>
+__global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
+{
+    constexpr int S = Cell::S, G = Cell::G, SS = S * S, CW = kWave * VEC, PR = Cell::PR;
+    constexpr int REC = SS + 2 * S, T = C * W;
+    constexpr bool kRaw = IsRaw<Cell>::value;
+    __shared__ float s_A[W][SS][CW];
+    __shared__ float s_b[W][S][CW];
+    __shared__ float s_carry[S][CW];
+    __shared__ float s_max[W];
+    __shared__ unsigned int s_ticket;
+
+    Ctrl *ctrl = a.ctrl;
+    if (ctrl->stop) return;
+    const ScanGeom &g = a.g;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const unsigned int epoch = (unsigned int)a.k;
+    const UT *u = static_cast<const UT *>(a.u);
+    const int cur = a.k & 1, nxt = cur ^ 1;
+    float wmax = 0.0f;
+    bool internal_error = false;
+
+    for (;;) {
+        if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+        __syncthreads();
+        const unsigned int t = s_ticket;
+        if (t >= (unsigned int)g.n_tiles) break;
+        const int grp = (int)(t % (unsigned int)g.n_groups), lt = (int)(t / (unsigned int)g.n_groups);
+        const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
+        const int ch = cg * CW + lane * VEC;
+        const bool ch_ok = ch < g.H;
+        const int l0 = lt * T + w * C;
+        const size_t seq = (size_t)b * g.L;
+
+        float p[VEC][PR > 0 ? PR : 1];
+        if constexpr (PR > 0) {
+#pragma unroll
+            for (int r = 0; r < PR; ++r) {
+                float tmp[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) tmp[v] = 0.0f;
+                if (ch_ok) load_vec<VEC>(a.params + (size_t)r * g.H + ch, tmp);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+            }
+        }
+
+        // ---- loads: u and the old iterate for the C steps of this thread
+        float uu[C][G][VEC], ho[C][S][VEC], jr[kRaw ? C : 1][kRaw ? SS : 1][VEC], hprev[S][VEC];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int l = l0 + i;
+            const bool ok = ch_ok && l < g.L;
+#pragma unroll
+            for (int q = 0; q < G; ++q) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) uu[i][q][v] = 0.0f;
+                if (ok) load_vec<VEC>(u + ((seq + l) * G + q) * g.H + ch, uu[i][q]);
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) ho[i][s][v] = 0.0f;
+                if constexpr (!kRaw) {
+                    if (ok) load_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                }
+            }
+            if constexpr (kRaw) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) jr[i][e][v] = 0.0f;
+                    if (ok) load_vec<VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch, jr[i][e]);
+                }
+            }
+        }
+        // state entering the chunk: h0, the previous tile's boundary row, or
+        // the row just before the chunk (still the old iterate: no wave of this
+        // tile stores before the barriers below)
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) hprev[s][v] = 0.0f;
+            if constexpr (!kRaw) {
+                if (ch_ok && l0 <= g.L) {
+                    if (l0 == 0) {
+                        if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hprev[s]);
+                    } else if (w == 0) {
+                        load_vec<VEC>(a.bnd + ((((size_t)cur * g.n_lt + (lt - 1)) * g.B + b) * S + s) * g.H + ch, hprev[s]);
+                    } else {
+                        load_vec<VEC>(a.hit + ((seq + l0 - 1) * S + s) * g.H + ch, hprev[s]);
+                    }
+                }
+            }
+        }
+
+        // ---- thread-level reduction: local prefix (PA_i, qb_i) after each step
+        float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            set_identity<S>(accA[v]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            if (l0 + i < g.L) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float J[SS], r[S];
+                    if constexpr (kRaw) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) J[e] = jr[i][e][v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) r[s] = uu[i][s][v];
+                    } else {
+                        float hp[S], ug[G], F[S];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
+#pragma unroll
+                        for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                        Cell::fwd(p[v], hp, ug, F, J);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
+                    }
+                    push_step<S>(J, r, accA[v], accB[v]);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
+            }
+        }
+
+        // ---- workgroup level: chunk aggregates through LDS
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+            for (int e = 0; e < SS; ++e) s_A[w][e][lane * VEC + v] = accA[v][e];
+#pragma unroll
+            for (int s = 0; s < S; ++s) s_b[w][s][lane * VEC + v] = accB[v][s];
+        }
+        __syncthreads();
+
+        // exclusive prefix over the waves before this one (all waves), and the
+        // tile aggregate (wave 0)
+        float exA[VEC][SS], exB[VEC][S];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            set_identity<S>(exA[v]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
+        }
+        const int upto = w == 0 ? W : w;
+        float tileA[SS][VEC], tileB[S][VEC];
+        for (int j = 0; j < upto; ++j) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float Aj[SS], bj[S];
+#pragma unroll
+                for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][lane * VEC + v];
+#pragma unroll
+                for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][lane * VEC + v];
+                push_step<S>(Aj, bj, exA[v], exB[v]);
+            }
+        }
+        if (w == 0) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) tileB[s][v] = exB[v][s];
+                set_identity<S>(exA[v]);
+#pragma unroll
+                for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
+            }
+            // ---- grid level: decoupled look-back along L
+            float carry[S][VEC];
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) carry[s][v] = 0.0f;
+            const bool has_next = lt + 1 < g.n_lt;
+            float *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (REC * CW);
+            unsigned int *flag = a.flags + (size_t)grp * g.n_lt + lt;
+            if (lt > 0) {
+                if (has_next) {
+                    float ab[SS + S][VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) ab[e][v] = tileA[e][v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
+                    }
+                    publish<SS + S, VEC>(rec, ab, flag, epoch * 4u + kFlagAgg, lane);
+                }
+                if (!lookback<S, VEC>(a.rec, a.flags, g.n_lt, grp, lt, -1, epoch, lane, carry))
+                    internal_error = true;
+            }
+            if (has_next) {
+                float inc[S][VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float A1[SS], x[S], b1[S], y[S];
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) A1[e] = tileA[e][v];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
+                    affine<S>(A1, x, b1, y);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) inc[s][v] = y[s];
+                }
+                publish<S, VEC>(rec + (SS + S) * CW, inc, flag, epoch * 4u + kFlagIncl, lane);
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) s_carry[s][lane * VEC + v] = carry[s][v];
+        }
+        __syncthreads();
+
+        // ---- back-substitution: delta entering this chunk, then every step
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float cin[S], din[S];
+#pragma unroll
+            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][lane * VEC + v];
+            affine<S>(exA[v], cin, exB[v], din);
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                float d[S];
+                affine<S>(PA[i][v], din, qb[i][v], d);
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    ho[i][s][v] += d[s];
+                    if (ch_ok && l0 + i < g.L) wmax = nanmax(wmax, __builtin_fabsf(d[s]));
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int l = l0 + i;
+            if (ch_ok && l < g.L) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) store_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+            }
+        }
+        if constexpr (!kRaw) {
+            if (ch_ok && w == W - 1 && lt + 1 < g.n_lt) {
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+                    store_vec<VEC>(a.bnd + ((((size_t)nxt * g.n_lt + lt) * g.B + b) * S + s) * g.H + ch, ho[C - 1][s]);
+            }
+        }
+    }
+
+    // ---- convergence reduction and, in the last workgroup, the stopping test
+    wmax = wave_nanmax(wmax);
+    if (lane == 0) s_max[w] = wmax;
+    if (internal_error && lane == 0) atomicExch(&ctrl->status, kStInternal);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = 0.0f;
+#pragma unroll
+        for (int j = 0; j < W; ++j) m = nanmax(m, s_max[j]);
+        atomicMax(&ctrl->gmax_bits, __float_as_uint(m));
+        __threadfence();
+        const unsigned int prev = atomicAdd(&ctrl->done, 1u);
+        if (prev == gridDim.x - 1) {
+            __threadfence();
+            const float mk = __uint_as_float(atomicMax(&ctrl->gmax_bits, 0u));
+            int status = atomicAdd(&ctrl->status, 0), stop = 0;
+            if (a.trace) a.trace[a.k - 1] = mk;
+            if (status == kStInternal) {
+                stop = 1;
+            } else if (!(mk - mk == 0.0f)) {
+                status = kStNonFinite;
+                stop = 1;
+            } else if (a.tol >= 0.0f && mk <= a.tol) {
+                status = kStOk;
+                stop = 1;
+            } else {
+                status = a.tol < 0.0f ? kStOk : kStNotConverged;
+            }
+            a.iters_out[0] = a.k;
+            a.iters_out[1] = status;
+            ctrl->iters = a.k;
+            ctrl->status = status;
+            ctrl->stop = stop;
+            ctrl->ticket = 0u;
+            ctrl->done = 0u;
+            ctrl->gmax_bits = 0u;
+            __threadfence();
+        }
+    }
+}
+
+// Initial guess h^0_l = f(h0, u_l) for every l (App. A), plus the boundary rows
+// the first iteration reads.  One thread per (b, l, VEC channels).
+template <class Cell, int VEC, typename UT>
+__global__ __launch_bounds__(256) void init_guess_kernel(const FwdArgs a)
+{
+    constexpr int S = Cell::S, G = Cell::G, PR = Cell::PR;
+    const ScanGeom &g = a.g;
+    const int hv = g.H / VEC;
+    const size_t n = (size_t)g.B * g.L * hv;
+    const UT *u = static_cast<const UT *>(a.u);
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        const int ch = (int)(idx % hv) * VEC;
+        const size_t bl = idx / hv;
+        const int l = (int)(bl % g.L), b = (int)(bl / g.L);
+        float p[VEC][PR], uu[G][VEC], hp[S][VEC], out[S][VEC];
+#pragma unroll
+        for (int r = 0; r < PR; ++r) {
+            float tmp[VEC];
+            load_vec<VEC>(a.params + (size_t)r * g.H + ch, tmp);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+        }
+#pragma unroll
+        for (int q = 0; q < G; ++q) load_vec<VEC>(u + (bl * G + q) * g.H + ch, uu[q]);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) hp[s][v] = 0.0f;
+            if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hp[s]);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float h1[S], u1[G], F[S];
+#pragma unroll
+            for (int s = 0; s < S; ++s) h1[s] = hp[s][v];
+#pragma unroll
+            for (int q = 0; q < G; ++q) u1[q] = uu[q][v];
+            Cell::step(p[v], h1, u1, F);
+#pragma unroll
+            for (int s = 0; s < S; ++s) out[s][v] = F[s];
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) store_vec<VEC>(a.hit + (bl * S + s) * g.H + ch, out[s]);
+        if ((l + 1) % g.T == 0 && (l + 1) / g.T < g.n_lt) {
+            const int lt = (l + 1) / g.T - 1;
+            // iteration 1 reads boundary buffer 1 (k & 1)
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                store_vec<VEC>(a.bnd + ((((size_t)1 * g.n_lt + lt) * g.B + b) * S + s) * g.H + ch, out[s]);
+        }
+    }
+}
+
+// ======================================================================
+// Backward (Eq. (6)) as one reverse scan.  With nu_l = J_l^T lam_l the adjoint
+// recurrence lam_{l-1} = J_l^T lam_l + g_{l-1} reads
+//     nu_l = J_l^T nu_{l+1} + J_l^T g_l,   nu_{L+1} = 0,   lam_l = g_l + nu_{l+1},
+// so element l of the scan needs only step l's own data (h_{l-1}, u_l, g_l).
+// dL/dh0 = nu_1.  Parameter gradients are reduced per tile into `part`
+// and summed by param_reduce_kernel (fixed order: bit-reproducible).
+// ======================================================================
+template <class Cell, int VEC, int C, int W, typename UT>
+__global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
+{
+    constexpr int S = Cell::S, G = Cell::G, SS = S * S, CW = kWave * VEC, PR = Cell::PR, NC = Cell::NC;
+    constexpr int REC = SS + 2 * S, T = C * W;
+    constexpr bool kRaw = IsRaw<Cell>::value;
+    constexpr int PRX = PR > 0 ? PR : 1;
+    constexpr int LDSROWS = (SS + S) > PRX ? (SS + S) : PRX;
+    __shared__ float s_buf[W][LDSROWS][CW];   // chunk aggregates, then gradient partials
+    __shared__ float s_carry[S][CW];
+    __shared__ unsigned int s_ticket;
+
+    Ctrl *ctrl = a.ctrl;
+    const ScanGeom &g = a.g;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const unsigned int epoch = 1u;
+    const UT *u = static_cast<const UT *>(a.u);
+    const UT *hres = static_cast<const UT *>(a.h);
+    const UT *gl = static_cast<const UT *>(a.gl);
+    UT *du = static_cast<UT *>(a.du);
+    bool internal_error = false;
+
+    for (;;) {
+        if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+        __syncthreads();
+        const unsigned int t = s_ticket;
+        if (t >= (unsigned int)g.n_tiles) break;
+        const int grp = (int)(t % (unsigned int)g.n_groups);
+        const int lt = g.n_lt - 1 - (int)(t / (unsigned int)g.n_groups);   // from the end of the sequence
+        const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
+        const int ch = cg * CW + lane * VEC;
+        const bool ch_ok = ch < g.H;
+        const int l0 = lt * T + w * C;
+        const size_t seq = (size_t)b * g.L;
+
+        float p[VEC][PRX];
+        if constexpr (PR > 0) {
+#pragma unroll
+            for (int r = 0; r < PR; ++r) {
+                float tmp[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) tmp[v] = 0.0f;
+                if (ch_ok) load_vec<VEC>(a.params + (size_t)r * g.H + ch, tmp);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+            }
+        }
+
+        // ---- loads: u_l, h_{l-1}, g_l for the C steps of this thread
+        float uu[C][G][VEC], hp[C][S][VEC], gg[C][S][VEC], jr[kRaw ? C : 1][kRaw ? SS : 1][VEC];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int l = l0 + i;
+            const bool ok = ch_ok && l < g.L;
+            if constexpr (!kRaw) {
+#pragma unroll
+                for (int q = 0; q < G; ++q) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) uu[i][q][v] = 0.0f;
+                    if (ok) load_vec<VEC>(u + ((seq + l) * G + q) * g.H + ch, uu[i][q]);
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) { hp[i][s][v] = 0.0f; gg[i][s][v] = 0.0f; }
+                if (ok) {
+                    load_vec<VEC>(gl + ((seq + l) * S + s) * g.H + ch, gg[i][s]);
+                    if constexpr (!kRaw) {
+                        if (l > 0) load_vec<VEC>(hres + ((seq + l - 1) * S + s) * g.H + ch, hp[i][s]);
+                        else if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hp[i][s]);
+                    }
+                }
+            }
+            if constexpr (kRaw) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) jr[i][e][v] = 0.0f;
+                    if (ok) load_vec<VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch, jr[i][e]);
+                }
+            }
+        }
+
+        // ---- thread-level reverse reduction.  For step i keep the map from the
+        // value entering the chunk on the right (nu_in) to lam_i:
+        //     lam_i = PX_i nu_in + qx_i,   PX_i = prod_{j>i} J_j^T,  qx_i = g_i + q_{i+1}
+        float PX[C][VEC][SS], qx[C][VEC][S], kk[C][VEC][NC], accA[VEC][SS], accB[VEC][S];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            set_identity<S>(accA[v]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
+        }
+#pragma unroll
+        for (int i = C - 1; i >= 0; --i) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) PX[i][v][e] = accA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) qx[i][v][s] = accB[v][s] + gg[i][s][v];
+            }
+            if (l0 + i < g.L) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float J[SS], zero[S];
+                    if constexpr (kRaw) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) J[e] = jr[i][e][v];
+                    } else {
+                        float h1[S], ug[G];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) h1[s] = hp[i][s][v];
+#pragma unroll
+                        for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                        Cell::bwd_prep(p[v], h1, ug, J, kk[i][v]);
+                    }
+                    transpose_inplace<S>(J);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) zero[s] = 0.0f;
+                    // nu_i = J^T (g_i + nu_{i+1}):  accB = J^T qx_i,  accA = J^T accA
+                    affine<S>(J, qx[i][v], zero, accB[v]);
+                    mat_mul<S>(J, accA[v], accA[v]);
+                }
+            }
+        }
+
+        // ---- workgroup level
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+            for (int e = 0; e < SS; ++e) s_buf[w][e][lane * VEC + v] = accA[v][e];
+#pragma unroll
+            for (int s = 0; s < S; ++s) s_buf[w][SS + s][lane * VEC + v] = accB[v][s];
+        }
+        __syncthreads();
+        // exclusive suffix over the waves after this one; wave W-1 also forms
+        // the tile aggregate and runs the look-forward
+        float exA[VEC][SS], exB[VEC][S];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            set_identity<S>(exA[v]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
+        }
+        const int down_to = w == W - 1 ? 0 : w + 1;
+        for (int j = W - 1; j >= down_to; --j) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float Aj[SS], bj[S];
+#pragma unroll
+                for (int e = 0; e < SS; ++e) Aj[e] = s_buf[j][e][lane * VEC + v];
+#pragma unroll
+                for (int s = 0; s < S; ++s) bj[s] = s_buf[j][SS + s][lane * VEC + v];
+                push_step<S>(Aj, bj, exA[v], exB[v]);
+            }
+        }
+        if (w == W - 1) {
+            float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
+                set_identity<S>(exA[v]);
+            }
+            const bool has_next = lt > 0;            // a tile to the left will ask
+            float *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (REC * CW);
+            unsigned int *flag = a.flags + (size_t)grp * g.n_lt + lt;
+            if (lt + 1 < g.n_lt) {
+                if (has_next) {
+                    float ab[SS + S][VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) ab[e][v] = tileA[e][v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
+                    }
+                    publish<SS + S, VEC>(rec, ab, flag, epoch * 4u + kFlagAgg, lane);
+                }
+                if (!lookback<S, VEC>(a.rec, a.flags, g.n_lt, grp, lt, +1, epoch, lane, carry))
+                    internal_error = true;
+            }
+            if (has_next) {
+                float inc[S][VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float A1[SS], x[S], b1[S], y[S];
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) A1[e] = tileA[e][v];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
+                    affine<S>(A1, x, b1, y);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) inc[s][v] = y[s];
+                }
+                publish<S, VEC>(rec + (SS + S) * CW, inc, flag, epoch * 4u + kFlagIncl, lane);
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) s_carry[s][lane * VEC + v] = carry[s][v];
+        }
+        __syncthreads();
+
+        // ---- back-substitution: lam for every step, then du and the
+        // parameter-gradient contributions
+        float acc[VEC][PRX];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+#pragma unroll
+            for (int r = 0; r < PRX; ++r) acc[v][r] = 0.0f;
+        float duv[C][G][VEC];
+        float nu0[S][VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float cin[S], nin[S];
+#pragma unroll
+            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][lane * VEC + v];
+            affine<S>(exA[v], cin, exB[v], nin);      // nu entering this chunk from the right
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                float lam[S], d1[G];
+                affine<S>(PX[i][v], nin, qx[i][v], lam);
+                if constexpr (kRaw) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) d1[s] = lam[s];
+                } else {
+                    if (l0 + i < g.L) Cell::bwd_emit(kk[i][v], lam, d1, acc[v]);
+                }
+#pragma unroll
+                for (int q = 0; q < G; ++q) duv[i][q][v] = d1[q];
+            }
+            // nu at the chunk's first step (dL/dh0 when that step is l = 0)
+            float n0[S];
+            affine<S>(accA[v], nin, accB[v], n0);
+#pragma unroll
+            for (int s = 0; s < S; ++s) nu0[s][v] = n0[s];
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const int l = l0 + i;
+            if (ch_ok && l < g.L) {
+#pragma unroll
+                for (int q = 0; q < G; ++q) store_vec<VEC>(du + ((seq + l) * G + q) * g.H + ch, duv[i][q]);
+            }
+        }
+        if (a.dh0 && ch_ok && l0 == 0) {
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                store_vec<VEC>(static_cast<UT *>(a.dh0) + ((size_t)b * S + s) * g.H + ch, nu0[s]);
+        }
+        if constexpr (PR > 0) {
+            __syncthreads();   // aggregates in s_buf are no longer needed
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                for (int r = 0; r < PR; ++r) s_buf[w][r][lane * VEC + v] = acc[v][r];
+            __syncthreads();
+            // W*PR*CW values -> PR*CW sums, spread over all threads of the workgroup
+            for (int idx = threadIdx.x; idx < PR * CW; idx += kWave * W) {
+                const int r = idx / CW, c = idx - r * CW;
+                float s = 0.0f;
+#pragma unroll
+                for (int j = 0; j < W; ++j) s += s_buf[j][r][c];
+                const int chn = cg * CW + c;
+                if (chn < g.H) a.part[(((size_t)lt * g.B + b) * PR + r) * g.H + chn] = s;
+            }
+        }
+    }
+    if (internal_error && lane == 0) atomicExch(&ctrl->status, kStInternal);
+}
+
+}  // namespace pararnn

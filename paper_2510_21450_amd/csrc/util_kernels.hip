@@ -1,0 +1,98 @@
+// Small helper kernels shared by all paths, and their launchers.
+#include "launch.h"
+
+namespace pararnn {
+
+// Clears the control block and the tile flags of a call, and sets the result
+// of a solve that performs no iteration.
+__global__ void reset_kernel(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        ctrl->ticket = 0u; ctrl->done = 0u; ctrl->gmax_bits = 0u;
+        ctrl->stop = 0; ctrl->iters = 0; ctrl->status = status0;
+        if (iters_out) { iters_out[0] = 0; iters_out[1] = status0; }
+    }
+    for (size_t j = i; j < n_flags; j += (size_t)gridDim.x * blockDim.x) flags[j] = 0u;
+}
+
+// bf16 storage: round the converged fp32 iterate once into the output.
+__global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsigned short *dst, size_t n4)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+        float v[4];
+        load_vec<4>(src + 4 * i, v);
+        store_vec<4>(dst + 4 * i, v);
+    }
+}
+
+__global__ void store_bf16_tail_kernel(const float *src, unsigned short *dst, int n)
+{
+    if ((int)threadIdx.x < n) dst[threadIdx.x] = f32_to_bf16(src[threadIdx.x]);
+}
+
+// dL/dparams[r][ch] = sum over (lt, b) of part[lt][b][r][ch], in index order.
+__global__ __launch_bounds__(256) void param_reduce_kernel(const float *part, float *out, int n_terms, int n_out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_out) return;
+    float s = 0.0f;
+    for (int t = 0; t < n_terms; ++t) s += part[(size_t)t * n_out + i];
+    out[i] = s;
+}
+
+}  // namespace pararnn
+
+namespace pararnn {
+
+hipError_t launch_reset(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0,
+                        hipStream_t st)
+{
+    size_t blocks = (n_flags + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ctrl, flags, n_flags, iters_out,
+                       status0);
+    return hipGetLastError();
+}
+
+hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t st)
+{
+    // n is a multiple of 4 whenever this is used (vec = 4 path) or handled by the tail kernel
+    const size_t n4 = n / 4;
+    if (n4) {
+        size_t blocks = (n4 + 255) / 256;
+        const size_t cap = (size_t)device_cu_count() * 32;
+        if (blocks > cap) blocks = cap;
+        hipLaunchKernelGGL(store_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src,
+                           static_cast<unsigned short *>(dst), n4);
+    }
+    if (n % 4) {
+        hipLaunchKernelGGL(store_bf16_tail_kernel, dim3(1), dim3(64), 0, st, src + 4 * n4,
+                           static_cast<unsigned short *>(dst) + 4 * n4, (int)(n % 4));
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(param_reduce_kernel, dim3((n_out + 255) / 256), dim3(256), 0, st, part, out, n_terms, n_out);
+    return hipGetLastError();
+}
+
+int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+}  // namespace pararnn
+

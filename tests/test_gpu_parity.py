@@ -1,0 +1,217 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on
+identical seeded inputs.  fp32 results must agree to 1e-5 (norm-wise max
+relative error), bf16-storage results to 2e-2, iteration counts
+exactly."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
+from workloads.rng import normal, uniform_sym               # noqa: E402
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2510_21450_amd as P
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return P
+
+
+def relerr(got, ref):
+    """max |got - ref| / max |ref| (norm-wise, infinity norm)."""
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def to_np(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+def problem(cell, B, L, H, seed, dtype=torch.float32, h0=True, bias=True, bound=0.9):
+    """Random problem with nonzero biases and h0, on the GPU, plus fp64 host copies."""
+    G, S = cell_dims(cell)
+    dev = "cuda"
+    if cell == "tanh_dense":
+        params = normal(seed, 5, (H, H), std=0.8 / H ** 0.5, device=dev)
+    else:
+        params = torch.zeros(2, G, H, device=dev)
+        params[0] = uniform_sym(seed, 2, (G, H), bound, device=dev)
+        if bias:
+            params[1] = normal(seed, 6, (G, H), std=0.3, device=dev)
+    u = normal(seed, 1, (B, L, G, H), dtype=dtype, device=dev)
+    h0t = normal(seed, 3, (B, S, H), std=0.3, dtype=dtype, device=dev) if h0 else None
+    g = normal(seed, 4, (B, L, S, H), dtype=dtype, device=dev)
+    return params, u, h0t, g
+
+
+SHAPES = [(1, 1, 8), (1, 2, 4), (2, 33, 1), (2, 100, 24), (3, 257, 68), (2, 1000, 130), (1, 31, 64),
+          (1, 32, 256), (2, 64, 512), (1, 65, 6)]
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_forward_backward_f32_small(P, oracle_mod, cell, shape):
+    B, L, H = shape
+    print(f"case {cell} B={B} L={L} H={H}", flush=True)
+    params, u, h0, g = problem(cell, B, L, H, seed=1000 + L * 7 + H)
+    tol = 1e-5
+    h, iters, tr = P.forward(cell, params, u, h0, tol=tol, max_iter=40, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    assert st == 0, P.status_string(st)
+    assert relerr(to_np(h), ref) <= TOL_F32
+    # iteration count: the oracle's Newton in the kernel's precision; only
+    # asserted where the stopping decision has a clear margin in fp32 and fp64
+    _, it32, _, tr32 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40, precision="f32")
+    _, it64, _, tr64 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40, precision="f64")
+    clear = it32 == it64 and tr32[-1] <= tol / 4 and (len(tr32) < 2 or tr32[-2] >= 4 * tol) \
+        and tr64[-1] <= tol / 4 and (len(tr64) < 2 or tr64[-2] >= 4 * tol)
+    if clear:
+        assert it == it32, (it, it32, tr.cpu().numpy()[:it], tr32)
+    else:
+        assert abs(it - it32) <= 1
+    # backward at the GPU's own forward result
+    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    torch.cuda.synchronize()
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+    assert relerr(to_np(du), rdu) <= TOL_F32
+    assert relerr(to_np(dp), rdp) <= TOL_F32
+    assert relerr(to_np(dh0), rdh0) <= TOL_F32
+
+
+def test_config_c1(P, oracle_mod):
+    """BASELINE config 1: GRU, B=1, L=64, H=8, tol 1e-6, max_iter 64, forward."""
+    w = CONFIGS["C1"]
+    d = make_inputs(w, device="cuda")
+    h, iters, tr = P.forward(w.cell, d["params"], d["u"], d["h0"], tol=w.tol, max_iter=w.max_iter, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    pn, un = to_np(d["params"]), to_np(d["u"])
+    ref = oracle_mod.seq_unroll(w.cell, pn, un, None)
+    assert st == 0 and relerr(to_np(h), ref) <= TOL_F32
+    _, it32, _, tr32 = oracle_mod.newton(w.cell, pn, un, None, tol=w.tol, max_iter=w.max_iter, precision="f32")
+    assert it == it32 == 5
+    got = tr.cpu().numpy()[:it]
+    # before the fp32 floor the per-iteration maxima agree closely
+    assert np.allclose(got[:3], tr32[:3], rtol=1e-3)
+    assert np.allclose(got[3], tr32[3], rtol=5e-2)     # 6.7e-6: fp32 rounding (~1e-7) shows
+
+
+def test_linear_cell_one_solve_is_exact(P, oracle_mod):
+    params, u, h0, _ = problem("linear_diag", 2, 300, 40, seed=7)
+    h, iters, _ = P.forward("linear_diag", params, u, h0, tol=-1.0, max_iter=1)
+    torch.cuda.synchronize()
+    ref = oracle_mod.seq_unroll("linear_diag", to_np(params), to_np(u), to_np(h0))
+    assert tuple(int(x) for x in iters.cpu()) == (1, 0)
+    assert relerr(to_np(h), ref) <= TOL_F32
+    # with a stopping test the second solve confirms: iters == 2
+    h, iters, tr = P.forward("linear_diag", params, u, h0, tol=1e-4, max_iter=10, trace=True)
+    assert tuple(int(x) for x in iters.cpu()) == (2, 0)
+
+
+def test_iteration_control_edge_cases(P, oracle_mod):
+    cell = "gru_diag"
+    params, u, h0, _ = problem(cell, 2, 70, 12, seed=11)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    # max_iter = 0: the initial guess f(h0, u_l)
+    h, iters, _ = P.forward(cell, params, u, h0, tol=1e-6, max_iter=0)
+    hg, _, _, _ = oracle_mod.newton(cell, pn, un, h0n, tol=1e-6, max_iter=0)
+    assert tuple(int(x) for x in iters.cpu()) == (0, 1)
+    assert relerr(to_np(h), hg) <= TOL_F32
+    # tol < 0: exactly max_iter solves, status OK; iterate k matches the oracle's iterate k
+    for k in (1, 2, 3):
+        h, iters, _ = P.forward(cell, params, u, h0, tol=-1.0, max_iter=k)
+        hk, _, _, _ = oracle_mod.newton(cell, pn, un, h0n, tol=-1.0, max_iter=k)
+        assert tuple(int(x) for x in iters.cpu()) == (k, 0)
+        assert relerr(to_np(h), hk) <= 2e-5
+    # not converged: last iterate, iters = max_iter, status NOT_CONVERGED
+    h, iters, _ = P.forward(cell, params, u, h0, tol=0.0, max_iter=2)
+    assert tuple(int(x) for x in iters.cpu()) == (2, 1)
+    # L = 1: the guess is exact; one solve with delta = 0
+    h, iters, tr = P.forward(cell, params, u[:, :1].contiguous(), h0, tol=0.0, max_iter=5, trace=True)
+    assert tuple(int(x) for x in iters.cpu()) == (1, 0) and float(tr[0]) == 0.0
+    # NaN in the input -> NONFINITE after the first solve
+    u2 = u.clone(); u2[0, 3, 0, 0] = float("nan")
+    h, iters, _ = P.forward(cell, params, u2, h0, tol=1e-6, max_iter=5)
+    assert tuple(int(x) for x in iters.cpu()) == (1, 5)
+    # h0 = None is zeros
+    ha, _, _ = P.forward(cell, params, u, None, tol=1e-6, max_iter=20)
+    hb, _, _ = P.forward(cell, params, u, torch.zeros_like(h0), tol=1e-6, max_iter=20)
+    assert torch.equal(ha, hb)
+
+
+def test_invalid_arguments_are_rejected(P):
+    params, u, h0, _ = problem("gru_diag", 1, 8, 8, seed=3)
+    with pytest.raises(RuntimeError, match="INVALID_ARG"):
+        P.forward("gru_diag", params, u, h0, tol=float("nan"))
+    with pytest.raises(RuntimeError, match="INVALID_ARG"):
+        P.forward("gru_diag", params, u, h0, max_iter=-1)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError, match="WORKSPACE_TOO_SMALL"):
+        P.forward("gru_diag", params, u, h0, workspace=small)
+
+
+@pytest.mark.parametrize("kind", ["diag", "block2"])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_affine_scan_matches_forward_substitution(P, oracle_mod, kind, reverse):
+    """The scan on its own (random J, r) against Eq. (4) at tile-boundary
+    lengths; reverse = the adjoint recurrence of Eq. (6)."""
+    H = 70
+    for L in (1, 2, 31, 32, 33, 63, 64, 65, 100, 257, 1025):
+        print(f"scan {kind} reverse={reverse} L={L}", flush=True)
+        B = 2
+        seed = 500 + L
+        if kind == "diag":
+            J = uniform_sym(seed, 1, (B, L, H), 0.95, device="cuda")
+            r = normal(seed, 2, (B, L, H), device="cuda")
+        else:
+            J = uniform_sym(seed, 1, (B, L, 2, 2, H), 0.6, device="cuda")
+            r = normal(seed, 2, (B, L, 2, H), device="cuda")
+        d = P.affine_scan(J, r, reverse=reverse)
+        torch.cuda.synchronize()
+        Jn, rn = to_np(J), to_np(r)
+        for b in range(B):
+            if not reverse:
+                ref = oracle_mod.forward_substitution(kind, Jn[b], rn[b])
+            else:
+                # lam_l = J_{l+1}^T lam_{l+1} + r_l: flip time, shift J by one, transpose
+                Jt = Jn[b][::-1].copy()
+                if kind == "block2":
+                    Jt = Jt.transpose(0, 2, 1, 3).copy()
+                Js = np.zeros_like(Jt); Js[1:] = Jt[:-1]
+                ref = oracle_mod.forward_substitution(kind, Js, rn[b][::-1].copy())[::-1]
+            assert relerr(to_np(d[b]), ref) <= TOL_F32, (kind, reverse, L)
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+def test_bf16_storage(P, oracle_mod, cell):
+    """bf16 storage, fp32 arithmetic: the oracle takes the bf16-rounded inputs
+    as exact and computes in fp64; bound 2e-2."""
+    B, L, H = 2, 300, 136
+    params, u, h0, g = problem(cell, B, L, H, seed=77, dtype=torch.bfloat16)
+    h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    assert st == 0 and h.dtype == torch.bfloat16
+    assert relerr(to_np(h), ref) <= TOL_BF16
+    _, it32, _, _ = oracle_mod.newton(cell, pn, un, h0n, tol=1e-5, max_iter=40, precision="f32")
+    assert abs(it - it32) <= 1
+    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    torch.cuda.synchronize()
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+    assert relerr(to_np(du), rdu) <= TOL_BF16
+    assert relerr(to_np(dp), rdp) <= TOL_BF16
+    assert relerr(to_np(dh0), rdh0) <= TOL_BF16
