@@ -1,0 +1,160 @@
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: the
+forward Newton solve (initial guess + Newton iterations until max|dh| <= tol)
+and, for workloads that have one, the backward adjoint scan.  Inputs are
+resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job throughput in timestep-channels/s, the roofline
+record of the dominant kernel (the fused Newton-iteration kernel) measured live
+with device events, and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# algorithmic bytes per timestep-channel (read u + read iterate + write iterate;
+# backward: read h, u, g + write du), storage sizes per workload
+ALGO_BYTES = {
+    "C1": {"iter": 20, "bwd": 32}, "C2": {"iter": 20, "bwd": 32}, "C3": {"iter": 32, "bwd": 48},
+    "C5": {"iter": 14, "bwd": 16},
+}
+
+
+def time_events(fn, reps):
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding or collectives are part of it); "
+                 "run with --gpus 1")
+
+    import torch
+    import paper_2510_21450_amd as P
+    from workloads import CONFIGS, make_inputs, cell_dims
+
+    torch.cuda.set_device(0)
+    w = CONFIGS[args.config]
+    G, S = cell_dims(w.cell)
+    d = make_inputs(w, device="cuda")
+    params, u, h0, g = d["params"], d["u"], d["h0"], d.get("g")
+    N = w.B * w.L * w.H
+    ws_f = torch.empty(P.workspace_bytes(w.cell, u.dtype, w.B, w.L, w.H, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(256, P.workspace_bytes(w.cell, u.dtype, w.B, w.L, w.H, True)), dtype=torch.uint8, device="cuda")
+    h_out = torch.empty((w.B, w.L, S, w.H), dtype=u.dtype, device="cuda")
+    state = {}
+
+    def step():
+        h, iters, _ = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
+        state["iters"] = iters
+        if w.backward:
+            state["grads"] = P.backward(w.cell, params, u, h0, h, g, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    iters, status = (int(x) for x in state["iters"].cpu())
+
+    # ---- per-kernel figures with device events on the launch stream
+    def fwd_fixed(m):
+        return lambda: P.forward(w.cell, params, u, h0, tol=-1.0, max_iter=m, workspace=ws_f, out=h_out)
+
+    m_lo, m_hi = 2, 10
+    for m in (m_lo, m_hi):
+        fwd_fixed(m)()
+    t_lo = time_events(fwd_fixed(m_lo), 10)
+    t_hi = time_events(fwd_fixed(m_hi), 10)
+    t_iter_ms = (sum(t_hi) / len(t_hi) - sum(t_lo) / len(t_lo)) / (m_hi - m_lo)
+    t_iter_min_ms = (min(t_hi) - min(t_lo)) / (m_hi - m_lo)
+    t_fwd = time_events(lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f,
+                                          out=h_out), 10)
+    ab = ALGO_BYTES[args.config]
+    iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9
+    detail = {"iters": iters, "status": P.status_string(status), "tol": w.tol, "max_iter": w.max_iter,
+              "t_fwd_ms": sum(t_fwd) / len(t_fwd), "t_fwd_min_ms": min(t_fwd),
+              "t_iter_ms": t_iter_ms, "t_iter_min_ms": t_iter_min_ms,
+              "iter_bytes_per_elt": ab["iter"]}
+    if w.backward:
+        h, _, _ = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
+        t_bwd = time_events(lambda: P.backward(w.cell, params, u, h0, h, g, workspace=ws_b), 10)
+        detail.update({"t_bwd_ms": sum(t_bwd) / len(t_bwd), "t_bwd_min_ms": min(t_bwd),
+                       "bwd_bytes_per_elt": ab["bwd"],
+                       "bwd_gbs": ab["bwd"] * N / (sum(t_bwd) / len(t_bwd) * 1e-3) / 1e9})
+        detail["bwd_frac_hbm"] = detail["bwd_gbs"] / HBM_PEAK_GBS
+
+    roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, d)
+
+    out = {
+        "metric": "Newton-solve timesteps*channels/s (fwd+bwd), % HBM roofline, 1 MI355X",
+        "value": N / (ms_per_step * 1e-3), "unit": "timestep-channels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.cell} {w.dtype} B={w.B} L={w.L} H={w.H} "
+                               f"{'forward+backward' if w.backward else 'forward'}",
+                   "tol": w.tol, "max_iter": w.max_iter},
+        "roofline": roofline, "cpu_baseline": cpu, "detail": detail,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, d):
+    """The CPU oracle as it stands (fp64 Newton with forward substitution +
+    adjoint recurrence), timed on the host cores on a bounded sample: the first
+    sequences of the same workload, one per host thread."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    threads = oracle.num_threads()
+    Bs = min(w.B, max(1, threads))
+    f64 = lambda t: None if t is None else t[:Bs].cpu().double().numpy()
+    params = d["params"].cpu().double().numpy()
+    u, h0 = f64(d["u"]), f64(d["h0"])
+    t0 = time.perf_counter()
+    h, it, st, _ = oracle.newton(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter)
+    t1 = time.perf_counter()
+    tb = 0.0
+    if w.backward:
+        g = f64(d["g"])
+        oracle.backward(w.cell, params, u, h0, h, g)
+        tb = time.perf_counter() - t1
+    n = Bs * w.L * w.H
+    return {"value": n / ((t1 - t0) + tb), "unit": "timestep-channels/s", "cores": min(threads, Bs),
+            "kind": "oracle", "sample": f"first {Bs} of {w.B} sequences, full L and H, fp64, "
+                                        f"{it} Newton iterations ({t1 - t0:.2f} s) + backward ({tb:.2f} s)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -75,6 +75,16 @@ const char *pararnn_status_string(int status);
 /* Library version, major*10000 + minor*100 + patch. */
 int pararnn_version(void);
 
+/* Tuning / test hook (host, process-wide, not thread-safe): force the tile
+ * shape of the scan kernels for all later calls -- vec channels per lane, ll
+ * segments along L per wave, c timesteps per thread, w waves per workgroup.
+ * Only shapes compiled into the library are accepted (else UNSUPPORTED); a
+ * call whose H or pointer alignment does not allow `vec` keeps the automatic
+ * choice.  vec = 0 restores the automatic choice.  Query workspace sizes
+ * after setting it.  The environment variable PARARNN_TILE="vec,ll,c,w" has
+ * the same effect at start-up. */
+int pararnn_set_tile(int vec, int ll, int c, int w);
+
 /* Gates G and state values S of a cell; -1 for an unknown cell. */
 int pararnn_cell_gates(int cell);
 int pararnn_cell_state(int cell);

@@ -24,6 +24,8 @@ _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_
 _lib.pararnn_status_string.restype = ctypes.c_char_p
 _lib.pararnn_status_string.argtypes = [_i]
 _lib.pararnn_version.restype = _i
+_lib.pararnn_set_tile.argtypes = [_i] * 4
+_lib.pararnn_set_tile.restype = _i
 _lib.pararnn_cell_gates.argtypes = [_i]
 _lib.pararnn_cell_state.argtypes = [_i]
 _lib.pararnn_workspace_bytes.restype = _sz
@@ -34,6 +36,11 @@ _lib.pararnn_backward.restype = _i
 _lib.pararnn_backward.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_affine_scan.restype = _i
 _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
+
+
+def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
+    """pararnn_set_tile: force a compiled tile shape (vec = 0: automatic)."""
+    _raise(_lib.pararnn_set_tile(vec, ll, c, w), "pararnn_set_tile")
 
 
 def lib_path() -> str:
@@ -113,8 +120,9 @@ def forward(cell: str, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64
     return h, iters, tr
 
 
-def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None):
-    """pararnn_backward.  Returns (dL_du, dL_dparams, dL_dh0 or None)."""
+def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None, out=None):
+    """pararnn_backward.  Returns (dL_du, dL_dparams, dL_dh0 or None); `out`
+    may hold a preallocated (dL_du, dL_dparams, dL_dh0) triple."""
     G, S = cell_dims(cell)
     B, L, Gu, H = u.shape
     dt = u.dtype
@@ -124,9 +132,16 @@ def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspac
     _check(dL_dh, "dL_dh", dt, (B, L, S, H))
     if h0 is not None:
         _check(h0, "h0", dt, (B, S, H))
-    du = torch.empty_like(u)
-    dparams = torch.empty_like(params)
-    dh0 = torch.empty((B, S, H), dtype=dt, device=u.device) if want_dh0 else None
+    if out is not None:
+        du, dparams, dh0 = out
+        _check(du, "dL_du", dt, u.shape)
+        _check(dparams, "dL_dparams", torch.float32, params.shape)
+        if dh0 is not None:
+            _check(dh0, "dL_dh0", dt, (B, S, H))
+    else:
+        du = torch.empty_like(u)
+        dparams = torch.empty_like(params)
+        dh0 = torch.empty((B, S, H), dtype=dt, device=u.device) if want_dh0 else None
     ws = _workspace(workspace_bytes(cell, dt, B, L, H, True), u.device, workspace)
     code = _lib.pararnn_backward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), _ptr(h), _ptr(dL_dh),
                                  B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))

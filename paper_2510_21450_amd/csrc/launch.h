@@ -7,13 +7,17 @@ namespace pararnn {
 
 struct TileCfg {
     int vec;  // channels per lane
+    int ll;   // segments along L inside a wave (64/ll lanes each)
     int c;    // timesteps per thread
     int w;    // waves per workgroup
 };
 
-// tile shapes compiled for every cell (C, W); T = C * W timesteps per tile
-#define PARARNN_TILE_SHAPES(X) X(4, 8) X(8, 8)
-// channels per lane compiled for every cell
+// Tile shapes compiled for every cell: X(VEC, LL, C, W).  A tile covers
+// (64/LL)*VEC channels x C*LL*W timesteps.
+#define PARARNN_SHAPES(X)                                                                       \
+    X(4, 1, 8, 8) X(4, 4, 4, 8) X(4, 4, 8, 8) X(4, 4, 8, 4) X(4, 2, 8, 8) X(4, 4, 4, 16) X(2, 4, 8, 8) \
+    X(2, 2, 8, 8) X(4, 8, 4, 8) X(1, 1, 4, 8) X(1, 8, 4, 2) X(2, 8, 8, 8) X(4, 2, 4, 16) X(2, 1, 4, 8)
+// channels per lane compiled for the element-wise kernels
 #define PARARNN_VECS(X) X(1) X(2) X(4)
 
 template <class Cell, typename UT> struct Kernels {
@@ -22,7 +26,7 @@ template <class Cell, typename UT> struct Kernels {
     static hipError_t backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st);
 };
 
-hipError_t launch_reset(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0,
+hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0,
                         hipStream_t st);
 hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t st);
 hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st);

@@ -15,11 +15,11 @@ template <typename K> static int persistent_grid(K kernel, int threads, int n_ti
 }
 
 // static LDS of the backward kernel must stay within 64 KiB
-template <class Cell, int VEC, int W> constexpr bool backward_fits_lds()
+template <class Cell, int VEC, int LL, int W> constexpr bool backward_fits_lds()
 {
     constexpr int S = Cell::S, SS = S * S, PRX = Cell::PR > 0 ? Cell::PR : 1;
     constexpr int rows = (SS + S) > PRX ? (SS + S) : PRX;
-    return (size_t)(W * rows + S) * kWave * VEC * sizeof(float) + 16 <= 65536;
+    return (size_t)(W * rows + S) * (kWave / LL) * VEC * sizeof(float) + 16 <= 65536;
 }
 
 template <class Cell, typename UT>
@@ -46,33 +46,28 @@ hipError_t Kernels<Cell, UT>::init_guess(int vec, const FwdArgs &a, hipStream_t 
 template <class Cell, typename UT>
 hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, hipStream_t st)
 {
-#define PARARNN_CASE2(V, C, W)                                                                 \
-    if (cfg.vec == V && cfg.c == C && cfg.w == W) {                                            \
+#define PARARNN_CASE(V, LLv, C, W)                                                             \
+    if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
         static int grid_cap = 0; /* per instantiation */                                       \
-        auto kern = newton_iter_kernel<Cell, V, C, W, UT>;                                     \
+        auto kern = newton_iter_kernel<Cell, V, LLv, C, W, UT>;                                \
         if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);               \
         const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                      \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
         return hipGetLastError();                                                              \
     }
-#define PARARNN_CASE_V1(C, W) PARARNN_CASE2(1, C, W)
-#define PARARNN_CASE_V2(C, W) PARARNN_CASE2(2, C, W)
-#define PARARNN_CASE_V4(C, W) PARARNN_CASE2(4, C, W)
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V1)
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V2)
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V4)
-#undef PARARNN_CASE2
+    PARARNN_SHAPES(PARARNN_CASE)
+#undef PARARNN_CASE
     return hipErrorInvalidValue;
 }
 
 template <class Cell, typename UT>
 hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st)
 {
-#define PARARNN_CASE2(V, C, W)                                                                 \
-    if (cfg.vec == V && cfg.c == C && cfg.w == W) {                                            \
-        if constexpr (backward_fits_lds<Cell, V, W>()) {                                       \
+#define PARARNN_CASE(V, LLv, C, W)                                                             \
+    if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
+        if constexpr (backward_fits_lds<Cell, V, LLv, W>()) {                                  \
             static int grid_cap = 0;                                                           \
-            auto kern = backward_kernel<Cell, V, C, W, UT>;                                    \
+            auto kern = backward_kernel<Cell, V, LLv, C, W, UT>;                               \
             if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \
             const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                  \
             hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
@@ -81,13 +76,8 @@ hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hip
             return hipErrorInvalidValue;                                                       \
         }                                                                                      \
     }
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V1)
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V2)
-    PARARNN_TILE_SHAPES(PARARNN_CASE_V4)
-#undef PARARNN_CASE2
-#undef PARARNN_CASE_V1
-#undef PARARNN_CASE_V2
-#undef PARARNN_CASE_V4
+    PARARNN_SHAPES(PARARNN_CASE)
+#undef PARARNN_CASE
     return hipErrorInvalidValue;
 }
 

@@ -29,9 +29,12 @@ bool cell_info(int cell, CellInfo *ci)
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// process-wide tile-shape override: {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
+int g_tile_override[4] = {-1, 0, 0, 0};
+
 // Tile shape for a problem: channels per lane as wide as divisibility and
 // pointer alignment allow, capped per kernel by its register footprint.
-// PARARNN_TILE="vec,c,w" overrides it (tuning aid; the combination must be one
+// PARARNN_TILE="vec,ll,c,w" overrides it (tuning aid; the combination must be one
 // that is compiled in).
 TileCfg choose_tile(int cell_kind, bool backward, int H, int align_elems)
 {
@@ -42,42 +45,47 @@ TileCfg choose_tile(int cell_kind, bool backward, int H, int align_elems)
     if (cell_kind == PARARNN_LSTM_DIAG || backward) want = 2;
     TileCfg cfg;
     cfg.vec = want < vmax ? want : vmax;
-    cfg.c = 4;
+    cfg.ll = 1;
+    cfg.c = cfg.vec == 4 ? 8 : 4;
     cfg.w = 8;
-    static int ov[3] = {-1, 0, 0};
-    if (ov[0] == -1) {
-        ov[0] = 0;
+    if (g_tile_override[0] == -1) {
+        g_tile_override[0] = 0;
         const char *e = getenv("PARARNN_TILE");
-        int v, c, w;
-        if (e && sscanf(e, "%d,%d,%d", &v, &c, &w) == 3) { ov[0] = v; ov[1] = c; ov[2] = w; }
+        int v, l, c, w;
+        if (e && sscanf(e, "%d,%d,%d,%d", &v, &l, &c, &w) == 4) {
+            g_tile_override[0] = v; g_tile_override[1] = l; g_tile_override[2] = c; g_tile_override[3] = w;
+        }
     }
-    if (ov[0] > 0 && ov[0] <= vmax) { cfg.vec = ov[0]; cfg.c = ov[1]; cfg.w = ov[2]; }
+    if (g_tile_override[0] > 0 && g_tile_override[0] <= vmax) {
+        cfg.vec = g_tile_override[0]; cfg.ll = g_tile_override[1];
+        cfg.c = g_tile_override[2]; cfg.w = g_tile_override[3];
+    }
     return cfg;
 }
 
 struct Layout {
     ScanGeom g;
     TileCfg cfg;
-    size_t off_flags, off_rec, off_bnd, off_iter, off_part, total;
+    size_t off_rec, n_rec, off_bnd, off_iter, off_part, total;
 };
 
-// Workspace: [Ctrl | flags | tile records | boundary rows | fp32 iterate (bf16 forward) |
+// Workspace: [Ctrl | carry records | boundary rows | fp32 iterate (bf16 forward) |
 // parameter-gradient partials (backward)]
 Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems)
 {
     Layout lo;
     lo.cfg = choose_tile(cell_kind, backward, H, align_elems);
-    const int CW = kWave * lo.cfg.vec, T = lo.cfg.c * lo.cfg.w;
+    const int CW = (kWave / lo.cfg.ll) * lo.cfg.vec, T = lo.cfg.c * lo.cfg.ll * lo.cfg.w;
     ScanGeom &g = lo.g;
     g.B = B; g.L = L; g.H = H; g.T = T;
     g.n_lt = (L + T - 1) / T;
     g.n_cg = (H + CW - 1) / CW;
     g.n_groups = B * g.n_cg;
     g.n_tiles = g.n_groups * g.n_lt;
-    const size_t REC = (size_t)ci.S * ci.S + 2 * ci.S;
+    const size_t NW = (size_t)ci.S * ci.S + 2 * ci.S;
     size_t off = round256(sizeof(Ctrl));
-    lo.off_flags = off; off += round256((size_t)g.n_tiles * sizeof(unsigned int));
-    lo.off_rec = off;   off += round256((size_t)g.n_tiles * REC * CW * sizeof(float));
+    lo.n_rec = (size_t)g.n_tiles * NW * CW;
+    lo.off_rec = off;   off += round256(lo.n_rec * sizeof(unsigned long long));
     lo.off_bnd = off;
     if (!backward) off += round256((size_t)2 * g.n_lt * B * ci.S * H * sizeof(float));
     lo.off_iter = off;
@@ -115,7 +123,7 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
                  int status0, int max_iter)
 {
     char *ws = reinterpret_cast<char *>(a.ctrl);
-    hipError_t e = launch_reset(a.ctrl, a.flags, (size_t)lo.g.n_tiles, a.iters_out, status0, st);
+    hipError_t e = launch_reset(a.ctrl, a.rec, lo.n_rec, a.iters_out, status0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     const bool bf = dtype == PARARNN_BF16;
     a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
@@ -136,7 +144,7 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
 template <class Cell>
 int backward_diag(const CellInfo &ci, int dtype, const Layout &lo, BwdArgs &a, hipStream_t st, float *dparams)
 {
-    hipError_t e = launch_reset(a.ctrl, a.flags, (size_t)lo.g.n_tiles, nullptr, 0, st);
+    hipError_t e = launch_reset(a.ctrl, a.rec, lo.n_rec, nullptr, 0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     e = dtype == PARARNN_BF16 ? Kernels<Cell, unsigned short>::backward(lo.cfg, a, st)
                               : Kernels<Cell, float>::backward(lo.cfg, a, st);
@@ -165,6 +173,18 @@ const char *pararnn_status_string(int status)
 }
 
 int pararnn_version(void) { return 100; }
+
+int pararnn_set_tile(int vec, int ll, int c, int w)
+{
+    if (vec == 0) { g_tile_override[0] = 0; return PARARNN_OK; }
+    bool known = false;
+#define PARARNN_CASE(V, LLv, C, W) known = known || (vec == V && ll == LLv && c == C && w == W);
+    PARARNN_SHAPES(PARARNN_CASE)
+#undef PARARNN_CASE
+    if (!known) return PARARNN_UNSUPPORTED;
+    g_tile_override[0] = vec; g_tile_override[1] = ll; g_tile_override[2] = c; g_tile_override[3] = w;
+    return PARARNN_OK;
+}
 
 int pararnn_cell_gates(int cell)
 {
@@ -221,8 +241,7 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     a.g = lo.g;
     a.params = params; a.u = u; a.h0 = h0; a.jac = nullptr;
     a.bnd = reinterpret_cast<float *>(ws + lo.off_bnd);
-    a.rec = reinterpret_cast<float *>(ws + lo.off_rec);
-    a.flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    a.rec = reinterpret_cast<unsigned long long *>(ws + lo.off_rec);
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
     a.iters_out = iters; a.trace = delta_trace;
     a.k = 0; a.max_iter = max_iter; a.tol = tol;
@@ -262,8 +281,7 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
     a.params = params; a.u = u; a.h0 = h0; a.h = h; a.gl = dL_dh; a.jac = nullptr;
     a.du = dL_du; a.dh0 = dL_dh0;
     a.part = reinterpret_cast<float *>(ws + lo.off_part);
-    a.rec = reinterpret_cast<float *>(ws + lo.off_rec);
-    a.flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    a.rec = reinterpret_cast<unsigned long long *>(ws + lo.off_rec);
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
     switch (cell) {
     case PARARNN_GRU_DIAG: return backward_diag<GruDiag>(ci, dtype, lo, a, st, dL_dparams);
@@ -286,16 +304,16 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
     if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
     Ctrl *ctrl = reinterpret_cast<Ctrl *>(ws);
-    unsigned int *flags = reinterpret_cast<unsigned int *>(ws + lo.off_flags);
+    unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_rec);
     // a device int[2] for the (unused) iteration result lives in the control block's padding
     int *scratch_iters = reinterpret_cast<int *>(&ctrl->pad[0]);
-    hipError_t e = launch_reset(ctrl, flags, (size_t)lo.g.n_tiles, nullptr, 0, st);
+    hipError_t e = launch_reset(ctrl, rec, lo.n_rec, nullptr, 0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     if (!reverse) {
         FwdArgs a;
         memset(&a, 0, sizeof(a));
         a.g = lo.g; a.u = r; a.jac = J; a.hit = delta;
-        a.rec = reinterpret_cast<float *>(ws + lo.off_rec); a.flags = flags; a.ctrl = ctrl;
+        a.rec = rec; a.ctrl = ctrl;
         a.bnd = nullptr; a.iters_out = scratch_iters; a.trace = nullptr;
         a.k = 1; a.max_iter = 1; a.tol = -1.0f;
         e = kind == 0 ? Kernels<RawScan<1>, float>::newton_iter(lo.cfg, a, st)
@@ -304,7 +322,7 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
         BwdArgs a;
         memset(&a, 0, sizeof(a));
         a.g = lo.g; a.gl = r; a.jac = J; a.du = delta; a.dh0 = nullptr; a.part = nullptr;
-        a.rec = reinterpret_cast<float *>(ws + lo.off_rec); a.flags = flags; a.ctrl = ctrl;
+        a.rec = rec; a.ctrl = ctrl;
         e = kind == 0 ? Kernels<RawScan<1>, float>::backward(lo.cfg, a, st)
                       : Kernels<RawScan<2>, float>::backward(lo.cfg, a, st);
     }

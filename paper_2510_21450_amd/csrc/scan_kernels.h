@@ -1,14 +1,18 @@
 // Fused Newton-iteration kernel and fused backward kernel for cells with a
 // diagonal (S = 1) or 2x2-block (S = 2) Jacobian.
 //
-// Work decomposition (one "tile" = CW = 64*VEC channels of one sequence x
-// T = C*W consecutive timesteps):
-//   lane   -> VEC adjacent channels (H is the contiguous axis, so a wave reads
-//             rows of 256*VEC bytes: fully coalesced, no cross-lane traffic)
-//   thread -> C consecutive timesteps, reduced sequentially in registers
-//             (thread-level forward substitution of the paper's App. D.2)
-//   wave   -> W waves of a workgroup take consecutive chunks; their chunk
-//             aggregates are combined through LDS
+// Work decomposition.  A "tile" is CW = (64/LL)*VEC channels of one sequence x
+// T = C*LL*W consecutive timesteps:
+//   lane   -> (segment, channel slot): the 64 lanes of a wave are LL segments
+//             of 64/LL lanes; a lane owns VEC adjacent channels (H is the
+//             contiguous axis, so each segment reads rows of (64/LL)*VEC*4
+//             contiguous bytes) and C consecutive timesteps, which it reduces
+//             sequentially in registers (the thread-level forward substitution
+//             of the paper's App. D.2)
+//   wave   -> the LL segments hold consecutive chunks of the same channels and
+//             are combined by a Kogge-Stone scan with cross-lane shuffles
+//   block  -> W waves take consecutive stretches; their aggregates are
+//             combined through LDS
 //   grid   -> tiles along L are chained by a decoupled look-back: a tile
 //             publishes its aggregate affine map (A, b), then walks back over
 //             its predecessors until it meets one whose inclusive value
@@ -50,8 +54,7 @@ struct FwdArgs {
     const float *jac;    // raw scans only: [B][L][S*S][H]
     float *hit;          // fp32 iterate [B][L][S][H], updated in place
     float *bnd;          // [2][n_lt][B][S][H]: iterate at each tile's last step
-    float *rec;          // tile records [n_groups][n_lt][S*S + 2S][CW]
-    unsigned int *flags; // [n_groups][n_lt]
+    unsigned long long *rec; // carry records [n_groups][n_lt][S*S + 2S][CW] of {value, tag}
     Ctrl *ctrl;
     int *iters_out;      // device int[2]
     float *trace;        // device float[max_iter] or NULL
@@ -71,8 +74,7 @@ struct BwdArgs {
     void *du;            // out [B][L][G][H]
     void *dh0;           // out [B][S][H] or NULL
     float *part;         // parameter-gradient partials [n_lt][B][PR][H]
-    float *rec;
-    unsigned int *flags;
+    unsigned long long *rec;
     Ctrl *ctrl;
 };
 
@@ -132,17 +134,45 @@ __device__ __forceinline__ void push_step(const float *J, const float *r, float 
     mat_mul<S>(J, accA, accA);
 }
 
-// Cross-workgroup carry: value entering tile `lt` of chain `grp`, obtained by
-// walking over the predecessors in direction `dir` (-1: towards l = 0, used by
-// the forward scan; +1: towards l = L, used by the reverse scan).  Called by
-// all 64 lanes of one wave; lane handles VEC channels.  Returns false when a
-// bounded wait ran out (carry is then zero).
-template <int S, int VEC>
-__device__ __forceinline__ bool lookback(const float *rec_base, const unsigned int *flags_base, int n_lt,
-                                         int grp, int lt, int dir, unsigned int epoch, int lane,
-                                         float (&carry)[S][VEC])
+// compose: (accA, accB) <- (accA, accB) o (pA, pB): the map p is applied first
+template <int S>
+__device__ __forceinline__ void compose_after(const float *pA, const float *pB, float *accA, float *accB)
 {
-    constexpr int SS = S * S, CW = kWave * VEC, REC = SS + 2 * S;
+    affine<S>(accA, pB, accB, accB);
+    mat_mul<S>(accA, pA, accA);
+}
+
+// ------------------------------------------------ cross-workgroup carry records
+// Every published float travels in its own 64-bit word {value, tag} written and
+// read with one relaxed agent-scope atomic access, so a word validates itself
+// and no fence (an L2 write-back on this chip) is needed.  tag = epoch*4+state.
+typedef unsigned long long rec_t;
+
+__device__ __forceinline__ rec_t rec_pack(float v, unsigned int tag)
+{
+    return ((rec_t)tag << 32) | (rec_t)__float_as_uint(v);
+}
+__device__ __forceinline__ void rec_store(rec_t *p, float v, unsigned int tag)
+{
+    __hip_atomic_store(p, rec_pack(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ rec_t rec_load(const rec_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Value entering tile `lt` of chain `grp`, obtained by walking over the
+// predecessors in direction `dir` (-1: towards l = 0, forward scan; +1: towards
+// l = L, reverse scan) until one with a known inclusive value is met.  Called
+// by a whole wave; lanes with active = true own VEC channels starting at
+// column `col` of the group, the others only keep the control flow uniform.
+// Returns false when the bounded wait ran out (carry is then zero).
+template <int S, int VEC, int CW>
+__device__ __forceinline__ bool lookback(const rec_t *rec_base, int n_lt, int grp, int lt, int dir,
+                                         unsigned int epoch, int col, bool active, float (&carry)[S][VEC])
+{
+    constexpr int SS = S * S, NW = SS + 2 * S;
+    const unsigned int tag_agg = epoch * 4u + kFlagAgg, tag_inc = epoch * 4u + kFlagIncl;
     float LA[VEC][SS], LB[VEC][S];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -151,77 +181,83 @@ __device__ __forceinline__ bool lookback(const float *rec_base, const unsigned i
         for (int s = 0; s < S; ++s) LB[v][s] = 0.0f;
     }
     int j = lt + dir;
+    unsigned int spins = 0;
     for (;;) {
-        const unsigned int *fj = flags_base + (size_t)grp * n_lt + j;
-        unsigned int f = 0, spins = 0;
-        for (;;) {
-            f = __builtin_amdgcn_readfirstlane(flag_load(fj));
-            if ((f >> 2) == epoch) break;
-            if (++spins >= kSpinLimit) break;
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if ((f >> 2) != epoch) {
+        const rec_t *rj = rec_base + ((size_t)grp * n_lt + j) * (NW * CW) + col;
+        // inclusive value of tile j
+        rec_t wi[S][VEC];
+        bool ok = true;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v)
+        for (int s = 0; s < S; ++s)
 #pragma unroll
-                for (int s = 0; s < S; ++s) carry[s][v] = 0.0f;
-            return false;
-        }
-        fence_acquire();
-        const float *rj = rec_base + ((size_t)grp * n_lt + j) * (REC * CW) + lane * VEC;
-        if ((f & 3u) == kFlagIncl) {
-            float inc[S][VEC];
-#pragma unroll
-            for (int s = 0; s < S; ++s) load_vec<VEC>(rj + (SS + S + s) * CW, inc[s]);
+            for (int v = 0; v < VEC; ++v) {
+                wi[s][v] = active ? rec_load(rj + (SS + S + s) * CW + v) : 0;
+                ok = ok && (unsigned int)(wi[s][v] >> 32) == tag_inc;
+            }
+        if (__all(ok || !active)) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 float x[S], y[S];
 #pragma unroll
-                for (int s = 0; s < S; ++s) x[s] = inc[s][v];
+                for (int s = 0; s < S; ++s) x[s] = __uint_as_float((unsigned int)wi[s][v]);
                 affine<S>(LA[v], x, LB[v], y);
 #pragma unroll
                 for (int s = 0; s < S; ++s) carry[s][v] = y[s];
             }
             return true;
         }
-        float Aj[SS][VEC], bj[S][VEC];
+        // aggregate of tile j
+        rec_t wa[SS + S][VEC];
+        ok = true;
 #pragma unroll
-        for (int e = 0; e < SS; ++e) load_vec<VEC>(rj + e * CW, Aj[e]);
+        for (int e = 0; e < SS + S; ++e)
 #pragma unroll
-        for (int s = 0; s < S; ++s) load_vec<VEC>(rj + (SS + s) * CW, bj[s]);
+            for (int v = 0; v < VEC; ++v) {
+                wa[e][v] = active ? rec_load(rj + e * CW + v) : 0;
+                ok = ok && (unsigned int)(wa[e][v] >> 32) == tag_agg;
+            }
+        if (__all(ok || !active)) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            float A1[SS], b1[S];
+            for (int v = 0; v < VEC; ++v) {
+                float A1[SS], b1[S];
 #pragma unroll
-            for (int e = 0; e < SS; ++e) A1[e] = Aj[e][v];
+                for (int e = 0; e < SS; ++e) A1[e] = __uint_as_float((unsigned int)wa[e][v]);
 #pragma unroll
-            for (int s = 0; s < S; ++s) b1[s] = bj[s][v];
-            affine<S>(LA[v], b1, LB[v], LB[v]);   // LB = LA b_j + LB
-            mat_mul<S>(LA[v], A1, LA[v]);         // LA = LA A_j
+                for (int s = 0; s < S; ++s) b1[s] = __uint_as_float((unsigned int)wa[SS + s][v]);
+                compose_after<S>(A1, b1, LA[v], LB[v]);
+            }
+            j += dir;
+            spins = 0;
+            if (j < 0 || j >= n_lt) {   // ran past the end of the chain: the value there is 0
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                    for (int s = 0; s < S; ++s) carry[s][v] = LB[v][s];
+                return true;
+            }
+            continue;
         }
-        j += dir;
-        if (j < 0 || j >= n_lt) {   // ran past the end of the chain: value there is 0
+        if (++spins >= kSpinLimit) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v)
 #pragma unroll
-                for (int s = 0; s < S; ++s) carry[s][v] = LB[v][s];
-            return true;
+                for (int s = 0; s < S; ++s) carry[s][v] = 0.0f;
+            return false;
         }
+        __builtin_amdgcn_s_sleep(1);
     }
 }
 
-// Publish this tile's aggregate or inclusive value.  All lanes of the wave
-// store their channels, the wave-wide release fence orders them before the
-// flag that one lane sets afterwards.
-template <int N, int VEC>
-__device__ __forceinline__ void publish(float *rec_rows, const float (&val)[N][VEC], unsigned int *flag,
-                                        unsigned int value, int lane)
+template <int N, int VEC, int CW>
+__device__ __forceinline__ void publish(rec_t *rec_rows, const float (&val)[N][VEC], unsigned int tag, int col,
+                                        bool active)
 {
-    constexpr int CW = kWave * VEC;
+    if (active) {
 #pragma unroll
-    for (int e = 0; e < N; ++e) store_vec<VEC>(rec_rows + e * CW + lane * VEC, val[e]);
-    fence_release();
-    if (lane == 0) flag_store(flag, value);
+        for (int e = 0; e < N; ++e)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) rec_store(rec_rows + e * CW + col + v, val[e][v], tag);
+    }
 }
 
 __device__ __forceinline__ float wave_nanmax(float m)
@@ -235,11 +271,11 @@ __device__ __forceinline__ float wave_nanmax(float m)
 // One Newton iteration (Alg. 1a body): residual + Jacobian (Eq. (3)), prefix
 // scan of Eq. (4), update, max|delta|, and the device-side stopping test.
 // ======================================================================
-template <class Cell, int VEC, int C, int W, typename UT>
+template <class Cell, int VEC, int LL, int C, int W, typename UT>
 __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 {
-    constexpr int S = Cell::S, G = Cell::G, SS = S * S, CW = kWave * VEC, PR = Cell::PR;
-    constexpr int REC = SS + 2 * S, T = C * W;
+    constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR;
+    constexpr int LPS = kWave / LL, CW = LPS * VEC, NW = SS + 2 * S, T = C * LL * W;
     constexpr bool kRaw = IsRaw<Cell>::value;
     __shared__ float s_A[W][SS][CW];
     __shared__ float s_b[W][S][CW];
@@ -251,6 +287,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
     if (ctrl->stop) return;
     const ScanGeom &g = a.g;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const unsigned int epoch = (unsigned int)a.k;
     const UT *u = static_cast<const UT *>(a.u);
     const int cur = a.k & 1, nxt = cur ^ 1;
@@ -264,9 +301,9 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         if (t >= (unsigned int)g.n_tiles) break;
         const int grp = (int)(t % (unsigned int)g.n_groups), lt = (int)(t / (unsigned int)g.n_groups);
         const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
-        const int ch = cg * CW + lane * VEC;
+        const int ch = cg * CW + col;
         const bool ch_ok = ch < g.H;
-        const int l0 = lt * T + w * C;
+        const int l0 = lt * T + (w * LL + seg) * C;
         const size_t seq = (size_t)b * g.L;
 
         float p[VEC][PR > 0 ? PR : 1];
@@ -312,8 +349,8 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             }
         }
         // state entering the chunk: h0, the previous tile's boundary row, or
-        // the row just before the chunk (still the old iterate: no wave of this
-        // tile stores before the barriers below)
+        // the row just before the chunk (still the old iterate: every store of
+        // this tile comes after the barriers below)
 #pragma unroll
         for (int s = 0; s < S; ++s) {
 #pragma unroll
@@ -322,7 +359,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 if (ch_ok && l0 <= g.L) {
                     if (l0 == 0) {
                         if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hprev[s]);
-                    } else if (w == 0) {
+                    } else if (w == 0 && seg == 0) {
                         load_vec<VEC>(a.bnd + ((((size_t)cur * g.n_lt + (lt - 1)) * g.B + b) * S + s) * g.H + ch, hprev[s]);
                     } else {
                         load_vec<VEC>(a.hit + ((seq + l0 - 1) * S + s) * g.H + ch, hprev[s]);
@@ -331,7 +368,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             }
         }
 
-        // ---- thread-level reduction: local prefix (PA_i, qb_i) after each step
+        // ---- thread level: local prefix (PA_i, qb_i) after each of the C steps
         float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
@@ -372,18 +409,49 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             }
         }
 
-        // ---- workgroup level: chunk aggregates through LDS
+        // ---- wave level: Kogge-Stone scan over the LL segments of the wave
+        // (lanes seg*LPS.. hold consecutive chunks of the same channels)
+        float lexA[VEC][SS], lexB[VEC][S];   // map of the segments before this one
+        if constexpr (LL > 1) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
+            for (int d = 1; d < LL; d <<= 1) {
 #pragma unroll
-            for (int e = 0; e < SS; ++e) s_A[w][e][lane * VEC + v] = accA[v][e];
+                for (int v = 0; v < VEC; ++v) {
+                    float pA[SS], pB[S];
 #pragma unroll
-            for (int s = 0; s < S; ++s) s_b[w][s][lane * VEC + v] = accB[v][s];
+                    for (int e = 0; e < SS; ++e) pA[e] = __shfl_up(accA[v][e], d * LPS, 64);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) pB[s] = __shfl_up(accB[v][s], d * LPS, 64);
+                    if (seg >= d) compose_after<S>(pA, pB, accA[v], accB[v]);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) lexA[v][e] = __shfl_up(accA[v][e], LPS, 64);
+#pragma unroll
+                for (int s = 0; s < S; ++s) lexB[v][s] = __shfl_up(accB[v][s], LPS, 64);
+                if (seg == 0) {
+                    set_identity<S>(lexA[v]);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) lexB[v][s] = 0.0f;
+                }
+            }
+        }
+
+        // ---- workgroup level: wave aggregates through LDS
+        if (seg == LL - 1) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) s_A[w][e][col + v] = accA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) s_b[w][s][col + v] = accB[v][s];
+            }
         }
         __syncthreads();
 
-        // exclusive prefix over the waves before this one (all waves), and the
-        // tile aggregate (wave 0)
+        // map of the waves before this one (all waves) / of the whole tile (wave 0)
         float exA[VEC][SS], exB[VEC][S];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
@@ -392,38 +460,31 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
         }
         const int upto = w == 0 ? W : w;
-        float tileA[SS][VEC], tileB[S][VEC];
         for (int j = 0; j < upto; ++j) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 float Aj[SS], bj[S];
 #pragma unroll
-                for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][lane * VEC + v];
+                for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
 #pragma unroll
-                for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][lane * VEC + v];
+                for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][col + v];
                 push_step<S>(Aj, bj, exA[v], exB[v]);
             }
         }
         if (w == 0) {
+            // ---- grid level: decoupled look-back along L, lanes of segment 0
+            float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
 #pragma unroll
                 for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
 #pragma unroll
-                for (int s = 0; s < S; ++s) tileB[s][v] = exB[v][s];
+                for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
                 set_identity<S>(exA[v]);
-#pragma unroll
-                for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
             }
-            // ---- grid level: decoupled look-back along L
-            float carry[S][VEC];
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) carry[s][v] = 0.0f;
+            const bool active = seg == 0;
             const bool has_next = lt + 1 < g.n_lt;
-            float *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (REC * CW);
-            unsigned int *flag = a.flags + (size_t)grp * g.n_lt + lt;
+            rec_t *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (NW * CW);
             if (lt > 0) {
                 if (has_next) {
                     float ab[SS + S][VEC];
@@ -434,9 +495,9 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
                         for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
                     }
-                    publish<SS + S, VEC>(rec, ab, flag, epoch * 4u + kFlagAgg, lane);
+                    publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
                 }
-                if (!lookback<S, VEC>(a.rec, a.flags, g.n_lt, grp, lt, -1, epoch, lane, carry))
+                if (!lookback<S, VEC, CW>(a.rec, g.n_lt, grp, lt, -1, epoch, col, active, carry))
                     internal_error = true;
             }
             if (has_next) {
@@ -452,12 +513,14 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
                     for (int s = 0; s < S; ++s) inc[s][v] = y[s];
                 }
-                publish<S, VEC>(rec + (SS + S) * CW, inc, flag, epoch * 4u + kFlagIncl, lane);
+                publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
             }
+            if (active) {
 #pragma unroll
-            for (int s = 0; s < S; ++s)
+                for (int s = 0; s < S; ++s)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) s_carry[s][lane * VEC + v] = carry[s][v];
+                    for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
+            }
         }
         __syncthreads();
 
@@ -466,8 +529,9 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         for (int v = 0; v < VEC; ++v) {
             float cin[S], din[S];
 #pragma unroll
-            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][lane * VEC + v];
+            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
             affine<S>(exA[v], cin, exB[v], din);
+            if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 float d[S];
@@ -488,7 +552,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             }
         }
         if constexpr (!kRaw) {
-            if (ch_ok && w == W - 1 && lt + 1 < g.n_lt) {
+            if (ch_ok && w == W - 1 && seg == LL - 1 && lt + 1 < g.n_lt) {
 #pragma unroll
                 for (int s = 0; s < S; ++s)
                     store_vec<VEC>(a.bnd + ((((size_t)nxt * g.n_lt + lt) * g.B + b) * S + s) * g.H + ch, ho[C - 1][s]);
@@ -598,21 +662,22 @@ __global__ __launch_bounds__(256) void init_guess_kernel(const FwdArgs a)
 // dL/dh0 = nu_1.  Parameter gradients are reduced per tile into `part`
 // and summed by param_reduce_kernel (fixed order: bit-reproducible).
 // ======================================================================
-template <class Cell, int VEC, int C, int W, typename UT>
+template <class Cell, int VEC, int LL, int C, int W, typename UT>
 __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 {
-    constexpr int S = Cell::S, G = Cell::G, SS = S * S, CW = kWave * VEC, PR = Cell::PR, NC = Cell::NC;
-    constexpr int REC = SS + 2 * S, T = C * W;
+    constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR, NC = Cell::NC;
+    constexpr int LPS = kWave / LL, CW = LPS * VEC, NW = SS + 2 * S, T = C * LL * W;
     constexpr bool kRaw = IsRaw<Cell>::value;
     constexpr int PRX = PR > 0 ? PR : 1;
     constexpr int LDSROWS = (SS + S) > PRX ? (SS + S) : PRX;
-    __shared__ float s_buf[W][LDSROWS][CW];   // chunk aggregates, then gradient partials
+    __shared__ float s_buf[W][LDSROWS][CW];   // wave aggregates, then gradient partials
     __shared__ float s_carry[S][CW];
     __shared__ unsigned int s_ticket;
 
     Ctrl *ctrl = a.ctrl;
     const ScanGeom &g = a.g;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const unsigned int epoch = 1u;
     const UT *u = static_cast<const UT *>(a.u);
     const UT *hres = static_cast<const UT *>(a.h);
@@ -628,9 +693,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
         const int grp = (int)(t % (unsigned int)g.n_groups);
         const int lt = g.n_lt - 1 - (int)(t / (unsigned int)g.n_groups);   // from the end of the sequence
         const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
-        const int ch = cg * CW + lane * VEC;
+        const int ch = cg * CW + col;
         const bool ch_ok = ch < g.H;
-        const int l0 = lt * T + w * C;
+        const int l0 = lt * T + (w * LL + seg) * C;
         const size_t seq = (size_t)b * g.L;
 
         float p[VEC][PRX];
@@ -682,7 +747,7 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             }
         }
 
-        // ---- thread-level reverse reduction.  For step i keep the map from the
+        // ---- thread level, right to left.  For step i keep the map from the
         // value entering the chunk on the right (nu_in) to lam_i:
         //     lam_i = PX_i nu_in + qx_i,   PX_i = prod_{j>i} J_j^T,  qx_i = g_i + q_{i+1}
         float PX[C][VEC][SS], qx[C][VEC][S], kk[C][VEC][NC], accA[VEC][SS], accB[VEC][S];
@@ -725,18 +790,58 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 }
             }
         }
-
-        // ---- workgroup level
+        // chunk aggregate before the wave-level scan overwrites it (nu at the chunk's first step)
+        float cA[VEC][SS], cB[VEC][S];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
 #pragma unroll
-            for (int e = 0; e < SS; ++e) s_buf[w][e][lane * VEC + v] = accA[v][e];
+            for (int e = 0; e < SS; ++e) cA[v][e] = accA[v][e];
 #pragma unroll
-            for (int s = 0; s < S; ++s) s_buf[w][SS + s][lane * VEC + v] = accB[v][s];
+            for (int s = 0; s < S; ++s) cB[v][s] = accB[v][s];
+        }
+
+        // ---- wave level: suffix scan over the segments to the right
+        float lexA[VEC][SS], lexB[VEC][S];
+        if constexpr (LL > 1) {
+#pragma unroll
+            for (int d = 1; d < LL; d <<= 1) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float pA[SS], pB[S];
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) pA[e] = __shfl_down(accA[v][e], d * LPS, 64);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) pB[s] = __shfl_down(accB[v][s], d * LPS, 64);
+                    if (seg + d < LL) compose_after<S>(pA, pB, accA[v], accB[v]);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) lexA[v][e] = __shfl_down(accA[v][e], LPS, 64);
+#pragma unroll
+                for (int s = 0; s < S; ++s) lexB[v][s] = __shfl_down(accB[v][s], LPS, 64);
+                if (seg == LL - 1) {
+                    set_identity<S>(lexA[v]);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) lexB[v][s] = 0.0f;
+                }
+            }
+        }
+
+        // ---- workgroup level
+        if (seg == 0) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) s_buf[w][e][col + v] = accA[v][e];
+#pragma unroll
+                for (int s = 0; s < S; ++s) s_buf[w][SS + s][col + v] = accB[v][s];
+            }
         }
         __syncthreads();
-        // exclusive suffix over the waves after this one; wave W-1 also forms
-        // the tile aggregate and runs the look-forward
+        // map of the waves after this one; wave W-1 also forms the tile
+        // aggregate and runs the look-forward
         float exA[VEC][SS], exB[VEC][S];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
@@ -750,9 +855,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             for (int v = 0; v < VEC; ++v) {
                 float Aj[SS], bj[S];
 #pragma unroll
-                for (int e = 0; e < SS; ++e) Aj[e] = s_buf[j][e][lane * VEC + v];
+                for (int e = 0; e < SS; ++e) Aj[e] = s_buf[j][e][col + v];
 #pragma unroll
-                for (int s = 0; s < S; ++s) bj[s] = s_buf[j][SS + s][lane * VEC + v];
+                for (int s = 0; s < S; ++s) bj[s] = s_buf[j][SS + s][col + v];
                 push_step<S>(Aj, bj, exA[v], exB[v]);
             }
         }
@@ -766,9 +871,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
                 set_identity<S>(exA[v]);
             }
+            const bool active = seg == 0;
             const bool has_next = lt > 0;            // a tile to the left will ask
-            float *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (REC * CW);
-            unsigned int *flag = a.flags + (size_t)grp * g.n_lt + lt;
+            rec_t *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (NW * CW);
             if (lt + 1 < g.n_lt) {
                 if (has_next) {
                     float ab[SS + S][VEC];
@@ -779,9 +884,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
                         for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
                     }
-                    publish<SS + S, VEC>(rec, ab, flag, epoch * 4u + kFlagAgg, lane);
+                    publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
                 }
-                if (!lookback<S, VEC>(a.rec, a.flags, g.n_lt, grp, lt, +1, epoch, lane, carry))
+                if (!lookback<S, VEC, CW>(a.rec, g.n_lt, grp, lt, +1, epoch, col, active, carry))
                     internal_error = true;
             }
             if (has_next) {
@@ -797,12 +902,14 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
                     for (int s = 0; s < S; ++s) inc[s][v] = y[s];
                 }
-                publish<S, VEC>(rec + (SS + S) * CW, inc, flag, epoch * 4u + kFlagIncl, lane);
+                publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
             }
+            if (active) {
 #pragma unroll
-            for (int s = 0; s < S; ++s)
+                for (int s = 0; s < S; ++s)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) s_carry[s][lane * VEC + v] = carry[s][v];
+                    for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
+            }
         }
         __syncthreads();
 
@@ -819,8 +926,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
         for (int v = 0; v < VEC; ++v) {
             float cin[S], nin[S];
 #pragma unroll
-            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][lane * VEC + v];
-            affine<S>(exA[v], cin, exB[v], nin);      // nu entering this chunk from the right
+            for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
+            affine<S>(exA[v], cin, exB[v], nin);      // nu entering this wave from the right
+            if constexpr (LL > 1) affine<S>(lexA[v], nin, lexB[v], nin);   // ... entering this chunk
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 float lam[S], d1[G];
@@ -836,7 +944,7 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             }
             // nu at the chunk's first step (dL/dh0 when that step is l = 0)
             float n0[S];
-            affine<S>(accA[v], nin, accB[v], n0);
+            affine<S>(cA[v], nin, cB[v], n0);
 #pragma unroll
             for (int s = 0; s < S; ++s) nu0[s][v] = n0[s];
         }
@@ -854,13 +962,22 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 store_vec<VEC>(static_cast<UT *>(a.dh0) + ((size_t)b * S + s) * g.H + ch, nu0[s]);
         }
         if constexpr (PR > 0) {
-            __syncthreads();   // aggregates in s_buf are no longer needed
+            // sum the accumulators over the segments of the wave, then over the waves
+            if constexpr (LL > 1) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v)
+                for (int d = LL / 2; d >= 1; d >>= 1)
 #pragma unroll
-                for (int r = 0; r < PR; ++r) s_buf[w][r][lane * VEC + v] = acc[v][r];
+                    for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                        for (int r = 0; r < PR; ++r) acc[v][r] += __shfl_down(acc[v][r], d * LPS, 64);
+            }
+            if (seg == 0) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                    for (int r = 0; r < PR; ++r) s_buf[w][r][col + v] = acc[v][r];
+            }
             __syncthreads();
-            // W*PR*CW values -> PR*CW sums, spread over all threads of the workgroup
             for (int idx = threadIdx.x; idx < PR * CW; idx += kWave * W) {
                 const int r = idx / CW, c = idx - r * CW;
                 float s = 0.0f;

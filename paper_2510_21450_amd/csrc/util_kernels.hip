@@ -3,9 +3,10 @@
 
 namespace pararnn {
 
-// Clears the control block and the tile flags of a call, and sets the result
-// of a solve that performs no iteration.
-__global__ void reset_kernel(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0)
+// Clears the control block and the carry records of a call (their tags must
+// not survive from an earlier call), and sets the result of a solve that
+// performs no iteration.
+__global__ void reset_kernel(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) {
@@ -13,7 +14,7 @@ __global__ void reset_kernel(Ctrl *ctrl, unsigned int *flags, size_t n_flags, in
         ctrl->stop = 0; ctrl->iters = 0; ctrl->status = status0;
         if (iters_out) { iters_out[0] = 0; iters_out[1] = status0; }
     }
-    for (size_t j = i; j < n_flags; j += (size_t)gridDim.x * blockDim.x) flags[j] = 0u;
+    for (size_t j = i; j < n_rec; j += (size_t)gridDim.x * blockDim.x) rec[j] = 0ull;
 }
 
 // bf16 storage: round the converged fp32 iterate once into the output.
@@ -45,13 +46,13 @@ __global__ __launch_bounds__(256) void param_reduce_kernel(const float *part, fl
 
 namespace pararnn {
 
-hipError_t launch_reset(Ctrl *ctrl, unsigned int *flags, size_t n_flags, int *iters_out, int status0,
+hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0,
                         hipStream_t st)
 {
-    size_t blocks = (n_flags + 255) / 256;
+    size_t blocks = (n_rec + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ctrl, flags, n_flags, iters_out,
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ctrl, rec, n_rec, iters_out,
                        status0);
     return hipGetLastError();
 }
