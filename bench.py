@@ -109,6 +109,13 @@ def main():
                        "bwd_gbs": ab["bwd"] * N / (sum(t_bwd) / len(t_bwd) * 1e-3) / 1e9})
         detail["bwd_frac_hbm"] = detail["bwd_gbs"] / HBM_PEAK_GBS
 
+    # a plain copy of known size, as the reference for hardware byte counters
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    t_copy = time_events(lambda: dst.copy_(src), 5)
+    detail["copy_1GiB_gbs"] = 2 * src.numel() * 4 / (min(t_copy) * 1e-3) / 1e9
+    del src, dst
+
     roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": None}
 

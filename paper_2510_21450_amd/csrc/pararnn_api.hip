@@ -41,13 +41,20 @@ TileCfg choose_tile(int cell_kind, bool backward, int H, int align_elems)
     int vmax = 1;
     if (H % 4 == 0 && align_elems >= 4) vmax = 4;
     else if (H % 2 == 0 && align_elems >= 2) vmax = 2;
+    // widest vector the register budget of the kernel allows
     int want = 4;
-    if (cell_kind == PARARNN_LSTM_DIAG || backward) want = 2;
+    if (cell_kind == PARARNN_LSTM_DIAG) want = 2;
     TileCfg cfg;
     cfg.vec = want < vmax ? want : vmax;
-    cfg.ll = 1;
-    cfg.c = cfg.vec == 4 ? 8 : 4;
-    cfg.w = 8;
+    if (cfg.vec == 4) {
+        // 64 channels x 256 steps (forward), 32 channels x 256 steps (backward)
+        cfg.ll = backward ? 8 : 4; cfg.c = backward ? 4 : 8; cfg.w = 8;
+    } else if (cfg.vec == 2) {
+        cfg.ll = 4; cfg.c = 8; cfg.w = 8;     // 32 channels x 256 steps
+    } else {
+        cfg.ll = 1; cfg.c = 4; cfg.w = 8;     // 64 channels x 32 steps
+    }
+    if (cfg.vec == 1 && H <= 8) { cfg.ll = 8; cfg.c = 4; cfg.w = 2; }   // 8 channels x 64 steps
     if (g_tile_override[0] == -1) {
         g_tile_override[0] = 0;
         const char *e = getenv("PARARNN_TILE");

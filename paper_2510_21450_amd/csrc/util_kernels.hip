@@ -32,14 +32,34 @@ __global__ void store_bf16_tail_kernel(const float *src, unsigned short *dst, in
     if ((int)threadIdx.x < n) dst[threadIdx.x] = f32_to_bf16(src[threadIdx.x]);
 }
 
-// dL/dparams[r][ch] = sum over (lt, b) of part[lt][b][r][ch], in index order.
-__global__ __launch_bounds__(256) void param_reduce_kernel(const float *part, float *out, int n_terms, int n_out)
+// dL/dparams[i] = sum over the n_terms (tile, sequence) partials part[t][i].
+// A block owns 64 outputs; its 16 slices of 64 threads sum interleaved terms
+// with independent accumulators, then the slices are added in a fixed order,
+// so the result does not depend on scheduling.
+__global__ __launch_bounds__(1024) void param_reduce_kernel(const float *part, float *out, int n_terms, int n_out)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_out) return;
-    float s = 0.0f;
-    for (int t = 0; t < n_terms; ++t) s += part[(size_t)t * n_out + i];
-    out[i] = s;
+    __shared__ float s_sum[16][64];
+    const int o = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + o;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    if (i < n_out) {
+        int t = slice;
+        for (; t + 48 < n_terms; t += 64) {
+            a0 += part[(size_t)t * n_out + i];
+            a1 += part[(size_t)(t + 16) * n_out + i];
+            a2 += part[(size_t)(t + 32) * n_out + i];
+            a3 += part[(size_t)(t + 48) * n_out + i];
+        }
+        for (; t < n_terms; t += 16) a0 += part[(size_t)t * n_out + i];
+    }
+    s_sum[slice][o] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (slice == 0 && i < n_out) {
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) s += s_sum[k][o];
+        out[i] = s;
+    }
 }
 
 }  // namespace pararnn
@@ -77,7 +97,7 @@ hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t 
 
 hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st)
 {
-    hipLaunchKernelGGL(param_reduce_kernel, dim3((n_out + 255) / 256), dim3(256), 0, st, part, out, n_terms, n_out);
+    hipLaunchKernelGGL(param_reduce_kernel, dim3((n_out + 63) / 64), dim3(1024), 0, st, part, out, n_terms, n_out);
     return hipGetLastError();
 }
 

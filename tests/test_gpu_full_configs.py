@@ -1,0 +1,93 @@
+"""Full-size benchmark workloads (BASELINE configs 2, 3, 5) in the launch
+configuration bench.py times: inputs are generated on the GPU, the library runs
+on all of them, and a sample of channels (all sequences, all timesteps) is
+copied to the host and recomputed by the CPU oracle.  The diagonal cells'
+channels are independent (Sec. 3, Eq. (9)), so the oracle can compute a sampled
+channel on its own.  Iteration counts are compared with the oracle's stored
+full-size traces (tests/golden/newton_traces.json)."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
+N_SAMPLE = 48
+
+
+def relerr(got, ref):
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def f64(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+def expected_iters(trace, tol):
+    for k, m in enumerate(trace, start=1):
+        if m <= tol:
+            return k
+    return None
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C5"])
+def test_full_size_config(name, oracle_mod):
+    import paper_2510_21450_amd as P
+    w = CONFIGS[name]
+    bound = 2e-2 if w.dtype == "bf16" else 1e-5
+    print(f"config {name}: generating inputs", flush=True)
+    d = make_inputs(w, device="cuda")
+    params, u, h0, g = d["params"], d["u"], d["h0"], d["g"]
+    print(f"config {name}: forward", flush=True)
+    h, iters, tr = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    assert st == 0, P.status_string(st)
+    print(f"config {name}: backward (iters={it})", flush=True)
+    du, dp, dh0 = P.backward(w.cell, params, u, h0, h, g)
+    torch.cuda.synchronize()
+
+    # ---- iteration count against the oracle's full-size trace
+    with open(GOLDEN) as f:
+        gold = json.load(f)[name]
+    assert (gold["B"], gold["L"], gold["H"], gold["seed"]) == (w.B, w.L, w.H, w.seed)
+    want = expected_iters(gold["f32"], w.tol)
+    assert want is not None and want == expected_iters(gold["f64"], w.tol)
+    assert it == want, (it, want, tr.cpu().numpy()[:it], gold["f32"])
+    got_tr = tr.cpu().numpy()[:it]
+    # well above the fp32 floor the per-iteration maxima agree with the oracle's
+    for k in range(it):
+        if gold["f64"][k] > 1e-3:
+            assert abs(got_tr[k] - gold["f64"][k]) <= 2e-3 * gold["f64"][k], (k, got_tr, gold["f64"])
+
+    # ---- sampled channels against the oracle
+    rng = np.random.default_rng(w.seed)
+    chans = np.sort(rng.choice(w.H, size=N_SAMPLE, replace=False))
+    # always include the first and last channel of the tensor and a tile edge
+    chans[0], chans[-1] = 0, w.H - 1
+    chans = np.unique(np.concatenate([chans, [63, 64]]))
+    idx = torch.as_tensor(chans, device="cuda")
+    pn = f64(params.index_select(-1, idx))
+    un = f64(u.index_select(-1, idx))
+    h0n = None if h0 is None else f64(h0.index_select(-1, idx))
+    gn = f64(g.index_select(-1, idx))
+    hn = f64(h.index_select(-1, idx))
+    print(f"config {name}: oracle on {len(chans)} channels", flush=True)
+    ref = oracle_mod.seq_unroll(w.cell, pn, un, h0n)
+    e_h = relerr(hn, ref)
+    rdu, rdp, rdh0 = oracle_mod.backward(w.cell, pn, un, h0n, hn, gn)
+    e_du = relerr(f64(du.index_select(-1, idx)), rdu)
+    e_dp = relerr(f64(dp.index_select(-1, idx)), rdp)
+    e_dh0 = relerr(f64(dh0.index_select(-1, idx)), rdh0)
+    print(f"config {name}: iters={it} rel err h={e_h:.2e} du={e_du:.2e} dparams={e_dp:.2e} dh0={e_dh0:.2e}", flush=True)
+    assert e_h <= bound and e_du <= bound and e_dp <= bound and e_dh0 <= bound
+    # properties that hold at any size: bounded state, finite outputs everywhere
+    hh = h[:, :, -1, :] if w.cell == "lstm_diag" else h
+    assert float(hh.abs().max()) <= 1.0
+    assert bool(torch.isfinite(du).all()) and bool(torch.isfinite(dp).all())

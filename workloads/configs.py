@@ -52,7 +52,7 @@ CONFIGS = {
     "C2": Workload("C2", "gru_diag", "f32", 16, 4096, 1024, 1e-5, 64, True, BASE_SEED + 1),
     "C3": Workload("C3", "lstm_diag", "f32", 8, 2048, 2048, 2e-5, 64, True, BASE_SEED + 2),
     "C4": Workload("C4", "tanh_dense", "f32", 64, 1024, 64, 1e-3, 32, False, BASE_SEED + 3),
-    "C5": Workload("C5", "gru_diag", "bf16", 4, 65536, 4096, 1e-5, 64, True, BASE_SEED + 4,
+    "C5": Workload("C5", "gru_diag", "bf16", 4, 65536, 4096, 2e-5, 64, True, BASE_SEED + 4,
                    h0_std=0.1),
 }
 
