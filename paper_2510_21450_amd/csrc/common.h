@@ -21,7 +21,7 @@ struct Ctrl {
 // status values mirrored from pararnn.h (device code does not include it)
 constexpr int kStOk = 0, kStNotConverged = 1, kStNonFinite = 5, kStInternal = 7;
 
-// Tile flag protocol of the cross-workgroup carry: flag = epoch * 4 + state.
+// States of a carry record's tag (tag = epoch * 4 + state).
 constexpr unsigned int kFlagAgg = 1;   // tile aggregate (A, b) published
 constexpr unsigned int kFlagIncl = 2;  // inclusive value (delta at the tile's end) published
 // polls of one predecessor before a tile gives up (reports kStInternal, uses a
@@ -91,6 +91,40 @@ __device__ __forceinline__ void store_vec(unsigned short *p, const float (&in)[V
     *reinterpret_cast<typename VecH<VEC>::type *>(p) = v;
 }
 
+// Raw (unconverted) vectors of VEC storage elements: loads are kept in this
+// form and widened only where they are used, so that a batch of loads can be
+// in flight together.
+template <typename T, int VEC> struct RawVec;
+template <int VEC> struct RawVec<float, VEC> { using type = typename VecF<VEC>::type; };
+template <int VEC> struct RawVec<unsigned short, VEC> { using type = typename VecH<VEC>::type; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ typename RawVec<T, VEC>::type load_raw(const T *p)
+{
+    return *reinterpret_cast<const typename RawVec<T, VEC>::type *>(p);
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ typename RawVec<T, VEC>::type zero_raw()
+{
+    typename RawVec<T, VEC>::type z;
+    unsigned char *b = reinterpret_cast<unsigned char *>(&z);
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(z); ++i) b[i] = 0;
+    return z;
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void raw_to_float(const typename RawVec<T, VEC>::type &r, float (&out)[VEC])
+{
+    const T *e = reinterpret_cast<const T *>(&r);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        if constexpr (sizeof(T) == 4) out[i] = e[i];
+        else out[i] = bf16_to_f32(e[i]);
+    }
+}
+
 // ------------------------------------------------------------------- fast math
 // v_exp_f32 / v_rcp_f32 (1 ulp each).  Saturation is exact: exp2 -> 0 or inf,
 // rcp(inf) = 0.
@@ -107,17 +141,5 @@ __device__ __forceinline__ float fast_tanh(float x)
 
 // max that keeps a NaN once seen (fmaxf would drop it)
 __device__ __forceinline__ float nanmax(float m, float a) { return (a > m || a != a) ? a : m; }
-
-// --------------------------------------------------- agent-scope flag accesses
-__device__ __forceinline__ unsigned int flag_load(const unsigned int *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void flag_store(unsigned int *p, unsigned int v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
-__device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
 }  // namespace pararnn

@@ -25,6 +25,8 @@
 // Nothing but u, the iterate and the new iterate crosses HBM per Newton
 // iteration: residual, Jacobian, scan, update and max|delta| are fused.
 #pragma once
+#include <type_traits>
+
 #include "cells.h"
 
 namespace pararnn {
@@ -319,35 +321,46 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             }
         }
 
-        // ---- loads: u and the old iterate for the C steps of this thread
-        float uu[C][G][VEC], ho[C][S][VEC], jr[kRaw ? C : 1][kRaw ? SS : 1][VEC], hprev[S][VEC];
+        // ---- loads: u and the old iterate for the C steps of this thread, kept
+        // raw so that all of them are in flight together; tiles that lie fully
+        // inside the tensor take the unguarded path
+        using RawU = typename RawVec<UT, VEC>::type;
+        using RawF = typename RawVec<float, VEC>::type;
+        RawU uur[C][G];
+        RawF hor[C][S], jrr[kRaw ? C : 1][kRaw ? SS : 1];
+        float hprev[S][VEC];
+        const bool full_tile = (lt + 1) * T <= g.L && (cg + 1) * CW <= g.H;
+        auto load_inputs = [&](auto guard) {
+            constexpr bool kGuard = decltype(guard)::value;
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const int l = l0 + i;
-            const bool ok = ch_ok && l < g.L;
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                const bool ok = !kGuard || (ch_ok && l < g.L);
 #pragma unroll
-            for (int q = 0; q < G; ++q) {
+                for (int q = 0; q < G; ++q) {
+                    if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
+                    else uur[i][q] = zero_raw<UT, VEC>();
+                }
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) uu[i][q][v] = 0.0f;
-                if (ok) load_vec<VEC>(u + ((seq + l) * G + q) * g.H + ch, uu[i][q]);
-            }
+                for (int s = 0; s < S; ++s) {
+                    if constexpr (!kRaw) {
+                        if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
+                        else hor[i][s] = zero_raw<float, VEC>();
+                    } else {
+                        hor[i][s] = zero_raw<float, VEC>();
+                    }
+                }
+                if constexpr (kRaw) {
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) ho[i][s][v] = 0.0f;
-                if constexpr (!kRaw) {
-                    if (ok) load_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                    for (int e = 0; e < SS; ++e) {
+                        if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
+                        else jrr[i][e] = zero_raw<float, VEC>();
+                    }
                 }
             }
-            if constexpr (kRaw) {
-#pragma unroll
-                for (int e = 0; e < SS; ++e) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) jr[i][e][v] = 0.0f;
-                    if (ok) load_vec<VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch, jr[i][e]);
-                }
-            }
-        }
+        };
+        if (full_tile) load_inputs(std::false_type{});
+        else load_inputs(std::true_type{});
         // state entering the chunk: h0, the previous tile's boundary row, or
         // the row just before the chunk (still the old iterate: every store of
         // this tile comes after the barriers below)
@@ -370,6 +383,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 
         // ---- thread level: local prefix (PA_i, qb_i) after each of the C steps
         float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
+        float uu[C][G][VEC], ho[C][S][VEC], jr[kRaw ? C : 1][kRaw ? SS : 1][VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             set_identity<S>(accA[v]);
@@ -378,6 +392,14 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         }
 #pragma unroll
         for (int i = 0; i < C; ++i) {
+#pragma unroll
+            for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu[i][q]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) raw_to_float<float, VEC>(hor[i][s], ho[i][s]);
+            if constexpr (kRaw) {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) raw_to_float<float, VEC>(jrr[i][e], jr[i][e]);
+            }
             if (l0 + i < g.L) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -711,41 +733,49 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             }
         }
 
-        // ---- loads: u_l, h_{l-1}, g_l for the C steps of this thread
-        float uu[C][G][VEC], hp[C][S][VEC], gg[C][S][VEC], jr[kRaw ? C : 1][kRaw ? SS : 1][VEC];
+        // ---- loads: u_l, h_{l-1}, g_l for the C steps of this thread (raw, all
+        // in flight together; unguarded for tiles fully inside the tensor)
+        using RawU = typename RawVec<UT, VEC>::type;
+        using RawF = typename RawVec<float, VEC>::type;
+        RawU uur[kRaw ? 1 : C][kRaw ? 1 : G], hpr[C][S], ggr[C][S];
+        RawF jrr[kRaw ? C : 1][kRaw ? SS : 1];
+        const bool full_tile = (lt + 1) * T <= g.L && (cg + 1) * CW <= g.H;
+        auto load_inputs = [&](auto guard) {
+            constexpr bool kGuard = decltype(guard)::value;
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const int l = l0 + i;
-            const bool ok = ch_ok && l < g.L;
-            if constexpr (!kRaw) {
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                const bool ok = !kGuard || (ch_ok && l < g.L);
+                if constexpr (!kRaw) {
 #pragma unroll
-                for (int q = 0; q < G; ++q) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) uu[i][q][v] = 0.0f;
-                    if (ok) load_vec<VEC>(u + ((seq + l) * G + q) * g.H + ch, uu[i][q]);
+                    for (int q = 0; q < G; ++q) {
+                        if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
+                        else uur[i][q] = zero_raw<UT, VEC>();
+                    }
                 }
-            }
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) { hp[i][s][v] = 0.0f; gg[i][s][v] = 0.0f; }
-                if (ok) {
-                    load_vec<VEC>(gl + ((seq + l) * S + s) * g.H + ch, gg[i][s]);
+                for (int s = 0; s < S; ++s) {
+                    if (ok) ggr[i][s] = load_raw<UT, VEC>(gl + ((seq + l) * S + s) * g.H + ch);
+                    else ggr[i][s] = zero_raw<UT, VEC>();
+                    hpr[i][s] = zero_raw<UT, VEC>();
                     if constexpr (!kRaw) {
-                        if (l > 0) load_vec<VEC>(hres + ((seq + l - 1) * S + s) * g.H + ch, hp[i][s]);
-                        else if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hp[i][s]);
+                        if (ok) {
+                            if (l > 0) hpr[i][s] = load_raw<UT, VEC>(hres + ((seq + l - 1) * S + s) * g.H + ch);
+                            else if (a.h0) hpr[i][s] = load_raw<UT, VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch);
+                        }
+                    }
+                }
+                if constexpr (kRaw) {
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) {
+                        if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
+                        else jrr[i][e] = zero_raw<float, VEC>();
                     }
                 }
             }
-            if constexpr (kRaw) {
-#pragma unroll
-                for (int e = 0; e < SS; ++e) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) jr[i][e][v] = 0.0f;
-                    if (ok) load_vec<VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch, jr[i][e]);
-                }
-            }
-        }
+        };
+        if (full_tile) load_inputs(std::false_type{});
+        else load_inputs(std::true_type{});
 
         // ---- thread level, right to left.  For step i keep the map from the
         // value entering the chunk on the right (nu_in) to lam_i:
@@ -759,12 +789,25 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
         }
 #pragma unroll
         for (int i = C - 1; i >= 0; --i) {
+            float uu1[G][VEC], hp1[S][VEC], gg1[S][VEC], jr1[kRaw ? SS : 1][VEC];
+            if constexpr (!kRaw) {
+#pragma unroll
+                for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu1[q]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < SS; ++e) raw_to_float<float, VEC>(jrr[i][e], jr1[e]);
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                raw_to_float<UT, VEC>(hpr[i][s], hp1[s]);
+                raw_to_float<UT, VEC>(ggr[i][s], gg1[s]);
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
 #pragma unroll
                 for (int e = 0; e < SS; ++e) PX[i][v][e] = accA[v][e];
 #pragma unroll
-                for (int s = 0; s < S; ++s) qx[i][v][s] = accB[v][s] + gg[i][s][v];
+                for (int s = 0; s < S; ++s) qx[i][v][s] = accB[v][s] + gg1[s][v];
             }
             if (l0 + i < g.L) {
 #pragma unroll
@@ -772,13 +815,13 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                     float J[SS], zero[S];
                     if constexpr (kRaw) {
 #pragma unroll
-                        for (int e = 0; e < SS; ++e) J[e] = jr[i][e][v];
+                        for (int e = 0; e < SS; ++e) J[e] = jr1[e][v];
                     } else {
                         float h1[S], ug[G];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) h1[s] = hp[i][s][v];
+                        for (int s = 0; s < S; ++s) h1[s] = hp1[s][v];
 #pragma unroll
-                        for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                        for (int q = 0; q < G; ++q) ug[q] = uu1[q][v];
                         Cell::bwd_prep(p[v], h1, ug, J, kk[i][v]);
                     }
                     transpose_inplace<S>(J);
