@@ -1,0 +1,99 @@
+"""GPU parity of the dense-Jacobian path (h' = tanh(W h + u), H = 64): the MFMA
+scan against the CPU oracle, including BASELINE config 4 at full size."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, make_inputs      # noqa: E402
+from workloads.rng import normal                 # noqa: E402
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
+
+
+def relerr(got, ref):
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def f64(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 16), (2, 17), (3, 50), (33, 100), (5, 257), (64, 32)])
+@pytest.mark.parametrize("with_h0", [False, True])
+def test_dense_small(oracle_mod, shape, with_h0):
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    print(f"dense B={B} L={L} h0={with_h0}", flush=True)
+    W = normal(900 + L, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(900 + L, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(900 + L, 3, (B, 1, H), std=0.3, device="cuda") if with_h0 else None
+    Wn, un, h0n = f64(W), f64(u), f64(h0)
+    ref = oracle_mod.seq_unroll("tanh_dense", Wn, un, h0n)
+    # fixed iteration counts: iterate k matches the oracle's iterate k
+    for k in (0, 1, 2):
+        h, iters, _ = P.forward("tanh_dense", W, u, h0, tol=-1.0, max_iter=k)
+        hk, _, _, _ = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=-1.0, max_iter=k)
+        assert tuple(int(x) for x in iters.cpu()) == (k, 0)
+        assert relerr(f64(h), hk) <= 2e-5, k
+    tol = 1e-4
+    h, iters, tr = P.forward("tanh_dense", W, u, h0, tol=tol, max_iter=32, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    assert st == 0
+    assert relerr(f64(h), ref) <= 1e-5
+    _, it32, _, tr32 = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=32, precision="f32")
+    _, it64, _, tr64 = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=32, precision="f64")
+    clear = it32 == it64 and all(t[-1] <= tol / 4 and (len(t) < 2 or t[-2] >= 4 * tol) for t in (tr32, tr64))
+    if clear:
+        assert it == it32
+    else:
+        assert abs(it - it32) <= 1
+
+
+def test_dense_zero_weights_is_tanh_of_input(oracle_mod):
+    import paper_2510_21450_amd as P
+    B, L, H = 2, 40, 64
+    W = torch.zeros(H, H, device="cuda")
+    u = normal(5, 1, (B, L, 1, H), device="cuda")
+    h, iters, tr = P.forward("tanh_dense", W, u, None, tol=1e-6, max_iter=8, trace=True)
+    assert tuple(int(x) for x in iters.cpu()) == (1, 0)          # guess exact, one confirming solve
+    assert relerr(f64(h), np.tanh(f64(u))) <= 1e-6
+
+
+def test_dense_unsupported_shapes_are_refused():
+    import paper_2510_21450_amd as P
+    W = torch.zeros(32, 32, device="cuda")
+    u = torch.zeros(1, 4, 1, 32, device="cuda")
+    with pytest.raises(RuntimeError, match="UNSUPPORTED"):
+        P.forward("tanh_dense", W, u, None)
+
+
+def test_config_c4_full_size(oracle_mod):
+    """BASELINE config 4: B=64, L=1024, H=64, max_iter 32, forward."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C4"]
+    d = make_inputs(w, device="cuda")
+    h, iters, tr = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=w.max_iter, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    assert st == 0
+    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), None)
+    e = relerr(f64(h), ref)
+    with open(GOLDEN) as f:
+        gold = json.load(f)["C4"]
+    want = next(k for k, m in enumerate(gold["f32"], start=1) if m <= w.tol)
+    assert want == next(k for k, m in enumerate(gold["f64"], start=1) if m <= w.tol)
+    print(f"C4: iters={it} (oracle {want}) rel err h={e:.2e} trace={tr.cpu().numpy()[:it]}", flush=True)
+    assert it == want
+    assert e <= 1e-5
+    got = tr.cpu().numpy()[:it]
+    for k in range(it):
+        if gold["f64"][k] > 1e-3:
+            assert abs(got[k] - gold["f64"][k]) <= 2e-3 * gold["f64"][k]
