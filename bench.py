@@ -19,12 +19,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak, published
 # algorithmic bytes per timestep-channel (read u + read iterate + write iterate;
 # backward: read h, u, g + write du), storage sizes per workload
 ALGO_BYTES = {
     "C1": {"iter": 20, "bwd": 32}, "C2": {"iter": 20, "bwd": 32}, "C3": {"iter": 32, "bwd": 48},
     "C5": {"iter": 14, "bwd": 16},
 }
+DENSE_CHUNK = 16               # timesteps per chunk of the dense scan (csrc/dense_kernels.hip)
 
 
 def time_events(fn, reps):
@@ -38,12 +40,32 @@ def time_events(fn, reps):
     return [a.elapsed_time(b) for a, b in evs]
 
 
+def kernel_time_ms(fn, name_part):
+    """Average duration of the kernels whose name contains name_part while fn
+    runs, from the device-side timestamps torch's profiler collects (roctracer);
+    None when the profiler is unavailable."""
+    import torch
+    try:
+        from torch.profiler import profile, ProfilerActivity
+        fn()
+        torch.cuda.synchronize()
+        with profile(activities=[ProfilerActivity.CUDA]) as prof:
+            fn()
+            torch.cuda.synchronize()
+        durs = [e.device_time_total if hasattr(e, "device_time_total") else e.cuda_time_total
+                for e in prof.events() if name_part in e.name]
+        durs = [x for x in durs if x > 0]
+        return (sum(durs) / len(durs)) * 1e-3 if durs else None
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,13 +117,29 @@ def main():
     t_iter_min_ms = (min(t_hi) - min(t_lo)) / (m_hi - m_lo)
     t_fwd = time_events(lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f,
                                           out=h_out), 10)
-    ab = ALGO_BYTES[args.config]
-    iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9
     detail = {"iters": iters, "status": P.status_string(status), "tol": w.tol, "max_iter": w.max_iter,
               "t_fwd_ms": sum(t_fwd) / len(t_fwd), "t_fwd_min_ms": min(t_fwd),
-              "t_iter_ms": t_iter_ms, "t_iter_min_ms": t_iter_min_ms,
-              "iter_bytes_per_elt": ab["iter"]}
+              "t_iter_ms": t_iter_ms, "t_iter_min_ms": t_iter_min_ms}
+    if w.cell == "tanh_dense":
+        # the scan composes one 64x64 Jacobian product (2 H^3 flop) per timestep
+        flops_iter = 2.0 * w.H ** 3 * w.B * w.L
+        n_c = (w.L + DENSE_CHUNK - 1) // DENSE_CHUNK
+        flops_kernel = 2.0 * w.H ** 3 * w.B * max(0, n_c - 2) * (DENSE_CHUNK - 1)
+        detail["iter_tflops"] = flops_iter / (t_iter_ms * 1e-3) / 1e12
+        detail["iter_frac_mfma"] = detail["iter_tflops"] / MFMA_F32_PEAK_TFLOPS
+        t_k = kernel_time_ms(lambda: P.forward(w.cell, params, u, h0, tol=-1.0, max_iter=4, workspace=ws_f, out=h_out),
+                             "dense_chunk_products")
+        ach = flops_kernel / (t_k * 1e-3) / 1e12 if t_k else None
+        detail["chunk_products_ms"] = t_k
+        roofline = {"bound": "mfma", "kernel": "dense_chunk_products_kernel", "achieved": ach,
+                    "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_F32_PEAK_TFLOPS if ach else None, "traffic": None}
+    else:
+        ab = ALGO_BYTES[args.config]
+        iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9
+        detail["iter_bytes_per_elt"] = ab["iter"]
     if w.backward:
+        ab = ALGO_BYTES[args.config]
         h, _, _ = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
         t_bwd = time_events(lambda: P.backward(w.cell, params, u, h0, h, g, workspace=ws_b), 10)
         detail.update({"t_bwd_ms": sum(t_bwd) / len(t_bwd), "t_bwd_min_ms": min(t_bwd),
@@ -116,8 +154,9 @@ def main():
     detail["copy_1GiB_gbs"] = 2 * src.numel() * 4 / (min(t_copy) * 1e-3) / 1e9
     del src, dst
 
-    roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": None}
+    if w.cell != "tanh_dense":
+        roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": None}
 
     cpu = None
     if not args.no_cpu_baseline:

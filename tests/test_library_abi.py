@@ -1,0 +1,112 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every function include/pararnn.h declares, and its host logic (status
+strings, cell tables, workspace sizes, tile-shape hook, argument validation
+that happens before any device work) behaves as the header says."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pararnn.h")
+LIB = os.path.join(ROOT, "paper_2510_21450_amd", "libpararnn.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2510_21450_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(pararnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for must in ("pararnn_forward", "pararnn_backward", "pararnn_workspace_bytes", "pararnn_affine_scan"):
+        assert must in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in pararnn.h but not exported"
+
+
+def test_status_strings_and_cell_tables(lib):
+    lib.pararnn_status_string.restype = ctypes.c_char_p
+    want = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR",
+            5: "NONFINITE", 6: "UNSUPPORTED", 7: "INTERNAL", 99: "UNKNOWN"}
+    for code, s in want.items():
+        assert lib.pararnn_status_string(code).decode() == s
+    assert lib.pararnn_version() >= 100
+    assert [(lib.pararnn_cell_gates(c), lib.pararnn_cell_state(c)) for c in range(4)] == [(3, 1), (4, 2), (1, 1), (1, 1)]
+    assert lib.pararnn_cell_gates(7) == -1 and lib.pararnn_cell_state(-1) == -1
+
+
+def test_workspace_bytes(lib):
+    ws = lib.pararnn_workspace_bytes
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [ctypes.c_int] * 6
+    # invalid requests give 0
+    assert ws(9, 0, 1, 1, 1, 0) == 0 and ws(0, 5, 1, 1, 1, 0) == 0 and ws(0, 0, 0, 8, 8, 0) == 0
+    assert ws(0, 0, 4, -1, 8, 0) == 0
+    small = ws(0, 0, 1, 64, 8, 0)
+    assert small >= 256 and small % 256 == 0
+    # grows with the problem; bf16 forward also holds the fp32 iterate
+    f32 = ws(0, 0, 16, 4096, 1024, 0)
+    bf = ws(0, 1, 16, 4096, 1024, 0)
+    assert f32 > small and bf >= f32 + 16 * 4096 * 1024 * 4
+    # the fp32 workspace is small next to the tensors (u alone is 805 MB)
+    assert f32 < 128 << 20
+    # backward workspace holds the per-tile parameter-gradient partials
+    assert ws(0, 0, 16, 4096, 1024, 1) > 0
+    # dense path: d, r, chunk products
+    assert ws(2, 0, 64, 1024, 64, 0) >= 2 * 64 * 1024 * 64 * 4 + 64 * 64 * 64 * 64 * 4
+
+
+def test_tile_hook(lib):
+    st = lib.pararnn_set_tile
+    assert st(4, 4, 8, 8) == 0          # a compiled shape
+    assert st(3, 1, 8, 8) == 6          # UNSUPPORTED
+    assert st(4, 4, 8, 7) == 6
+    assert st(0, 0, 0, 0) == 0          # back to automatic
+
+
+def test_host_side_argument_validation(lib):
+    """These requests are refused before any device call is made."""
+    f = lib.pararnn_forward
+    f.restype = ctypes.c_int
+    vp, i, fl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    f.argtypes = [i, i, vp, vp, vp, i, i, i, fl, i, vp, vp, vp, vp, sz, vp]
+    p = 0x1000  # any aligned non-null address: it is never dereferenced on these paths
+    INVALID = 2
+    assert f(9, 0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == INVALID      # cell
+    assert f(0, 3, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == INVALID      # dtype
+    assert f(0, 0, p, p, None, 0, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == INVALID      # B = 0
+    assert f(0, 0, p, p, None, 1, 8, 8, 1e-6, -1, p, p, None, p, 1 << 20, None) == INVALID     # max_iter
+    assert f(0, 0, None, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == INVALID   # params NULL
+    assert f(0, 0, p, p, None, 1, 8, 8, float("nan"), 4, p, p, None, p, 1 << 20, None) == INVALID
+    assert f(0, 0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p + 8, 1 << 20, None) == INVALID  # workspace alignment
+    assert f(0, 0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 16, None) == 3                 # WORKSPACE_TOO_SMALL
+    b = lib.pararnn_backward
+    b.restype = ctypes.c_int
+    b.argtypes = [i, i, vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, sz, vp]
+    assert b(0, 0, p, p, None, p, None, 1, 8, 8, p, p, None, p, 1 << 20, None) == INVALID      # dL_dh NULL
+    assert b(2, 0, p, p, None, p, p, 1, 8, 64, p, p, None, p, 1 << 20, None) == 6              # dense backward
+    s = lib.pararnn_affine_scan
+    s.restype = ctypes.c_int
+    s.argtypes = [i, i, vp, vp, i, i, i, vp, vp, sz, vp]
+    assert s(2, 0, p, p, 1, 8, 8, p, p, 1 << 20, None) == INVALID
+    assert s(0, 0, p, p, 1, 8, 8, p, p, 16, None) == 3
+
+
+def test_python_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2510_21450_amd as P
+    with pytest.raises(ValueError, match="CUDA"):
+        P.forward("gru_diag", torch.zeros(2, 3, 8), torch.zeros(1, 4, 3, 8))
