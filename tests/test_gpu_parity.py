@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle on
 identical seeded inputs.  fp32 results must agree to 1e-5 (norm-wise max
-relative error), bf16-storage results to 2e-2, iteration counts
-exactly."""
+relative error: max|x - ref| / max|ref| per tensor), bf16-storage results to
+2e-2, iteration counts exactly."""
 import json
 import os
 
