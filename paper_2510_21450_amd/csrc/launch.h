@@ -22,7 +22,8 @@ struct TileCfg {
 
 template <class Cell, typename UT> struct Kernels {
     static hipError_t init_guess(int vec, const FwdArgs &a, hipStream_t st);
-    static hipError_t newton_iter(const TileCfg &cfg, const FwdArgs &a, hipStream_t st);
+    // fold_guess: this is iteration 1 and the initial guess is computed inside it
+    static hipError_t newton_iter(const TileCfg &cfg, const FwdArgs &a, bool fold_guess, hipStream_t st);
     static hipError_t backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st);
 };
 

@@ -44,14 +44,19 @@ hipError_t Kernels<Cell, UT>::init_guess(int vec, const FwdArgs &a, hipStream_t 
 }
 
 template <class Cell, typename UT>
-hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, hipStream_t st)
+hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, bool fold_guess, hipStream_t st)
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
-        static int grid_cap = 0; /* per instantiation */                                       \
-        auto kern = newton_iter_kernel<Cell, V, LLv, C, W, UT>;                                \
-        if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);               \
-        const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                      \
+        static int grid_cap[2] = {0, 0}; /* per instantiation */                               \
+        constexpr bool kFoldGuess = !IsRaw<Cell>::value;                                       \
+        const int first = (kFoldGuess && fold_guess) ? 1 : 0;                                  \
+        auto kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, false>;                         \
+        if constexpr (kFoldGuess) {                                                            \
+            if (first) kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, true>;                \
+        }                                                                                      \
+        if (grid_cap[first] == 0) grid_cap[first] = persistent_grid(kern, kWave * W, 1 << 30); \
+        const int grid = a.g.n_tiles < grid_cap[first] ? a.g.n_tiles : grid_cap[first];        \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
         return hipGetLastError();                                                              \
     }

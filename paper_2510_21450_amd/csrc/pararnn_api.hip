@@ -134,11 +134,15 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     const bool bf = dtype == PARARNN_BF16;
     a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
-    e = bf ? Kernels<Cell, unsigned short>::init_guess(lo.cfg.vec, a, st) : Kernels<Cell, float>::init_guess(lo.cfg.vec, a, st);
-    if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    if (max_iter == 0) {
+        // only the initial guess is asked for; otherwise iteration 1 computes it on the fly
+        e = bf ? Kernels<Cell, unsigned short>::init_guess(lo.cfg.vec, a, st) : Kernels<Cell, float>::init_guess(lo.cfg.vec, a, st);
+        if (e != hipSuccess) return PARARNN_HIP_ERROR;
+    }
     for (int k = 1; k <= max_iter; ++k) {
         a.k = k;
-        e = bf ? Kernels<Cell, unsigned short>::newton_iter(lo.cfg, a, st) : Kernels<Cell, float>::newton_iter(lo.cfg, a, st);
+        e = bf ? Kernels<Cell, unsigned short>::newton_iter(lo.cfg, a, k == 1, st)
+               : Kernels<Cell, float>::newton_iter(lo.cfg, a, k == 1, st);
         if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
     }
     if (bf) {
@@ -323,8 +327,8 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
         a.rec = rec; a.ctrl = ctrl;
         a.bnd = nullptr; a.iters_out = scratch_iters; a.trace = nullptr;
         a.k = 1; a.max_iter = 1; a.tol = -1.0f;
-        e = kind == 0 ? Kernels<RawScan<1>, float>::newton_iter(lo.cfg, a, st)
-                      : Kernels<RawScan<2>, float>::newton_iter(lo.cfg, a, st);
+        e = kind == 0 ? Kernels<RawScan<1>, float>::newton_iter(lo.cfg, a, false, st)
+                      : Kernels<RawScan<2>, float>::newton_iter(lo.cfg, a, false, st);
     } else {
         BwdArgs a;
         memset(&a, 0, sizeof(a));

@@ -273,7 +273,11 @@ __device__ __forceinline__ float wave_nanmax(float m)
 // One Newton iteration (Alg. 1a body): residual + Jacobian (Eq. (3)), prefix
 // scan of Eq. (4), update, max|delta|, and the device-side stopping test.
 // ======================================================================
-template <class Cell, int VEC, int LL, int C, int W, typename UT>
+// FIRST = true is iteration 1 with the initial guess folded in: the old iterate
+// h^0_l = f(h0, u_l) (App. A) is computed from u on the fly instead of being read
+// (one extra row of u per chunk supplies h^0_{l0-1}), so no separate pass
+// writes and re-reads the guess.
+template <class Cell, int VEC, int LL, int C, int W, typename UT, bool FIRST>
 __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 {
     constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR;
@@ -326,8 +330,8 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         // inside the tensor take the unguarded path
         using RawU = typename RawVec<UT, VEC>::type;
         using RawF = typename RawVec<float, VEC>::type;
-        RawU uur[C][G];
-        RawF hor[C][S], jrr[kRaw ? C : 1][kRaw ? SS : 1];
+        RawU uur[C][G], uhalo[FIRST ? G : 1];
+        RawF hor[FIRST ? 1 : C][S], jrr[kRaw ? C : 1][kRaw ? SS : 1];
         float hprev[S][VEC];
         const bool full_tile = (lt + 1) * T <= g.L && (cg + 1) * CW <= g.H;
         auto load_inputs = [&](auto guard) {
@@ -341,13 +345,15 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                     if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
                     else uur[i][q] = zero_raw<UT, VEC>();
                 }
+                if constexpr (!FIRST) {
 #pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if constexpr (!kRaw) {
-                        if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
-                        else hor[i][s] = zero_raw<float, VEC>();
-                    } else {
-                        hor[i][s] = zero_raw<float, VEC>();
+                    for (int s = 0; s < S; ++s) {
+                        if constexpr (!kRaw) {
+                            if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
+                            else hor[i][s] = zero_raw<float, VEC>();
+                        } else {
+                            hor[i][s] = zero_raw<float, VEC>();
+                        }
                     }
                 }
                 if constexpr (kRaw) {
@@ -361,6 +367,13 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         };
         if (full_tile) load_inputs(std::false_type{});
         else load_inputs(std::true_type{});
+        if constexpr (FIRST) {
+#pragma unroll
+            for (int q = 0; q < G; ++q) {
+                uhalo[q] = zero_raw<UT, VEC>();
+                if (ch_ok && l0 > 0 && l0 <= g.L) uhalo[q] = load_raw<UT, VEC>(u + ((seq + l0 - 1) * G + q) * g.H + ch);
+            }
+        }
         // state entering the chunk: h0, the previous tile's boundary row, or
         // the row just before the chunk (still the old iterate: every store of
         // this tile comes after the barriers below)
@@ -368,7 +381,9 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         for (int s = 0; s < S; ++s) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) hprev[s][v] = 0.0f;
-            if constexpr (!kRaw) {
+            if constexpr (FIRST) {
+                if (ch_ok && a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hprev[s]);
+            } else if constexpr (!kRaw) {
                 if (ch_ok && l0 <= g.L) {
                     if (l0 == 0) {
                         if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, hprev[s]);
@@ -390,12 +405,52 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
             for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
         }
+        float h0v[FIRST ? S : 1][VEC];
+        if constexpr (FIRST) {
+            // hprev holds h0 here; the state entering the chunk is the guess of
+            // the row before it, f(h0, u_{l0-1}), or h0 itself at the sequence start
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) h0v[s][v] = hprev[s][v];
+            if (l0 > 0) {
+                float uh[G][VEC];
+#pragma unroll
+                for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uhalo[q], uh[q]);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float h1[S], ug[G], F0[S];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
+#pragma unroll
+                    for (int q = 0; q < G; ++q) ug[q] = uh[q][v];
+                    Cell::step(p[v], h1, ug, F0);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) hprev[s][v] = F0[s];
+                }
+            }
+        }
 #pragma unroll
         for (int i = 0; i < C; ++i) {
 #pragma unroll
             for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu[i][q]);
+            if constexpr (FIRST) {
+                // old iterate = initial guess h^0_l = f(h0, u_l)
 #pragma unroll
-            for (int s = 0; s < S; ++s) raw_to_float<float, VEC>(hor[i][s], ho[i][s]);
+                for (int v = 0; v < VEC; ++v) {
+                    float h1[S], ug[G], F0[S];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
+#pragma unroll
+                    for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                    Cell::step(p[v], h1, ug, F0);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) ho[i][s][v] = F0[s];
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < S; ++s) raw_to_float<float, VEC>(hor[i][s], ho[i][s]);
+            }
             if constexpr (kRaw) {
 #pragma unroll
                 for (int e = 0; e < SS; ++e) raw_to_float<float, VEC>(jrr[i][e], jr[i][e]);
