@@ -13,10 +13,12 @@ struct TileCfg {
 };
 
 // Tile shapes compiled for every cell: X(VEC, LL, C, W).  A tile covers
-// (64/LL)*VEC channels x C*LL*W timesteps.
+// (64/LL)*VEC channels x C*LL*W timesteps.  Measured on MI355X the narrow
+// shapes (one or two channels per lane: few registers, many resident waves)
+// beat wide vector loads; the automatic choice is in pararnn_api.hip.
 #define PARARNN_SHAPES(X)                                                                       \
-    X(4, 1, 8, 8) X(4, 4, 4, 8) X(4, 4, 8, 8) X(4, 4, 8, 4) X(4, 2, 8, 8) X(4, 4, 4, 16) X(2, 4, 8, 8) \
-    X(2, 2, 8, 8) X(4, 8, 4, 8) X(1, 1, 4, 8) X(1, 8, 4, 2) X(2, 8, 8, 8) X(4, 2, 4, 16) X(2, 1, 4, 8)
+    X(1, 1, 8, 16) X(1, 2, 8, 16) X(1, 2, 16, 4) X(1, 2, 8, 8) X(1, 1, 8, 8) X(2, 2, 8, 8)            \
+    X(1, 1, 4, 8) X(1, 8, 4, 2) X(4, 4, 8, 8) X(2, 4, 8, 8)
 // channels per lane compiled for the element-wise kernels
 #define PARARNN_VECS(X) X(1) X(2) X(4)
 

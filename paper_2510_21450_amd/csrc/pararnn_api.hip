@@ -32,29 +32,32 @@ size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 // process-wide tile-shape override: {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
 int g_tile_override[4] = {-1, 0, 0, 0};
 
-// Tile shape for a problem: channels per lane as wide as divisibility and
-// pointer alignment allow, capped per kernel by its register footprint.
-// PARARNN_TILE="vec,ll,c,w" overrides it (tuning aid; the combination must be one
-// that is compiled in).
-TileCfg choose_tile(int cell_kind, bool backward, int H, int align_elems)
+// Tile shape for a problem.  The table is the result of sweeps on MI355X over
+// the compiled shapes (fp32 and bf16 storage, forward and backward, GRU and
+// LSTM at 2^25..2^30 timestep-channels): one channel per lane (two for bf16
+// forward) with 128..256-byte row segments and 128..256 steps per tile.
+// PARARNN_TILE="vec,ll,c,w" or pararnn_set_tile() overrides it (tuning aid; the
+// combination must be one that is compiled in and allowed by H and alignment).
+TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_elems)
 {
     int vmax = 1;
     if (H % 4 == 0 && align_elems >= 4) vmax = 4;
     else if (H % 2 == 0 && align_elems >= 2) vmax = 2;
-    // widest vector the register budget of the kernel allows
-    int want = 4;
-    if (cell_kind == PARARNN_LSTM_DIAG) want = 2;
-    TileCfg cfg;
-    cfg.vec = want < vmax ? want : vmax;
-    if (cfg.vec == 4) {
-        // 64 channels x 256 steps (forward), 32 channels x 256 steps (backward)
-        cfg.ll = backward ? 8 : 4; cfg.c = backward ? 4 : 8; cfg.w = 8;
-    } else if (cfg.vec == 2) {
-        cfg.ll = 4; cfg.c = 8; cfg.w = 8;     // 32 channels x 256 steps
+    TileCfg cfg = {1, 2, 8, 8};                          // 32 channels x 128 steps
+    const bool lstm = cell_kind == PARARNN_LSTM_DIAG, bf = dtype == PARARNN_BF16;
+    if (H <= 8) {
+        cfg = {1, 8, 4, 2};                              // 8 channels x 64 steps
+    } else if (H <= 32) {
+        cfg = {1, 2, 8, 8};
+    } else if (!backward) {
+        if (lstm) cfg = {1, 2, 16, 4};                   // 32 channels x 128 steps
+        else if (bf && vmax >= 2) cfg = {2, 2, 8, 8};    // 64 channels x 128 steps
+        else cfg = {1, 1, 8, 16};                        // 64 channels x 128 steps
     } else {
-        cfg.ll = 1; cfg.c = 4; cfg.w = 8;     // 64 channels x 32 steps
+        if (lstm) cfg = {1, 2, 8, 8};
+        else if (bf) cfg = {1, 1, 8, 8};                 // 64 channels x 64 steps
+        else cfg = {1, 2, 8, 16};                        // 32 channels x 256 steps
     }
-    if (cfg.vec == 1 && H <= 8) { cfg.ll = 8; cfg.c = 4; cfg.w = 2; }   // 8 channels x 64 steps
     if (g_tile_override[0] == -1) {
         g_tile_override[0] = 0;
         const char *e = getenv("PARARNN_TILE");
@@ -81,7 +84,7 @@ struct Layout {
 Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems)
 {
     Layout lo;
-    lo.cfg = choose_tile(cell_kind, backward, H, align_elems);
+    lo.cfg = choose_tile(cell_kind, dtype, backward, H, align_elems);
     const int CW = (kWave / lo.cfg.ll) * lo.cfg.vec, T = lo.cfg.c * lo.cfg.ll * lo.cfg.w;
     ScanGeom &g = lo.g;
     g.B = B; g.L = L; g.H = H; g.T = T;

@@ -74,6 +74,7 @@ def test_tile_hook(lib):
     assert st(4, 4, 8, 8) == 0          # a compiled shape
     assert st(3, 1, 8, 8) == 6          # UNSUPPORTED
     assert st(4, 4, 8, 7) == 6
+    assert st(1, 1, 8, 16) == 0
     assert st(0, 0, 0, 0) == 0          # back to automatic
 
 
