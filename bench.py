@@ -26,7 +26,6 @@ ALGO_BYTES = {
     "C1": {"iter": 20, "bwd": 32}, "C2": {"iter": 20, "bwd": 32}, "C3": {"iter": 32, "bwd": 48},
     "C5": {"iter": 14, "bwd": 16},
 }
-DENSE_CHUNK = 16               # timesteps per chunk of the dense scan (csrc/dense_kernels.hip)
 
 
 def time_events(fn, reps):
@@ -38,26 +37,6 @@ def time_events(fn, reps):
         b.record()
     torch.cuda.synchronize()
     return [a.elapsed_time(b) for a, b in evs]
-
-
-def kernel_time_ms(fn, name_part):
-    """Average duration of the kernels whose name contains name_part while fn
-    runs, from the device-side timestamps torch's profiler collects (roctracer);
-    None when the profiler is unavailable."""
-    import torch
-    try:
-        from torch.profiler import profile, ProfilerActivity
-        fn()
-        torch.cuda.synchronize()
-        with profile(activities=[ProfilerActivity.CUDA]) as prof:
-            fn()
-            torch.cuda.synchronize()
-        durs = [e.device_time_total if hasattr(e, "device_time_total") else e.cuda_time_total
-                for e in prof.events() if name_part in e.name]
-        durs = [x for x in durs if x > 0]
-        return (sum(durs) / len(durs)) * 1e-3 if durs else None
-    except Exception:
-        return None
 
 
 def main():
@@ -123,17 +102,23 @@ def main():
     if w.cell == "tanh_dense":
         # the scan composes one 64x64 Jacobian product (2 H^3 flop) per timestep
         flops_iter = 2.0 * w.H ** 3 * w.B * w.L
-        n_c = (w.L + DENSE_CHUNK - 1) // DENSE_CHUNK
-        flops_kernel = 2.0 * w.H ** 3 * w.B * max(0, n_c - 2) * (DENSE_CHUNK - 1)
+        chunk = P.dense_chunk()
+        n_c = (w.L + chunk - 1) // chunk
+        flops_kernel = 2.0 * w.H ** 3 * w.B * max(0, n_c - 2) * (chunk - 1)
         detail["iter_tflops"] = flops_iter / (t_iter_ms * 1e-3) / 1e12
         detail["iter_frac_mfma"] = detail["iter_tflops"] / MFMA_F32_PEAK_TFLOPS
-        t_k = kernel_time_ms(lambda: P.forward(w.cell, params, u, h0, tol=-1.0, max_iter=4, workspace=ws_f, out=h_out),
-                             "dense_chunk_products")
-        ach = flops_kernel / (t_k * 1e-3) / 1e12 if t_k else None
+        # the composition kernel alone, same launch as inside the solve, on Jacobian factors of the same
+        # distribution (d = 1 - tanh^2 of the converged states)
+        dfac = (1.0 - h_out.view(w.B, w.L, w.H) ** 2).contiguous()
+        Aout = torch.zeros((w.B, n_c, w.H, w.H), dtype=torch.float32, device="cuda")
+        P.dense_chunk_products(params, dfac, out=Aout)
+        t_ks = time_events(lambda: P.dense_chunk_products(params, dfac, out=Aout), 20)
+        t_k = sum(t_ks) / len(t_ks)
+        ach = flops_kernel / (t_k * 1e-3) / 1e12
         detail["chunk_products_ms"] = t_k
         roofline = {"bound": "mfma", "kernel": "dense_chunk_products_kernel", "achieved": ach,
                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_F32_PEAK_TFLOPS if ach else None, "traffic": None}
+                    "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
     else:
         ab = ALGO_BYTES[args.config]
         iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9

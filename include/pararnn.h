@@ -157,6 +157,20 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
 int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, int B, int L, int H,
                         float *delta, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The composition kernel of the dense scan on its own (testing / profiling):
+ * the products of Jacobians J_l = diag(d_l) W that Alg. 1b's update of A
+ * performs, taken over chunks of pararnn_dense_chunk() consecutive timesteps,
+ *     A[b][c] = J_e ... J_{s+1} J_s,   s = c*chunk, e = min(L, s+chunk) - 1,
+ * on the matrix cores.  W [H][H] row-major, d [B][L][H], A out
+ * [B][ceil(L/chunk)][H][H] row-major; only the chunks c = 1 .. n_c-2 that the
+ * scan uses are written.  fp32, H = 64 (else UNSUPPORTED).  workspace: 256
+ * bytes of device memory, 256-byte aligned.
+ */
+int pararnn_dense_chunk(void);
+int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,6 +34,8 @@ _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_backward.restype = _i
 _lib.pararnn_backward.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.pararnn_dense_chunk_products.restype = _i
+_lib.pararnn_dense_chunk_products.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.pararnn_affine_scan.restype = _i
 _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
 
@@ -41,6 +43,24 @@ _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz
 def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
     """pararnn_set_tile: force a compiled tile shape (vec = 0: automatic)."""
     _raise(_lib.pararnn_set_tile(vec, ll, c, w), "pararnn_set_tile")
+
+
+def dense_chunk() -> int:
+    return _lib.pararnn_dense_chunk()
+
+
+def dense_chunk_products(W, d, out=None, stream=None):
+    """pararnn_dense_chunk_products.  W [H][H], d [B][L][H] -> A [B][n_c][H][H]
+    (chunks 1 .. n_c-2 written, the rest zero)."""
+    B, L, H = d.shape
+    _check(W, "W", torch.float32, (H, H))
+    _check(d, "d", torch.float32)
+    n_c = (L + dense_chunk() - 1) // dense_chunk()
+    A = torch.zeros((B, n_c, H, H), dtype=torch.float32, device=d.device) if out is None else out
+    ws = torch.empty(256, dtype=torch.uint8, device=d.device)
+    code = _lib.pararnn_dense_chunk_products(_ptr(W), _ptr(d), B, L, H, _ptr(A), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, "pararnn_dense_chunk_products")
+    return A
 
 
 def lib_path() -> str:

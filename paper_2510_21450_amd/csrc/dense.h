@@ -10,4 +10,11 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
                   int max_iter, void *h, int *iters, float *delta_trace, void *workspace, size_t workspace_bytes,
                   hipStream_t st);
 
+// Timesteps per chunk of the dense scan, and its composition kernel alone:
+// A[b][c] = J_e ... J_s, J_l = diag(d_l) W, for the chunks 1 .. n_c-2 (the ones the
+// scan needs); ctrl_scratch is 256 bytes of device memory.
+int dense_chunk();
+int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
+                         hipStream_t st);
+
 }  // namespace pararnn

@@ -23,6 +23,10 @@
 #include "dense.h"
 #include "launch.h"
 
+#include <string.h>
+
+#include <type_traits>
+
 namespace pararnn {
 
 namespace {
@@ -64,35 +68,70 @@ __device__ __forceinline__ void load_w_operand(const float *W, int lane, float (
 }
 
 // ---------------------------------------------------------------- residual
-// One wave per block of rows (b, l); lane = channel.  mode 0: write d and r
-// for the current iterate; mode 1: write the initial guess h = tanh(W h0 + u).
+// F = tanh(W h_{l-1} + u_l) for 32 consecutive rows (b, l) per wave as one MFMA
+// product W [h_{l-1} rows]; lane = row, registers = channels (accumulator
+// layout), so every access is a float4 inside a 256-byte row.
+// mode 0: write d = 1 - F^2 and r = F - h for the current iterate;
+// mode 1: write the initial guess h = tanh(W h0 + u) (App. A).
 __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
 {
     if (a.ctrl->stop) return;
-    const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int n_waves = gridDim.x * 4;
-    float wrow[DH];
-#pragma unroll
-    for (int j = 0; j < DH; j += 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(a.W + lane * DH + j);
-        wrow[j] = t.x; wrow[j + 1] = t.y; wrow[j + 2] = t.z; wrow[j + 3] = t.w;
-    }
+    const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
     const size_t rows = (size_t)a.B * a.L;
-    for (size_t row = wave; row < rows; row += n_waves) {
-        const int l = (int)(row % a.L), b = (int)(row / a.L);
-        float hp = 0.0f;
-        if (mode == 1 || l == 0) { if (a.h0) hp = a.h0[(size_t)b * DH + lane]; }
-        else hp = a.h[(row - 1) * DH + lane];
-        float s = a.u[row * DH + lane];
+    const size_t n_items = (rows + 31) / 32;
+    float wr[2][2][16];
+    load_w_operand(a.W, lane, wr);
+    for (size_t item = wave; item < n_items; item += n_waves) {
+        const size_t row = item * 32 + n;
+        const bool ok = row < rows;
+        const int l = ok ? (int)(row % a.L) : 0;
+        const size_t b = ok ? row / a.L : 0;
+        // previous state of this row: h0 (or zero) at l = 0 and for the guess, else the row before
+        const float *hp = nullptr;
+        if (ok) {
+            if (mode == 1 || l == 0) hp = a.h0 ? a.h0 + b * DH : nullptr;
+            else hp = a.h + (row - 1) * DH;
+        }
+        f16v X[2], Y[2];
 #pragma unroll
-        for (int j = 0; j < DH; ++j) s = fmaf(wrow[j], __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(hp), j)), s);
-        const float F = fast_tanh(s);
-        if (mode == 1) {
-            a.h[row * DH + lane] = F;
-        } else {
-            a.d[row * DH + lane] = fmaf(-F, F, 1.0f);
-            a.r[row * DH + lane] = F - a.h[row * DH + lane];
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (hp) t = *reinterpret_cast<const float4 *>(hp + 32 * kt + 8 * g + 4 * half);
+                X[kt][4 * g] = t.x; X[kt][4 * g + 1] = t.y; X[kt][4 * g + 2] = t.z; X[kt][4 * g + 3] = t.w;
+            }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Y[mt][v] = 0.0f;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                Y[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[0][kt][v], X[kt][v], Y[0], 0, 0, 0);
+                Y[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[1][kt][v], X[kt][v], Y[1], 0, 0, 0);
+            }
+        if (ok) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const size_t off = row * DH + 32 * mt + 8 * g + 4 * half;
+                    const float4 uv = *reinterpret_cast<const float4 *>(a.u + off);
+                    float4 F;
+                    F.x = fast_tanh(Y[mt][4 * g] + uv.x); F.y = fast_tanh(Y[mt][4 * g + 1] + uv.y);
+                    F.z = fast_tanh(Y[mt][4 * g + 2] + uv.z); F.w = fast_tanh(Y[mt][4 * g + 3] + uv.w);
+                    if (mode == 1) {
+                        *reinterpret_cast<float4 *>(a.h + off) = F;
+                    } else {
+                        const float4 hv = *reinterpret_cast<const float4 *>(a.h + off);
+                        *reinterpret_cast<float4 *>(a.d + off) =
+                            make_float4(fmaf(-F.x, F.x, 1.0f), fmaf(-F.y, F.y, 1.0f), fmaf(-F.z, F.z, 1.0f), fmaf(-F.w, F.w, 1.0f));
+                        *reinterpret_cast<float4 *>(a.r + off) = make_float4(F.x - hv.x, F.y - hv.y, F.z - hv.z, F.w - hv.w);
+                    }
+                }
         }
     }
 }
@@ -126,9 +165,21 @@ __global__ __launch_bounds__(256) void dense_chunk_products_kernel(const DenseAr
             P[mt][0][v] = dv * a.W[row * DH + n];
             P[mt][1][v] = dv * a.W[row * DH + 32 + n];
         }
-    for (int l = ls + 1; l < le; ++l) {
-        dl += DH;
-        const float d0 = dl[n], d1 = dl[32 + n];
+    // the row factors d_l of all later steps up front, so that the product loop never waits on memory
+    float dpre[CD][2];
+#pragma unroll
+    for (int i = 1; i < CD; ++i) {
+        const bool ok = ls + i < le;
+        dpre[i][0] = ok ? dl[i * DH + n] : 0.0f;
+        dpre[i][1] = ok ? dl[i * DH + 32 + n] : 0.0f;
+    }
+#pragma unroll 1
+    for (int i = 1; i < CD; ++i) {
+        if (ls + i >= le) break;
+        float d0 = 0.0f, d1 = 0.0f;
+#pragma unroll
+        for (int q = 1; q < CD; ++q)
+            if (q == i) { d0 = dpre[q][0]; d1 = dpre[q][1]; }
         f16v Q[2][2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -206,6 +257,7 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
         const int c = item / n_bt, bt = item - c * n_bt;
         const int b = bt * 32 + n;
         const bool b_ok = b < a.B;
+        const bool full = bt * 32 + 32 <= a.B;          // wave-uniform: no guards needed in the loop
         const int ls = c * CD, le = min(a.L, ls + CD);
         float wr[2][2][16];
         load_w_operand(a.W, lane, wr);
@@ -224,42 +276,70 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
                     X[kt][4 * g] = t.x; X[kt][4 * g + 1] = t.y; X[kt][4 * g + 2] = t.z; X[kt][4 * g + 3] = t.w;
                 }
         }
-        for (int l = ls; l < le; ++l) {
-            const size_t off = b_ok ? ((size_t)b * a.L + l) * DH : 0;
-            f16v Y[2];
+        // rows of an invalid lane are read from sequence B-1 (valid memory) and
+        // multiplied by zero; only stores are guarded, and only in ragged tiles
+        const size_t brow = (size_t)(b_ok ? b : a.B - 1) * a.L;
+        const float keep = b_ok ? 1.0f : 0.0f;
+        auto sweep = [&](auto guard) {
+            constexpr bool kGuard = decltype(guard)::value;
+            // d, r (and h) of the next step are fetched before the products of
+            // this step are issued, so their latency hides behind the MFMAs
+            float4 dc[8], rc[8], hc[FINAL ? 8 : 1], dn[8], rn[8], hn[FINAL ? 8 : 1];
+            auto fetch = [&](int l, float4 (&dd)[8], float4 (&rr)[8], float4 (&hh)[FINAL ? 8 : 1]) {
+                const size_t off = (brow + l) * DH;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) Y[mt][v] = 0.0f;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    Y[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[0][kt][v], X[kt][v], Y[0], 0, 0, 0);
-                    Y[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[1][kt][v], X[kt][v], Y[1], 0, 0, 0);
+                for (int q = 0; q < 8; ++q) {
+                    const int ch = 32 * (q >> 2) + 8 * (q & 3) + 4 * half;
+                    dd[q] = *reinterpret_cast<const float4 *>(a.d + off + ch);
+                    rr[q] = *reinterpret_cast<const float4 *>(a.r + off + ch);
+                    if constexpr (FINAL != 0) hh[q] = *reinterpret_cast<const float4 *>(a.h + off + ch);
                 }
+            };
+            fetch(ls, dc, rc, hc);
+            for (int l = ls; l < le; ++l) {
+                fetch(min(l + 1, le - 1), dn, rn, hn);
+                const size_t off = (brow + l) * DH;
+                f16v Y[2];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
+                    for (int v = 0; v < 16; ++v) Y[mt][v] = 0.0f;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        Y[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[0][kt][v], X[kt][v], Y[0], 0, 0, 0);
+                        Y[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[1][kt][v], X[kt][v], Y[1], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int mt = q >> 2, g = q & 3;
                     const int ch = 32 * mt + 8 * g + 4 * half;
-                    float4 dv = make_float4(0.f, 0.f, 0.f, 0.f), rv = dv;
-                    if (b_ok) {
-                        dv = *reinterpret_cast<const float4 *>(a.d + off + ch);
-                        rv = *reinterpret_cast<const float4 *>(a.r + off + ch);
+                    float4 dv = dc[q], rv = rc[q];
+                    if constexpr (kGuard) {
+                        dv.x *= keep; dv.y *= keep; dv.z *= keep; dv.w *= keep;
+                        rv.x *= keep; rv.y *= keep; rv.z *= keep; rv.w *= keep;
                     }
                     const float x0 = fmaf(dv.x, Y[mt][4 * g], rv.x), x1 = fmaf(dv.y, Y[mt][4 * g + 1], rv.y);
                     const float x2 = fmaf(dv.z, Y[mt][4 * g + 2], rv.z), x3 = fmaf(dv.w, Y[mt][4 * g + 3], rv.w);
                     X[mt][4 * g] = x0; X[mt][4 * g + 1] = x1; X[mt][4 * g + 2] = x2; X[mt][4 * g + 3] = x3;
-                    if (FINAL && b_ok) {
-                        float4 hv = *reinterpret_cast<const float4 *>(a.h + off + ch);
+                    if constexpr (FINAL != 0) {
+                        float4 hv = hc[q];
                         hv.x += x0; hv.y += x1; hv.z += x2; hv.w += x3;
-                        *reinterpret_cast<float4 *>(a.h + off + ch) = hv;
+                        if (!kGuard || b_ok) *reinterpret_cast<float4 *>(a.h + off + ch) = hv;
                         wmax = nanmax(nanmax(nanmax(nanmax(wmax, __builtin_fabsf(x0)), __builtin_fabsf(x1)),
                                              __builtin_fabsf(x2)), __builtin_fabsf(x3));
                     }
                 }
-        }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    dc[q] = dn[q]; rc[q] = rn[q];
+                    if constexpr (FINAL != 0) hc[q] = hn[q];
+                }
+            }
+        };
+        if (full) sweep(std::false_type{});
+        else sweep(std::true_type{});
         if (!FINAL && b_ok) {
             float *out = a.bc + ((size_t)b * a.n_c + c) * DH;
 #pragma unroll
@@ -282,31 +362,54 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
 
 // --------------------------------------------------------------------- carry
 // x_c = A_c x_{c-1} + b_c for c = 0 .. n_c-2 (x_{-1} = 0, so x_0 = b_0); one
-// wave per sequence, lane = row of A_c, x broadcast through LDS.
+// wave per sequence, lane = row of A_c.  The rows of the next four chunks are
+// in flight while one is used (the chain is otherwise bound by memory latency);
+// the loop body is branch-free (indices are clamped instead) so that the loads
+// really stay outstanding; x is broadcast lane by lane (v_readlane).
 __global__ __launch_bounds__(64) void dense_carry_kernel(const DenseArgs a)
 {
-    __shared__ float s_x[DH];
+    constexpr int DEPTH = 4;
     if (a.ctrl->stop) return;
     const int lane = threadIdx.x, b = blockIdx.x;
-    float x = a.bc[((size_t)b * a.n_c) * DH + lane];
-    a.xc[((size_t)b * a.n_c) * DH + lane] = x;
-    for (int c = 1; c + 1 < a.n_c; ++c) {
-        const float *Arow = a.Ac + (((size_t)b * a.n_c + c) * DH + lane) * DH;
-        float4 ar[DH / 4];
+    const float *bcb = a.bc + (size_t)b * a.n_c * DH + lane;
+    float *xcb = a.xc + (size_t)b * a.n_c * DH + lane;
+    const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + lane) * DH;     // row `lane` of chunk 0
+    float x = bcb[0];
+    xcb[0] = x;
+    const int last = a.n_c - 2;                       // last chunk whose end value is needed
+    if (last < 1) return;
+    float4 buf[DEPTH][DH / 4];
+    float bb[DEPTH];
 #pragma unroll
-        for (int j = 0; j < DH / 4; ++j) ar[j] = *reinterpret_cast<const float4 *>(Arow + 4 * j);
-        s_x[lane] = x;
-        __syncthreads();
-        float s = a.bc[((size_t)b * a.n_c + c) * DH + lane];
+    for (int k = 0; k < DEPTH; ++k) {
+        const int c = min(1 + k, last);
 #pragma unroll
-        for (int j = 0; j < DH / 4; ++j) {
-            const float4 xv = *reinterpret_cast<const float4 *>(s_x + 4 * j);
-            s = fmaf(ar[j].x, xv.x, s); s = fmaf(ar[j].y, xv.y, s);
-            s = fmaf(ar[j].z, xv.z, s); s = fmaf(ar[j].w, xv.w, s);
+        for (int j = 0; j < DH / 4; ++j)
+            buf[k][j] = *reinterpret_cast<const float4 *>(Ab + (size_t)c * DH * DH + 4 * j);
+        bb[k] = bcb[(size_t)c * DH];
+    }
+    for (int base = 1; base <= last; base += DEPTH) {
+#pragma unroll
+        for (int k = 0; k < DEPTH; ++k) {
+            const int c = base + k;
+            float s0 = bb[k], s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+            const unsigned int xb = __float_as_uint(x);
+#pragma unroll
+            for (int j = 0; j < DH / 4; ++j) {
+                s0 = fmaf(buf[k][j].x, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j)), s0);
+                s1 = fmaf(buf[k][j].y, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 1)), s1);
+                s2 = fmaf(buf[k][j].z, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 2)), s2);
+                s3 = fmaf(buf[k][j].w, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 3)), s3);
+            }
+            // past the end the value is simply kept (and rewritten to the last slot)
+            x = c <= last ? (s0 + s1) + (s2 + s3) : x;
+            xcb[(size_t)min(c, last) * DH] = x;
+            const int cn = min(c + DEPTH, last);
+#pragma unroll
+            for (int j = 0; j < DH / 4; ++j)
+                buf[k][j] = *reinterpret_cast<const float4 *>(Ab + (size_t)cn * DH * DH + 4 * j);
+            bb[k] = bcb[(size_t)cn * DH];
         }
-        __syncthreads();
-        x = s;
-        a.xc[((size_t)b * a.n_c + c) * DH + lane] = x;
     }
 }
 
@@ -329,6 +432,25 @@ DenseLayout dense_layout(int B, int L)
 }
 
 }  // namespace
+
+int dense_chunk() { return CD; }
+
+int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
+                         hipStream_t st)
+{
+    if (H != DH) return PARARNN_UNSUPPORTED;
+    if (((uintptr_t)W | (uintptr_t)d | (uintptr_t)A) % 16) return PARARNN_UNSUPPORTED;
+    DenseArgs a;
+    memset(&a, 0, sizeof(a));
+    a.W = W; a.d = const_cast<float *>(d); a.Ac = A;
+    a.ctrl = static_cast<Ctrl *>(ctrl_scratch);
+    a.B = B; a.L = L; a.n_c = (L + CD - 1) / CD;
+    if (launch_reset(a.ctrl, nullptr, 0, nullptr, 0, st) != hipSuccess) return PARARNN_HIP_ERROR;
+    const int n_prod = B * (a.n_c - 2);
+    if (n_prod > 0)
+        hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
+}
 
 size_t dense_workspace_bytes(int dtype, int B, int L, int H, int backward)
 {
@@ -359,8 +481,8 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
 
     const int status0 = tol < 0.0f ? PARARNN_OK : PARARNN_NOT_CONVERGED;
     if (launch_reset(a.ctrl, nullptr, 0, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
-    const size_t rows = (size_t)B * L;
-    const int res_blocks = (int)((rows + 3) / 4 < 2048 ? (rows + 3) / 4 : 2048);
+    const size_t res_items = ((size_t)B * L + 31) / 32;
+    const int res_blocks = (int)((res_items + 3) / 4 < 512 ? (res_items + 3) / 4 : 512);
     hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
     const int n_sweep = lo.n_c * ((B + 31) / 32);

@@ -344,4 +344,15 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
     return PARARNN_OK;
 }
 
+int pararnn_dense_chunk(void) { return dense_chunk(); }
+
+int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream)
+{
+    if (!dims_ok(B, L, H) || !W || !d || !A || !workspace) return PARARNN_INVALID_ARG;
+    if (!aligned(workspace, 256)) return PARARNN_INVALID_ARG;
+    if (workspace_bytes < 256) return PARARNN_WORKSPACE_TOO_SMALL;
+    return dense_chunk_products(W, d, B, L, H, A, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // extern "C"

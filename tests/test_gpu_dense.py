@@ -57,6 +57,31 @@ def test_dense_small(oracle_mod, shape, with_h0):
         assert abs(it - it32) <= 1
 
 
+@pytest.mark.parametrize("shape", [(2, 48), (3, 70), (5, 160)])
+def test_chunk_products_match_plain_matrix_products(shape):
+    """The MFMA composition kernel alone against numpy's fp64 matrix products:
+    A[b][c] = J_e ... J_s with J_l = diag(d_l) W over each chunk (Alg. 1b's
+    Jacobian update accumulated over a chunk)."""
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    W = normal(77, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    d = (1.0 - torch.tanh(normal(77, 1, (B, L, H), device="cuda")) ** 2).contiguous()
+    A = P.dense_chunk_products(W, d)
+    torch.cuda.synchronize()
+    chunk = P.dense_chunk()
+    n_c = (L + chunk - 1) // chunk
+    Wn, dn, An = f64(W), f64(d), f64(A)
+    assert A.shape == (B, n_c, H, H)
+    for b in range(B):
+        for c in range(1, n_c - 1):
+            ref = np.eye(H)
+            for l in range(c * chunk, min(L, (c + 1) * chunk)):
+                ref = (dn[b, l][:, None] * Wn) @ ref
+            assert relerr(An[b, c], ref) <= 1e-5, (b, c)
+        assert not An[b, 0].any() and not An[b, n_c - 1].any()     # not needed by the scan, not written
+
+
 def test_dense_zero_weights_is_tanh_of_input(oracle_mod):
     import paper_2510_21450_amd as P
     B, L, H = 2, 40, 64
