@@ -292,18 +292,22 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
     Ctrl *ctrl = a.ctrl;
     if (ctrl->stop) return;
     const ScanGeom &g = a.g;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keep it scalar
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const unsigned int epoch = (unsigned int)a.k;
     const UT *u = static_cast<const UT *>(a.u);
     const int cur = a.k & 1, nxt = cur ^ 1;
-    float wmax = 0.0f;
+    // max |delta| as its bit pattern: for non-negative floats the unsigned order is the float order, and
+    // NaN patterns sort above infinity, so one integer max both orders the values and keeps a NaN
+    unsigned int wmax_bits = 0u;
     bool internal_error = false;
 
     for (;;) {
         if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
         __syncthreads();
-        const unsigned int t = s_ticket;
+        // the ticket comes through LDS; make it scalar so that the whole tile geometry is computed on the SALU
+        const unsigned int t = __builtin_amdgcn_readfirstlane(s_ticket);
         if (t >= (unsigned int)g.n_tiles) break;
         const int grp = (int)(t % (unsigned int)g.n_groups), lt = (int)(t / (unsigned int)g.n_groups);
         const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
@@ -311,6 +315,17 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         const bool ch_ok = ch < g.H;
         const int l0 = lt * T + (w * LL + seg) * C;
         const size_t seq = (size_t)b * g.L;
+        // interior tiles address memory as buffer resource (scalar base of the wave's first row)
+        // + one per-lane byte offset + a scalar row offset: no per-load vector address arithmetic
+        const int wl = lt * T + w * (LL * C);
+        const unsigned int Hn = (unsigned int)g.H;
+        const size_t row_w = seq + (size_t)wl;
+        const buf_rsrc ru = make_rsrc(u + row_w * G * Hn + (size_t)cg * CW);
+        const buf_rsrc rh = make_rsrc(a.hit + row_w * S * Hn + (size_t)cg * CW);
+        const buf_rsrc rj = make_rsrc(kRaw ? a.jac + row_w * SS * Hn + (size_t)cg * CW : nullptr);
+        const unsigned int vu = ((unsigned int)(seg * (C * G)) * Hn + col) * (unsigned int)sizeof(UT);
+        const unsigned int vh = ((unsigned int)(seg * (C * S)) * Hn + col) * 4u;
+        const unsigned int vj = ((unsigned int)(seg * (C * SS)) * Hn + col) * 4u;
 
         float p[VEC][PR > 0 ? PR : 1];
         if constexpr (PR > 0) {
@@ -342,14 +357,16 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 const bool ok = !kGuard || (ch_ok && l < g.L);
 #pragma unroll
                 for (int q = 0; q < G; ++q) {
-                    if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
+                    if constexpr (!kGuard) uur[i][q] = buf_load<UT, VEC>(ru, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT));
+                    else if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
                     else uur[i][q] = zero_raw<UT, VEC>();
                 }
                 if constexpr (!FIRST) {
 #pragma unroll
                     for (int s = 0; s < S; ++s) {
                         if constexpr (!kRaw) {
-                            if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
+                            if constexpr (!kGuard) hor[i][s] = buf_load<float, VEC>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u);
+                            else if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
                             else hor[i][s] = zero_raw<float, VEC>();
                         } else {
                             hor[i][s] = zero_raw<float, VEC>();
@@ -359,7 +376,8 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 if constexpr (kRaw) {
 #pragma unroll
                     for (int e = 0; e < SS; ++e) {
-                        if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
+                        if constexpr (!kGuard) jrr[i][e] = buf_load<float, VEC>(rj, vj, (unsigned int)(i * SS + e) * Hn * 4u);
+                        else if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
                         else jrr[i][e] = zero_raw<float, VEC>();
                     }
                 }
@@ -371,7 +389,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
             for (int q = 0; q < G; ++q) {
                 uhalo[q] = zero_raw<UT, VEC>();
-                if (ch_ok && l0 > 0 && l0 <= g.L) uhalo[q] = load_raw<UT, VEC>(u + ((seq + l0 - 1) * G + q) * g.H + ch);
+                if (ch_ok && l0 > 0 && l0 <= g.L) uhalo[q] = load_raw<UT, VEC>(u + ((seq + l0 - 1) * G + q) * Hn + ch);
             }
         }
         // state entering the chunk: h0, the previous tile's boundary row, or
@@ -616,16 +634,23 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
                     ho[i][s][v] += d[s];
-                    if (ch_ok && l0 + i < g.L) wmax = nanmax(wmax, __builtin_fabsf(d[s]));
+                    if (ch_ok && l0 + i < g.L) wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
                 }
             }
         }
+        if (full_tile) {
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const int l = l0 + i;
-            if (ch_ok && l < g.L) {
+            for (int i = 0; i < C; ++i)
 #pragma unroll
-                for (int s = 0; s < S; ++s) store_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                for (int s = 0; s < S; ++s) buf_store<float, VEC>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u, ho[i][s]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                if (ch_ok && l < g.L) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) store_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                }
             }
         }
         if constexpr (!kRaw) {
@@ -638,7 +663,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
     }
 
     // ---- convergence reduction and, in the last workgroup, the stopping test
-    wmax = wave_nanmax(wmax);
+    float wmax = wave_nanmax(__uint_as_float(wmax_bits));
     if (lane == 0) s_max[w] = wmax;
     if (internal_error && lane == 0) atomicExch(&ctrl->status, kStInternal);
     __syncthreads();
@@ -753,7 +778,8 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 
     Ctrl *ctrl = a.ctrl;
     const ScanGeom &g = a.g;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keep it scalar
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const unsigned int epoch = 1u;
     const UT *u = static_cast<const UT *>(a.u);
@@ -765,7 +791,8 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
     for (;;) {
         if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
         __syncthreads();
-        const unsigned int t = s_ticket;
+        // the ticket comes through LDS; make it scalar so that the whole tile geometry is computed on the SALU
+        const unsigned int t = __builtin_amdgcn_readfirstlane(s_ticket);
         if (t >= (unsigned int)g.n_tiles) break;
         const int grp = (int)(t % (unsigned int)g.n_groups);
         const int lt = g.n_lt - 1 - (int)(t / (unsigned int)g.n_groups);   // from the end of the sequence
@@ -774,6 +801,20 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
         const bool ch_ok = ch < g.H;
         const int l0 = lt * T + (w * LL + seg) * C;
         const size_t seq = (size_t)b * g.L;
+        const int wl = lt * T + w * (LL * C);
+        const unsigned int Hn = (unsigned int)g.H;
+        const size_t row_w = seq + (size_t)wl;
+        const buf_rsrc ru = make_rsrc(u + row_w * G * Hn + (size_t)cg * CW);
+        const buf_rsrc rdu = make_rsrc(du + row_w * G * Hn + (size_t)cg * CW);
+        const buf_rsrc rg = make_rsrc(gl + row_w * S * Hn + (size_t)cg * CW);
+        // h one row earlier (address arithmetic on the integer value: for the very first row of the tensor
+        // the base lies one row before the buffer and is never dereferenced, since l = 0 reads h0)
+        const buf_rsrc rh1 = make_rsrc(reinterpret_cast<const void *>(reinterpret_cast<uintptr_t>(hres) +
+                                       (row_w * S * Hn + (size_t)cg * CW) * sizeof(UT) - (size_t)S * Hn * sizeof(UT)));
+        const buf_rsrc rj = make_rsrc(kRaw ? a.jac + row_w * SS * Hn + (size_t)cg * CW : nullptr);
+        const unsigned int vu = ((unsigned int)(seg * (C * G)) * Hn + col) * (unsigned int)sizeof(UT);
+        const unsigned int vh = ((unsigned int)(seg * (C * S)) * Hn + col) * (unsigned int)sizeof(UT);
+        const unsigned int vj = ((unsigned int)(seg * (C * SS)) * Hn + col) * 4u;
 
         float p[VEC][PRX];
         if constexpr (PR > 0) {
@@ -804,26 +845,33 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 if constexpr (!kRaw) {
 #pragma unroll
                     for (int q = 0; q < G; ++q) {
-                        if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
+                        if constexpr (!kGuard) uur[i][q] = buf_load<UT, VEC>(ru, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT));
+                        else if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
                         else uur[i][q] = zero_raw<UT, VEC>();
                     }
                 }
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
-                    if (ok) ggr[i][s] = load_raw<UT, VEC>(gl + ((seq + l) * S + s) * g.H + ch);
+                    if constexpr (!kGuard) ggr[i][s] = buf_load<UT, VEC>(rg, vh, (unsigned int)(i * S + s) * Hn * (unsigned int)sizeof(UT));
+                    else if (ok) ggr[i][s] = load_raw<UT, VEC>(gl + ((seq + l) * S + s) * g.H + ch);
                     else ggr[i][s] = zero_raw<UT, VEC>();
                     hpr[i][s] = zero_raw<UT, VEC>();
                     if constexpr (!kRaw) {
                         if (ok) {
-                            if (l > 0) hpr[i][s] = load_raw<UT, VEC>(hres + ((seq + l - 1) * S + s) * g.H + ch);
-                            else if (a.h0) hpr[i][s] = load_raw<UT, VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch);
+                            if (i > 0 || l > 0) {        // only a chunk's first step can be l = 0
+                                if constexpr (!kGuard) hpr[i][s] = buf_load<UT, VEC>(rh1, vh, (unsigned int)(i * S + s) * Hn * (unsigned int)sizeof(UT));
+                                else hpr[i][s] = load_raw<UT, VEC>(hres + ((seq + l - 1) * S + s) * g.H + ch);
+                            } else if (a.h0) {
+                                hpr[i][s] = load_raw<UT, VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch);
+                            }
                         }
                     }
                 }
                 if constexpr (kRaw) {
 #pragma unroll
                     for (int e = 0; e < SS; ++e) {
-                        if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
+                        if constexpr (!kGuard) jrr[i][e] = buf_load<float, VEC>(rj, vj, (unsigned int)(i * SS + e) * Hn * 4u);
+                        else if (ok) jrr[i][e] = load_raw<float, VEC>(a.jac + ((seq + l) * SS + e) * g.H + ch);
                         else jrr[i][e] = zero_raw<float, VEC>();
                     }
                 }
@@ -1046,12 +1094,20 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
             for (int s = 0; s < S; ++s) nu0[s][v] = n0[s];
         }
+        if (full_tile) {
 #pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const int l = l0 + i;
-            if (ch_ok && l < g.L) {
+            for (int i = 0; i < C; ++i)
 #pragma unroll
-                for (int q = 0; q < G; ++q) store_vec<VEC>(du + ((seq + l) * G + q) * g.H + ch, duv[i][q]);
+                for (int q = 0; q < G; ++q)
+                    buf_store<UT, VEC>(rdu, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT), duv[i][q]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                if (ch_ok && l < g.L) {
+#pragma unroll
+                    for (int q = 0; q < G; ++q) store_vec<VEC>(du + ((seq + l) * G + q) * g.H + ch, duv[i][q]);
+                }
             }
         }
         if (a.dh0 && ch_ok && l0 == 0) {
