@@ -22,7 +22,8 @@
  *   h, dL_dh   [B][L][S][H]  states / loss gradients, S values per channel
  *   h0, dL_dh0 [B][S][H]
  *   params     always fp32.  Diagonal cells: [2][G][H] = recurrent weights,
- *              then biases.  Dense cell: W[H][H] row-major.
+ *              then biases (PARALSTM_DIAG: [8][H], see below).  Dense cell:
+ *              W[H][H] row-major.
  * Gate order: GRU (z, r, c); LSTM (i, f, o, g).  LSTM state order (c, h).
  */
 #ifndef PARARNN_H
@@ -45,12 +46,19 @@ extern "C" {
  *  TANH_DENSE (G=1,S=1): h' = tanh(W h + u), dense Jacobian diag(1-h'^2) W
  *             (the generic dense case of Sec. 2.1).
  *  LINEAR_DIAG(G=1,S=1): h' = a h + u + b, the linear SSM of the footnote in
- *             Sec. 2; used to test that one Newton solve is exact. */
+ *             Sec. 2; used to test that one Newton solve is exact.
+ *  PARALSTM_DIAG (G=3,S=2): the paper's ParaLSTM, Sec. 3, Eq. (7b) with diagonal
+ *             A_*, C_* (Eq. (9)): f = sig(a_f h + u_f + c_f c + b_f),
+ *             z = tanh(a_z h + u_z + b_z), c' = f c + (1-f) z,
+ *             o = sig(a_o h + u_o + c_o c' + b_o), h' = o tanh(c'); Jacobian
+ *             blocks Eq. (8b).  Gates (f, z, o); params [8][H] = a_f, a_z, a_o,
+ *             c_f, c_o, b_f, b_z, b_o. */
 typedef enum {
     PARARNN_GRU_DIAG = 0,
     PARARNN_LSTM_DIAG = 1,
     PARARNN_TANH_DENSE = 2,
-    PARARNN_LINEAR_DIAG = 3
+    PARARNN_LINEAR_DIAG = 3,
+    PARARNN_PARALSTM_DIAG = 4
 } pararnn_cell_t;
 
 /* Storage type of u, h0, h, dL_dh, dL_du, dL_dh0.  With BF16 all arithmetic,

@@ -17,7 +17,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "pararnn_oracle.c")
 _LIBS = {}
 
-CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3}
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4}
 STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 5: "NONFINITE"}
 JAC_KIND = {"diag": 0, "block2": 1, "dense": 2}
 
@@ -86,7 +86,8 @@ def cell_jacobian(cell, params, hp, u, precision="f64"):
     H = hp_a.shape[-1]
     _, pp = _c(params, precision)
     _, up = _c(u, precision)
-    shape = {"gru_diag": (H,), "linear_diag": (H,), "lstm_diag": (2, 2, H), "tanh_dense": (H, H)}[cell]
+    shape = {"gru_diag": (H,), "linear_diag": (H,), "lstm_diag": (2, 2, H), "paralstm_diag": (2, 2, H),
+             "tanh_dense": (H, H)}[cell]
     out = np.empty(shape, dtype=_np_t(precision))
     lib.oracle_cell_jacobian(CELLS[cell], H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
     return out

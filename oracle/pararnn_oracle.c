@@ -16,6 +16,8 @@
  *   - Sec. 2, Eq. (6): the backward (adjoint) recurrence          -> oracle_backward
  *   - Sec. 3, Eq. (7a) with the diagonal weights of Eq. (9): GRU  -> cell 0
  *   - Sec. 3, Eq. (8a): its Jacobian                              -> oracle_cell_jacobian
+ *   - Sec. 3, Eq. (7b) / (8b) with diagonal A_*, C_* (Eq. (9)): the
+ *     CIFG LSTM with peepholes (ParaLSTM) and its 2x2 Jacobian    -> cell 4
  *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
  *
  * Precision: REAL is double unless the file is compiled with -DREAL=float
@@ -23,8 +25,9 @@
  *
  * Layouts (H contiguous): u [B][L][G][H]; h, g [B][L][S][H]; h0 [B][S][H];
  * params for the diagonal cells [2][G][H] (recurrent weights, then biases),
- * for the dense cell W[H][H] row-major.  Gate order GRU (z,r,c), LSTM
- * (i,f,o,g); LSTM state order (c,h).
+ * for the dense cell W[H][H] row-major, for the ParaLSTM [8][H] = (a_f, a_z,
+ * a_o, c_f, c_o, b_f, b_z, b_o).  Gate order GRU (z,r,c), LSTM (i,f,o,g),
+ * ParaLSTM (f,z,o); LSTM state order (c,h).
  *
  * Parity pins: every function here is checked by tests that do not call it to
  * produce their own expected value (closed forms, finite differences, brute
@@ -42,7 +45,7 @@
 #define REAL double
 #endif
 
-enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3 };
+enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3, CELL_PARALSTM_DIAG = 4 };
 enum { ST_OK = 0, ST_NOT_CONVERGED = 1, ST_INVALID = 2, ST_NONFINITE = 5 };
 enum { JAC_DIAG = 0, JAC_BLOCK2 = 1, JAC_DENSE = 2 };
 
@@ -67,15 +70,20 @@ int oracle_gates(int cell)
     case CELL_LSTM_DIAG: return 4;
     case CELL_TANH_DENSE: return 1;
     case CELL_LINEAR_DIAG: return 1;
+    case CELL_PARALSTM_DIAG: return 3;
     }
     return -1;
 }
 
-int oracle_state(int cell) { return cell == CELL_LSTM_DIAG ? 2 : (cell >= 0 && cell <= 3 ? 1 : -1); }
+int oracle_state(int cell)
+{
+    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG) return 2;
+    return cell >= 0 && cell <= 3 ? 1 : -1;
+}
 
 int oracle_jac_kind(int cell)
 {
-    if (cell == CELL_LSTM_DIAG) return JAC_BLOCK2;
+    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG) return JAC_BLOCK2;
     if (cell == CELL_TANH_DENSE) return JAC_DENSE;
     return JAC_DIAG;
 }
@@ -91,6 +99,7 @@ static size_t jac_size(int kind, int H)
 static size_t param_count(int cell, int H)
 {
     if (cell == CELL_TANH_DENSE) return (size_t)H * H;
+    if (cell == CELL_PARALSTM_DIAG) return (size_t)8 * H;
     return (size_t)2 * oracle_gates(cell) * H;
 }
 
@@ -124,6 +133,22 @@ void oracle_cell_step(int cell, int H, const REAL *params, const REAL *hp, const
             REAL o = sigmoid(w[2 * H + j] * h + u[2 * H + j] + b[2 * H + j]);
             REAL g = tanh_r(w[3 * H + j] * h + u[3 * H + j] + b[3 * H + j]);
             REAL cn = f * cp[j] + i * g;
+            out[j] = cn;
+            out[H + j] = o * tanh_r(cn);
+        }
+    } else if (cell == CELL_PARALSTM_DIAG) {
+        /* Eq. (7b) with A_* = diag(a_*), C_* = diag(c_*) (Eq. (9)): input and
+         * forget gates combined, peepholes from c_{l-1} into f and from the
+         * NEW c_l into o; the candidate nonlinearity sigma_z is taken as tanh. */
+        const REAL *af = params, *az = params + H, *ao = params + 2 * H, *cf = params + 3 * H,
+                   *co = params + 4 * H, *bf = params + 5 * H, *bz = params + 6 * H, *bo = params + 7 * H;
+        const REAL *cp = hp, *hh = hp + H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hh[j], c = cp[j];
+            REAL f = sigmoid(af[j] * h + u[0 * H + j] + cf[j] * c + bf[j]);
+            REAL z = tanh_r(az[j] * h + u[1 * H + j] + bz[j]);
+            REAL cn = f * c + ((REAL)1 - f) * z;
+            REAL o = sigmoid(ao[j] * h + u[2 * H + j] + co[j] * cn + bo[j]);
             out[j] = cn;
             out[H + j] = o * tanh_r(cn);
         }
@@ -176,6 +201,26 @@ void oracle_cell_jacobian(int cell, int H, const REAL *params, const REAL *hp, c
             J[1 * H + j] = Jch;                                        /* dc'/dh */
             J[2 * H + j] = o * ((REAL)1 - t * t) * f;                  /* dh'/dc */
             J[3 * H + j] = t * o * ((REAL)1 - o) * w[2 * H + j] + o * ((REAL)1 - t * t) * Jch; /* dh'/dh */
+        }
+    } else if (cell == CELL_PARALSTM_DIAG) {
+        /* Eq. (8b) with diagonal A_*, C_*: every block is a per-channel scalar. */
+        const REAL *af = params, *az = params + H, *ao = params + 2 * H, *cf = params + 3 * H,
+                   *co = params + 4 * H, *bf = params + 5 * H, *bz = params + 6 * H, *bo = params + 7 * H;
+        const REAL *cp = hp, *hh = hp + H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hh[j], c = cp[j];
+            REAL f = sigmoid(af[j] * h + u[0 * H + j] + cf[j] * c + bf[j]);
+            REAL z = tanh_r(az[j] * h + u[1 * H + j] + bz[j]);
+            REAL cn = f * c + ((REAL)1 - f) * z;
+            REAL o = sigmoid(ao[j] * h + u[2 * H + j] + co[j] * cn + bo[j]);
+            REAL t = tanh_r(cn);
+            REAL sf = f * ((REAL)1 - f), so = o * ((REAL)1 - o), sz = (REAL)1 - z * z, st = (REAL)1 - t * t;
+            REAL Jcc = f + (c - z) * sf * cf[j];
+            REAL Jch = (c - z) * sf * af[j] + ((REAL)1 - f) * sz * az[j];
+            J[0 * H + j] = Jcc;
+            J[1 * H + j] = Jch;
+            J[2 * H + j] = (t * so * co[j] + o * st) * Jcc;
+            J[3 * H + j] = t * so * (ao[j] + co[j] * Jch) + o * st * Jch;
         }
     } else if (cell == CELL_TANH_DENSE) {
         int i;
@@ -459,6 +504,30 @@ void oracle_backward(int cell, int B, int L, int H, const REAL *params, const RE
                     lprev[j] = d_cn * f;
                     lprev[H + j] = d_pi * w[0 * H + j] + d_pf * w[1 * H + j] + d_po * w[2 * H + j]
                                  + d_pg * w[3 * H + j];
+                }
+            } else if (cell == CELL_PARALSTM_DIAG) {
+                const REAL *af = params, *az = params + H, *ao = params + 2 * H, *cf = params + 3 * H,
+                           *co = params + 4 * H, *bf = params + 5 * H, *bz = params + 6 * H, *bo = params + 7 * H;
+                for (j = 0; j < H; ++j) {
+                    REAL c = hp[j], hh = hp[H + j], lc = lam[j], lh = lam[H + j];
+                    REAL f = sigmoid(af[j] * hh + ul[0 * H + j] + cf[j] * c + bf[j]);
+                    REAL z = tanh_r(az[j] * hh + ul[1 * H + j] + bz[j]);
+                    REAL cn = f * c + ((REAL)1 - f) * z;
+                    REAL o = sigmoid(ao[j] * hh + ul[2 * H + j] + co[j] * cn + bo[j]);
+                    REAL t = tanh_r(cn);
+                    /* h' = o t;  o reads the new c through its peephole */
+                    REAL d_o = lh * t;
+                    REAL d_po = d_o * o * ((REAL)1 - o);
+                    REAL d_cn = lc + lh * o * ((REAL)1 - t * t) + d_po * co[j];
+                    /* c' = f c + (1 - f) z */
+                    REAL d_f = d_cn * (c - z), d_z = d_cn * ((REAL)1 - f);
+                    REAL d_pf = d_f * f * ((REAL)1 - f), d_pz = d_z * ((REAL)1 - z * z);
+                    dul[0 * H + j] = d_pf; dul[1 * H + j] = d_pz; dul[2 * H + j] = d_po;
+                    dp[0 * H + j] += d_pf * hh; dp[1 * H + j] += d_pz * hh; dp[2 * H + j] += d_po * hh;
+                    dp[3 * H + j] += d_pf * c;  dp[4 * H + j] += d_po * cn;
+                    dp[5 * H + j] += d_pf; dp[6 * H + j] += d_pz; dp[7 * H + j] += d_po;
+                    lprev[j] = d_cn * f + d_pf * cf[j];
+                    lprev[H + j] = d_pf * af[j] + d_pz * az[j] + d_po * ao[j];
                 }
             } else if (cell == CELL_TANH_DENSE) {
                 const REAL *hl = h + ((size_t)b * L + l) * n;

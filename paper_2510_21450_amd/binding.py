@@ -10,7 +10,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libpararnn.so")
 
-CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3}
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4}
 DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR",
           5: "NONFINITE", 6: "UNSUPPORTED", 7: "INTERNAL"}

@@ -151,6 +151,87 @@ struct LstmDiag {
     }
 };
 
+// The paper's ParaLSTM: Sec. 3, Eq. (7b) with diagonal A_*, C_* (Eq. (9)) -- input
+// and forget gates combined, peepholes from c_{l-1} into f and from the new c
+// into o, candidate nonlinearity tanh.  Jacobian blocks: Eq. (8b).
+// Parameter rows: a_f, a_z, a_o, c_f, c_o, b_f, b_z, b_o.  Gates (f, z, o).
+struct ParaLstmDiag {
+    static constexpr int G = 3, S = 2, PR = 8, NC = 8;
+
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    {
+        const float c = hp[0], h = hp[1];
+        const float f = fast_sigmoid(fmaf(p[0], h, fmaf(p[3], c, u[0] + p[5])));
+        const float z = fast_tanh(fmaf(p[1], h, u[1] + p[6]));
+        const float cn = fmaf(f, c - z, z);
+        const float o = fast_sigmoid(fmaf(p[2], h, fmaf(p[4], cn, u[2] + p[7])));
+        F[0] = cn;
+        F[1] = o * fast_tanh(cn);
+    }
+
+    // k[0] = d c'/d u_f = (c - z) f(1-f), k[1] = d c'/d u_z = (1-f)(1-z^2),
+    // k[2] = d h'/d u_o = t o(1-o), k[3] = o (1-t^2), k[4] = c_o, k[5] = h, k[6] = c, k[7] = c'.
+    __device__ __forceinline__ static void coefs(const float *p, const float *hp, const float *u, float *F,
+                                                 float *J, float *k)
+    {
+        const float c = hp[0], h = hp[1];
+        const float f = fast_sigmoid(fmaf(p[0], h, fmaf(p[3], c, u[0] + p[5])));
+        const float z = fast_tanh(fmaf(p[1], h, u[1] + p[6]));
+        const float cmz = c - z;
+        const float cn = fmaf(f, cmz, z);
+        const float o = fast_sigmoid(fmaf(p[2], h, fmaf(p[4], cn, u[2] + p[7])));
+        const float t = fast_tanh(cn);
+        F[0] = cn;
+        F[1] = o * t;
+        k[0] = cmz * (f * (1.0f - f));
+        k[1] = (1.0f - f) * fmaf(-z, z, 1.0f);
+        k[2] = t * (o * (1.0f - o));
+        k[3] = o * fmaf(-t, t, 1.0f);
+        k[4] = p[4];
+        k[5] = h;
+        k[6] = c;
+        k[7] = cn;
+        const float jcc = fmaf(k[0], p[3], f);
+        const float jch = fmaf(k[0], p[0], k[1] * p[1]);
+        const float hc = fmaf(k[2], p[4], k[3]);          // d h'/d c' including the peephole of o
+        J[0] = jcc;
+        J[1] = jch;
+        J[2] = hc * jcc;
+        J[3] = fmaf(k[2], p[2], hc * jch);
+    }
+
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    {
+        float k[NC];
+        coefs(p, hp, u, F, J, k);
+    }
+
+    __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
+                                                    float *J, float *k)
+    {
+        float F[2];
+        coefs(p, hp, u, F, J, k);
+    }
+
+    __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
+    {
+        const float dpo = lam[1] * k[2];
+        const float dcn = fmaf(lam[1], k[3], fmaf(dpo, k[4], lam[0]));
+        const float dpf = dcn * k[0], dpz = dcn * k[1];
+        du[0] = dpf;
+        du[1] = dpz;
+        du[2] = dpo;
+        acc[0] = fmaf(dpf, k[5], acc[0]);
+        acc[1] = fmaf(dpz, k[5], acc[1]);
+        acc[2] = fmaf(dpo, k[5], acc[2]);
+        acc[3] = fmaf(dpf, k[6], acc[3]);
+        acc[4] = fmaf(dpo, k[7], acc[4]);
+        acc[5] += dpf;
+        acc[6] += dpz;
+        acc[7] += dpo;
+    }
+};
+
 // Linear SSM of the footnote in Sec. 2: f = a h + u + b, J = a.
 struct LinearDiag {
     static constexpr int G = 1, S = 1, PR = 2, NC = 1;

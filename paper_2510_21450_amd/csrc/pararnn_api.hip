@@ -23,6 +23,7 @@ bool cell_info(int cell, CellInfo *ci)
     case PARARNN_LSTM_DIAG: *ci = {4, 2, 8}; return true;
     case PARARNN_TANH_DENSE: *ci = {1, 1, 0}; return true;
     case PARARNN_LINEAR_DIAG: *ci = {1, 1, 2}; return true;
+    case PARARNN_PARALSTM_DIAG: *ci = {3, 2, 8}; return true;
     }
     return false;
 }
@@ -44,17 +45,17 @@ TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_el
     if (H % 4 == 0 && align_elems >= 4) vmax = 4;
     else if (H % 2 == 0 && align_elems >= 2) vmax = 2;
     TileCfg cfg = {1, 2, 8, 8};                          // 32 channels x 128 steps
-    const bool lstm = cell_kind == PARARNN_LSTM_DIAG, bf = dtype == PARARNN_BF16;
+    const bool lstm = cell_kind == PARARNN_LSTM_DIAG || cell_kind == PARARNN_PARALSTM_DIAG, bf = dtype == PARARNN_BF16;
     if (H <= 8) {
         cfg = {1, 8, 4, 2};                              // 8 channels x 64 steps
     } else if (H <= 32) {
         cfg = {1, 2, 8, 8};
     } else if (!backward) {
-        if (lstm) cfg = {1, 2, 16, 4};                   // 32 channels x 128 steps
+        if (lstm) cfg = {1, 1, 8, 16};                   // 64 channels x 128 steps
         else if (bf && vmax >= 2) cfg = {2, 2, 8, 8};    // 64 channels x 128 steps
         else cfg = {1, 1, 8, 16};                        // 64 channels x 128 steps
     } else {
-        if (lstm) cfg = {1, 2, 8, 8};
+        if (lstm) cfg = {1, 1, 16, 8};                   // 64 channels x 128 steps
         else if (bf) cfg = {1, 1, 8, 8};                 // 64 channels x 64 steps
         else cfg = {1, 2, 8, 16};                        // 32 channels x 256 steps
     }
@@ -263,6 +264,7 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
     case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
     case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
+    case PARARNN_PARALSTM_DIAG: return forward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
     }
     return PARARNN_INVALID_ARG;
 }
@@ -301,6 +303,7 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
     case PARARNN_GRU_DIAG: return backward_diag<GruDiag>(ci, dtype, lo, a, st, dL_dparams);
     case PARARNN_LSTM_DIAG: return backward_diag<LstmDiag>(ci, dtype, lo, a, st, dL_dparams);
     case PARARNN_LINEAR_DIAG: return backward_diag<LinearDiag>(ci, dtype, lo, a, st, dL_dparams);
+    case PARARNN_PARALSTM_DIAG: return backward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, dL_dparams);
     }
     return PARARNN_INVALID_ARG;
 }

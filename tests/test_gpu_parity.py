@@ -42,6 +42,11 @@ def problem(cell, B, L, H, seed, dtype=torch.float32, h0=True, bias=True, bound=
     dev = "cuda"
     if cell == "tanh_dense":
         params = normal(seed, 5, (H, H), std=0.8 / H ** 0.5, device=dev)
+    elif cell == "paralstm_diag":       # a_f, a_z, a_o, c_f, c_o, b_f, b_z, b_o
+        params = torch.zeros(8, H, device=dev)
+        params[:5] = uniform_sym(seed, 2, (5, H), bound, device=dev)
+        if bias:
+            params[5:] = normal(seed, 6, (3, H), std=0.3, device=dev)
     else:
         params = torch.zeros(2, G, H, device=dev)
         params[0] = uniform_sym(seed, 2, (G, H), bound, device=dev)
@@ -57,7 +62,7 @@ SHAPES = [(1, 1, 8), (1, 2, 4), (2, 33, 1), (2, 100, 24), (3, 257, 68), (2, 1000
           (1, 32, 256), (2, 64, 512), (1, 65, 6)]
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_forward_backward_f32_small(P, oracle_mod, cell, shape):
     B, L, H = shape
@@ -162,11 +167,11 @@ def test_invalid_arguments_are_rejected(P):
         P.forward("gru_diag", params, u, h0, workspace=small)
 
 
-TILE_SHAPES = [(1, 1, 8, 16), (1, 2, 8, 16), (1, 2, 16, 4), (1, 2, 8, 8), (1, 1, 8, 8), (2, 2, 8, 8), (1, 1, 4, 8),
+TILE_SHAPES = [(1, 1, 8, 16), (1, 2, 8, 16), (1, 2, 16, 4), (1, 2, 8, 8), (1, 1, 8, 8), (2, 2, 8, 8), (1, 1, 4, 8), (1, 1, 16, 8),
                (1, 8, 4, 2), (4, 4, 8, 8), (2, 4, 8, 8)]
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("tile", TILE_SHAPES)
 def test_every_tile_shape(P, oracle_mod, cell, tile):
     """Every compiled tile shape (channels per lane, segments per wave, steps
@@ -183,7 +188,7 @@ def test_every_tile_shape(P, oracle_mod, cell, tile):
             du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
         except RuntimeError as e:
             # wide LSTM tiles exceed the backward kernel's 64 KiB of LDS and are refused by the host
-            if "UNSUPPORTED" in str(e) and cell == "lstm_diag" and tile[0] * 64 // tile[1] * tile[3] >= 2048:
+            if "UNSUPPORTED" in str(e) and cell != "gru_diag" and tile[0] * 64 // tile[1] * tile[3] >= 2048:
                 pytest.skip("tile shape not offered for the LSTM backward kernel (LDS)")
             raise
         torch.cuda.synchronize()
@@ -231,7 +236,7 @@ def test_affine_scan_matches_forward_substitution(P, oracle_mod, kind, reverse):
             assert relerr(to_np(d[b]), ref) <= TOL_F32, (kind, reverse, L)
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 def test_bf16_storage(P, oracle_mod, cell):
     """bf16 storage, fp32 arithmetic: the oracle takes the bf16-rounded inputs
     as exact and computes in fp64; bound 2e-2."""

@@ -44,7 +44,7 @@ def test_status_strings_and_cell_tables(lib):
     for code, s in want.items():
         assert lib.pararnn_status_string(code).decode() == s
     assert lib.pararnn_version() >= 100
-    assert [(lib.pararnn_cell_gates(c), lib.pararnn_cell_state(c)) for c in range(4)] == [(3, 1), (4, 2), (1, 1), (1, 1)]
+    assert [(lib.pararnn_cell_gates(c), lib.pararnn_cell_state(c)) for c in range(5)] == [(3, 1), (4, 2), (1, 1), (1, 1), (3, 2)]
     assert lib.pararnn_cell_gates(7) == -1 and lib.pararnn_cell_state(-1) == -1
 
 

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 DIAG_CELLS = ["gru_diag", "linear_diag"]
-ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag"]
+ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag"]
 
 
 def sig(x):
@@ -22,6 +22,12 @@ def rand_params(oracle, cell, H, rng, bound=0.9, bias=True):
     G, S = oracle.dims(cell)
     if cell == "tanh_dense":
         return rng.normal(0, 0.8 / math.sqrt(H), (H, H))
+    if cell == "paralstm_diag":          # a_f, a_z, a_o, c_f, c_o, then biases b_f, b_z, b_o
+        p = np.zeros((8, H))
+        p[:5] = rng.uniform(-bound, bound, (5, H))
+        if bias:
+            p[5:] = rng.normal(0, 0.3, (3, H))
+        return p
     p = np.zeros((2, G, H))
     p[0] = rng.uniform(-bound, bound, (G, H))
     if bias:
@@ -103,6 +109,29 @@ def test_lstm_step_hand_values(oracle_mod):
     assert abs(got[1, 0] - 0.5 * math.tanh(sig(1.0) * c)) < 1e-15
 
 
+def test_paralstm_step_hand_values(oracle_mod):
+    """Eq. (7b) with Eq. (9): f = sig(a_f h + u_f + c_f c + b_f), z = tanh(a_z h + u_z + b_z),
+    c' = f c + (1-f) z, o = sig(a_o h + u_o + c_o c' + b_o) (peephole on the NEW c), h' = o tanh(c')."""
+    o = oracle_mod
+    af, az, ao, cf, co, bf, bz, bo = 0.4, -0.7, 0.6, 0.5, -0.3, 0.2, -0.1, 0.05
+    uf, uz, uo, c, h = 0.3, -0.8, 0.9, 0.7, -0.45
+    f = sig(af * h + uf + cf * c + bf)
+    z = math.tanh(az * h + uz + bz)
+    cn = f * c + (1 - f) * z
+    oo = sig(ao * h + uo + co * cn + bo)
+    hn = oo * math.tanh(cn)
+    p = np.array([[x] for x in (af, az, ao, cf, co, bf, bz, bo)])
+    got = o.cell_step("paralstm_diag", p, [[c], [h]], [[uf], [uz], [uo]])
+    assert abs(got[0, 0] - cn) < 1e-15 and abs(got[1, 0] - hn) < 1e-15
+    # the o peephole reads the new c: with a_o = u_o = b_o = 0 and a huge c_o the gate saturates by sign(c')
+    p2 = p.copy(); p2[2] = 0; p2[7] = 0; p2[4] = 1e4
+    got = o.cell_step("paralstm_diag", p2, [[c], [h]], [[uf], [uz], [0.0]])
+    assert abs(got[1, 0] - (math.tanh(cn) if cn > 0 else 0.0)) < 1e-12
+    # f -> 1 keeps c (CIFG: the input gate is 1 - f)
+    got = o.cell_step("paralstm_diag", p, [[c], [h]], [[60.0], [uz], [uo]])
+    assert abs(got[0, 0] - c) < 1e-14
+
+
 def test_dense_step_is_tanh_of_matvec(oracle_mod):
     o = oracle_mod
     rng = np.random.default_rng(1)
@@ -122,7 +151,7 @@ def test_bounded_state_invariant(oracle_mod):
     """GRU: h' is a convex combination of h and tanh(.) so |h_l| < 1 when
     |h_0| <= 1; LSTM: |h_l| < 1 since h' = o tanh(c')."""
     o = oracle_mod
-    for cell in ("gru_diag", "lstm_diag"):
+    for cell in ("gru_diag", "lstm_diag", "paralstm_diag"):
         params, u, h0 = rand_problem(o, cell, 2, 200, 7, seed=3)
         u *= 3.0
         h = o.seq_unroll(cell, params, u, None)
@@ -152,7 +181,7 @@ def test_jacobian_matches_central_differences(oracle_mod, cell):
         Jfd[:, q] = (fp - fm) / (2 * eps)
     if cell in DIAG_CELLS:
         Jfull = np.diag(J)
-    elif cell == "lstm_diag":
+    elif cell in ("lstm_diag", "paralstm_diag"):
         Jfull = np.zeros((n, n))
         for p_, q_ in itertools.product(range(2), range(2)):
             Jfull[p_ * H:(p_ + 1) * H, q_ * H:(q_ + 1) * H] = np.diag(J[p_, q_])
@@ -274,7 +303,7 @@ def test_linear_cell_one_newton_solve_is_exact(oracle_mod):
     assert np.max(np.abs(h1 - ref)) < 1e-13
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag"])
 def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     """Sec. 2.1: convergence in at most L Newton steps is guaranteed because
     after k solves the first k states equal the sequential result, whatever the
@@ -296,7 +325,7 @@ def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     assert np.max(np.abs(hL - ref)) < 1e-11
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag"])
 def test_newton_converges_quadratically_to_the_unroll(oracle_mod, cell):
     """App. A: the residual falls to machine precision in a handful of
     iterations; the converged iterate is the sequential result of Eq. (1)."""
@@ -392,7 +421,7 @@ def test_backward_matches_finite_differences(oracle_mod, cell):
         assert abs(du[idx] - fd(u, idx, "u")) < 2e-8, ("du", idx)
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 def test_backward_dummy_loss_sum_h_squared(oracle_mod, cell):
     """App. B's dummy loss L(h) = sum_l h_l^2, i.e. g_l = 2 h_l."""
     o = oracle_mod
@@ -406,7 +435,7 @@ def test_backward_dummy_loss_sum_h_squared(oracle_mod, cell):
         assert abs(dh0[idx] - fdv) < 1e-7
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag"])
 def test_adjoint_identity_between_forward_solve_and_backward(oracle_mod, cell):
     """Eq. (6) is the transpose of the solve of Eq. (3)/(4): for the solution
     operator S of delta_l = J_l delta_{l-1} + r_l and the reverse recurrence
@@ -422,7 +451,7 @@ def test_adjoint_identity_between_forward_solve_and_backward(oracle_mod, cell):
     h = o.seq_unroll(cell, params, u, h0)
     g = rng.normal(0, 1, (B, L, S, H))
     # Jacobians at the converged states
-    kind = {"gru_diag": "diag", "lstm_diag": "block2", "tanh_dense": "dense"}[cell]
+    kind = {"gru_diag": "diag", "lstm_diag": "block2", "paralstm_diag": "block2", "tanh_dense": "dense"}[cell]
     Js = [o.cell_jacobian(cell, params, h0[0] if l == 0 else h[0, l - 1], u[0, l]) for l in range(L)]
     J = np.stack(Js)
     r = rng.normal(0, 1, (L, S, H))

@@ -6,7 +6,8 @@ Tensor layouts (H contiguous everywhere):
   h0     [B][S][H]
   params diag cells: [2][G][H] = recurrent weights then biases (fp32)
          dense cell: W[H][H] row-major (fp32)
-Gate order: GRU (z, r, c); LSTM (i, f, o, g).  LSTM state order (c, h).
+         ParaLSTM (CIFG + peepholes): [8][H] = a_f, a_z, a_o, c_f, c_o, b_f, b_z, b_o
+Gate order: GRU (z, r, c); LSTM (i, f, o, g); ParaLSTM (f, z, o).  LSTM state order (c, h).
 Streams of the generator: 1 = u, 2 = weights, 3 = h0, 4 = dL/dh, 5 = W.
 """
 from __future__ import annotations
@@ -19,7 +20,8 @@ from .rng import normal, uniform_sym
 BASE_SEED = 20251021
 
 # cell name -> (gates G, state size S)
-_DIMS = {"gru_diag": (3, 1), "lstm_diag": (4, 2), "tanh_dense": (1, 1), "linear_diag": (1, 1)}
+_DIMS = {"gru_diag": (3, 1), "lstm_diag": (4, 2), "tanh_dense": (1, 1), "linear_diag": (1, 1),
+         "paralstm_diag": (3, 2)}
 
 
 def cell_dims(cell: str):
