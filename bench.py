@@ -22,6 +22,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak, published
 # algorithmic bytes per timestep-channel (read u + read iterate + write iterate;
 # backward: read h, u, g + write du), storage sizes per workload
+# HBM bytes one launch of newton_iter_kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes scaled
+# by the same counters' reading for a plain copy of known size (profiles/newton_iter_*.txt)
+MEASURED_TRAFFIC = {"C2": 1364.4e6, "C3": 1101.3e6, "C5": 15715.5e6}
 ALGO_BYTES = {
     "C1": {"iter": 20, "bwd": 32}, "C2": {"iter": 20, "bwd": 32}, "C3": {"iter": 32, "bwd": 48},
     "C5": {"iter": 14, "bwd": 16},
@@ -141,7 +144,7 @@ def main():
 
     if w.cell != "tanh_dense":
         roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": None}
+                    "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(args.config)}
 
     cpu = None
     if not args.no_cpu_baseline:
