@@ -102,6 +102,19 @@ int pararnn_cell_state(int cell);
  * arguments.  The workspace needs 256-byte alignment and no initialisation. */
 size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int backward);
 
+/* Workspace size that lets a fixed-count solve (tol < 0, 1 <= n_iters <= 8) run
+ * all its iterations in ONE launch (the paper's "fully fused" mode, Sec. 4 item 3:
+ * u is read once and h written once): one carry-record slot per iteration.  Never
+ * smaller than pararnn_workspace_bytes(.., 0).  pararnn_forward takes the
+ * one-launch path whenever tol < 0, max_iter <= 8 and the workspace it is given
+ * is at least this large; otherwise it launches one kernel per iteration.  Both
+ * paths compute the same iterations (results agree to fp32 rounding). */
+size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, int n_iters);
+
+/* Test / tuning hook (host, process-wide): enable = 0 makes pararnn_forward
+ * always launch one kernel per iteration. */
+int pararnn_set_fused(int enable);
+
 /*
  * Forward: solve Eq. (2) by Newton iterations (Alg. 1a).
  *   initial guess   h^0_l = f(h0, u_l) for every l (App. A; f(0, x_l) when h0 = 0)

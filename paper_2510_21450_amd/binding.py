@@ -30,6 +30,9 @@ _lib.pararnn_cell_gates.argtypes = [_i]
 _lib.pararnn_cell_state.argtypes = [_i]
 _lib.pararnn_workspace_bytes.restype = _sz
 _lib.pararnn_workspace_bytes.argtypes = [_i] * 6
+_lib.pararnn_workspace_bytes_fused.restype = _sz
+_lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
+_lib.pararnn_set_fused.argtypes = [_i]
 _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_backward.restype = _i
@@ -85,6 +88,15 @@ def workspace_bytes(cell: str, dtype, B: int, L: int, H: int, backward: bool = F
     return _lib.pararnn_workspace_bytes(CELLS[cell], DTYPES[dtype], B, L, H, int(backward))
 
 
+def workspace_bytes_fused(cell: str, dtype, B: int, L: int, H: int, n_iters: int) -> int:
+    return _lib.pararnn_workspace_bytes_fused(CELLS[cell], DTYPES[dtype], B, L, H, n_iters)
+
+
+def set_fused(enable: bool = True) -> None:
+    """pararnn_set_fused: allow (default) or forbid the one-launch path of fixed-count solves."""
+    _raise(_lib.pararnn_set_fused(int(enable)), "pararnn_set_fused")
+
+
 def _ptr(t):
     return None if t is None else t.data_ptr()
 
@@ -133,7 +145,8 @@ def forward(cell: str, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64
     _check(h, "h", dt, (B, L, S, H))
     iters = torch.empty(2, dtype=torch.int32, device=u.device)
     tr = torch.zeros(max(max_iter, 1), dtype=torch.float32, device=u.device) if trace else None
-    ws = _workspace(workspace_bytes(cell, dt, B, L, H, False), u.device, workspace)
+    need = workspace_bytes_fused(cell, dt, B, L, H, max_iter) if tol < 0 else workspace_bytes(cell, dt, B, L, H, False)
+    ws = _workspace(need, u.device, workspace)
     code = _lib.pararnn_forward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol, max_iter,
                                 _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
     _raise(code, "pararnn_forward")

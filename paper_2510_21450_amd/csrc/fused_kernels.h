@@ -1,0 +1,386 @@
+// All Newton iterations of a fixed-count solve in one launch (the paper's "fully
+// fused" mode, Sec. 4 item 3 and App. D.3, where N_its is fixed and there is no
+// stopping test): u is read once, the K iterations run on registers, h is
+// written once.  Traffic per timestep-channel drops from K * (u + 2 h) to u + h.
+//
+// Same tile decomposition and the same look-back as newton_iter_kernel, with one
+// carry-record slot per iteration: tile t at iteration k waits only for tile
+// t-1 at iteration k, and tile t-1 never waits for tile t, so a tile may run
+// ahead by any number of iterations and every wait ends.
+//
+// The state that enters a chunk, h_{l0-1}, belongs to another lane; it is kept
+// up to date without any exchange because the delta that enters the chunk IS the
+// update of that state: h^k_{l0-1} = h^{k-1}_{l0-1} + delta^k_{l0-1}.
+#pragma once
+#include "scan_kernels.h"
+
+namespace pararnn {
+
+constexpr int kMaxFused = 8;    // iterations one fused launch may run
+
+struct FusedArgs {
+    ScanGeom g;
+    const float *params;
+    const void *u;
+    const void *h0;
+    void *h;                 // out [B][L][S][H] in storage type
+    unsigned long long *rec; // [n_iters][n_groups][n_lt][NW][CW]
+    size_t rec_stride;       // words per iteration
+    unsigned int *gmaxk;     // [kMaxFused] max |delta| bits per iteration (zeroed by the reset kernel)
+    Ctrl *ctrl;
+    int *iters_out;
+    float *trace;
+    int n_iters;
+};
+
+template <class Cell, int VEC, int LL, int C, int W, typename UT>
+__global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs a)
+{
+    constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR;
+    constexpr int LPS = kWave / LL, CW = LPS * VEC, NW = SS + 2 * S, T = C * LL * W;
+    __shared__ float s_A[W][SS][CW];
+    __shared__ float s_b[W][S][CW];
+    __shared__ float s_carry[S][CW];
+    __shared__ unsigned int s_maxk[kMaxFused];
+    __shared__ unsigned int s_ticket;
+
+    Ctrl *ctrl = a.ctrl;
+    const ScanGeom &g = a.g;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int seg = lane / LPS, col = (lane % LPS) * VEC;
+    const UT *u = static_cast<const UT *>(a.u);
+    UT *hout = static_cast<UT *>(a.h);
+    const int K = a.n_iters;
+    bool internal_error = false;
+    if (threadIdx.x < kMaxFused) s_maxk[threadIdx.x] = 0u;
+
+    for (;;) {
+        if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+        __syncthreads();
+        const unsigned int t = __builtin_amdgcn_readfirstlane(s_ticket);
+        if (t >= (unsigned int)g.n_tiles) break;
+        const int grp = (int)(t % (unsigned int)g.n_groups), lt = (int)(t / (unsigned int)g.n_groups);
+        const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
+        const int ch = cg * CW + col;
+        const bool ch_ok = ch < g.H;
+        const int l0 = lt * T + (w * LL + seg) * C;
+        const size_t seq = (size_t)b * g.L;
+        const int wl = lt * T + w * (LL * C);
+        const unsigned int Hn = (unsigned int)g.H;
+        const size_t row_w = seq + (size_t)wl;
+        const buf_rsrc ru = make_rsrc(u + row_w * G * Hn + (size_t)cg * CW);
+        const buf_rsrc rho = make_rsrc(hout + row_w * S * Hn + (size_t)cg * CW);
+        const unsigned int vu = ((unsigned int)(seg * (C * G)) * Hn + col) * (unsigned int)sizeof(UT);
+        const unsigned int vh = ((unsigned int)(seg * (C * S)) * Hn + col) * (unsigned int)sizeof(UT);
+        const bool full_tile = (lt + 1) * T <= g.L && (cg + 1) * CW <= g.H;
+
+        float p[VEC][PR];
+#pragma unroll
+        for (int r = 0; r < PR; ++r) {
+            float tmp[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) tmp[v] = 0.0f;
+            if (ch_ok) load_vec<VEC>(a.params + (size_t)r * g.H + ch, tmp);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+        }
+
+        // ---- u for the C steps of this thread (kept for all iterations), the row before, h0
+        using RawU = typename RawVec<UT, VEC>::type;
+        RawU uur[C][G], uhalo[G];
+        auto load_inputs = [&](auto guard) {
+            constexpr bool kGuard = decltype(guard)::value;
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                const bool ok = !kGuard || (ch_ok && l < g.L);
+#pragma unroll
+                for (int q = 0; q < G; ++q) {
+                    if constexpr (!kGuard) uur[i][q] = buf_load<UT, VEC>(ru, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT));
+                    else if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
+                    else uur[i][q] = zero_raw<UT, VEC>();
+                }
+            }
+        };
+        if (full_tile) load_inputs(std::false_type{});
+        else load_inputs(std::true_type{});
+#pragma unroll
+        for (int q = 0; q < G; ++q) {
+            uhalo[q] = zero_raw<UT, VEC>();
+            if (ch_ok && l0 > 0 && l0 <= g.L) uhalo[q] = load_raw<UT, VEC>(u + ((seq + l0 - 1) * G + q) * Hn + ch);
+        }
+        float h0v[S][VEC], hprev[S][VEC];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) h0v[s][v] = 0.0f;
+            if (ch_ok && a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, h0v[s]);
+        }
+
+        // ---- initial guess h^0_l = f(h0, u_l) (App. A) for the own steps and for the row before the chunk
+        float uu[C][G][VEC], ho[C][S][VEC];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+#pragma unroll
+            for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu[i][q]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float h1[S], ug[G], F0[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
+#pragma unroll
+                for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                Cell::step(p[v], h1, ug, F0);
+#pragma unroll
+                for (int s = 0; s < S; ++s) ho[i][s][v] = F0[s];
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) hprev[s][v] = h0v[s][v];
+        if (l0 > 0) {
+            float uh[G][VEC];
+#pragma unroll
+            for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uhalo[q], uh[q]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float h1[S], ug[G], F0[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
+#pragma unroll
+                for (int q = 0; q < G; ++q) ug[q] = uh[q][v];
+                Cell::step(p[v], h1, ug, F0);
+#pragma unroll
+                for (int s = 0; s < S; ++s) hprev[s][v] = F0[s];
+            }
+        }
+
+#pragma unroll 1
+        for (int k = 1; k <= K; ++k) {
+            const unsigned int epoch = (unsigned int)k;
+            unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
+
+            // ---- thread level
+            float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                set_identity<S>(accA[v]);
+#pragma unroll
+                for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                if (l0 + i < g.L) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float J[SS], r[S], hp[S], ug[G], F[S];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
+#pragma unroll
+                        for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                        Cell::fwd(p[v], hp, ug, F, J);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
+                        push_step<S>(J, r, accA[v], accB[v]);
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
+                }
+            }
+
+            // ---- wave level
+            float lexA[VEC][SS], lexB[VEC][S];
+            if constexpr (LL > 1) {
+#pragma unroll
+                for (int d = 1; d < LL; d <<= 1) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float pA[SS], pB[S];
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) pA[e] = __shfl_up(accA[v][e], d * LPS, 64);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) pB[s] = __shfl_up(accB[v][s], d * LPS, 64);
+                        if (seg >= d) compose_after<S>(pA, pB, accA[v], accB[v]);
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) lexA[v][e] = __shfl_up(accA[v][e], LPS, 64);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) lexB[v][s] = __shfl_up(accB[v][s], LPS, 64);
+                    if (seg == 0) {
+                        set_identity<S>(lexA[v]);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) lexB[v][s] = 0.0f;
+                    }
+                }
+            }
+
+            // ---- workgroup level
+            if (seg == LL - 1) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) s_A[w][e][col + v] = accA[v][e];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) s_b[w][s][col + v] = accB[v][s];
+                }
+            }
+            __syncthreads();
+            float exA[VEC][SS], exB[VEC][S];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                set_identity<S>(exA[v]);
+#pragma unroll
+                for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
+            }
+            const int upto = w == 0 ? W : w;
+            for (int j = 0; j < upto; ++j) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float Aj[SS], bj[S];
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][col + v];
+                    push_step<S>(Aj, bj, exA[v], exB[v]);
+                }
+            }
+            if (w == 0) {
+                // ---- grid level: look-back within this iteration's record slot
+                float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                    for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
+                    set_identity<S>(exA[v]);
+                }
+                const bool active = seg == 0;
+                const bool has_next = lt + 1 < g.n_lt;
+                rec_t *rec = reck + ((size_t)grp * g.n_lt + lt) * (NW * CW);
+                if (lt > 0) {
+                    if (has_next) {
+                        float ab[SS + S][VEC];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) ab[e][v] = tileA[e][v];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
+                        }
+                        publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
+                    }
+                    if (!lookback<S, VEC, CW>(reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
+                        internal_error = true;
+                }
+                if (has_next) {
+                    float inc[S][VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float A1[SS], x[S], b1[S], y[S];
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) A1[e] = tileA[e][v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
+                        affine<S>(A1, x, b1, y);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) inc[s][v] = y[s];
+                    }
+                    publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
+                }
+                if (active) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
+                }
+            }
+            __syncthreads();
+
+            // ---- back-substitution; the delta entering the chunk also updates the state before it
+            unsigned int wmax_bits = 0u;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float cin[S], din[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
+                affine<S>(exA[v], cin, exB[v], din);
+                if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
+#pragma unroll
+                for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    float d[S];
+                    affine<S>(PA[i][v], din, qb[i][v], d);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) {
+                        ho[i][s][v] += d[s];
+                        if (ch_ok && l0 + i < g.L) wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
+                    }
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) wmax_bits = max(wmax_bits, (unsigned int)__shfl_xor((int)wmax_bits, off, 64));
+            if (lane == 0) atomicMax(&s_maxk[k - 1], wmax_bits);
+            // s_A / s_carry are rewritten only after the next iteration's first barrier
+        }
+
+        // ---- the result, once
+        if (full_tile) {
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+                    buf_store<UT, VEC>(rho, vh, (unsigned int)(i * S + s) * Hn * (unsigned int)sizeof(UT), ho[i][s]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const int l = l0 + i;
+                if (ch_ok && l < g.L) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) store_vec<VEC>(hout + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                }
+            }
+        }
+    }
+
+    // ---- per-iteration maxima; the last workgroup writes the results
+    if (internal_error && lane == 0) atomicExch(&ctrl->status, kStInternal);
+    __syncthreads();
+    if ((int)threadIdx.x < K) atomicMax(&a.gmaxk[threadIdx.x], s_maxk[threadIdx.x]);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const unsigned int prev = atomicAdd(&ctrl->done, 1u);
+        if (prev == gridDim.x - 1) {
+            __threadfence();
+            int status = atomicAdd(&ctrl->status, 0) == kStInternal ? kStInternal : kStOk;
+            int iters = K;
+            for (int k = 0; k < K; ++k) {
+                const float mk = __uint_as_float(atomicMax(&a.gmaxk[k], 0u));
+                if (a.trace) a.trace[k] = mk;
+                if (status == kStOk && !(mk - mk == 0.0f)) { status = kStNonFinite; iters = k + 1; }
+            }
+            a.iters_out[0] = iters;
+            a.iters_out[1] = status;
+            ctrl->iters = iters;
+            ctrl->status = status;
+            ctrl->stop = 1;
+            ctrl->ticket = 0u;
+            ctrl->done = 0u;
+            __threadfence();
+        }
+    }
+}
+
+}  // namespace pararnn

@@ -1,7 +1,7 @@
 // Host-side launch interface between the C ABI and the per-cell kernel
 // instantiations (each cell / storage type is compiled in its own file).
 #pragma once
-#include "scan_kernels.h"
+#include "fused_kernels.h"
 
 namespace pararnn {
 
@@ -27,6 +27,8 @@ template <class Cell, typename UT> struct Kernels {
     // fold_guess: this is iteration 1 and the initial guess is computed inside it
     static hipError_t newton_iter(const TileCfg &cfg, const FwdArgs &a, bool fold_guess, hipStream_t st);
     static hipError_t backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st);
+    // all iterations of a fixed-count solve in one launch
+    static hipError_t newton_fused(const TileCfg &cfg, const FusedArgs &a, hipStream_t st);
 };
 
 hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0,

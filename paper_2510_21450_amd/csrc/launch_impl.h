@@ -66,6 +66,27 @@ hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, 
 }
 
 template <class Cell, typename UT>
+hipError_t Kernels<Cell, UT>::newton_fused(const TileCfg &cfg, const FusedArgs &a, hipStream_t st)
+{
+    if constexpr (IsRaw<Cell>::value) {
+        return hipErrorInvalidValue;
+    } else {
+#define PARARNN_CASE(V, LLv, C, W)                                                             \
+    if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
+        static int grid_cap = 0;                                                               \
+        auto kern = newton_fused_kernel<Cell, V, LLv, C, W, UT>;                               \
+        if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);               \
+        const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                      \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
+        return hipGetLastError();                                                              \
+    }
+        PARARNN_SHAPES(PARARNN_CASE)
+#undef PARARNN_CASE
+        return hipErrorInvalidValue;
+    }
+}
+
+template <class Cell, typename UT>
 hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st)
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \

@@ -30,6 +30,9 @@ bool cell_info(int cell, CellInfo *ci)
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// process-wide switch for the one-launch path of fixed-count solves (pararnn_set_fused)
+int g_fused_enabled = 1;
+
 // process-wide tile-shape override: {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
 int g_tile_override[4] = {-1, 0, 0, 0};
 
@@ -39,7 +42,7 @@ int g_tile_override[4] = {-1, 0, 0, 0};
 // forward) with 128..256-byte row segments and 128..256 steps per tile.
 // PARARNN_TILE="vec,ll,c,w" or pararnn_set_tile() overrides it (tuning aid; the
 // combination must be one that is compiled in and allowed by H and alignment).
-TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_elems)
+TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_elems, bool fused = false)
 {
     int vmax = 1;
     if (H % 4 == 0 && align_elems >= 4) vmax = 4;
@@ -50,6 +53,10 @@ TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_el
         cfg = {1, 8, 4, 2};                              // 8 channels x 64 steps
     } else if (H <= 32) {
         cfg = {1, 2, 8, 8};
+    } else if (fused) {
+        // the one-launch path is bound by vector arithmetic, not by HBM: shorter tiles, more workgroups per CU
+        if (lstm) cfg = {1, 1, 8, 16};
+        else cfg = {1, 1, 8, 8};                         // 64 channels x 64 steps
     } else if (!backward) {
         if (lstm) cfg = {1, 1, 8, 16};                   // 64 channels x 128 steps
         else if (bf && vmax >= 2) cfg = {2, 2, 8, 8};    // 64 channels x 128 steps
@@ -82,10 +89,11 @@ struct Layout {
 
 // Workspace: [Ctrl | carry records | boundary rows | fp32 iterate (bf16 forward) |
 // parameter-gradient partials (backward)]
-Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems)
+Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems,
+                   bool fused = false)
 {
     Layout lo;
-    lo.cfg = choose_tile(cell_kind, dtype, backward, H, align_elems);
+    lo.cfg = choose_tile(cell_kind, dtype, backward, H, align_elems, fused);
     const int CW = (kWave / lo.cfg.ll) * lo.cfg.vec, T = lo.cfg.c * lo.cfg.ll * lo.cfg.w;
     ScanGeom &g = lo.g;
     g.B = B; g.L = L; g.H = H; g.T = T;
@@ -131,12 +139,28 @@ int align_elems(size_t esz, std::initializer_list<const void *> ptrs)
 
 template <class Cell>
 int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hipStream_t st, void *h,
-                 int status0, int max_iter)
+                 int status0, int max_iter, bool fused)
 {
     char *ws = reinterpret_cast<char *>(a.ctrl);
-    hipError_t e = launch_reset(a.ctrl, a.rec, lo.n_rec, a.iters_out, status0, st);
-    if (e != hipSuccess) return PARARNN_HIP_ERROR;
     const bool bf = dtype == PARARNN_BF16;
+    hipError_t e;
+    // fixed iteration count (tol < 0): all iterations in one launch when the workspace holds one
+    // carry-record slot per iteration
+    if (fused) {
+        e = launch_reset(a.ctrl, a.rec, lo.n_rec * (size_t)max_iter, a.iters_out, status0, st);
+        if (e != hipSuccess) return PARARNN_HIP_ERROR;
+        FusedArgs f;
+        memset(&f, 0, sizeof(f));
+        f.g = a.g; f.params = a.params; f.u = a.u; f.h0 = a.h0; f.h = h;
+        f.rec = a.rec; f.rec_stride = lo.n_rec;
+        f.gmaxk = reinterpret_cast<unsigned int *>(ws + 64);
+        f.ctrl = a.ctrl; f.iters_out = a.iters_out; f.trace = a.trace; f.n_iters = max_iter;
+        e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
+        if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+        return PARARNN_OK;
+    }
+    e = launch_reset(a.ctrl, a.rec, lo.n_rec, a.iters_out, status0, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
     a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
     if (max_iter == 0) {
         // only the initial guess is asked for; otherwise iteration 1 computes it on the fly
@@ -227,6 +251,26 @@ size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int bac
     return need;
 }
 
+size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, int n_iters)
+{
+    CellInfo ci;
+    if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
+    if (cell == PARARNN_TANH_DENSE || n_iters < 1 || n_iters > kMaxFused) return pararnn_workspace_bytes(cell, dtype, B, L, H, 0);
+    size_t need = pararnn_workspace_bytes(cell, dtype, B, L, H, 0);
+    for (int al = 1; al <= 4; al *= 2) {
+        const Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al, true);
+        const size_t fused = lo.off_rec + round256(lo.n_rec * (size_t)n_iters * sizeof(unsigned long long));
+        if (fused > need) need = fused;
+    }
+    return need;
+}
+
+int pararnn_set_fused(int enable)
+{
+    g_fused_enabled = enable ? 1 : 0;
+    return PARARNN_OK;
+}
+
 int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
                     int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
                     size_t workspace_bytes, void *hip_stream)
@@ -248,8 +292,17 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     int al = align_elems(esz, {u, h, h0});
     const int alp = align_elems(4, {params});
     if (alp < al) al = alp;
-    const Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al);
-    if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    // a fixed-count solve (tol < 0) runs in one launch when the workspace holds a record slot per iteration
+    Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al);
+    bool fused = false;
+    if (tol < 0.0f && max_iter >= 1 && max_iter <= kMaxFused && g_fused_enabled) {
+        const Layout lf = make_layout(cell, ci, dtype, B, L, H, false, al, true);
+        if (workspace_bytes >= lf.off_rec + round256(lf.n_rec * (size_t)max_iter * sizeof(unsigned long long))) {
+            lo = lf;
+            fused = true;
+        }
+    }
+    if (!fused && workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
     FwdArgs a;
     memset(&a, 0, sizeof(a));
@@ -261,10 +314,10 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     a.iters_out = iters; a.trace = delta_trace;
     a.k = 0; a.max_iter = max_iter; a.tol = tol;
     switch (cell) {
-    case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
-    case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
-    case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
-    case PARARNN_PARALSTM_DIAG: return forward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter);
+    case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
+    case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
+    case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
+    case PARARNN_PARALSTM_DIAG: return forward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
     }
     return PARARNN_INVALID_ARG;
 }

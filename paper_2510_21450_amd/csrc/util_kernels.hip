@@ -9,9 +9,10 @@ namespace pararnn {
 __global__ void reset_kernel(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 64) reinterpret_cast<unsigned int *>(ctrl)[i] = 0u;     // the whole 256-byte control block
+    __syncthreads();
     if (i == 0) {
-        ctrl->ticket = 0u; ctrl->done = 0u; ctrl->gmax_bits = 0u;
-        ctrl->stop = 0; ctrl->iters = 0; ctrl->status = status0;
+        ctrl->status = status0;
         if (iters_out) { iters_out[0] = 0; iters_out[1] = status0; }
     }
     for (size_t j = i; j < n_rec; j += (size_t)gridDim.x * blockDim.x) rec[j] = 0ull;

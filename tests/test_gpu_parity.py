@@ -204,6 +204,43 @@ def test_every_tile_shape(P, oracle_mod, cell, tile):
     assert relerr(to_np(dh0), rdh0) <= TOL_F32
 
 
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fixed_count_solve_in_one_launch(P, oracle_mod, cell, dtype):
+    """tol < 0 (the paper's fixed N_its): all iterations in one launch must give
+    the oracle's iterate K, and the same iterate as one launch per iteration."""
+    B, L, H = 2, 700, 100
+    params, u, h0, _ = problem(cell, B, L, H, seed=2024, dtype=dtype)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    bound = 2e-5 if dtype == torch.float32 else TOL_BF16
+    for tile in [None, (1, 2, 8, 8), (2, 2, 8, 8), (1, 1, 4, 8)]:
+        for K in (1, 2, 3, 5, 8):
+            print(f"fused {cell} {dtype} tile={tile} K={K}", flush=True)
+            try:
+                if tile:
+                    P.set_tile(*tile)
+                assert P.workspace_bytes_fused(cell, dtype, B, L, H, K) >= P.workspace_bytes(cell, dtype, B, L, H)
+                hf, it_f, tr_f = P.forward(cell, params, u, h0, tol=-1.0, max_iter=K, trace=True)
+                P.set_fused(False)
+                hi, it_i, tr_i = P.forward(cell, params, u, h0, tol=-1.0, max_iter=K, trace=True)
+                torch.cuda.synchronize()
+            finally:
+                P.set_fused(True)
+                P.set_tile(0)
+            hk, _, _, trk = oracle_mod.newton(cell, pn, un, h0n, tol=-1.0, max_iter=K)
+            assert tuple(int(x) for x in it_f.cpu()) == (K, 0) == tuple(int(x) for x in it_i.cpu())
+            assert relerr(to_np(hf), hk) <= bound
+            assert relerr(to_np(hf), to_np(hi)) <= (2e-6 if dtype == torch.float32 else 1e-2)
+            got = tr_f.cpu().numpy()[:K]
+            for k in range(K):
+                if trk[k] > 1e-4:
+                    assert abs(got[k] - trk[k]) <= 2e-3 * trk[k], (k, got, trk)
+    # a NaN in the input is reported with the first iteration it shows up in
+    u2 = u.clone(); u2[0, 3, 0, 0] = float("nan")
+    _, it, _ = P.forward(cell, params, u2, h0, tol=-1.0, max_iter=3)
+    assert tuple(int(x) for x in it.cpu()) == (1, 5)
+
+
 @pytest.mark.parametrize("kind", ["diag", "block2"])
 @pytest.mark.parametrize("reverse", [False, True])
 def test_affine_scan_matches_forward_substitution(P, oracle_mod, kind, reverse):
