@@ -1,0 +1,89 @@
+"""The library only enqueues work: a forward solve and a backward pass can be
+recorded into a HIP graph (no host synchronisation, no allocation, no memset
+node inside) and replayed, and they run correctly on a non-default stream."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
+
+
+def f64(t):
+    return t.detach().to("cpu", torch.float64).numpy()
+
+
+def relerr(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def test_forward_and_backward_replay_from_a_graph(oracle_mod):
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2"].scaled(B=2, L=600, H=192)
+    G, S = cell_dims(w.cell)
+    d = make_inputs(w, device="cuda")
+    params, u, g = d["params"], d["u"], d["g"]
+    ws_f = torch.empty(P.workspace_bytes(w.cell, u.dtype, w.B, w.L, w.H), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(P.workspace_bytes(w.cell, u.dtype, w.B, w.L, w.H, True), dtype=torch.uint8, device="cuda")
+    h = torch.empty((w.B, w.L, S, w.H), device="cuda")
+    outs = (torch.empty_like(u), torch.empty_like(params), torch.empty((w.B, S, w.H), device="cuda"))
+    # eager reference
+    h_e, it_e, _ = P.forward(w.cell, params, u, None, tol=w.tol, max_iter=16, workspace=ws_f)
+    du_e, dp_e, dh0_e = P.backward(w.cell, params, u, None, h_e, g, workspace=ws_b)
+    torch.cuda.synchronize()
+    it_e = it_e.cpu().clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            _, iters, _ = P.forward(w.cell, params, u, None, tol=w.tol, max_iter=16, workspace=ws_f, out=h)
+            P.backward(w.cell, params, u, None, h, g, workspace=ws_b, out=outs)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        # clobber the outputs, do unrelated eager work, then replay
+        h.fill_(float("nan")); outs[0].zero_(); outs[1].zero_(); outs[2].zero_(); iters.zero_()
+        _ = (u.float() * 2).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(iters.cpu(), it_e), rep
+        assert torch.equal(h, h_e), rep
+        assert torch.equal(outs[0], du_e) and torch.equal(outs[2], dh0_e), rep
+        assert torch.equal(outs[1], dp_e), rep            # fixed-order reduction: bit-reproducible
+    ref = oracle_mod.seq_unroll(w.cell, f64(params), f64(u), None)
+    assert relerr(f64(h), ref) <= 1e-5
+
+
+def test_runs_on_a_side_stream(oracle_mod):
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C3"].scaled(B=2, L=300, H=96)
+    d = make_inputs(w, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        h, iters, _ = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=32)
+        du, dp, dh0 = P.backward(w.cell, d["params"], d["u"], None, h, d["g"])
+    s.synchronize()
+    assert int(iters.cpu()[1]) == 0
+    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), None)
+    assert relerr(f64(h), ref) <= 1e-5
+    rdu, rdp, rdh0 = oracle_mod.backward(w.cell, f64(d["params"]), f64(d["u"]), None, f64(h), f64(d["g"]))
+    assert relerr(f64(du), rdu) <= 1e-5 and relerr(f64(dp), rdp) <= 1e-5
+
+
+def test_repeated_calls_share_a_workspace_and_are_bit_reproducible():
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2"].scaled(B=3, L=1000, H=200)
+    d = make_inputs(w, device="cuda")
+    ws = torch.empty(P.workspace_bytes(w.cell, d["u"].dtype, w.B, w.L, w.H), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xAB)           # the workspace needs no initialisation
+    first = None
+    for rep in range(4):
+        h, iters, tr = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=32, trace=True, workspace=ws)
+        torch.cuda.synchronize()
+        cur = (h.clone(), iters.cpu().clone(), tr.cpu().clone())
+        if first is None:
+            first = cur
+        else:
+            assert torch.equal(cur[0], first[0]) and torch.equal(cur[1], first[1]) and torch.equal(cur[2], first[2])
