@@ -156,6 +156,54 @@ def test_iteration_control_edge_cases(P, oracle_mod):
     assert torch.equal(ha, hb)
 
 
+def _misaligned(t, elems=1):
+    """A contiguous copy of t whose data pointer is off by `elems` elements from the allocation."""
+    flat = torch.empty(t.numel() + elems, dtype=t.dtype, device=t.device)
+    out = flat[elems:].view(t.shape)
+    out.copy_(t)
+    assert out.is_contiguous() and out.data_ptr() % 16 != 0
+    return out
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_pointers_without_vector_alignment(P, oracle_mod, dtype):
+    """Buffers that are only element-aligned (and an H that allows no vector
+    width) must still work: the library falls back to narrower accesses."""
+    cell = "gru_diag"
+    bound = TOL_F32 if dtype == torch.float32 else TOL_BF16
+    for H in (64, 66, 67):
+        params, u, h0, g = problem(cell, 2, 150, H, seed=31 + H, dtype=dtype)
+        pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+        try:
+            P.set_tile(2, 2, 8, 8)       # asks for 2 channels per lane; refused silently when not allowed
+            um, h0m, gm, pm = _misaligned(u), _misaligned(h0), _misaligned(g), _misaligned(params)
+            h, iters, _ = P.forward(cell, pm, um, h0m, tol=1e-5, max_iter=40)
+            du, dp, dh0 = P.backward(cell, pm, um, h0m, h, gm)
+            torch.cuda.synchronize()
+        finally:
+            P.set_tile(0)
+        assert int(iters.cpu()[1]) == 0
+        ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+        assert relerr(to_np(h), ref) <= bound
+        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+        assert relerr(to_np(du), rdu) <= bound and relerr(to_np(dp), rdp) <= bound and relerr(to_np(dh0), rdh0) <= bound
+
+
+def test_many_short_sequences_and_one_long(P, oracle_mod):
+    """Extreme aspect ratios: B*H large with tiny L, and one long sequence with few channels."""
+    for cell, (B, L, H) in (("gru_diag", (300, 3, 40)), ("lstm_diag", (1, 20000, 8)), ("paralstm_diag", (64, 1, 130))):
+        params, u, h0, g = problem(cell, B, L, H, seed=B + L)
+        h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
+        du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+        torch.cuda.synchronize()
+        assert int(iters.cpu()[1]) == 0
+        pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+        ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+        assert relerr(to_np(h), ref) <= TOL_F32, (cell, B, L, H)
+        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+        assert relerr(to_np(du), rdu) <= TOL_F32 and relerr(to_np(dp), rdp) <= TOL_F32 and relerr(to_np(dh0), rdh0) <= TOL_F32
+
+
 def test_invalid_arguments_are_rejected(P):
     params, u, h0, _ = problem("gru_diag", 1, 8, 8, seed=3)
     with pytest.raises(RuntimeError, match="INVALID_ARG"):
