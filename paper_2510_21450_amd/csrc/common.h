@@ -34,13 +34,11 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short v)
     return __uint_as_float(((unsigned int)v) << 16);
 }
 
-// round to nearest, ties to even; NaN stays NaN
+// round to nearest, ties to even; NaN stays NaN.  gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32, two values per instruction).
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
 {
-    unsigned int x = __float_as_uint(f);
-    if ((x & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((x >> 16) | 0x40u);
-    x += 0x7fffu + ((x >> 16) & 1u);
-    return (unsigned short)(x >> 16);
+    return __builtin_bit_cast(unsigned short, (__bf16)f);
 }
 
 // ------------------------------------------------------ vectors of VEC channels
@@ -183,6 +181,7 @@ __device__ __forceinline__ float fast_tanh(float x)
     // 1 - 2 / (1 + e^{2x}); absolute error ~1e-7 everywhere
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
 }
+
 
 // max that keeps a NaN once seen (fmaxf would drop it)
 __device__ __forceinline__ float nanmax(float m, float a) { return (a > m || a != a) ? a : m; }
