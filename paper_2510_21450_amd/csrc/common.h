@@ -182,6 +182,14 @@ __device__ __forceinline__ float fast_tanh(float x)
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
 }
 
+// Workgroup barrier that orders LDS accesses only: global loads and stores
+// issued before it stay in flight (a full __syncthreads() waits for them).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // max that keeps a NaN once seen (fmaxf would drop it)
 __device__ __forceinline__ float nanmax(float m, float a) { return (a > m || a != a) ? a : m; }

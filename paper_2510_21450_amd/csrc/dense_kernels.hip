@@ -9,9 +9,9 @@
 //   sweep (local)    b_c = solution at the chunk's end for a zero input
 //   carry            x_c = A_c x_{c-1} + b_c, sequential over the chunks of a sequence
 //   sweep (final)    delta_l = J_l delta_{l-1} + r_l from x_{c-1}; h += delta; max|delta|
-// The sweeps batch 32 sequences per wave so that the mat-vecs W delta of
-// different sequences become one MFMA product W [delta_b]; the per-sequence
-// factor d_l is applied to the product afterwards.
+// The sweeps batch 16 (sequence, chunk) columns per workgroup so that the
+// mat-vecs W delta of different columns become one MFMA product W [delta];
+// the per-column factor d_l is applied to the product afterwards.
 //
 // MFMA operand trick: the 32x32 accumulator layout (lane = column, register v
 // of lane half h = row 8*(v/4) + 4*h + v%4) is used unchanged as the B operand
@@ -34,6 +34,7 @@ namespace {
 constexpr int DH = 64;          // hidden size this path is built for
 constexpr int CD = 16;          // timesteps per chunk
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 struct DenseArgs {
     const float *W;      // [64][64] row-major
@@ -64,7 +65,11 @@ __device__ __forceinline__ void load_w_operand(const float *W, int lane, float (
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) wr[mt][kt][v] = W[(32 * mt + n) * DH + 32 * kt + mfma_row(v, half)];
+            for (int g = 0; g < 4; ++g) {
+                // rows(4g .. 4g+3, half) are four consecutive columns of W
+                const float4 t = *reinterpret_cast<const float4 *>(W + (32 * mt + n) * DH + 32 * kt + 8 * g + 4 * half);
+                wr[mt][kt][4 * g] = t.x; wr[mt][kt][4 * g + 1] = t.y; wr[mt][kt][4 * g + 2] = t.z; wr[mt][kt][4 * g + 3] = t.w;
+            }
 }
 
 // ---------------------------------------------------------------- residual
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
 // A_c = J_e ... J_{s+1} J_s with J_l = diag(d_l) W, one wave per (b, chunk).
 // Chunk 0 and the last chunk are skipped: nothing enters chunk 0 (delta_0 = 0)
 // and nothing follows the last one.
-__global__ __launch_bounds__(256) void dense_chunk_products_kernel(const DenseArgs a)
+__global__ __launch_bounds__(256, 2) void dense_chunk_products_kernel(const DenseArgs a)
 {
     if (a.ctrl->stop) return;
     const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
@@ -148,13 +153,13 @@ __global__ __launch_bounds__(256) void dense_chunk_products_kernel(const DenseAr
     const int per_seq = a.n_c - 2;
     if (per_seq <= 0 || item >= a.B * per_seq) return;
     const int b = item / per_seq, c = 1 + item % per_seq;
-    const int ls = c * CD, le = min(a.L, ls + CD);
+    const int ls = c * CD, n_steps = min(a.L, ls + CD) - ls;
 
     float wr[2][2][16];
     load_w_operand(a.W, lane, wr);
 
     // P = J_ls in accumulator layout: P[mt][nt][v] = d[row] W[row][32 nt + n]
-    f16v P[2][2];
+    f16v P[2][2], Q[2][2];
     const float *dl = a.d + ((size_t)b * a.L + ls) * DH;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -165,51 +170,49 @@ __global__ __launch_bounds__(256) void dense_chunk_products_kernel(const DenseAr
             P[mt][0][v] = dv * a.W[row * DH + n];
             P[mt][1][v] = dv * a.W[row * DH + 32 + n];
         }
-    // the row factors d_l of all later steps up front, so that the product loop never waits on memory
-    float dpre[CD][2];
-#pragma unroll
-    for (int i = 1; i < CD; ++i) {
-        const bool ok = ls + i < le;
-        dpre[i][0] = ok ? dl[i * DH + n] : 0.0f;
-        dpre[i][1] = ok ? dl[i * DH + 32 + n] : 0.0f;
-    }
-#pragma unroll 1
-    for (int i = 1; i < CD; ++i) {
-        if (ls + i >= le) break;
-        float d0 = 0.0f, d1 = 0.0f;
-#pragma unroll
-        for (int q = 1; q < CD; ++q)
-            if (q == i) { d0 = dpre[q][0]; d1 = dpre[q][1]; }
-        f16v Q[2][2];
+    // dst = diag(d) W src.  The two products alternate between P and Q, so no
+    // accumulator is ever copied: the result of one step is the B operand of the next.
+    auto compose = [&](const f16v(&src)[2][2], f16v(&dst)[2][2], float d0, float d1) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) Q[mt][nt][v] = 0.0f;
+                for (int v = 0; v < 16; ++v) dst[mt][nt][v] = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float a0 = wr[0][kt][v] * d0, a1 = wr[1][kt][v] * d1;
-                const float b0 = P[kt][0][v], b1 = P[kt][1][v];
-                Q[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, Q[0][0], 0, 0, 0);
-                Q[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, Q[0][1], 0, 0, 0);
-                Q[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, Q[1][0], 0, 0, 0);
-                Q[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, Q[1][1], 0, 0, 0);
+                const float b0 = src[kt][0][v], b1 = src[kt][1][v];
+                dst[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, dst[0][0], 0, 0, 0);
+                dst[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, dst[0][1], 0, 0, 0);
+                dst[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, dst[1][0], 0, 0, 0);
+                dst[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, dst[1][1], 0, 0, 0);
             }
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) P[mt][nt] = Q[mt][nt];
+    };
+    // row factors of the next two steps are fetched while the current two run
+    // (indices clamped to the chunk: the extra values are never used)
+    auto dload = [&](int i, int hi) { return dl[min(i, n_steps - 1) * DH + 32 * hi + n]; };
+    float da0 = dload(1, 0), da1 = dload(1, 1), db0 = dload(2, 0), db1 = dload(2, 1);
+    int i = 1;
+#pragma unroll 1
+    for (; i + 1 < n_steps; i += 2) {
+        const float na0 = dload(i + 2, 0), na1 = dload(i + 2, 1), nb0 = dload(i + 3, 0), nb1 = dload(i + 3, 1);
+        compose(P, Q, da0, da1);
+        compose(Q, P, db0, db1);
+        da0 = na0; da1 = na1; db0 = nb0; db1 = nb1;
     }
+    const bool odd = i < n_steps;                 // one step left: the result ends up in Q
+    if (odd) compose(P, Q, da0, da1);
     float *out = a.Ac + ((size_t)b * a.n_c + c) * DH * DH;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) out[(32 * mt + mfma_row(v, half)) * DH + 32 * nt + n] = P[mt][nt][v];
+            for (int v = 0; v < 16; ++v)
+                out[(32 * mt + mfma_row(v, half)) * DH + 32 * nt + n] = odd ? Q[mt][nt][v] : P[mt][nt][v];
 }
 
 // The last workgroup of the final sweep closes the iteration: stopping test,
@@ -240,175 +243,161 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 }
 
 // -------------------------------------------------------------------- sweeps
-// X <- diag(d_l) (W X) + r_l over the steps of one chunk for 32 sequences at
-// once: X is 64 channels x 32 sequences in accumulator layout (2 row tiles).
-// final = 0: X starts at 0, only the end value is kept (b_c).
-// final = 1: X starts at x_{c-1}; every step updates h and feeds max|delta|.
+// x <- diag(d_l) (W x) + r_l over the CD steps of a chunk.  The chain is
+// sequential, so what counts is the latency of one step; every (sequence,
+// chunk) pair is an independent column, and one workgroup advances 16 columns
+// with the 64 x 64 x 16 product of a step split over its four waves: wave w
+// owns rows 16w .. 16w+15 and issues 16 v_mfma_f32_16x16x4_f32.
+//
+// Operand layout: the 16x16 accumulator gives lane (n = lane % 16, g = lane / 16)
+// the rows 16w + 4g + v, v = 0..3, of column n.  Each wave drops its float4 into
+// LDS at [w][lane]; for the next step every wave reads the four float4 at
+// [ww][lane], ww = 0..3, and uses component v of wave ww's value as the B
+// operand of k-step (ww, v), whose four k-slots (one per lane group g) are then
+// the rows 16ww + 4g + v.  W is held in registers in the matching A-operand
+// order, so the exchange is one float4 write and four conflict-free float4
+// reads per step, with no index arithmetic.
+//
+// d and r of all CD steps are loaded before the chain starts; the barrier
+// between steps orders LDS only.
+// final = 0: x starts at 0, only the end value is kept (b_c).
+// final = 1: x starts at x_{c-1}; afterwards h += delta and max|delta|.
 template <int FINAL>
 __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
 {
+    __shared__ f4v s_x[2][4][64];
     __shared__ float s_max[4];
     if (a.ctrl->stop) return;
-    const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5, w = threadIdx.x >> 6;
-    const int n_bt = (a.B + 31) / 32;
-    const int item = blockIdx.x * 4 + w;
-    float wmax = 0.0f;
-    if (item < a.n_c * n_bt) {
-        const int c = item / n_bt, bt = item - c * n_bt;
-        const int b = bt * 32 + n;
-        const bool b_ok = b < a.B;
-        const bool full = bt * 32 + 32 <= a.B;          // wave-uniform: no guards needed in the loop
-        const int ls = c * CD, le = min(a.L, ls + CD);
-        float wr[2][2][16];
-        load_w_operand(a.W, lane, wr);
-        f16v X[2];
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n = lane & 15, g = lane >> 4;
+    const int n_cols = a.B * a.n_c;
+    const int col = blockIdx.x * 16 + n;
+    const bool ok = col < n_cols;
+    const int cc = ok ? col : n_cols - 1;         // a column past the end reads valid memory and stores nothing
+    const int b = cc / a.n_c, c = cc - b * a.n_c;
+    const int ls = c * CD;
+    const int chn = 16 * w + 4 * g;               // first of this lane's four channels
+
+    // wa[ww][v] = W[16w + n][16ww + 4g + v]
+    float wa[4][4];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+    for (int ww = 0; ww < 4; ++ww) {
+        const f4v t = *reinterpret_cast<const f4v *>(a.W + (16 * w + n) * DH + 16 * ww + 4 * g);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) X[kt][v] = 0.0f;
-        if (FINAL && c > 0 && b_ok) {
-            const float *x0 = a.xc + ((size_t)b * a.n_c + (c - 1)) * DH;
+        for (int v = 0; v < 4; ++v) wa[ww][v] = t[v];
+    }
+    const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f4v dv[CD], rv[CD];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+    for (int i = 0; i < CD; ++i) {
+        const int l = ls + i;
+        const size_t off = ((size_t)b * a.L + min(l, a.L - 1)) * DH + chn;
+        dv[i] = *reinterpret_cast<const f4v *>(a.d + off);
+        rv[i] = *reinterpret_cast<const f4v *>(a.r + off);
+        if (!(ok && l < a.L)) { dv[i] = zero; rv[i] = zero; }     // steps past the end leave x = 0
+    }
+    f4v x = zero;
+    if (FINAL && ok && c > 0) x = *reinterpret_cast<const f4v *>(a.xc + ((size_t)b * a.n_c + (c - 1)) * DH + chn);
+    s_x[0][w][lane] = x;
+    lds_barrier();
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 t = *reinterpret_cast<const float4 *>(x0 + 32 * kt + 8 * g + 4 * half);
-                    X[kt][4 * g] = t.x; X[kt][4 * g + 1] = t.y; X[kt][4 * g + 2] = t.z; X[kt][4 * g + 3] = t.w;
-                }
-        }
-        // rows of an invalid lane are read from sequence B-1 (valid memory) and
-        // multiplied by zero; only stores are guarded, and only in ragged tiles
-        const size_t brow = (size_t)(b_ok ? b : a.B - 1) * a.L;
-        const float keep = b_ok ? 1.0f : 0.0f;
-        auto sweep = [&](auto guard) {
-            constexpr bool kGuard = decltype(guard)::value;
-            // d, r (and h) of the next step are fetched before the products of
-            // this step are issued, so their latency hides behind the MFMAs
-            float4 dc[8], rc[8], hc[FINAL ? 8 : 1], dn[8], rn[8], hn[FINAL ? 8 : 1];
-            auto fetch = [&](int l, float4 (&dd)[8], float4 (&rr)[8], float4 (&hh)[FINAL ? 8 : 1]) {
-                const size_t off = (brow + l) * DH;
+    for (int i = 0; i < CD; ++i) {
+        f4v acc0 = zero, acc1 = zero;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const int ch = 32 * (q >> 2) + 8 * (q & 3) + 4 * half;
-                    dd[q] = *reinterpret_cast<const float4 *>(a.d + off + ch);
-                    rr[q] = *reinterpret_cast<const float4 *>(a.r + off + ch);
-                    if constexpr (FINAL != 0) hh[q] = *reinterpret_cast<const float4 *>(a.h + off + ch);
-                }
-            };
-            fetch(ls, dc, rc, hc);
-            for (int l = ls; l < le; ++l) {
-                fetch(min(l + 1, le - 1), dn, rn, hn);
-                const size_t off = (brow + l) * DH;
-                f16v Y[2];
+        for (int ww = 0; ww < 4; ww += 2) {
+            const f4v xa = s_x[i & 1][ww][lane], xb = s_x[i & 1][ww + 1][lane];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) Y[mt][v] = 0.0f;
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        Y[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[0][kt][v], X[kt][v], Y[0], 0, 0, 0);
-                        Y[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[1][kt][v], X[kt][v], Y[1], 0, 0, 0);
-                    }
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const int mt = q >> 2, g = q & 3;
-                    const int ch = 32 * mt + 8 * g + 4 * half;
-                    float4 dv = dc[q], rv = rc[q];
-                    if constexpr (kGuard) {
-                        dv.x *= keep; dv.y *= keep; dv.z *= keep; dv.w *= keep;
-                        rv.x *= keep; rv.y *= keep; rv.z *= keep; rv.w *= keep;
-                    }
-                    const float x0 = fmaf(dv.x, Y[mt][4 * g], rv.x), x1 = fmaf(dv.y, Y[mt][4 * g + 1], rv.y);
-                    const float x2 = fmaf(dv.z, Y[mt][4 * g + 2], rv.z), x3 = fmaf(dv.w, Y[mt][4 * g + 3], rv.w);
-                    X[mt][4 * g] = x0; X[mt][4 * g + 1] = x1; X[mt][4 * g + 2] = x2; X[mt][4 * g + 3] = x3;
-                    if constexpr (FINAL != 0) {
-                        float4 hv = hc[q];
-                        hv.x += x0; hv.y += x1; hv.z += x2; hv.w += x3;
-                        if (!kGuard || b_ok) *reinterpret_cast<float4 *>(a.h + off + ch) = hv;
-                        wmax = nanmax(nanmax(nanmax(nanmax(wmax, __builtin_fabsf(x0)), __builtin_fabsf(x1)),
-                                             __builtin_fabsf(x2)), __builtin_fabsf(x3));
-                    }
-                }
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    dc[q] = dn[q]; rc[q] = rn[q];
-                    if constexpr (FINAL != 0) hc[q] = hn[q];
-                }
+            for (int v = 0; v < 4; ++v) {
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww][v], xa[v], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww + 1][v], xb[v], acc1, 0, 0, 0);
             }
-        };
-        if (full) sweep(std::false_type{});
-        else sweep(std::true_type{});
-        if (!FINAL && b_ok) {
-            float *out = a.bc + ((size_t)b * a.n_c + c) * DH;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    *reinterpret_cast<float4 *>(out + 32 * mt + 8 * g + 4 * half) =
-                        make_float4(X[mt][4 * g], X[mt][4 * g + 1], X[mt][4 * g + 2], X[mt][4 * g + 3]);
+        }
+        x = dv[i] * (acc0 + acc1) + rv[i];
+        if (FINAL) rv[i] = x;                     // delta_l, applied to h after the chain
+        if (i + 1 < CD) {
+            s_x[(i + 1) & 1][w][lane] = x;
+            lds_barrier();
         }
     }
-    if (FINAL) {
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) wmax = nanmax(wmax, __shfl_xor(wmax, off, 64));
-        if (lane == 0) s_max[w] = wmax;
-        __syncthreads();
-        if (threadIdx.x == 0)
-            finish_iteration(a, nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3])));
+    if (!FINAL) {
+        if (ok) *reinterpret_cast<f4v *>(a.bc + ((size_t)b * a.n_c + c) * DH + chn) = x;
+        return;
     }
+    float wmax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < CD; ++i) {
+        const int l = ls + i;
+        if (ok && l < a.L) {
+            f4v *hp = reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn);
+            *hp = *hp + rv[i];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) wmax = nanmax(wmax, __shfl_xor(wmax, off, 64));
+    if (lane == 0) s_max[w] = wmax;
+    __syncthreads();
+    if (threadIdx.x == 0) finish_iteration(a, nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3])));
 }
 
 // --------------------------------------------------------------------- carry
-// x_c = A_c x_{c-1} + b_c for c = 0 .. n_c-2 (x_{-1} = 0, so x_0 = b_0); one
-// wave per sequence, lane = row of A_c.  The rows of the next four chunks are
-// in flight while one is used (the chain is otherwise bound by memory latency);
-// the loop body is branch-free (indices are clamped instead) so that the loads
-// really stay outstanding; x is broadcast lane by lane (v_readlane).
-__global__ __launch_bounds__(64) void dense_carry_kernel(const DenseArgs a)
+// x_c = A_c x_{c-1} + b_c for c = 0 .. n_c-2 (x_{-1} = 0, so x_0 = b_0), one
+// workgroup per sequence.  Lane (row = lane / 4, q = lane % 4) of wave w holds
+// columns 16q .. 16q+15 of row 16w + row of A_c: sixteen FMAs against x from
+// LDS, two DPP adds across the quad, and the row's new value goes back to LDS.
+// The matrices of the next DEPTH chunks are in flight meanwhile; the loop body
+// is branch-free around the loads (indices are clamped) and its barrier orders
+// LDS only, so those loads stay outstanding across steps.
+__global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
 {
-    constexpr int DEPTH = 4;
+    constexpr int DEPTH = 8;
+    __shared__ __attribute__((aligned(16))) float s_x[2][DH];
     if (a.ctrl->stop) return;
-    const int lane = threadIdx.x, b = blockIdx.x;
-    const float *bcb = a.bc + (size_t)b * a.n_c * DH + lane;
-    float *xcb = a.xc + (size_t)b * a.n_c * DH + lane;
-    const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + lane) * DH;     // row `lane` of chunk 0
-    float x = bcb[0];
-    xcb[0] = x;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int row = 16 * w + (lane >> 2), q = lane & 3, b = blockIdx.x;
+    const float *bcb = a.bc + (size_t)b * a.n_c * DH + row;
+    float *xcb = a.xc + (size_t)b * a.n_c * DH + row;
+    const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + row) * DH + 16 * q;   // this lane's 16 columns, chunk 0
     const int last = a.n_c - 2;                       // last chunk whose end value is needed
+    {
+        const float x0 = bcb[0];
+        if (q == 0) { s_x[0][row] = x0; xcb[0] = x0; }
+    }
     if (last < 1) return;
-    float4 buf[DEPTH][DH / 4];
+    f4v buf[DEPTH][4];
     float bb[DEPTH];
 #pragma unroll
     for (int k = 0; k < DEPTH; ++k) {
         const int c = min(1 + k, last);
 #pragma unroll
-        for (int j = 0; j < DH / 4; ++j)
-            buf[k][j] = *reinterpret_cast<const float4 *>(Ab + (size_t)c * DH * DH + 4 * j);
+        for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)c * DH * DH + 4 * j);
         bb[k] = bcb[(size_t)c * DH];
     }
+    lds_barrier();
+    int cur = 0;
     for (int base = 1; base <= last; base += DEPTH) {
 #pragma unroll
         for (int k = 0; k < DEPTH; ++k) {
             const int c = base + k;
-            float s0 = bb[k], s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-            const unsigned int xb = __float_as_uint(x);
+            const f4v *xs = reinterpret_cast<const f4v *>(&s_x[cur][16 * q]);
+            f4v s = buf[k][0] * xs[0];
 #pragma unroll
-            for (int j = 0; j < DH / 4; ++j) {
-                s0 = fmaf(buf[k][j].x, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j)), s0);
-                s1 = fmaf(buf[k][j].y, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 1)), s1);
-                s2 = fmaf(buf[k][j].z, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 2)), s2);
-                s3 = fmaf(buf[k][j].w, __uint_as_float(__builtin_amdgcn_readlane(xb, 4 * j + 3)), s3);
+            for (int j = 1; j < 4; ++j) s = buf[k][j] * xs[j] + s;
+            float t = (s[0] + s[1]) + (s[2] + s[3]);
+            t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0xB1, 0xf, 0xf, false));
+            t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x4E, 0xf, 0xf, false));
+            const float xn = t + bb[k];
+            // past the last chunk nothing is written and the buffers do not flip
+            if (c <= last) {
+                if (q == 0) { s_x[cur ^ 1][row] = xn; xcb[(size_t)c * DH] = xn; }
+                cur ^= 1;
             }
-            // past the end the value is simply kept (and rewritten to the last slot)
-            x = c <= last ? (s0 + s1) + (s2 + s3) : x;
-            xcb[(size_t)min(c, last) * DH] = x;
             const int cn = min(c + DEPTH, last);
 #pragma unroll
-            for (int j = 0; j < DH / 4; ++j)
-                buf[k][j] = *reinterpret_cast<const float4 *>(Ab + (size_t)cn * DH * DH + 4 * j);
+            for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)cn * DH * DH + 4 * j);
             bb[k] = bcb[(size_t)cn * DH];
+            lds_barrier();
         }
     }
 }
@@ -485,15 +474,15 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     const int res_blocks = (int)((res_items + 3) / 4 < 512 ? (res_items + 3) / 4 : 512);
     hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
-    const int n_sweep = lo.n_c * ((B + 31) / 32);
+    const int n_sweep = (B * lo.n_c + 15) / 16;       // workgroups: 16 (sequence, chunk) columns each
     for (int k = 1; k <= max_iter; ++k) {
         a.k = k;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
         if (n_prod > 0)
             hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(dense_sweep_kernel<0>, dim3((n_sweep + 3) / 4), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(64), 0, st, a);
-        hipLaunchKernelGGL(dense_sweep_kernel<1>, dim3((n_sweep + 3) / 4), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_sweep_kernel<0>, dim3(n_sweep), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_sweep_kernel<1>, dim3(n_sweep), dim3(256), 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
