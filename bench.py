@@ -6,8 +6,9 @@ and, for workloads that have one, the backward adjoint scan.  Inputs are
 resident in HBM before the timed region.
 
 Prints ONE JSON line: whole-job throughput in timestep-channels/s, the roofline
-record of the dominant kernel (the fused Newton-iteration kernel) measured live
-with device events, and the CPU oracle timed on the host cores.
+record of the dominant kernel (the fused block of Newton iterations; for the
+dense cell the Jacobian-composition kernel) measured live with device events,
+and the CPU oracle timed on the host cores.
 """
 import argparse
 import json
@@ -20,15 +21,27 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak, published
-# algorithmic bytes per timestep-channel (read u + read iterate + write iterate;
+# fp32 vector peak of the instructions this build may use: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (FMA).
+# The published 157.3 TFLOP/s needs packed two-wide FMAs, which the build switches off.
+VALU_F32_PEAK_TFLOPS = 78.6
+VALU_ISSUE_PEAK = 39.32e12     # lane-instructions per second: 256 x 4 x 16 x 2.4 GHz
+FUSED_HEAD = 5                 # iterations in the first launch of a solve (the library's default)
+# algorithmic bytes per timestep-channel (per-iteration kernel: read u + read iterate + write iterate;
+# fused block: read u + write h, plus the fp32 iterate it leaves for later launches under bf16 storage;
 # backward: read h, u, g + write du), storage sizes per workload
-# HBM bytes one launch of newton_iter_kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes scaled
-# by the same counters' reading for a plain copy of known size (profiles/newton_iter_*.txt)
-MEASURED_TRAFFIC = {"C2": 1364.4e6, "C3": 1101.3e6, "C5": 15715.5e6}
 ALGO_BYTES = {
-    "C1": {"iter": 20, "bwd": 32}, "C2": {"iter": 20, "bwd": 32}, "C3": {"iter": 32, "bwd": 48},
-    "C5": {"iter": 14, "bwd": 16},
+    "C1": {"iter": 20, "block": 16, "bwd": 32}, "C2": {"iter": 20, "block": 16, "bwd": 32},
+    "C3": {"iter": 32, "block": 24, "bwd": 48}, "C5": {"iter": 14, "block": 12, "bwd": 16},
 }
+# algorithmic fp32 operations per timestep-channel and Newton iteration (cell, Jacobian, residual, the
+# thread-level scan step and the back-substitution; +, -, *, / and exp count one each)
+ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93}
+# From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt): HBM bytes one launch of
+# the first fused block moves (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
+# size), and the vector instructions it issues per wave-lane (SQ_INSTS_VALU, with the quarter-rate
+# transcendental ones, SQ_INSTS_VALU_TRANS_F32, counted four times).
+MEASURED_TRAFFIC = {}
+MEASURED_ISSUE_SLOTS = {}
 
 
 def time_events(fn, reps):
@@ -59,6 +72,7 @@ def main():
     from workloads import CONFIGS, make_inputs, cell_dims
 
     torch.cuda.set_device(0)
+    P.set_fused_head(FUSED_HEAD)
     w = CONFIGS[args.config]
     G, S = cell_dims(w.cell)
     d = make_inputs(w, device="cuda")
@@ -90,11 +104,14 @@ def main():
     def fwd_fixed(m):
         return lambda: P.forward(w.cell, params, u, h0, tol=-1.0, max_iter=m, workspace=ws_f, out=h_out)
 
+    # one launch per iteration (the path without fused blocks): time per Newton iteration
+    P.set_fused(False)
     m_lo, m_hi = 2, 10
     for m in (m_lo, m_hi):
         fwd_fixed(m)()
     t_lo = time_events(fwd_fixed(m_lo), 10)
     t_hi = time_events(fwd_fixed(m_hi), 10)
+    P.set_fused(True)
     t_iter_ms = (sum(t_hi) / len(t_hi) - sum(t_lo) / len(t_lo)) / (m_hi - m_lo)
     t_iter_min_ms = (min(t_hi) - min(t_lo)) / (m_hi - m_lo)
     t_fwd = time_events(lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f,
@@ -125,7 +142,30 @@ def main():
     else:
         ab = ALGO_BYTES[args.config]
         iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9
-        detail["iter_bytes_per_elt"] = ab["iter"]
+        detail.update({"iter_bytes_per_elt": ab["iter"], "iter_gbs": iter_gbs, "iter_frac_hbm": iter_gbs / HBM_PEAK_GBS})
+        # The dominant launch of a solve: its first fused block of FUSED_HEAD iterations from the initial
+        # guess (u read once, the iterate in registers, h written once).  Timed as the library runs it
+        # inside a solve: a tolerance that is met at once ends the solve after this launch, which still
+        # performs all its iterations; the call also holds the reset of the carry records and one
+        # launch that returns at once.
+        K0 = min(FUSED_HEAD, w.max_iter)
+        block = lambda: P.forward(w.cell, params, u, h0, tol=3.0e38, max_iter=K0 + 1, workspace=ws_f, out=h_out)
+        block()
+        t_blk = time_events(block, 10)
+        t_block_ms = sum(t_blk) / len(t_blk)
+        flops = ALGO_FLOPS[w.cell] * float(N) * K0
+        ach = flops / (t_block_ms * 1e-3) / 1e12
+        detail.update({"fused_block_iterations": K0, "t_block_ms": t_block_ms, "t_block_min_ms": min(t_blk),
+                       "block_flops_per_elt_iter": ALGO_FLOPS[w.cell],
+                       "block_bytes_per_elt": ab["block"],
+                       "block_gbs": ab["block"] * N / (t_block_ms * 1e-3) / 1e9,
+                       # what one launch per iteration would have had to move for the same iterations
+                       "block_equivalent_per_iteration_gbs": ab["iter"] * N * K0 / (t_block_ms * 1e-3) / 1e9})
+        slots = MEASURED_ISSUE_SLOTS.get(args.config)
+        if slots:
+            detail["block_valu_issue_utilisation"] = slots / (t_block_ms * 1e-3) / VALU_ISSUE_PEAK
+        roofline = {"bound": "alu", "kernel": "newton_fused_kernel", "achieved": ach, "peak": VALU_F32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / VALU_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(args.config)}
     if w.cell != "tanh_dense":
         # the paper's operating mode: a fixed N_its = 3 and no stopping test (tol < 0), which the library
         # runs in one launch (u read once, h written once)
@@ -150,10 +190,6 @@ def main():
     t_copy = time_events(lambda: dst.copy_(src), 5)
     detail["copy_1GiB_gbs"] = 2 * src.numel() * 4 / (min(t_copy) * 1e-3) / 1e9
     del src, dst
-
-    if w.cell != "tanh_dense":
-        roofline = {"bound": "hbm", "kernel": "newton_iter_kernel", "achieved": iter_gbs, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": iter_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(args.config)}
 
     cpu = None
     if not args.no_cpu_baseline:

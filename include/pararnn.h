@@ -115,6 +115,20 @@ size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, i
  * always launch one kernel per iteration. */
 int pararnn_set_fused(int enable);
 
+/* Tuning hook (host, process-wide): a solve to a tolerance (tol >= 0) runs its
+ * first min(n_iters, max_iter) iterations in ONE launch of the fused kernel (u
+ * read once, the iterate kept in registers), then one launch per further
+ * iteration.  The stopping test still sees m_k of every iteration: `iters`,
+ * the status and delta_trace are those of the per-iteration solve.  When the
+ * tolerance is met at an iteration before the end of that first launch, the
+ * returned h is the iterate at the END of the launch -- the converged iterate
+ * refined by the Newton iterations that were already in flight -- so it differs
+ * from the per-iteration path's h by less than tol.  0 <= n_iters <= 8; 0 turns
+ * it off; default 5.  Query workspace sizes after setting it (a workspace
+ * that is too small for the record slots falls back to one launch per
+ * iteration). */
+int pararnn_set_fused_head(int n_iters);
+
 /*
  * Forward: solve Eq. (2) by Newton iterations (Alg. 1a).
  *   initial guess   h^0_l = f(h0, u_l) for every l (App. A; f(0, x_l) when h0 = 0)
@@ -130,7 +144,9 @@ int pararnn_set_fused(int enable);
  *   tol             absolute tolerance on max|delta h|; tol < 0 runs exactly
  *                   max_iter iterations (the paper's fixed N_its) with status OK
  *   max_iter        >= 0; 0 returns the initial guess
- *   h               out [B][L][S][H]; on NOT_CONVERGED the last iterate
+ *   h               out [B][L][S][H]; on NOT_CONVERGED the last iterate; on OK an
+ *                   iterate at or after the one that met the tolerance (see
+ *                   pararnn_set_fused_head)
  *   iters           out, DEVICE int32[2] = {iterations performed (number of
  *                   linear solves), device status (OK / NOT_CONVERGED /
  *                   NONFINITE / INTERNAL)}

@@ -33,6 +33,7 @@ _lib.pararnn_workspace_bytes.argtypes = [_i] * 6
 _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
+_lib.pararnn_set_fused_head.argtypes = [_i]
 _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_backward.restype = _i
@@ -93,8 +94,13 @@ def workspace_bytes_fused(cell: str, dtype, B: int, L: int, H: int, n_iters: int
 
 
 def set_fused(enable: bool = True) -> None:
-    """pararnn_set_fused: allow (default) or forbid the one-launch path of fixed-count solves."""
+    """pararnn_set_fused: allow (default) or forbid the fused multi-iteration launches."""
     _raise(_lib.pararnn_set_fused(int(enable)), "pararnn_set_fused")
+
+
+def set_fused_head(n_iters: int = 5) -> None:
+    """pararnn_set_fused_head: iterations a solve to a tolerance runs in its first launch (0 = none)."""
+    _raise(_lib.pararnn_set_fused_head(int(n_iters)), "pararnn_set_fused_head")
 
 
 def _ptr(t):

@@ -16,6 +16,8 @@ struct Ctrl {
     int iters;
     int status;
     unsigned int pad[2];
+    int h_final;             // bf16 storage: the output already holds the final iterate (no conversion pass needed)
+    unsigned int pad2[7];
 };
 
 // status values mirrored from pararnn.h (device code does not include it)

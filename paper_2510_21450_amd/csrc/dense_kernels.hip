@@ -72,23 +72,40 @@ __device__ __forceinline__ void load_w_operand(const float *W, int lane, float (
             }
 }
 
+// W in A-operand form for the 16x16x4 products of wave w:
+// wa[ww][v] = W[16w + n][16ww + 4g + v], lane = (n = lane % 16, g = lane / 16)
+__device__ __forceinline__ void load_w_operand16(const float *W, int w, int n, int g, float (&wa)[4][4])
+{
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+        const f4v t = *reinterpret_cast<const f4v *>(W + (16 * w + n) * DH + 16 * ww + 4 * g);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) wa[ww][v] = t[v];
+    }
+}
+
 // ---------------------------------------------------------------- residual
-// F = tanh(W h_{l-1} + u_l) for 32 consecutive rows (b, l) per wave as one MFMA
-// product W [h_{l-1} rows]; lane = row, registers = channels (accumulator
-// layout), so every access is a float4 inside a 256-byte row.
+// F = tanh(W h_{l-1} + u_l) for 16 consecutive rows (b, l) per workgroup as one
+// 64 x 64 x 16 product W [h_{l-1} rows] on v_mfma_f32_16x16x4_f32: wave w owns
+// channels 16w .. 16w+15, lane (n = lane % 16, g = lane / 16) ends up with
+// channels 16w + 4g .. +3 of row n, so u, h, d and r move as float4.  The B
+// operand of k-step (ww, v) is component v of the float4 at channels
+// 16ww + 4g of the previous state, read straight from memory.
 // mode 0: write d = 1 - F^2 and r = F - h for the current iterate;
 // mode 1: write the initial guess h = tanh(W h0 + u) (App. A).
 __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
 {
     if (a.ctrl->stop) return;
-    const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
-    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n = lane & 15, g = lane >> 4;
+    const int chn = 16 * w + 4 * g;
     const size_t rows = (size_t)a.B * a.L;
-    const size_t n_items = (rows + 31) / 32;
-    float wr[2][2][16];
-    load_w_operand(a.W, lane, wr);
-    for (size_t item = wave; item < n_items; item += n_waves) {
-        const size_t row = item * 32 + n;
+    const size_t n_items = (rows + 15) / 16;
+    float wa[4][4];
+    load_w_operand16(a.W, w, n, g, wa);
+    const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (size_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const size_t row = item * 16 + n;
         const bool ok = row < rows;
         const int l = ok ? (int)(row % a.L) : 0;
         const size_t b = ok ? row / a.L : 0;
@@ -98,45 +115,33 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
             if (mode == 1 || l == 0) hp = a.h0 ? a.h0 + b * DH : nullptr;
             else hp = a.h + (row - 1) * DH;
         }
-        f16v X[2], Y[2];
+        f4v xb[4];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int ww = 0; ww < 4; ++ww) xb[ww] = hp ? *reinterpret_cast<const f4v *>(hp + 16 * ww + 4 * g) : zero;
+        f4v uv = zero, hv = zero;
+        if (ok) {
+            uv = *reinterpret_cast<const f4v *>(a.u + row * DH + chn);
+            if (mode == 0) hv = *reinterpret_cast<const f4v *>(a.h + row * DH + chn);
+        }
+        f4v acc0 = zero, acc1 = zero;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (hp) t = *reinterpret_cast<const float4 *>(hp + 32 * kt + 8 * g + 4 * half);
-                X[kt][4 * g] = t.x; X[kt][4 * g + 1] = t.y; X[kt][4 * g + 2] = t.z; X[kt][4 * g + 3] = t.w;
-            }
+        for (int ww = 0; ww < 4; ww += 2)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) Y[mt][v] = 0.0f;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                Y[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[0][kt][v], X[kt][v], Y[0], 0, 0, 0);
-                Y[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[1][kt][v], X[kt][v], Y[1], 0, 0, 0);
+            for (int v = 0; v < 4; ++v) {
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww][v], xb[ww][v], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww + 1][v], xb[ww + 1][v], acc1, 0, 0, 0);
             }
         if (ok) {
+            const f4v y = acc0 + acc1 + uv;
+            f4v F;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const size_t off = row * DH + 32 * mt + 8 * g + 4 * half;
-                    const float4 uv = *reinterpret_cast<const float4 *>(a.u + off);
-                    float4 F;
-                    F.x = fast_tanh(Y[mt][4 * g] + uv.x); F.y = fast_tanh(Y[mt][4 * g + 1] + uv.y);
-                    F.z = fast_tanh(Y[mt][4 * g + 2] + uv.z); F.w = fast_tanh(Y[mt][4 * g + 3] + uv.w);
-                    if (mode == 1) {
-                        *reinterpret_cast<float4 *>(a.h + off) = F;
-                    } else {
-                        const float4 hv = *reinterpret_cast<const float4 *>(a.h + off);
-                        *reinterpret_cast<float4 *>(a.d + off) =
-                            make_float4(fmaf(-F.x, F.x, 1.0f), fmaf(-F.y, F.y, 1.0f), fmaf(-F.z, F.z, 1.0f), fmaf(-F.w, F.w, 1.0f));
-                        *reinterpret_cast<float4 *>(a.r + off) = make_float4(F.x - hv.x, F.y - hv.y, F.z - hv.z, F.w - hv.w);
-                    }
-                }
+            for (int v = 0; v < 4; ++v) F[v] = fast_tanh(y[v]);
+            if (mode == 1) {
+                *reinterpret_cast<f4v *>(a.h + row * DH + chn) = F;
+            } else {
+                *reinterpret_cast<f4v *>(a.d + row * DH + chn) = 1.0f - F * F;
+                *reinterpret_cast<f4v *>(a.r + row * DH + chn) = F - hv;
+            }
         }
     }
 }
@@ -258,7 +263,7 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 // order, so the exchange is one float4 write and four conflict-free float4
 // reads per step, with no index arithmetic.
 //
-// d and r of all CD steps are loaded before the chain starts; the barrier
+// d and r (and h) of all CD steps are loaded before the chain starts; the barrier
 // between steps orders LDS only.
 // final = 0: x starts at 0, only the end value is kept (b_c).
 // final = 1: x starts at x_{c-1}; afterwards h += delta and max|delta|.
@@ -278,22 +283,17 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
     const int ls = c * CD;
     const int chn = 16 * w + 4 * g;               // first of this lane's four channels
 
-    // wa[ww][v] = W[16w + n][16ww + 4g + v]
     float wa[4][4];
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
-        const f4v t = *reinterpret_cast<const f4v *>(a.W + (16 * w + n) * DH + 16 * ww + 4 * g);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) wa[ww][v] = t[v];
-    }
+    load_w_operand16(a.W, w, n, g, wa);
     const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    f4v dv[CD], rv[CD];
+    f4v dv[CD], rv[CD], hv[FINAL ? CD : 1];
 #pragma unroll
     for (int i = 0; i < CD; ++i) {
         const int l = ls + i;
         const size_t off = ((size_t)b * a.L + min(l, a.L - 1)) * DH + chn;
         dv[i] = *reinterpret_cast<const f4v *>(a.d + off);
         rv[i] = *reinterpret_cast<const f4v *>(a.r + off);
+        if (FINAL) hv[i] = *reinterpret_cast<const f4v *>(a.h + off);
         if (!(ok && l < a.L)) { dv[i] = zero; rv[i] = zero; }     // steps past the end leave x = 0
     }
     f4v x = zero;
@@ -327,10 +327,7 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
 #pragma unroll
     for (int i = 0; i < CD; ++i) {
         const int l = ls + i;
-        if (ok && l < a.L) {
-            f4v *hp = reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn);
-            *hp = *hp + rv[i];
-        }
+        if (ok && l < a.L) *reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn) = hv[i] + rv[i];
 #pragma unroll
         for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
     }
@@ -344,7 +341,8 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
 // --------------------------------------------------------------------- carry
 // x_c = A_c x_{c-1} + b_c for c = 0 .. n_c-2 (x_{-1} = 0, so x_0 = b_0), one
 // workgroup per sequence.  Lane (row = lane / 4, q = lane % 4) of wave w holds
-// columns 16q .. 16q+15 of row 16w + row of A_c: sixteen FMAs against x from
+// columns 16j + 4q .. 16j + 4q + 3, j = 0..3, of row 16w + row of A_c (so that the
+// four lanes of a quad load 64 contiguous bytes at a time): sixteen FMAs against x from
 // LDS, two DPP adds across the quad, and the row's new value goes back to LDS.
 // The matrices of the next DEPTH chunks are in flight meanwhile; the loop body
 // is branch-free around the loads (indices are clamped) and its barrier orders
@@ -358,7 +356,7 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
     const int row = 16 * w + (lane >> 2), q = lane & 3, b = blockIdx.x;
     const float *bcb = a.bc + (size_t)b * a.n_c * DH + row;
     float *xcb = a.xc + (size_t)b * a.n_c * DH + row;
-    const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + row) * DH + 16 * q;   // this lane's 16 columns, chunk 0
+    const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + row) * DH + 4 * q;    // this lane's first columns, chunk 0
     const int last = a.n_c - 2;                       // last chunk whose end value is needed
     {
         const float x0 = bcb[0];
@@ -371,7 +369,7 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
     for (int k = 0; k < DEPTH; ++k) {
         const int c = min(1 + k, last);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)c * DH * DH + 4 * j);
+        for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)c * DH * DH + 16 * j);
         bb[k] = bcb[(size_t)c * DH];
     }
     lds_barrier();
@@ -380,10 +378,10 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
 #pragma unroll
         for (int k = 0; k < DEPTH; ++k) {
             const int c = base + k;
-            const f4v *xs = reinterpret_cast<const f4v *>(&s_x[cur][16 * q]);
+            const f4v *xs = reinterpret_cast<const f4v *>(&s_x[cur][4 * q]);
             f4v s = buf[k][0] * xs[0];
 #pragma unroll
-            for (int j = 1; j < 4; ++j) s = buf[k][j] * xs[j] + s;
+            for (int j = 1; j < 4; ++j) s = buf[k][j] * xs[4 * j] + s;
             float t = (s[0] + s[1]) + (s[2] + s[3]);
             t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0xB1, 0xf, 0xf, false));
             t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x4E, 0xf, 0xf, false));
@@ -395,7 +393,7 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
             }
             const int cn = min(c + DEPTH, last);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)cn * DH * DH + 4 * j);
+            for (int j = 0; j < 4; ++j) buf[k][j] = *reinterpret_cast<const f4v *>(Ab + (size_t)cn * DH * DH + 16 * j);
             bb[k] = bcb[(size_t)cn * DH];
             lds_barrier();
         }
@@ -470,8 +468,9 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
 
     const int status0 = tol < 0.0f ? PARARNN_OK : PARARNN_NOT_CONVERGED;
     if (launch_reset(a.ctrl, nullptr, 0, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
-    const size_t res_items = ((size_t)B * L + 31) / 32;
-    const int res_blocks = (int)((res_items + 3) / 4 < 512 ? (res_items + 3) / 4 : 512);
+    const size_t res_items = ((size_t)B * L + 15) / 16;           // one workgroup per 16 rows, a few rounds at most
+    const size_t res_cap = (size_t)device_cu_count() * 8;
+    const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
     hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
     const int n_sweep = (B * lo.n_c + 15) / 16;       // workgroups: 16 (sequence, chunk) columns each

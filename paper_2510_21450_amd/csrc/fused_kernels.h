@@ -1,7 +1,17 @@
-// All Newton iterations of a fixed-count solve in one launch (the paper's "fully
-// fused" mode, Sec. 4 item 3 and App. D.3, where N_its is fixed and there is no
-// stopping test): u is read once, the K iterations run on registers, h is
-// written once.  Traffic per timestep-channel drops from K * (u + 2 h) to u + h.
+// K Newton iterations in one launch (the paper's "fully fused" mode, Sec. 4
+// item 3 and App. D.3, where N_its is fixed and there is no stopping test): u
+// is read once, the K iterations run on registers, h is written once.  Traffic
+// per timestep-channel drops from K * (u + 2 h) to u + h.
+//
+// Two uses.  A fixed-count solve (tol < 0) runs entirely here.  A solve to a
+// tolerance is a sequence of such blocks of K iterations: the maximum of |delta|
+// is kept per iteration, the last workgroup reports the first iteration that
+// met the tolerance, and the returned state is the iterate at the end of the
+// block, i.e. the converged one refined by the iterations that were already in
+// flight.  The first block starts from the initial guess (k0 = 0); a later one
+// (k0 > 0) starts from the fp32 iterate and the tile-boundary rows its
+// predecessor left behind, exactly as the per-iteration kernel does, and may be
+// mixed with launches of that kernel.
 //
 // Same tile decomposition and the same look-back as newton_iter_kernel, with one
 // carry-record slot per iteration: tile t at iteration k waits only for tile
@@ -31,6 +41,15 @@ struct FusedArgs {
     int *iters_out;
     float *trace;
     int n_iters;
+    // block of a solve to a tolerance (head != 0)
+    int head;
+    int k0;                  // iterations performed before this launch
+    int max_iter;            // of the whole solve
+    float tol;
+    float *hit;              // fp32 iterate, read when k0 > 0 and written when more launches may follow;
+                             // the output h itself for fp32 storage
+    float *bnd;              // [2][n_lt][B][S][H] tile-boundary rows, see FwdArgs
+    int bnd_cur;             // buffer read (k0 > 0); the other one is written
 };
 
 template <class Cell, int VEC, int LL, int C, int W, typename UT>
@@ -45,6 +64,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
     __shared__ unsigned int s_ticket;
 
     Ctrl *ctrl = a.ctrl;
+    if (ctrl->stop) return;
     const ScanGeom &g = a.g;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -52,6 +72,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
     const UT *u = static_cast<const UT *>(a.u);
     UT *hout = static_cast<UT *>(a.h);
     const int K = a.n_iters;
+    const bool resume = a.k0 > 0;
     bool internal_error = false;
     if (threadIdx.x < kMaxFused) s_maxk[threadIdx.x] = 0u;
 
@@ -118,12 +139,22 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             if (ch_ok && a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + ((size_t)b * S + s) * g.H + ch, h0v[s]);
         }
 
-        // ---- initial guess h^0_l = f(h0, u_l) (App. A) for the own steps and for the row before the chunk
+        // ---- initial guess h^0_l = f(h0, u_l) (App. A) for the own steps and for the row before the chunk;
+        //      a resumed solve reads both from the iterate instead
         float uu[C][G][VEC], ho[C][S][VEC];
 #pragma unroll
         for (int i = 0; i < C; ++i) {
 #pragma unroll
             for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu[i][q]);
+            if (resume) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) ho[i][s][v] = 0.0f;
+                    if (ch_ok && l0 + i < g.L) load_vec<VEC>(a.hit + ((seq + l0 + i) * S + s) * g.H + ch, ho[i][s]);
+                }
+                continue;
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 float h1[S], ug[G], F0[S];
@@ -140,7 +171,19 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         for (int s = 0; s < S; ++s)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) hprev[s][v] = h0v[s][v];
-        if (l0 > 0) {
+        if (resume) {
+            // the previous tile's boundary row, or the row just before the chunk (still the old
+            // iterate: every store of this tile comes after the barriers below)
+            if (ch_ok && l0 > 0 && l0 <= g.L) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (w == 0 && seg == 0)
+                        load_vec<VEC>(a.bnd + ((((size_t)a.bnd_cur * g.n_lt + (lt - 1)) * g.B + b) * S + s) * g.H + ch, hprev[s]);
+                    else
+                        load_vec<VEC>(a.hit + ((seq + l0 - 1) * S + s) * g.H + ch, hprev[s]);
+                }
+            }
+        } else if (l0 > 0) {
             float uh[G][VEC];
 #pragma unroll
             for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uhalo[q], uh[q]);
@@ -159,7 +202,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 
 #pragma unroll 1
         for (int k = 1; k <= K; ++k) {
-            const unsigned int epoch = (unsigned int)k;
+            const unsigned int epoch = (unsigned int)(a.k0 + k);      // unique within the call
             unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
 
             // ---- thread level
@@ -335,6 +378,26 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             // s_A / s_carry are rewritten only after the next iteration's first barrier
         }
 
+        // ---- what a following per-iteration launch needs: the fp32 iterate and the tile's last row
+        if (a.head && a.k0 + K < a.max_iter) {
+            if (a.hit && static_cast<void *>(a.hit) != a.h) {
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    const int l = l0 + i;
+                    if (ch_ok && l < g.L) {
+#pragma unroll
+                        for (int s = 0; s < S; ++s) store_vec<VEC>(a.hit + ((seq + l) * S + s) * g.H + ch, ho[i][s]);
+                    }
+                }
+            }
+            if (ch_ok && w == W - 1 && seg == LL - 1 && lt + 1 < g.n_lt) {
+                const int nxt = a.bnd_cur ^ 1;
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+                    store_vec<VEC>(a.bnd + ((((size_t)nxt * g.n_lt + lt) * g.B + b) * S + s) * g.H + ch, ho[C - 1][s]);
+            }
+        }
+
         // ---- the result, once
         if (full_tile) {
 #pragma unroll
@@ -364,18 +427,25 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         const unsigned int prev = atomicAdd(&ctrl->done, 1u);
         if (prev == gridDim.x - 1) {
             __threadfence();
-            int status = atomicAdd(&ctrl->status, 0) == kStInternal ? kStInternal : kStOk;
-            int iters = K;
+            const bool internal = atomicAdd(&ctrl->status, 0) == kStInternal;
+            int status = internal ? kStInternal : (a.head ? kStNotConverged : kStOk);
+            int iters = K, stop = (a.head && !internal) ? 0 : 1;
+            bool ended = false;
+            iters += a.k0;
             for (int k = 0; k < K; ++k) {
-                const float mk = __uint_as_float(atomicMax(&a.gmaxk[k], 0u));
-                if (a.trace) a.trace[k] = mk;
-                if (status == kStOk && !(mk - mk == 0.0f)) { status = kStNonFinite; iters = k + 1; }
+                const float mk = __uint_as_float(atomicExch(&a.gmaxk[k], 0u));   // zero again for the next block
+                if (ended) continue;                  // iterations past the end are not reported
+                if (a.trace) a.trace[a.k0 + k] = mk;
+                if (internal) continue;
+                if (!(mk - mk == 0.0f)) { status = kStNonFinite; iters = a.k0 + k + 1; stop = 1; ended = true; }
+                else if (a.head && mk <= a.tol) { status = kStOk; iters = a.k0 + k + 1; stop = 1; ended = true; }
             }
             a.iters_out[0] = iters;
             a.iters_out[1] = status;
             ctrl->iters = iters;
             ctrl->status = status;
-            ctrl->stop = 1;
+            ctrl->stop = stop;
+            ctrl->h_final = (stop || a.k0 + K >= a.max_iter) ? 1 : 0;
             ctrl->ticket = 0u;
             ctrl->done = 0u;
             __threadfence();

@@ -33,7 +33,8 @@ template <class Cell, typename UT> struct Kernels {
 
 hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0,
                         hipStream_t st);
-hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t st);
+// ctrl may be NULL; otherwise the pass is skipped on the device when ctrl->h_final is set
+hipError_t launch_store_bf16(const float *src, void *dst, size_t n, const Ctrl *ctrl, hipStream_t st);
 hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st);
 int device_cu_count();
 

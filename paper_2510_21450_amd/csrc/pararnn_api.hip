@@ -32,6 +32,7 @@ size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // process-wide switch for the one-launch path of fixed-count solves (pararnn_set_fused)
 int g_fused_enabled = 1;
+int g_fused_head = 5;      // iterations in the first launch of a solve to a tolerance (0 = none)
 
 // process-wide tile-shape override: {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
 int g_tile_override[4] = {-1, 0, 0, 0};
@@ -87,10 +88,10 @@ struct Layout {
     size_t off_rec, n_rec, off_bnd, off_iter, off_part, total;
 };
 
-// Workspace: [Ctrl | carry records | boundary rows | fp32 iterate (bf16 forward) |
+// Workspace: [Ctrl | carry records (rec_slots sets) | boundary rows | fp32 iterate (bf16 forward) |
 // parameter-gradient partials (backward)]
 Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems,
-                   bool fused = false)
+                   bool fused = false, int rec_slots = 1)
 {
     Layout lo;
     lo.cfg = choose_tile(cell_kind, dtype, backward, H, align_elems, fused);
@@ -104,7 +105,7 @@ Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, i
     const size_t NW = (size_t)ci.S * ci.S + 2 * ci.S;
     size_t off = round256(sizeof(Ctrl));
     lo.n_rec = (size_t)g.n_tiles * NW * CW;
-    lo.off_rec = off;   off += round256(lo.n_rec * sizeof(unsigned long long));
+    lo.off_rec = off;   off += round256(lo.n_rec * (size_t)rec_slots * sizeof(unsigned long long));
     lo.off_bnd = off;
     if (!backward) off += round256((size_t)2 * g.n_lt * B * ci.S * H * sizeof(float));
     lo.off_iter = off;
@@ -137,44 +138,63 @@ int align_elems(size_t esz, std::initializer_list<const void *> ptrs)
     return a;
 }
 
+// n_fused = number of carry-record slots the workspace holds (0: none; fused launches are not used).
+// tol < 0: the whole fixed-count solve is one fused launch of n_fused = max_iter iterations.
+// tol >= 0: the solve is a sequence of launches, each checked by the stopping test on the
+// device: a fused block of n_fused iterations from the initial guess, then blocks of 1, 2,
+// 4, ... (at most n_fused) iterations from the iterate; a block of one iteration is the
+// per-iteration kernel.  Launches after the one that met the tolerance return at once, and
+// there are O(max_iter / n_fused) of them instead of max_iter.
 template <class Cell>
 int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hipStream_t st, void *h,
-                 int status0, int max_iter, bool fused)
+                 int status0, int max_iter, int n_fused)
 {
     char *ws = reinterpret_cast<char *>(a.ctrl);
     const bool bf = dtype == PARARNN_BF16;
+    const bool to_tol = a.tol >= 0.0f;
     hipError_t e;
-    // fixed iteration count (tol < 0): all iterations in one launch when the workspace holds one
-    // carry-record slot per iteration
-    if (fused) {
-        e = launch_reset(a.ctrl, a.rec, lo.n_rec * (size_t)max_iter, a.iters_out, status0, st);
-        if (e != hipSuccess) return PARARNN_HIP_ERROR;
-        FusedArgs f;
-        memset(&f, 0, sizeof(f));
-        f.g = a.g; f.params = a.params; f.u = a.u; f.h0 = a.h0; f.h = h;
-        f.rec = a.rec; f.rec_stride = lo.n_rec;
-        f.gmaxk = reinterpret_cast<unsigned int *>(ws + 64);
-        f.ctrl = a.ctrl; f.iters_out = a.iters_out; f.trace = a.trace; f.n_iters = max_iter;
-        e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
-        if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
-        return PARARNN_OK;
-    }
-    e = launch_reset(a.ctrl, a.rec, lo.n_rec, a.iters_out, status0, st);
-    if (e != hipSuccess) return PARARNN_HIP_ERROR;
     a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
+    e = launch_reset(a.ctrl, a.rec, lo.n_rec * (size_t)(n_fused > 0 ? n_fused : 1), a.iters_out, status0, st);
+    if (e != hipSuccess) return PARARNN_HIP_ERROR;
     if (max_iter == 0) {
-        // only the initial guess is asked for; otherwise iteration 1 computes it on the fly
+        // only the initial guess is asked for; otherwise the first iteration computes it on the fly
         e = bf ? Kernels<Cell, unsigned short>::init_guess(lo.cfg.vec, a, st) : Kernels<Cell, float>::init_guess(lo.cfg.vec, a, st);
         if (e != hipSuccess) return PARARNN_HIP_ERROR;
     }
-    for (int k = 1; k <= max_iter; ++k) {
-        a.k = k;
-        e = bf ? Kernels<Cell, unsigned short>::newton_iter(lo.cfg, a, k == 1, st)
-               : Kernels<Cell, float>::newton_iter(lo.cfg, a, k == 1, st);
+    FusedArgs f;
+    memset(&f, 0, sizeof(f));
+    f.g = a.g; f.params = a.params; f.u = a.u; f.h0 = a.h0; f.h = h;
+    f.rec = a.rec; f.rec_stride = lo.n_rec;
+    f.gmaxk = reinterpret_cast<unsigned int *>(ws + 64);
+    f.ctrl = a.ctrl; f.iters_out = a.iters_out; f.trace = a.trace;
+    f.head = to_tol ? 1 : 0; f.max_iter = max_iter; f.tol = a.tol;
+    f.hit = to_tol ? a.hit : nullptr;
+    f.bnd = a.bnd;
+    int done = 0, cur = 0, next_block = 1;
+    while (done < max_iter) {
+        int K = 1;
+        if (n_fused > 0) {
+            K = done == 0 ? n_fused : next_block;
+            if (K > n_fused) K = n_fused;
+            if (K > max_iter - done) K = max_iter - done;
+        }
+        if (n_fused > 0 && (K > 1 || done == 0)) {
+            f.n_iters = K; f.k0 = done; f.bnd_cur = cur;
+            e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
+        } else {
+            a.k = done + 1; a.bnd_cur = cur;
+            e = bf ? Kernels<Cell, unsigned short>::newton_iter(lo.cfg, a, done == 0, st)
+                   : Kernels<Cell, float>::newton_iter(lo.cfg, a, done == 0, st);
+        }
         if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+        if (done > 0) next_block *= 2;
+        done += K;
+        cur ^= 1;
     }
-    if (bf) {
-        e = launch_store_bf16(a.hit, h, (size_t)lo.g.B * lo.g.L * ci.S * lo.g.H, st);
+    if (bf && !(n_fused > 0 && !to_tol)) {
+        // rounds the fp32 iterate into the output; skipped on the device when a fused block
+        // already wrote the final iterate
+        e = launch_store_bf16(a.hit, h, (size_t)lo.g.B * lo.g.L * ci.S * lo.g.H, a.ctrl, st);
         if (e != hipSuccess) return PARARNN_HIP_ERROR;
     }
     return PARARNN_OK;
@@ -242,11 +262,15 @@ size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int bac
     CellInfo ci;
     if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
     if (cell == PARARNN_TANH_DENSE) return dense_workspace_bytes(dtype, B, L, H, backward);
-    // the size must not depend on pointer alignment: take the larger (vec = 1) footprint when they differ
+    // the size must not depend on pointer alignment: take the larger footprint when they differ
     size_t need = 0;
     for (int al = 1; al <= 4; al *= 2) {
         const Layout lo = make_layout(cell, ci, dtype, B, L, H, backward != 0, al);
         if (lo.total > need) need = lo.total;
+        if (!backward && g_fused_enabled && g_fused_head > 0) {
+            const Layout lf = make_layout(cell, ci, dtype, B, L, H, false, al, true, g_fused_head);
+            if (lf.total > need) need = lf.total;
+        }
     }
     return need;
 }
@@ -255,12 +279,11 @@ size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, i
 {
     CellInfo ci;
     if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
-    if (cell == PARARNN_TANH_DENSE || n_iters < 1 || n_iters > kMaxFused) return pararnn_workspace_bytes(cell, dtype, B, L, H, 0);
     size_t need = pararnn_workspace_bytes(cell, dtype, B, L, H, 0);
+    if (cell == PARARNN_TANH_DENSE || n_iters < 1 || n_iters > kMaxFused) return need;
     for (int al = 1; al <= 4; al *= 2) {
-        const Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al, true);
-        const size_t fused = lo.off_rec + round256(lo.n_rec * (size_t)n_iters * sizeof(unsigned long long));
-        if (fused > need) need = fused;
+        const Layout lf = make_layout(cell, ci, dtype, B, L, H, false, al, true, n_iters);
+        if (lf.off_bnd > need) need = lf.off_bnd;
     }
     return need;
 }
@@ -268,6 +291,13 @@ size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, i
 int pararnn_set_fused(int enable)
 {
     g_fused_enabled = enable ? 1 : 0;
+    return PARARNN_OK;
+}
+
+int pararnn_set_fused_head(int n_iters)
+{
+    if (n_iters < 0 || n_iters > kMaxFused) return PARARNN_INVALID_ARG;
+    g_fused_head = n_iters;
     return PARARNN_OK;
 }
 
@@ -292,17 +322,23 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     int al = align_elems(esz, {u, h, h0});
     const int alp = align_elems(4, {params});
     if (alp < al) al = alp;
-    // a fixed-count solve (tol < 0) runs in one launch when the workspace holds a record slot per iteration
+    // Fused launches need one carry-record slot per iteration they run; they are used when the
+    // workspace holds those: the whole solve when the count is fixed (tol < 0), else its first
+    // g_fused_head iterations.
     Layout lo = make_layout(cell, ci, dtype, B, L, H, false, al);
-    bool fused = false;
-    if (tol < 0.0f && max_iter >= 1 && max_iter <= kMaxFused && g_fused_enabled) {
-        const Layout lf = make_layout(cell, ci, dtype, B, L, H, false, al, true);
-        if (workspace_bytes >= lf.off_rec + round256(lf.n_rec * (size_t)max_iter * sizeof(unsigned long long))) {
-            lo = lf;
-            fused = true;
+    int n_fused = 0;
+    if (g_fused_enabled && max_iter >= 1) {
+        const int want = tol < 0.0f ? (max_iter <= kMaxFused ? max_iter : 0)
+                                    : (max_iter < g_fused_head ? max_iter : g_fused_head);
+        if (want > 0) {
+            const Layout lf = make_layout(cell, ci, dtype, B, L, H, false, al, true, want);
+            if (workspace_bytes >= (tol < 0.0f ? lf.off_bnd : lf.total)) {
+                lo = lf;
+                n_fused = want;
+            }
         }
     }
-    if (!fused && workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    if (n_fused == 0 && workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
     FwdArgs a;
     memset(&a, 0, sizeof(a));
@@ -314,10 +350,10 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     a.iters_out = iters; a.trace = delta_trace;
     a.k = 0; a.max_iter = max_iter; a.tol = tol;
     switch (cell) {
-    case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
-    case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
-    case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
-    case PARARNN_PARALSTM_DIAG: return forward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, fused);
+    case PARARNN_GRU_DIAG: return forward_diag<GruDiag>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
+    case PARARNN_LSTM_DIAG: return forward_diag<LstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
+    case PARARNN_LINEAR_DIAG: return forward_diag<LinearDiag>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
+    case PARARNN_PARALSTM_DIAG: return forward_diag<ParaLstmDiag>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
     }
     return PARARNN_INVALID_ARG;
 }

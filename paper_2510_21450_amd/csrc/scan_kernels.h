@@ -56,6 +56,7 @@ struct FwdArgs {
     const float *jac;    // raw scans only: [B][L][S*S][H]
     float *hit;          // fp32 iterate [B][L][S][H], updated in place
     float *bnd;          // [2][n_lt][B][S][H]: iterate at each tile's last step
+    int bnd_cur;         // which of the two holds the rows of the iterate being read (the other is written)
     unsigned long long *rec; // carry records [n_groups][n_lt][S*S + 2S][CW] of {value, tag}
     Ctrl *ctrl;
     int *iters_out;      // device int[2]
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const unsigned int epoch = (unsigned int)a.k;
     const UT *u = static_cast<const UT *>(a.u);
-    const int cur = a.k & 1, nxt = cur ^ 1;
+    const int cur = a.bnd_cur, nxt = cur ^ 1;
     // max |delta| as its bit pattern: for non-negative floats the unsigned order is the float order, and
     // NaN patterns sort above infinity, so one integer max both orders the values and keeps a NaN
     unsigned int wmax_bits = 0u;

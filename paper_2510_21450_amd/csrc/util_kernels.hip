@@ -19,8 +19,10 @@ __global__ void reset_kernel(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, 
 }
 
 // bf16 storage: round the converged fp32 iterate once into the output.
-__global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsigned short *dst, size_t n4)
+__global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsigned short *dst, size_t n4,
+                                                         const Ctrl *ctrl)
 {
+    if (ctrl && ctrl->h_final) return;            // the output was already written in its final form
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
         float v[4];
         load_vec<4>(src + 4 * i, v);
@@ -28,8 +30,9 @@ __global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsig
     }
 }
 
-__global__ void store_bf16_tail_kernel(const float *src, unsigned short *dst, int n)
+__global__ void store_bf16_tail_kernel(const float *src, unsigned short *dst, int n, const Ctrl *ctrl)
 {
+    if (ctrl && ctrl->h_final) return;
     if ((int)threadIdx.x < n) dst[threadIdx.x] = f32_to_bf16(src[threadIdx.x]);
 }
 
@@ -78,7 +81,7 @@ hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *
     return hipGetLastError();
 }
 
-hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t st)
+hipError_t launch_store_bf16(const float *src, void *dst, size_t n, const Ctrl *ctrl, hipStream_t st)
 {
     // n is a multiple of 4 whenever this is used (vec = 4 path) or handled by the tail kernel
     const size_t n4 = n / 4;
@@ -87,11 +90,11 @@ hipError_t launch_store_bf16(const float *src, void *dst, size_t n, hipStream_t 
         const size_t cap = (size_t)device_cu_count() * 32;
         if (blocks > cap) blocks = cap;
         hipLaunchKernelGGL(store_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src,
-                           static_cast<unsigned short *>(dst), n4);
+                           static_cast<unsigned short *>(dst), n4, ctrl);
     }
     if (n % 4) {
         hipLaunchKernelGGL(store_bf16_tail_kernel, dim3(1), dim3(64), 0, st, src + 4 * n4,
-                           static_cast<unsigned short *>(dst) + 4 * n4, (int)(n % 4));
+                           static_cast<unsigned short *>(dst) + 4 * n4, (int)(n % 4), ctrl);
     }
     return hipGetLastError();
 }

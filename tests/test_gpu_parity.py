@@ -289,6 +289,66 @@ def test_fixed_count_solve_in_one_launch(P, oracle_mod, cell, dtype):
     assert tuple(int(x) for x in it.cpu()) == (1, 5)
 
 
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_solve_to_tolerance_in_fused_blocks(P, oracle_mod, cell, dtype):
+    """A solve to a tolerance is a sequence of launches: a fused block from the
+    initial guess, then blocks of 1, 2, 4, ... iterations from the iterate.  For
+    every size of the first block the tolerance is met in a different launch
+    (inside the first block, in the single-iteration launch after it, inside a
+    resumed fused block) or never; `iters`, status and trace must be those of the
+    oracle's Newton, and h the converged state, whichever launch ended the solve."""
+    B, L, H = 2, 700, 100
+    params, u, h0, _ = problem(cell, B, L, H, seed=77, dtype=dtype)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    bound = TOL_F32 if dtype == torch.float32 else TOL_BF16
+    # the tolerance sits in the middle of the last jump of the oracle's trace, so that the
+    # stopping decision has a clear margin in fp64 and in fp32
+    tr0 = oracle_mod.newton(cell, pn, un, h0n, tol=1e-5, max_iter=40)[3]
+    tol = float(np.sqrt(tr0[-2] * tr0[-1]))
+    _, it64, _, tr64 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40)
+    _, it32, _, tr32 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40, precision="f32")
+    assert it64 == it32 == len(tr0) and it64 >= 4, (it64, it32)
+    k = it64 - 1
+    assert min(tr64[k - 1], tr32[k - 1]) >= 8 * tol and max(tr64[k], tr32[k]) <= tol / 8, (tr64, tr32)
+    try:
+        for head in (0, 1, 2, 3, 4, 5, 6, 8):
+            for tile in (None, (1, 2, 8, 8)):
+                for max_iter in (40, it64, it64 - 1, 2):
+                    print(f"blocks {cell} {dtype} head={head} tile={tile} max_iter={max_iter}", flush=True)
+                    P.set_fused_head(head)
+                    if tile:
+                        P.set_tile(*tile)
+                    h, iters, tr = P.forward(cell, params, u, h0, tol=tol, max_iter=max_iter, trace=True)
+                    torch.cuda.synchronize()
+                    P.set_tile(0)
+                    it, st = (int(x) for x in iters.cpu())
+                    if max_iter >= it64:
+                        assert (it, st) == (it64, 0), (it, st, it64)
+                        assert relerr(to_np(h), ref) <= bound
+                    else:
+                        assert (it, st) == (max_iter, 1), (it, st)
+                        hk = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=max_iter)[0]
+                        assert relerr(to_np(h), hk) <= (2e-5 if dtype == torch.float32 else TOL_BF16)
+                    got = tr.cpu().numpy()[:it]
+                    for j in range(it):
+                        if tr64[j] > 1e-4:
+                            assert abs(got[j] - tr64[j]) <= 5e-3 * tr64[j], (j, got, tr64)
+        # the same solve with one launch per iteration agrees on everything but the extra refinement of h
+        P.set_fused_head(5)
+        hf, itf, _ = P.forward(cell, params, u, h0, tol=tol, max_iter=40)
+        P.set_fused(False)
+        hi, iti, _ = P.forward(cell, params, u, h0, tol=tol, max_iter=40)
+        torch.cuda.synchronize()
+        assert tuple(int(x) for x in itf.cpu()) == tuple(int(x) for x in iti.cpu())
+        assert relerr(to_np(hf), to_np(hi)) <= (1e-5 if dtype == torch.float32 else 1e-2)
+    finally:
+        P.set_fused(True)
+        P.set_fused_head(5)
+        P.set_tile(0)
+
+
 @pytest.mark.parametrize("kind", ["diag", "block2"])
 @pytest.mark.parametrize("reverse", [False, True])
 def test_affine_scan_matches_forward_substitution(P, oracle_mod, kind, reverse):

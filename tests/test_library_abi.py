@@ -61,8 +61,9 @@ def test_workspace_bytes(lib):
     f32 = ws(0, 0, 16, 4096, 1024, 0)
     bf = ws(0, 1, 16, 4096, 1024, 0)
     assert f32 > small and bf >= f32 + 16 * 4096 * 1024 * 4
-    # the fp32 workspace is small next to the tensors (u alone is 805 MB)
-    assert f32 < 128 << 20
+    # the fp32 workspace (carry records for the fused first launch, boundary rows) is small next
+    # to the tensors (u alone is 805 MB)
+    assert f32 < 192 << 20
     # backward workspace holds the per-tile parameter-gradient partials
     assert ws(0, 0, 16, 4096, 1024, 1) > 0
     # dense path: d, r, chunk products
