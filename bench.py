@@ -24,7 +24,6 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak, published
 # fp32 vector peak of the instructions this build may use: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (FMA).
 # The published 157.3 TFLOP/s needs packed two-wide FMAs, which the build switches off.
 VALU_F32_PEAK_TFLOPS = 78.6
-VALU_ISSUE_PEAK = 39.32e12     # lane-instructions per second: 256 x 4 x 16 x 2.4 GHz
 FUSED_HEAD = 5                 # iterations in the first launch of a solve (the library's default)
 # algorithmic bytes per timestep-channel (per-iteration kernel: read u + read iterate + write iterate;
 # fused block: read u + write h, plus the fp32 iterate it leaves for later launches under bf16 storage;
@@ -36,12 +35,11 @@ ALGO_BYTES = {
 # algorithmic fp32 operations per timestep-channel and Newton iteration (cell, Jacobian, residual, the
 # thread-level scan step and the back-substitution; +, -, *, / and exp count one each)
 ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93}
-# From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt): HBM bytes one launch of
-# the first fused block moves (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
-# size), and the vector instructions it issues per wave-lane (SQ_INSTS_VALU, with the quarter-rate
-# transcendental ones, SQ_INSTS_VALU_TRANS_F32, counted four times).
-MEASURED_TRAFFIC = {}
-MEASURED_ISSUE_SLOTS = {}
+# From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt), per launch of the first
+# fused block: HBM bytes moved (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
+# size), and the cycles its vector ALUs were busy summed over the 1024 SIMDs (4 x SQ_ACTIVE_INST_VALU).
+MEASURED_TRAFFIC = {"C2": 1258.2e6, "C3": 911.5e6, "C5": 15888.5e6}
+MEASURED_VALU_BUSY_CYCLES = {"C2": 1.2947e9, "C3": 1.1308e9, "C5": 2.1330e10}
 
 
 def time_events(fn, reps):
@@ -161,9 +159,10 @@ def main():
                        "block_gbs": ab["block"] * N / (t_block_ms * 1e-3) / 1e9,
                        # what one launch per iteration would have had to move for the same iterations
                        "block_equivalent_per_iteration_gbs": ab["iter"] * N * K0 / (t_block_ms * 1e-3) / 1e9})
-        slots = MEASURED_ISSUE_SLOTS.get(args.config)
-        if slots:
-            detail["block_valu_issue_utilisation"] = slots / (t_block_ms * 1e-3) / VALU_ISSUE_PEAK
+        busy = MEASURED_VALU_BUSY_CYCLES.get(args.config)
+        if busy:
+            # share of the launch during which the vector ALUs were issuing (1024 SIMDs at 2.4 GHz)
+            detail["block_valu_busy_frac"] = busy / (t_block_ms * 1e-3 * 1024 * 2.4e9)
         roofline = {"bound": "alu", "kernel": "newton_fused_kernel", "achieved": ach, "peak": VALU_F32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / VALU_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(args.config)}
     if w.cell != "tanh_dense":

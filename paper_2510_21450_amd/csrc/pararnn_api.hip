@@ -56,7 +56,7 @@ TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_el
         cfg = {1, 2, 8, 8};
     } else if (fused) {
         // the one-launch path is bound by vector arithmetic, not by HBM: shorter tiles, more workgroups per CU
-        if (lstm) cfg = {1, 1, 8, 16};
+        if (lstm) cfg = {1, 1, 16, 8};                   // 64 channels x 128 steps
         else cfg = {1, 1, 8, 8};                         // 64 channels x 64 steps
     } else if (!backward) {
         if (lstm) cfg = {1, 1, 8, 16};                   // 64 channels x 128 steps

@@ -15,7 +15,11 @@ __global__ void reset_kernel(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, 
         ctrl->status = status0;
         if (iters_out) { iters_out[0] = 0; iters_out[1] = status0; }
     }
-    for (size_t j = i; j < n_rec; j += (size_t)gridDim.x * blockDim.x) rec[j] = 0ull;
+    // two records per store (the array is 256-byte aligned); the odd last one separately
+    ulonglong2 *rec2 = reinterpret_cast<ulonglong2 *>(rec);
+    const size_t n2 = n_rec / 2;
+    for (size_t j = i; j < n2; j += (size_t)gridDim.x * blockDim.x) rec2[j] = make_ulonglong2(0ull, 0ull);
+    if (i == 0 && (n_rec & 1)) rec[n_rec - 1] = 0ull;
 }
 
 // bf16 storage: round the converged fp32 iterate once into the output.
@@ -73,9 +77,10 @@ namespace pararnn {
 hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *iters_out, int status0,
                         hipStream_t st)
 {
-    size_t blocks = (n_rec + 255) / 256;
+    size_t blocks = (n_rec / 2 + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 2048) blocks = 2048;
+    const size_t cap = (size_t)device_cu_count() * 32;
+    if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ctrl, rec, n_rec, iters_out,
                        status0);
     return hipGetLastError();
