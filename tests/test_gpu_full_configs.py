@@ -91,3 +91,39 @@ def test_full_size_config(name, oracle_mod):
     hh = h[:, :, -1, :] if w.cell == "lstm_diag" else h
     assert float(hh.abs().max()) <= 1.0
     assert bool(torch.isfinite(du).all()) and bool(torch.isfinite(dp).all())
+
+
+def test_four_times_config_5(oracle_mod):
+    """2^32 timestep-channels (config 5's recipe at B=8, L=131072; about 100 GB of
+    tensors and workspace): element counts beyond 32 bits, two million tiles,
+    carry records in the gigabytes.  Sampled channels against the oracle."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C5"].scaled(B=8, L=131072)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 120 << 30:
+        pytest.skip("needs 120 GB of free device memory")
+    print("4 x C5: generating inputs", flush=True)
+    d = make_inputs(w, device="cuda")
+    params, u, h0, g = d["params"], d["u"], d["h0"], d["g"]
+    print("4 x C5: forward", flush=True)
+    h, iters, tr = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    assert st == 0 and 4 <= it <= 6, (it, st)
+    print(f"4 x C5: backward (iters={it})", flush=True)
+    du, dp, dh0 = P.backward(w.cell, params, u, h0, h, g)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    chans = np.unique(np.concatenate([rng.choice(w.H, size=20, replace=False), [0, 63, 64, w.H - 1]]))
+    idx = torch.as_tensor(chans, device="cuda")
+    pn, un, h0n = f64(params.index_select(-1, idx)), f64(u.index_select(-1, idx)), f64(h0.index_select(-1, idx))
+    gn, hn = f64(g.index_select(-1, idx)), f64(h.index_select(-1, idx))
+    print(f"4 x C5: oracle on {len(chans)} channels", flush=True)
+    ref = oracle_mod.seq_unroll(w.cell, pn, un, h0n)
+    rdu, rdp, rdh0 = oracle_mod.backward(w.cell, pn, un, h0n, hn, gn)
+    errs = (relerr(hn, ref), relerr(f64(du.index_select(-1, idx)), rdu), relerr(f64(dp.index_select(-1, idx)), rdp),
+            relerr(f64(dh0.index_select(-1, idx)), rdh0))
+    print("4 x C5: rel err h, du, dparams, dh0 =", errs, flush=True)
+    assert max(errs) <= 2e-2
+    # the last timesteps of the last sequence were reached by the scan (not left at the initial guess)
+    assert float(h.abs().max()) <= 1.0 and bool(torch.isfinite(h[-1, -4096:]).all())
