@@ -174,6 +174,10 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
  *   dL_dparams      out fp32, same shape as params; overwritten, not accumulated
  *   dL_dh0          out [B][S][H], or NULL
  *   workspace       DEVICE scratch of at least pararnn_workspace_bytes(.., 1)
+ * Dense cell (H = 64, fp32): with mu_l = (1 - F_l^2) * lam_l the recurrence reads
+ * mu_l = diag(1 - F_l^2) W^T mu_{l+1} + (1 - F_l^2) * g_l, which the forward scan
+ * kernels run with W^T and the time axis reversed; dL_du = mu, dL_dparams =
+ * dL/dW = sum_{b,l} mu_l h_{l-1}^T, dL_dh0 = W^T mu_1.
  * Same return convention as pararnn_forward.
  */
 int pararnn_backward(int cell, int dtype, const float *params, const void *u, const void *h0,

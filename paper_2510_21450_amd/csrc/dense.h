@@ -10,6 +10,11 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
                   int max_iter, void *h, int *iters, float *delta_trace, void *workspace, size_t workspace_bytes,
                   hipStream_t st);
 
+// Adjoint scan and gradients at the forward result h: du [B][L][H], dW [H][H], dh0 [B][H] (or NULL).
+int dense_backward(int dtype, const float *W, const void *u, const void *h0, const void *h, const void *g, int B,
+                   int L, int H, void *du, float *dW, void *dh0, void *workspace, size_t workspace_bytes,
+                   hipStream_t st);
+
 // Timesteps per chunk of the dense scan, and its composition kernel alone:
 // A[b][c] = J_e ... J_s, J_l = diag(d_l) W, for the chunks 1 .. n_c-2 (the ones the
 // scan needs); ctrl_scratch is 256 bytes of device memory.

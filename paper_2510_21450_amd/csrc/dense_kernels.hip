@@ -13,6 +13,14 @@
 // mat-vecs W delta of different columns become one MFMA product W [delta];
 // the per-column factor d_l is applied to the product afterwards.
 //
+// Backward (Eq. (6)): with mu_l = d_l * lam_l (which is dL/du_l) the adjoint
+// recurrence lam_l = g_l + W^T (d_{l+1} * lam_{l+1}) becomes
+//   mu_l = diag(d_l) W^T mu_{l+1} + d_l * g_l,
+// the same affine recurrence as the forward solve with W^T in place of W, the
+// time axis reversed and r_l = d_l * g_l: the same kernels run it (rev = 1,
+// W = the transposed matrix), followed by dL/dh0 = W^T mu_1 and
+// dL/dW = sum_{b,l} mu_l h_{l-1}^T (one more MFMA reduction).
+//
 // MFMA operand trick: the 32x32 accumulator layout (lane = column, register v
 // of lane half h = row 8*(v/4) + 4*h + v%4) is used unchanged as the B operand
 // of the next product; the k-pair an instruction consumes is then (row(v,0),
@@ -52,7 +60,17 @@ struct DenseArgs {
     int B, L, n_c;
     int k, max_iter;
     float tol;
+    // backward
+    const float *g;      // dL/dh [B][L][64]
+    float *du;           // out [B][L][64]: mu
+    int rev;             // 1: scan step t of the recurrence is timestep L-1-t
 };
+
+// row of the [B][L][64] arrays that scan step t of sequence b touches
+__device__ __forceinline__ size_t scan_row(const DenseArgs &a, size_t b, int t)
+{
+    return b * a.L + (a.rev ? a.L - 1 - t : t);
+}
 
 __device__ __forceinline__ int mfma_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
 
@@ -165,13 +183,13 @@ __global__ __launch_bounds__(256, 2) void dense_chunk_products_kernel(const Dens
 
     // P = J_ls in accumulator layout: P[mt][nt][v] = d[row] W[row][32 nt + n]
     f16v P[2][2], Q[2][2];
-    const float *dl = a.d + ((size_t)b * a.L + ls) * DH;
+    const float *dl0 = a.d + scan_row(a, b, ls) * DH;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = 32 * mt + mfma_row(v, half);
-            const float dv = dl[row];
+            const float dv = dl0[row];
             P[mt][0][v] = dv * a.W[row * DH + n];
             P[mt][1][v] = dv * a.W[row * DH + 32 + n];
         }
@@ -198,7 +216,7 @@ __global__ __launch_bounds__(256, 2) void dense_chunk_products_kernel(const Dens
     };
     // row factors of the next two steps are fetched while the current two run
     // (indices clamped to the chunk: the extra values are never used)
-    auto dload = [&](int i, int hi) { return dl[min(i, n_steps - 1) * DH + 32 * hi + n]; };
+    auto dload = [&](int i, int hi) { return a.d[scan_row(a, b, ls + min(i, n_steps - 1)) * DH + 32 * hi + n]; };
     float da0 = dload(1, 0), da1 = dload(1, 1), db0 = dload(2, 0), db1 = dload(2, 1);
     int i = 1;
 #pragma unroll 1
@@ -267,7 +285,8 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 // between steps orders LDS only.
 // final = 0: x starts at 0, only the end value is kept (b_c).
 // final = 1: x starts at x_{c-1}; afterwards h += delta and max|delta|.
-template <int FINAL>
+// BWD: the backward recurrence (r_l = d_l * g_l; the final sweep writes mu = dL/du and nothing else).
+template <int FINAL, bool BWD = false>
 __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
 {
     __shared__ f4v s_x[2][4][64];
@@ -286,14 +305,15 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
     float wa[4][4];
     load_w_operand16(a.W, w, n, g, wa);
     const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    f4v dv[CD], rv[CD], hv[FINAL ? CD : 1];
+    f4v dv[CD], rv[CD], hv[(FINAL && !BWD) ? CD : 1];
 #pragma unroll
     for (int i = 0; i < CD; ++i) {
         const int l = ls + i;
-        const size_t off = ((size_t)b * a.L + min(l, a.L - 1)) * DH + chn;
+        const size_t off = scan_row(a, b, min(l, a.L - 1)) * DH + chn;
         dv[i] = *reinterpret_cast<const f4v *>(a.d + off);
-        rv[i] = *reinterpret_cast<const f4v *>(a.r + off);
-        if (FINAL) hv[i] = *reinterpret_cast<const f4v *>(a.h + off);
+        if (BWD) rv[i] = dv[i] * *reinterpret_cast<const f4v *>(a.g + off);
+        else rv[i] = *reinterpret_cast<const f4v *>(a.r + off);
+        if (FINAL && !BWD) hv[i] = *reinterpret_cast<const f4v *>(a.h + off);
         if (!(ok && l < a.L)) { dv[i] = zero; rv[i] = zero; }     // steps past the end leave x = 0
     }
     f4v x = zero;
@@ -321,6 +341,14 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
     }
     if (!FINAL) {
         if (ok) *reinterpret_cast<f4v *>(a.bc + ((size_t)b * a.n_c + c) * DH + chn) = x;
+        return;
+    }
+    if (BWD) {
+#pragma unroll
+        for (int i = 0; i < CD; ++i) {
+            const int l = ls + i;
+            if (ok && l < a.L) *reinterpret_cast<f4v *>(a.du + scan_row(a, b, l) * DH + chn) = rv[i];
+        }
         return;
     }
     float wmax = 0.0f;
@@ -400,6 +428,66 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
     }
 }
 
+// ------------------------------------------------------------ backward extras
+// Wt = W^T (16 KB)
+__global__ __launch_bounds__(256) void dense_transpose_kernel(const float *W, float *Wt)
+{
+    for (int i = threadIdx.x; i < DH * DH; i += 256) Wt[(i % DH) * DH + i / DH] = W[i];
+}
+
+// dL/dh0[b] = W^T mu_{b,0}: thread j sums over the rows i of W
+__global__ __launch_bounds__(64) void dense_dh0_kernel(const float *W, const float *mu, int L, float *dh0)
+{
+    const int b = blockIdx.x, j = threadIdx.x;
+    const float *m = mu + (size_t)b * L * DH;
+    float s = 0.0f;
+    for (int i = 0; i < DH; ++i) s = fmaf(W[i * DH + j], m[i], s);
+    dh0[(size_t)b * DH + j] = s;
+}
+
+// Partial sums of dL/dW = sum over rows (b, l) of mu_l h_{l-1}^T: wave p sums its
+// contiguous share of the rows as 64 x 64 x (rows) products on
+// v_mfma_f32_32x32x2_f32 (two rows per instruction: A = mu, B = h_{l-1}) and
+// writes part[p][64][64]; the partials are added in a fixed order afterwards.
+__global__ __launch_bounds__(256) void dense_dw_kernel(const DenseArgs a, float *part, int rows_per_wave)
+{
+    const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t rows = (size_t)a.B * a.L;
+    const size_t r0 = (size_t)p * rows_per_wave;
+    const size_t r1 = r0 + rows_per_wave < rows ? r0 + rows_per_wave : rows;
+    f16v Q[2][2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Q[mt][nt][v] = 0.0f;
+    for (size_t r = r0; r < r1; r += 2) {
+        const size_t row = r + half;               // this lane half's row of the pair
+        const bool ok = row < r1;
+        float m0 = 0.0f, m1 = 0.0f, h0v = 0.0f, h1v = 0.0f;
+        if (ok) {
+            m0 = a.du[row * DH + n];
+            m1 = a.du[row * DH + 32 + n];
+            const int l = (int)(row % a.L);
+            const float *hp = l == 0 ? (a.h0 ? a.h0 + (row / a.L) * DH : nullptr) : a.h + (row - 1) * DH;
+            if (hp) { h0v = hp[n]; h1v = hp[32 + n]; }
+        }
+        Q[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(m0, h0v, Q[0][0], 0, 0, 0);
+        Q[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(m0, h1v, Q[0][1], 0, 0, 0);
+        Q[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(m1, h0v, Q[1][0], 0, 0, 0);
+        Q[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(m1, h1v, Q[1][1], 0, 0, 0);
+    }
+    float *out = part + (size_t)p * DH * DH;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[(32 * mt + mfma_row(v, half)) * DH + 32 * nt + n] = Q[mt][nt][v];
+}
+
 size_t r256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct DenseLayout { size_t off_d, off_r, off_A, off_b, off_x, total; int n_c; };
@@ -439,10 +527,74 @@ int dense_chunk_products(const float *W, const float *d, int B, int L, int H, fl
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
+// waves that share the rows of the dL/dW reduction (a multiple of 4: whole workgroups)
+int dw_waves(int B, int L)
+{
+    const size_t rows = (size_t)B * L;
+    size_t wv = (rows + 63) / 64;                 // at least 64 rows per wave
+    if (wv > 1024) wv = 1024;
+    return (int)((wv + 3) / 4 * 4);
+}
+
 size_t dense_workspace_bytes(int dtype, int B, int L, int H, int backward)
 {
-    if (dtype != PARARNN_F32 || H != DH || backward) return 256;
-    return dense_layout(B, L).total;
+    if (dtype != PARARNN_F32 || H != DH) return 256;
+    const DenseLayout lo = dense_layout(B, L);
+    if (!backward) return lo.total;
+    // the forward layout, then W^T and the dL/dW partials
+    return lo.total + r256((size_t)DH * DH * 4) + r256((size_t)dw_waves(B, L) * DH * DH * 4);
+}
+
+int dense_backward(int dtype, const float *W, const void *u, const void *h0, const void *h, const void *g, int B,
+                   int L, int H, void *du, float *dW, void *dh0, void *workspace, size_t workspace_bytes,
+                   hipStream_t st)
+{
+    if (dtype != PARARNN_F32 || H != DH) return PARARNN_UNSUPPORTED;
+    if (((uintptr_t)W | (uintptr_t)u | (uintptr_t)h | (uintptr_t)h0 | (uintptr_t)g | (uintptr_t)du) % 16)
+        return PARARNN_UNSUPPORTED;
+    if (workspace_bytes < dense_workspace_bytes(dtype, B, L, H, 1)) return PARARNN_WORKSPACE_TOO_SMALL;
+    const DenseLayout lo = dense_layout(B, L);
+    char *ws = static_cast<char *>(workspace);
+    float *Wt = reinterpret_cast<float *>(ws + lo.total);
+    float *part = reinterpret_cast<float *>(ws + lo.total + r256((size_t)DH * DH * 4));
+    DenseArgs a;
+    memset(&a, 0, sizeof(a));
+    a.u = static_cast<const float *>(u); a.h0 = static_cast<const float *>(h0);
+    a.h = const_cast<float *>(static_cast<const float *>(h));       // only read on this path
+    a.d = reinterpret_cast<float *>(ws + lo.off_d);
+    a.r = reinterpret_cast<float *>(ws + lo.off_r);
+    a.Ac = reinterpret_cast<float *>(ws + lo.off_A);
+    a.bc = reinterpret_cast<float *>(ws + lo.off_b);
+    a.xc = reinterpret_cast<float *>(ws + lo.off_x);
+    a.ctrl = reinterpret_cast<Ctrl *>(ws);
+    a.g = static_cast<const float *>(g); a.du = static_cast<float *>(du);
+    a.B = B; a.L = L; a.n_c = lo.n_c;
+    if (launch_reset(a.ctrl, nullptr, 0, nullptr, 0, st) != hipSuccess) return PARARNN_HIP_ERROR;
+    hipLaunchKernelGGL(dense_transpose_kernel, dim3(1), dim3(256), 0, st, W, Wt);
+    // d_l = 1 - tanh^2(W h_{l-1} + u_l) at the given states (forward addressing, W itself)
+    const size_t res_items = ((size_t)B * L + 15) / 16;
+    const size_t res_cap = (size_t)device_cu_count() * 8;
+    const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
+    a.W = W; a.rev = 0;
+    hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
+    // the reverse scan with W^T
+    a.W = Wt; a.rev = 1;
+    const int n_prod = B * (lo.n_c - 2);
+    const int n_sweep = (B * lo.n_c + 15) / 16;
+    if (n_prod > 0)
+        hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((dense_sweep_kernel<0, true>), dim3(n_sweep), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((dense_sweep_kernel<1, true>), dim3(n_sweep), dim3(256), 0, st, a);
+    // step-local gradients
+    if (dh0) hipLaunchKernelGGL(dense_dh0_kernel, dim3(B), dim3(64), 0, st, W, a.du, L, static_cast<float *>(dh0));
+    const int wv = dw_waves(B, L);
+    const size_t rows = (size_t)B * L;
+    int rows_per_wave = (int)((rows + wv - 1) / wv);
+    rows_per_wave += rows_per_wave & 1;           // pairs of rows
+    hipLaunchKernelGGL(dense_dw_kernel, dim3(wv / 4), dim3(256), 0, st, a, part, rows_per_wave);
+    if (hipGetLastError() != hipSuccess) return PARARNN_HIP_ERROR;
+    return launch_param_reduce(part, dW, wv, DH * DH, st) == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
 int dense_forward(int dtype, const float *W, const void *u, const void *h0, int B, int L, int H, float tol,
@@ -455,6 +607,7 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
     DenseArgs a;
+    memset(&a, 0, sizeof(a));
     a.W = W; a.u = static_cast<const float *>(u); a.h0 = static_cast<const float *>(h0);
     a.h = static_cast<float *>(h);
     a.d = reinterpret_cast<float *>(ws + lo.off_d);

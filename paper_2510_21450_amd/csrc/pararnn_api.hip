@@ -372,7 +372,9 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
         (dL_dh0 && !aligned(dL_dh0, esz)))
         return PARARNN_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (cell == PARARNN_TANH_DENSE) return PARARNN_UNSUPPORTED;
+    if (cell == PARARNN_TANH_DENSE)
+        return dense_backward(dtype, params, u, h0, h, dL_dh, B, L, H, dL_du, dL_dparams, dL_dh0, workspace,
+                              workspace_bytes, st);
 
     int al = align_elems(esz, {u, h, h0, dL_dh, dL_du, dL_dh0});
     const int alp = align_elems(4, {params, dL_dparams});

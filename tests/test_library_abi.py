@@ -99,7 +99,8 @@ def test_host_side_argument_validation(lib):
     b.restype = ctypes.c_int
     b.argtypes = [i, i, vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, sz, vp]
     assert b(0, 0, p, p, None, p, None, 1, 8, 8, p, p, None, p, 1 << 20, None) == INVALID      # dL_dh NULL
-    assert b(2, 0, p, p, None, p, p, 1, 8, 64, p, p, None, p, 1 << 20, None) == 6              # dense backward
+    assert b(2, 0, p, p, None, p, p, 1, 8, 32, p, p, None, p, 1 << 20, None) == 6              # dense path: H = 64 only
+    assert b(2, 0, p, p, None, p, p, 1, 8, 64, p, p, None, p, 4096, None) == 3                 # dense backward workspace
     s = lib.pararnn_affine_scan
     s.restype = ctypes.c_int
     s.argtypes = [i, i, vp, vp, i, i, i, vp, vp, sz, vp]
