@@ -5,6 +5,10 @@
 // values), u[] the G pre-activations.  J is row-major S x S with
 // J[p*S+q] = d(out_p)/d(in_q).
 //
+// step<true> / fwd<true> are the folded forms: u[] then holds fold_u()'s output
+// (the gate inputs u + b scaled for the exp2-based nonlinearities) and q[] the
+// PQ scaled weights from fold_params(); p[] is still needed for the Jacobian.
+//
 // Backward (Sec. 2, Eq. (6)): bwd_prep returns J and NC coefficients from which
 // bwd_emit maps the incoming adjoint lam (dL/d state_l) to dL/du_l and adds this
 // step's contribution to the PR parameter-gradient accumulators.
@@ -15,31 +19,44 @@ namespace pararnn {
 
 // Sec. 3, Eq. (7a) with the diagonal weights of Eq. (9); Jacobian Eq. (8a).
 struct GruDiag {
-    static constexpr int G = 3, S = 1, PR = 6, NC = 5;
+    static constexpr int G = 3, S = 1, PR = 6, NC = 5, PQ = 3;
 
-    __device__ __forceinline__ static void gates(const float *p, float h, const float *u, float &z,
-                                                 float &r, float &rh, float &c)
+    __device__ __forceinline__ static void fold_params(const float *p, float *q)
     {
-        z = fast_sigmoid(fmaf(p[0], h, u[0] + p[3]));
-        r = fast_sigmoid(fmaf(p[1], h, u[1] + p[4]));
-        rh = r * h;
-        c = fast_tanh(fmaf(p[2], rh, u[2] + p[5]));
+        q[0] = kSigFold * p[0]; q[1] = kSigFold * p[1]; q[2] = kTanhFold * p[2];
+    }
+    __device__ __forceinline__ static void fold_u(const float *p, float *u)
+    {
+        u[0] = kSigFold * (u[0] + p[3]); u[1] = kSigFold * (u[1] + p[4]); u[2] = kTanhFold * (u[2] + p[5]);
     }
 
-    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    template <bool FOLD>
+    __device__ __forceinline__ static void gates(const float *p, const float *q, float h, const float *u, float &z,
+                                                 float &r, float &rh, float &c)
+    {
+        z = gate_sigmoid<FOLD>(gate_in<FOLD>(p[0], FOLD ? q[0] : 0.0f, h, u[0], p[3]));
+        r = gate_sigmoid<FOLD>(gate_in<FOLD>(p[1], FOLD ? q[1] : 0.0f, h, u[1], p[4]));
+        rh = r * h;
+        c = gate_tanh<FOLD>(gate_in<FOLD>(p[2], FOLD ? q[2] : 0.0f, rh, u[2], p[5]));
+    }
+
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F,
+                                                const float *q = nullptr)
     {
         float z, r, rh, c;
-        gates(p, hp[0], u, z, r, rh, c);
+        gates<FOLD>(p, q, hp[0], u, z, r, rh, c);
         F[0] = fmaf(z, c - hp[0], hp[0]);
     }
 
     // k_z = (c-h) z(1-z), k_c = z (1-c^2), k_r = k_c a_c h r(1-r) are df/du_z,
     // df/du_c, df/du_r;  J = (1-z) + a_z k_z + a_c r k_c + a_r k_r  (Eq. (8a)).
-    __device__ __forceinline__ static void coefs(const float *p, float h, const float *u, float &F,
+    template <bool FOLD>
+    __device__ __forceinline__ static void coefs(const float *p, const float *q, float h, const float *u, float &F,
                                                  float &J, float &kz, float &kr, float &kc, float &rh)
     {
         float z, r, c;
-        gates(p, h, u, z, r, rh, c);
+        gates<FOLD>(p, q, h, u, z, r, rh, c);
         const float cmh = c - h, omz = 1.0f - z;
         F = fmaf(z, cmh, h);
         kz = cmh * (z * omz);
@@ -51,17 +68,19 @@ struct GruDiag {
         J = fmaf(p[1], kr, J);
     }
 
-    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J,
+                                               const float *q = nullptr)
     {
         float kz, kr, kc, rh;
-        coefs(p, hp[0], u, F[0], J[0], kz, kr, kc, rh);
+        coefs<FOLD>(p, q, hp[0], u, F[0], J[0], kz, kr, kc, rh);
     }
 
     __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
                                                     float *J, float *k)
     {
         float F;
-        coefs(p, hp[0], u, F, J[0], k[0], k[1], k[2], k[4]);
+        coefs<false>(p, nullptr, hp[0], u, F, J[0], k[0], k[1], k[2], k[4]);
         k[3] = hp[0];
     }
 
@@ -83,29 +102,47 @@ struct GruDiag {
 // through diagonal weights; state (c, h); 2x2 Jacobian block per channel (the
 // block structure of Eq. (8b)).
 struct LstmDiag {
-    static constexpr int G = 4, S = 2, PR = 8, NC = 6;
+    static constexpr int G = 4, S = 2, PR = 8, NC = 6, PQ = 4;
 
-    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    __device__ __forceinline__ static void fold_params(const float *p, float *q)
     {
-        const float h = hp[1];
-        const float i = fast_sigmoid(fmaf(p[0], h, u[0] + p[4]));
-        const float f = fast_sigmoid(fmaf(p[1], h, u[1] + p[5]));
-        const float o = fast_sigmoid(fmaf(p[2], h, u[2] + p[6]));
-        const float g = fast_tanh(fmaf(p[3], h, u[3] + p[7]));
+        q[0] = kSigFold * p[0]; q[1] = kSigFold * p[1]; q[2] = kSigFold * p[2]; q[3] = kTanhFold * p[3];
+    }
+    __device__ __forceinline__ static void fold_u(const float *p, float *u)
+    {
+        u[0] = kSigFold * (u[0] + p[4]); u[1] = kSigFold * (u[1] + p[5]);
+        u[2] = kSigFold * (u[2] + p[6]); u[3] = kTanhFold * (u[3] + p[7]);
+    }
+
+    template <bool FOLD>
+    __device__ __forceinline__ static void gates(const float *p, const float *q, float h, const float *u, float &i,
+                                                 float &f, float &o, float &g)
+    {
+        i = gate_sigmoid<FOLD>(gate_in<FOLD>(p[0], FOLD ? q[0] : 0.0f, h, u[0], p[4]));
+        f = gate_sigmoid<FOLD>(gate_in<FOLD>(p[1], FOLD ? q[1] : 0.0f, h, u[1], p[5]));
+        o = gate_sigmoid<FOLD>(gate_in<FOLD>(p[2], FOLD ? q[2] : 0.0f, h, u[2], p[6]));
+        g = gate_tanh<FOLD>(gate_in<FOLD>(p[3], FOLD ? q[3] : 0.0f, h, u[3], p[7]));
+    }
+
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F,
+                                                const float *q = nullptr)
+    {
+        float i, f, o, g;
+        gates<FOLD>(p, q, hp[1], u, i, f, o, g);
         F[0] = fmaf(f, hp[0], i * g);
         F[1] = o * fast_tanh(F[0]);
     }
 
     // k[0..3] = d c'/d u_{i,f,g-slot order i,f,o,g} with k[2] = d h'/d u_o,
     // k[4] = o (1 - tanh(c')^2) = d h'/d c', k[5] = h.
-    __device__ __forceinline__ static void coefs(const float *p, const float *hp, const float *u, float *F,
-                                                 float *J, float *k)
+    template <bool FOLD>
+    __device__ __forceinline__ static void coefs(const float *p, const float *q, const float *hp, const float *u,
+                                                 float *F, float *J, float *k)
     {
         const float c = hp[0], h = hp[1];
-        const float i = fast_sigmoid(fmaf(p[0], h, u[0] + p[4]));
-        const float f = fast_sigmoid(fmaf(p[1], h, u[1] + p[5]));
-        const float o = fast_sigmoid(fmaf(p[2], h, u[2] + p[6]));
-        const float g = fast_tanh(fmaf(p[3], h, u[3] + p[7]));
+        float i, f, o, g;
+        gates<FOLD>(p, q, h, u, i, f, o, g);
         const float cn = fmaf(f, c, i * g);
         const float t = fast_tanh(cn);
         F[0] = cn;
@@ -123,17 +160,19 @@ struct LstmDiag {
         J[3] = fmaf(k[2], p[2], k[4] * jch);
     }
 
-    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J,
+                                               const float *q = nullptr)
     {
         float k[NC];
-        coefs(p, hp, u, F, J, k);
+        coefs<FOLD>(p, q, hp, u, F, J, k);
     }
 
     __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
                                                     float *J, float *k)
     {
         float F[2];
-        coefs(p, hp, u, F, J, k);
+        coefs<false>(p, nullptr, hp, u, F, J, k);
     }
 
     __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
@@ -156,30 +195,64 @@ struct LstmDiag {
 // into o, candidate nonlinearity tanh.  Jacobian blocks: Eq. (8b).
 // Parameter rows: a_f, a_z, a_o, c_f, c_o, b_f, b_z, b_o.  Gates (f, z, o).
 struct ParaLstmDiag {
-    static constexpr int G = 3, S = 2, PR = 8, NC = 8;
+    static constexpr int G = 3, S = 2, PR = 8, NC = 8, PQ = 5;
 
-    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    // q = scaled a_f, a_z, a_o, c_f, c_o
+    __device__ __forceinline__ static void fold_params(const float *p, float *q)
+    {
+        q[0] = kSigFold * p[0]; q[1] = kTanhFold * p[1]; q[2] = kSigFold * p[2];
+        q[3] = kSigFold * p[3]; q[4] = kSigFold * p[4];
+    }
+    __device__ __forceinline__ static void fold_u(const float *p, float *u)
+    {
+        u[0] = kSigFold * (u[0] + p[5]); u[1] = kTanhFold * (u[1] + p[6]); u[2] = kSigFold * (u[2] + p[7]);
+    }
+
+    // f and z from the previous state; o needs the new c
+    template <bool FOLD>
+    __device__ __forceinline__ static void gates_fz(const float *p, const float *q, float c, float h, const float *u,
+                                                    float &f, float &z)
+    {
+        if constexpr (FOLD) {
+            f = gate_sigmoid<true>(fmaf(q[0], h, fmaf(q[3], c, u[0])));
+            z = gate_tanh<true>(fmaf(q[1], h, u[1]));
+        } else {
+            f = fast_sigmoid(fmaf(p[0], h, fmaf(p[3], c, u[0] + p[5])));
+            z = fast_tanh(fmaf(p[1], h, u[1] + p[6]));
+        }
+    }
+    template <bool FOLD>
+    __device__ __forceinline__ static float gate_o(const float *p, const float *q, float cn, float h, const float *u)
+    {
+        if constexpr (FOLD) return gate_sigmoid<true>(fmaf(q[2], h, fmaf(q[4], cn, u[2])));
+        else return fast_sigmoid(fmaf(p[2], h, fmaf(p[4], cn, u[2] + p[7])));
+    }
+
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F,
+                                                const float *q = nullptr)
     {
         const float c = hp[0], h = hp[1];
-        const float f = fast_sigmoid(fmaf(p[0], h, fmaf(p[3], c, u[0] + p[5])));
-        const float z = fast_tanh(fmaf(p[1], h, u[1] + p[6]));
+        float f, z;
+        gates_fz<FOLD>(p, q, c, h, u, f, z);
         const float cn = fmaf(f, c - z, z);
-        const float o = fast_sigmoid(fmaf(p[2], h, fmaf(p[4], cn, u[2] + p[7])));
+        const float o = gate_o<FOLD>(p, q, cn, h, u);
         F[0] = cn;
         F[1] = o * fast_tanh(cn);
     }
 
     // k[0] = d c'/d u_f = (c - z) f(1-f), k[1] = d c'/d u_z = (1-f)(1-z^2),
     // k[2] = d h'/d u_o = t o(1-o), k[3] = o (1-t^2), k[4] = c_o, k[5] = h, k[6] = c, k[7] = c'.
-    __device__ __forceinline__ static void coefs(const float *p, const float *hp, const float *u, float *F,
-                                                 float *J, float *k)
+    template <bool FOLD>
+    __device__ __forceinline__ static void coefs(const float *p, const float *q, const float *hp, const float *u,
+                                                 float *F, float *J, float *k)
     {
         const float c = hp[0], h = hp[1];
-        const float f = fast_sigmoid(fmaf(p[0], h, fmaf(p[3], c, u[0] + p[5])));
-        const float z = fast_tanh(fmaf(p[1], h, u[1] + p[6]));
+        float f, z;
+        gates_fz<FOLD>(p, q, c, h, u, f, z);
         const float cmz = c - z;
         const float cn = fmaf(f, cmz, z);
-        const float o = fast_sigmoid(fmaf(p[2], h, fmaf(p[4], cn, u[2] + p[7])));
+        const float o = gate_o<FOLD>(p, q, cn, h, u);
         const float t = fast_tanh(cn);
         F[0] = cn;
         F[1] = o * t;
@@ -200,17 +273,19 @@ struct ParaLstmDiag {
         J[3] = fmaf(k[2], p[2], hc * jch);
     }
 
-    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J,
+                                               const float *q = nullptr)
     {
         float k[NC];
-        coefs(p, hp, u, F, J, k);
+        coefs<FOLD>(p, q, hp, u, F, J, k);
     }
 
     __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
                                                     float *J, float *k)
     {
         float F[2];
-        coefs(p, hp, u, F, J, k);
+        coefs<false>(p, nullptr, hp, u, F, J, k);
     }
 
     __device__ __forceinline__ static void bwd_emit(const float *k, const float *lam, float *du, float *acc)
@@ -234,15 +309,22 @@ struct ParaLstmDiag {
 
 // Linear SSM of the footnote in Sec. 2: f = a h + u + b, J = a.
 struct LinearDiag {
-    static constexpr int G = 1, S = 1, PR = 2, NC = 1;
+    static constexpr int G = 1, S = 1, PR = 2, NC = 1, PQ = 0;
 
-    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F)
+    __device__ __forceinline__ static void fold_params(const float *, float *) {}
+    __device__ __forceinline__ static void fold_u(const float *p, float *u) { u[0] += p[1]; }
+
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void step(const float *p, const float *hp, const float *u, float *F,
+                                                const float * = nullptr)
     {
-        F[0] = fmaf(p[0], hp[0], u[0] + p[1]);
+        F[0] = fmaf(p[0], hp[0], FOLD ? u[0] : u[0] + p[1]);
     }
-    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J)
+    template <bool FOLD = false>
+    __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J,
+                                               const float * = nullptr)
     {
-        step(p, hp, u, F);
+        step<FOLD>(p, hp, u, F);
         J[0] = p[0];
     }
     __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *, float *J, float *k)

@@ -184,6 +184,29 @@ __device__ __forceinline__ float fast_tanh(float x)
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * x));
 }
 
+// Folded gate arithmetic, for kernels that evaluate a cell several times on the
+// same u (the fused blocks): the gate input u + b is scaled once by the factor
+// the exp2-based sigmoid / tanh needs, and the recurrent weights likewise, so
+// that a gate costs one FMA, one exp2 and one rcp.  FOLD = false is the plain form.
+constexpr float kSigFold = -1.4426950408889634f;    // sigmoid(x) = 1 / (1 + 2^(kSigFold x))
+constexpr float kTanhFold = 2.8853900817779268f;    // tanh(x) = 1 - 2 / (1 + 2^(kTanhFold x))
+template <bool FOLD> __device__ __forceinline__ float gate_sigmoid(float x)
+{
+    if constexpr (FOLD) return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x));
+    else return fast_sigmoid(x);
+}
+template <bool FOLD> __device__ __forceinline__ float gate_tanh(float x)
+{
+    if constexpr (FOLD) return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x)), 1.0f);
+    else return fast_tanh(x);
+}
+// w h + u + b, or in folded form wq h + u (u and wq pre-scaled, b inside u)
+template <bool FOLD> __device__ __forceinline__ float gate_in(float w, float wq, float h, float u, float b)
+{
+    if constexpr (FOLD) return fmaf(wq, h, u);
+    else return fmaf(w, h, u + b);
+}
+
 // Workgroup barrier that orders LDS accesses only: global loads and stores
 // issued before it stay in flight (a full __syncthreads() waits for them).
 __device__ __forceinline__ void lds_barrier()

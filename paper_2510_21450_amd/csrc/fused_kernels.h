@@ -106,6 +106,10 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 #pragma unroll
             for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
         }
+        // weights scaled for the folded gate arithmetic (u is folded once below, then reused K times)
+        float pq[VEC][Cell::PQ > 0 ? Cell::PQ : 1];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) Cell::fold_params(p[v], pq[v]);
 
         // ---- u for the C steps of this thread (kept for all iterations), the row before, h0
         using RawU = typename RawVec<UT, VEC>::type;
@@ -146,6 +150,15 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         for (int i = 0; i < C; ++i) {
 #pragma unroll
             for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu[i][q]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float ug[G];
+#pragma unroll
+                for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                Cell::fold_u(p[v], ug);
+#pragma unroll
+                for (int q = 0; q < G; ++q) uu[i][q][v] = ug[q];
+            }
             if (resume) {
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
@@ -162,7 +175,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
 #pragma unroll
                 for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
-                Cell::step(p[v], h1, ug, F0);
+                Cell::template step<true>(p[v], h1, ug, F0, pq[v]);
 #pragma unroll
                 for (int s = 0; s < S; ++s) ho[i][s][v] = F0[s];
             }
@@ -194,7 +207,8 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 for (int s = 0; s < S; ++s) h1[s] = h0v[s][v];
 #pragma unroll
                 for (int q = 0; q < G; ++q) ug[q] = uh[q][v];
-                Cell::step(p[v], h1, ug, F0);
+                Cell::fold_u(p[v], ug);
+                Cell::template step<true>(p[v], h1, ug, F0, pq[v]);
 #pragma unroll
                 for (int s = 0; s < S; ++s) hprev[s][v] = F0[s];
             }
@@ -223,7 +237,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                         for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
 #pragma unroll
                         for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
-                        Cell::fwd(p[v], hp, ug, F, J);
+                        Cell::template fwd<true>(p[v], hp, ug, F, J, pq[v]);
 #pragma unroll
                         for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
                         push_step<S>(J, r, accA[v], accB[v]);
