@@ -129,6 +129,13 @@ int pararnn_set_fused(int enable);
  * iteration). */
 int pararnn_set_fused_head(int n_iters);
 
+/* The launches pararnn_forward enqueues for a solve with these settings when the
+ * workspace is of the size pararnn_workspace_bytes reports (host only, no device
+ * work): writes the number of Newton iterations of each launch to
+ * block_sizes[0 .. capacity) and returns the number of launches (which may
+ * exceed capacity), or -1 on invalid arguments.  The sizes add up to max_iter. */
+int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity);
+
 /*
  * Forward: solve Eq. (2) by Newton iterations (Alg. 1a).
  *   initial guess   h^0_l = f(h0, u_l) for every l (App. A; f(0, x_l) when h0 = 0)

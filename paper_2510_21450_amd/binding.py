@@ -34,6 +34,8 @@ _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
+_lib.pararnn_solve_plan.restype = _i
+_lib.pararnn_solve_plan.argtypes = [ctypes.c_float, _i, ctypes.POINTER(ctypes.c_int), _i]
 _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_backward.restype = _i
@@ -96,6 +98,15 @@ def workspace_bytes_fused(cell: str, dtype, B: int, L: int, H: int, n_iters: int
 def set_fused(enable: bool = True) -> None:
     """pararnn_set_fused: allow (default) or forbid the fused multi-iteration launches."""
     _raise(_lib.pararnn_set_fused(int(enable)), "pararnn_set_fused")
+
+
+def solve_plan(tol: float, max_iter: int):
+    """pararnn_solve_plan: Newton iterations per launch of a solve with the current settings."""
+    buf = (ctypes.c_int * max(1, max_iter))()
+    n = _lib.pararnn_solve_plan(float(tol), int(max_iter), buf, max(1, max_iter))
+    if n < 0:
+        raise ValueError("pararnn_solve_plan: invalid arguments")
+    return [buf[i] for i in range(n)]
 
 
 def set_fused_head(n_iters: int = 5) -> None:

@@ -138,6 +138,21 @@ int align_elems(size_t esz, std::initializer_list<const void *> ptrs)
     return a;
 }
 
+// Iterations the next launch of a solve performs: `done` of max_iter are behind it, `n_fused`
+// carry-record slots are available (0: every launch is one iteration).  The first launch takes
+// n_fused, the following ones 1, 2, 4, ... capped by n_fused and by what is left.
+int next_block_size(int done, int launches, int max_iter, int n_fused)
+{
+    int K = 1;
+    if (n_fused > 0) {
+        if (launches == 0) K = n_fused;
+        else K = launches - 1 < 30 ? 1 << (launches - 1) : n_fused;
+        if (K > n_fused) K = n_fused;
+    }
+    if (K > max_iter - done) K = max_iter - done;
+    return K;
+}
+
 // n_fused = number of carry-record slots the workspace holds (0: none; fused launches are not used).
 // tol < 0: the whole fixed-count solve is one fused launch of n_fused = max_iter iterations.
 // tol >= 0: the solve is a sequence of launches, each checked by the stopping test on the
@@ -170,14 +185,9 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
     f.head = to_tol ? 1 : 0; f.max_iter = max_iter; f.tol = a.tol;
     f.hit = to_tol ? a.hit : nullptr;
     f.bnd = a.bnd;
-    int done = 0, cur = 0, next_block = 1;
-    while (done < max_iter) {
-        int K = 1;
-        if (n_fused > 0) {
-            K = done == 0 ? n_fused : next_block;
-            if (K > n_fused) K = n_fused;
-            if (K > max_iter - done) K = max_iter - done;
-        }
+    int done = 0, cur = 0;
+    for (int launches = 0; done < max_iter; ++launches) {
+        const int K = next_block_size(done, launches, max_iter, n_fused);
         if (n_fused > 0 && (K > 1 || done == 0)) {
             f.n_iters = K; f.k0 = done; f.bnd_cur = cur;
             e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
@@ -187,7 +197,6 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
                    : Kernels<Cell, float>::newton_iter(lo.cfg, a, done == 0, st);
         }
         if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
-        if (done > 0) next_block *= 2;
         done += K;
         cur ^= 1;
     }
@@ -292,6 +301,21 @@ int pararnn_set_fused(int enable)
 {
     g_fused_enabled = enable ? 1 : 0;
     return PARARNN_OK;
+}
+
+int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity)
+{
+    if (max_iter < 0 || tol != tol || (capacity > 0 && !block_sizes)) return -1;
+    int n_fused = 0;
+    if (g_fused_enabled && max_iter >= 1)
+        n_fused = tol < 0.0f ? (max_iter <= kMaxFused ? max_iter : 0) : (max_iter < g_fused_head ? max_iter : g_fused_head);
+    int done = 0, launches = 0;
+    for (; done < max_iter; ++launches) {
+        const int K = next_block_size(done, launches, max_iter, n_fused);
+        if (launches < capacity) block_sizes[launches] = K;
+        done += K;
+    }
+    return launches;
 }
 
 int pararnn_set_fused_head(int n_iters)

@@ -113,3 +113,42 @@ def test_python_binding_refuses_cpu_tensors():
     import paper_2510_21450_amd as P
     with pytest.raises(ValueError, match="CUDA"):
         P.forward("gru_diag", torch.zeros(2, 3, 8), torch.zeros(1, 4, 3, 8))
+
+
+def test_solve_plan(lib):
+    """The launch schedule of a solve: a first fused block, then blocks of 1, 2, 4, ...
+    iterations capped by the size of the first; sizes add up to max_iter."""
+    plan = lib.pararnn_solve_plan
+    plan.restype = ctypes.c_int
+    plan.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.c_int]
+    buf = (ctypes.c_int * 256)()
+
+    def blocks(tol, max_iter):
+        n = plan(tol, max_iter, buf, 256)
+        assert 0 <= n <= 256
+        return [buf[i] for i in range(n)]
+
+    try:
+        assert lib.pararnn_set_fused_head(5) == 0 and lib.pararnn_set_fused(1) == 0
+        assert blocks(1e-5, 64) == [5, 1, 2, 4] + [5] * 10 + [2]
+        assert blocks(1e-5, 5) == [5] and blocks(1e-5, 3) == [3] and blocks(1e-5, 0) == []
+        assert blocks(1e-5, 6) == [5, 1] and blocks(1e-5, 9) == [5, 1, 2, 1]
+        # fixed-count solves: one launch up to 8 iterations, else one launch per iteration
+        assert blocks(-1.0, 3) == [3] and blocks(-1.0, 8) == [8] and blocks(-1.0, 10) == [1] * 10
+        for head in range(0, 9):
+            assert lib.pararnn_set_fused_head(head) == 0
+            for max_iter in (1, 2, 7, 8, 9, 31, 64, 200):
+                b = blocks(1e-6, max_iter)
+                assert sum(b) == max_iter and all(1 <= k <= max(head, 1) for k in b)
+                assert b[0] == (min(head, max_iter) if head else 1)
+                if head >= 4:
+                    assert len(b) <= 4 + max_iter // head + 1
+        assert lib.pararnn_set_fused_head(9) == 2 and lib.pararnn_set_fused_head(-1) == 2
+        lib.pararnn_set_fused_head(5)
+        # more launches than the caller has room for: the count is still returned
+        assert plan(1e-5, 64, buf, 2) == 15 and plan(1e-5, -1, buf, 2) == -1
+        lib.pararnn_set_fused(0)
+        assert blocks(1e-5, 7) == [1] * 7 and blocks(-1.0, 3) == [1] * 3
+    finally:
+        lib.pararnn_set_fused(1)
+        lib.pararnn_set_fused_head(5)
