@@ -290,6 +290,36 @@ def test_fixed_count_solve_in_one_launch(P, oracle_mod, cell, dtype):
 
 
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
+@pytest.mark.parametrize("shape", [(3, 257, 68), (1, 65, 6), (2, 1000, 130), (1, 129, 64), (4, 64, 31)])
+def test_fused_blocks_ragged_shapes(P, oracle_mod, cell, shape):
+    """Resumed blocks on shapes with ragged tiles along L and H (and the small-H
+    tile shape): a first block too short to converge, so that the solve ends in
+    a resumed fused block or in the single-iteration launch."""
+    B, L, H = shape
+    params, u, h0, _ = problem(cell, B, L, H, seed=300 + L + H)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    tr0 = oracle_mod.newton(cell, pn, un, h0n, tol=1e-5, max_iter=40)[3]
+    # in the middle of the last jump of the trace, but well above the fp32 floor of the updates
+    tol = max(float(np.sqrt(tr0[-2] * tr0[-1])), 2e-6)
+    _, it64, _, tr64 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40)
+    _, it32, _, tr32 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40, precision="f32")
+    clear = it64 == it32 and min(tr64[-2], tr32[-2]) >= 8 * tol and max(tr64[-1], tr32[-1]) <= tol / 8
+    try:
+        for head in (1, 2, 3, 4, 8):
+            print(f"ragged blocks {cell} {shape} head={head}", flush=True)
+            P.set_fused_head(head)
+            h, iters, tr = P.forward(cell, params, u, h0, tol=tol, max_iter=40, trace=True)
+            torch.cuda.synchronize()
+            it, st = (int(x) for x in iters.cpu())
+            assert st == 0
+            assert it == it64 if clear else abs(it - it64) <= 1
+            assert relerr(to_np(h), ref) <= TOL_F32
+    finally:
+        P.set_fused_head(5)
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_solve_to_tolerance_in_fused_blocks(P, oracle_mod, cell, dtype):
     """A solve to a tolerance is a sequence of launches: a fused block from the
@@ -306,7 +336,7 @@ def test_solve_to_tolerance_in_fused_blocks(P, oracle_mod, cell, dtype):
     # the tolerance sits in the middle of the last jump of the oracle's trace, so that the
     # stopping decision has a clear margin in fp64 and in fp32
     tr0 = oracle_mod.newton(cell, pn, un, h0n, tol=1e-5, max_iter=40)[3]
-    tol = float(np.sqrt(tr0[-2] * tr0[-1]))
+    tol = max(float(np.sqrt(tr0[-2] * tr0[-1])), 2e-6)
     _, it64, _, tr64 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40)
     _, it32, _, tr32 = oracle_mod.newton(cell, pn, un, h0n, tol=tol, max_iter=40, precision="f32")
     assert it64 == it32 == len(tr0) and it64 >= 4, (it64, it32)
