@@ -97,6 +97,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     iters, status = (int(x) for x in state["iters"].cpu())
+    t_steps = sorted(time_events(step, max(args.steps, 20)))      # per step, device events: minimum and median
 
     # ---- per-kernel figures with device events on the launch stream
     def fwd_fixed(m):
@@ -115,6 +116,8 @@ def main():
     t_fwd = time_events(lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f,
                                           out=h_out), 10)
     detail = {"iters": iters, "status": P.status_string(status), "tol": w.tol, "max_iter": w.max_iter,
+              "ms_per_step_min": t_steps[0], "ms_per_step_median": t_steps[len(t_steps) // 2],
+              "launches": P.solve_plan(w.tol, w.max_iter) if w.cell != "tanh_dense" else None,
               "t_fwd_ms": sum(t_fwd) / len(t_fwd), "t_fwd_min_ms": min(t_fwd),
               "t_iter_ms": t_iter_ms, "t_iter_min_ms": t_iter_min_ms}
     if w.cell == "tanh_dense":
@@ -245,10 +248,18 @@ def cpu_baseline(w, d):
         oracle.backward(w.cell, params, u, h0, h, g)
         tb = time.perf_counter() - t1
     n = Bs * w.L * Hs
+    # the plain sequential application (Eq. (1)) of one sequence in fp32 on one core: the paper's
+    # "naive sequential" reference point
+    u1 = None if u is None else u[:1]
+    h01 = None if h0 is None else h0[:1]
+    t2 = time.perf_counter()
+    oracle.seq_unroll(w.cell, params, u1, h01, precision="f32")
+    t_seq = time.perf_counter() - t2
+    extra = {"seq_unroll_f32_1core": w.L * Hs / t_seq}
     # the oracle spreads whole sequences over the OpenMP threads
     return {"value": n / ((t1 - t0) + tb), "unit": "timestep-channels/s", "cores": min(threads, Bs),
             "kind": "oracle", "sample": f"{Bs} of {w.B} sequences, {Hs} of {w.H} channels, full L, fp64, "
-                                        f"{it} Newton iterations ({t1 - t0:.2f} s) + backward ({tb:.2f} s)"}
+                                        f"{it} Newton iterations ({t1 - t0:.2f} s) + backward ({tb:.2f} s)", **extra}
 
 
 if __name__ == "__main__":
