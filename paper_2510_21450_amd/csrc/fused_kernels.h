@@ -227,30 +227,38 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 #pragma unroll
                 for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
             }
+            // interior tiles take the form without bounds tests: the C cell evaluations of a thread are
+            // independent (they read the previous iterate), and without branches between them the
+            // compiler interleaves their dependency chains
+            auto thread_level = [&](auto guard) {
+                constexpr bool kGuard = decltype(guard)::value;
 #pragma unroll
-            for (int i = 0; i < C; ++i) {
-                if (l0 + i < g.L) {
+                for (int i = 0; i < C; ++i) {
+                    if (!kGuard || l0 + i < g.L) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            float J[SS], r[S], hp[S], ug[G], F[S];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
+#pragma unroll
+                            for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                            Cell::template fwd<true>(p[v], hp, ug, F, J, pq[v]);
+#pragma unroll
+                            for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
+                            push_step<S>(J, r, accA[v], accB[v]);
+                        }
+                    }
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        float J[SS], r[S], hp[S], ug[G], F[S];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
+                        for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
 #pragma unroll
-                        for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
-                        Cell::template fwd<true>(p[v], hp, ug, F, J, pq[v]);
-#pragma unroll
-                        for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
-                        push_step<S>(J, r, accA[v], accB[v]);
+                        for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
                     }
                 }
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-                    for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
-#pragma unroll
-                    for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
-                }
-            }
+            };
+            if (full_tile) thread_level(std::false_type{});
+            else thread_level(std::true_type{});
 
             // ---- wave level
             float lexA[VEC][SS], lexB[VEC][S];
@@ -366,26 +374,32 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 
             // ---- back-substitution; the delta entering the chunk also updates the state before it
             unsigned int wmax_bits = 0u;
+            auto back_substitute = [&](auto guard) {
+                constexpr bool kGuard = decltype(guard)::value;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                float cin[S], din[S];
+                for (int v = 0; v < VEC; ++v) {
+                    float cin[S], din[S];
 #pragma unroll
-                for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
-                affine<S>(exA[v], cin, exB[v], din);
-                if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
+                    for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
+                    affine<S>(exA[v], cin, exB[v], din);
+                    if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
 #pragma unroll
-                for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
+                    for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
 #pragma unroll
-                for (int i = 0; i < C; ++i) {
-                    float d[S];
-                    affine<S>(PA[i][v], din, qb[i][v], d);
+                    for (int i = 0; i < C; ++i) {
+                        float d[S];
+                        affine<S>(PA[i][v], din, qb[i][v], d);
 #pragma unroll
-                    for (int s = 0; s < S; ++s) {
-                        ho[i][s][v] += d[s];
-                        if (ch_ok && l0 + i < g.L) wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
+                        for (int s = 0; s < S; ++s) {
+                            ho[i][s][v] += d[s];
+                            if (!kGuard || (ch_ok && l0 + i < g.L))
+                                wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
+                        }
                     }
                 }
-            }
+            };
+            if (full_tile) back_substitute(std::false_type{});
+            else back_substitute(std::true_type{});
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) wmax_bits = max(wmax_bits, (unsigned int)__shfl_xor((int)wmax_bits, off, 64));
             if (lane == 0) atomicMax(&s_maxk[k - 1], wmax_bits);
