@@ -1,5 +1,6 @@
 // Shared device helpers of the ParaRNN HIP library (gfx950 only).
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -214,6 +215,23 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Maximum of an unsigned value over the 64 lanes of a wave, returned wave-uniform
+// (in scalar registers).  Four DPP butterfly steps make every row of 16 lanes
+// uniform, then one lane of each row is read.  All lanes must be active.
+__device__ __forceinline__ unsigned int wave_max_u32(unsigned int v)
+{
+    auto dpp = [](unsigned int x, auto ctrl) {
+        return (unsigned int)__builtin_amdgcn_update_dpp(0, (int)x, decltype(ctrl)::value, 0xf, 0xf, false);
+    };
+    v = max(v, dpp(v, std::integral_constant<int, 0xB1>{}));     // quad_perm [1,0,3,2]
+    v = max(v, dpp(v, std::integral_constant<int, 0x4E>{}));     // quad_perm [2,3,0,1]
+    v = max(v, dpp(v, std::integral_constant<int, 0x141>{}));    // row_half_mirror
+    v = max(v, dpp(v, std::integral_constant<int, 0x140>{}));    // row_mirror
+    const unsigned int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const unsigned int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return max(max(a, b), max(c, d));
 }
 
 // max that keeps a NaN once seen (fmaxf would drop it)

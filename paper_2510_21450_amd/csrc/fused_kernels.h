@@ -400,9 +400,8 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             };
             if (full_tile) back_substitute(std::false_type{});
             else back_substitute(std::true_type{});
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) wmax_bits = max(wmax_bits, (unsigned int)__shfl_xor((int)wmax_bits, off, 64));
-            if (lane == 0) atomicMax(&s_maxk[k - 1], wmax_bits);
+            const unsigned int wave_bits = wave_max_u32(wmax_bits);
+            if (lane == 0) atomicMax(&s_maxk[k - 1], wave_bits);
             // s_A / s_carry are rewritten only after the next iteration's first barrier
         }
 
