@@ -38,8 +38,8 @@ ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93}
 # From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt), per launch of the first
 # fused block: HBM bytes moved (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
 # size), and the cycles its vector ALUs were busy summed over the 1024 SIMDs (4 x SQ_ACTIVE_INST_VALU).
-MEASURED_TRAFFIC = {"C2": 1256.5e6, "C3": 911.5e6, "C5": 15887.2e6}
-MEASURED_VALU_BUSY_CYCLES = {"C2": 1.1716e9, "C3": 1.0117e9, "C5": 1.9112e10}
+MEASURED_TRAFFIC = {"C2": 1204.1e6, "C3": 1044.3e6, "C5": 15036.7e6}
+MEASURED_VALU_BUSY_CYCLES = {"C2": 1.1165e9, "C3": 0.9917e9, "C5": 1.8168e10}
 
 
 def time_events(fn, reps):
