@@ -7,6 +7,7 @@ runs in the HIP kernels.  The library must have been built
 """
 from .binding import (CELLS, DTYPES, STATUS, affine_scan, backward, cell_dims, dense_chunk, dense_chunk_products, forward, lib_path, set_fused, set_fused_head, set_tile, solve_plan,
                       status_string, version, workspace_bytes, workspace_bytes_fused)
+from .autograd import rnn_apply
 
-__all__ = ["CELLS", "DTYPES", "STATUS", "affine_scan", "backward", "cell_dims", "dense_chunk", "dense_chunk_products", "forward", "lib_path", "set_fused", "set_fused_head", "set_tile", "solve_plan",
+__all__ = ["rnn_apply", "CELLS", "DTYPES", "STATUS", "affine_scan", "backward", "cell_dims", "dense_chunk", "dense_chunk_products", "forward", "lib_path", "set_fused", "set_fused_head", "set_tile", "solve_plan",
            "status_string", "version", "workspace_bytes", "workspace_bytes_fused"]

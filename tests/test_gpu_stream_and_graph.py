@@ -87,3 +87,35 @@ def test_repeated_calls_share_a_workspace_and_are_bit_reproducible():
             first = cur
         else:
             assert torch.equal(cur[0], first[0]) and torch.equal(cur[1], first[1]) and torch.equal(cur[2], first[2])
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
+def test_autograd_wrapper_matches_oracle_gradients(cell, oracle_mod):
+    """rnn_apply inside a PyTorch graph: loss = sum(w * h), gradients with respect
+    to params, u and h0 against the oracle's reverse sweep."""
+    import numpy as np
+    import paper_2510_21450_amd as P
+    from workloads.rng import normal, uniform_sym
+    G, S = P.cell_dims(cell)
+    B, L, H = 2, 300, 64
+    if cell == "tanh_dense":
+        params = normal(41, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    else:
+        params = torch.zeros(2, G, H, device="cuda")
+        params[0] = uniform_sym(41, 2, (G, H), 0.9, device="cuda")
+    u = normal(41, 1, (B, L, G, H), device="cuda")
+    h0 = normal(41, 3, (B, S, H), std=0.3, device="cuda")
+    w = normal(41, 4, (B, L, S, H), device="cuda")
+    params.requires_grad_(True); u.requires_grad_(True); h0.requires_grad_(True)
+    h, iters = P.rnn_apply(cell, params, u, h0, tol=1e-5, max_iter=40)
+    assert int(iters.cpu()[1]) == 0 and not iters.requires_grad
+    (h * w).sum().backward()
+    f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, f64(params), f64(u), f64(h0), f64(h), f64(w))
+    rel = lambda a, b: float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30))
+    assert rel(f64(u.grad), rdu) <= 1e-5 and rel(f64(params.grad), rdp) <= 1e-5 and rel(f64(h0.grad), rdh0) <= 1e-5
+    # without h0 the wrapper asks for no dL/dh0
+    u2 = u.detach().clone().requires_grad_(True)
+    h2, _ = P.rnn_apply(cell, params.detach(), u2, None, tol=1e-5, max_iter=40)
+    h2.sum().backward()
+    assert u2.grad is not None and bool(torch.isfinite(u2.grad).all())
