@@ -197,11 +197,13 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
  * and profiling the scan without a cell: delta_l = J_l delta_{l-1} + r_l,
  * delta_0 = 0 (reverse = 0), or the adjoint
  * lam_l = J_{l+1}^T lam_{l+1} + r_l, lam_{L+1} = 0 (reverse = 1).
- *   kind   0: diagonal, J [B][L][H];  1: 2x2 blocks, J [B][L][2][2][H] with
- *          J[p][q] = d(out_p)/d(in_q);  r, delta [B][L][S][H], fp32
- *   workspace as for pararnn_forward of a cell with that structure
- *          (GRU_DIAG for kind 0, LSTM_DIAG for kind 1).
+ *   kind   0: diagonal, J [B][L][H];  1, 2, 3: blocks of S x S with S = 2, 3, 4
+ *          (the block-diagonal Jacobians of Sec. 3 for cells with S state
+ *          values per channel), J [B][L][S][S][H] with J[p][q] =
+ *          d(out_p)/d(in_q);  r, delta [B][L][S][H], fp32
+ *   workspace of at least pararnn_affine_scan_workspace_bytes(kind, reverse, ..)
  */
+size_t pararnn_affine_scan_workspace_bytes(int kind, int reverse, int B, int L, int H);
 int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, int B, int L, int H,
                         float *delta, void *workspace, size_t workspace_bytes, void *hip_stream);
 

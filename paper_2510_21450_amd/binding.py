@@ -43,6 +43,8 @@ _lib.pararnn_backward.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _
 _lib.pararnn_dense_chunk_products.restype = _i
 _lib.pararnn_dense_chunk_products.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.pararnn_affine_scan.restype = _i
+_lib.pararnn_affine_scan_workspace_bytes.restype = _sz
+_lib.pararnn_affine_scan_workspace_bytes.argtypes = [_i] * 5
 _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
 
 
@@ -200,16 +202,22 @@ def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspac
 
 
 def affine_scan(J, r, reverse: bool = False, workspace=None, stream=None):
-    """pararnn_affine_scan.  J [B][L][H] (diagonal) or [B][L][2][2][H]; r
-    [B][L][S][H] or [B][L][H].  Returns delta with r's shape."""
-    kind = 0 if J.dim() == 3 else 1
+    """pararnn_affine_scan.  J [B][L][H] (diagonal) or [B][L][S][S][H] (blocks,
+    S = 2, 3, 4); r [B][L][S][H] or [B][L][H].  Returns delta with r's shape."""
     B, L = r.shape[0], r.shape[1]
     H = r.shape[-1]
-    _check(J, "J", torch.float32, (B, L, H) if kind == 0 else (B, L, 2, 2, H))
+    if J.dim() == 3:
+        kind = 0
+        _check(J, "J", torch.float32, (B, L, H))
+    else:
+        S = J.shape[2]
+        if J.dim() != 5 or S not in (2, 3, 4):
+            raise ValueError("J must be [B][L][H] or [B][L][S][S][H] with S in 2..4")
+        kind = S - 1
+        _check(J, "J", torch.float32, (B, L, S, S, H))
     _check(r, "r", torch.float32)
     delta = torch.empty_like(r)
-    cell = "gru_diag" if kind == 0 else "lstm_diag"
-    ws = _workspace(workspace_bytes(cell, torch.float32, B, L, H, False), r.device, workspace)
+    ws = _workspace(_lib.pararnn_affine_scan_workspace_bytes(kind, int(reverse), B, L, H), r.device, workspace)
     code = _lib.pararnn_affine_scan(kind, int(reverse), _ptr(J), _ptr(r), B, L, H, _ptr(delta), _ptr(ws),
                                     ws.numel(), _stream(stream))
     _raise(code, "pararnn_affine_scan")

@@ -1,0 +1,4 @@
+// Kernel instantiations for one cell / storage type (compiled separately to
+// keep build times short).
+#include "launch_impl.h"
+namespace pararnn { template struct Kernels<RawScan<3>, float>; }

@@ -14,6 +14,13 @@ template <typename K> static int persistent_grid(K kernel, int threads, int n_ti
     return (int)(n_tiles < cap ? n_tiles : cap);
 }
 
+// static LDS of the forward kernels must stay within 64 KiB
+template <class Cell, int VEC, int LL, int W> constexpr bool forward_fits_lds()
+{
+    constexpr int S = Cell::S, SS = S * S;
+    return (size_t)(W * (SS + S) + S) * (kWave / LL) * VEC * sizeof(float) + 4 * W + 64 <= 65536;
+}
+
 // static LDS of the backward kernel must stay within 64 KiB
 template <class Cell, int VEC, int LL, int W> constexpr bool backward_fits_lds()
 {
@@ -48,17 +55,21 @@ hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, 
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
-        static int grid_cap[2] = {0, 0}; /* per instantiation */                               \
-        constexpr bool kFoldGuess = !IsRaw<Cell>::value;                                       \
-        const int first = (kFoldGuess && fold_guess) ? 1 : 0;                                  \
-        auto kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, false>;                         \
-        if constexpr (kFoldGuess) {                                                            \
-            if (first) kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, true>;                \
+        if constexpr (forward_fits_lds<Cell, V, LLv, W>()) {                                   \
+            static int grid_cap[2] = {0, 0}; /* per instantiation */                           \
+            constexpr bool kFoldGuess = !IsRaw<Cell>::value;                                   \
+            const int first = (kFoldGuess && fold_guess) ? 1 : 0;                              \
+            auto kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, false>;                     \
+            if constexpr (kFoldGuess) {                                                        \
+                if (first) kern = newton_iter_kernel<Cell, V, LLv, C, W, UT, true>;            \
+            }                                                                                  \
+            if (grid_cap[first] == 0) grid_cap[first] = persistent_grid(kern, kWave * W, 1 << 30); \
+            const int grid = a.g.n_tiles < grid_cap[first] ? a.g.n_tiles : grid_cap[first];    \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
+            return hipGetLastError();                                                          \
+        } else {                                                                               \
+            return hipErrorInvalidValue;                                                       \
         }                                                                                      \
-        if (grid_cap[first] == 0) grid_cap[first] = persistent_grid(kern, kWave * W, 1 << 30); \
-        const int grid = a.g.n_tiles < grid_cap[first] ? a.g.n_tiles : grid_cap[first];        \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
-        return hipGetLastError();                                                              \
     }
     PARARNN_SHAPES(PARARNN_CASE)
 #undef PARARNN_CASE

@@ -92,10 +92,10 @@ struct Layout {
 // Workspace: [Ctrl | carry records (rec_slots sets) | boundary rows | fp32 iterate (bf16 forward) |
 // parameter-gradient partials (backward)]
 Layout make_layout(int cell_kind, const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems,
-                   bool fused = false, int rec_slots = 1)
+                   bool fused = false, int rec_slots = 1, const TileCfg *force = nullptr)
 {
     Layout lo;
-    lo.cfg = choose_tile(cell_kind, dtype, backward, H, align_elems, fused);
+    lo.cfg = force ? *force : choose_tile(cell_kind, dtype, backward, H, align_elems, fused);
     const int CW = (kWave / lo.cfg.ll) * lo.cfg.vec, T = lo.cfg.c * lo.cfg.ll * lo.cfg.w;
     ScanGeom &g = lo.g;
     g.B = B; g.L = L; g.H = H; g.T = T;
@@ -424,16 +424,67 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
     return PARARNN_INVALID_ARG;
 }
 
+}  // extern "C" (reopened below, after the scan helpers)
+
+namespace {
+
+// the scan on its own: kind 0 diagonal, 1..3 blocks of 2x2, 3x3, 4x4
+bool scan_kind_ok(int kind) { return kind >= 0 && kind <= 3; }
+
+Layout scan_layout(int kind, int reverse, int B, int L, int H, int al)
+{
+    const int S = kind + 1;
+    const CellInfo ci = {S, S, 0};
+    if (S <= 2)
+        return make_layout(S == 1 ? PARARNN_GRU_DIAG : PARARNN_LSTM_DIAG, ci, PARARNN_F32, B, L, H, reverse != 0, al);
+    // 3x3 and 4x4 blocks keep 12 / 20 floats per step in registers: four steps per thread
+    const TileCfg cfg = H <= 8 ? TileCfg{1, 8, 4, 2} : TileCfg{1, 1, 4, 8};
+    return make_layout(PARARNN_LSTM_DIAG, ci, PARARNN_F32, B, L, H, reverse != 0, al, false, 1, &cfg);
+}
+
+template <int S>
+hipError_t scan_launch(const Layout &lo, int reverse, const float *J, const float *r, float *delta, Ctrl *ctrl,
+                       unsigned long long *rec, int *scratch_iters, hipStream_t st)
+{
+    if (!reverse) {
+        FwdArgs a;
+        memset(&a, 0, sizeof(a));
+        a.g = lo.g; a.u = r; a.jac = J; a.hit = delta;
+        a.rec = rec; a.ctrl = ctrl;
+        a.bnd = nullptr; a.iters_out = scratch_iters; a.trace = nullptr;
+        a.k = 1; a.max_iter = 1; a.tol = -1.0f;
+        return Kernels<RawScan<S>, float>::newton_iter(lo.cfg, a, false, st);
+    }
+    BwdArgs a;
+    memset(&a, 0, sizeof(a));
+    a.g = lo.g; a.gl = r; a.jac = J; a.du = delta; a.dh0 = nullptr; a.part = nullptr;
+    a.rec = rec; a.ctrl = ctrl;
+    return Kernels<RawScan<S>, float>::backward(lo.cfg, a, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pararnn_affine_scan_workspace_bytes(int kind, int reverse, int B, int L, int H)
+{
+    if (!scan_kind_ok(kind) || !dims_ok(B, L, H)) return 0;
+    size_t need = 0;
+    for (int al = 1; al <= 4; al *= 2) {
+        const Layout lo = scan_layout(kind, reverse, B, L, H, al);
+        if (lo.total > need) need = lo.total;
+    }
+    return need;
+}
+
 int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, int B, int L, int H, float *delta,
                         void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if ((kind != 0 && kind != 1) || !dims_ok(B, L, H) || !J || !r || !delta || !workspace) return PARARNN_INVALID_ARG;
+    if (!scan_kind_ok(kind) || !dims_ok(B, L, H) || !J || !r || !delta || !workspace) return PARARNN_INVALID_ARG;
     if (!aligned(workspace, 256) || !aligned(J, 4) || !aligned(r, 4) || !aligned(delta, 4)) return PARARNN_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    CellInfo ci = kind == 0 ? CellInfo{1, 1, 0} : CellInfo{2, 2, 0};
     const int al = align_elems(4, {J, r, delta});
-    const Layout lo = make_layout(kind == 0 ? PARARNN_GRU_DIAG : PARARNN_LSTM_DIAG, ci, PARARNN_F32, B, L, H,
-                                  reverse != 0, al);
+    const Layout lo = scan_layout(kind, reverse, B, L, H, al);
     if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
     Ctrl *ctrl = reinterpret_cast<Ctrl *>(ws);
@@ -442,22 +493,11 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
     int *scratch_iters = reinterpret_cast<int *>(&ctrl->pad[0]);
     hipError_t e = launch_reset(ctrl, rec, lo.n_rec, nullptr, 0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
-    if (!reverse) {
-        FwdArgs a;
-        memset(&a, 0, sizeof(a));
-        a.g = lo.g; a.u = r; a.jac = J; a.hit = delta;
-        a.rec = rec; a.ctrl = ctrl;
-        a.bnd = nullptr; a.iters_out = scratch_iters; a.trace = nullptr;
-        a.k = 1; a.max_iter = 1; a.tol = -1.0f;
-        e = kind == 0 ? Kernels<RawScan<1>, float>::newton_iter(lo.cfg, a, false, st)
-                      : Kernels<RawScan<2>, float>::newton_iter(lo.cfg, a, false, st);
-    } else {
-        BwdArgs a;
-        memset(&a, 0, sizeof(a));
-        a.g = lo.g; a.gl = r; a.jac = J; a.du = delta; a.dh0 = nullptr; a.part = nullptr;
-        a.rec = rec; a.ctrl = ctrl;
-        e = kind == 0 ? Kernels<RawScan<1>, float>::backward(lo.cfg, a, st)
-                      : Kernels<RawScan<2>, float>::backward(lo.cfg, a, st);
+    switch (kind) {
+    case 0: e = scan_launch<1>(lo, reverse, J, r, delta, ctrl, rec, scratch_iters, st); break;
+    case 1: e = scan_launch<2>(lo, reverse, J, r, delta, ctrl, rec, scratch_iters, st); break;
+    case 2: e = scan_launch<3>(lo, reverse, J, r, delta, ctrl, rec, scratch_iters, st); break;
+    default: e = scan_launch<4>(lo, reverse, J, r, delta, ctrl, rec, scratch_iters, st); break;
     }
     if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
     return PARARNN_OK;

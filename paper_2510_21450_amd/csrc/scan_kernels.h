@@ -82,15 +82,29 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------ small matrix ops
+// Row-major S x S blocks in registers; outputs may alias inputs.  S = 1 and 2 (the
+// cells) are written out; larger blocks (the scan on its own, S = 3, 4) loop.
 // y = A x (S x S times S)
 template <int S>
 __device__ __forceinline__ void mat_vec(const float *A, const float *x, float *y)
 {
     if constexpr (S == 1) {
         y[0] = A[0] * x[0];
+    } else if constexpr (S == 2) {
+        const float y0 = fmaf(A[0], x[0], A[1] * x[1]);
+        const float y1 = fmaf(A[2], x[0], A[3] * x[1]);
+        y[0] = y0; y[1] = y1;
     } else {
-        y[0] = fmaf(A[0], x[0], A[1] * x[1]);
-        y[1] = fmaf(A[2], x[0], A[3] * x[1]);
+        float t[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            float s = A[i * S] * x[0];
+#pragma unroll
+            for (int k = 1; k < S; ++k) s = fmaf(A[i * S + k], x[k], s);
+            t[i] = s;
+        }
+#pragma unroll
+        for (int i = 0; i < S; ++i) y[i] = t[i];
     }
 }
 // y = A x + b
@@ -99,11 +113,22 @@ __device__ __forceinline__ void affine(const float *A, const float *x, const flo
 {
     if constexpr (S == 1) {
         y[0] = fmaf(A[0], x[0], b[0]);
-    } else {
+    } else if constexpr (S == 2) {
         const float y0 = fmaf(A[0], x[0], fmaf(A[1], x[1], b[0]));
         const float y1 = fmaf(A[2], x[0], fmaf(A[3], x[1], b[1]));
         y[0] = y0;
         y[1] = y1;
+    } else {
+        float t[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            float s = b[i];
+#pragma unroll
+            for (int k = 0; k < S; ++k) s = fmaf(A[i * S + k], x[k], s);
+            t[i] = s;
+        }
+#pragma unroll
+        for (int i = 0; i < S; ++i) y[i] = t[i];
     }
 }
 // C = A B
@@ -112,21 +137,44 @@ __device__ __forceinline__ void mat_mul(const float *A, const float *Bm, float *
 {
     if constexpr (S == 1) {
         Cm[0] = A[0] * Bm[0];
-    } else {
+    } else if constexpr (S == 2) {
         const float c0 = fmaf(A[0], Bm[0], A[1] * Bm[2]);
         const float c1 = fmaf(A[0], Bm[1], A[1] * Bm[3]);
         const float c2 = fmaf(A[2], Bm[0], A[3] * Bm[2]);
         const float c3 = fmaf(A[2], Bm[1], A[3] * Bm[3]);
         Cm[0] = c0; Cm[1] = c1; Cm[2] = c2; Cm[3] = c3;
+    } else {
+        float t[S * S];
+#pragma unroll
+        for (int i = 0; i < S; ++i)
+#pragma unroll
+            for (int j = 0; j < S; ++j) {
+                float s = A[i * S] * Bm[j];
+#pragma unroll
+                for (int k = 1; k < S; ++k) s = fmaf(A[i * S + k], Bm[k * S + j], s);
+                t[i * S + j] = s;
+            }
+#pragma unroll
+        for (int e = 0; e < S * S; ++e) Cm[e] = t[e];
     }
 }
 template <int S> __device__ __forceinline__ void set_identity(float *A)
 {
-    if constexpr (S == 1) { A[0] = 1.0f; } else { A[0] = 1.0f; A[1] = 0.0f; A[2] = 0.0f; A[3] = 1.0f; }
+#pragma unroll
+    for (int i = 0; i < S; ++i)
+#pragma unroll
+        for (int j = 0; j < S; ++j) A[i * S + j] = i == j ? 1.0f : 0.0f;
 }
 template <int S> __device__ __forceinline__ void transpose_inplace(float *A)
 {
-    if constexpr (S == 2) { const float t = A[1]; A[1] = A[2]; A[2] = t; }
+#pragma unroll
+    for (int i = 0; i < S; ++i)
+#pragma unroll
+        for (int j = i + 1; j < S; ++j) {
+            const float t = A[i * S + j];
+            A[i * S + j] = A[j * S + i];
+            A[j * S + i] = t;
+        }
 }
 
 // (accA, accB) <- (J, r) o (accA, accB): apply one more step after the prefix

@@ -289,6 +289,34 @@ def test_fixed_count_solve_in_one_launch(P, oracle_mod, cell, dtype):
     assert tuple(int(x) for x in it.cpu()) == (1, 5)
 
 
+@pytest.mark.parametrize("S", [3, 4])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_affine_scan_larger_blocks(P, oracle_mod, S, reverse):
+    """3x3 and 4x4 block-diagonal Jacobians (cells with S state values per channel):
+    every channel is an S x S recurrence, which the oracle solves as a dense one."""
+    for (B, L, H) in [(1, 1, 4), (2, 33, 6), (2, 100, 37), (1, 257, 64), (2, 1025, 70)]:
+        print(f"scan blocks {S}x{S} reverse={reverse} B={B} L={L} H={H}", flush=True)
+        seed = 800 + L + S
+        J = uniform_sym(seed, 1, (B, L, S, S, H), 0.45, device="cuda")
+        r = normal(seed, 2, (B, L, S, H), device="cuda")
+        d = P.affine_scan(J, r, reverse=reverse)
+        torch.cuda.synchronize()
+        Jn, rn, dn = to_np(J), to_np(r), to_np(d)
+        worst = 0.0
+        for b in range(B):
+            for ch in range(H):
+                Jc = np.ascontiguousarray(Jn[b, :, :, :, ch])          # [L][S][S]
+                rc = np.ascontiguousarray(rn[b, :, :, ch])             # [L][S]
+                if not reverse:
+                    ref = oracle_mod.forward_substitution("dense", Jc, rc)
+                else:
+                    Jt = np.ascontiguousarray(Jc[::-1].transpose(0, 2, 1))
+                    Js = np.zeros_like(Jt); Js[1:] = Jt[:-1]
+                    ref = oracle_mod.forward_substitution("dense", Js, np.ascontiguousarray(rc[::-1]))[::-1]
+                worst = max(worst, relerr(dn[b, :, :, ch], ref.reshape(L, S)))
+        assert worst <= TOL_F32, (S, reverse, L, worst)
+
+
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("shape", [(3, 257, 68), (1, 65, 6), (2, 1000, 130), (1, 129, 64), (4, 64, 31)])
 def test_fused_blocks_ragged_shapes(P, oracle_mod, cell, shape):

@@ -104,7 +104,12 @@ def test_host_side_argument_validation(lib):
     s = lib.pararnn_affine_scan
     s.restype = ctypes.c_int
     s.argtypes = [i, i, vp, vp, i, i, i, vp, vp, sz, vp]
-    assert s(2, 0, p, p, 1, 8, 8, p, p, 1 << 20, None) == INVALID
+    assert s(4, 0, p, p, 1, 8, 8, p, p, 1 << 20, None) == INVALID and s(-1, 0, p, p, 1, 8, 8, p, p, 1 << 20, None) == INVALID
+    assert s(3, 0, p, p, 1, 8, 8, p, p, 16, None) == 3            # 4x4 blocks are a valid kind
+    sw = lib.pararnn_affine_scan_workspace_bytes
+    sw.restype = ctypes.c_size_t
+    sw.argtypes = [i] * 5
+    assert sw(4, 0, 1, 8, 8) == 0 and 0 < sw(0, 0, 2, 100, 64) < sw(1, 0, 2, 100, 64) < sw(3, 0, 2, 100, 64)
     assert s(0, 0, p, p, 1, 8, 8, p, p, 16, None) == 3
 
 
