@@ -112,18 +112,22 @@ size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int bac
 size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, int n_iters);
 
 /* Test / tuning hook (host, process-wide): enable = 0 makes pararnn_forward
- * always launch one kernel per iteration. */
+ * always launch one kernel per iteration (fixed-count solves and solves to a
+ * tolerance alike); the returned h is then exactly the iterate of the stopping
+ * iteration. */
 int pararnn_set_fused(int enable);
 
 /* Tuning hook (host, process-wide): a solve to a tolerance (tol >= 0) runs its
  * first min(n_iters, max_iter) iterations in ONE launch of the fused kernel (u
- * read once, the iterate kept in registers), then one launch per further
- * iteration.  The stopping test still sees m_k of every iteration: `iters`,
- * the status and delta_trace are those of the per-iteration solve.  When the
- * tolerance is met at an iteration before the end of that first launch, the
- * returned h is the iterate at the END of the launch -- the converged iterate
- * refined by the Newton iterations that were already in flight -- so it differs
- * from the per-iteration path's h by less than tol.  0 <= n_iters <= 8; 0 turns
+ * read once, the iterate kept in registers), then blocks of 1, 2, 4, ...
+ * iterations (at most n_iters each) until max_iter; a block of more than one
+ * iteration is again one fused launch, resumed from the iterate.  The stopping
+ * test still sees m_k of every iteration: `iters`, the status and delta_trace
+ * are those of the per-iteration solve.  When the tolerance is met at an
+ * iteration before the end of a launch, the returned h is the iterate at the
+ * END of that launch -- the converged iterate refined by the Newton iterations
+ * that were already in flight -- so it differs from the per-iteration path's h
+ * by less than tol.  0 <= n_iters <= 8; 0 turns
  * it off; default 5.  Query workspace sizes after setting it (a workspace
  * that is too small for the record slots falls back to one launch per
  * iteration). */

@@ -30,7 +30,7 @@ bool cell_info(int cell, CellInfo *ci)
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// process-wide switch for the one-launch path of fixed-count solves (pararnn_set_fused)
+// process-wide switch for launches that run several Newton iterations (pararnn_set_fused)
 int g_fused_enabled = 1;
 int g_fused_head = 5;      // iterations in the first launch of a solve to a tolerance (0 = none)
 
