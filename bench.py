@@ -144,7 +144,7 @@ def main():
         dense_bwd()
         t_db = time_events(dense_bwd, 10)
         detail["dense_backward_ms"] = sum(t_db) / len(t_db)
-        roofline = {"bound": "mfma", "kernel": "dense_chunk_products_kernel", "achieved": ach,
+        roofline = {"bound": "mfma", "kernel": "dense_products_sweep_kernel (chunk products part)", "achieved": ach,
                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
     else:

@@ -1,7 +1,7 @@
 // Dense-Jacobian path: h' = tanh(W h + u), J_l = diag(1 - F_l^2) W (the generic
 // dense case of Sec. 2.1), H = 64, fp32.
 //
-// One Newton iteration (Alg. 1a) is five launches:
+// One Newton iteration (Alg. 1a) is four launches (chunk_products and the local sweep share one):
 //   residual  F_l = tanh(W h_{l-1} + u_l), d_l = 1 - F_l^2, r_l = F_l - h_l   (Eq. (3))
 //   chunk_products   A_c = J_e ... J_s for every chunk of CD timesteps: the
 //             64x64x64 Jacobian compositions of the scan, on the matrix cores
@@ -168,11 +168,10 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
 // A_c = J_e ... J_{s+1} J_s with J_l = diag(d_l) W, one wave per (b, chunk).
 // Chunk 0 and the last chunk are skipped: nothing enters chunk 0 (delta_0 = 0)
 // and nothing follows the last one.
-__global__ __launch_bounds__(256, 2) void dense_chunk_products_kernel(const DenseArgs a)
+__device__ __forceinline__ void chunk_products_body(const DenseArgs &a, int block)
 {
-    if (a.ctrl->stop) return;
     const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
-    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int item = block * 4 + (threadIdx.x >> 6);
     const int per_seq = a.n_c - 2;
     if (per_seq <= 0 || item >= a.B * per_seq) return;
     const int b = item / per_seq, c = 1 + item % per_seq;
@@ -286,16 +285,15 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 // final = 0: x starts at 0, only the end value is kept (b_c).
 // final = 1: x starts at x_{c-1}; afterwards h += delta and max|delta|.
 // BWD: the backward recurrence (r_l = d_l * g_l; the final sweep writes mu = dL/du and nothing else).
-template <int FINAL, bool BWD = false>
-__global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
+template <int FINAL, bool BWD>
+__device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
 {
     __shared__ f4v s_x[2][4][64];
     __shared__ float s_max[4];
-    if (a.ctrl->stop) return;
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n = lane & 15, g = lane >> 4;
     const int n_cols = a.B * a.n_c;
-    const int col = blockIdx.x * 16 + n;
+    const int col = block * 16 + n;
     const bool ok = col < n_cols;
     const int cc = ok ? col : n_cols - 1;         // a column past the end reads valid memory and stores nothing
     const int b = cc / a.n_c, c = cc - b * a.n_c;
@@ -364,6 +362,26 @@ __global__ __launch_bounds__(256) void dense_sweep_kernel(const DenseArgs a)
     if (lane == 0) s_max[w] = wmax;
     __syncthreads();
     if (threadIdx.x == 0) finish_iteration(a, nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3])));
+}
+
+// The final sweep of an iteration (or of the backward pass).
+template <bool BWD>
+__global__ __launch_bounds__(256) void dense_final_sweep_kernel(const DenseArgs a)
+{
+    if (a.ctrl->stop) return;
+    sweep_body<1, BWD>(a, blockIdx.x);
+}
+
+// Chunk products and chunk-local sweeps need only d and r, and nothing of each
+// other: one launch runs both.  The first n_sweep workgroups take the sweeps,
+// whose sequential chains are bound by latency and so start first; the rest
+// compose the chunk products, which keep the matrix cores busy meanwhile.
+template <bool BWD>
+__global__ __launch_bounds__(256, 2) void dense_products_sweep_kernel(const DenseArgs a, int n_sweep)
+{
+    if (a.ctrl->stop) return;
+    if ((int)blockIdx.x < n_sweep) sweep_body<0, BWD>(a, blockIdx.x);
+    else chunk_products_body(a, (int)blockIdx.x - n_sweep);
 }
 
 // --------------------------------------------------------------------- carry
@@ -523,7 +541,7 @@ int dense_chunk_products(const float *W, const float *d, int B, int L, int H, fl
     if (launch_reset(a.ctrl, nullptr, 0, nullptr, 0, st) != hipSuccess) return PARARNN_HIP_ERROR;
     const int n_prod = B * (a.n_c - 2);
     if (n_prod > 0)
-        hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_products_sweep_kernel<false>, dim3((n_prod + 3) / 4), dim3(256), 0, st, a, 0);
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
@@ -581,11 +599,10 @@ int dense_backward(int dtype, const float *W, const void *u, const void *h0, con
     a.W = Wt; a.rev = 1;
     const int n_prod = B * (lo.n_c - 2);
     const int n_sweep = (B * lo.n_c + 15) / 16;
-    if (n_prod > 0)
-        hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((dense_sweep_kernel<0, true>), dim3(n_sweep), dim3(256), 0, st, a);
+    const int n_prod_blocks = n_prod > 0 ? (n_prod + 3) / 4 : 0;
+    hipLaunchKernelGGL(dense_products_sweep_kernel<true>, dim3(n_sweep + n_prod_blocks), dim3(256), 0, st, a, n_sweep);
     hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((dense_sweep_kernel<1, true>), dim3(n_sweep), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(dense_final_sweep_kernel<true>, dim3(n_sweep), dim3(256), 0, st, a);
     // step-local gradients
     if (dh0) hipLaunchKernelGGL(dense_dh0_kernel, dim3(B), dim3(64), 0, st, W, a.du, L, static_cast<float *>(dh0));
     const int wv = dw_waves(B, L);
@@ -626,15 +643,14 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
     hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
+    const int n_prod_blocks = n_prod > 0 ? (n_prod + 3) / 4 : 0;
     const int n_sweep = (B * lo.n_c + 15) / 16;       // workgroups: 16 (sequence, chunk) columns each
     for (int k = 1; k <= max_iter; ++k) {
         a.k = k;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
-        if (n_prod > 0)
-            hipLaunchKernelGGL(dense_chunk_products_kernel, dim3((n_prod + 3) / 4), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(dense_sweep_kernel<0>, dim3(n_sweep), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_products_sweep_kernel<false>, dim3(n_sweep + n_prod_blocks), dim3(256), 0, st, a, n_sweep);
         hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(dense_sweep_kernel<1>, dim3(n_sweep), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(dense_final_sweep_kernel<false>, dim3(n_sweep), dim3(256), 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
