@@ -372,7 +372,7 @@ def test_solve_to_tolerance_in_fused_blocks(P, oracle_mod, cell, dtype):
     assert min(tr64[k - 1], tr32[k - 1]) >= 8 * tol and max(tr64[k], tr32[k]) <= tol / 8, (tr64, tr32)
     try:
         for head in (0, 1, 2, 3, 4, 5, 6, 8):
-            for tile in (None, (1, 2, 8, 8)):
+            for tile in (None, (1, 2, 8, 8), (2, 2, 8, 8), (4, 4, 8, 8)):
                 for max_iter in (40, it64, it64 - 1, 2):
                     print(f"blocks {cell} {dtype} head={head} tile={tile} max_iter={max_iter}", flush=True)
                     P.set_fused_head(head)
