@@ -89,6 +89,34 @@ def test_repeated_calls_share_a_workspace_and_are_bit_reproducible():
             assert torch.equal(cur[0], first[0]) and torch.equal(cur[1], first[1]) and torch.equal(cur[2], first[2])
 
 
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+def test_lookback_stress_many_small_tiles(cell, oracle_mod):
+    """The carry chain under stress: the smallest tile shape (8 channels x 64
+    steps) on long sequences gives hundreds of tiles per chain and thousands of
+    workgroups racing for tickets; whatever order they run in, forward and
+    backward must give the same bits every time, and the oracle's result."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2" if cell == "gru_diag" else "C3"].scaled(B=4, L=20000, H=8)
+    d = make_inputs(w, device="cuda")
+    ws = torch.empty(P.workspace_bytes(w.cell, d["u"].dtype, w.B, w.L, w.H), dtype=torch.uint8, device="cuda")
+    ws.random_(0, 255)       # garbage, including tags that look almost valid
+    first = None
+    for rep in range(12):
+        h, iters, _ = P.forward(w.cell, d["params"], d["u"], d["h0"], tol=w.tol, max_iter=32, workspace=ws)
+        du, dp, dh0 = P.backward(w.cell, d["params"], d["u"], d["h0"], h, d["g"])
+        torch.cuda.synchronize()
+        cur = (h.clone(), iters.cpu().clone(), du.clone(), dp.clone(), dh0.clone())
+        if first is None:
+            first = cur
+            assert int(cur[1][1]) == 0
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(cur, first)), rep
+    f64 = lambda t: None if t is None else t.detach().to("cpu", torch.float64).numpy()
+    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), f64(d["h0"]))
+    err = float(np.max(np.abs(f64(first[0]) - ref)) / np.max(np.abs(ref)))
+    assert err <= 1e-5, err
+
+
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
 def test_autograd_wrapper_matches_oracle_gradients(cell, oracle_mod):
     """rnn_apply inside a PyTorch graph: loss = sum(w * h), gradients with respect
