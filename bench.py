@@ -31,10 +31,11 @@ FUSED_HEAD = 5                 # iterations in the first launch of a solve (the 
 ALGO_BYTES = {
     "C1": {"iter": 20, "block": 16, "bwd": 32}, "C2": {"iter": 20, "block": 16, "bwd": 32},
     "C3": {"iter": 32, "block": 24, "bwd": 48}, "C5": {"iter": 14, "block": 12, "bwd": 16},
+    "X3": {"iter": 28, "block": 20, "bwd": 40},     # ParaLSTM: 3 gates, state (c, h)
 }
 # algorithmic fp32 operations per timestep-channel and Newton iteration (cell, Jacobian, residual, the
 # thread-level scan step and the back-substitution; +, -, *, / and exp count one each)
-ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93}
+ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93, "paralstm_diag": 92}
 # From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt), per launch of the first
 # fused block: HBM bytes moved (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
 # size), and the cycles its vector ALUs were busy summed over the 1024 SIMDs (4 x SQ_ACTIVE_INST_VALU).
@@ -58,7 +59,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "X3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -67,7 +68,7 @@ def main():
 
     import torch
     import paper_2510_21450_amd as P
-    from workloads import CONFIGS, make_inputs, cell_dims
+    from workloads import ALL_CONFIGS as CONFIGS, make_inputs, cell_dims
 
     torch.cuda.set_device(0)
     P.set_fused_head(FUSED_HEAD)

@@ -7,7 +7,7 @@ channel slices with a fixed iteration count (tol < 0) and the per-iteration
 maxima are combined with max().  The diagonal cells' channels are independent,
 so a slice of channels is moved into the batch axis to use all host threads.
 
-Usage: python tests/golden/make_traces.py [C1 C2 ...]   (C5 takes ~15 min)
+Usage: python tests/golden/make_traces.py [C1 C2 ... X3]   (C5 takes ~15 min)
 """
 import json
 import os
@@ -19,7 +19,7 @@ import torch
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
 import oracle                                   # noqa: E402
-from workloads import CONFIGS, make_inputs      # noqa: E402
+from workloads import ALL_CONFIGS as CONFIGS, make_inputs      # noqa: E402
 
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "newton_traces.json")
 N_ITERS = 9

@@ -8,10 +8,10 @@ import os
 import numpy as np
 import pytest
 
-from workloads import CONFIGS
+from workloads import ALL_CONFIGS as CONFIGS
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
-EXPECTED_ITERS = {"C1": 5, "C2": 5, "C3": 6, "C4": 4, "C5": 5}
+EXPECTED_ITERS = {"C1": 5, "C2": 5, "C3": 6, "C4": 4, "C5": 5, "X3": 5}
 
 
 @pytest.mark.parametrize("name", sorted(EXPECTED_ITERS))

@@ -1,4 +1,5 @@
-"""Full-size benchmark workloads (BASELINE configs 2, 3, 5) in the launch
+"""Full-size benchmark workloads (BASELINE configs 2, 3, 5, and the paper's ParaLSTM
+cell on config 3's shapes, "X3") in the launch
 configuration bench.py times: inputs are generated on the GPU, the library runs
 on all of them, and a sample of channels (all sequences, all timesteps) is
 copied to the host and recomputed by the CPU oracle.  The diagonal cells'
@@ -14,7 +15,7 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
-from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
+from workloads import ALL_CONFIGS as CONFIGS, make_inputs, cell_dims      # noqa: E402
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
 N_SAMPLE = 48
@@ -36,7 +37,7 @@ def expected_iters(trace, tol):
     return None
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C5", "X3"])
 def test_full_size_config(name, oracle_mod):
     import paper_2510_21450_amd as P
     w = CONFIGS[name]
@@ -88,7 +89,7 @@ def test_full_size_config(name, oracle_mod):
     print(f"config {name}: iters={it} rel err h={e_h:.2e} du={e_du:.2e} dparams={e_dp:.2e} dh0={e_dh0:.2e}", flush=True)
     assert e_h <= bound and e_du <= bound and e_dp <= bound and e_dh0 <= bound
     # properties that hold at any size: bounded state, finite outputs everywhere
-    hh = h[:, :, -1, :] if w.cell == "lstm_diag" else h
+    hh = h[:, :, -1, :] if w.cell in ("lstm_diag", "paralstm_diag") else h
     assert float(hh.abs().max()) <= 1.0
     assert bool(torch.isfinite(du).all()) and bool(torch.isfinite(dp).all())
 

@@ -6,7 +6,7 @@ method's arithmetic: both the CPU oracle's tests and the GPU path's tests
 draw their bytes from here, and neither side's code is imported.
 """
 from .rng import uniform01, normal, uniform_sym
-from .configs import CONFIGS, Workload, make_inputs, cell_dims
+from .configs import ALL_CONFIGS, CONFIGS, EXTRA_CONFIGS, Workload, make_inputs, cell_dims
 
-__all__ = ["uniform01", "normal", "uniform_sym", "CONFIGS", "Workload",
+__all__ = ["uniform01", "normal", "uniform_sym", "ALL_CONFIGS", "CONFIGS", "EXTRA_CONFIGS", "Workload",
            "make_inputs", "cell_dims"]

@@ -59,6 +59,13 @@ CONFIGS = {
 }
 
 
+# Beyond the five: the paper's own ParaLSTM cell (Eq. (7b)) on config 3's shapes and recipe.
+EXTRA_CONFIGS = {
+    "X3": Workload("X3", "paralstm_diag", "f32", 8, 2048, 2048, 1e-4, 64, True, BASE_SEED + 5),
+}
+ALL_CONFIGS = {**CONFIGS, **EXTRA_CONFIGS}
+
+
 def _storage(dtype: str):
     return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
 
@@ -72,10 +79,16 @@ def make_inputs(w: Workload, device="cpu", need_g: bool | None = None) -> dict:
         out["params"] = normal(w.seed, 5, (w.H, w.H), std=w.w_std_dense / w.H ** 0.5,
                                dtype=torch.float32, device=device)
     else:
-        p = torch.zeros(2, G, w.H, dtype=torch.float32, device=device)
-        p[0] = uniform_sym(w.seed, 2, (G, w.H), w.w_bound, dtype=torch.float32, device=device)
-        if w.cell == "lstm_diag":
-            p[1, 1] = 1.0          # forget-gate bias +1
+        if w.cell == "paralstm_diag":
+            # a_f, a_z, a_o, c_f, c_o ~ U(-bound, bound); b_f = +1, b_z = b_o = 0
+            p = torch.zeros(8, w.H, dtype=torch.float32, device=device)
+            p[:5] = uniform_sym(w.seed, 2, (5, w.H), w.w_bound, dtype=torch.float32, device=device)
+            p[5] = 1.0
+        else:
+            p = torch.zeros(2, G, w.H, dtype=torch.float32, device=device)
+            p[0] = uniform_sym(w.seed, 2, (G, w.H), w.w_bound, dtype=torch.float32, device=device)
+            if w.cell == "lstm_diag":
+                p[1, 1] = 1.0          # forget-gate bias +1
         out["params"] = p
     out["u"] = normal(w.seed, 1, (w.B, w.L, G, w.H), dtype=st, device=device)
     out["h0"] = (normal(w.seed, 3, (w.B, S, w.H), std=w.h0_std, dtype=st, device=device)
