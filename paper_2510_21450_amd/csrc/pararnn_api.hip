@@ -64,7 +64,8 @@ TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_el
         else if (bf && vmax >= 2) cfg = {2, 2, 8, 8};    // 64 channels x 128 steps
         else cfg = {1, 1, 8, 16};                        // 64 channels x 128 steps
     } else {
-        if (lstm) cfg = {1, 1, 16, 8};                   // 64 channels x 128 steps
+        if (cell_kind == PARARNN_PARALSTM_DIAG) cfg = {1, 1, 12, 8};   // 64 channels x 96 steps
+        else if (lstm) cfg = {1, 1, 16, 8};              // 64 channels x 128 steps
         else if (bf) cfg = {1, 1, 8, 8};                 // 64 channels x 64 steps
         else cfg = {1, 2, 8, 16};                        // 32 channels x 256 steps
     }
