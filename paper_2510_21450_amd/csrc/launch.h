@@ -18,7 +18,7 @@ struct TileCfg {
 // beat wide vector loads; the automatic choice is in pararnn_api.hip.
 #define PARARNN_SHAPES(X)                                                                       \
     X(1, 1, 8, 16) X(1, 2, 8, 16) X(1, 2, 16, 4) X(1, 2, 8, 8) X(1, 1, 8, 8) X(2, 2, 8, 8)            \
-    X(1, 1, 16, 8) X(1, 1, 4, 8) X(1, 8, 4, 2) X(4, 4, 8, 8) X(2, 4, 8, 8) X(1, 1, 16, 4) X(1, 1, 12, 8) X(1, 2, 12, 4)
+    X(1, 1, 16, 8) X(1, 1, 4, 8) X(1, 8, 4, 2) X(4, 4, 8, 8) X(2, 4, 8, 8) X(1, 1, 16, 4) X(1, 1, 12, 8)
 // channels per lane compiled for the element-wise kernels
 #define PARARNN_VECS(X) X(1) X(2) X(4)
 

@@ -58,7 +58,6 @@ TileCfg choose_tile(int cell_kind, int dtype, bool backward, int H, int align_el
         // the fused blocks are bound by vector arithmetic, not by HBM: long per-thread chunks spread the
         // per-thread cost of the wave / workgroup / look-back levels over more cell evaluations
         if (lstm) cfg = {1, 1, 16, 4};                   // 64 channels x 64 steps
-        else if (bf) cfg = {1, 2, 12, 4};                // 32 channels x 96 steps
         else cfg = {1, 1, 12, 8};                        // 64 channels x 96 steps
     } else if (!backward) {
         if (lstm) cfg = {1, 1, 8, 16};                   // 64 channels x 128 steps
