@@ -43,6 +43,11 @@ MEASURED_TRAFFIC = {"C2": 1204.1e6, "C3": 1044.3e6, "C5": 15036.7e6}
 MEASURED_VALU_BUSY_CYCLES = {"C2": 1.1165e9, "C3": 0.9917e9, "C5": 1.8168e10}
 
 
+def note(msg):
+    """Progress on stderr (stdout carries the one JSON line)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def time_events(fn, reps):
     import torch
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
@@ -88,6 +93,7 @@ def main():
         if w.backward:
             state["grads"] = P.backward(w.cell, params, u, h0, h, g, workspace=ws_b)
 
+    note(f"inputs ready: {w.name} {w.cell} {w.dtype} B={w.B} L={w.L} H={w.H}")
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -98,6 +104,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     iters, status = (int(x) for x in state["iters"].cpu())
+    note(f"{args.steps} timed steps: {ms_per_step:.4f} ms per step, iters={iters}")
     t_steps = sorted(time_events(step, max(args.steps, 20)))      # per step, device events: minimum and median
 
     # ---- per-kernel figures with device events on the launch stream
@@ -194,6 +201,7 @@ def main():
                        "bwd_gbs": ab["bwd"] * N / (sum(t_bwd) / len(t_bwd) * 1e-3) / 1e9})
         detail["bwd_frac_hbm"] = detail["bwd_gbs"] / HBM_PEAK_GBS
 
+    note("per-kernel timings done")
     # a plain copy of known size, as the reference for hardware byte counters
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty_like(src)
@@ -203,6 +211,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
+        note("timing the CPU oracle on its sample")
         cpu = cpu_baseline(w, d)
 
     out = {
