@@ -39,7 +39,8 @@ ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93, "paralstm_diag": 92}
 # From rocprofv3 --pmc passes over this file's own run (profiles/newton_fused_*.txt), per launch of the first
 # fused block: HBM bytes moved (FETCH_SIZE / WRITE_SIZE scaled by their reading for a plain copy of known
 # size), and the cycles its vector ALUs were busy summed over the 1024 SIMDs (4 x SQ_ACTIVE_INST_VALU).
-MEASURED_TRAFFIC = {"C2": 1204.1e6, "C3": 1044.3e6, "C5": 15036.7e6}
+MEASURED_TRAFFIC = {"C2": 1204.1e6, "C3": 1044.3e6, "C5": 15036.7e6,
+                    "C4": 81.6e6}   # C4: the stand-alone chunk-products launch (d in, 3968 products of 16 KB out)
 MEASURED_VALU_BUSY_CYCLES = {"C2": 1.1165e9, "C3": 0.9917e9, "C5": 1.8168e10}
 
 
@@ -154,7 +155,7 @@ def main():
         detail["dense_backward_ms"] = sum(t_db) / len(t_db)
         roofline = {"bound": "mfma", "kernel": "dense_products_sweep_kernel (chunk products part)", "achieved": ach,
                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+                    "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(args.config)}
     else:
         ab = ALGO_BYTES[args.config]
         iter_gbs = ab["iter"] * N / (t_iter_ms * 1e-3) / 1e9
