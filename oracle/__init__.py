@@ -17,7 +17,18 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "pararnn_oracle.c")
 _LIBS = {}
 
-CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4}
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4, "rot_tanh": 5}
+NONLIN = {"sigmoid": 0, "tanh": 1, "identity": 2, "softsign": 3}
+
+
+def cell_id(cell: str) -> int:
+    """Number of a cell; "gru_nl:<update>,<reset>,<state>" names the GRU with those nonlinearities."""
+    if cell.startswith("gru_nl:"):
+        nu, nr, ns = (NONLIN[s] for s in cell[len("gru_nl:"):].split(","))
+        return 100 + 16 * nu + 4 * nr + ns
+    return CELLS[cell]
+
+
 STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 5: "NONFINITE"}
 JAC_KIND = {"diag": 0, "block2": 1, "dense": 2}
 
@@ -60,7 +71,7 @@ def _c(a, precision):
 
 def dims(cell: str):
     lib = _lib()
-    return lib.oracle_gates(CELLS[cell]), lib.oracle_state(CELLS[cell])
+    return lib.oracle_gates(cell_id(cell)), lib.oracle_state(cell_id(cell))
 
 
 def num_threads() -> int:
@@ -75,7 +86,7 @@ def cell_step(cell, params, hp, u, precision="f64"):
     _, pp = _c(params, precision)
     _, up = _c(u, precision)
     out = np.empty_like(hp_a)
-    lib.oracle_cell_step(CELLS[cell], H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
+    lib.oracle_cell_step(cell_id(cell), H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
     return out
 
 
@@ -86,10 +97,9 @@ def cell_jacobian(cell, params, hp, u, precision="f64"):
     H = hp_a.shape[-1]
     _, pp = _c(params, precision)
     _, up = _c(u, precision)
-    shape = {"gru_diag": (H,), "linear_diag": (H,), "lstm_diag": (2, 2, H), "paralstm_diag": (2, 2, H),
-             "tanh_dense": (H, H)}[cell]
+    shape = {0: (H,), 1: (2, 2, H), 2: (H, H)}[lib.oracle_jac_kind(cell_id(cell))]
     out = np.empty(shape, dtype=_np_t(precision))
-    lib.oracle_cell_jacobian(CELLS[cell], H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
+    lib.oracle_cell_jacobian(cell_id(cell), H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
     return out
 
 
@@ -98,12 +108,12 @@ def seq_unroll(cell, params, u, h0=None, precision="f64"):
     lib = _lib(precision)
     u_a, up = _c(u, precision)
     B, L, G, H = u_a.shape
-    S = lib.oracle_state(CELLS[cell])
-    assert G == lib.oracle_gates(CELLS[cell])
+    S = lib.oracle_state(cell_id(cell))
+    assert G == lib.oracle_gates(cell_id(cell))
     _, pp = _c(params, precision)
     _h0, h0p = _c(h0, precision)
     h = np.empty((B, L, S, H), dtype=_np_t(precision))
-    lib.oracle_seq_unroll(CELLS[cell], B, L, H, pp, up, h0p, h.ctypes.data_as(ctypes.c_void_p))
+    lib.oracle_seq_unroll(cell_id(cell), B, L, H, pp, up, h0p, h.ctypes.data_as(ctypes.c_void_p))
     return h
 
 
@@ -133,7 +143,7 @@ def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64"):
     lib = _lib(precision)
     u_a, up = _c(u, precision)
     B, L, G, H = u_a.shape
-    S = lib.oracle_state(CELLS[cell])
+    S = lib.oracle_state(cell_id(cell))
     _, pp = _c(params, precision)
     _h0, h0p = _c(h0, precision)
     h = np.empty((B, L, S, H), dtype=_np_t(precision))
@@ -142,7 +152,7 @@ def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64"):
     real = ctypes.c_double if precision == "f64" else ctypes.c_float
     lib.oracle_newton.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 3 + [real, ctypes.c_int,
                                   ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
-    st = lib.oracle_newton(CELLS[cell], B, L, H, pp, up, h0p, tol, max_iter,
+    st = lib.oracle_newton(cell_id(cell), B, L, H, pp, up, h0p, tol, max_iter,
                            h.ctypes.data_as(ctypes.c_void_p), ctypes.byref(iters),
                            trace.ctypes.data_as(ctypes.c_void_p))
     return h, iters.value, st, trace[:iters.value].copy()
@@ -153,7 +163,7 @@ def backward(cell, params, u, h0, h, g, precision="f64"):
     lib = _lib(precision)
     u_a, up = _c(u, precision)
     B, L, G, H = u_a.shape
-    S = lib.oracle_state(CELLS[cell])
+    S = lib.oracle_state(cell_id(cell))
     p_a, pp = _c(params, precision)
     _h0, h0p = _c(h0, precision)
     _h, hp = _c(h, precision)
@@ -161,7 +171,7 @@ def backward(cell, params, u, h0, h, g, precision="f64"):
     du = np.empty_like(u_a)
     dparams = np.empty_like(p_a)
     dh0 = np.empty((B, S, H), dtype=_np_t(precision))
-    lib.oracle_backward(CELLS[cell], B, L, H, pp, up, h0p, hp, gp,
+    lib.oracle_backward(cell_id(cell), B, L, H, pp, up, h0p, hp, gp,
                         du.ctypes.data_as(ctypes.c_void_p), dparams.ctypes.data_as(ctypes.c_void_p),
                         dh0.ctypes.data_as(ctypes.c_void_p))
     return du, dparams, dh0

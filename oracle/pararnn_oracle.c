@@ -19,6 +19,12 @@
  *   - Sec. 3, Eq. (7b) / (8b) with diagonal A_*, C_* (Eq. (9)): the
  *     CIFG LSTM with peepholes (ParaLSTM) and its 2x2 Jacobian    -> cell 4
  *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
+ *   - App. D.3: the GRU's update / reset / state nonlinearities are
+ *     parameters of the cell: Eq. (7a) / (8a) with each of them chosen
+ *     from sigmoid, tanh, identity, softsign                      -> cells 100..163
+ *   - Sec. 2.1 (block-diagonal Jacobians): a cell written only to
+ *     exercise 2x2 blocks that do not come from an LSTM, a per-channel
+ *     rotation-scaling followed by tanh                           -> cell 5
  *
  * Precision: REAL is double unless the file is compiled with -DREAL=float
  * (a second build used only to look at fp32 iteration traces).
@@ -27,7 +33,10 @@
  * params for the diagonal cells [2][G][H] (recurrent weights, then biases),
  * for the dense cell W[H][H] row-major, for the ParaLSTM [8][H] = (a_f, a_z,
  * a_o, c_f, c_o, b_f, b_z, b_o).  Gate order GRU (z,r,c), LSTM (i,f,o,g),
- * ParaLSTM (f,z,o); LSTM state order (c,h).
+ * ParaLSTM (f,z,o); LSTM state order (c,h).  Cells 100 + 16 nu + 4 nr + ns
+ * (nu, nr, ns in 0..3 = sigmoid, tanh, identity, softsign) share the GRU's
+ * layouts.  Cell 5: params [2][H] = (a, b), u [2][H], state (p, q):
+ * p' = tanh(a p - b q + u_1), q' = tanh(b p + a q + u_2).
  *
  * Parity pins: every function here is checked by tests that do not call it to
  * produce their own expected value (closed forms, finite differences, brute
@@ -45,12 +54,33 @@
 #define REAL double
 #endif
 
-enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3, CELL_PARALSTM_DIAG = 4 };
+enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3, CELL_PARALSTM_DIAG = 4,
+       CELL_ROT_TANH = 5, CELL_GRU_NL = 100 /* .. 163 */ };
+enum { NL_SIGMOID = 0, NL_TANH = 1, NL_IDENTITY = 2, NL_SOFTSIGN = 3 };
 enum { ST_OK = 0, ST_NOT_CONVERGED = 1, ST_INVALID = 2, ST_NONFINITE = 5 };
 enum { JAC_DIAG = 0, JAC_BLOCK2 = 1, JAC_DENSE = 2 };
 
 static REAL sigmoid(REAL x) { return (REAL)1 / ((REAL)1 + (REAL)exp(-(double)x)); }
 static REAL tanh_r(REAL x) { return (REAL)tanh((double)x); }
+
+static int is_gru_nl(int cell) { return cell >= CELL_GRU_NL && cell < CELL_GRU_NL + 64; }
+
+/* a nonlinearity by number and its derivative, both as functions of the pre-activation */
+static REAL nl_f(int kind, REAL x)
+{
+    if (kind == NL_SIGMOID) return sigmoid(x);
+    if (kind == NL_TANH) return tanh_r(x);
+    if (kind == NL_SOFTSIGN) return x / ((REAL)1 + (REAL)fabs((double)x));
+    return x;
+}
+
+static REAL nl_d(int kind, REAL x)
+{
+    if (kind == NL_SIGMOID) { REAL s = sigmoid(x); return s * ((REAL)1 - s); }
+    if (kind == NL_TANH) { REAL t = tanh_r(x); return (REAL)1 - t * t; }
+    if (kind == NL_SOFTSIGN) { REAL q = (REAL)1 + (REAL)fabs((double)x); return (REAL)1 / (q * q); }
+    return (REAL)1;
+}
 
 int oracle_real_bytes(void) { return (int)sizeof(REAL); }
 
@@ -71,19 +101,20 @@ int oracle_gates(int cell)
     case CELL_TANH_DENSE: return 1;
     case CELL_LINEAR_DIAG: return 1;
     case CELL_PARALSTM_DIAG: return 3;
+    case CELL_ROT_TANH: return 2;
     }
-    return -1;
+    return is_gru_nl(cell) ? 3 : -1;
 }
 
 int oracle_state(int cell)
 {
-    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG) return 2;
-    return cell >= 0 && cell <= 3 ? 1 : -1;
+    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG || cell == CELL_ROT_TANH) return 2;
+    return (cell >= 0 && cell <= 3) || is_gru_nl(cell) ? 1 : -1;
 }
 
 int oracle_jac_kind(int cell)
 {
-    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG) return JAC_BLOCK2;
+    if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG || cell == CELL_ROT_TANH) return JAC_BLOCK2;
     if (cell == CELL_TANH_DENSE) return JAC_DENSE;
     return JAC_DIAG;
 }
@@ -100,6 +131,7 @@ static size_t param_count(int cell, int H)
 {
     if (cell == CELL_TANH_DENSE) return (size_t)H * H;
     if (cell == CELL_PARALSTM_DIAG) return (size_t)8 * H;
+    if (cell == CELL_ROT_TANH) return (size_t)2 * H;
     return (size_t)2 * oracle_gates(cell) * H;
 }
 
@@ -151,6 +183,24 @@ void oracle_cell_step(int cell, int H, const REAL *params, const REAL *hp, const
             REAL o = sigmoid(ao[j] * h + u[2 * H + j] + co[j] * cn + bo[j]);
             out[j] = cn;
             out[H + j] = o * tanh_r(cn);
+        }
+    } else if (is_gru_nl(cell)) {
+        /* Eq. (7a) with diagonal weights and the three nonlinearities chosen by number */
+        const int nu = ((cell - CELL_GRU_NL) >> 4) & 3, nr = ((cell - CELL_GRU_NL) >> 2) & 3, ns = (cell - CELL_GRU_NL) & 3;
+        const REAL *a = params, *b = params + 3 * H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hp[j];
+            REAL z = nl_f(nu, a[0 * H + j] * h + u[0 * H + j] + b[0 * H + j]);
+            REAL r = nl_f(nr, a[1 * H + j] * h + u[1 * H + j] + b[1 * H + j]);
+            REAL c = nl_f(ns, a[2 * H + j] * (r * h) + u[2 * H + j] + b[2 * H + j]);
+            out[j] = ((REAL)1 - z) * h + z * c;
+        }
+    } else if (cell == CELL_ROT_TANH) {
+        const REAL *a = params, *b = params + H;
+        for (j = 0; j < H; ++j) {
+            REAL p = hp[j], q = hp[H + j];
+            out[j] = tanh_r(a[j] * p - b[j] * q + u[j]);
+            out[H + j] = tanh_r(b[j] * p + a[j] * q + u[H + j]);
         }
     } else if (cell == CELL_TANH_DENSE) {
         /* generic dense-Jacobian cell: h' = tanh(W h + u) (Sec. 2.1) */
@@ -221,6 +271,31 @@ void oracle_cell_jacobian(int cell, int H, const REAL *params, const REAL *hp, c
             J[1 * H + j] = Jch;
             J[2 * H + j] = (t * so * co[j] + o * st) * Jcc;
             J[3 * H + j] = t * so * (ao[j] + co[j] * Jch) + o * st * Jch;
+        }
+    } else if (is_gru_nl(cell)) {
+        /* Eq. (8a) with sigma' and tanh' replaced by the chosen nonlinearities' derivatives */
+        const int nu = ((cell - CELL_GRU_NL) >> 4) & 3, nr = ((cell - CELL_GRU_NL) >> 2) & 3, ns = (cell - CELL_GRU_NL) & 3;
+        const REAL *a = params, *b = params + 3 * H;
+        for (j = 0; j < H; ++j) {
+            REAL h = hp[j];
+            REAL xz = a[0 * H + j] * h + u[0 * H + j] + b[0 * H + j];
+            REAL xr = a[1 * H + j] * h + u[1 * H + j] + b[1 * H + j];
+            REAL z = nl_f(nu, xz), r = nl_f(nr, xr);
+            REAL xc = a[2 * H + j] * (r * h) + u[2 * H + j] + b[2 * H + j];
+            REAL c = nl_f(ns, xc);
+            J[j] = ((REAL)1 - z) + (c - h) * nl_d(nu, xz) * a[0 * H + j]
+                 + z * nl_d(ns, xc) * a[2 * H + j] * (r + h * nl_d(nr, xr) * a[1 * H + j]);
+        }
+    } else if (cell == CELL_ROT_TANH) {
+        const REAL *a = params, *b = params + H;
+        for (j = 0; j < H; ++j) {
+            REAL p = hp[j], q = hp[H + j];
+            REAL t1 = tanh_r(a[j] * p - b[j] * q + u[j]), t2 = tanh_r(b[j] * p + a[j] * q + u[H + j]);
+            REAL d1 = (REAL)1 - t1 * t1, d2 = (REAL)1 - t2 * t2;
+            J[0 * H + j] = d1 * a[j];
+            J[1 * H + j] = -d1 * b[j];
+            J[2 * H + j] = d2 * b[j];
+            J[3 * H + j] = d2 * a[j];
         }
     } else if (cell == CELL_TANH_DENSE) {
         int i;
@@ -528,6 +603,44 @@ void oracle_backward(int cell, int B, int L, int H, const REAL *params, const RE
                     dp[5 * H + j] += d_pf; dp[6 * H + j] += d_pz; dp[7 * H + j] += d_po;
                     lprev[j] = d_cn * f + d_pf * cf[j];
                     lprev[H + j] = d_pf * af[j] + d_pz * az[j] + d_po * ao[j];
+                }
+            } else if (is_gru_nl(cell)) {
+                const int nu = ((cell - CELL_GRU_NL) >> 4) & 3, nr = ((cell - CELL_GRU_NL) >> 2) & 3,
+                          ns = (cell - CELL_GRU_NL) & 3;
+                const REAL *a = params, *bb = params + 3 * H;
+                for (j = 0; j < H; ++j) {
+                    REAL hh = hp[j], lm = lam[j];
+                    REAL xz = a[0 * H + j] * hh + ul[0 * H + j] + bb[0 * H + j];
+                    REAL xr = a[1 * H + j] * hh + ul[1 * H + j] + bb[1 * H + j];
+                    REAL z = nl_f(nu, xz), r = nl_f(nr, xr);
+                    REAL xc = a[2 * H + j] * (r * hh) + ul[2 * H + j] + bb[2 * H + j];
+                    REAL c = nl_f(ns, xc);
+                    /* h' = (1-z) h + z c, taken apart from the output backwards */
+                    REAL d_z = lm * (c - hh), d_c = lm * z, d_h = lm * ((REAL)1 - z);
+                    REAL d_pc = d_c * nl_d(ns, xc);
+                    REAL d_rh = d_pc * a[2 * H + j];
+                    REAL d_r = d_rh * hh, d_pr, d_pz;
+                    d_h += d_rh * r;
+                    d_pr = d_r * nl_d(nr, xr);
+                    d_h += d_pr * a[1 * H + j];
+                    d_pz = d_z * nl_d(nu, xz);
+                    d_h += d_pz * a[0 * H + j];
+                    dul[0 * H + j] = d_pz; dul[1 * H + j] = d_pr; dul[2 * H + j] = d_pc;
+                    dp[0 * H + j] += d_pz * hh; dp[1 * H + j] += d_pr * hh; dp[2 * H + j] += d_pc * (r * hh);
+                    dp[3 * H + j] += d_pz; dp[4 * H + j] += d_pr; dp[5 * H + j] += d_pc;
+                    lprev[j] = d_h;
+                }
+            } else if (cell == CELL_ROT_TANH) {
+                const REAL *a = params, *bb = params + H;
+                for (j = 0; j < H; ++j) {
+                    REAL p = hp[j], q = hp[H + j];
+                    REAL t1 = tanh_r(a[j] * p - bb[j] * q + ul[j]), t2 = tanh_r(bb[j] * p + a[j] * q + ul[H + j]);
+                    REAL d1 = lam[j] * ((REAL)1 - t1 * t1), d2 = lam[H + j] * ((REAL)1 - t2 * t2);
+                    dul[j] = d1; dul[H + j] = d2;
+                    dp[j] += d1 * p + d2 * q;
+                    dp[H + j] += -d1 * q + d2 * p;
+                    lprev[j] = a[j] * d1 + bb[j] * d2;
+                    lprev[H + j] = -bb[j] * d1 + a[j] * d2;
                 }
             } else if (cell == CELL_TANH_DENSE) {
                 const REAL *hl = h + ((size_t)b * L + l) * n;

@@ -10,8 +10,10 @@ import math
 import numpy as np
 import pytest
 
-DIAG_CELLS = ["gru_diag", "linear_diag"]
-ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag"]
+NL_CELLS = ["gru_nl:tanh,softsign,identity", "gru_nl:sigmoid,sigmoid,softsign", "gru_nl:softsign,tanh,sigmoid"]
+DIAG_CELLS = ["gru_diag", "linear_diag"] + NL_CELLS
+BLOCK2_CELLS = ["lstm_diag", "paralstm_diag", "rot_tanh"]
+ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag", "rot_tanh"] + NL_CELLS
 
 
 def sig(x):
@@ -28,6 +30,8 @@ def rand_params(oracle, cell, H, rng, bound=0.9, bias=True):
         if bias:
             p[5:] = rng.normal(0, 0.3, (3, H))
         return p
+    if cell == "rot_tanh":               # a, b of the per-channel rotation-scaling
+        return rng.uniform(-bound / 1.5, bound / 1.5, (2, H))
     p = np.zeros((2, G, H))
     p[0] = rng.uniform(-bound, bound, (G, H))
     if bias:
@@ -181,7 +185,7 @@ def test_jacobian_matches_central_differences(oracle_mod, cell):
         Jfd[:, q] = (fp - fm) / (2 * eps)
     if cell in DIAG_CELLS:
         Jfull = np.diag(J)
-    elif cell in ("lstm_diag", "paralstm_diag"):
+    elif cell in BLOCK2_CELLS:
         Jfull = np.zeros((n, n))
         for p_, q_ in itertools.product(range(2), range(2)):
             Jfull[p_ * H:(p_ + 1) * H, q_ * H:(q_ + 1) * H] = np.diag(J[p_, q_])
@@ -414,11 +418,11 @@ def test_backward_matches_finite_differences(oracle_mod, cell):
         return (loss(args1["p"], args1["u"], args1["h0"]) - loss(args2["p"], args2["u"], args2["h0"])) / (2 * eps)
 
     for idx in np.ndindex(*params.shape):
-        assert abs(dp[idx] - fd(params, idx, "p")) < 2e-8, ("dparams", idx)
+        assert abs(dp[idx] - fd(params, idx, "p")) < 2e-8 * max(1.0, abs(dp[idx])), ("dparams", idx)
     for idx in np.ndindex(*h0.shape):
-        assert abs(dh0[idx] - fd(h0, idx, "h0")) < 2e-8, ("dh0", idx)
+        assert abs(dh0[idx] - fd(h0, idx, "h0")) < 2e-8 * max(1.0, abs(dh0[idx])), ("dh0", idx)
     for idx in list(np.ndindex(*u.shape))[::5]:
-        assert abs(du[idx] - fd(u, idx, "u")) < 2e-8, ("du", idx)
+        assert abs(du[idx] - fd(u, idx, "u")) < 2e-8 * max(1.0, abs(du[idx])), ("du", idx)
 
 
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
@@ -487,3 +491,93 @@ def test_linear_cell_backward_du_is_lambda(oracle_mod):
     assert abs(dp[1, 0, 0] - du.sum()) < 1e-12
     hprev = np.concatenate([[0.0], h[0, :-1, 0, 0]])
     assert abs(dp[0, 0, 0] - np.sum(du[0, :, 0, 0] * hprev)) < 1e-12
+
+
+# ------------------------------------- selectable nonlinearities, 2x2 example cell
+
+def test_gru_with_default_nonlinearities_is_the_gru(oracle_mod):
+    """App. D.3: sigmoid, sigmoid, tanh are the defaults, so the selectable form
+    must reproduce Eq. (7a) / (8a) / (6) of the plain GRU exactly."""
+    o = oracle_mod
+    params, u, h0 = rand_problem(o, "gru_diag", 2, 9, 5, seed=91)
+    nl = "gru_nl:sigmoid,sigmoid,tanh"
+    assert np.array_equal(o.seq_unroll(nl, params, u, h0), o.seq_unroll("gru_diag", params, u, h0))
+    assert np.array_equal(o.cell_jacobian(nl, params, h0[0], u[0, 0]), o.cell_jacobian("gru_diag", params, h0[0], u[0, 0]))
+    h = o.seq_unroll("gru_diag", params, u, h0)
+    g = np.random.default_rng(92).normal(0, 1, h.shape)
+    for a, b in zip(o.backward(nl, params, u, h0, h, g), o.backward("gru_diag", params, u, h0, h, g)):
+        assert np.allclose(a, b, rtol=1e-13, atol=1e-15)      # products associate differently
+
+
+@pytest.mark.parametrize("state_nl", ["identity", "tanh", "softsign"])
+def test_gru_state_nonlinearity_alone(oracle_mod, state_nl):
+    """With identity update / reset gates held at z = r = 1 (a_z = a_r = 0, u_z = u_r = 1)
+    Eq. (7a) collapses to h' = NS(a_c h + u_c + b_c): the linear cell of the Sec. 2
+    footnote for identity, the dense tanh cell with a diagonal W for tanh, and
+    x / (1 + |x|) with its known values for softsign."""
+    o = oracle_mod
+    rng = np.random.default_rng(93)
+    H, L = 4, 6
+    params = np.zeros((2, 3, H)); params[0, 2] = rng.uniform(-0.9, 0.9, H); params[1, 2] = rng.normal(0, 0.3, H)
+    u = rng.normal(0, 1, (1, L, 3, H)); u[:, :, :2] = 1.0
+    h0 = rng.normal(0, 0.3, (1, 1, H))
+    h = o.seq_unroll(f"gru_nl:identity,identity,{state_nl}", params, u, h0)
+    if state_nl == "identity":
+        lin = np.stack([params[0, 2], params[1, 2]])[:, None, :]
+        assert np.allclose(h, o.seq_unroll("linear_diag", lin, u[:, :, 2:3], h0), rtol=0, atol=1e-15)
+    elif state_nl == "tanh":
+        W = np.diag(params[0, 2])
+        ref = o.seq_unroll("tanh_dense", W, u[:, :, 2:3] + params[1, 2], h0)
+        assert np.allclose(h, ref, rtol=0, atol=1e-15)
+    else:
+        pz = np.zeros((2, 3, 1))
+        for x, y in ((0.0, 0.0), (1.0, 0.5), (-1.0, -0.5), (3.0, 0.75), (-7.0, -0.875)):
+            uu = np.array([1.0, 1.0, x]).reshape(1, 1, 3, 1)
+            assert o.seq_unroll("gru_nl:identity,identity,softsign", pz, uu, None)[0, 0, 0, 0] == y
+
+
+def test_gru_gate_nonlinearities_reach_the_right_gates(oracle_mod):
+    """Which of the three selectors acts on which gate: with a_* = 0 the step is
+    h' = (1 - z) h + z c with z = NU(u_z), c = NS(u_c) and r unused; with a_c = 1,
+    u_c = 0 and identity state nonlinearity c = NR(u_r) h."""
+    o = oracle_mod
+    pz = np.zeros((2, 3, 1))
+    h0 = np.full((1, 1, 1), 0.25)
+    uu = np.array([1.0, -7.0, 3.0]).reshape(1, 1, 3, 1)
+    # z = softsign(1) = 1/2, c = softsign(3) = 3/4 -> h' = (0.25 + 0.75) / 2
+    assert o.seq_unroll("gru_nl:softsign,sigmoid,softsign", pz, uu, h0)[0, 0, 0, 0] == 0.5
+    # z = identity(1) = 1 -> h' = c = identity(3)
+    assert o.seq_unroll("gru_nl:identity,tanh,identity", pz, uu, h0)[0, 0, 0, 0] == 3.0
+    pc = pz.copy(); pc[0, 2, 0] = 1.0
+    uu = np.array([1.0, -7.0, 0.0]).reshape(1, 1, 3, 1)
+    # z = 1, c = a_c * softsign(-7) * h = -7/8 * 1/4
+    assert o.seq_unroll("gru_nl:identity,softsign,identity", pc, uu, h0)[0, 0, 0, 0] == -0.875 * 0.25
+
+
+def test_rot_tanh_is_the_dense_cell_with_a_2x2_matrix(oracle_mod):
+    """One channel of the 2x2 example cell is h' = tanh(W h + u) with
+    W = [[a, -b], [b, a]]: step, Jacobian, Newton solve and backward must agree
+    with the dense cell at H = 2 (dL/da = dW_00 + dW_11, dL/db = dW_10 - dW_01)."""
+    o = oracle_mod
+    rng = np.random.default_rng(95)
+    a, b = 0.55, -0.4
+    L = 12
+    W = np.array([[a, -b], [b, a]])
+    u = rng.normal(0, 1, (1, L, 1, 2)); h0 = rng.normal(0, 0.3, (1, 1, 2))
+    pr = np.array([[a], [b]])
+    ur = u.reshape(1, L, 2, 1); h0r = h0.reshape(1, 2, 1)
+    hd = o.seq_unroll("tanh_dense", W, u, h0)
+    hr = o.seq_unroll("rot_tanh", pr, ur, h0r)
+    assert np.allclose(hr.reshape(L, 2), hd.reshape(L, 2), rtol=0, atol=1e-15)
+    Jd = o.cell_jacobian("tanh_dense", W, h0[0], u[0, 0])
+    Jr = o.cell_jacobian("rot_tanh", pr, h0r[0], ur[0, 0])
+    assert np.allclose(Jr.reshape(2, 2), Jd, rtol=0, atol=1e-15)
+    nd = o.newton("tanh_dense", W, u, h0, tol=1e-12, max_iter=20)
+    nr = o.newton("rot_tanh", pr, ur, h0r, tol=1e-12, max_iter=20)
+    assert nd[1] == nr[1] and np.allclose(nd[3], nr[3], rtol=1e-9, atol=1e-15)
+    g = rng.normal(0, 1, (1, L, 1, 2))
+    dud, dWd, dh0d = o.backward("tanh_dense", W, u, h0, hd, g)
+    dur, dpr, dh0r = o.backward("rot_tanh", pr, ur, h0r, hr, g.reshape(1, L, 2, 1))
+    assert np.allclose(dur.reshape(L, 2), dud.reshape(L, 2), rtol=0, atol=1e-14)
+    assert np.allclose(dh0r.ravel(), dh0d.ravel(), rtol=0, atol=1e-14)
+    assert np.allclose(dpr.ravel(), [dWd[0, 0] + dWd[1, 1], dWd[1, 0] - dWd[0, 1]], rtol=0, atol=1e-13)
