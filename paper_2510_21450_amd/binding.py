@@ -48,6 +48,58 @@ _lib.pararnn_affine_scan_workspace_bytes.argtypes = [_i] * 5
 _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz, _vp]
 
 
+_FWD_ARGS = [_i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_BWD_ARGS = [_i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+class _BuiltinCell:
+    """Entry points of one built-in cell: the pararnn_* functions with the cell number bound."""
+
+    def __init__(self, name):
+        self.name = name
+        c = CELLS[name]
+        self.G, self.S = _lib.pararnn_cell_gates(c), _lib.pararnn_cell_state(c)
+        self.what = "pararnn"
+        self.ws = lambda *a: _lib.pararnn_workspace_bytes(c, *a)
+        self.ws_fused = lambda *a: _lib.pararnn_workspace_bytes_fused(c, *a)
+        self.fwd = lambda *a: _lib.pararnn_forward(c, *a)
+        self.bwd = lambda *a: _lib.pararnn_backward(c, *a)
+
+
+class UserCell:
+    """A cell from a library built with PARARNN_DEFINE_CELL(Cell, name) (include/pararnn_cell.h):
+    pass the object wherever the functions of this module take a cell name."""
+
+    def __init__(self, lib_path: str, name: str):
+        if not os.path.exists(lib_path):
+            raise ImportError(f"{lib_path} is missing: build it with `python -m paper_2510_21450_amd.build --cell ...`")
+        self.name, self.what = name, name
+        self._lib = lib = ctypes.CDLL(lib_path)
+        f = lambda s: getattr(lib, f"{name}_{s}")
+        self.G, self.S, self.param_rows = f("gates")(), f("state")(), f("param_rows")()
+        self.ws, self.ws_fused, self.fwd, self.bwd = f("workspace_bytes"), f("workspace_bytes_fused"), f("forward"), f("backward")
+        self.ws.restype = self.ws_fused.restype = _sz
+        self.ws.argtypes = self.ws_fused.argtypes = [_i] * 5
+        self.fwd.restype = self.bwd.restype = _i
+        self.fwd.argtypes, self.bwd.argtypes = _FWD_ARGS, _BWD_ARGS
+
+
+_builtin = {}
+
+
+def _api(cell):
+    if isinstance(cell, UserCell):
+        return cell
+    if cell not in _builtin:
+        _builtin[cell] = _BuiltinCell(cell)
+    return _builtin[cell]
+
+
+def example_cell(name: str) -> UserCell:
+    """One of the example cells shipped under user_cells/ ("gru_softsign", "rot_tanh")."""
+    return UserCell(os.path.join(_PKG, f"libpararnn_{name}.so"), name)
+
+
 def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
     """pararnn_set_tile: force a compiled tile shape (vec = 0: automatic)."""
     _raise(_lib.pararnn_set_tile(vec, ll, c, w), "pararnn_set_tile")
@@ -83,18 +135,18 @@ def status_string(code: int) -> str:
     return _lib.pararnn_status_string(code).decode()
 
 
-def cell_dims(cell: str):
-    """(gates G, state values S) of a cell."""
-    c = CELLS[cell]
-    return _lib.pararnn_cell_gates(c), _lib.pararnn_cell_state(c)
+def cell_dims(cell):
+    """(gates G, state values S) of a cell (a built-in cell's name or a UserCell)."""
+    a = _api(cell)
+    return a.G, a.S
 
 
-def workspace_bytes(cell: str, dtype, B: int, L: int, H: int, backward: bool = False) -> int:
-    return _lib.pararnn_workspace_bytes(CELLS[cell], DTYPES[dtype], B, L, H, int(backward))
+def workspace_bytes(cell, dtype, B: int, L: int, H: int, backward: bool = False) -> int:
+    return _api(cell).ws(DTYPES[dtype], B, L, H, int(backward))
 
 
-def workspace_bytes_fused(cell: str, dtype, B: int, L: int, H: int, n_iters: int) -> int:
-    return _lib.pararnn_workspace_bytes_fused(CELLS[cell], DTYPES[dtype], B, L, H, n_iters)
+def workspace_bytes_fused(cell, dtype, B: int, L: int, H: int, n_iters: int) -> int:
+    return _api(cell).ws_fused(DTYPES[dtype], B, L, H, n_iters)
 
 
 def set_fused(enable: bool = True) -> None:
@@ -147,9 +199,9 @@ def _raise(code, what):
         raise RuntimeError(f"{what} failed: {status_string(code)} ({code})")
 
 
-def forward(cell: str, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, trace: bool = False,
+def forward(cell, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, trace: bool = False,
             workspace=None, stream=None, out=None):
-    """pararnn_forward.  u [B][L][G][H] (fp32 or bf16), params fp32.
+    """pararnn_forward (or <name>_forward of a UserCell).  u [B][L][G][H] (fp32 or bf16), params fp32.
     Returns (h, iters, delta_trace): iters is a DEVICE int32[2] tensor
     {iterations, status} (no synchronisation happens here), delta_trace a
     device float[max_iter] tensor or None."""
@@ -166,13 +218,14 @@ def forward(cell: str, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64
     tr = torch.zeros(max(max_iter, 1), dtype=torch.float32, device=u.device) if trace else None
     need = workspace_bytes_fused(cell, dt, B, L, H, max_iter) if tol < 0 else workspace_bytes(cell, dt, B, L, H, False)
     ws = _workspace(need, u.device, workspace)
-    code = _lib.pararnn_forward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol, max_iter,
-                                _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
-    _raise(code, "pararnn_forward")
+    api = _api(cell)
+    code = api.fwd(DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol, max_iter,
+                   _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, f"{api.what}_forward")
     return h, iters, tr
 
 
-def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None, out=None):
+def backward(cell, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None, out=None):
     """pararnn_backward.  Returns (dL_du, dL_dparams, dL_dh0 or None); `out`
     may hold a preallocated (dL_du, dL_dparams, dL_dh0) triple."""
     G, S = cell_dims(cell)
@@ -195,9 +248,10 @@ def backward(cell: str, params, u, h0, h, dL_dh, want_dh0: bool = True, workspac
         dparams = torch.empty_like(params)
         dh0 = torch.empty((B, S, H), dtype=dt, device=u.device) if want_dh0 else None
     ws = _workspace(workspace_bytes(cell, dt, B, L, H, True), u.device, workspace)
-    code = _lib.pararnn_backward(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), _ptr(h), _ptr(dL_dh),
-                                 B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))
-    _raise(code, "pararnn_backward")
+    api = _api(cell)
+    code = api.bwd(DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), _ptr(h), _ptr(dL_dh),
+                   B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, f"{api.what}_backward")
     return du, dparams, dh0
 
 

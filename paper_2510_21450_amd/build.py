@@ -2,6 +2,11 @@
 
 Each .hip file is compiled to an object on its own (in parallel) and linked
 into paper_2510_21450_amd/libpararnn.so.  No GPU is needed to build.
+
+`python -m paper_2510_21450_amd.build` builds the library and the example
+cells under user_cells/; `--cell my_cell.hip [-o libmy_cell.so]` builds a
+library for a cell written against include/pararnn_cell.h and links it
+against libpararnn.so.
 """
 from __future__ import annotations
 
@@ -22,6 +27,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-but-set-variable", "-Wno-unknown-warning-option",
          "-Wno-sometimes-uninitialized", "-Wno-uninitialized"]
+
+
+USER_CELLS = os.path.join(PKG, "user_cells")
 
 
 def _compile(src: str, extra) -> str:
@@ -52,5 +60,41 @@ def build(jobs: int | None = None, extra_flags=(), verbose: bool = False) -> str
     return LIB
 
 
+def build_cell(src: str, out: str | None = None, extra_flags=(), verbose: bool = False) -> str:
+    """Compile one .hip file that defines a cell (PARARNN_DEFINE_CELL) into a shared
+    library next to libpararnn.so (or at `out`), linked against libpararnn.so."""
+    if not os.path.exists(LIB):
+        raise RuntimeError(f"{LIB} is missing: build the library first")
+    os.makedirs(OBJ, exist_ok=True)
+    stem = os.path.splitext(os.path.basename(src))[0]
+    out = out or os.path.join(PKG, f"libpararnn_{stem}.so")
+    obj = _compile(src, list(extra_flags))
+    rpath = "$ORIGIN" if os.path.dirname(os.path.abspath(out)) == PKG else PKG
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", out, obj,
+           f"-L{PKG}", "-lpararnn", f"-Wl,-rpath,{rpath}"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    if verbose:
+        print("built", out)
+    return out
+
+
+def build_examples(jobs: int | None = None, verbose: bool = False):
+    """The example cells under user_cells/ (libpararnn_<name>.so beside the library)."""
+    srcs = sorted(glob.glob(os.path.join(USER_CELLS, "*.hip")))
+    with cf.ThreadPoolExecutor(max_workers=jobs or min(8, os.cpu_count() or 1)) as ex:
+        return list(ex.map(lambda s: build_cell(s, verbose=verbose), srcs))
+
+
 if __name__ == "__main__":
-    build(verbose=True)
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--cell", help="build only this user-cell source against the existing library")
+    ap.add_argument("-o", "--out", help="output path of the user-cell library")
+    args = ap.parse_args()
+    if args.cell:
+        build_cell(args.cell, args.out, verbose=True)
+    else:
+        build(verbose=True)
+        build_examples(verbose=True)

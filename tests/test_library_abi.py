@@ -113,6 +113,46 @@ def test_host_side_argument_validation(lib):
     assert s(0, 0, p, p, 1, 8, 8, p, p, 16, None) == 3
 
 
+@pytest.mark.parametrize("name,gsp", [("gru_softsign", (3, 1, 6)), ("rot_tanh", (2, 2, 2))])
+def test_user_cell_libraries_export_their_abi(lib, name, gsp):
+    """A library made by PARARNN_DEFINE_CELL (include/pararnn_cell.h) exports the functions the
+    header lists and validates arguments like the built-in entry points."""
+    path = os.path.join(ROOT, "paper_2510_21450_amd", f"libpararnn_{name}.so")
+    if not os.path.exists(path):
+        from paper_2510_21450_amd import build
+        build.build_examples()
+    ul = ctypes.CDLL(path)
+    for fn in ("gates", "state", "param_rows", "workspace_bytes", "workspace_bytes_fused", "forward", "backward"):
+        assert hasattr(ul, f"{name}_{fn}")
+    f = lambda s: getattr(ul, f"{name}_{s}")
+    assert (f("gates")(), f("state")(), f("param_rows")()) == gsp
+    ws = f("workspace_bytes")
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [ctypes.c_int] * 5
+    assert ws(3, 1, 8, 8, 0) == 0 and ws(0, 0, 8, 8, 0) == 0
+    assert ws(0, 2, 1000, 64, 0) >= 256 and ws(1, 2, 1000, 64, 0) >= ws(0, 2, 1000, 64, 0) + 2 * 1000 * gsp[1] * 64 * 4
+    vp, i, fl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    fw = f("forward")
+    fw.restype = ctypes.c_int
+    fw.argtypes = [i, vp, vp, vp, i, i, i, fl, i, vp, vp, vp, vp, sz, vp]
+    p = 0x1000
+    assert fw(3, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == 2       # dtype
+    assert fw(0, None, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None) == 2    # params NULL
+    assert fw(0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 16, None) == 3            # WORKSPACE_TOO_SMALL
+    bw = f("backward")
+    bw.restype = ctypes.c_int
+    bw.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, sz, vp]
+    assert bw(0, p, p, None, p, None, 1, 8, 8, p, p, None, p, 1 << 20, None) == 2       # dL_dh NULL
+    assert bw(0, p, p, None, p, p, 1, 8, 8, p, p, None, p, 16, None) == 3
+    # the settings are the main library's: switching fused launches off shrinks this library's workspace too
+    big = ws(0, 4, 4096, 256, 0)
+    lib.pararnn_set_fused(0)
+    try:
+        assert ws(0, 4, 4096, 256, 0) < big
+    finally:
+        lib.pararnn_set_fused(1)
+
+
 def test_python_binding_refuses_cpu_tensors():
     import torch
     import paper_2510_21450_amd as P
