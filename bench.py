@@ -153,6 +153,22 @@ def main():
         dense_bwd()
         t_db = time_events(dense_bwd, 10)
         detail["dense_backward_ms"] = sum(t_db) / len(t_db)
+        # inexact Newton (opt-in, not the timed step): Jacobian products from bf16 terms, fp32 residual
+        inexact = {}
+        for mode, name in ((1, "bf16x3"), (2, "bf16")):
+            P.set_dense_products(mode)
+            try:
+                solve = lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
+                _, it_m, _ = solve()
+                t_m = time_events(solve, 10)
+                t_km = time_events(lambda: P.dense_chunk_products(params, dfac, out=Aout), 10)
+                it_m = [int(x) for x in it_m.cpu()]
+                inexact[name] = {"t_fwd_ms": sum(t_m) / len(t_m), "iters": it_m[0], "status": P.status_string(it_m[1]),
+                                 "chunk_products_ms": sum(t_km) / len(t_km)}
+            finally:
+                P.set_dense_products(0)
+        detail["inexact_products"] = inexact
+        P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
         roofline = {"bound": "mfma", "kernel": "dense_products_sweep_kernel (chunk products part)", "achieved": ach,
                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(args.config)}

@@ -222,6 +222,24 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
  * bytes of device memory, 256-byte aligned.
  */
 int pararnn_dense_chunk(void);
+
+/*
+ * Inexact-Newton switch of the dense path (host, process-wide; default 0).
+ * The Jacobian products of the scan are what makes dense Jacobians expensive
+ * (Sec. 2.1: cubic in the state size); mode selects their arithmetic in
+ * FORWARD solves (pararnn_forward, pararnn_dense_chunk_products):
+ *   0  fp32 on the matrix cores: Newton's method proper;
+ *   1  every operand split into two bf16 terms, three bf16 products per fp32
+ *      product (relative error about 2^-16 per product);
+ *   2  one bf16 product (about 2^-8).
+ * In modes 1 and 2 the linear solve of an iteration is approximate while the
+ * residual stays fp32, so a solve to a tolerance converges to the same states
+ * (same stopping test) and may take more iterations; with tol < 0 the iterate
+ * after max_iter iterations differs from Newton's.  pararnn_backward is one
+ * linear solve, not an iteration, and always uses fp32 products.
+ * Returns PARARNN_INVALID_ARG for any other mode.
+ */
+int pararnn_set_dense_products(int mode);
 int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -3,11 +3,23 @@
 Thin Python binding over the C ABI of libpararnn.so (include/pararnn.h).
 PyTorch is used for device memory and streams only; every step of the method
 runs in the HIP kernels.  The library must have been built
-(`python -m paper_2510_21450_amd.build`); importing without it fails.
+(`python -m paper_2510_21450_amd.build`): the binding is loaded on first use of
+any name below and raises ImportError when the library is missing or older
+than the binding (there is no CPU fallback).  Only the `build` submodule works
+without the library.
 """
-from .binding import (CELLS, DTYPES, STATUS, UserCell, example_cell, affine_scan, backward, cell_dims, dense_chunk, dense_chunk_products, forward, lib_path, set_fused, set_fused_head, set_tile, solve_plan,
-                      status_string, version, workspace_bytes, workspace_bytes_fused)
-from .autograd import rnn_apply
+import importlib
 
-__all__ = ["rnn_apply", "UserCell", "example_cell", "CELLS", "DTYPES", "STATUS", "affine_scan", "backward", "cell_dims", "dense_chunk", "dense_chunk_products", "forward", "lib_path", "set_fused", "set_fused_head", "set_tile", "solve_plan",
-           "status_string", "version", "workspace_bytes", "workspace_bytes_fused"]
+_BINDING = ["CELLS", "DTYPES", "STATUS", "UserCell", "example_cell", "affine_scan", "backward", "cell_dims",
+            "dense_chunk", "dense_chunk_products", "forward", "lib_path", "set_dense_products", "set_fused",
+            "set_fused_head", "set_tile", "solve_plan", "status_string", "version", "workspace_bytes",
+            "workspace_bytes_fused"]
+__all__ = ["rnn_apply"] + _BINDING
+
+
+def __getattr__(name):
+    if name in _BINDING:
+        return getattr(importlib.import_module(".binding", __name__), name)
+    if name == "rnn_apply":
+        return importlib.import_module(".autograd", __name__).rnn_apply
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -20,6 +20,10 @@ if not os.path.exists(_LIB_PATH):
                       "(there is no CPU fallback)")
 
 _lib = ctypes.CDLL(_LIB_PATH)
+for _name in ("pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
+    if not hasattr(_lib, _name):
+        raise ImportError(f"{_LIB_PATH} is older than this binding ({_name} is missing): rebuild it with "
+                          "`python -m paper_2510_21450_amd.build`")
 _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
 _lib.pararnn_status_string.restype = ctypes.c_char_p
 _lib.pararnn_status_string.argtypes = [_i]
@@ -33,6 +37,7 @@ _lib.pararnn_workspace_bytes.argtypes = [_i] * 6
 _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
+_lib.pararnn_set_dense_products.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
 _lib.pararnn_solve_plan.restype = _i
 _lib.pararnn_solve_plan.argtypes = [ctypes.c_float, _i, ctypes.POINTER(ctypes.c_int), _i]
@@ -103,6 +108,11 @@ def example_cell(name: str) -> UserCell:
 def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
     """pararnn_set_tile: force a compiled tile shape (vec = 0: automatic)."""
     _raise(_lib.pararnn_set_tile(vec, ll, c, w), "pararnn_set_tile")
+
+
+def set_dense_products(mode: int = 0) -> None:
+    """pararnn_set_dense_products: 0 fp32 Jacobian products (default), 1 three bf16 terms, 2 one bf16 term."""
+    _raise(_lib.pararnn_set_dense_products(int(mode)), "pararnn_set_dense_products")
 
 
 def dense_chunk() -> int:

@@ -19,6 +19,8 @@ int dense_backward(int dtype, const float *W, const void *u, const void *h0, con
 // A[b][c] = J_e ... J_s, J_l = diag(d_l) W, for the chunks 1 .. n_c-2 (the ones the
 // scan needs); ctrl_scratch is 256 bytes of device memory.
 int dense_chunk();
+// Arithmetic of the chunk products of forward solves: 0 fp32 (default), 1 three bf16 terms, 2 one bf16 term.
+int dense_set_products(int mode);
 int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
                          hipStream_t st);
 

@@ -43,6 +43,9 @@ constexpr int DH = 64;          // hidden size this path is built for
 constexpr int CD = 16;          // timesteps per chunk
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef float f4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
 struct DenseArgs {
     const float *W;      // [64][64] row-major
@@ -237,6 +240,159 @@ __device__ __forceinline__ void chunk_products_body(const DenseArgs &a, int bloc
                 out[(32 * mt + mfma_row(v, half)) * DH + 32 * nt + n] = odd ? Q[mt][nt][v] : P[mt][nt][v];
 }
 
+// ------------------------------------------- chunk products, bf16 matrix cores
+// The same compositions with the operands split into bf16 terms (an inexact
+// Jacobian for the Newton step: the residual stays fp32, so the solve converges to
+// the same states; only the carries x_c are computed from approximate A_c).
+// TERMS = 3: x = hi + lo with hi = bf16(x), lo = bf16(x - hi), and
+//   W B ~ W_hi B_hi + W_hi B_lo + W_lo B_hi   (relative error ~2^-16 per product);
+// TERMS = 1: W_hi B_hi only (~2^-8).
+// v_mfma_f32_32x32x16_bf16 takes eight consecutive k per lane half.  As in the
+// fp32 kernel the accumulator is fed back as the B operand without a layout
+// change: k-slot j of lane half g of k-block kb stands for row
+// 16 kb + 8 (j / 4) + 4 g + j % 4 of the 32-row block, which is accumulator
+// register 8 kb + j, and W is held in registers with its columns in that order.
+// The row factor d_l is applied to the fp32 result, so W's split is done once.
+__device__ __forceinline__ unsigned int pack_bf16(float x0, float x1)
+{
+    const bf2v p = {(__bf16)x0, (__bf16)x1};
+    return __builtin_bit_cast(unsigned int, p);
+}
+
+// registers 8 kb .. 8 kb + 7 of an accumulator as bf16 operand(s)
+template <int TERMS>
+__device__ __forceinline__ void split_operand(const f16v &x, int kb, bf8v &hi, bf8v &lo)
+{
+    u4v ph, pl = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float x0 = x[8 * kb + 2 * j], x1 = x[8 * kb + 2 * j + 1];
+        const unsigned int pk = pack_bf16(x0, x1);
+        ph[j] = pk;
+        if (TERMS > 1) {
+            const float h0 = __builtin_bit_cast(float, pk << 16), h1 = __builtin_bit_cast(float, pk & 0xffff0000u);
+            pl[j] = pack_bf16(x0 - h0, x1 - h1);
+        }
+    }
+    hi = __builtin_bit_cast(bf8v, ph);
+    lo = __builtin_bit_cast(bf8v, pl);
+}
+
+template <int TERMS>
+__device__ __forceinline__ void chunk_products_bf16_body(const DenseArgs &a, int block)
+{
+    const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+    const int item = block * 4 + (threadIdx.x >> 6);
+    const int per_seq = a.n_c - 2;
+    if (per_seq <= 0 || item >= a.B * per_seq) return;
+    const int b = item / per_seq, c = 1 + item % per_seq;
+    const int ls = c * CD, n_steps = min(a.L, ls + CD) - ls;
+
+    // W as A operands: whi[mt][kt][kb] slot j = W[32 mt + n][32 kt + 16 kb + 8 (j/4) + 4 half + j%4]
+    bf8v whi[2][2][2], wlo[2][2][2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                f16v t;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const f4v w4 = *reinterpret_cast<const f4v *>(a.W + (32 * mt + n) * DH + 32 * kt + 16 * kb + 8 * q + 4 * half);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[4 * q + e] = w4[e];
+                }
+                split_operand<TERMS>(t, 0, whi[mt][kt][kb], wlo[mt][kt][kb]);
+            }
+
+    // The row factors of the chunk go through LDS (one region per wave): rows of d arrive as
+    // coalesced float4 loads and are read back in accumulator order, dq[mt][q] =
+    // d[32 mt + 8 q + 4 half .. +3], the same 16 bytes for all lanes of a half.  Only this
+    // wave touches its region, and a wave's LDS operations complete in order.
+    __shared__ __attribute__((aligned(16))) float s_d[4][CD][DH];
+    float(*sd)[DH] = s_d[threadIdx.x >> 6];
+#pragma unroll
+    for (int j = 0; j < CD / 4; ++j) {
+        const int i = 4 * j + (lane >> 4);
+        const f4v t = *reinterpret_cast<const f4v *>(a.d + scan_row(a, b, ls + min(i, n_steps - 1)) * DH + 4 * (lane & 15));
+        *reinterpret_cast<f4v *>(&sd[i][4 * (lane & 15)]) = t;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    auto dload = [&](int i, f4v(&dq)[2][4]) {
+        const int ii = min(i, CD - 1);                // the value past the last step is never used
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dq[mt][q] = *reinterpret_cast<const f4v *>(&sd[ii][32 * mt + 8 * q + 4 * half]);
+    };
+    // acc = J_ls in accumulator layout: acc[mt][nt][v] = d[row] W[row][32 nt + n]
+    f16v acc[2][2];
+    {
+        f4v d0[2][4];
+        dload(0, d0);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 32 * mt + mfma_row(v, half);
+                const float dv = d0[mt][v >> 2][v & 3];
+                acc[mt][0][v] = dv * a.W[row * DH + n];
+                acc[mt][1][v] = dv * a.W[row * DH + 32 + n];
+            }
+    }
+    f4v dcur[2][4], dnext[2][4];
+    dload(1, dcur);
+#pragma unroll 1
+    for (int i = 1; i < n_steps; ++i) {
+        dload(i + 1, dnext);
+        bf8v bhi[2][2][2], blo[2][2][2];              // [kt][nt][kb]
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) split_operand<TERMS>(acc[kt][nt], kb, bhi[kt][nt][kb], blo[kt][nt][kb]);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                f16v s;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+                if (TERMS > 1) {
+                    // the small terms first
+#pragma unroll
+                    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                        for (int kb = 0; kb < 2; ++kb) {
+                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi[mt][kt][kb], blo[kt][nt][kb], s, 0, 0, 0);
+                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo[mt][kt][kb], bhi[kt][nt][kb], s, 0, 0, 0);
+                        }
+                }
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi[mt][kt][kb], bhi[kt][nt][kb], s, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mt][nt][v] = s[v] * dcur[mt][v >> 2][v & 3];
+            }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dcur[mt][q] = dnext[mt][q];
+    }
+    float *out = a.Ac + ((size_t)b * a.n_c + c) * DH * DH;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[(32 * mt + mfma_row(v, half)) * DH + 32 * nt + n] = acc[mt][nt][v];
+}
+
 // The last workgroup of the final sweep closes the iteration: stopping test,
 // results, reset of the counters (same protocol as the scan kernels).
 __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block_max)
@@ -376,12 +532,24 @@ __global__ __launch_bounds__(256) void dense_final_sweep_kernel(const DenseArgs 
 // other: one launch runs both.  The first n_sweep workgroups take the sweeps,
 // whose sequential chains are bound by latency and so start first; the rest
 // compose the chunk products, which keep the matrix cores busy meanwhile.
-template <bool BWD>
+// PROD: how the chunk products are formed: 0 fp32, 1 three bf16 terms, 2 one bf16 term
+template <bool BWD, int PROD>
 __global__ __launch_bounds__(256, 2) void dense_products_sweep_kernel(const DenseArgs a, int n_sweep)
 {
     if (a.ctrl->stop) return;
     if ((int)blockIdx.x < n_sweep) sweep_body<0, BWD>(a, blockIdx.x);
-    else chunk_products_body(a, (int)blockIdx.x - n_sweep);
+    else if (PROD == 0) chunk_products_body(a, (int)blockIdx.x - n_sweep);
+    else chunk_products_bf16_body<PROD == 1 ? 3 : 1>(a, (int)blockIdx.x - n_sweep);
+}
+
+// process-wide choice of the product arithmetic of forward solves (pararnn_set_dense_products)
+int g_dense_products = 0;
+
+void launch_products_sweep(int prod, int blocks, hipStream_t st, const DenseArgs &a, int n_sweep)
+{
+    if (prod == 1) hipLaunchKernelGGL((dense_products_sweep_kernel<false, 1>), dim3(blocks), dim3(256), 0, st, a, n_sweep);
+    else if (prod == 2) hipLaunchKernelGGL((dense_products_sweep_kernel<false, 2>), dim3(blocks), dim3(256), 0, st, a, n_sweep);
+    else hipLaunchKernelGGL((dense_products_sweep_kernel<false, 0>), dim3(blocks), dim3(256), 0, st, a, n_sweep);
 }
 
 // --------------------------------------------------------------------- carry
@@ -528,6 +696,13 @@ DenseLayout dense_layout(int B, int L)
 
 int dense_chunk() { return CD; }
 
+int dense_set_products(int mode)
+{
+    if (mode < 0 || mode > 2) return PARARNN_INVALID_ARG;
+    g_dense_products = mode;
+    return PARARNN_OK;
+}
+
 int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
                          hipStream_t st)
 {
@@ -541,7 +716,7 @@ int dense_chunk_products(const float *W, const float *d, int B, int L, int H, fl
     if (launch_reset(a.ctrl, nullptr, 0, nullptr, 0, st) != hipSuccess) return PARARNN_HIP_ERROR;
     const int n_prod = B * (a.n_c - 2);
     if (n_prod > 0)
-        hipLaunchKernelGGL(dense_products_sweep_kernel<false>, dim3((n_prod + 3) / 4), dim3(256), 0, st, a, 0);
+        launch_products_sweep(g_dense_products, (n_prod + 3) / 4, st, a, 0);
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
@@ -600,7 +775,8 @@ int dense_backward(int dtype, const float *W, const void *u, const void *h0, con
     const int n_prod = B * (lo.n_c - 2);
     const int n_sweep = (B * lo.n_c + 15) / 16;
     const int n_prod_blocks = n_prod > 0 ? (n_prod + 3) / 4 : 0;
-    hipLaunchKernelGGL(dense_products_sweep_kernel<true>, dim3(n_sweep + n_prod_blocks), dim3(256), 0, st, a, n_sweep);
+    // always fp32 products: this is one linear solve, not an iteration that would correct an inexact one
+    hipLaunchKernelGGL((dense_products_sweep_kernel<true, 0>), dim3(n_sweep + n_prod_blocks), dim3(256), 0, st, a, n_sweep);
     hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
     hipLaunchKernelGGL(dense_final_sweep_kernel<true>, dim3(n_sweep), dim3(256), 0, st, a);
     // step-local gradients
@@ -648,7 +824,7 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     for (int k = 1; k <= max_iter; ++k) {
         a.k = k;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
-        hipLaunchKernelGGL(dense_products_sweep_kernel<false>, dim3(n_sweep + n_prod_blocks), dim3(256), 0, st, a, n_sweep);
+        launch_products_sweep(g_dense_products, n_sweep + n_prod_blocks, st, a, n_sweep);
         hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
         hipLaunchKernelGGL(dense_final_sweep_kernel<false>, dim3(n_sweep), dim3(256), 0, st, a);
     }

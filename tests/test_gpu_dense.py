@@ -178,3 +178,76 @@ def test_dense_backward_config_c4(oracle_mod):
         sl = slice(b, b + 16)
         acc += f64(P.backward(w.cell, W, u[sl].contiguous(), None, h[sl].contiguous(), g[sl].contiguous())[1])
     assert relerr(f64(dW), acc) <= 1e-5
+
+
+# ---------------------------------------------------- inexact Jacobian products
+
+@pytest.fixture
+def products_mode():
+    """Sets the product arithmetic for one test and always restores fp32."""
+    import paper_2510_21450_amd as P
+    yield P.set_dense_products
+    P.set_dense_products(0)
+
+
+@pytest.mark.parametrize("mode,bound", [(1, 1e-4), (2, 2e-2)])
+@pytest.mark.parametrize("shape", [(2, 48), (3, 70), (5, 160)])
+def test_chunk_products_in_bf16_terms(products_mode, mode, bound, shape):
+    """The compositions from bf16 terms against numpy's fp64 products: three
+    terms lose about 2^-16 per product, one term about 2^-8; 15 products per chunk."""
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    W = normal(78, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    d = (1.0 - torch.tanh(normal(78, 1, (B, L, H), device="cuda")) ** 2).contiguous()
+    products_mode(mode)
+    A = P.dense_chunk_products(W, d)
+    torch.cuda.synchronize()
+    chunk = P.dense_chunk()
+    n_c = (L + chunk - 1) // chunk
+    Wn, dn, An = f64(W), f64(d), f64(A)
+    worst = 0.0
+    for b in range(B):
+        for c in range(1, n_c - 1):
+            ref = np.eye(H)
+            for l in range(c * chunk, min(L, (c + 1) * chunk)):
+                ref = (dn[b, l][:, None] * Wn) @ ref
+            worst = max(worst, relerr(An[b, c], ref))
+    print(f"mode {mode} {shape}: worst norm-wise error of a chunk product {worst:.2e}", flush=True)
+    assert worst <= bound
+    assert worst >= 1e-7          # it is not the fp32 kernel that ran
+
+
+@pytest.mark.parametrize("mode,extra", [(1, 1), (2, 12)])
+@pytest.mark.parametrize("shape", [(3, 50), (33, 100), (5, 257), (64, 1024)])
+def test_dense_solve_with_inexact_products_reaches_the_same_states(oracle_mod, products_mode, mode, extra, shape):
+    """Inexact Newton: with approximate Jacobian products and the fp32 residual the
+    solve still ends at the recurrence's states (1e-5 against the sequential
+    unroll), the stopping test still holds what it promises, and the iteration
+    count is at least Newton's and exceeds it by a few at most."""
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    W = normal(950 + L, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(950 + L, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(950 + L, 3, (B, 1, H), std=0.3, device="cuda")
+    Wn, un, h0n = f64(W), f64(u), f64(h0)
+    ref = oracle_mod.seq_unroll("tanh_dense", Wn, un, h0n)
+    tol = 1e-5
+    _, it32, st32, _ = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=32, precision="f32")
+    assert st32 == 0
+    products_mode(mode)
+    h, iters, tr = P.forward("tanh_dense", W, u, h0, tol=tol, max_iter=32, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    tr = tr.cpu().numpy()[:it]
+    print(f"mode {mode} {shape}: {it} iterations (Newton {it32}), trace {tr}", flush=True)
+    assert st == 0 and tr[-1] <= tol and (it == 1 or tr[-2] > tol)
+    assert relerr(f64(h), ref) <= 1e-5
+    assert it32 - 1 <= it <= it32 + extra
+    # the backward pass is unaffected by the mode (always fp32 products)
+    g = normal(951 + L, 4, (B, L, 1, H), device="cuda")
+    du, dW, dh0 = P.backward("tanh_dense", W, u, h0, h, g)
+    torch.cuda.synchronize()
+    rdu, rdW, rdh0 = oracle_mod.backward("tanh_dense", Wn, un, h0n, f64(h), f64(g))
+    assert relerr(f64(du), rdu) <= 1e-5 and relerr(f64(dW), rdW) <= 1e-5 and relerr(f64(dh0), rdh0) <= 1e-5

@@ -70,6 +70,12 @@ def test_workspace_bytes(lib):
     assert ws(2, 0, 64, 1024, 64, 0) >= 2 * 64 * 1024 * 64 * 4 + 64 * 64 * 64 * 64 * 4
 
 
+def test_dense_products_switch(lib):
+    sp = lib.pararnn_set_dense_products
+    assert sp(1) == 0 and sp(2) == 0 and sp(0) == 0
+    assert sp(3) == 2 and sp(-1) == 2
+
+
 def test_tile_hook(lib):
     st = lib.pararnn_set_tile
     assert st(4, 4, 8, 8) == 0          # a compiled shape
