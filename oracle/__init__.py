@@ -175,3 +175,35 @@ def backward(cell, params, u, h0, h, g, precision="f64"):
                         du.ctypes.data_as(ctypes.c_void_p), dparams.ctypes.data_as(ctypes.c_void_p),
                         dh0.ctypes.data_as(ctypes.c_void_p))
     return du, dparams, dh0
+
+
+def input_projection(x, Wx, bias=None, n_heads=1, precision="f64"):
+    """u = B x + b for all gates (Eq. (7a) / (7b) input terms, multi-head per App. C).
+    x [..., H], Wx [G][H][H / n_heads], bias [G][H] or None -> u [..., G, H]."""
+    lib = _lib(precision)
+    x_a, xp = _c(x, precision)
+    w_a, wp = _c(Wx, precision)
+    G, H, dh = w_a.shape
+    assert x_a.shape[-1] == H and dh * n_heads == H
+    _b, bp = _c(bias, precision)
+    rows = x_a.size // H
+    u = np.empty(x_a.shape[:-1] + (G, H), dtype=_np_t(precision))
+    lib.oracle_input_projection(rows, H, G, n_heads, xp, wp, bp, u.ctypes.data_as(ctypes.c_void_p))
+    return u
+
+
+def input_projection_backward(x, Wx, du, n_heads=1, precision="f64"):
+    """Returns (dx, dWx, dbias) for du = dL/du of input_projection."""
+    lib = _lib(precision)
+    x_a, xp = _c(x, precision)
+    w_a, wp = _c(Wx, precision)
+    du_a, dup = _c(du, precision)
+    G, H, dh = w_a.shape
+    rows = x_a.size // H
+    assert du_a.shape == x_a.shape[:-1] + (G, H)
+    dx = np.empty_like(x_a)
+    dW = np.empty_like(w_a)
+    db = np.empty((G, H), dtype=_np_t(precision))
+    lib.oracle_input_projection_backward(rows, H, G, n_heads, xp, wp, dup, dx.ctypes.data_as(ctypes.c_void_p),
+                                         dW.ctypes.data_as(ctypes.c_void_p), db.ctypes.data_as(ctypes.c_void_p))
+    return dx, dW, db

@@ -19,6 +19,9 @@
  *   - Sec. 3, Eq. (7b) / (8b) with diagonal A_*, C_* (Eq. (9)): the
  *     CIFG LSTM with peepholes (ParaLSTM) and its 2x2 Jacobian    -> cell 4
  *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
+ *   - Sec. 3, Eq. (7a) / (7b): the input terms B_* x_l + b_* of all gates,
+ *     with the multi-head (block-diagonal) input matrices of App. C     -> oracle_input_projection
+ *     and the derivatives of that map                                   -> oracle_input_projection_backward
  *   - App. D.3: the GRU's update / reset / state nonlinearities are
  *     parameters of the cell: Eq. (7a) / (8a) with each of them chosen
  *     from sigmoid, tanh, identity, softsign                      -> cells 100..163
@@ -677,4 +680,72 @@ void oracle_backward(int cell, int B, int L, int H, const REAL *params, const RE
         dparams[q] = s;
     }
     free(dpb);
+}
+
+/* ------------------------------------------------------- input projection */
+
+/* The gate pre-activations that feed the recurrence: for every row m = (b, l),
+ * gate g and channel h,
+ *     u[m][g][h] = sum_j Wx[g][h][j] x[m][head(h) * dh + j] + bias[g][h],
+ * dh = H / n_heads, head(h) = h / dh: each head's dh outputs read only that
+ * head's dh inputs (App. C), i.e. the input matrix B_g of Eq. (7a) / (7b) is
+ * block diagonal with n_heads blocks; n_heads = 1 is a full matrix.
+ * x [rows][H], Wx [G][H][dh], bias [G][H] or NULL, u [rows][G][H]. */
+void oracle_input_projection(int rows, int H, int G, int n_heads, const REAL *x, const REAL *Wx,
+                             const REAL *bias, REAL *u)
+{
+    const int dh = H / n_heads;
+    int m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < rows; ++m) {
+        int g, h, j;
+        for (g = 0; g < G; ++g)
+            for (h = 0; h < H; ++h) {
+                const REAL *w = Wx + ((size_t)g * H + h) * dh;
+                const REAL *xr = x + (size_t)m * H + (size_t)(h / dh) * dh;
+                REAL s = bias ? bias[(size_t)g * H + h] : (REAL)0;
+                for (j = 0; j < dh; ++j) s += w[j] * xr[j];
+                u[((size_t)m * G + g) * H + h] = s;
+            }
+    }
+}
+
+/* Derivatives of the map above for an incoming du = dL/du:
+ *     dx[m][head*dh + j]   = sum_g sum_{h in head} du[m][g][h] Wx[g][h][j]
+ *     dWx[g][h][j]         = sum_m du[m][g][h] x[m][head(h)*dh + j]
+ *     dbias[g][h]          = sum_m du[m][g][h]
+ * dbias may be NULL. */
+void oracle_input_projection_backward(int rows, int H, int G, int n_heads, const REAL *x, const REAL *Wx,
+                                      const REAL *du, REAL *dx, REAL *dWx, REAL *dbias)
+{
+    const int dh = H / n_heads;
+    int m, q;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < rows; ++m) {
+        int g, h, j;
+        REAL *dxr = dx + (size_t)m * H;
+        for (j = 0; j < H; ++j) dxr[j] = 0;
+        for (g = 0; g < G; ++g)
+            for (h = 0; h < H; ++h) {
+                const REAL d = du[((size_t)m * G + g) * H + h];
+                const REAL *w = Wx + ((size_t)g * H + h) * dh;
+                REAL *dxh = dxr + (size_t)(h / dh) * dh;
+                for (j = 0; j < dh; ++j) dxh[j] += d * w[j];
+            }
+    }
+#pragma omp parallel for schedule(static)
+    for (q = 0; q < G * H; ++q) {
+        const int h = q % H;
+        int j;
+        REAL *dw = dWx + (size_t)q * dh;
+        REAL sb = 0;
+        for (j = 0; j < dh; ++j) dw[j] = 0;
+        for (m = 0; m < rows; ++m) {
+            const REAL d = du[(size_t)m * G * H + q];
+            const REAL *xr = x + (size_t)m * H + (size_t)(h / dh) * dh;
+            for (j = 0; j < dh; ++j) dw[j] += d * xr[j];
+            sb += d;
+        }
+        if (dbias) dbias[q] = sb;
+    }
 }

@@ -581,3 +581,49 @@ def test_rot_tanh_is_the_dense_cell_with_a_2x2_matrix(oracle_mod):
     assert np.allclose(dur.reshape(L, 2), dud.reshape(L, 2), rtol=0, atol=1e-14)
     assert np.allclose(dh0r.ravel(), dh0d.ravel(), rtol=0, atol=1e-14)
     assert np.allclose(dpr.ravel(), [dWd[0, 0] + dWd[1, 1], dWd[1, 0] - dWd[0, 1]], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------- input projection
+
+@pytest.mark.parametrize("n_heads", [1, 2, 4])
+def test_input_projection_is_a_block_diagonal_matrix_product(oracle_mod, n_heads):
+    """Eq. (7a): u_g = B_g x + b_g.  With n_heads heads B_g is block diagonal
+    (App. C); expanding it to a full H x H matrix, the map is a plain matrix
+    product, here numpy's."""
+    o = oracle_mod
+    rng = np.random.default_rng(101 + n_heads)
+    Bt, L, H, G = 2, 5, 8, 3
+    dh = H // n_heads
+    x = rng.normal(0, 1, (Bt, L, H)); Wx = rng.normal(0, 1, (G, H, dh)); b = rng.normal(0, 1, (G, H))
+    full = np.zeros((G, H, H))
+    for h in range(H):
+        k = h // dh
+        full[:, h, k * dh:(k + 1) * dh] = Wx[:, h, :]
+    ref = np.einsum("blj,ghj->blgh", x, full) + b
+    assert np.allclose(o.input_projection(x, Wx, b, n_heads), ref, rtol=0, atol=1e-13)
+    assert np.allclose(o.input_projection(x, Wx, None, n_heads), ref - b, rtol=0, atol=1e-13)
+    # heads do not mix: changing head 0's inputs leaves the other heads' outputs alone
+    if n_heads > 1:
+        x2 = x.copy(); x2[..., :dh] += 1.0
+        u1, u2 = o.input_projection(x, Wx, b, n_heads), o.input_projection(x2, Wx, b, n_heads)
+        assert np.array_equal(u1[..., dh:], u2[..., dh:]) and not np.allclose(u1[..., :dh], u2[..., :dh])
+
+
+@pytest.mark.parametrize("n_heads", [1, 2])
+def test_input_projection_backward_matches_finite_differences(oracle_mod, n_heads):
+    o = oracle_mod
+    rng = np.random.default_rng(111)
+    rows, H, G = 6, 4, 3
+    dh = H // n_heads
+    x = rng.normal(0, 1, (rows, H)); Wx = rng.normal(0, 1, (G, H, dh)); b = rng.normal(0, 1, (G, H))
+    w = rng.normal(0, 1, (rows, G, H))
+    loss = lambda xx, WW, bb: float(np.sum(w * o.input_projection(xx, WW, bb, n_heads)))
+    dx, dW, db = o.input_projection_backward(x, Wx, w, n_heads)
+    eps = 1e-6
+    for arr, grad, which in ((x, dx, 0), (Wx, dW, 1), (b, db, 2)):
+        for idx in np.ndindex(*arr.shape):
+            a1 = arr.copy(); a2 = arr.copy(); a1[idx] += eps; a2[idx] -= eps
+            args1 = [x, Wx, b]; args2 = [x, Wx, b]
+            args1[which] = a1; args2[which] = a2
+            fd = (loss(*args1) - loss(*args2)) / (2 * eps)
+            assert abs(grad[idx] - fd) < 1e-7 * max(1.0, abs(fd)), (which, idx)
