@@ -212,6 +212,39 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
                         float *delta, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The input projection in front of the recurrence and its derivatives, on the
+ * matrix cores.  Sec. 3, Eq. (7a) / (7b): every gate reads the input through
+ * B_g x_l + b_g; App. C: with n_heads heads the channels are split into n_heads
+ * groups of dh = H / n_heads and B_g is block diagonal, head k's dh outputs
+ * reading only head k's dh inputs (n_heads = 1: a full H x H matrix).
+ *
+ *   forward:   u[b][l][g][h] = sum_j Wx[g][h][j] * x[b][l][head(h)*dh + j] + bias[g][h]
+ *   backward:  dx[b][l][k*dh + j] = sum_g sum_i du[b][l][g][k*dh + i] * Wx[g][k*dh + i][j]
+ *              dWx[g][h][j]       = sum_{b,l} du[b][l][g][h] * x[b][l][head(h)*dh + j]
+ *              dbias[g][h]        = sum_{b,l} du[b][l][g][h]
+ *
+ * x, dx [B][L][H]; u, du [B][L][G][H] (the layout pararnn_forward reads and
+ * pararnn_backward writes), all of type dtype; Wx, dWx fp32 [G][H][dh]; bias,
+ * dbias fp32 [G][H].  bias may be NULL (no bias); in the backward call dx, dWx
+ * and dbias may each be NULL (not wanted), dbias only together with dWx.
+ * Arithmetic: operands rounded to bf16, products accumulated in fp32 (the
+ * paper's mixed-precision set-up); dWx / dbias partial sums are added in a fixed
+ * order, so results are bit-reproducible.  Device pointers, 16-byte aligned
+ * (else UNSUPPORTED); dh must be a multiple of 64 (else UNSUPPORTED), G <= 8.
+ * workspace: pararnn_input_projection_workspace_bytes() bytes (0 for invalid
+ * arguments), 256-byte aligned, needs no initialisation, may be shared with the
+ * other calls on the same stream.  Kernels are enqueued on hip_stream; nothing
+ * is allocated or synchronised.  Status codes as above.
+ */
+size_t pararnn_input_projection_workspace_bytes(int dtype, int B, int L, int H, int G, int n_heads, int backward);
+int pararnn_input_projection(int dtype, const void *x, const float *Wx, const float *bias, int B, int L, int H,
+                             int G, int n_heads, void *u, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+int pararnn_input_projection_backward(int dtype, const void *x, const float *Wx, const void *du, int B, int L,
+                                      int H, int G, int n_heads, void *dx, float *dWx, float *dbias,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The composition kernel of the dense scan on its own (testing / profiling):
  * the products of Jacobians J_l = diag(d_l) W that Alg. 1b's update of A
  * performs, taken over chunks of pararnn_dense_chunk() consecutive timesteps,

@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
                       "(there is no CPU fallback)")
 
 _lib = ctypes.CDLL(_LIB_PATH)
-for _name in ("pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
+for _name in ("pararnn_input_projection", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
     if not hasattr(_lib, _name):
         raise ImportError(f"{_LIB_PATH} is older than this binding ({_name} is missing): rebuild it with "
                           "`python -m paper_2510_21450_amd.build`")
@@ -263,6 +263,56 @@ def backward(cell, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=Non
                    B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))
     _raise(code, f"{api.what}_backward")
     return du, dparams, dh0
+
+
+_lib.pararnn_input_projection_workspace_bytes.restype = _sz
+_lib.pararnn_input_projection_workspace_bytes.argtypes = [_i] * 7
+_lib.pararnn_input_projection.restype = _i
+_lib.pararnn_input_projection.argtypes = [_i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.pararnn_input_projection_backward.restype = _i
+_lib.pararnn_input_projection_backward.argtypes = [_i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+def input_projection_workspace_bytes(dtype, B: int, L: int, H: int, G: int, n_heads: int = 1, backward: bool = False) -> int:
+    return _lib.pararnn_input_projection_workspace_bytes(DTYPES[dtype], B, L, H, G, n_heads, int(backward))
+
+
+def input_projection(x, Wx, bias=None, n_heads: int = 1, workspace=None, stream=None, out=None):
+    """pararnn_input_projection.  x [B][L][H], Wx fp32 [G][H][H / n_heads], bias fp32 [G][H] or None
+    -> u [B][L][G][H] of x's dtype."""
+    B, L, H = x.shape
+    G = Wx.shape[0]
+    dt = x.dtype
+    _check(x, "x", dt, (B, L, H))
+    _check(Wx, "Wx", torch.float32, (G, H, H // n_heads))
+    if bias is not None:
+        _check(bias, "bias", torch.float32, (G, H))
+    u = torch.empty((B, L, G, H), dtype=dt, device=x.device) if out is None else out
+    _check(u, "u", dt, (B, L, G, H))
+    ws = _workspace(input_projection_workspace_bytes(dt, B, L, H, G, n_heads), x.device, workspace)
+    code = _lib.pararnn_input_projection(DTYPES[dt], _ptr(x), _ptr(Wx), _ptr(bias), B, L, H, G, n_heads, _ptr(u),
+                                         _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, "pararnn_input_projection")
+    return u
+
+
+def input_projection_backward(x, Wx, du, n_heads: int = 1, want_dx: bool = True, want_dw: bool = True,
+                              want_dbias: bool = True, workspace=None, stream=None):
+    """pararnn_input_projection_backward.  Returns (dx, dWx, dbias); entries not wanted are None."""
+    B, L, H = x.shape
+    G = Wx.shape[0]
+    dt = x.dtype
+    _check(x, "x", dt, (B, L, H))
+    _check(Wx, "Wx", torch.float32, (G, H, H // n_heads))
+    _check(du, "du", dt, (B, L, G, H))
+    dx = torch.empty_like(x) if want_dx else None
+    dW = torch.empty_like(Wx) if want_dw else None
+    db = torch.empty((G, H), dtype=torch.float32, device=x.device) if want_dbias else None
+    ws = _workspace(input_projection_workspace_bytes(dt, B, L, H, G, n_heads, True), x.device, workspace)
+    code = _lib.pararnn_input_projection_backward(DTYPES[dt], _ptr(x), _ptr(Wx), _ptr(du), B, L, H, G, n_heads,
+                                                  _ptr(dx), _ptr(dW), _ptr(db), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(code, "pararnn_input_projection_backward")
+    return dx, dW, db
 
 
 def affine_scan(J, r, reverse: bool = False, workspace=None, stream=None):

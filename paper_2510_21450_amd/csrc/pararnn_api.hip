@@ -2,6 +2,7 @@
 // cell-generic host driver is driver.h.  No kernel code here.
 #include "dense.h"
 #include "driver.h"
+#include "proj.h"
 
 using namespace pararnn;
 
@@ -243,6 +244,28 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
     }
     if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
     return PARARNN_OK;
+}
+
+size_t pararnn_input_projection_workspace_bytes(int dtype, int B, int L, int H, int G, int n_heads, int backward)
+{
+    return proj_workspace_bytes(dtype, B, L, H, G, n_heads, backward);
+}
+
+int pararnn_input_projection(int dtype, const void *x, const float *Wx, const float *bias, int B, int L, int H,
+                             int G, int n_heads, void *u, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!x || !Wx || !u || !workspace || !aligned(workspace, 256)) return PARARNN_INVALID_ARG;
+    return proj_forward(dtype, x, Wx, bias, B, L, H, G, n_heads, u, workspace, workspace_bytes,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int pararnn_input_projection_backward(int dtype, const void *x, const float *Wx, const void *du, int B, int L,
+                                      int H, int G, int n_heads, void *dx, float *dWx, float *dbias,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!x || !Wx || !du || !workspace || !aligned(workspace, 256) || (dbias && !dWx)) return PARARNN_INVALID_ARG;
+    return proj_backward(dtype, x, Wx, du, B, L, H, G, n_heads, dx, dWx, dbias, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(hip_stream));
 }
 
 int pararnn_dense_chunk(void) { return dense_chunk(); }

@@ -1,0 +1,125 @@
+"""GPU parity of the input projection u = B x + b (Eq. (7a) / (7b) input terms,
+multi-head per App. C) and its derivatives against the CPU oracle.
+
+The kernels round their operands to bf16 and accumulate in fp32.  Against the
+oracle evaluated (in fp64) on the same bf16-rounded operands only the
+accumulation order and the output's storage rounding differ: 1e-5 norm-wise for
+fp32 outputs, 1e-2 (one bf16 rounding of the output) for bf16 storage.  Against
+the oracle on the unrounded operands the difference is the operand rounding:
+2e-2."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads.rng import normal               # noqa: E402
+
+
+def relerr(got, ref):
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def f64(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+def rounded(t):
+    """The value the kernels' bf16 operand rounding gives (round to nearest even)."""
+    return t.to(torch.bfloat16).to(torch.float64).cpu().numpy()
+
+
+# (B, L, H, G, n_heads): dh = 64 .. 512, ragged row tiles, a ragged column tile (dh = 192)
+SHAPES = [(1, 1, 64, 3, 1), (2, 33, 128, 3, 2), (2, 100, 256, 4, 1), (1, 300, 192, 3, 1), (3, 257, 512, 3, 2),
+          (1, 130, 384, 1, 2), (4, 1000, 1024, 3, 4), (2, 700, 512, 3, 1)]
+
+
+def problem(shape, dtype, seed):
+    B, L, H, G, heads = shape
+    dh = H // heads
+    x = normal(seed, 1, (B, L, H), dtype=dtype, device="cuda")
+    Wx = normal(seed, 2, (G, H, dh), std=1.0 / dh ** 0.5, device="cuda")
+    bias = normal(seed, 3, (G, H), std=0.5, device="cuda")
+    du = normal(seed, 4, (B, L, G, H), dtype=dtype, device="cuda")
+    return x, Wx, bias, du
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_input_projection_forward(oracle_mod, shape, dtype):
+    import paper_2510_21450_amd as P
+    print(f"projection forward {shape} {dtype}", flush=True)
+    B, L, H, G, heads = shape
+    x, Wx, bias, _ = problem(shape, dtype, seed=5000 + L + H)
+    u = P.input_projection(x, Wx, bias, n_heads=heads)
+    torch.cuda.synchronize()
+    assert u.shape == (B, L, G, H) and u.dtype == dtype
+    ref_r = oracle_mod.input_projection(rounded(x), rounded(Wx), f64(bias), heads)
+    ref = oracle_mod.input_projection(f64(x), f64(Wx), f64(bias), heads)
+    assert relerr(f64(u), ref_r) <= (1e-5 if dtype == torch.float32 else 1e-2)
+    assert relerr(f64(u), ref) <= 2e-2
+    # without a bias
+    u0 = P.input_projection(x, Wx, None, n_heads=heads)
+    torch.cuda.synchronize()
+    assert relerr(f64(u0), ref_r - f64(bias)) <= (1e-5 if dtype == torch.float32 else 1e-2)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_input_projection_backward(oracle_mod, shape, dtype):
+    import paper_2510_21450_amd as P
+    print(f"projection backward {shape} {dtype}", flush=True)
+    B, L, H, G, heads = shape
+    x, Wx, _, du = problem(shape, dtype, seed=5100 + L + H)
+    dx, dW, db = P.input_projection_backward(x, Wx, du, n_heads=heads)
+    torch.cuda.synchronize()
+    rdx, rdW, _ = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(du), heads)
+    _, _, rdb = oracle_mod.input_projection_backward(f64(x), f64(Wx), f64(du), heads)     # column sums of du as stored
+    out_tol = 1e-5 if dtype == torch.float32 else 1e-2
+    assert relerr(f64(dx), rdx) <= out_tol
+    assert relerr(f64(dW), rdW) <= 1e-5
+    assert relerr(f64(db), rdb) <= 1e-5
+    # bit-reproducible, whatever else runs
+    dx2, dW2, db2 = P.input_projection_backward(x, Wx, du, n_heads=heads)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2) and torch.equal(db, db2) and torch.equal(dx, dx2)
+    # parts of the result only
+    dx3, dW3, db3 = P.input_projection_backward(x, Wx, du, n_heads=heads, want_dx=False, want_dbias=False)
+    torch.cuda.synchronize()
+    assert dx3 is None and db3 is None and torch.equal(dW3, dW)
+
+
+def test_projection_feeds_the_solver(oracle_mod):
+    """x -> u -> Newton solve -> backward -> du -> dx, dWx, dbias: the chain the
+    paper's cell runs, against the oracle's chain on the same rounded operands."""
+    import paper_2510_21450_amd as P
+    B, L, H, G, heads = 2, 400, 256, 3, 4
+    x, Wx, bias, _ = problem((B, L, H, G, heads), torch.float32, seed=5200)
+    params = torch.zeros(2, G, H, device="cuda")
+    params[0] = normal(5200, 7, (G, H), std=0.3, device="cuda").clamp(-0.5, 0.5)
+    g = normal(5200, 8, (B, L, 1, H), device="cuda")
+    u = P.input_projection(x, Wx, bias, n_heads=heads)
+    h, iters, _ = P.forward("gru_diag", params, u, None, tol=1e-5, max_iter=32)
+    du, dp, _ = P.backward("gru_diag", params, u, None, h, g, want_dh0=False)
+    dx, dW, db = P.input_projection_backward(x, Wx, du, n_heads=heads)
+    torch.cuda.synchronize()
+    assert int(iters.cpu()[1]) == 0
+    ru = oracle_mod.input_projection(rounded(x), rounded(Wx), f64(bias), heads)
+    assert relerr(f64(u), ru) <= 1e-5
+    rh = oracle_mod.seq_unroll("gru_diag", f64(params), f64(u), None)
+    assert relerr(f64(h), rh) <= 1e-5
+    rdu, _, _ = oracle_mod.backward("gru_diag", f64(params), f64(u), None, f64(h), f64(g))
+    assert relerr(f64(du), rdu) <= 1e-5
+    rdx, rdW, _ = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(du), heads)
+    _, _, rdb = oracle_mod.input_projection_backward(f64(x), f64(Wx), f64(du), heads)
+    assert relerr(f64(dx), rdx) <= 1e-5 and relerr(f64(dW), rdW) <= 1e-5 and relerr(f64(db), rdb) <= 1e-5
+
+
+def test_projection_refuses_what_it_cannot_do():
+    import paper_2510_21450_amd as P
+    x = torch.zeros(1, 4, 96, device="cuda")
+    with pytest.raises(RuntimeError, match="UNSUPPORTED"):
+        P.input_projection(x, torch.zeros(3, 96, 96, device="cuda"))          # dh = 96 is not a multiple of 64
+    assert P.input_projection_workspace_bytes(torch.float32, 1, 4, 96, 3, 1) == 0
+    assert P.input_projection_workspace_bytes(torch.float32, 1, 4, 128, 3, 3) == 0      # heads must divide H
