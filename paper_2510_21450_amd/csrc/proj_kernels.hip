@@ -50,19 +50,41 @@ __device__ __forceinline__ unsigned int pack2(float x0, float x1)
     return __builtin_bit_cast(unsigned int, p);
 }
 
-// eight consecutive elements as packed bf16
+// eight consecutive elements as fetched, and as packed bf16
+struct Raw8f {
+    f4v lo, hi;
+};
 __device__ __forceinline__ u4v load8(const unsigned short *p) { return *reinterpret_cast<const u4v *>(p); }
-__device__ __forceinline__ u4v load8(const float *p)
+__device__ __forceinline__ Raw8f load8(const float *p)
 {
-    const f4v a = *reinterpret_cast<const f4v *>(p), b = *reinterpret_cast<const f4v *>(p + 4);
-    const u4v r = {pack2(a[0], a[1]), pack2(a[2], a[3]), pack2(b[0], b[1]), pack2(b[2], b[3])};
+    Raw8f r;
+    r.lo = *reinterpret_cast<const f4v *>(p);
+    r.hi = *reinterpret_cast<const f4v *>(p + 4);
     return r;
 }
+__device__ __forceinline__ u4v to_bf16x8(const u4v &v) { return v; }
+__device__ __forceinline__ u4v to_bf16x8(const Raw8f &v)
+{
+    const u4v r = {pack2(v.lo[0], v.lo[1]), pack2(v.lo[2], v.lo[3]), pack2(v.hi[0], v.hi[1]), pack2(v.hi[2], v.hi[3])};
+    return r;
+}
+template <typename AT> struct Raw8 { typedef u4v type; };
+template <> struct Raw8<float> { typedef Raw8f type; };
 
-__device__ __forceinline__ void store1(float *p, float v) { *p = v; }
-__device__ __forceinline__ void store1(unsigned short *p, float v) { *p = f32_to_bf16(v); }
+// four consecutive outputs in the storage type
+__device__ __forceinline__ void store4(float *p, const f4v &v) { *reinterpret_cast<f4v *>(p) = v; }
+__device__ __forceinline__ void store4(unsigned short *p, const f4v &v)
+{
+    *reinterpret_cast<uint2 *>(p) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+}
 
 __device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+// Element offset of 16-byte chunk `chunk` (0..7) of row `row` in an LDS operand tile.  The
+// pitch of 144 bytes spreads the fragment reads of 16 consecutive rows over all banks; the
+// XOR with the row's 16-row group does the same for the transposing stores of the dWx
+// kernel (lanes four rows apart) and leaves those reads as they are.
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * PITCH + 8 * (chunk ^ ((row >> 4) & 7)); }
 
 // one 64-k step of a 64 x 64 wave tile from the LDS operand tiles
 __device__ __forceinline__ void mma_step(const unsigned short *sa, const unsigned short *sb, int wm, int wn, int l32,
@@ -73,14 +95,64 @@ __device__ __forceinline__ void mma_step(const unsigned short *sa, const unsigne
         bf8v fa[2], fb[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            fa[i] = *reinterpret_cast<const bf8v *>(sa + (64 * wm + 32 * i + l32) * PITCH + 16 * kb + 8 * half);
-            fb[i] = *reinterpret_cast<const bf8v *>(sb + (64 * wn + 32 * i + l32) * PITCH + 16 * kb + 8 * half);
+            fa[i] = *reinterpret_cast<const bf8v *>(sa + lds_off(64 * wm + 32 * i + l32, 2 * kb + half));
+            fb[i] = *reinterpret_cast<const bf8v *>(sb + lds_off(64 * wn + 32 * i + l32, 2 * kb + half));
         }
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+    }
+}
+
+// The step loop of both products.  Step t is multiplied from LDS buffer t % 2 while the
+// global loads of steps t+1 and t+2 are outstanding in two register sets (memory latency
+// is several times the duration of a step).  load(set) fetches the next step in stream
+// order, store(buf, set) puts a fetched step into an LDS buffer, compute(buf) multiplies.
+// Loads and stores are issued unconditionally, also past the end of the stream (load()
+// then has to deliver something harmless, which is stored and never multiplied): with
+// no branch around them the compiler can wait for exactly the older register set while
+// the younger loads stay in flight.  For the same reason load() must not touch what it
+// fetched: conversion, zeroing of rows past the end and transposition happen in store().
+// Every thread of the workgroup runs the same number of steps: the barriers are uniform.
+template <class Stage, class Load, class Store, class Compute>
+__device__ __forceinline__ void two_ahead(int n_steps, Load load, Store store, Compute compute)
+{
+    Stage r0, r1;
+    load(r0);
+    load(r1);
+    store(0, r0);
+    __syncthreads();
+    for (int t = 0; t < n_steps; t += 2) {
+        // step t from buffer 0; set 0 is free, set 1 holds step t+1
+        load(r0);
+        compute(0);
+        store(1, r1);
+        __syncthreads();
+        if (t + 1 >= n_steps) break;
+        // step t+1 from buffer 1; set 1 is free, set 0 holds step t+2
+        load(r1);
+        compute(1);
+        store(0, r0);
+        __syncthreads();
+    }
+}
+
+// The same with one register set: the loads of step t+1 are outstanding while step t is
+// multiplied.  For stages too large to hold twice (fp32 rows before their transposition).
+template <class Stage, class Load, class Store, class Compute>
+__device__ __forceinline__ void one_ahead(int n_steps, Load load, Store store, Compute compute)
+{
+    Stage r;
+    load(r);
+    store(0, r);
+    __syncthreads();
+    for (int t = 0; t < n_steps; ++t) {
+        load(r);
+        compute(t & 1);
+        store((t + 1) & 1, r);
+        __syncthreads();
     }
 }
 
@@ -96,85 +168,166 @@ struct GemmArgs {
     long long kseg_stride;
     int nz0, n_batch;              // batch index z = z1 * nz0 + z0
     long long a_off[2], b_off[2], c_off[2];     // element offsets per unit of z0, z1
-    int tiles_m, tiles_n, per_xcd;
+    int tiles_m, tiles_n;
 };
 
-// Workgroups are dealt to the eight XCDs round-robin by the dispatcher; renumbering
-// them so that each XCD works through a contiguous range of tiles keeps the tiles
-// that share a row block of A (all n tiles, gates and heads of it) on one L2.
-template <typename AT, typename CT>
+// Persistent workgroups, each walking a list of output tiles; the (tile, k-step) pairs
+// of that list form one flat stream of steps, so that the loads of a tile's first steps
+// are in flight while the previous tile is still being multiplied.  Step t is multiplied
+// from LDS buffer t % 2 while the global loads of steps t+1 and t+2 are outstanding in two
+// register sets (memory latency is several times the duration of a step).
+//
+// Workgroups are dealt to the eight XCDs round-robin by the dispatcher; tile numbers are
+// assigned so that each XCD works through a contiguous range, neighbours in time being
+// the tiles that share a row block of A (all n tiles, gates and heads of it): they meet
+// in one L2.
+template <typename AT, typename CT, bool BIAS>
 __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
     __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
-    const long long id = (long long)(blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int inner_n = a.tiles_n * a.n_batch;
-    if (id >= (long long)a.tiles_m * inner_n) return;
-    const int mt = (int)(id / inner_n), inner = (int)(id % inner_n);
-    const int nt = inner % a.tiles_n, z = inner / a.tiles_n;
-    const int z0 = z % a.nz0, z1 = z / a.nz0;
-    const AT *A = static_cast<const AT *>(a.A) + z0 * a.a_off[0] + z1 * a.a_off[1];
-    const unsigned short *Bw = a.Bw + z0 * a.b_off[0] + z1 * a.b_off[1];
-    const long long coff = z0 * a.c_off[0] + z1 * a.c_off[1];
-    const int m0 = mt * BM, n0 = nt * BN;
+    // This XCD owns the row blocks [xcd * mx, (xcd + 1) * mx).  Its (row block, inner) grid is
+    // cut into patches of 8 x 8 tiles, numbered one after the other, and the workgroup takes the
+    // numbers slot, slot + slots, ...: the 64 workgroups of an XCD are then inside one patch at
+    // a time and its 8 + 8 operand panels stay in that XCD's L2.
+    const int mx = (a.tiles_m + 7) / 8;
+    const int n_pn = (inner_n + 7) / 8, n_pm = (mx + 7) / 8;
+    const int n_local = n_pm * n_pn * 64;
+    auto decode = [&](int local, int &mt, int &inner) {
+        const int patch = local >> 6, within = local & 63;
+        mt = xcd * mx + 8 * (patch / n_pn) + (within >> 3);
+        inner = 8 * (patch % n_pn) + (within & 7);
+        return mt < a.tiles_m && mt < (xcd + 1) * mx && inner < inner_n;
+    };
+    // first valid tile number at or after `local` on this workgroup's list, n_local if none
+    auto next_valid = [&](int local) {
+        int mt, inner;
+        while (local < n_local && !decode(local, mt, inner)) local += slots;
+        return local;
+    };
+    int n_my = 0;
+    for (int l = next_valid(slot); l < n_local; l = next_valid(l + slots)) ++n_my;
+    if (n_my == 0) return;
+    const int nk = a.K / BK;
+    const int n_steps = n_my * nk;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
     const int half = lane >> 5, l32 = lane & 31;
 
+    struct Tile {
+        const AT *A;
+        const unsigned short *Bw;
+        long long coff;
+        int m0, n0;
+        int local;
+    };
+    auto tile_of = [&](int local) {
+        int mt, inner;
+        decode(local, mt, inner);
+        const int nt = inner % a.tiles_n, z = inner / a.tiles_n;
+        const int z0 = z % a.nz0, z1 = z / a.nz0;
+        Tile t;
+        t.A = static_cast<const AT *>(a.A) + z0 * a.a_off[0] + z1 * a.a_off[1];
+        t.Bw = a.Bw + z0 * a.b_off[0] + z1 * a.b_off[1];
+        t.coff = z0 * a.c_off[0] + z1 * a.c_off[1];
+        t.m0 = mt * BM; t.n0 = nt * BN;
+        t.local = local;
+        return t;
+    };
     // a thread stages four 16-byte pieces of each operand tile per step: piece q = tid + 256 i
-    // is k-chunk q % 8 of tile row q / 8
-    u4v ra[4], rb[4];
+    // is k-chunk q % 8 of the tile row below: eight lanes cover one row, and the two rows of
+    // sixteen consecutive lanes are eight apart, which the 144-byte pitch turns into the two
+    // halves of the banks
+    auto piece_row = [](int q) { return ((q >> 4) & 7) + 8 * ((q >> 3) & 1) + 16 * (q >> 7); };
     const u4v zero4 = {0u, 0u, 0u, 0u};
-    auto load_stage = [&](int k0) {
+    Tile lt = tile_of(next_valid(slot));     // tile of the next step to load
+    int lj = 0, lks = 0;
+    struct Stage {
+        typename Raw8<AT>::type a[4];
+        u4v b[4];
+        unsigned int valid;            // bit i: row of a[i] exists, bit 4 + i: row of b[i] exists
+    };
+    auto load_next = [&](Stage &r) {
+        const int k0 = lks * BK;
         const long long kbase = (long long)(k0 / a.kseg) * a.kseg_stride + k0 % a.kseg;
+        r.valid = 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int q = tid + 256 * i, row = q >> 3, c = q & 7;
-            const int gm = m0 + row, gn = n0 + row;
-            ra[i] = gm < a.M ? load8(A + (long long)gm * a.lda + kbase + 8 * c) : zero4;
-            rb[i] = gn < a.N ? load8(Bw + (long long)gn * a.ldb + k0 + 8 * c) : zero4;
+            const int q = tid + 256 * i, row = piece_row(q), c = q & 7;
+            // rows past the end read the last row (valid memory) and are stored as zeros
+            const int gm = lt.m0 + row, gn = lt.n0 + row;
+            r.a[i] = load8(lt.A + (long long)min(gm, a.M - 1) * a.lda + kbase + 8 * c);
+            r.b[i] = load8(lt.Bw + (long long)min(gn, a.N - 1) * a.ldb + k0 + 8 * c);
+            r.valid |= (gm < a.M ? 1u : 0u) << i | (gn < a.N ? 16u : 0u) << i;
+        }
+        // past the end of the stream the last step is fetched again
+        if (lks + 1 < nk) {
+            ++lks;
+        } else if (lj + 1 < n_my) {
+            lks = 0;
+            ++lj;
+            lt = tile_of(next_valid(lt.local + slots));
         }
     };
-    auto store_stage = [&](int buf) {
+    auto store_stage = [&](int buf, const Stage &r) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int q = tid + 256 * i, row = q >> 3, c = q & 7;
-            *reinterpret_cast<u4v *>(&s_a[buf][row * PITCH + 8 * c]) = ra[i];
-            *reinterpret_cast<u4v *>(&s_b[buf][row * PITCH + 8 * c]) = rb[i];
+            const int q = tid + 256 * i, row = piece_row(q), c = q & 7;
+            *reinterpret_cast<u4v *>(&s_a[buf][lds_off(row, c)]) = (r.valid >> i & 1u) ? to_bf16x8(r.a[i]) : zero4;
+            *reinterpret_cast<u4v *>(&s_b[buf][lds_off(row, c)]) = (r.valid >> (4 + i) & 1u) ? r.b[i] : zero4;
         }
     };
     f16v acc[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
-
-    const int nk = a.K / BK;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-    for (int s = 0; s < nk; ++s) {
-        if (s + 1 < nk) load_stage((s + 1) * BK);
-        mma_step(s_a[s & 1], s_b[s & 1], wm, wn, l32, half, acc);
-        if (s + 1 < nk) store_stage((s + 1) & 1);
-        __syncthreads();
-    }
-    // epilogue: bias, storage type, the caller's layout; a lane owns one column
-    CT *C = static_cast<CT *>(a.C) + coff;
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int col = n0 + 64 * wn + 32 * ni + l32;
-        if (col >= a.N) continue;
-        const float bv = a.bias ? a.bias[coff + col] : 0.0f;
+    auto clear_acc = [&]() {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + 64 * wm + 32 * mi + acc_row(v, half);
-                if (row < a.M) store1(C + (long long)row * a.ldc + col, acc[mi][ni][v] + bv);
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+    };
+    // The product is formed transposed, acc[ni][mi] = (W tile)(A tile)^T: a lane then owns one
+    // ROW of C and, per group of four accumulator registers, four consecutive columns, so the
+    // epilogue (bias, storage type, the caller's layout) stores 8 or 16 bytes per lane.
+    Tile ct = lt;                      // tile being multiplied
+    int cj = 0, cks = 0;
+    auto finish_step = [&]() {
+        if (++cks < nk) return;
+        CT *C = static_cast<CT *>(a.C) + ct.coff;
+        // this lane's columns: col(ni, q) .. + 3 (N is a multiple of 4); one group of 32 columns at a time
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            f4v bv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = ct.n0 + 64 * wn + 32 * ni + 8 * q + 4 * half;
+                if (BIAS) bv[q] = *reinterpret_cast<const f4v *>(a.bias + ct.coff + min(col, a.N - 4));
             }
-    }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const int row = ct.m0 + 64 * wm + 32 * mi + l32;
+                if (row >= a.M) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = ct.n0 + 64 * wn + 32 * ni + 8 * q + 4 * half;
+                    if (col >= a.N) continue;
+                    f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+                    if (BIAS) o += bv[q];
+                    store4(C + (long long)row * a.ldc + col, o);
+                }
+            }
+        }
+        clear_acc();
+        cks = 0;
+        if (++cj < n_my) ct = tile_of(next_valid(ct.local + slots));
+    };
+    clear_acc();
+
+    two_ahead<Stage>(n_steps, load_next, store_stage, [&](int buf) {
+        mma_step(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
+        finish_step();
+    });
 }
 
 // --------------------------------------------------- dWx and dbias (TN product)
@@ -188,56 +341,75 @@ struct DwArgs {
     int tiles;             // 128-wide tiles per dh
 };
 
-// two adjacent channels of eight consecutive rows -> one 16-byte k-run per channel
-template <typename AT> struct PairLoad;
-template <> struct PairLoad<unsigned short> {
-    __device__ __forceinline__ static void run(const unsigned short *p, long long ld, int m, int m_end, bool ok,
-                                               u4v &c0, u4v &c1, float &s0, float &s1)
+// Four adjacent channels of eight consecutive rows as fetched; transposed in registers into
+// one 16-byte k-run per channel (rows that do not count become zeros), plus column sums.
+template <typename AT> struct QuadRows;
+template <> struct QuadRows<unsigned short> {
+    uint2 v[8];
+    int n_valid;
+    __device__ __forceinline__ void load(const unsigned short *p, long long ld, int m, int m_last, int n_valid_)
     {
-        unsigned int v[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-            v[r] = (ok && m + r < m_end) ? *reinterpret_cast<const unsigned int *>(p + (long long)(m + r) * ld) : 0u;
+        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const uint2 *>(p + (long long)min(m + r, m_last) * ld);
+        n_valid = n_valid_;
+    }
+    __device__ __forceinline__ void transpose(u4v (&c)[4], float (&s)[4]) const
+    {
+        uint2 t[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t[r] = r < n_valid ? v[r] : make_uint2(0u, 0u);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            c0[k] = (v[2 * k] & 0xffffu) | (v[2 * k + 1] << 16);
-            c1[k] = (v[2 * k] >> 16) | (v[2 * k + 1] & 0xffff0000u);
+            c[0][k] = (t[2 * k].x & 0xffffu) | (t[2 * k + 1].x << 16);
+            c[1][k] = (t[2 * k].x >> 16) | (t[2 * k + 1].x & 0xffff0000u);
+            c[2][k] = (t[2 * k].y & 0xffffu) | (t[2 * k + 1].y << 16);
+            c[3][k] = (t[2 * k].y >> 16) | (t[2 * k + 1].y & 0xffff0000u);
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            s0 += __builtin_bit_cast(float, v[r] << 16);
-            s1 += __builtin_bit_cast(float, v[r] & 0xffff0000u);
+            s[0] += __builtin_bit_cast(float, t[r].x << 16);
+            s[1] += __builtin_bit_cast(float, t[r].x & 0xffff0000u);
+            s[2] += __builtin_bit_cast(float, t[r].y << 16);
+            s[3] += __builtin_bit_cast(float, t[r].y & 0xffff0000u);
         }
     }
 };
-template <> struct PairLoad<float> {
-    __device__ __forceinline__ static void run(const float *p, long long ld, int m, int m_end, bool ok, u4v &c0,
-                                               u4v &c1, float &s0, float &s1)
+template <> struct QuadRows<float> {
+    f4v v[8];
+    int n_valid;
+    __device__ __forceinline__ void load(const float *p, long long ld, int m, int m_last, int n_valid_)
     {
-        f2v v[8];
-        const f2v zero2 = {0.0f, 0.0f};
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f4v *>(p + (long long)min(m + r, m_last) * ld);
+        n_valid = n_valid_;
+    }
+    __device__ __forceinline__ void transpose(u4v (&c)[4], float (&s)[4]) const
+    {
+        const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        f4v t[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t[r] = r < n_valid ? v[r] : zero;
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) c[ch][k] = pack2(t[2 * k][ch], t[2 * k + 1][ch]);
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-            v[r] = (ok && m + r < m_end) ? *reinterpret_cast<const f2v *>(p + (long long)(m + r) * ld) : zero2;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            c0[k] = pack2(v[2 * k][0], v[2 * k + 1][0]);
-            c1[k] = pack2(v[2 * k][1], v[2 * k + 1][1]);
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) { s0 += v[r][0]; s1 += v[r][1]; }
+            for (int ch = 0; ch < 4; ++ch) s[ch] += t[r][ch];
     }
 };
 
 // One workgroup: a 128 x 128 tile of dWx[g][head] for one row range.  Tile rows are
 // the output channels i (operand du), tile columns the input channels j (operand x);
-// k runs over the rows m of the range.
+// k runs over the rows m of the range, 64 per step.  A thread stages channels
+// 4 c4 .. 4 c4 + 3 of rows 8 rg .. 8 rg + 7 of the step for both operands.
 template <typename AT>
 __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
     __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
-    __shared__ float s_db[4][BM];
+    __shared__ float s_db[8][BM];
     int id = blockIdx.x;
     const int tj = id % a.tiles; id /= a.tiles;
     const int ti = id % a.tiles; id /= a.tiles;
@@ -248,32 +420,37 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
     const int m_begin = s * a.rows_per_split;
     const int m_end = min(a.M, m_begin + a.rows_per_split);
     const long long ld_du = (long long)a.G * a.H, ld_x = a.H;
-    const AT *du = static_cast<const AT *>(a.du) + (long long)g * a.H + head * a.dh + i0;
-    const AT *x = static_cast<const AT *>(a.x) + head * a.dh + j0;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
     const int half = lane >> 5, l32 = lane & 31;
-    // staging item (channel pair p, row group mg + 4 i): rows 8 (mg + 4 i) .. +7 of the 64-row step
-    const int p = tid & 63, mg = tid >> 6;
-    const bool ok_a = i0 + 2 * p < a.dh, ok_b = j0 + 2 * p < a.dh;     // dh is even: a pair is valid or not as a whole
+    const int c4 = tid & 31, rg = tid >> 5;
+    // dh is a multiple of 64: a quad of channels is valid or not as a whole; an invalid one reads
+    // the tile's first quad (valid memory) and counts as zeros
+    const bool ok_a = i0 + 4 * c4 < a.dh, ok_b = j0 + 4 * c4 < a.dh;
+    const AT *du = static_cast<const AT *>(a.du) + (long long)g * a.H + head * a.dh + i0 + (ok_a ? 4 * c4 : 0);
+    const AT *x = static_cast<const AT *>(a.x) + head * a.dh + j0 + (ok_b ? 4 * c4 : 0);
 
-    u4v ra[2][2], rb[2][2];
-    float sdb0 = 0.0f, sdb1 = 0.0f, unused0 = 0.0f, unused1 = 0.0f;
-    auto load_stage = [&](int m0) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int m = m0 + 8 * (mg + 4 * i);
-            PairLoad<AT>::run(du + 2 * p, ld_du, m, m_end, ok_a, ra[i][0], ra[i][1], sdb0, sdb1);
-            PairLoad<AT>::run(x + 2 * p, ld_x, m, m_end, ok_b, rb[i][0], rb[i][1], unused0, unused1);
-        }
+    float sdb[4] = {0.0f, 0.0f, 0.0f, 0.0f}, unused[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    struct Stage {
+        QuadRows<AT> a, b;
     };
-    auto store_stage = [&](int buf) {
+    int m_next = m_begin;
+    auto load_next = [&](Stage &r) {
+        // past the end of the range the last step is fetched again and counts as zeros
+        const bool real = m_next < m_end;
+        const int m = (real ? m_next : m_next - BK) + 8 * rg;
+        const int n_valid = real ? m_end - m : 0;      // rows of this thread's group that count
+        r.a.load(du, ld_du, m, a.M - 1, ok_a ? n_valid : 0);
+        r.b.load(x, ld_x, m, a.M - 1, ok_b ? n_valid : 0);
+        if (real) m_next += BK;
+    };
+    auto store_stage = [&](int buf, const Stage &r) {
+        u4v ca[4], cb[4];
+        r.a.transpose(ca, sdb);
+        r.b.transpose(cb, unused);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int k = 8 * (mg + 4 * i);
-            *reinterpret_cast<u4v *>(&s_a[buf][(2 * p) * PITCH + k]) = ra[i][0];
-            *reinterpret_cast<u4v *>(&s_a[buf][(2 * p + 1) * PITCH + k]) = ra[i][1];
-            *reinterpret_cast<u4v *>(&s_b[buf][(2 * p) * PITCH + k]) = rb[i][0];
-            *reinterpret_cast<u4v *>(&s_b[buf][(2 * p + 1) * PITCH + k]) = rb[i][1];
+        for (int ch = 0; ch < 4; ++ch) {
+            *reinterpret_cast<u4v *>(&s_a[buf][lds_off(4 * c4 + ch, rg)]) = ca[ch];
+            *reinterpret_cast<u4v *>(&s_b[buf][lds_off(4 * c4 + ch, rg)]) = cb[ch];
         }
     };
     f16v acc[2][2];
@@ -285,16 +462,10 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     const int nk = m_end > m_begin ? (m_end - m_begin + BK - 1) / BK : 0;
+    auto compute = [&](int buf) { mma_step(s_a[buf], s_b[buf], wm, wn, l32, half, acc); };
     if (nk > 0) {
-        load_stage(m_begin);
-        store_stage(0);
-    }
-    __syncthreads();
-    for (int st = 0; st < nk; ++st) {
-        if (st + 1 < nk) load_stage(m_begin + (st + 1) * BK);
-        mma_step(s_a[st & 1], s_b[st & 1], wm, wn, l32, half, acc);
-        if (st + 1 < nk) store_stage((st + 1) & 1);
-        __syncthreads();
+        if constexpr (sizeof(AT) == 4) one_ahead<Stage>(nk, load_next, store_stage, compute);
+        else two_ahead<Stage>(nk, load_next, store_stage, compute);
     }
     float *out = a.part + (((long long)s * a.G + g) * a.H + head * a.dh + i0) * a.dh + j0;
 #pragma unroll
@@ -311,12 +482,15 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
     }
     // column sums of du seen by this workgroup (the tj = 0 tiles cover every channel once)
     if (a.dbpart && tj == 0) {
-        s_db[mg][2 * p] = sdb0;
-        s_db[mg][2 * p + 1] = sdb1;
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch) s_db[rg][4 * c4 + ch] = sdb[ch];
         __syncthreads();
-        if (tid < BM && i0 + tid < a.dh)
-            a.dbpart[((long long)s * a.G + g) * a.H + head * a.dh + i0 + tid] =
-                (s_db[0][tid] + s_db[1][tid]) + (s_db[2][tid] + s_db[3][tid]);
+        if (tid < BM && i0 + tid < a.dh) {
+            float t = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t += s_db[q][tid];
+            a.dbpart[((long long)s * a.G + g) * a.H + head * a.dh + i0 + tid] = t;
+        }
     }
 }
 
@@ -392,9 +566,12 @@ template <typename AT, typename CT> hipError_t launch_nt(GemmArgs &g, hipStream_
 {
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
-    const long long total = (long long)g.tiles_m * g.tiles_n * g.n_batch;
-    g.per_xcd = (int)((total + 7) / 8);
-    hipLaunchKernelGGL((proj_gemm_nt_kernel<AT, CT>), dim3((unsigned)(8 * g.per_xcd)), dim3(256), 0, st, g);
+    // two workgroups per compute unit (their LDS and registers allow no more), the same number on every XCD
+    int slots = 2 * device_cu_count() / 8;
+    if (slots < 1) slots = 1;
+    if (slots > 64) slots = 64;                      // a patch of tiles has 64 members
+    if (g.bias) hipLaunchKernelGGL((proj_gemm_nt_kernel<AT, CT, true>), dim3((unsigned)(8 * slots)), dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((proj_gemm_nt_kernel<AT, CT, false>), dim3((unsigned)(8 * slots)), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
