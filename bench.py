@@ -218,6 +218,32 @@ def main():
                        "bwd_gbs": ab["bwd"] * N / (sum(t_bwd) / len(t_bwd) * 1e-3) / 1e9})
         detail["bwd_frac_hbm"] = detail["bwd_gbs"] / HBM_PEAK_GBS
 
+    if w.cell != "tanh_dense" and w.H % 256 == 0:
+        # not part of the timed step: the input projection u = Bx + b in front of the solve and its
+        # derivatives behind the backward pass, four heads (the paper's 400M .. 7B models), same shapes
+        G = u.shape[2]
+        heads = 4
+        dh = w.H // heads
+        xin = torch.randn((w.B, w.L, w.H), device="cuda").to(u.dtype)
+        Wx = torch.randn((G, w.H, dh), device="cuda") / dh ** 0.5
+        bx = torch.randn((G, w.H), device="cuda")
+        ws_p = torch.empty(P.input_projection_workspace_bytes(u.dtype, w.B, w.L, w.H, G, heads, True),
+                           dtype=torch.uint8, device="cuda")
+        u_p = torch.empty_like(u)
+        pf = lambda: P.input_projection(xin, Wx, bx, n_heads=heads, workspace=ws_p, out=u_p)
+        pb = lambda: P.input_projection_backward(xin, Wx, u_p, n_heads=heads, workspace=ws_p)
+        pf(); pb()
+        t_pf, t_pb = time_events(pf, 5), time_events(pb, 5)
+        t_pf, t_pb = sum(t_pf) / len(t_pf), sum(t_pb) / len(t_pb)
+        es = u.element_size()
+        flops = 2.0 * N * G * dh
+        detail["input_projection"] = {
+            "n_heads": heads, "arithmetic": "bf16 operands, fp32 accumulation",
+            "fwd_ms": t_pf, "fwd_tflops": flops / (t_pf * 1e-3) / 1e12,
+            "fwd_gbs": (N + N * G) * es / (t_pf * 1e-3) / 1e9,
+            "bwd_ms": t_pb, "bwd_tflops": 2 * flops / (t_pb * 1e-3) / 1e12,
+            "bwd_gbs": (2 * N + 2 * N * G) * es / (t_pb * 1e-3) / 1e9}
+        del xin, u_p, ws_p
     note("per-kernel timings done")
     # a plain copy of known size, as the reference for hardware byte counters
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

@@ -115,44 +115,48 @@ __device__ __forceinline__ void mma_step(const unsigned short *sa, const unsigne
 // no branch around them the compiler can wait for exactly the older register set while
 // the younger loads stay in flight.  For the same reason load() must not touch what it
 // fetched: conversion, zeroing of rows past the end and transposition happen in store().
-// Every thread of the workgroup runs the same number of steps: the barriers are uniform.
-template <class Stage, class Load, class Store, class Compute>
-__device__ __forceinline__ void two_ahead(int n_steps, Load load, Store store, Compute compute)
+// done() is asked after every step and must give every thread the same answer: the
+// barriers are uniform.
+template <class Stage, class Load, class Store, class Compute, class Done>
+__device__ __forceinline__ void two_ahead(Load load, Store store, Compute compute, Done done)
 {
     Stage r0, r1;
     load(r0);
+    __syncthreads();          // load() may publish something through LDS for the next load()
     load(r1);
     store(0, r0);
     __syncthreads();
-    for (int t = 0; t < n_steps; t += 2) {
-        // step t from buffer 0; set 0 is free, set 1 holds step t+1
+    for (;;) {
+        // a step from buffer 0; set 0 is free, set 1 holds the next step
         load(r0);
         compute(0);
         store(1, r1);
         __syncthreads();
-        if (t + 1 >= n_steps) break;
-        // step t+1 from buffer 1; set 1 is free, set 0 holds step t+2
+        if (done()) break;
+        // a step from buffer 1; set 1 is free, set 0 holds the next step
         load(r1);
         compute(1);
         store(0, r0);
         __syncthreads();
+        if (done()) break;
     }
 }
 
 // The same with one register set: the loads of step t+1 are outstanding while step t is
 // multiplied.  For stages too large to hold twice (fp32 rows before their transposition).
-template <class Stage, class Load, class Store, class Compute>
-__device__ __forceinline__ void one_ahead(int n_steps, Load load, Store store, Compute compute)
+template <class Stage, class Load, class Store, class Compute, class Done>
+__device__ __forceinline__ void one_ahead(Load load, Store store, Compute compute, Done done)
 {
     Stage r;
     load(r);
     store(0, r);
     __syncthreads();
-    for (int t = 0; t < n_steps; ++t) {
+    for (int t = 0;; ++t) {
         load(r);
         compute(t & 1);
         store((t + 1) & 1, r);
         __syncthreads();
+        if (done()) break;
     }
 }
 
@@ -169,6 +173,7 @@ struct GemmArgs {
     int nz0, n_batch;              // batch index z = z1 * nz0 + z0
     long long a_off[2], b_off[2], c_off[2];     // element offsets per unit of z0, z1
     int tiles_m, tiles_n;
+    int *tickets;                  // eight counters, zero at launch: the next tile number of each XCD
 };
 
 // Persistent workgroups, each walking a list of output tiles; the (tile, k-step) pairs
@@ -186,12 +191,13 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
     __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    __shared__ int s_ring[8];
+    const int xcd = blockIdx.x & 7;
     const int inner_n = a.tiles_n * a.n_batch;
     // This XCD owns the row blocks [xcd * mx, (xcd + 1) * mx).  Its (row block, inner) grid is
-    // cut into patches of 8 x 8 tiles, numbered one after the other, and the workgroup takes the
-    // numbers slot, slot + slots, ...: the 64 workgroups of an XCD are then inside one patch at
-    // a time and its 8 + 8 operand panels stay in that XCD's L2.
+    // cut into patches of 8 x 8 tiles, numbered one after the other, and its workgroups draw
+    // numbers from a counter: whatever their relative speed they are inside one or two
+    // neighbouring patches at any time, whose 8 + 8 operand panels stay in that XCD's L2.
     const int mx = (a.tiles_m + 7) / 8;
     const int n_pn = (inner_n + 7) / 8, n_pm = (mx + 7) / 8;
     const int n_local = n_pm * n_pn * 64;
@@ -201,26 +207,29 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         inner = 8 * (patch % n_pn) + (within & 7);
         return mt < a.tiles_m && mt < (xcd + 1) * mx && inner < inner_n;
     };
-    // first valid tile number at or after `local` on this workgroup's list, n_local if none
-    auto next_valid = [&](int local) {
-        int mt, inner;
-        while (local < n_local && !decode(local, mt, inner)) local += slots;
-        return local;
-    };
-    int n_my = 0;
-    for (int l = next_valid(slot); l < n_local; l = next_valid(l + slots)) ++n_my;
-    if (n_my == 0) return;
     const int nk = a.K / BK;
-    const int n_steps = n_my * nk;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
     const int half = lane >> 5, l32 = lane & 31;
+    // Thread 0 draws the number of this workgroup's n-th tile (the next one that exists, or
+    // n_local when the XCD's list is used up) and leaves it in s_ring[n % 8]; everybody reads
+    // it after a later barrier.  At most three tiles are drawn ahead of the one being multiplied.
+    auto draw = [&](int n) {
+        if (tid != 0) return;
+        int t, mt, inner;
+        do {
+            t = atomicAdd(a.tickets + xcd, 1);
+        } while (t < n_local && !decode(t, mt, inner));
+        s_ring[n & 7] = t < n_local ? t : n_local;
+    };
+    draw(0);
+    __syncthreads();
+    if (s_ring[0] >= n_local) return;
 
     struct Tile {
         const AT *A;
         const unsigned short *Bw;
         long long coff;
         int m0, n0;
-        int local;
     };
     auto tile_of = [&](int local) {
         int mt, inner;
@@ -232,7 +241,6 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         t.Bw = a.Bw + z0 * a.b_off[0] + z1 * a.b_off[1];
         t.coff = z0 * a.c_off[0] + z1 * a.c_off[1];
         t.m0 = mt * BM; t.n0 = nt * BN;
-        t.local = local;
         return t;
     };
     // a thread stages four 16-byte pieces of each operand tile per step: piece q = tid + 256 i
@@ -241,14 +249,28 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     // halves of the banks
     auto piece_row = [](int q) { return ((q >> 4) & 7) + 8 * ((q >> 3) & 1) + 16 * (q >> 7); };
     const u4v zero4 = {0u, 0u, 0u, 0u};
-    Tile lt = tile_of(next_valid(slot));     // tile of the next step to load
-    int lj = 0, lks = 0;
+    // the loading side: tile number ln of this workgroup, k-step lks of it; l_switch: the tile
+    // is finished and the next load starts the tile drawn meanwhile; l_end: there was none
+    Tile lt = tile_of(s_ring[0]);
+    int ln = 0, lks = 0;
+    bool l_switch = false, l_end = false;
     struct Stage {
         typename Raw8<AT>::type a[4];
         u4v b[4];
         unsigned int valid;            // bit i: row of a[i] exists, bit 4 + i: row of b[i] exists
     };
     auto load_next = [&](Stage &r) {
+        if (l_switch) {
+            const int t = s_ring[(ln + 1) & 7];
+            if (t >= n_local) {
+                l_end = true;              // from here on the last step is fetched again (never multiplied)
+            } else {
+                lt = tile_of(t);
+                ++ln;
+                lks = 0;
+            }
+            l_switch = false;
+        }
         const int k0 = lks * BK;
         const long long kbase = (long long)(k0 / a.kseg) * a.kseg_stride + k0 % a.kseg;
         r.valid = 0u;
@@ -261,13 +283,13 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
             r.b[i] = load8(lt.Bw + (long long)min(gn, a.N - 1) * a.ldb + k0 + 8 * c);
             r.valid |= (gm < a.M ? 1u : 0u) << i | (gn < a.N ? 16u : 0u) << i;
         }
-        // past the end of the stream the last step is fetched again
-        if (lks + 1 < nk) {
-            ++lks;
-        } else if (lj + 1 < n_my) {
-            lks = 0;
-            ++lj;
-            lt = tile_of(next_valid(lt.local + slots));
+        if (!l_end) {
+            if (lks + 1 < nk) {
+                ++lks;
+            } else {
+                draw(ln + 1);
+                l_switch = true;
+            }
         }
     };
     auto store_stage = [&](int buf, const Stage &r) {
@@ -290,8 +312,9 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     // The product is formed transposed, acc[ni][mi] = (W tile)(A tile)^T: a lane then owns one
     // ROW of C and, per group of four accumulator registers, four consecutive columns, so the
     // epilogue (bias, storage type, the caller's layout) stores 8 or 16 bytes per lane.
-    Tile ct = lt;                      // tile being multiplied
-    int cj = 0, cks = 0;
+    Tile ct = lt;                      // tile being multiplied: number cn of this workgroup
+    int cn = 0, cks = 0;
+    bool c_end = false;
     auto finish_step = [&]() {
         if (++cks < nk) return;
         CT *C = static_cast<CT *>(a.C) + ct.coff;
@@ -320,14 +343,18 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         }
         clear_acc();
         cks = 0;
-        if (++cj < n_my) ct = tile_of(next_valid(ct.local + slots));
+        const int t = s_ring[++cn & 7];     // drawn at least one barrier ago
+        if (t >= n_local) c_end = true;
+        else ct = tile_of(t);
     };
     clear_acc();
 
-    two_ahead<Stage>(n_steps, load_next, store_stage, [&](int buf) {
-        mma_step(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
-        finish_step();
-    });
+    two_ahead<Stage>(load_next, store_stage,
+                     [&](int buf) {
+                         mma_step(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
+                         finish_step();
+                     },
+                     [&]() { return c_end; });
 }
 
 // --------------------------------------------------- dWx and dbias (TN product)
@@ -462,10 +489,15 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     const int nk = m_end > m_begin ? (m_end - m_begin + BK - 1) / BK : 0;
-    auto compute = [&](int buf) { mma_step(s_a[buf], s_b[buf], wm, wn, l32, half, acc); };
+    int steps_done = 0;
+    auto compute = [&](int buf) {
+        mma_step(s_a[buf], s_b[buf], wm, wn, l32, half, acc);
+        ++steps_done;
+    };
+    auto done = [&]() { return steps_done >= nk; };
     if (nk > 0) {
-        if constexpr (sizeof(AT) == 4) one_ahead<Stage>(nk, load_next, store_stage, compute);
-        else two_ahead<Stage>(nk, load_next, store_stage, compute);
+        if constexpr (sizeof(AT) == 4) one_ahead<Stage>(load_next, store_stage, compute, done);
+        else two_ahead<Stage>(load_next, store_stage, compute, done);
     }
     float *out = a.part + (((long long)s * a.G + g) * a.H + head * a.dh + i0) * a.dh + j0;
 #pragma unroll
@@ -496,15 +528,18 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
 
 // ------------------------------------------------------------- weight copies
 // Wb = bf16(Wx), same layout [G][H][dh]
-__global__ __launch_bounds__(256) void proj_wb_kernel(const float *Wx, unsigned short *Wb, size_t n)
+__global__ __launch_bounds__(256) void proj_wb_kernel(const float *Wx, unsigned short *Wb, size_t n, int *tickets)
 {
+    if (blockIdx.x == 0 && threadIdx.x < 8) tickets[threadIdx.x] = 0;      // for the product that follows
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         Wb[i] = f32_to_bf16(Wx[i]);
 }
 
 // Wt[head][j][g dh + i] = bf16(Wx[g][head dh + i][j]): the B operand of the dx product
-__global__ __launch_bounds__(256) void proj_wt_kernel(const float *Wx, unsigned short *Wt, int G, int H, int dh)
+__global__ __launch_bounds__(256) void proj_wt_kernel(const float *Wx, unsigned short *Wt, int G, int H, int dh,
+                                                      int *tickets)
 {
+    if (blockIdx.x == 0 && threadIdx.x < 8) tickets[threadIdx.x] = 0;      // for the product that follows
     const size_t n = (size_t)G * H * dh;
     for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < n; o += (size_t)gridDim.x * blockDim.x) {
         const int i = (int)(o % dh);
@@ -539,7 +574,7 @@ void dw_split(int M, int base_tiles, int *S, int *rows_per_split)
 }
 
 struct ProjLayout {
-    size_t off_w, off_part, off_db, total;
+    size_t off_tickets, off_w, off_part, off_db, total;
     int S, rows_per_split, tiles;
 };
 
@@ -549,6 +584,7 @@ ProjLayout proj_layout(int B, int L, int H, int G, int n_heads, int backward)
     const int dh = H / n_heads;
     const size_t nw = (size_t)G * H * dh;
     size_t off = 0;
+    lo.off_tickets = off; off += 256;
     lo.off_w = off; off += r256(nw * sizeof(unsigned short));
     lo.tiles = (dh + BM - 1) / BM;
     lo.S = 0; lo.rows_per_split = 0;
@@ -601,10 +637,11 @@ int proj_forward(int dtype, const void *x, const float *Wx, const float *bias, i
     if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
     unsigned short *Wb = reinterpret_cast<unsigned short *>(static_cast<char *>(workspace) + lo.off_w);
     const size_t nw = (size_t)G * H * dh;
-    hipLaunchKernelGGL(proj_wb_kernel, dim3(elementwise_blocks(nw)), dim3(256), 0, st, Wx, Wb, nw);
+    int *tickets = reinterpret_cast<int *>(static_cast<char *>(workspace) + lo.off_tickets);
+    hipLaunchKernelGGL(proj_wb_kernel, dim3(elementwise_blocks(nw)), dim3(256), 0, st, Wx, Wb, nw, tickets);
     GemmArgs g;
     memset(&g, 0, sizeof(g));
-    g.A = x; g.Bw = Wb; g.C = u; g.bias = bias;
+    g.A = x; g.Bw = Wb; g.C = u; g.bias = bias; g.tickets = tickets;
     g.lda = H; g.ldb = dh; g.ldc = (long long)G * H;
     g.M = B * L; g.N = dh; g.K = dh;
     g.kseg = dh; g.kseg_stride = 0;
@@ -631,10 +668,11 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
     hipError_t e = hipSuccess;
     if (dx) {
         unsigned short *Wt = reinterpret_cast<unsigned short *>(ws + lo.off_w);
-        hipLaunchKernelGGL(proj_wt_kernel, dim3(elementwise_blocks(nw)), dim3(256), 0, st, Wx, Wt, G, H, dh);
+        int *tickets = reinterpret_cast<int *>(ws + lo.off_tickets);
+        hipLaunchKernelGGL(proj_wt_kernel, dim3(elementwise_blocks(nw)), dim3(256), 0, st, Wx, Wt, G, H, dh, tickets);
         GemmArgs g;
         memset(&g, 0, sizeof(g));
-        g.A = du; g.Bw = Wt; g.C = dx; g.bias = nullptr;
+        g.A = du; g.Bw = Wt; g.C = dx; g.bias = nullptr; g.tickets = tickets;
         g.lda = (long long)G * H; g.ldb = (long long)G * dh; g.ldc = H;
         g.M = B * L; g.N = dh; g.K = G * dh;
         g.kseg = dh; g.kseg_stride = H;                 // k = (gate, i): gates are H apart in a row of du

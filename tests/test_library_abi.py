@@ -70,6 +70,36 @@ def test_workspace_bytes(lib):
     assert ws(2, 0, 64, 1024, 64, 0) >= 2 * 64 * 1024 * 64 * 4 + 64 * 64 * 64 * 64 * 4
 
 
+def test_input_projection_host_checks(lib):
+    """Workspace sizes and the refusals that need no device."""
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    ws = lib.pararnn_input_projection_workspace_bytes
+    ws.restype = sz
+    ws.argtypes = [i] * 7
+    fwd = ws(1, 16, 4096, 1024, 3, 4, 0)
+    bwd = ws(1, 16, 4096, 1024, 3, 4, 1)
+    assert fwd >= 3 * 1024 * 256 * 2 and fwd % 256 == 0            # the bf16 copy of the weights
+    assert bwd > fwd + 3 * 1024 * 256 * 4                          # + partial sums of the weight gradient
+    assert ws(0, 1, 4, 96, 3, 1, 0) == 0 and ws(0, 1, 4, 128, 3, 3, 0) == 0 and ws(2, 1, 4, 128, 3, 1, 0) == 0
+    assert ws(0, 1, 4, 128, 9, 1, 0) == 0 and ws(0, 0, 4, 128, 3, 1, 0) == 0
+    f = lib.pararnn_input_projection
+    f.restype = i
+    f.argtypes = [i, vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
+    p = 0x1000
+    assert f(0, None, p, None, 1, 4, 128, 3, 1, p, p, 1 << 20, None) == 2          # x NULL
+    assert f(0, p, p, None, 1, 4, 128, 3, 1, p, p + 8, 1 << 20, None) == 2         # workspace alignment
+    assert f(0, p, p, None, 1, 4, 128, 3, 3, p, p, 1 << 20, None) == 2             # heads do not divide H
+    assert f(0, p, p, None, 1, 4, 96, 3, 1, p, p, 1 << 20, None) == 6              # dh not a multiple of 64
+    assert f(0, p + 4, p, None, 1, 4, 128, 3, 1, p, p, 1 << 20, None) == 6         # x not 16-byte aligned
+    assert f(0, p, p, None, 1, 4, 128, 3, 1, p, p, 256, None) == 3                 # WORKSPACE_TOO_SMALL
+    b = lib.pararnn_input_projection_backward
+    b.restype = i
+    b.argtypes = [i, vp, vp, vp, i, i, i, i, i, vp, vp, vp, vp, sz, vp]
+    assert b(0, p, p, None, 1, 4, 128, 3, 1, p, p, p, p, 1 << 20, None) == 2       # du NULL
+    assert b(0, p, p, p, 1, 4, 128, 3, 1, p, None, p, p, 1 << 20, None) == 2       # dbias without dWx
+    assert b(0, p, p, p, 1, 4, 128, 3, 1, p, p, p, p, 256, None) == 3
+
+
 def test_dense_products_switch(lib):
     sp = lib.pararnn_set_dense_products
     assert sp(1) == 0 and sp(2) == 0 and sp(0) == 0
