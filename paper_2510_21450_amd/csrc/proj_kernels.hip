@@ -86,30 +86,54 @@ __device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 
 // kernel (lanes four rows apart) and leaves those reads as they are.
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * PITCH + 8 * (chunk ^ ((row >> 4) & 7)); }
 
-// one 64-k step of a 64 x 64 wave tile from the LDS operand tiles
+// one 64-k step of a 64 x 64 wave tile from the LDS operand tiles.  PREFETCH: the fragments
+// of the next 16 k are requested before the products of the current 16 k are issued (the
+// scheduling barriers keep that order), so that LDS latency is paid once per step, not four
+// times; it costs 16 registers, which only the bf16 NT kernel has to spare.
+template <bool PREFETCH>
 __device__ __forceinline__ void mma_step(const unsigned short *sa, const unsigned short *sb, int wm, int wn, int l32,
                                          int half, f16v (&acc)[2][2])
 {
-#pragma unroll
-    for (int kb = 0; kb < BK / 16; ++kb) {
-        bf8v fa[2], fb[2];
+    auto read = [&](int kb, bf8v(&a)[2], bf8v(&b)[2]) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            fa[i] = *reinterpret_cast<const bf8v *>(sa + lds_off(64 * wm + 32 * i + l32, 2 * kb + half));
-            fb[i] = *reinterpret_cast<const bf8v *>(sb + lds_off(64 * wn + 32 * i + l32, 2 * kb + half));
+            a[i] = *reinterpret_cast<const bf8v *>(sa + lds_off(64 * wm + 32 * i + l32, 2 * kb + half));
+            b[i] = *reinterpret_cast<const bf8v *>(sb + lds_off(64 * wn + 32 * i + l32, 2 * kb + half));
         }
+    };
+    if constexpr (PREFETCH) {
+        bf8v fa[2][2], fb[2][2];
+        read(0, fa[0], fb[0]);
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int kb = 0; kb < BK / 16; ++kb) {
+            if (kb + 1 < BK / 16) read(kb + 1, fa[(kb + 1) & 1], fb[(kb + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kb & 1][mi], fb[kb & 1][ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < BK / 16; ++kb) {
+            bf8v fa[2], fb[2];
+            read(kb, fa, fb);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        }
     }
 }
 
 // The step loop of both products.  Step t is multiplied from LDS buffer t % 2 while the
 // global loads of steps t+1 and t+2 are outstanding in two register sets (memory latency
 // is several times the duration of a step).  load(set) fetches the next step in stream
-// order, store(buf, set) puts a fetched step into an LDS buffer, compute(buf) multiplies.
+// order, store(buf, set) puts a fetched step into an LDS buffer (buf = -1: into none) and
+// may publish through LDS what load() needs at its next call, compute(buf) multiplies.
 // Loads and stores are issued unconditionally, also past the end of the stream (load()
 // then has to deliver something harmless, which is stored and never multiplied): with
 // no branch around them the compiler can wait for exactly the older register set while
@@ -122,9 +146,10 @@ __device__ __forceinline__ void two_ahead(Load load, Store store, Compute comput
 {
     Stage r0, r1;
     load(r0);
-    __syncthreads();          // load() may publish something through LDS for the next load()
-    load(r1);
     store(0, r0);
+    __syncthreads();
+    load(r1);
+    store(-1, r1);            // nothing goes to a buffer: only what load() wants published through LDS
     __syncthreads();
     for (;;) {
         // a step from buffer 0; set 0 is free, set 1 holds the next step
@@ -195,33 +220,30 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     const int xcd = blockIdx.x & 7;
     const int inner_n = a.tiles_n * a.n_batch;
     // This XCD owns the row blocks [xcd * mx, (xcd + 1) * mx).  Its (row block, inner) grid is
-    // cut into patches of 8 x 8 tiles, numbered one after the other, and its workgroups draw
-    // numbers from a counter: whatever their relative speed they are inside one or two
-    // neighbouring patches at any time, whose 8 + 8 operand panels stay in that XCD's L2.
+    // cut into patches of 8 x 8 tiles (smaller at the edges), numbered one after the other, and
+    // its workgroups draw numbers from a counter: whatever their relative speed they are inside
+    // one or two neighbouring patches at any time, whose 8 + 8 operand panels stay in that
+    // XCD's L2.
     const int mx = (a.tiles_m + 7) / 8;
-    const int n_pn = (inner_n + 7) / 8, n_pm = (mx + 7) / 8;
-    const int n_local = n_pm * n_pn * 64;
+    int my_rows = a.tiles_m - xcd * mx;            // row blocks of this XCD
+    if (my_rows > mx) my_rows = mx;
+    if (my_rows <= 0) return;
+    const int n_local = my_rows * inner_n;
     auto decode = [&](int local, int &mt, int &inner) {
-        const int patch = local >> 6, within = local & 63;
-        mt = xcd * mx + 8 * (patch / n_pn) + (within >> 3);
-        inner = 8 * (patch % n_pn) + (within & 7);
-        return mt < a.tiles_m && mt < (xcd + 1) * mx && inner < inner_n;
+        const int pm = local / (8 * inner_n), rem = local - pm * 8 * inner_n;
+        const int hm = min(8, my_rows - 8 * pm);                 // rows of this patch row
+        const int pn = rem / (8 * hm), rem2 = rem - pn * 8 * hm;
+        const int hn = min(8, inner_n - 8 * pn);                 // columns of this patch
+        mt = xcd * mx + 8 * pm + rem2 / hn;
+        inner = 8 * pn + rem2 % hn;
     };
     const int nk = a.K / BK;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
     const int half = lane >> 5, l32 = lane & 31;
-    // Thread 0 draws the number of this workgroup's n-th tile (the next one that exists, or
-    // n_local when the XCD's list is used up) and leaves it in s_ring[n % 8]; everybody reads
-    // it after a later barrier.  At most three tiles are drawn ahead of the one being multiplied.
-    auto draw = [&](int n) {
-        if (tid != 0) return;
-        int t, mt, inner;
-        do {
-            t = atomicAdd(a.tickets + xcd, 1);
-        } while (t < n_local && !decode(t, mt, inner));
-        s_ring[n & 7] = t < n_local ? t : n_local;
-    };
-    draw(0);
+    // Thread 0 draws the number of this workgroup's n-th tile and leaves it in s_ring[n % 8]
+    // (n_local or more: the XCD's list is used up); everybody reads it after a later barrier.
+    // At most three tiles are drawn ahead of the one being multiplied.
+    if (tid == 0) s_ring[0] = atomicAdd(a.tickets + xcd, 1);
     __syncthreads();
     if (s_ring[0] >= n_local) return;
 
@@ -254,6 +276,10 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     Tile lt = tile_of(s_ring[0]);
     int ln = 0, lks = 0;
     bool l_switch = false, l_end = false;
+    // the number drawn for tile ln + 1: requested when the last step of tile ln is fetched,
+    // put into the ring by the store() that follows (the request's latency passes meanwhile)
+    int drawn = 0;
+    bool drawn_pending = false;
     struct Stage {
         typename Raw8<AT>::type a[4];
         u4v b[4];
@@ -271,6 +297,8 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
             }
             l_switch = false;
         }
+        const bool last_step = !l_end && lks + 1 == nk;
+        if (last_step && tid == 0) drawn = atomicAdd(a.tickets + xcd, 1);
         const int k0 = lks * BK;
         const long long kbase = (long long)(k0 / a.kseg) * a.kseg_stride + k0 % a.kseg;
         r.valid = 0u;
@@ -283,16 +311,19 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
             r.b[i] = load8(lt.Bw + (long long)min(gn, a.N - 1) * a.ldb + k0 + 8 * c);
             r.valid |= (gm < a.M ? 1u : 0u) << i | (gn < a.N ? 16u : 0u) << i;
         }
-        if (!l_end) {
-            if (lks + 1 < nk) {
-                ++lks;
-            } else {
-                draw(ln + 1);
-                l_switch = true;
-            }
+        if (last_step) {
+            drawn_pending = true;
+            l_switch = true;
+        } else if (!l_end) {
+            ++lks;
         }
     };
     auto store_stage = [&](int buf, const Stage &r) {
+        if (drawn_pending) {
+            if (tid == 0) s_ring[(ln + 1) & 7] = drawn;
+            drawn_pending = false;
+        }
+        if (buf < 0) return;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int q = tid + 256 * i, row = piece_row(q), c = q & 7;
@@ -351,7 +382,7 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 
     two_ahead<Stage>(load_next, store_stage,
                      [&](int buf) {
-                         mma_step(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
+                         mma_step<sizeof(AT) == 2>(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
                          finish_step();
                      },
                      [&]() { return c_end; });
@@ -471,6 +502,7 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
         if (real) m_next += BK;
     };
     auto store_stage = [&](int buf, const Stage &r) {
+        if (buf < 0) return;
         u4v ca[4], cb[4];
         r.a.transpose(ca, sdb);
         r.b.transpose(cb, unused);
@@ -491,7 +523,7 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
     const int nk = m_end > m_begin ? (m_end - m_begin + BK - 1) / BK : 0;
     int steps_done = 0;
     auto compute = [&](int buf) {
-        mma_step(s_a[buf], s_b[buf], wm, wn, l32, half, acc);
+        mma_step<false>(s_a[buf], s_b[buf], wm, wn, l32, half, acc);
         ++steps_done;
     };
     auto done = [&]() { return steps_done >= nk; };
