@@ -397,6 +397,7 @@ struct DwArgs {
     int M, H, G, heads, dh;
     int S, rows_per_split; // rows_per_split a multiple of BK
     int tiles;             // 128-wide tiles per dh
+    int n_blocks, per_xcd; // tiles^2 * G * heads * S workgroups, an eighth of them (rounded up)
 };
 
 // Four adjacent channels of eight consecutive rows as fetched; transposed in registers into
@@ -468,12 +469,16 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
     __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
     __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
     __shared__ float s_db[8][BM];
-    int id = blockIdx.x;
+    // Workgroups go to the eight XCDs round-robin; numbering them so that each XCD works through a
+    // contiguous range keeps the tiles that share operand panels (the tiles of one (head, range):
+    // x is common to its gates, du to its column tiles) on one L2 at about the same time.
+    int id = (int)(blockIdx.x & 7) * a.per_xcd + (int)(blockIdx.x >> 3);
+    if (id >= a.n_blocks) return;
     const int tj = id % a.tiles; id /= a.tiles;
     const int ti = id % a.tiles; id /= a.tiles;
-    const int head = id % a.heads; id /= a.heads;
-    const int g = id % a.G;
-    const int s = id / a.G;
+    const int g = id % a.G; id /= a.G;
+    const int head = id % a.heads;
+    const int s = id / a.heads;
     const int i0 = ti * BM, j0 = tj * BN;
     const int m_begin = s * a.rows_per_split;
     const int m_end = min(a.M, m_begin + a.rows_per_split);
@@ -677,10 +682,10 @@ int proj_forward(int dtype, const void *x, const float *Wx, const float *bias, i
     g.lda = H; g.ldb = dh; g.ldc = (long long)G * H;
     g.M = B * L; g.N = dh; g.K = dh;
     g.kseg = dh; g.kseg_stride = 0;
-    g.nz0 = n_heads; g.n_batch = n_heads * G;          // z0 = head, z1 = gate
-    g.a_off[0] = dh; g.a_off[1] = 0;
-    g.b_off[0] = (long long)dh * dh; g.b_off[1] = (long long)H * dh;
-    g.c_off[0] = dh; g.c_off[1] = H;
+    g.nz0 = G; g.n_batch = n_heads * G;                // z0 = gate, z1 = head: the tiles that read the same
+    g.a_off[0] = 0; g.a_off[1] = dh;                   // columns of x (all gates of a head) are neighbours
+    g.b_off[0] = (long long)H * dh; g.b_off[1] = (long long)dh * dh;
+    g.c_off[0] = H; g.c_off[1] = dh;
     const hipError_t e = dtype == PARARNN_BF16 ? launch_nt<unsigned short, unsigned short>(g, st) : launch_nt<float, float>(g, st);
     return e == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
@@ -721,7 +726,9 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         a.dbpart = dbias ? reinterpret_cast<float *>(ws + lo.off_db) : nullptr;
         a.M = B * L; a.H = H; a.G = G; a.heads = n_heads; a.dh = dh;
         a.S = lo.S; a.rows_per_split = lo.rows_per_split; a.tiles = lo.tiles;
-        const int blocks = lo.tiles * lo.tiles * n_heads * G * lo.S;
+        a.n_blocks = lo.tiles * lo.tiles * n_heads * G * lo.S;
+        a.per_xcd = (a.n_blocks + 7) / 8;
+        const int blocks = 8 * a.per_xcd;
         if (bf) hipLaunchKernelGGL(proj_dw_kernel<unsigned short>, dim3(blocks), dim3(256), 0, st, a);
         else hipLaunchKernelGGL(proj_dw_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return PARARNN_HIP_ERROR;
