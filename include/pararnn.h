@@ -111,6 +111,13 @@ size_t pararnn_workspace_bytes(int cell, int dtype, int B, int L, int H, int bac
  * paths compute the same iterations (results agree to fp32 rounding). */
 size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, int n_iters);
 
+/* Test hook (host, process-wide): the number of times a tile polls its
+ * predecessor's carry record before it gives up (polls = 0: the default, about
+ * two million, i.e. seconds).  A tile that gives up uses a zero carry, the call's
+ * device status becomes PARARNN_INTERNAL and every wave still exits: with a tiny
+ * limit this path can be exercised without any wait that does not end. */
+int pararnn_set_spin_limit(unsigned int polls);
+
 /* Test / tuning hook (host, process-wide): enable = 0 makes pararnn_forward
  * always launch one kernel per iteration (fixed-count solves and solves to a
  * tolerance alike); the returned h is then exactly the iterate of the stopping

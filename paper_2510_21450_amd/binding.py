@@ -159,6 +159,12 @@ def workspace_bytes_fused(cell, dtype, B: int, L: int, H: int, n_iters: int) -> 
     return _api(cell).ws_fused(DTYPES[dtype], B, L, H, n_iters)
 
 
+def set_spin_limit(polls: int = 0) -> None:
+    """pararnn_set_spin_limit: polls of a predecessor's carry record before a tile gives up (0 = default)."""
+    _lib.pararnn_set_spin_limit.argtypes = [ctypes.c_uint]
+    _raise(_lib.pararnn_set_spin_limit(int(polls)), "pararnn_set_spin_limit")
+
+
 def set_fused(enable: bool = True) -> None:
     """pararnn_set_fused: allow (default) or forbid the fused multi-iteration launches."""
     _raise(_lib.pararnn_set_fused(int(enable)), "pararnn_set_fused")

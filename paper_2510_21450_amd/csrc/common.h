@@ -27,9 +27,11 @@ constexpr int kStOk = 0, kStNotConverged = 1, kStNonFinite = 5, kStInternal = 7;
 // States of a carry record's tag (tag = epoch * 4 + state).
 constexpr unsigned int kFlagAgg = 1;   // tile aggregate (A, b) published
 constexpr unsigned int kFlagIncl = 2;  // inclusive value (delta at the tile's end) published
-// polls of one predecessor before a tile gives up (reports kStInternal, uses a
-// zero carry) so that every wave terminates whatever happens
-constexpr unsigned int kSpinLimit = 1u << 24;
+// default number of polls of one predecessor before a tile gives up (reports
+// kStInternal, uses a zero carry) so that every wave terminates whatever happens:
+// a poll is a memory round trip and a sleep, about a microsecond, so this is seconds,
+// where a legitimate wait lasts at most the few milliseconds of a launch
+constexpr unsigned int kSpinLimit = 1u << 21;
 
 // ---------------------------------------------------------------- bf16 <-> fp32
 __device__ __forceinline__ float bf16_to_f32(unsigned short v)

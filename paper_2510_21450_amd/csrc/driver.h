@@ -26,6 +26,7 @@ struct Settings {
     int fused_enabled;     // launches that run several Newton iterations are allowed
     int fused_head;        // iterations in the first launch of a solve to a tolerance (0 = none)
     int tile[4];           // tile-shape override {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
+    unsigned int spin_limit;   // polls of one predecessor before a tile gives up (pararnn_set_spin_limit)
 };
 Settings &settings();
 
@@ -98,6 +99,7 @@ inline Layout make_layout(const CellInfo &ci, int dtype, int B, int L, int H, bo
     g.n_cg = (H + CW - 1) / CW;
     g.n_groups = B * g.n_cg;
     g.n_tiles = g.n_groups * g.n_lt;
+    g.spin_limit = settings().spin_limit;
     const size_t NW = (size_t)ci.S * ci.S + 2 * ci.S;
     size_t off = round256(sizeof(Ctrl));
     lo.n_rec = (size_t)g.n_tiles * NW * CW;

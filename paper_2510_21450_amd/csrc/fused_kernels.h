@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                         }
                         publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
                     }
-                    if (!lookback<S, VEC, CW>(reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
+                    if (!lookback<S, VEC, CW>(g.spin_limit, reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
                         internal_error = true;
                 }
                 if (has_next) {

@@ -10,7 +10,7 @@ namespace pararnn {
 
 Settings &settings()
 {
-    static Settings s = {1, 5, {-1, 0, 0, 0}};
+    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit};
     return s;
 }
 
@@ -90,6 +90,12 @@ size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, i
     if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
     if (cell == PARARNN_TANH_DENSE) return dense_workspace_bytes(dtype, B, L, H, 0);
     return diag_workspace_bytes_fused(ci, dtype, B, L, H, n_iters);
+}
+
+int pararnn_set_spin_limit(unsigned int polls)
+{
+    settings().spin_limit = polls ? polls : kSpinLimit;
+    return PARARNN_OK;
 }
 
 int pararnn_set_fused(int enable)

@@ -46,6 +46,7 @@ struct ScanGeom {
     int n_cg;      // channel groups per sequence
     int n_groups;  // B * n_cg
     int n_tiles;   // n_groups * n_lt
+    unsigned int spin_limit;   // polls of one predecessor before a tile gives up
 };
 
 struct FwdArgs {
@@ -219,7 +220,7 @@ __device__ __forceinline__ rec_t rec_load(const rec_t *p)
 // column `col` of the group, the others only keep the control flow uniform.
 // Returns false when the bounded wait ran out (carry is then zero).
 template <int S, int VEC, int CW>
-__device__ __forceinline__ bool lookback(const rec_t *rec_base, int n_lt, int grp, int lt, int dir,
+__device__ __forceinline__ bool lookback(unsigned int spin_limit, const rec_t *rec_base, int n_lt, int grp, int lt, int dir,
                                          unsigned int epoch, int col, bool active, float (&carry)[S][VEC])
 {
     constexpr int SS = S * S, NW = SS + 2 * S;
@@ -288,7 +289,7 @@ __device__ __forceinline__ bool lookback(const rec_t *rec_base, int n_lt, int gr
             }
             continue;
         }
-        if (++spins >= kSpinLimit) {
+        if (++spins >= spin_limit) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v)
 #pragma unroll
@@ -641,7 +642,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                     }
                     publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
                 }
-                if (!lookback<S, VEC, CW>(a.rec, g.n_lt, grp, lt, -1, epoch, col, active, carry))
+                if (!lookback<S, VEC, CW>(g.spin_limit, a.rec, g.n_lt, grp, lt, -1, epoch, col, active, carry))
                     internal_error = true;
             }
             if (has_next) {
@@ -1081,7 +1082,7 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                     }
                     publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
                 }
-                if (!lookback<S, VEC, CW>(a.rec, g.n_lt, grp, lt, +1, epoch, col, active, carry))
+                if (!lookback<S, VEC, CW>(g.spin_limit, a.rec, g.n_lt, grp, lt, +1, epoch, col, active, carry))
                     internal_error = true;
             }
             if (has_next) {

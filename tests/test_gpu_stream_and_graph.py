@@ -11,7 +11,7 @@ from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
 
 
 def f64(t):
-    return t.detach().to("cpu", torch.float64).numpy()
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
 
 
 def relerr(got, ref):
@@ -147,3 +147,35 @@ def test_autograd_wrapper_matches_oracle_gradients(cell, oracle_mod):
     h2, _ = P.rnn_apply(cell, params.detach(), u2, None, tol=1e-5, max_iter=40)
     h2.sum().backward()
     assert u2.grad is not None and bool(torch.isfinite(u2.grad).all())
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+def test_bounded_wait_gives_up_cleanly(cell, oracle_mod):
+    """The look-back wait is bounded: with the limit forced to a single poll from the
+    host, a tile whose predecessor has not published yet gives up, the status becomes
+    INTERNAL (or the solve happens to succeed), every wave exits, and the next call
+    with the default limit is correct again.  Forward (fused blocks and one launch
+    per iteration) and backward."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2" if cell == "gru_diag" else "C3"].scaled(B=4, L=20000, H=64)
+    d = make_inputs(w, device="cuda")
+    try:
+        P.set_spin_limit(1)
+        seen = set()
+        for fused in (True, False):
+            P.set_fused(fused)
+            for rep in range(3):
+                h, iters, _ = P.forward(w.cell, d["params"], d["u"], d["h0"], tol=w.tol, max_iter=8)
+                du, dp, dh0 = P.backward(w.cell, d["params"], d["u"], d["h0"], h, d["g"])
+                torch.cuda.synchronize()
+                seen.add(P.status_string(int(iters.cpu()[1])))
+        print(f"{cell}: statuses with one poll: {sorted(seen)}", flush=True)
+        assert seen <= {"OK", "INTERNAL", "NOT_CONVERGED"}
+    finally:
+        P.set_spin_limit(0)
+        P.set_fused(True)
+    h, iters, _ = P.forward(w.cell, d["params"], d["u"], d["h0"], tol=w.tol, max_iter=32)
+    torch.cuda.synchronize()
+    assert int(iters.cpu()[1]) == 0
+    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), f64(d["h0"]))
+    assert relerr(f64(h), ref) <= 1e-5

@@ -100,6 +100,12 @@ def test_input_projection_host_checks(lib):
     assert b(0, p, p, p, 1, 4, 128, 3, 1, p, p, p, p, 256, None) == 3
 
 
+def test_spin_limit_hook(lib):
+    sl = lib.pararnn_set_spin_limit
+    sl.argtypes = [ctypes.c_uint]
+    assert sl(1) == 0 and sl(0) == 0          # 0 restores the default
+
+
 def test_dense_products_switch(lib):
     sp = lib.pararnn_set_dense_products
     assert sp(1) == 0 and sp(2) == 0 and sp(0) == 0
