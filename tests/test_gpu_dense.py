@@ -1,5 +1,5 @@
 """GPU parity of the dense-Jacobian path (h' = tanh(W h + u), H = 64): the MFMA
-scan against the CPU oracle, including BASELINE config 4 at full size."""
+scan against the CPU oracle, including benchmark configuration 4 at full size."""
 import json
 import os
 
@@ -101,7 +101,7 @@ def test_dense_unsupported_shapes_are_refused():
 
 
 def test_config_c4_full_size(oracle_mod):
-    """BASELINE config 4: B=64, L=1024, H=64, max_iter 32, forward."""
+    """Benchmark configuration 4: B=64, L=1024, H=64, max_iter 32, forward."""
     import paper_2510_21450_amd as P
     w = CONFIGS["C4"]
     d = make_inputs(w, device="cuda")

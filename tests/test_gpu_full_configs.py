@@ -1,4 +1,4 @@
-"""Full-size benchmark workloads (BASELINE configs 2, 3, 5, and the paper's ParaLSTM
+"""Full-size benchmark workloads (benchmark configurations 2, 3, 5, and the paper's ParaLSTM
 cell on config 3's shapes, "X3") in the launch
 configuration bench.py times: inputs are generated on the GPU, the library runs
 on all of them, and a sample of channels (all sequences, all timesteps) is

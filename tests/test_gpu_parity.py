@@ -96,7 +96,7 @@ def test_forward_backward_f32_small(P, oracle_mod, cell, shape):
 
 
 def test_config_c1(P, oracle_mod):
-    """BASELINE config 1: GRU, B=1, L=64, H=8, tol 1e-6, max_iter 64, forward."""
+    """Benchmark configuration 1: GRU, B=1, L=64, H=8, tol 1e-6, max_iter 64, forward."""
     w = CONFIGS["C1"]
     d = make_inputs(w, device="cuda")
     h, iters, tr = P.forward(w.cell, d["params"], d["u"], d["h0"], tol=w.tol, max_iter=w.max_iter, trace=True)
