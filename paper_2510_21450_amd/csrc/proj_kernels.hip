@@ -18,10 +18,9 @@
 // row ranges whose partial results are added in a fixed order afterwards.
 //
 // Tiles: 128 x 128 outputs per workgroup of four waves (64 x 64 per wave, four
-// 32 x 32 accumulators), 64 k per step, both operand tiles in LDS as rows of 64
-// bf16 with a pitch of 144 bytes (the 16-byte fragments of 16 consecutive rows
-// then cover all 64 banks once), double buffered: the global loads of step s+1
-// are in flight while step s is multiplied.
+// 32 x 32 accumulators), 64 k per step, both operand tiles in LDS in k-chunk-major
+// order (fragment reads are contiguous), double buffered, the global loads of the
+// next two steps in flight while a step is multiplied.
 #include "../../include/pararnn.h"
 #include "common.h"
 #include "launch.h"
@@ -42,7 +41,10 @@ typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int PITCH = BK + 8;            // bf16 elements per LDS row (144 bytes)
+// An operand tile in LDS: eight planes, one per 16-byte k-chunk, each holding that chunk of the
+// 128 rows back to back, planes 16 bytes further apart than their size.
+constexpr int PLANE = 128 * 8 + 8;       // bf16 elements from one plane to the next
+constexpr int TILE = 8 * PLANE;          // bf16 elements of a tile
 
 __device__ __forceinline__ unsigned int pack2(float x0, float x1)
 {
@@ -80,11 +82,11 @@ __device__ __forceinline__ void store4(unsigned short *p, const f4v &v)
 
 __device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
 
-// Element offset of 16-byte chunk `chunk` (0..7) of row `row` in an LDS operand tile.  The
-// pitch of 144 bytes spreads the fragment reads of 16 consecutive rows over all banks; the
-// XOR with the row's 16-row group does the same for the transposing stores of the dWx
-// kernel (lanes four rows apart) and leaves those reads as they are.
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * PITCH + 8 * (chunk ^ ((row >> 4) & 7)); }
+// Element offset of 16-byte chunk `chunk` (0..7) of row `row` in an LDS operand tile.  A
+// fragment read (32 consecutive rows, one chunk per lane half) is 512 contiguous bytes; the
+// eight chunks of a row, stored by eight neighbouring lanes, fall into eight different
+// 16-byte bank groups because of the 16 bytes between planes.
+__device__ __forceinline__ int lds_off(int row, int chunk) { return chunk * PLANE + row * 8; }
 
 // one 64-k step of a 64 x 64 wave tile from the LDS operand tiles.  PREFETCH: the fragments
 // of the next 16 k are requested before the products of the current 16 k are issued (the
@@ -214,8 +216,8 @@ struct GemmArgs {
 template <typename AT, typename CT, bool BIAS>
 __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
-    __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
+    __shared__ __attribute__((aligned(16))) unsigned short s_a[2][TILE];
+    __shared__ __attribute__((aligned(16))) unsigned short s_b[2][TILE];
     __shared__ int s_ring[8];
     const int xcd = blockIdx.x & 7;
     const int inner_n = a.tiles_n * a.n_batch;
@@ -266,9 +268,8 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         return t;
     };
     // a thread stages four 16-byte pieces of each operand tile per step: piece q = tid + 256 i
-    // is k-chunk q % 8 of the tile row below: eight lanes cover one row, and the two rows of
-    // sixteen consecutive lanes are eight apart, which the 144-byte pitch turns into the two
-    // halves of the banks
+    // is k-chunk q % 8 of the tile row below: eight lanes cover one row (eight bank groups), and
+    // the two rows of sixteen consecutive lanes are eight apart (the other eight)
     auto piece_row = [](int q) { return ((q >> 4) & 7) + 8 * ((q >> 3) & 1) + 16 * (q >> 7); };
     const u4v zero4 = {0u, 0u, 0u, 0u};
     // the loading side: tile number ln of this workgroup, k-step lks of it; l_switch: the tile
@@ -466,8 +467,8 @@ template <> struct QuadRows<float> {
 template <typename AT>
 __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned short s_a[2][BM * PITCH];
-    __shared__ __attribute__((aligned(16))) unsigned short s_b[2][BN * PITCH];
+    __shared__ __attribute__((aligned(16))) unsigned short s_a[2][TILE];
+    __shared__ __attribute__((aligned(16))) unsigned short s_b[2][TILE];
     __shared__ float s_db[8][BM];
     // Workgroups go to the eight XCDs round-robin; numbering them so that each XCD works through a
     // contiguous range keeps the tiles that share operand panels (the tiles of one (head, range):
@@ -511,10 +512,15 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
         u4v ca[4], cb[4];
         r.a.transpose(ca, sdb);
         r.b.transpose(cb, unused);
+        // lane c4 stores its channels in the order ch = (i + c4 / 4) % 4: sixteen neighbouring lanes
+        // then hit sixteen different 16-byte bank groups
 #pragma unroll
-        for (int ch = 0; ch < 4; ++ch) {
-            *reinterpret_cast<u4v *>(&s_a[buf][lds_off(4 * c4 + ch, rg)]) = ca[ch];
-            *reinterpret_cast<u4v *>(&s_b[buf][lds_off(4 * c4 + ch, rg)]) = cb[ch];
+        for (int i = 0; i < 4; ++i) {
+            const int ch = (i + (c4 >> 2)) & 3;
+            const u4v va = ch == 0 ? ca[0] : ch == 1 ? ca[1] : ch == 2 ? ca[2] : ca[3];
+            const u4v vb = ch == 0 ? cb[0] : ch == 1 ? cb[1] : ch == 2 ? cb[2] : cb[3];
+            *reinterpret_cast<u4v *>(&s_a[buf][lds_off(4 * c4 + ch, rg)]) = va;
+            *reinterpret_cast<u4v *>(&s_b[buf][lds_off(4 * c4 + ch, rg)]) = vb;
         }
     };
     f16v acc[2][2];
