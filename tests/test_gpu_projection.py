@@ -123,3 +123,33 @@ def test_projection_refuses_what_it_cannot_do():
         P.input_projection(x, torch.zeros(3, 96, 96, device="cuda"))          # dh = 96 is not a multiple of 64
     assert P.input_projection_workspace_bytes(torch.float32, 1, 4, 96, 3, 1) == 0
     assert P.input_projection_workspace_bytes(torch.float32, 1, 4, 128, 3, 3) == 0      # heads must divide H
+
+
+def test_projection_replays_from_a_graph():
+    """Forward and backward recorded into a HIP graph (no allocation, no memset node; the tile
+    counters of the products are reset by the weight-copy kernels inside the graph) and replayed
+    with eager work in between: every replay equals the eager result bit for bit."""
+    import paper_2510_21450_amd as P
+    shape = (2, 700, 512, 3, 2)
+    B, L, H, G, heads = shape
+    x, Wx, bias, du = problem(shape, torch.bfloat16, seed=5300)
+    ws = torch.empty(P.input_projection_workspace_bytes(x.dtype, B, L, H, G, heads, True), dtype=torch.uint8, device="cuda")
+    u_e = P.input_projection(x, Wx, bias, n_heads=heads, workspace=ws)
+    dx_e, dW_e, db_e = P.input_projection_backward(x, Wx, du, n_heads=heads, workspace=ws)
+    torch.cuda.synchronize()
+    u = torch.empty_like(u_e)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            P.input_projection(x, Wx, bias, n_heads=heads, workspace=ws, out=u)
+            dx, dW, db = P.input_projection_backward(x, Wx, du, n_heads=heads, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        u.zero_(); dx.zero_(); dW.zero_(); db.zero_()
+        _ = (x.float() * 2).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(u, u_e) and torch.equal(dx, dx_e), rep
+        assert torch.equal(dW, dW_e) and torch.equal(db, db_e), rep
