@@ -347,31 +347,42 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     Tile ct = lt;                      // tile being multiplied: number cn of this workgroup
     int cn = 0, cks = 0;
     bool c_end = false;
-    auto finish_step = [&]() {
+    auto finish_step = [&](int buf) {
         if (++cks < nk) return;
+        // Epilogue.  The accumulators go through LDS so that a wave's global stores are whole
+        // row segments (16 bytes per lane, neighbouring lanes neighbouring addresses): each
+        // wave transposes its 64 x 64 part in two passes of 32 rows, in its own quarter of the
+        // operand buffer that has just been multiplied (free once every wave is past this
+        // step).  16-byte chunk c of row r sits at chunk position c ^ (r % chunks per row).
+        __syncthreads();
+        constexpr int EPC = 16 / (int)sizeof(CT);          // elements per 16-byte chunk
+        constexpr int CPR = 64 / EPC;                      // chunks per 64-column row
+        CT *stage = reinterpret_cast<CT *>(w < 2 ? s_a[buf] : s_b[buf]) + (w & 1) * (32 * 64);
         CT *C = static_cast<CT *>(a.C) + ct.coff;
-        // this lane's columns: col(ni, q) .. + 3 (N is a multiple of 4); one group of 32 columns at a time
+        const int col0 = ct.n0 + 64 * wn;                  // N is a multiple of 64: all 64 columns exist or none
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            f4v bv[4];
+        for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = ct.n0 + 64 * wn + 32 * ni + 8 * q + 4 * half;
-                if (BIAS) bv[q] = *reinterpret_cast<const f4v *>(a.bias + ct.coff + min(col, a.N - 4));
-            }
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                const int row = ct.m0 + 64 * wm + 32 * mi + l32;
-                if (row >= a.M) continue;
+            for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = ct.n0 + 64 * wn + 32 * ni + 8 * q + 4 * half;
-                    if (col >= a.N) continue;
+                    const int col = 32 * ni + 8 * q + 4 * half;      // this lane's four columns, row l32
                     f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
-                    if (BIAS) o += bv[q];
-                    store4(C + (long long)row * a.ldc + col, o);
+                    if (BIAS) o += *reinterpret_cast<const f4v *>(a.bias + ct.coff + min(col0, a.N - 64) + col);
+                    store4(stage + l32 * 64 + ((col / EPC) ^ (l32 & (CPR - 1))) * EPC + col % EPC, o);
                 }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            constexpr int RPI = 64 / CPR;                  // rows per store instruction
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int r = it * RPI + lane / CPR, cc = lane % CPR;
+                const u4v v = *reinterpret_cast<const u4v *>(stage + r * 64 + (cc ^ (r & (CPR - 1))) * EPC);
+                const int row = ct.m0 + 64 * wm + 32 * mi + r;
+                if (row < a.M && col0 < a.N) *reinterpret_cast<u4v *>(C + (long long)row * a.ldc + col0 + cc * EPC) = v;
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
         clear_acc();
         cks = 0;
@@ -384,7 +395,7 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
     two_ahead<Stage>(load_next, store_stage,
                      [&](int buf) {
                          mma_step<sizeof(AT) == 2>(s_b[buf], s_a[buf], wn, wm, l32, half, acc);
-                         finish_step();
+                         finish_step(buf);
                      },
                      [&]() { return c_end; });
 }
