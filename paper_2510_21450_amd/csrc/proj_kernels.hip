@@ -523,11 +523,11 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
         u4v ca[4], cb[4];
         r.a.transpose(ca, sdb);
         r.b.transpose(cb, unused);
-        // lane c4 stores its channels in the order ch = (i + c4 / 4) % 4: sixteen neighbouring lanes
-        // then hit sixteen different 16-byte bank groups
+        // lane c4 stores its channels in the order ch = (i + c4 / 2) % 4: the eight neighbouring lanes
+        // of a 16-byte store pass then hit eight different 16-byte bank groups
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ch = (i + (c4 >> 2)) & 3;
+            const int ch = (i + (c4 >> 1)) & 3;
             const u4v va = ch == 0 ? ca[0] : ch == 1 ? ca[1] : ch == 2 ? ca[2] : ca[3];
             const u4v vb = ch == 0 ? cb[0] : ch == 1 ? cb[1] : ch == 2 ? cb[2] : cb[3];
             *reinterpret_cast<u4v *>(&s_a[buf][lds_off(4 * c4 + ch, rg)]) = va;
