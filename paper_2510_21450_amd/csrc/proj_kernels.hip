@@ -286,6 +286,23 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         u4v b[4];
         unsigned int valid;            // bit i: row of a[i] exists, bit 4 + i: row of b[i] exists
     };
+    // per tile: where this thread's four pieces of each operand start (k = 0), and which of their
+    // rows exist; rows past the end read the last row (valid memory) and are stored as zeros
+    const AT *pa[4];
+    const unsigned short *pb[4];
+    unsigned int l_valid = 0u;
+    auto point_at = [&](const Tile &t) {
+        l_valid = 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = tid + 256 * i, row = piece_row(q), c = q & 7;
+            const int gm = t.m0 + row, gn = t.n0 + row;
+            pa[i] = t.A + (long long)min(gm, a.M - 1) * a.lda + 8 * c;
+            pb[i] = t.Bw + (long long)min(gn, a.N - 1) * a.ldb + 8 * c;
+            l_valid |= (gm < a.M ? 1u : 0u) << i | (gn < a.N ? 16u : 0u) << i;
+        }
+    };
+    point_at(lt);
     auto load_next = [&](Stage &r) {
         if (l_switch) {
             const int t = s_ring[(ln + 1) & 7];
@@ -293,6 +310,7 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
                 l_end = true;              // from here on the last step is fetched again (never multiplied)
             } else {
                 lt = tile_of(t);
+                point_at(lt);
                 ++ln;
                 lks = 0;
             }
@@ -302,16 +320,12 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
         if (last_step && tid == 0) drawn = atomicAdd(a.tickets + xcd, 1);
         const int k0 = lks * BK;
         const long long kbase = (long long)(k0 / a.kseg) * a.kseg_stride + k0 % a.kseg;
-        r.valid = 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int q = tid + 256 * i, row = piece_row(q), c = q & 7;
-            // rows past the end read the last row (valid memory) and are stored as zeros
-            const int gm = lt.m0 + row, gn = lt.n0 + row;
-            r.a[i] = load8(lt.A + (long long)min(gm, a.M - 1) * a.lda + kbase + 8 * c);
-            r.b[i] = load8(lt.Bw + (long long)min(gn, a.N - 1) * a.ldb + k0 + 8 * c);
-            r.valid |= (gm < a.M ? 1u : 0u) << i | (gn < a.N ? 16u : 0u) << i;
+            r.a[i] = load8(pa[i] + kbase);
+            r.b[i] = load8(pb[i] + k0);
         }
+        r.valid = l_valid;
         if (last_step) {
             drawn_pending = true;
             l_switch = true;
