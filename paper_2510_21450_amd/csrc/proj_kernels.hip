@@ -434,8 +434,11 @@ template <> struct QuadRows<unsigned short> {
     int n_valid;
     __device__ __forceinline__ void load(const unsigned short *p, long long ld, int m, int m_last, int n_valid_)
     {
+        // rows m .. m + 7, those past m_last replaced by m_last (valid memory, counted as zeros)
+        const unsigned short *base = p + (long long)min(m, m_last) * ld;
+        const int dm = max(m_last - m, 0), ldi = (int)ld;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const uint2 *>(p + (long long)min(m + r, m_last) * ld);
+        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const uint2 *>(base + min(r, dm) * ldi);
         n_valid = n_valid_;
     }
     __device__ __forceinline__ void transpose(u4v (&c)[4], float (&s)[4]) const
@@ -464,8 +467,10 @@ template <> struct QuadRows<float> {
     int n_valid;
     __device__ __forceinline__ void load(const float *p, long long ld, int m, int m_last, int n_valid_)
     {
+        const float *base = p + (long long)min(m, m_last) * ld;
+        const int dm = max(m_last - m, 0), ldi = (int)ld;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f4v *>(p + (long long)min(m + r, m_last) * ld);
+        for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f4v *>(base + min(r, dm) * ldi);
         n_valid = n_valid_;
     }
     __device__ __forceinline__ void transpose(u4v (&c)[4], float (&s)[4]) const
