@@ -15,12 +15,13 @@ _BINDING = ["CELLS", "DTYPES", "STATUS", "UserCell", "example_cell", "affine_sca
             "input_projection_workspace_bytes", "lib_path", "set_dense_products", "set_fused",
             "set_fused_head", "set_spin_limit", "set_tile", "solve_plan", "status_string", "version", "workspace_bytes",
             "workspace_bytes_fused"]
-__all__ = ["rnn_apply"] + _BINDING
+_AUTOGRAD = ["rnn_apply", "rnn_layer", "input_projection_apply"]
+__all__ = _AUTOGRAD + _BINDING
 
 
 def __getattr__(name):
     if name in _BINDING:
         return getattr(importlib.import_module(".binding", __name__), name)
-    if name == "rnn_apply":
-        return importlib.import_module(".autograd", __name__).rnn_apply
+    if name in _AUTOGRAD:
+        return getattr(importlib.import_module(".autograd", __name__), name)
     raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

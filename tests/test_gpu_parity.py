@@ -64,7 +64,7 @@ SHAPES = [(1, 1, 8), (1, 2, 4), (2, 33, 1), (2, 100, 24), (3, 257, 68), (2, 1000
 
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_forward_backward_f32_small(P, oracle_mod, cell, shape):
+def test_forward_backward_f32_small(P, oracle_mod, as_stored, cell, shape):
     B, L, H = shape
     print(f"case {cell} B={B} L={L} H={H}", flush=True)
     params, u, h0, g = problem(cell, B, L, H, seed=1000 + L * 7 + H)
@@ -86,10 +86,11 @@ def test_forward_backward_f32_small(P, oracle_mod, cell, shape):
         assert it == it32, (it, it32, tr.cpu().numpy()[:it], tr32)
     else:
         assert abs(it - it32) <= 1
-    # backward at the GPU's own forward result
-    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    # backward: both sides at the oracle's states
+    hs = as_stored(ref, h)
+    du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
     torch.cuda.synchronize()
-    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
     assert relerr(to_np(du), rdu) <= TOL_F32
     assert relerr(to_np(dp), rdp) <= TOL_F32
     assert relerr(to_np(dh0), rdh0) <= TOL_F32
@@ -166,7 +167,7 @@ def _misaligned(t, elems=1):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-def test_pointers_without_vector_alignment(P, oracle_mod, dtype):
+def test_pointers_without_vector_alignment(P, oracle_mod, as_stored, dtype):
     """Buffers that are only element-aligned (and an H that allows no vector
     width) must still work: the library falls back to narrower accesses."""
     cell = "gru_diag"
@@ -174,33 +175,35 @@ def test_pointers_without_vector_alignment(P, oracle_mod, dtype):
     for H in (64, 66, 67):
         params, u, h0, g = problem(cell, 2, 150, H, seed=31 + H, dtype=dtype)
         pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+        ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+        hs = as_stored(ref, u)
         try:
             P.set_tile(2, 2, 8, 8)       # asks for 2 channels per lane; refused silently when not allowed
             um, h0m, gm, pm = _misaligned(u), _misaligned(h0), _misaligned(g), _misaligned(params)
             h, iters, _ = P.forward(cell, pm, um, h0m, tol=1e-5, max_iter=40)
-            du, dp, dh0 = P.backward(cell, pm, um, h0m, h, gm)
+            du, dp, dh0 = P.backward(cell, pm, um, h0m, _misaligned(hs), gm)
             torch.cuda.synchronize()
         finally:
             P.set_tile(0)
         assert int(iters.cpu()[1]) == 0
-        ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
         assert relerr(to_np(h), ref) <= bound
-        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
         assert relerr(to_np(du), rdu) <= bound and relerr(to_np(dp), rdp) <= bound and relerr(to_np(dh0), rdh0) <= bound
 
 
-def test_many_short_sequences_and_one_long(P, oracle_mod):
+def test_many_short_sequences_and_one_long(P, oracle_mod, as_stored):
     """Extreme aspect ratios: B*H large with tiny L, and one long sequence with few channels."""
     for cell, (B, L, H) in (("gru_diag", (300, 3, 40)), ("lstm_diag", (1, 20000, 8)), ("paralstm_diag", (64, 1, 130))):
         params, u, h0, g = problem(cell, B, L, H, seed=B + L)
-        h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
-        du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
-        torch.cuda.synchronize()
-        assert int(iters.cpu()[1]) == 0
         pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
         ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+        hs = as_stored(ref, u)
+        h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
+        du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
+        torch.cuda.synchronize()
+        assert int(iters.cpu()[1]) == 0
         assert relerr(to_np(h), ref) <= TOL_F32, (cell, B, L, H)
-        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
         assert relerr(to_np(du), rdu) <= TOL_F32 and relerr(to_np(dp), rdp) <= TOL_F32 and relerr(to_np(dh0), rdh0) <= TOL_F32
 
 
@@ -221,7 +224,7 @@ TILE_SHAPES = [(1, 1, 8, 16), (1, 2, 8, 16), (1, 2, 16, 4), (1, 2, 8, 8), (1, 1,
 
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
 @pytest.mark.parametrize("tile", TILE_SHAPES)
-def test_every_tile_shape(P, oracle_mod, cell, tile):
+def test_every_tile_shape(P, oracle_mod, as_stored, cell, tile):
     """Every compiled tile shape (channels per lane, segments per wave, steps
     per thread, waves per workgroup) on a problem spanning several tiles with
     ragged tails in L and H."""
@@ -229,11 +232,13 @@ def test_every_tile_shape(P, oracle_mod, cell, tile):
     print(f"tile {tile} {cell}", flush=True)
     params, u, h0, g = problem(cell, B, L, H, seed=4242)
     pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    hs = as_stored(ref, u)
     try:
         P.set_tile(*tile)
         h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
         try:
-            du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+            du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
         except RuntimeError as e:
             # wide LSTM tiles exceed the backward kernel's 64 KiB of LDS and are refused by the host
             if "UNSUPPORTED" in str(e) and cell != "gru_diag" and tile[0] * 64 // tile[1] * tile[3] >= 2048:
@@ -244,9 +249,8 @@ def test_every_tile_shape(P, oracle_mod, cell, tile):
         P.set_tile(0)
     it, st = (int(x) for x in iters.cpu())
     assert st == 0
-    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
     assert relerr(to_np(h), ref) <= TOL_F32
-    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
     assert relerr(to_np(du), rdu) <= TOL_F32
     assert relerr(to_np(dp), rdp) <= TOL_F32
     assert relerr(to_np(dh0), rdh0) <= TOL_F32
@@ -440,7 +444,7 @@ def test_affine_scan_matches_forward_substitution(P, oracle_mod, kind, reverse):
 
 
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
-def test_bf16_storage(P, oracle_mod, cell):
+def test_bf16_storage(P, oracle_mod, as_stored, cell):
     """bf16 storage, fp32 arithmetic: the oracle takes the bf16-rounded inputs
     as exact and computes in fp64; bound 2e-2."""
     B, L, H = 2, 300, 136
@@ -454,9 +458,10 @@ def test_bf16_storage(P, oracle_mod, cell):
     assert relerr(to_np(h), ref) <= TOL_BF16
     _, it32, _, _ = oracle_mod.newton(cell, pn, un, h0n, tol=1e-5, max_iter=40, precision="f32")
     assert abs(it - it32) <= 1
-    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    hs = as_stored(ref, h)                      # the oracle's states rounded to bf16, for both sides
+    du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
     torch.cuda.synchronize()
-    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(h), gn)
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
     assert relerr(to_np(du), rdu) <= TOL_BF16
     assert relerr(to_np(dp), rdp) <= TOL_BF16
     assert relerr(to_np(dh0), rdh0) <= TOL_BF16

@@ -27,7 +27,7 @@ def f64(t):
 
 def rounded(t):
     """The value the kernels' bf16 operand rounding gives (round to nearest even)."""
-    return t.to(torch.bfloat16).to(torch.float64).cpu().numpy()
+    return t.detach().to(torch.bfloat16).to(torch.float64).cpu().numpy()
 
 
 # (B, L, H, G, n_heads): dh = 64 .. 512, ragged row tiles, a ragged column tile (dh = 192)
@@ -90,29 +90,34 @@ def test_input_projection_backward(oracle_mod, shape, dtype):
     assert dx3 is None and db3 is None and torch.equal(dW3, dW)
 
 
-def test_projection_feeds_the_solver(oracle_mod):
-    """x -> u -> Newton solve -> backward -> du -> dx, dWx, dbias: the chain the
-    paper's cell runs, against the oracle's chain on the same rounded operands."""
+def test_projection_feeds_the_solver(oracle_mod, as_stored):
+    """x -> u -> Newton solve -> backward -> du -> dx, dWx, dbias: the chain the paper's cell runs,
+    stage by stage.  Each stage is given, on both sides, the oracle's result of the stage before
+    (in the storage type), so every comparison is at equal inputs and none of them was computed
+    on the GPU."""
     import paper_2510_21450_amd as P
     B, L, H, G, heads = 2, 400, 256, 3, 4
     x, Wx, bias, _ = problem((B, L, H, G, heads), torch.float32, seed=5200)
     params = torch.zeros(2, G, H, device="cuda")
     params[0] = normal(5200, 7, (G, H), std=0.3, device="cuda").clamp(-0.5, 0.5)
     g = normal(5200, 8, (B, L, 1, H), device="cuda")
+    ru = oracle_mod.input_projection(rounded(x), rounded(Wx), f64(bias), heads)
+    us = as_stored(ru, x)
+    rh = oracle_mod.seq_unroll("gru_diag", f64(params), f64(us), None)
+    hs = as_stored(rh, x)
+    rdu, _, _ = oracle_mod.backward("gru_diag", f64(params), f64(us), None, f64(hs), f64(g))
+    dus = as_stored(rdu, x)
+    rdx, rdW, _ = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(dus), heads)
+    _, _, rdb = oracle_mod.input_projection_backward(f64(x), f64(Wx), f64(dus), heads)
     u = P.input_projection(x, Wx, bias, n_heads=heads)
-    h, iters, _ = P.forward("gru_diag", params, u, None, tol=1e-5, max_iter=32)
-    du, dp, _ = P.backward("gru_diag", params, u, None, h, g, want_dh0=False)
-    dx, dW, db = P.input_projection_backward(x, Wx, du, n_heads=heads)
+    h, iters, _ = P.forward("gru_diag", params, us, None, tol=1e-5, max_iter=32)
+    du, dp, _ = P.backward("gru_diag", params, us, None, hs, g, want_dh0=False)
+    dx, dW, db = P.input_projection_backward(x, Wx, dus, n_heads=heads)
     torch.cuda.synchronize()
     assert int(iters.cpu()[1]) == 0
-    ru = oracle_mod.input_projection(rounded(x), rounded(Wx), f64(bias), heads)
     assert relerr(f64(u), ru) <= 1e-5
-    rh = oracle_mod.seq_unroll("gru_diag", f64(params), f64(u), None)
     assert relerr(f64(h), rh) <= 1e-5
-    rdu, _, _ = oracle_mod.backward("gru_diag", f64(params), f64(u), None, f64(h), f64(g))
     assert relerr(f64(du), rdu) <= 1e-5
-    rdx, rdW, _ = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(du), heads)
-    _, _, rdb = oracle_mod.input_projection_backward(f64(x), f64(Wx), f64(du), heads)
     assert relerr(f64(dx), rdx) <= 1e-5 and relerr(f64(dW), rdW) <= 1e-5 and relerr(f64(db), rdb) <= 1e-5
 
 
@@ -153,3 +158,34 @@ def test_projection_replays_from_a_graph():
         torch.cuda.synchronize()
         assert torch.equal(u, u_e) and torch.equal(dx, dx_e), rep
         assert torch.equal(dW, dW_e) and torch.equal(db, db_e), rep
+
+
+def test_layer_through_autograd(oracle_mod):
+    """rnn_layer = projection + solve inside a PyTorch graph: gradients of sum(w * h) with respect
+    to x, Wx, bias and the cell parameters against the oracle's chain.  Each side runs the whole
+    chain on its own from x, so intermediate results differ slightly before they are rounded to
+    bf16 as operands of the next product: where the two values of dL/du straddle a rounding
+    boundary the operands differ by one bf16 step (2^-8 relative) in that element.  With values
+    1e-5 apart that happens to about 1e-5 / 2^-8 = 0.3 % of the elements, and a sum over 3 dh
+    terms then moves by about sqrt(0.003) * 2^-8 = 2e-4 of one term's size, 1e-4 of the result's
+    maximum at most: the bound for dL/dx and dL/dWx here."""
+    import paper_2510_21450_amd as P
+    B, L, H, G, heads = 2, 300, 128, 3, 2
+    x, Wx, bias, _ = problem((B, L, H, G, heads), torch.float32, seed=5400)
+    params = torch.zeros(2, G, H, device="cuda")
+    params[0] = normal(5400, 7, (G, H), std=0.3, device="cuda").clamp(-0.5, 0.5)
+    w = normal(5400, 8, (B, L, 1, H), device="cuda")
+    for t in (x, Wx, bias, params):
+        t.requires_grad_(True)
+    h, iters = P.rnn_layer("gru_diag", x, Wx, bias, params, None, n_heads=heads, tol=1e-5, max_iter=32)
+    assert int(iters.cpu()[1]) == 0
+    (h * w).sum().backward()
+    ru = oracle_mod.input_projection(rounded(x), rounded(Wx), f64(bias), heads)
+    rh = oracle_mod.seq_unroll("gru_diag", f64(params), ru, None)
+    assert relerr(f64(h), rh) <= 1e-5
+    rdu, rdp, _ = oracle_mod.backward("gru_diag", f64(params), ru, None, rh, f64(w))
+    rdx, rdW, _ = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(torch.from_numpy(rdu).float()), heads)
+    _, _, rdb = oracle_mod.input_projection_backward(f64(x), f64(Wx), rdu, heads)
+    errs = (relerr(f64(params.grad), rdp), relerr(f64(bias.grad), rdb), relerr(f64(x.grad), rdx), relerr(f64(Wx.grad), rdW))
+    print(f"layer chain: rel err dparams, dbias, dx, dWx = {errs}", flush=True)
+    assert max(errs[:2]) <= 3e-5 and max(errs[2:]) <= 1e-4

@@ -7,6 +7,11 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
+# Where each side runs the whole chain on its own (forward solve, then the backward pass at its own
+# states) the gradients differ by the backward pass's own 1e-5 plus the effect of the <= 1e-5
+# difference between the two sets of states, which the adjoint recursion carries along a sequence.
+CHAIN_TOL = 3e-5
+
 from workloads import CONFIGS, make_inputs, cell_dims      # noqa: E402
 
 
@@ -55,20 +60,21 @@ def test_forward_and_backward_replay_from_a_graph(oracle_mod):
     assert relerr(f64(h), ref) <= 1e-5
 
 
-def test_runs_on_a_side_stream(oracle_mod):
+def test_runs_on_a_side_stream(oracle_mod, as_stored):
     import paper_2510_21450_amd as P
     w = CONFIGS["C3"].scaled(B=2, L=300, H=96)
     d = make_inputs(w, device="cuda")
+    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), None)
+    hs = as_stored(ref, d["u"])             # backward: both sides at the oracle's states
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(s):
         h, iters, _ = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=32)
-        du, dp, dh0 = P.backward(w.cell, d["params"], d["u"], None, h, d["g"])
+        du, dp, dh0 = P.backward(w.cell, d["params"], d["u"], None, hs, d["g"])
     s.synchronize()
     assert int(iters.cpu()[1]) == 0
-    ref = oracle_mod.seq_unroll(w.cell, f64(d["params"]), f64(d["u"]), None)
     assert relerr(f64(h), ref) <= 1e-5
-    rdu, rdp, rdh0 = oracle_mod.backward(w.cell, f64(d["params"]), f64(d["u"]), None, f64(h), f64(d["g"]))
+    rdu, rdp, rdh0 = oracle_mod.backward(w.cell, f64(d["params"]), f64(d["u"]), None, f64(hs), f64(d["g"]))
     assert relerr(f64(du), rdu) <= 1e-5 and relerr(f64(dp), rdp) <= 1e-5
 
 
@@ -120,7 +126,8 @@ def test_lookback_stress_many_small_tiles(cell, oracle_mod):
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense"])
 def test_autograd_wrapper_matches_oracle_gradients(cell, oracle_mod):
     """rnn_apply inside a PyTorch graph: loss = sum(w * h), gradients with respect
-    to params, u and h0 against the oracle's reverse sweep."""
+    to params, u and h0 against the oracle's chain (its own states, then its reverse sweep).
+    Each side runs forward and backward on its own here, so the bound is CHAIN_TOL."""
     import numpy as np
     import paper_2510_21450_amd as P
     from workloads.rng import normal, uniform_sym
@@ -139,9 +146,12 @@ def test_autograd_wrapper_matches_oracle_gradients(cell, oracle_mod):
     assert int(iters.cpu()[1]) == 0 and not iters.requires_grad
     (h * w).sum().backward()
     f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
-    rdu, rdp, rdh0 = oracle_mod.backward(cell, f64(params), f64(u), f64(h0), f64(h), f64(w))
+    ref = oracle_mod.seq_unroll(cell, f64(params), f64(u), f64(h0))
+    rdu, rdp, rdh0 = oracle_mod.backward(cell, f64(params), f64(u), f64(h0), ref, f64(w))
     rel = lambda a, b: float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30))
-    assert rel(f64(u.grad), rdu) <= 1e-5 and rel(f64(params.grad), rdp) <= 1e-5 and rel(f64(h0.grad), rdh0) <= 1e-5
+    errs = (rel(f64(h), ref), rel(f64(u.grad), rdu), rel(f64(params.grad), rdp), rel(f64(h0.grad), rdh0))
+    print(f"autograd chain {cell}: rel err h, du, dparams, dh0 = {errs}", flush=True)
+    assert errs[0] <= 1e-5 and max(errs[1:]) <= CHAIN_TOL
     # without h0 the wrapper asks for no dL/dh0
     u2 = u.detach().clone().requires_grad_(True)
     h2, _ = P.rnn_apply(cell, params.detach(), u2, None, tol=1e-5, max_iter=40)

@@ -14,6 +14,7 @@ from workloads.rng import normal, uniform_sym               # noqa: E402
 
 TOL_F32 = 1e-5
 TOL_BF16 = 2e-2
+TOL_CHAIN = 3e-5        # forward and backward run by each side on its own: the backward's 1e-5 plus the effect of states that differ by <= 1e-5
 ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh"}
 
 
@@ -45,7 +46,7 @@ SHAPES = [(1, 1, 8), (2, 33, 1), (2, 100, 24), (3, 257, 68), (2, 1000, 130), (1,
 
 @pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh"])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_user_cell_forward_backward_f32(oracle_mod, name, shape):
+def test_user_cell_forward_backward_f32(oracle_mod, as_stored, name, shape):
     import paper_2510_21450_amd as P
     cell = P.example_cell(name)
     oname = ORACLE_NAME[name]
@@ -69,9 +70,10 @@ def test_user_cell_forward_backward_f32(oracle_mod, name, shape):
         assert it == it32, (it, it32, tr.cpu().numpy()[:it], tr32)
     else:
         assert abs(it - it32) <= 1
-    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    hs = as_stored(ref, h)          # backward: both sides at the oracle's states
+    du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
     torch.cuda.synchronize()
-    rdu, rdp, rdh0 = oracle_mod.backward(oname, pn, un, h0n, to_np(h), gn)
+    rdu, rdp, rdh0 = oracle_mod.backward(oname, pn, un, h0n, to_np(hs), gn)
     assert relerr(to_np(du), rdu) <= TOL_F32
     assert relerr(to_np(dp), rdp) <= TOL_F32
     assert relerr(to_np(dh0), rdh0) <= TOL_F32
@@ -102,7 +104,7 @@ def test_user_cell_per_iteration_and_fused_paths_agree(oracle_mod, name, fused):
 
 
 @pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh"])
-def test_user_cell_bf16_storage(oracle_mod, name):
+def test_user_cell_bf16_storage(oracle_mod, as_stored, name):
     import paper_2510_21450_amd as P
     cell = P.example_cell(name)
     oname = ORACLE_NAME[name]
@@ -113,9 +115,10 @@ def test_user_cell_bf16_storage(oracle_mod, name):
     pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
     ref = oracle_mod.seq_unroll(oname, pn, un, h0n)
     assert relerr(to_np(h), ref) <= TOL_BF16
-    du, dp, dh0 = P.backward(cell, params, u, h0, h, g)
+    hs = as_stored(ref, h)
+    du, dp, dh0 = P.backward(cell, params, u, h0, hs, g)
     torch.cuda.synchronize()
-    rdu, rdp, rdh0 = oracle_mod.backward(oname, pn, un, h0n, to_np(h), gn)
+    rdu, rdp, rdh0 = oracle_mod.backward(oname, pn, un, h0n, to_np(hs), gn)
     assert relerr(to_np(du), rdu) <= TOL_BF16 and relerr(to_np(dp), rdp) <= TOL_BF16 and relerr(to_np(dh0), rdh0) <= TOL_BF16
 
 
@@ -127,6 +130,9 @@ def test_user_cell_through_autograd(oracle_mod):
     h, iters = P.rnn_apply(cell, params, u, h0, tol=1e-5, max_iter=40)
     assert int(iters.cpu()[1]) == 0
     (h * w).sum().backward()
-    rdu, rdp, rdh0 = oracle_mod.backward("rot_tanh", to_np(params), to_np(u), to_np(h0), to_np(h), to_np(w))
-    assert relerr(to_np(u.grad), rdu) <= TOL_F32 and relerr(to_np(params.grad), rdp) <= TOL_F32
-    assert relerr(to_np(h0.grad), rdh0) <= TOL_F32
+    # each side runs its own chain here: the oracle's reverse sweep is taken at the oracle's states
+    ref = oracle_mod.seq_unroll("rot_tanh", to_np(params), to_np(u), to_np(h0))
+    rdu, rdp, rdh0 = oracle_mod.backward("rot_tanh", to_np(params), to_np(u), to_np(h0), ref, to_np(w))
+    errs = (relerr(to_np(h), ref), relerr(to_np(u.grad), rdu), relerr(to_np(params.grad), rdp), relerr(to_np(h0.grad), rdh0))
+    print(f"autograd chain rot_tanh: rel err h, du, dparams, dh0 = {errs}", flush=True)
+    assert errs[0] <= TOL_F32 and max(errs[1:]) <= TOL_CHAIN
