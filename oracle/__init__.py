@@ -117,6 +117,20 @@ def seq_unroll(cell, params, u, h0=None, precision="f64"):
     return h
 
 
+def residual_norm(cell, params, u, h0, h, precision="f64"):
+    """App. A: max |h_l - f(h_{l-1}, u_l)| over the batch, all steps, state values and channels."""
+    lib = _lib(precision)
+    u_a, up = _c(u, precision)
+    B, L, G, H = u_a.shape
+    h_a, hp = _c(h, precision)
+    assert h_a.shape == (B, L, lib.oracle_state(cell_id(cell)), H)
+    _, pp = _c(params, precision)
+    _h0, h0p = _c(h0, precision)
+    fn = lib.oracle_residual_norm
+    fn.restype = ctypes.c_double if precision == "f64" else ctypes.c_float
+    return float(fn(cell_id(cell), B, L, H, pp, up, h0p, hp))
+
+
 def _solver(name, kind, J, r, precision):
     lib = _lib(precision)
     r_a, rp = _c(r, precision)

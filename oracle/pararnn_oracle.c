@@ -19,6 +19,8 @@
  *   - Sec. 3, Eq. (7b) / (8b) with diagonal A_*, C_* (Eq. (9)): the
  *     CIFG LSTM with peepholes (ParaLSTM) and its 2x2 Jacobian    -> cell 4
  *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
+ *   - App. A: the max-norm of the residual of Eq. (2), the
+ *     quantity its convergence figure plots per iteration         -> oracle_residual_norm
  *   - Sec. 3, Eq. (7a) / (7b): the input terms B_* x_l + b_* of all gates,
  *     with the multi-head (block-diagonal) input matrices of App. C     -> oracle_input_projection
  *     and the derivatives of that map                                   -> oracle_input_projection_backward
@@ -380,6 +382,35 @@ void oracle_seq_unroll(int cell, int B, int L, int H, const REAL *params, const 
         }
         free(zero);
     }
+}
+
+/* App. A (the convergence figure's observable): how far given states are from
+ * solving the stacked system Eq. (2), in max-norm:
+ *     max over b, l, state value, channel of | h_l - f(h_{l-1}, u_l) |,  h_0 = h0 (NULL = zeros).
+ * A NaN anywhere gives NaN. */
+REAL oracle_residual_norm(int cell, int B, int L, int H, const REAL *params, const REAL *u,
+                          const REAL *h0, const REAL *h)
+{
+    const int G = oracle_gates(cell), S = oracle_state(cell);
+    const size_t n = (size_t)S * H;
+    REAL *zero = (REAL *)calloc(n, sizeof(REAL)), *F = (REAL *)malloc(n * sizeof(REAL));
+    REAL m = 0;
+    int b, l;
+    size_t i;
+    for (b = 0; b < B; ++b)
+        for (l = 0; l < L; ++l) {
+            const REAL *hl = h + ((size_t)b * L + l) * n;
+            const REAL *hp = l == 0 ? (h0 ? h0 + (size_t)b * n : zero) : hl - n;
+            oracle_cell_step(cell, H, params, hp, u + ((size_t)b * L + l) * G * H, F);
+            for (i = 0; i < n; ++i) {
+                const REAL e = (REAL)fabs((double)(hl[i] - F[i]));
+                if (e > m || e != e) m = e;
+                if (m != m) break;
+            }
+        }
+    free(zero);
+    free(F);
+    return m;
 }
 
 /* ----------------------------------------------- linear solvers, one sequence */

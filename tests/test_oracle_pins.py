@@ -627,3 +627,80 @@ def test_input_projection_backward_matches_finite_differences(oracle_mod, n_head
             args1[which] = a1; args2[which] = a2
             fd = (loss(*args1) - loss(*args2)) / (2 * eps)
             assert abs(grad[idx] - fd) < 1e-7 * max(1.0, abs(fd)), (which, idx)
+
+
+# ------------------------------------------------------- residual max-norm (App. A)
+
+@pytest.mark.parametrize("cell", ALL_CELLS)
+def test_residual_norm_vanishes_on_the_recurrence_only(oracle_mod, cell):
+    """The states of Eq. (1) solve Eq. (2) exactly (the same function on the same numbers), with
+    the h0 they started from and with no other."""
+    o = oracle_mod
+    H = 64 if cell == "tanh_dense" else 5
+    params, u, h0 = rand_problem(o, cell, 2, 9, H, seed=71)
+    h = o.seq_unroll(cell, params, u, h0)
+    assert o.residual_norm(cell, params, u, h0, h) == 0.0
+    # with h0 left out only row 1 of Eq. (2) is violated: by f(0, u_1) - h_1
+    want = max(np.max(np.abs(o.cell_step(cell, params, np.zeros_like(h0[b]), u[b, 0]) - h[b, 0])) for b in range(2))
+    assert want > 1e-3
+    assert o.residual_norm(cell, params, u, None, h) == pytest.approx(want, rel=1e-14)
+
+
+def test_residual_norm_linear_cell_closed_form(oracle_mod):
+    """f = a h + u (footnote of Sec. 2): the residual of arbitrary states is a h_{l-1} + u_l - h_l,
+    typed out with numpy."""
+    o = oracle_mod
+    rng = np.random.default_rng(72)
+    B, L, H = 3, 7, 4
+    params = np.zeros((2, 1, H)); params[0] = rng.uniform(-0.9, 0.9, (1, H))
+    u = rng.normal(0, 1, (B, L, 1, H)); h = rng.normal(0, 1, (B, L, 1, H)); h0 = rng.normal(0, 1, (B, 1, H))
+    prev = np.concatenate([h0[:, None], h[:, :-1]], axis=1)
+    want = np.max(np.abs(params[0][None, None] * prev + u - h))
+    assert o.residual_norm("linear_diag", params, u, h0, h) == pytest.approx(want, rel=1e-15)
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag", "tanh_dense", "rot_tanh"])
+def test_residual_norm_of_one_perturbed_state(oracle_mod, cell):
+    """One state value of the exact trajectory moved by eps, at step l0: equation l0 is off by eps
+    and equation l0 + 1 by f(h_l0 + eps e) - h_{l0+1}; every other equation still holds.  Pins which
+    state each equation reads (a shift the wrong way, or a wrong batch / state index, changes the
+    value) and that the maximum runs over everything."""
+    o = oracle_mod
+    H = 64 if cell == "tanh_dense" else 3
+    B, L = 2, 6
+    params, u, h0 = rand_problem(o, cell, B, L, H, seed=73)
+    h = o.seq_unroll(cell, params, u, h0)
+    S = h.shape[2]
+    eps = 0.25
+    for b, l0, s, ch in [(0, 0, 0, 0), (1, 3, S - 1, H - 1), (1, L - 1, 0, 1)]:
+        hh = h.copy()
+        hh[b, l0, s, ch] += eps
+        nxt = 0.0 if l0 == L - 1 else np.max(np.abs(o.cell_step(cell, params, hh[b, l0], u[b, l0 + 1]) - h[b, l0 + 1]))
+        assert o.residual_norm(cell, params, u, h0, hh) == pytest.approx(max(eps, nxt), rel=1e-13), (b, l0, s, ch)
+    hh = h.copy()
+    hh[1, 2, 0, 0] = np.nan
+    assert math.isnan(o.residual_norm(cell, params, u, h0, hh))
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "paralstm_diag", "tanh_dense"])
+def test_residual_norm_along_newton(oracle_mod, cell):
+    """App. A's convergence figure: the residual max-norm of the Newton iterates drops to rounding
+    level within a handful of iterations, quadratically at the end (each value at most the square
+    root scale of the one before is too strict for the first steps, so: the last three values above
+    the floor shrink faster than linearly, and the floor is reached by iteration 7)."""
+    o = oracle_mod
+    H = 64 if cell == "tanh_dense" else 6
+    params, u, h0 = rand_problem(o, cell, 2, 200, H, seed=74)
+    norms = []
+    for k in range(9):
+        hk = o.newton(cell, params, u, h0, tol=-1.0, max_iter=k)[0]
+        norms.append(o.residual_norm(cell, params, u, h0, hk))
+    assert norms[0] > 1e-2                                   # the initial guess is not the solution
+    assert min(norms[:8]) < 1e-13, norms
+    above = [x for x in norms if x > 1e-12]
+    assert len(above) <= 7, norms
+    if len(above) >= 3:
+        assert above[-1] / above[-2] < above[-2] / above[-3], norms      # super-linear at the end
+    # App. A's guess h^0_l = f(h0, u_l) satisfies the first equation exactly
+    h_guess = o.newton(cell, params, u, h0, tol=-1.0, max_iter=0)[0]
+    assert o.residual_norm(cell, params, u[:, :1], h0, h_guess[:, :1]) == 0.0
