@@ -218,6 +218,18 @@ def main():
                        "bwd_gbs": ab["bwd"] * N / (sum(t_bwd) / len(t_bwd) * 1e-3) / 1e9})
         detail["bwd_frac_hbm"] = detail["bwd_gbs"] / HBM_PEAK_GBS
 
+    # not part of the timed step: the residual max-norm of the result (the paper's convergence
+    # observable), one pass over u and h
+    h, _, _ = P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
+    rn_out = torch.empty(1, dtype=torch.float32, device="cuda")
+    rn = lambda: P.residual_norm(w.cell, params, u, h0, h, out=rn_out)
+    rn()
+    t_rn = time_events(rn, 10)
+    G_, S_ = u.shape[2], h.shape[2]
+    detail["residual_norm"] = {"value": float(rn_out.cpu()), "ms": sum(t_rn) / len(t_rn),
+                               "bytes_per_elt": (G_ + S_) * u.element_size(),
+                               "gbs": (G_ + S_) * u.element_size() * N / (sum(t_rn) / len(t_rn) * 1e-3) / 1e9}
+
     if w.cell != "tanh_dense" and w.H % 256 == 0:
         # not part of the timed step: the input projection u = Bx + b in front of the solve and its
         # derivatives behind the backward pass, four heads (the paper's 400M .. 7B models), same shapes

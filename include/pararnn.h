@@ -204,6 +204,25 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
                      void *hip_stream);
 
 /*
+ * How far given states are from solving the stacked system of Sec. 2, Eq. (2),
+ * in max-norm: the quantity App. A's convergence figure plots per Newton
+ * iteration,
+ *     max over b, l, state value, channel of | h_l - f(h_{l-1}, u_l) |,  h_0 = h0.
+ * Evaluate it on the iterates of fixed-count solves (tol < 0, max_iter = k) to
+ * obtain that curve; pararnn_forward's own stopping test uses the size of the
+ * update instead.
+ *   params, u, h0  as for pararnn_forward (h0 may be NULL = zeros)
+ *   h              device [B][L][S][H], the states to test, in the storage type
+ *   out            device float[1]; overwritten.  A NaN among the inputs gives NaN.
+ * One pass over u and h (each read once), no workspace, asynchronous on the
+ * stream, nothing allocated.  Returns PARARNN_OK or a host-detected error as
+ * pararnn_forward does; the dense cell has pararnn_forward's restrictions
+ * (fp32, H = 64, 16-byte aligned pointers, else PARARNN_UNSUPPORTED).
+ */
+int pararnn_residual_norm(int cell, int dtype, const float *params, const void *u, const void *h0,
+                          const void *h, int B, int L, int H, float *out, void *hip_stream);
+
+/*
  * The linear solve on its own (the operation Alg. 1b performs), for testing
  * and profiling the scan without a cell: delta_l = J_l delta_{l-1} + r_l,
  * delta_0 = 0 (reverse = 0), or the adjoint

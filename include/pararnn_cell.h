@@ -123,6 +123,14 @@ template <class Impl> struct UserCell {
                                                                h, iters, delta_trace, workspace, workspace_bytes, \
                                                                static_cast<hipStream_t>(hip_stream));             \
     }                                                                                                             \
+    int name##_residual_norm(int dtype, const float *params, const void *u, const void *h0, const void *h,        \
+                             int B, int L, int H, float *out, void *hip_stream)                                   \
+    {                                                                                                             \
+        const int bad = pararnn::check_residual_args(dtype, params, u, h0, h, B, L, H, out);                      \
+        if (bad != PARARNN_OK) return bad;                                                                        \
+        return pararnn::residual_norm_diag<pararnn::UserCell<Impl>>(dtype, params, u, h0, h, B, L, H, out,        \
+                                                                    static_cast<hipStream_t>(hip_stream));        \
+    }                                                                                                             \
     int name##_backward(int dtype, const float *params, const void *u, const void *h0, const void *h,             \
                         const void *dL_dh, int B, int L, int H, void *dL_du, float *dL_dparams, void *dL_dh0,     \
                         void *workspace, size_t workspace_bytes, void *hip_stream)                                \

@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
                       "(there is no CPU fallback)")
 
 _lib = ctypes.CDLL(_LIB_PATH)
-for _name in ("pararnn_input_projection", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
+for _name in ("pararnn_input_projection", "pararnn_residual_norm", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
     if not hasattr(_lib, _name):
         raise ImportError(f"{_LIB_PATH} is older than this binding ({_name} is missing): rebuild it with "
                           "`python -m paper_2510_21450_amd.build`")
@@ -55,6 +55,9 @@ _lib.pararnn_affine_scan.argtypes = [_i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _sz
 
 _FWD_ARGS = [_i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _BWD_ARGS = [_i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_RES_ARGS = [_i, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp]
+_lib.pararnn_residual_norm.restype = _i
+_lib.pararnn_residual_norm.argtypes = [_i] + _RES_ARGS
 
 
 class _BuiltinCell:
@@ -69,6 +72,7 @@ class _BuiltinCell:
         self.ws_fused = lambda *a: _lib.pararnn_workspace_bytes_fused(c, *a)
         self.fwd = lambda *a: _lib.pararnn_forward(c, *a)
         self.bwd = lambda *a: _lib.pararnn_backward(c, *a)
+        self.res = lambda *a: _lib.pararnn_residual_norm(c, *a)
 
 
 class UserCell:
@@ -87,6 +91,8 @@ class UserCell:
         self.ws.argtypes = self.ws_fused.argtypes = [_i] * 5
         self.fwd.restype = self.bwd.restype = _i
         self.fwd.argtypes, self.bwd.argtypes = _FWD_ARGS, _BWD_ARGS
+        self.res = f("residual_norm")
+        self.res.restype, self.res.argtypes = _i, _RES_ARGS
 
 
 _builtin = {}
@@ -269,6 +275,25 @@ def backward(cell, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=Non
                    B, L, H, _ptr(du), _ptr(dparams), _ptr(dh0), _ptr(ws), ws.numel(), _stream(stream))
     _raise(code, f"{api.what}_backward")
     return du, dparams, dh0
+
+
+def residual_norm(cell, params, u, h0, h, stream=None, out=None):
+    """pararnn_residual_norm: max |h_l - f(h_{l-1}, u_l)| of the given states, as a device float[1]."""
+    G, S = cell_dims(cell)
+    B, L, Gu, H = u.shape
+    dt = u.dtype
+    _check(u, "u", dt, (B, L, G, H))
+    _check(params, "params", torch.float32)
+    _check(h, "h", dt, (B, L, S, H))
+    if h0 is not None:
+        _check(h0, "h0", dt, (B, S, H))
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=u.device)
+    _check(out, "out", torch.float32, (1,))
+    api = _api(cell)
+    code = api.res(DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), _ptr(h), B, L, H, _ptr(out), _stream(stream))
+    _raise(code, f"{api.what}_residual_norm")
+    return out
 
 
 _lib.pararnn_input_projection_workspace_bytes.restype = _sz

@@ -15,6 +15,10 @@ int dense_backward(int dtype, const float *W, const void *u, const void *h0, con
                    int L, int H, void *du, float *dW, void *dh0, void *workspace, size_t workspace_bytes,
                    hipStream_t st);
 
+// max |h_l - tanh(W h_{l-1} + u_l)| over everything (App. A), to a device float
+int dense_residual_norm(int dtype, const float *W, const void *u, const void *h0, const void *h, int B, int L, int H,
+                        float *out, hipStream_t st);
+
 // Timesteps per chunk of the dense scan, and its composition kernel alone:
 // A[b][c] = J_e ... J_s, J_l = diag(d_l) W, for the chunks 1 .. n_c-2 (the ones the
 // scan needs); ctrl_scratch is 256 bytes of device memory.

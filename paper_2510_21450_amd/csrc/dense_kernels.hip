@@ -67,6 +67,7 @@ struct DenseArgs {
     const float *g;      // dL/dh [B][L][64]
     float *du;           // out [B][L][64]: mu
     int rev;             // 1: scan step t of the recurrence is timestep L-1-t
+    unsigned int *norm;  // residual max-norm only: bits of the result, zero on entry
 };
 
 // row of the [B][L][64] arrays that scan step t of sequence b touches
@@ -113,10 +114,12 @@ __device__ __forceinline__ void load_w_operand16(const float *W, int w, int n, i
 // operand of k-step (ww, v) is component v of the float4 at channels
 // 16ww + 4g of the previous state, read straight from memory.
 // mode 0: write d = 1 - F^2 and r = F - h for the current iterate;
-// mode 1: write the initial guess h = tanh(W h0 + u) (App. A).
+// mode 1: write the initial guess h = tanh(W h0 + u) (App. A);
+// mode 2: write nothing but max |F - h| over all rows to a.norm (no control block is read).
 __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
 {
-    if (a.ctrl->stop) return;
+    if (mode != 2 && a.ctrl->stop) return;
+    float nmax = 0.0f;
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n = lane & 15, g = lane >> 4;
     const int chn = 16 * w + 4 * g;
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
         f4v uv = zero, hv = zero;
         if (ok) {
             uv = *reinterpret_cast<const f4v *>(a.u + row * DH + chn);
-            if (mode == 0) hv = *reinterpret_cast<const f4v *>(a.h + row * DH + chn);
+            if (mode != 1) hv = *reinterpret_cast<const f4v *>(a.h + row * DH + chn);
         }
         f4v acc0 = zero, acc1 = zero;
 #pragma unroll
@@ -159,10 +162,25 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
             for (int v = 0; v < 4; ++v) F[v] = fast_tanh(y[v]);
             if (mode == 1) {
                 *reinterpret_cast<f4v *>(a.h + row * DH + chn) = F;
+            } else if (mode == 2) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) nmax = nanmax(nmax, fabsf(hv[v] - F[v]));
             } else {
                 *reinterpret_cast<f4v *>(a.d + row * DH + chn) = 1.0f - F * F;
                 *reinterpret_cast<f4v *>(a.r + row * DH + chn) = F - hv;
             }
+        }
+    }
+    if (mode == 2) {
+        // one atomic per workgroup: they all go to one address
+        __shared__ float s_nmax[4];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) nmax = nanmax(nmax, __shfl_xor(nmax, off, 64));
+        if (lane == 0) s_nmax[w] = nmax;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            nmax = nanmax(nanmax(s_nmax[0], s_nmax[1]), nanmax(s_nmax[2], s_nmax[3]));
+            atomicMax(a.norm, nmax != nmax ? 0x7fc00000u : __float_as_uint(nmax));
         }
     }
 }
@@ -788,6 +806,25 @@ int dense_backward(int dtype, const float *W, const void *u, const void *h0, con
     hipLaunchKernelGGL(dense_dw_kernel, dim3(wv / 4), dim3(256), 0, st, a, part, rows_per_wave);
     if (hipGetLastError() != hipSuccess) return PARARNN_HIP_ERROR;
     return launch_param_reduce(part, dW, wv, DH * DH, st) == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
+}
+
+int dense_residual_norm(int dtype, const float *W, const void *u, const void *h0, const void *h, int B, int L, int H,
+                        float *out, hipStream_t st)
+{
+    if (dtype != PARARNN_F32 || H != DH) return PARARNN_UNSUPPORTED;
+    if (((uintptr_t)W | (uintptr_t)u | (uintptr_t)h | (uintptr_t)h0) % 16) return PARARNN_UNSUPPORTED;
+    DenseArgs a;
+    memset(&a, 0, sizeof(a));
+    a.W = W; a.u = static_cast<const float *>(u); a.h0 = static_cast<const float *>(h0);
+    a.h = const_cast<float *>(static_cast<const float *>(h));        // mode 2 only reads it
+    a.B = B; a.L = L;
+    a.norm = reinterpret_cast<unsigned int *>(out);
+    if (launch_zero_words(a.norm, 1, st) != hipSuccess) return PARARNN_HIP_ERROR;
+    const size_t res_items = ((size_t)B * L + 15) / 16;
+    const size_t res_cap = (size_t)device_cu_count() * 4;
+    const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
+    hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 2);
+    return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
 int dense_forward(int dtype, const float *W, const void *u, const void *h0, int B, int L, int H, float tol,

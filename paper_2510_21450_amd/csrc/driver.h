@@ -323,6 +323,38 @@ int forward_solve(const CellInfo &ci, int dtype, const float *params, const void
     return forward_diag<Cell>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
 }
 
+// Residual max-norm of given states (App. A); out is a device float.
+inline int check_residual_args(int dtype, const float *params, const void *u, const void *h0, const void *h, int B,
+                               int L, int H, float *out)
+{
+    if (dtype != PARARNN_F32 && dtype != PARARNN_BF16) return PARARNN_INVALID_ARG;
+    if (!dims_ok(B, L, H) || !params || !u || !h || !out) return PARARNN_INVALID_ARG;
+    const size_t esz = dtype == PARARNN_BF16 ? 2 : 4;
+    if (!aligned(params, 4) || !aligned(out, 4) || !aligned(u, esz) || !aligned(h, esz) || (h0 && !aligned(h0, esz)))
+        return PARARNN_INVALID_ARG;
+    return PARARNN_OK;
+}
+
+template <class Cell>
+int residual_norm_diag(int dtype, const float *params, const void *u, const void *h0, const void *h, int B, int L,
+                       int H, float *out, hipStream_t st)
+{
+    const size_t esz = dtype == PARARNN_BF16 ? 2 : 4;
+    int al = align_elems(esz, {u, h, h0});
+    const int alp = align_elems(4, {params});
+    if (alp < al) al = alp;
+    const int vec = (H % 4 == 0 && al >= 4) ? 4 : (H % 2 == 0 && al >= 2) ? 2 : 1;
+    ResArgs a;
+    memset(&a, 0, sizeof(a));
+    a.B = B; a.L = L; a.H = H;
+    a.params = params; a.u = u; a.h0 = h0; a.h = h;
+    a.out = reinterpret_cast<unsigned int *>(out);
+    if (launch_zero_words(a.out, 1, st) != hipSuccess) return PARARNN_HIP_ERROR;
+    const hipError_t e = dtype == PARARNN_BF16 ? Kernels<Cell, unsigned short>::residual_norm(vec, a, st)
+                                               : Kernels<Cell, float>::residual_norm(vec, a, st);
+    return e == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
+}
+
 // A backward pass with checked arguments.
 template <class Cell>
 int backward_pass(const CellInfo &ci, int dtype, const float *params, const void *u, const void *h0, const void *h,

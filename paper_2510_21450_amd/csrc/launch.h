@@ -24,6 +24,7 @@ struct TileCfg {
 
 template <class Cell, typename UT> struct Kernels {
     static hipError_t init_guess(int vec, const FwdArgs &a, hipStream_t st);
+    static hipError_t residual_norm(int vec, const ResArgs &a, hipStream_t st);
     // fold_guess: this is iteration 1 and the initial guess is computed inside it
     static hipError_t newton_iter(const TileCfg &cfg, const FwdArgs &a, bool fold_guess, hipStream_t st);
     static hipError_t backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st);
@@ -35,6 +36,8 @@ hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *
                         hipStream_t st);
 // ctrl may be NULL; otherwise the pass is skipped on the device when ctrl->h_final is set
 hipError_t launch_store_bf16(const float *src, void *dst, size_t n, const Ctrl *ctrl, hipStream_t st);
+// n 32-bit words of zeros, written by a kernel (no memset node when a caller captures a graph)
+hipError_t launch_zero_words(unsigned int *dst, int n, hipStream_t st);
 hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st);
 int device_cu_count();
 

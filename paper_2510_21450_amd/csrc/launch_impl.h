@@ -51,6 +51,27 @@ hipError_t Kernels<Cell, UT>::init_guess(int vec, const FwdArgs &a, hipStream_t 
 }
 
 template <class Cell, typename UT>
+hipError_t Kernels<Cell, UT>::residual_norm(int vec, const ResArgs &a, hipStream_t st)
+{
+    if constexpr (IsRaw<Cell>::value) {
+        return hipErrorInvalidValue;
+    } else {
+        const size_t n = (size_t)a.B * ((a.L + kResRun - 1) / kResRun) * (a.H / vec);
+        size_t blocks = (n + 255) / 256;
+        const size_t cap = (size_t)device_cu_count() * 8;
+        if (blocks > cap) blocks = cap;
+#define PARARNN_CASE(V)                                                                       \
+    if (vec == V) {                                                                           \
+        hipLaunchKernelGGL((residual_norm_kernel<Cell, V, UT>), dim3((unsigned)blocks), dim3(256), 0, st, a); \
+        return hipGetLastError();                                                             \
+    }
+        PARARNN_VECS(PARARNN_CASE)
+#undef PARARNN_CASE
+        return hipErrorInvalidValue;
+    }
+}
+
+template <class Cell, typename UT>
 hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, bool fold_guess, hipStream_t st)
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \

@@ -174,6 +174,26 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
     return PARARNN_INVALID_ARG;
 }
 
+int pararnn_residual_norm(int cell, int dtype, const float *params, const void *u, const void *h0, const void *h,
+                          int B, int L, int H, float *out, void *hip_stream)
+{
+    CellInfo ci;
+    if (!cell_info(cell, &ci)) return PARARNN_INVALID_ARG;
+    const int bad = check_residual_args(dtype, params, u, h0, h, B, L, H, out);
+    if (bad != PARARNN_OK) return bad;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+#define PARARNN_RES(Cell) residual_norm_diag<Cell>(dtype, params, u, h0, h, B, L, H, out, st)
+    switch (cell) {
+    case PARARNN_TANH_DENSE: return dense_residual_norm(dtype, params, u, h0, h, B, L, H, out, st);
+    case PARARNN_GRU_DIAG: return PARARNN_RES(GruDiag);
+    case PARARNN_LSTM_DIAG: return PARARNN_RES(LstmDiag);
+    case PARARNN_LINEAR_DIAG: return PARARNN_RES(LinearDiag);
+    case PARARNN_PARALSTM_DIAG: return PARARNN_RES(ParaLstmDiag);
+    }
+#undef PARARNN_RES
+    return PARARNN_INVALID_ARG;
+}
+
 }  // extern "C" (reopened below, after the scan helpers)
 
 namespace {

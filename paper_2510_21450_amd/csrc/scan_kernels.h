@@ -67,6 +67,16 @@ struct FwdArgs {
     float tol;
 };
 
+// arguments of the residual max-norm (App. A)
+struct ResArgs {
+    int B, L, H;
+    const float *params;
+    const void *u;       // [B][L][G][H]
+    const void *h0;      // [B][S][H] or NULL
+    const void *h;       // states [B][L][S][H] in storage type
+    unsigned int *out;   // bits of the result, a non-negative float (or a NaN); zero on entry
+};
+
 struct BwdArgs {
     ScanGeom g;
     const float *params;
@@ -750,6 +760,76 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             ctrl->gmax_bits = 0u;
             __threadfence();
         }
+    }
+}
+
+// Residual max-norm of given states (App. A, the observable of the convergence
+// figure): max |h_l - f(h_{l-1}, u_l)| over everything.  A thread owns VEC channels
+// and kResRun consecutive steps, so each state row is read once as h_l and carried
+// in registers as h_{l-1} of the next step (plus one extra row per run).  One
+// atomic max per workgroup; NaNs propagate (their bit pattern orders above +inf).
+constexpr int kResRun = 8;
+
+template <class Cell, int VEC, typename UT>
+__global__ __launch_bounds__(256) void residual_norm_kernel(const ResArgs a)
+{
+    constexpr int S = Cell::S, G = Cell::G, PR = Cell::PR;
+    __shared__ float s_max[4];
+    const int hv = a.H / VEC;
+    const int n_runs = (a.L + kResRun - 1) / kResRun;
+    const size_t n = (size_t)a.B * n_runs * hv;
+    const UT *u = static_cast<const UT *>(a.u), *h = static_cast<const UT *>(a.h);
+    float m = 0.0f;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+        const int ch = (int)(idx % hv) * VEC;
+        const size_t br = idx / hv;
+        const int l0 = (int)(br % n_runs) * kResRun;
+        const size_t b = br / n_runs;
+        const int l1 = min(a.L, l0 + kResRun);
+        float p[VEC][PR], hp[S][VEC];
+#pragma unroll
+        for (int r = 0; r < PR; ++r) {
+            float tmp[VEC];
+            load_vec<VEC>(a.params + (size_t)r * a.H + ch, tmp);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) hp[s][v] = 0.0f;
+            if (l0 > 0) load_vec<VEC>(h + ((b * a.L + l0 - 1) * S + s) * a.H + ch, hp[s]);
+            else if (a.h0) load_vec<VEC>(static_cast<const UT *>(a.h0) + (b * S + s) * a.H + ch, hp[s]);
+        }
+        for (int l = l0; l < l1; ++l) {
+            const size_t row = b * a.L + l;
+            float uu[G][VEC], hl[S][VEC];
+#pragma unroll
+            for (int q = 0; q < G; ++q) load_vec<VEC>(u + (row * G + q) * a.H + ch, uu[q]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) load_vec<VEC>(h + (row * S + s) * a.H + ch, hl[s]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float h1[S], u1[G], F[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) h1[s] = hp[s][v];
+#pragma unroll
+                for (int q = 0; q < G; ++q) u1[q] = uu[q][v];
+                Cell::step(p[v], h1, u1, F);
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    m = nanmax(m, fabsf(hl[s][v] - F[s]));
+                    hp[s][v] = hl[s][v];
+                }
+            }
+        }
+    }
+    m = wave_nanmax(m);
+    if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3]));
+        atomicMax(a.out, m != m ? 0x7fc00000u : __float_as_uint(m));
     }
 }
 

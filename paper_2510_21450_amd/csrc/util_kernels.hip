@@ -22,6 +22,12 @@ __global__ void reset_kernel(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, 
     if (i == 0 && (n_rec & 1)) rec[n_rec - 1] = 0ull;
 }
 
+__global__ void zero_words_kernel(unsigned int *dst, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0u;
+}
+
 // bf16 storage: round the converged fp32 iterate once into the output.
 __global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsigned short *dst, size_t n4,
                                                          const Ctrl *ctrl)
@@ -83,6 +89,12 @@ hipError_t launch_reset(Ctrl *ctrl, unsigned long long *rec, size_t n_rec, int *
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ctrl, rec, n_rec, iters_out,
                        status0);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_words(unsigned int *dst, int n, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_words_kernel, dim3((n + 63) / 64), dim3(64), 0, st, dst, n);
     return hipGetLastError();
 }
 

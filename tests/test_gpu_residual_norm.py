@@ -1,0 +1,152 @@
+"""GPU parity of pararnn_residual_norm (App. A: the max-norm of the residual of the
+stacked system, the observable of the paper's convergence figure) against the CPU
+oracle.
+
+Both sides are given the same states: the oracle's Newton iterates after k
+iterations, converted to the storage type on the CPU.  The kernel evaluates f in
+fp32 with hardware exp / rcp (absolute error of a few 1e-7 on values of order 1),
+the oracle in fp64: |got - ref| <= 1e-4 ref + 1e-6."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, make_inputs              # noqa: E402
+from workloads.rng import normal, uniform_sym           # noqa: E402
+
+ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh"}
+
+
+def f64(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+def close(got, ref):
+    return abs(got - ref) <= 1e-4 * ref + 1e-6
+
+
+def problem(P, cell, B, L, H, seed, dtype=torch.float32, h0=True):
+    G, S = P.cell_dims(cell)
+    name = cell if isinstance(cell, str) else cell.name
+    dev = "cuda"
+    if name == "tanh_dense":
+        params = normal(seed, 5, (H, H), std=0.8 / H ** 0.5, device=dev)
+    elif name == "rot_tanh":
+        params = uniform_sym(seed, 2, (2, H), 0.6, device=dev)
+    elif name == "paralstm_diag":
+        params = torch.zeros(8, H, device=dev)
+        params[:5] = uniform_sym(seed, 2, (5, H), 0.9, device=dev)
+        params[5:] = normal(seed, 6, (3, H), std=0.3, device=dev)
+    else:
+        params = torch.zeros(2, G, H, device=dev)
+        params[0] = uniform_sym(seed, 2, (G, H), 0.9, device=dev)
+        params[1] = normal(seed, 6, (G, H), std=0.3, device=dev)
+    u = normal(seed, 1, (B, L, G, H), dtype=dtype, device=dev)
+    h0v = normal(seed, 3, (B, S, H), std=0.3, dtype=dtype, device=dev) if h0 else None
+    return params, u, h0v
+
+
+SHAPES = [(1, 1, 8), (2, 7, 1), (2, 33, 6), (3, 257, 68), (2, 1000, 130), (1, 64, 256)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag", "linear_diag"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_residual_norm_of_newton_iterates(oracle_mod, as_stored, cell, shape, dtype):
+    import paper_2510_21450_amd as P
+    B, L, H = shape
+    print(f"residual norm {cell} {shape} {dtype}", flush=True)
+    params, u, h0 = problem(P, cell, B, L, H, seed=6000 + L + H, dtype=dtype)
+    pn, un, h0n = f64(params), f64(u), f64(h0)
+    for k in (0, 1, 3):
+        hk = as_stored(oracle_mod.newton(cell, pn, un, h0n, tol=-1.0, max_iter=k)[0], u)
+        ref = oracle_mod.residual_norm(cell, pn, un, h0n, f64(hk))
+        got = float(P.residual_norm(cell, params, u, h0, hk).cpu())
+        assert close(got, ref), (k, got, ref)
+    # without h0 (zeros), and an unaligned view
+    ref = oracle_mod.residual_norm(cell, pn, un, None, f64(hk))
+    assert close(float(P.residual_norm(cell, params, u, None, hk).cpu()), ref)
+    buf = torch.empty(hk.numel() + 1, dtype=dtype, device="cuda")
+    hm = buf[1:].view(hk.shape)
+    hm.copy_(hk)
+    assert close(float(P.residual_norm(cell, params, u, None, hm).cpu()), ref)
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (2, 17), (3, 50), (5, 257)])
+def test_residual_norm_dense(oracle_mod, as_stored, shape):
+    import paper_2510_21450_amd as P
+    B, L = shape
+    params, u, h0 = problem(P, "tanh_dense", B, L, 64, seed=6100 + L)
+    pn, un, h0n = f64(params), f64(u), f64(h0)
+    for k in (0, 2):
+        hk = as_stored(oracle_mod.newton("tanh_dense", pn, un, h0n, tol=-1.0, max_iter=k)[0], u)
+        for h0_t, h0_n in ((h0, h0n), (None, None)):
+            ref = oracle_mod.residual_norm("tanh_dense", pn, un, h0_n, f64(hk))
+            got = float(P.residual_norm("tanh_dense", params, u, h0_t, hk).cpu())
+            assert close(got, ref), (k, got, ref)
+    with pytest.raises(RuntimeError, match="UNSUPPORTED"):
+        P.residual_norm("tanh_dense", params, u.bfloat16(), None, hk.bfloat16())
+
+
+@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh"])
+def test_residual_norm_user_cells(oracle_mod, as_stored, name):
+    import paper_2510_21450_amd as P
+    cell = P.example_cell(name)
+    params, u, h0 = problem(P, cell, 2, 300, 70, seed=6200)
+    pn, un, h0n = f64(params), f64(u), f64(h0)
+    for k in (0, 2):
+        hk = as_stored(oracle_mod.newton(ORACLE_NAME[name], pn, un, h0n, tol=-1.0, max_iter=k)[0], u)
+        ref = oracle_mod.residual_norm(ORACLE_NAME[name], pn, un, h0n, f64(hk))
+        assert close(float(P.residual_norm(cell, params, u, h0, hk).cpu()), ref)
+
+
+def test_residual_norm_propagates_nan_and_overwrites_out(oracle_mod, as_stored):
+    import paper_2510_21450_amd as P
+    params, u, h0 = problem(P, "gru_diag", 2, 100, 24, seed=6300)
+    h = as_stored(oracle_mod.seq_unroll("gru_diag", f64(params), f64(u), f64(h0)), u)
+    out = torch.full((1,), 123.0, device="cuda")
+    P.residual_norm("gru_diag", params, u, h0, h, out=out)
+    assert 0.0 <= float(out.cpu()) <= 1e-6                 # the recurrence's states, to fp32 rounding
+    hn = h.clone()
+    hn[1, 57, 0, 13] = float("nan")
+    assert math.isnan(float(P.residual_norm("gru_diag", params, u, h0, hn).cpu()))
+
+
+def test_convergence_curve_of_the_solver(oracle_mod):
+    """App. A's figure with the library alone: fixed-count solves of k = 0..6 iterations, the
+    residual max-norm of each.  Each side runs its own chain here; the values above 1e-3 agree with
+    the oracle's curve to 1 %, and the curve reaches the fp32 floor by iteration 5."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2"].scaled(B=2, L=2048, H=128)
+    d = make_inputs(w, device="cuda")
+    pn, un = f64(d["params"]), f64(d["u"])
+    curve, ref_curve = [], []
+    for k in range(7):
+        h, iters, _ = P.forward(w.cell, d["params"], d["u"], None, tol=-1.0, max_iter=k)
+        curve.append(float(P.residual_norm(w.cell, d["params"], d["u"], None, h).cpu()))
+        hk = oracle_mod.newton(w.cell, pn, un, None, tol=-1.0, max_iter=k)[0]
+        ref_curve.append(oracle_mod.residual_norm(w.cell, pn, un, None, hk))
+    print("residual max-norm per iteration:", curve, "oracle:", ref_curve, flush=True)
+    for got, ref in zip(curve, ref_curve):
+        if ref > 1e-3:
+            assert abs(got - ref) <= 1e-2 * ref, (curve, ref_curve)
+    assert curve[0] > 1e-2 and min(curve[:6]) <= 5e-6, curve
+
+
+def test_residual_norm_config_2_full_size(oracle_mod, as_stored):
+    """Benchmark configuration 2 (2^26 timestep-channels), the launch the benchmark times: the
+    oracle's iterate after two Newton iterations, given to both sides."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C2"]
+    d = make_inputs(w, device="cuda")
+    pn, un = f64(d["params"]), f64(d["u"])
+    print("C2 residual norm: oracle iterate", flush=True)
+    hk = as_stored(oracle_mod.newton(w.cell, pn, un, None, tol=-1.0, max_iter=2)[0], d["u"])
+    print("C2 residual norm: oracle norm", flush=True)
+    ref = oracle_mod.residual_norm(w.cell, pn, un, None, f64(hk))
+    got = float(P.residual_norm(w.cell, d["params"], d["u"], None, hk).cpu())
+    print(f"C2 residual norm after 2 iterations: {got} (oracle {ref})", flush=True)
+    assert ref > 1e-4 and close(got, ref)

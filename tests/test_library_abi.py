@@ -239,3 +239,20 @@ def test_solve_plan(lib):
     finally:
         lib.pararnn_set_fused(1)
         lib.pararnn_set_fused_head(5)
+
+
+def test_residual_norm_host_checks(lib):
+    """Refusals of pararnn_residual_norm that need no device."""
+    vp, i = ctypes.c_void_p, ctypes.c_int
+    f = lib.pararnn_residual_norm
+    f.restype = i
+    f.argtypes = [i, i, vp, vp, vp, vp, i, i, i, vp, vp]
+    p = 0x1000
+    assert f(0, 0, p, p, None, p, 1, 4, 8, None, None) == 2            # out NULL
+    assert f(0, 0, p, None, None, p, 1, 4, 8, p, None) == 2            # u NULL
+    assert f(9, 0, p, p, None, p, 1, 4, 8, p, None) == 2               # unknown cell
+    assert f(0, 2, p, p, None, p, 1, 4, 8, p, None) == 2               # unknown dtype
+    assert f(0, 0, p, p, None, p, 1, 0, 8, p, None) == 2               # L = 0
+    assert f(0, 0, p, p + 2, None, p, 1, 4, 8, p, None) == 2           # fp32 u at an odd 2-byte address
+    assert f(2, 1, p, p, None, p, 1, 4, 64, p, None) == 6              # dense cell: fp32 only
+    assert f(2, 0, p, p, None, p, 1, 4, 32, p, None) == 6              # dense cell: H = 64 only
