@@ -43,6 +43,7 @@
  *                         workspace, workspace_bytes, hip_stream);
  *     int    name_backward(int dtype, params, u, h0, h, dL_dh, B, L, H, dL_du, dL_dparams, dL_dh0,
  *                          workspace, workspace_bytes, hip_stream);
+ *     int    name_residual_norm(int dtype, params, u, h0, h, B, L, H, out, hip_stream);
  * with the semantics, status codes and error behaviour of the pararnn_* functions
  * of the same name.
  */

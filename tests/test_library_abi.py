@@ -164,7 +164,8 @@ def test_user_cell_libraries_export_their_abi(lib, name, gsp):
         from paper_2510_21450_amd import build
         build.build_examples()
     ul = ctypes.CDLL(path)
-    for fn in ("gates", "state", "param_rows", "workspace_bytes", "workspace_bytes_fused", "forward", "backward"):
+    for fn in ("gates", "state", "param_rows", "workspace_bytes", "workspace_bytes_fused", "forward", "backward",
+               "residual_norm"):
         assert hasattr(ul, f"{name}_{fn}")
     f = lambda s: getattr(ul, f"{name}_{s}")
     assert (f("gates")(), f("state")(), f("param_rows")()) == gsp
@@ -186,6 +187,11 @@ def test_user_cell_libraries_export_their_abi(lib, name, gsp):
     bw.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, sz, vp]
     assert bw(0, p, p, None, p, None, 1, 8, 8, p, p, None, p, 1 << 20, None) == 2       # dL_dh NULL
     assert bw(0, p, p, None, p, p, 1, 8, 8, p, p, None, p, 16, None) == 3
+    rn = f("residual_norm")
+    rn.restype = ctypes.c_int
+    rn.argtypes = [i, vp, vp, vp, vp, i, i, i, vp, vp]
+    assert rn(0, p, p, None, p, 1, 8, 8, None, None) == 2                                # out NULL
+    assert rn(0, p, p, None, p, 0, 8, 8, p, None) == 2                                   # B = 0
     # the settings are the main library's: switching fused launches off shrinks this library's workspace too
     big = ws(0, 4, 4096, 256, 0)
     lib.pararnn_set_fused(0)
