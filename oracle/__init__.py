@@ -152,8 +152,10 @@ def parallel_reduce(kind, J, r, precision="f64"):
     return _solver("oracle_parallel_reduce", kind, J, r, precision)
 
 
-def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64"):
-    """Alg. 1a with Eq. (4). Returns (h, iters, status, trace[iters])."""
+def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64", jacobian="full"):
+    """Alg. 1a with Eq. (4). Returns (h, iters, status, trace[iters]).
+    jacobian="diagonal": the quasi-Newton variant (every J_l replaced by its diagonal)."""
+    assert jacobian in ("full", "diagonal")
     lib = _lib(precision)
     u_a, up = _c(u, precision)
     B, L, G, H = u_a.shape
@@ -164,11 +166,12 @@ def newton(cell, params, u, h0=None, tol=1e-6, max_iter=64, precision="f64"):
     iters = ctypes.c_int(0)
     trace = np.zeros(max(max_iter, 1), dtype=_np_t(precision))
     real = ctypes.c_double if precision == "f64" else ctypes.c_float
-    lib.oracle_newton.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 3 + [real, ctypes.c_int,
-                                  ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
-    st = lib.oracle_newton(cell_id(cell), B, L, H, pp, up, h0p, tol, max_iter,
-                           h.ctypes.data_as(ctypes.c_void_p), ctypes.byref(iters),
-                           trace.ctypes.data_as(ctypes.c_void_p))
+    fn = lib.oracle_newton if jacobian == "full" else lib.oracle_newton_diag
+    fn.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 3 + [real, ctypes.c_int,
+                   ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
+    st = fn(cell_id(cell), B, L, H, pp, up, h0p, tol, max_iter,
+            h.ctypes.data_as(ctypes.c_void_p), ctypes.byref(iters),
+            trace.ctypes.data_as(ctypes.c_void_p))
     return h, iters.value, st, trace[:iters.value].copy()
 
 

@@ -19,6 +19,8 @@
  *   - Sec. 3, Eq. (7b) / (8b) with diagonal A_*, C_* (Eq. (9)): the
  *     CIFG LSTM with peepholes (ParaLSTM) and its 2x2 Jacobian    -> cell 4
  *   - App. A: the initial guess h^0_l = f(h_0, x_l)               -> oracle_newton
+ *   - Sec. 1 / Sec. 2.1: the quasi-Newton variant of prior work, Newton with
+ *     every Jacobian replaced by its diagonal                     -> oracle_newton_diag
  *   - App. A: the max-norm of the residual of Eq. (2), the
  *     quantity its convergence figure plots per iteration         -> oracle_residual_norm
  *   - Sec. 3, Eq. (7a) / (7b): the input terms B_* x_l + b_* of all gates,
@@ -337,6 +339,20 @@ static void jac_apply(int kind, int H, const REAL *J, const REAL *x, REAL *y)
     }
 }
 
+/* J <- diag(J): zero every entry d(out_i)/d(in_j) with i != j (state values of all channels
+ * counted as one vector, so the 2x2 blocks lose J_ch and J_hc) */
+static void jac_keep_diagonal(int kind, int H, REAL *J)
+{
+    int i, j;
+    if (kind == JAC_BLOCK2) {
+        for (j = 0; j < H; ++j) J[1 * H + j] = J[2 * H + j] = 0;
+    } else if (kind != JAC_DIAG) {
+        for (i = 0; i < H; ++i)
+            for (j = 0; j < H; ++j)
+                if (i != j) J[(size_t)i * H + j] = 0;
+    }
+}
+
 /* C = A B for two Jacobians of the same kind */
 static void jac_mul(int kind, int H, const REAL *A, const REAL *Bm, REAL *C)
 {
@@ -482,9 +498,11 @@ static REAL nanmax(REAL m, REAL a) { return (a > m || a != a) ? a : m; }
  *       delta = forward substitution;  h^k = h^{k-1} + delta
  *       m_k = max |delta| over the whole batch;  stop when m_k <= tol
  * tol < 0: run exactly max_iter iterations.  trace (or NULL) receives m_k.
- * iters = number of linear solves performed.  Returns the status. */
-int oracle_newton(int cell, int B, int L, int H, const REAL *params, const REAL *u, const REAL *h0,
-                  REAL tol, int max_iter, REAL *h, int *iters, REAL *trace)
+ * iters = number of linear solves performed.  Returns the status.
+ * diag_only != 0: the quasi-Newton variant Sec. 1 and Sec. 2.1 mention (prior work): every
+ * J_l is replaced by its diagonal before the linear solve, nothing else changes. */
+static int newton_impl(int cell, int B, int L, int H, const REAL *params, const REAL *u, const REAL *h0,
+                       REAL tol, int max_iter, REAL *h, int *iters, REAL *trace, int diag_only)
 {
     const int G = oracle_gates(cell), S = oracle_state(cell), kind = oracle_jac_kind(cell);
     const size_t n = (size_t)S * H, js = jac_size(kind, H);
@@ -523,6 +541,7 @@ int oracle_newton(int cell, int B, int L, int H, const REAL *params, const REAL 
                 oracle_cell_step(cell, H, params, hp, ul, r + (size_t)l * n);
                 for (j = 0; j < n; ++j) r[(size_t)l * n + j] -= hb[(size_t)l * n + j];
                 oracle_cell_jacobian(cell, H, params, hp, ul, J + (size_t)l * js);
+                if (diag_only) jac_keep_diagonal(kind, H, J + (size_t)l * js);
             }
             oracle_forward_substitution(kind, L, H, J, r, d);
             for (j = 0; j < n * (size_t)L; ++j) {
@@ -540,6 +559,18 @@ int oracle_newton(int cell, int B, int L, int H, const REAL *params, const REAL 
         if (tol >= 0 && m <= tol) { status = ST_OK; break; }
     }
     return status;
+}
+
+int oracle_newton(int cell, int B, int L, int H, const REAL *params, const REAL *u, const REAL *h0,
+                  REAL tol, int max_iter, REAL *h, int *iters, REAL *trace)
+{
+    return newton_impl(cell, B, L, H, params, u, h0, tol, max_iter, h, iters, trace, 0);
+}
+
+int oracle_newton_diag(int cell, int B, int L, int H, const REAL *params, const REAL *u, const REAL *h0,
+                       REAL tol, int max_iter, REAL *h, int *iters, REAL *trace)
+{
+    return newton_impl(cell, B, L, H, params, u, h0, tol, max_iter, h, iters, trace, 1);
 }
 
 /* ----------------------------------------------------------------- backward */

@@ -704,3 +704,78 @@ def test_residual_norm_along_newton(oracle_mod, cell):
     # App. A's guess h^0_l = f(h0, u_l) satisfies the first equation exactly
     h_guess = o.newton(cell, params, u, h0, tol=-1.0, max_iter=0)[0]
     assert o.residual_norm(cell, params, u[:, :1], h0, h_guess[:, :1]) == 0.0
+
+
+# ------------------------------------- quasi-Newton with diagonal Jacobians (Sec. 1, Sec. 2.1)
+
+@pytest.mark.parametrize("cell", DIAG_CELLS)
+def test_quasi_newton_is_newton_for_diagonal_cells(oracle_mod, cell):
+    """Eq. (9): these cells' Jacobians are diagonal already, so dropping off-diagonal entries
+    changes nothing, bit for bit."""
+    o = oracle_mod
+    params, u, h0 = rand_problem(o, cell, 2, 40, 5, seed=81)
+    a = o.newton(cell, params, u, h0, tol=1e-10, max_iter=30)
+    b = o.newton(cell, params, u, h0, tol=1e-10, max_iter=30, jacobian="diagonal")
+    assert a[1] == b[1] and a[2] == b[2] and np.array_equal(a[0], b[0]) and np.array_equal(a[3], b[3])
+
+
+def _diag_of(J, kind):
+    """The Jacobian of all state values of one step as a dense matrix, off-diagonal entries dropped."""
+    if kind == "dense":
+        return np.diag(np.diag(J))
+    H = J.shape[-1]                      # 2x2 blocks [2][2][H] -> diag(J_cc, J_hh) of size 2H
+    return np.diag(np.concatenate([J[0, 0], J[1, 1]]))
+
+
+@pytest.mark.parametrize("cell,kind,H", [("tanh_dense", "dense", 4), ("lstm_diag", "block", 3), ("paralstm_diag", "block", 3),
+                                          ("rot_tanh", "block", 2)])
+def test_quasi_newton_iterates_by_a_global_solve(oracle_mod, cell, kind, H):
+    """Each quasi-Newton iterate re-derived without forward substitution: assemble the block
+    bi-diagonal matrix of Eq. (3) with diag(J_l) below the identity blocks, as one (L n) x (L n)
+    matrix, and solve it with LAPACK; the Jacobians and the cell come from the routines pinned
+    above (finite differences, hand values)."""
+    o = oracle_mod
+    B, L = 1, 6
+    params, u, h0 = rand_problem(o, cell, B, L, H, seed=82)
+    S = o.dims(cell)[1]
+    n = S * H
+    h = np.stack([o.cell_step(cell, params, h0[0], u[0, l]) for l in range(L)])          # App. A's guess
+    for k in range(1, 5):
+        M = np.eye(L * n)
+        r = np.zeros(L * n)
+        for l in range(L):
+            hp = h0[0] if l == 0 else h[l - 1]
+            r[l * n:(l + 1) * n] = (o.cell_step(cell, params, hp, u[0, l]) - h[l]).reshape(-1)
+            if l > 0:
+                M[l * n:(l + 1) * n, (l - 1) * n:l * n] = -_diag_of(o.cell_jacobian(cell, params, hp, u[0, l]), kind)
+        delta = np.linalg.solve(M, r).reshape(L, S, H)
+        h = h + delta
+        got, it, st, tr = o.newton(cell, params, u, h0, tol=-1.0, max_iter=k, jacobian="diagonal")
+        assert it == k and np.max(np.abs(got[0] - h)) < 1e-13, k
+        assert tr[-1] == pytest.approx(np.max(np.abs(delta)), rel=1e-12)
+    # and it is not Newton: with the full Jacobian the same iterate is elsewhere
+    full = o.newton(cell, params, u, h0, tol=-1.0, max_iter=2)[0]
+    quasi = o.newton(cell, params, u, h0, tol=-1.0, max_iter=2, jacobian="diagonal")[0]
+    assert np.max(np.abs(full - quasi)) > 1e-6
+
+
+@pytest.mark.parametrize("cell", ["tanh_dense", "lstm_diag", "paralstm_diag"])
+def test_quasi_newton_is_causal_and_reaches_the_recurrence(oracle_mod, cell):
+    """The system is lower block-triangular with identity diagonal blocks, whatever stands below
+    them: the guess solves step 1 and iteration k makes step k + 1 exact, so the recurrence's states
+    are reached after at most L - 1 iterations, however poor the approximation; it converges to the
+    same states as Newton, only linearly (more iterations than Newton here)."""
+    o = oracle_mod
+    H = 64 if cell == "tanh_dense" else 4
+    L = 12
+    params, u, h0 = rand_problem(o, cell, 2, L, H, seed=83)
+    ref = o.seq_unroll(cell, params, u, h0)
+    for k in (0, 1, 4, L - 1):
+        hk = o.newton(cell, params, u, h0, tol=-1.0, max_iter=k, jacobian="diagonal")[0]
+        assert np.max(np.abs(hk[:, :k + 1] - ref[:, :k + 1])) < 1e-14, k
+    params, u, h0 = rand_problem(o, cell, 2, 300, H, seed=84)
+    ref = o.seq_unroll(cell, params, u, h0)
+    hq, itq, stq, trq = o.newton(cell, params, u, h0, tol=1e-9, max_iter=300, jacobian="diagonal")
+    hn, itn, stn, _ = o.newton(cell, params, u, h0, tol=1e-9, max_iter=300)
+    assert stq == 0 and stn == 0 and itq > itn
+    assert np.max(np.abs(hq - ref)) < 1e-8 and np.max(np.abs(hn - ref)) < 1e-12
