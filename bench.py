@@ -168,6 +168,18 @@ def main():
             finally:
                 P.set_dense_products(0)
         detail["inexact_products"] = inexact
+        # not part of the timed step: the quasi-Newton ablation (the Jacobian replaced by its diagonal,
+        # a diagonal scan instead of the matrix products; linear convergence, more iterations)
+        P.set_dense_jacobian(1)
+        try:
+            solve = lambda: P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
+            _, it_q, _ = solve()
+            t_q = time_events(solve, 10)
+            it_q = [int(x) for x in it_q.cpu()]
+            detail["quasi_newton_diagonal"] = {"t_fwd_ms": sum(t_q) / len(t_q), "iters": it_q[0],
+                                               "status": P.status_string(it_q[1])}
+        finally:
+            P.set_dense_jacobian(0)
         P.forward(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, workspace=ws_f, out=h_out)
         roofline = {"bound": "mfma", "kernel": "dense_products_sweep_kernel (chunk products part)", "achieved": ach,
                     "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",

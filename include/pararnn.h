@@ -299,6 +299,25 @@ int pararnn_dense_chunk(void);
  * Returns PARARNN_INVALID_ARG for any other mode.
  */
 int pararnn_set_dense_products(int mode);
+
+/*
+ * Quasi-Newton switch of the dense path (host, process-wide; default 0): the
+ * variant of prior work that Sec. 1 and Sec. 2.1 describe, in which the
+ * Jacobian of the linear solve is replaced by its diagonal.
+ *   0  the full Jacobian J_l = diag(1 - F_l^2) W: Newton's method;
+ *   1  its diagonal (1 - F_l^2) * W_ii: the linear solve of an iteration is a
+ *      diagonal scan over the H channels, no matrix products at all.  The
+ *      residual is still the exact one, so the iteration has the same fixed
+ *      point (the recurrence's states) and the same stopping test; it
+ *      converges linearly instead of quadratically, i.e. it needs more (and
+ *      much cheaper) iterations, and when it stops the error of h is of the
+ *      order of tol rather than far below it.  Iteration k makes timestep
+ *      k + 1 exact, so at most L - 1 iterations are needed in any case.
+ * Affects pararnn_forward of PARARNN_TANH_DENSE only; pararnn_set_dense_products
+ * is irrelevant in mode 1; pararnn_backward always solves with the full
+ * transposed Jacobian.  Returns PARARNN_INVALID_ARG for any other mode.
+ */
+int pararnn_set_dense_jacobian(int mode);
 int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 

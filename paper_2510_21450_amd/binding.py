@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
                       "(there is no CPU fallback)")
 
 _lib = ctypes.CDLL(_LIB_PATH)
-for _name in ("pararnn_input_projection", "pararnn_residual_norm", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
+for _name in ("pararnn_input_projection", "pararnn_residual_norm", "pararnn_set_dense_jacobian", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
     if not hasattr(_lib, _name):
         raise ImportError(f"{_LIB_PATH} is older than this binding ({_name} is missing): rebuild it with "
                           "`python -m paper_2510_21450_amd.build`")
@@ -119,6 +119,11 @@ def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
 def set_dense_products(mode: int = 0) -> None:
     """pararnn_set_dense_products: 0 fp32 Jacobian products (default), 1 three bf16 terms, 2 one bf16 term."""
     _raise(_lib.pararnn_set_dense_products(int(mode)), "pararnn_set_dense_products")
+
+
+def set_dense_jacobian(mode: int = 0) -> None:
+    """pararnn_set_dense_jacobian: 0 the full Jacobian (Newton, default), 1 its diagonal (quasi-Newton)."""
+    _raise(_lib.pararnn_set_dense_jacobian(int(mode)), "pararnn_set_dense_jacobian")
 
 
 def dense_chunk() -> int:

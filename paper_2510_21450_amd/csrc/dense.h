@@ -25,6 +25,8 @@ int dense_residual_norm(int dtype, const float *W, const void *u, const void *h0
 int dense_chunk();
 // Arithmetic of the chunk products of forward solves: 0 fp32 (default), 1 three bf16 terms, 2 one bf16 term.
 int dense_set_products(int mode);
+// Jacobian of the linear solves of forward solves: 0 full (Newton, default), 1 its diagonal (quasi-Newton).
+int dense_set_jacobian(int mode);
 int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
                          hipStream_t st);
 

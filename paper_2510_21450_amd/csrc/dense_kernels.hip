@@ -29,6 +29,7 @@
 #include "../../include/pararnn.h"
 #include "common.h"
 #include "dense.h"
+#include "driver.h"
 #include "launch.h"
 
 #include <string.h>
@@ -115,11 +116,18 @@ __device__ __forceinline__ void load_w_operand16(const float *W, int w, int n, i
 // 16ww + 4g of the previous state, read straight from memory.
 // mode 0: write d = 1 - F^2 and r = F - h for the current iterate;
 // mode 1: write the initial guess h = tanh(W h0 + u) (App. A);
-// mode 2: write nothing but max |F - h| over all rows to a.norm (no control block is read).
+// mode 2: write nothing but max |F - h| over all rows to a.norm (no control block is read);
+// mode 3: as mode 0, but d is the diagonal of the Jacobian, (1 - F^2) * W_ii (quasi-Newton).
 __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
 {
     if (mode != 2 && a.ctrl->stop) return;
     float nmax = 0.0f;
+    f4v wdiag = {1.0f, 1.0f, 1.0f, 1.0f};
+    if (mode == 3) {
+        const int c0 = 16 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) + 4 * (int)((threadIdx.x & 63) >> 4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) wdiag[v] = a.W[(c0 + v) * DH + c0 + v];
+    }
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n = lane & 15, g = lane >> 4;
     const int chn = 16 * w + 4 * g;
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
 #pragma unroll
                 for (int v = 0; v < 4; ++v) nmax = nanmax(nmax, fabsf(hv[v] - F[v]));
             } else {
-                *reinterpret_cast<f4v *>(a.d + row * DH + chn) = 1.0f - F * F;
+                *reinterpret_cast<f4v *>(a.d + row * DH + chn) = (1.0f - F * F) * wdiag;
                 *reinterpret_cast<f4v *>(a.r + row * DH + chn) = F - hv;
             }
         }
@@ -562,6 +570,20 @@ __global__ __launch_bounds__(256, 2) void dense_products_sweep_kernel(const Dens
 
 // process-wide choice of the product arithmetic of forward solves (pararnn_set_dense_products)
 int g_dense_products = 0;
+int g_dense_jacobian = 0;       // 0: the full Jacobian (Newton), 1: its diagonal (quasi-Newton)
+
+// h += delta after the linear solve of iteration k, unless that iteration was skipped because an
+// earlier one had met the tolerance (the solve's last workgroup records the iteration it ran as)
+__global__ __launch_bounds__(256) void dense_add_delta_kernel(float *h, const float *delta, size_t n4, const Ctrl *ctrl,
+                                                               int k)
+{
+    if (ctrl->iters != k) return;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+        f4v hv = reinterpret_cast<const f4v *>(h)[i];
+        hv += reinterpret_cast<const f4v *>(delta)[i];
+        reinterpret_cast<f4v *>(h)[i] = hv;
+    }
+}
 
 void launch_products_sweep(int prod, int blocks, hipStream_t st, const DenseArgs &a, int n_sweep)
 {
@@ -721,6 +743,13 @@ int dense_set_products(int mode)
     return PARARNN_OK;
 }
 
+int dense_set_jacobian(int mode)
+{
+    if (mode < 0 || mode > 1) return PARARNN_INVALID_ARG;
+    g_dense_jacobian = mode;
+    return PARARNN_OK;
+}
+
 int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
                          hipStream_t st)
 {
@@ -850,10 +879,41 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     a.B = B; a.L = L; a.n_c = lo.n_c; a.k = 0; a.max_iter = max_iter; a.tol = tol;
 
     const int status0 = tol < 0.0f ? PARARNN_OK : PARARNN_NOT_CONVERGED;
-    if (launch_reset(a.ctrl, nullptr, 0, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
     const size_t res_items = ((size_t)B * L + 15) / 16;           // one workgroup per 16 rows, a few rounds at most
     const size_t res_cap = (size_t)device_cu_count() * 8;
     const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
+    if (g_dense_jacobian == 1) {
+        // Quasi-Newton: J_l is replaced by its diagonal (1 - F_l^2) * W_ii, so the linear solve is the
+        // diagonal scan over 64 independent channels per sequence; no matrix products.  The update
+        // delta and the scan's carry records live where the chunk products would (always large enough).
+        const CellInfo ci = {1, 1, 0, -1};
+        const Layout sl = make_layout(ci, PARARNN_F32, B, L, DH, false, 4);
+        float *delta = a.Ac;
+        const size_t n = (size_t)B * L * DH;
+        unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_A + r256(n * 4));
+        if (lo.off_A + r256(n * 4) + sl.n_rec * sizeof(unsigned long long) > lo.off_b) return PARARNN_INTERNAL;
+        if (launch_reset(a.ctrl, rec, sl.n_rec, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
+        hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
+        FwdArgs f;
+        memset(&f, 0, sizeof(f));
+        f.g = sl.g;
+        f.u = a.r; f.jac = a.d; f.hit = delta;
+        f.rec = rec; f.ctrl = a.ctrl;
+        f.iters_out = iters; f.trace = delta_trace;
+        f.max_iter = max_iter; f.tol = tol;
+        const size_t n4 = n / 4;
+        const size_t add_cap = (size_t)device_cu_count() * 8;
+        const int add_blocks = (int)((n4 + 255) / 256 < add_cap ? (n4 + 255) / 256 : add_cap);
+        for (int k = 1; k <= max_iter; ++k) {
+            hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 3);
+            f.k = k;
+            const hipError_t e = Kernels<RawScan<1>, float>::newton_iter(sl.cfg, f, false, st);
+            if (e != hipSuccess) return PARARNN_HIP_ERROR;
+            hipLaunchKernelGGL(dense_add_delta_kernel, dim3(add_blocks), dim3(256), 0, st, a.h, delta, n4, a.ctrl, k);
+        }
+        return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
+    }
+    if (launch_reset(a.ctrl, nullptr, 0, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
     hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
     const int n_prod_blocks = n_prod > 0 ? (n_prod + 3) / 4 : 0;

@@ -298,6 +298,8 @@ int pararnn_dense_chunk(void) { return dense_chunk(); }
 
 int pararnn_set_dense_products(int mode) { return dense_set_products(mode); }
 
+int pararnn_set_dense_jacobian(int mode) { return dense_set_jacobian(mode); }
+
 int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *workspace,
                                  size_t workspace_bytes, void *hip_stream)
 {

@@ -256,3 +256,72 @@ def test_dense_solve_with_inexact_products_reaches_the_same_states(oracle_mod, a
     torch.cuda.synchronize()
     rdu, rdW, rdh0 = oracle_mod.backward("tanh_dense", Wn, un, h0n, f64(hs), f64(g))
     assert relerr(f64(du), rdu) <= 1e-5 and relerr(f64(dW), rdW) <= 1e-5 and relerr(f64(dh0), rdh0) <= 1e-5
+
+
+# ------------------------------------------- quasi-Newton: diagonal of the Jacobian
+
+@pytest.fixture
+def jacobian_mode():
+    """Sets the Jacobian of the dense path's linear solves for one test and always restores the full one."""
+    import paper_2510_21450_amd as P
+    yield P.set_dense_jacobian
+    P.set_dense_jacobian(0)
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (2, 17), (3, 64), (3, 65), (5, 257), (64, 33), (2, 1000)])
+def test_dense_quasi_newton_against_the_oracle(oracle_mod, jacobian_mode, shape):
+    """pararnn_set_dense_jacobian(1): every iterate, the per-iteration maxima and the iteration
+    count against the oracle's quasi-Newton (Newton with J_l replaced by its diagonal)."""
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    print(f"dense quasi-Newton B={B} L={L}", flush=True)
+    W = normal(970 + L, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(970 + L, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(970 + L, 3, (B, 1, H), std=0.3, device="cuda")
+    Wn, un, h0n = f64(W), f64(u), f64(h0)
+    jacobian_mode(1)
+    for k in (0, 1, 2, 5):
+        h, iters, tr = P.forward("tanh_dense", W, u, h0, tol=-1.0, max_iter=k, trace=True)
+        torch.cuda.synchronize()
+        hk, _, _, trk = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=-1.0, max_iter=k, jacobian="diagonal")
+        assert tuple(int(x) for x in iters.cpu()) == (k, 0)
+        assert relerr(f64(h), hk) <= 1e-5, k
+        assert np.allclose(tr.cpu().numpy()[:k], trk, rtol=1e-3, atol=1e-6), k
+    tol = 1e-6
+    h, iters, tr = P.forward("tanh_dense", W, u, h0, tol=tol, max_iter=200, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    h64, it64, st64, tr64 = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=200, jacobian="diagonal")
+    _, it32, _, tr32 = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=200, jacobian="diagonal", precision="f32")
+    _, itn, _, _ = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=tol, max_iter=200)
+    assert st == 0 and st64 == 0
+    # linear convergence leaves little room between consecutive maxima: the count is compared
+    # exactly where the stopping decision clears tol by 5 % on both sides in fp32 and in fp64
+    clear = it32 == it64 and all(t[-1] <= tol / 1.05 and (len(t) < 2 or t[-2] >= 1.05 * tol) for t in (tr32, tr64))
+    print(f"  {it} iterations (oracle {it64} / fp32 {it32}, Newton {itn}), clear margin: {clear}", flush=True)
+    assert it == it64 if clear else abs(it - it64) <= 1
+    assert it64 >= itn
+    assert relerr(f64(h), h64) <= 1e-5
+    assert relerr(f64(h), oracle_mod.seq_unroll("tanh_dense", Wn, un, h0n)) <= 1e-5      # error at the stop is of the order of tol
+    # the full Jacobian again: Newton's count
+    jacobian_mode(0)
+    _, iters, _ = P.forward("tanh_dense", W, u, h0, tol=tol, max_iter=200)
+    assert abs(int(iters.cpu()[0]) - itn) <= 1
+
+
+def test_dense_quasi_newton_config_c4(oracle_mod, jacobian_mode):
+    """Benchmark configuration 4 with the diagonal approximation: same states, more iterations."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C4"]
+    d = make_inputs(w, device="cuda")
+    Wn, un = f64(d["params"]), f64(d["u"])
+    jacobian_mode(1)
+    h, iters, tr = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=w.max_iter, trace=True)
+    torch.cuda.synchronize()
+    it, st = (int(x) for x in iters.cpu())
+    h64, it64, st64, tr64 = oracle_mod.newton(w.cell, Wn, un, None, tol=w.tol, max_iter=w.max_iter, jacobian="diagonal")
+    print(f"C4 quasi-Newton: {it} iterations (oracle {it64}), status {st} (oracle {st64}), trace {tr.cpu().numpy()[:it]}", flush=True)
+    assert st == st64 and abs(it - it64) <= 1
+    assert relerr(f64(h), h64) <= 1e-5
+    assert np.allclose(tr.cpu().numpy()[:min(it, it64)], tr64[:min(it, it64)], rtol=2e-3)

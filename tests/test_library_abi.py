@@ -112,6 +112,12 @@ def test_dense_products_switch(lib):
     assert sp(3) == 2 and sp(-1) == 2
 
 
+def test_dense_jacobian_switch(lib):
+    sj = lib.pararnn_set_dense_jacobian
+    assert sj(1) == 0 and sj(0) == 0
+    assert sj(2) == 2 and sj(-1) == 2
+
+
 def test_tile_hook(lib):
     st = lib.pararnn_set_tile
     assert st(4, 4, 8, 8) == 0          # a compiled shape
