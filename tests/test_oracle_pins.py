@@ -13,7 +13,8 @@ import pytest
 NL_CELLS = ["gru_nl:tanh,softsign,identity", "gru_nl:sigmoid,sigmoid,softsign", "gru_nl:softsign,tanh,sigmoid"]
 DIAG_CELLS = ["gru_diag", "linear_diag"] + NL_CELLS
 BLOCK2_CELLS = ["lstm_diag", "paralstm_diag", "rot_tanh"]
-ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag", "rot_tanh"] + NL_CELLS
+BLOCK3_CELLS = ["tri_tanh"]
+ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag", "rot_tanh", "tri_tanh"] + NL_CELLS
 
 
 def sig(x):
@@ -30,6 +31,8 @@ def rand_params(oracle, cell, H, rng, bound=0.9, bias=True):
         if bias:
             p[5:] = rng.normal(0, 0.3, (3, H))
         return p
+    if cell == "tri_tanh":               # the per-channel 3x3 matrix, [3][3][H] as 9 rows
+        return rng.uniform(-bound / 2, bound / 2, (9, H))
     if cell == "rot_tanh":               # a, b of the per-channel rotation-scaling
         return rng.uniform(-bound / 1.5, bound / 1.5, (2, H))
     p = np.zeros((2, G, H))
@@ -185,9 +188,9 @@ def test_jacobian_matches_central_differences(oracle_mod, cell):
         Jfd[:, q] = (fp - fm) / (2 * eps)
     if cell in DIAG_CELLS:
         Jfull = np.diag(J)
-    elif cell in BLOCK2_CELLS:
+    elif cell in BLOCK2_CELLS + BLOCK3_CELLS:
         Jfull = np.zeros((n, n))
-        for p_, q_ in itertools.product(range(2), range(2)):
+        for p_, q_ in itertools.product(range(S), range(S)):
             Jfull[p_ * H:(p_ + 1) * H, q_ * H:(q_ + 1) * H] = np.diag(J[p_, q_])
     else:
         Jfull = J
@@ -213,6 +216,8 @@ def _rand_system(kind, L, H, rng, scale=0.9):
         return rng.uniform(-scale, scale, (L, H)), rng.normal(0, 1, (L, H))
     if kind == "block2":
         return rng.uniform(-scale, scale, (L, 2, 2, H)), rng.normal(0, 1, (L, 2, H))
+    if kind == "block3":
+        return rng.uniform(-scale / 1.5, scale / 1.5, (L, 3, 3, H)), rng.normal(0, 1, (L, 3, H))
     return rng.normal(0, scale / math.sqrt(H), (L, H, H)), rng.normal(0, 1, (L, H))
 
 
@@ -221,16 +226,17 @@ def _dense_view(kind, J, H):
     L = J.shape[0]
     if kind == "diag":
         return np.stack([np.diag(J[l]) for l in range(L)])
-    if kind == "block2":
-        out = np.zeros((L, 2 * H, 2 * H))
+    if kind in ("block2", "block3"):
+        S = J.shape[1]
+        out = np.zeros((L, S * H, S * H))
         for l in range(L):
-            for p_, q_ in itertools.product(range(2), range(2)):
+            for p_, q_ in itertools.product(range(S), range(S)):
                 out[l, p_ * H:(p_ + 1) * H, q_ * H:(q_ + 1) * H] = np.diag(J[l, p_, q_])
         return out
     return J
 
 
-@pytest.mark.parametrize("kind", ["diag", "block2", "dense"])
+@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "dense"])
 def test_forward_substitution_equals_unrolled_sum(oracle_mod, kind):
     """Eq. (5): delta_l = sum_{s<=l} (J_l J_{l-1} ... J_{s+1}) r_s, by brute force."""
     o = oracle_mod
@@ -250,7 +256,7 @@ def test_forward_substitution_equals_unrolled_sum(oracle_mod, kind):
             assert np.allclose(got[l], want, rtol=1e-12, atol=1e-13)
 
 
-@pytest.mark.parametrize("kind", ["diag", "block2", "dense"])
+@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "dense"])
 def test_parallel_reduce_equals_dense_solve(oracle_mod, kind):
     """Alg. 1b solves the block bi-diagonal system of Eq. (3): compare with a
     dense LAPACK solve of (I - subdiag(J)) delta = r, for every L up to 70
@@ -307,7 +313,7 @@ def test_linear_cell_one_newton_solve_is_exact(oracle_mod):
     assert np.max(np.abs(h1 - ref)) < 1e-13
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh"])
 def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     """Sec. 2.1: convergence in at most L Newton steps is guaranteed because
     after k solves the first k states equal the sequential result, whatever the
@@ -329,7 +335,7 @@ def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     assert np.max(np.abs(hL - ref)) < 1e-11
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh"])
 def test_newton_converges_quadratically_to_the_unroll(oracle_mod, cell):
     """App. A: the residual falls to machine precision in a handful of
     iterations; the converged iterate is the sequential result of Eq. (1)."""
@@ -581,6 +587,37 @@ def test_rot_tanh_is_the_dense_cell_with_a_2x2_matrix(oracle_mod):
     assert np.allclose(dur.reshape(L, 2), dud.reshape(L, 2), rtol=0, atol=1e-14)
     assert np.allclose(dh0r.ravel(), dh0d.ravel(), rtol=0, atol=1e-14)
     assert np.allclose(dpr.ravel(), [dWd[0, 0] + dWd[1, 1], dWd[1, 0] - dWd[0, 1]], rtol=0, atol=1e-13)
+
+
+def test_tri_tanh_is_the_dense_cell_with_a_3x3_matrix_per_channel(oracle_mod):
+    """Each channel of the 3x3-block example cell is h' = tanh(M h + u) with that channel's own
+    matrix M: step, Jacobian, Newton solve (both Jacobian modes) and backward must agree with the
+    dense cell at H = 3, channel by channel (channels do not mix)."""
+    o = oracle_mod
+    rng = np.random.default_rng(96)
+    L, H = 10, 2
+    M = rng.uniform(-0.45, 0.45, (H, 3, 3))                  # M[channel][a][b]
+    pt = np.transpose(M, (1, 2, 0)).reshape(9, H)            # rows m_ab, channels last
+    ut = rng.normal(0, 1, (1, L, 3, H)); h0t = rng.normal(0, 0.3, (1, 3, H)); gt = rng.normal(0, 1, (1, L, 3, H))
+    ht = o.seq_unroll("tri_tanh", pt, ut, h0t)
+    Jt = o.cell_jacobian("tri_tanh", pt, h0t[0], ut[0, 0])
+    nt = o.newton("tri_tanh", pt, ut, h0t, tol=-1.0, max_iter=3)
+    qt = o.newton("tri_tanh", pt, ut, h0t, tol=-1.0, max_iter=3, jacobian="diagonal")
+    dut, dpt, dh0t = o.backward("tri_tanh", pt, ut, h0t, ht, gt)
+    for ch in range(H):
+        W = M[ch]
+        u = ut[:, :, :, ch].reshape(1, L, 1, 3); h0 = h0t[:, :, ch].reshape(1, 1, 3); g = gt[:, :, :, ch].reshape(1, L, 1, 3)
+        hd = o.seq_unroll("tanh_dense", W, u, h0)
+        assert np.allclose(ht[0, :, :, ch], hd.reshape(L, 3), rtol=0, atol=1e-15)
+        assert np.allclose(Jt[:, :, ch], o.cell_jacobian("tanh_dense", W, h0[0], u[0, 0]), rtol=0, atol=1e-15)
+        nd = o.newton("tanh_dense", W, u, h0, tol=-1.0, max_iter=3)
+        qd = o.newton("tanh_dense", W, u, h0, tol=-1.0, max_iter=3, jacobian="diagonal")
+        assert np.allclose(nt[0][0, :, :, ch], nd[0].reshape(L, 3), rtol=0, atol=1e-14)
+        assert np.allclose(qt[0][0, :, :, ch], qd[0].reshape(L, 3), rtol=0, atol=1e-14)
+        dud, dWd, dh0d = o.backward("tanh_dense", W, u, h0, hd, g)
+        assert np.allclose(dut[0, :, :, ch], dud.reshape(L, 3), rtol=0, atol=1e-14)
+        assert np.allclose(dh0t[0, :, ch], dh0d.ravel(), rtol=0, atol=1e-14)
+        assert np.allclose(dpt[:, ch].reshape(3, 3), dWd, rtol=0, atol=1e-13)
 
 
 # ---------------------------------------------------------- input projection
