@@ -60,6 +60,45 @@ def test_forward_and_backward_replay_from_a_graph(oracle_mod):
     assert relerr(f64(h), ref) <= 1e-5
 
 
+@pytest.mark.parametrize("jacobian", [0, 1])
+def test_dense_solve_and_residual_norm_replay_from_a_graph(jacobian):
+    """The dense cell's solve (Newton, and the quasi-Newton mode chosen at capture time) followed by
+    the residual max-norm of its result, recorded into a HIP graph and replayed with eager work in
+    between: every replay equals the eager result bit for bit."""
+    import paper_2510_21450_amd as P
+    from workloads.rng import normal
+    B, L, H = 3, 300, 64
+    W = normal(77, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(77, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(77, 3, (B, 1, H), std=0.3, device="cuda")
+    ws = torch.empty(P.workspace_bytes("tanh_dense", u.dtype, B, L, H), dtype=torch.uint8, device="cuda")
+    h = torch.empty_like(u)
+    rn = torch.empty(1, device="cuda")
+    P.set_dense_jacobian(jacobian)
+    try:
+        h_e, it_e, _ = P.forward("tanh_dense", W, u, h0, tol=1e-5, max_iter=60, workspace=ws)
+        rn_e = P.residual_norm("tanh_dense", W, u, h0, h_e)
+        torch.cuda.synchronize()
+        h_e, it_e, rn_e = h_e.clone(), it_e.cpu().clone(), rn_e.cpu().clone()
+        assert int(it_e[1]) == 0 and float(rn_e) < 1e-4
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                _, iters, _ = P.forward("tanh_dense", W, u, h0, tol=1e-5, max_iter=60, workspace=ws, out=h)
+                P.residual_norm("tanh_dense", W, u, h0, h, out=rn)
+        torch.cuda.current_stream().wait_stream(side)
+    finally:
+        P.set_dense_jacobian(0)
+    for rep in range(3):
+        h.fill_(float("nan")); iters.zero_(); rn.fill_(7.0)
+        _ = (u * 2).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(iters.cpu(), it_e) and torch.equal(h, h_e) and torch.equal(rn.cpu(), rn_e), rep
+
+
 def test_runs_on_a_side_stream(oracle_mod, as_stored):
     import paper_2510_21450_amd as P
     w = CONFIGS["C3"].scaled(B=2, L=300, H=96)
