@@ -129,6 +129,11 @@ def main():
               "launches": P.solve_plan(w.tol, w.max_iter) if w.cell != "tanh_dense" else None,
               "t_fwd_ms": sum(t_fwd) / len(t_fwd), "t_fwd_min_ms": min(t_fwd),
               "t_iter_ms": t_iter_ms, "t_iter_min_ms": t_iter_min_ms}
+    # what the runtime reports for this device, beside the published figures the rooflines use
+    props = torch.cuda.get_device_properties(0)
+    dev = {"name": props.name, "arch": getattr(props, "gcnArchName", None), "memory_gib": props.total_memory / 2 ** 30}
+    dev.update(P.device_info())
+    detail["device"] = dev
     if w.cell == "tanh_dense":
         # the scan composes one 64x64 Jacobian product (2 H^3 flop) per timestep
         flops_iter = 2.0 * w.H ** 3 * w.B * w.L

@@ -83,6 +83,17 @@ const char *pararnn_status_string(int status);
 /* Library version, major*10000 + minor*100 + patch. */
 int pararnn_version(void);
 
+/*
+ * What the HIP runtime reports for the current device (host only; used by the
+ * benchmark to print the machine's own figures beside the published peaks its
+ * rooflines use).  info[0..5] = compute units, core clock in kHz, memory clock
+ * in kHz, memory bus width in bits, L2 size in bytes, LDS bytes a workgroup may
+ * use; -1 where the runtime gives no answer.  Returns the number of entries
+ * written (6), or -1 if info is NULL, capacity is below 6 or no device is
+ * current.
+ */
+int pararnn_device_info(int *info, int capacity);
+
 /* Tuning / test hook (host, process-wide, not thread-safe): force the tile
  * shape of the scan kernels for all later calls -- vec channels per lane, ll
  * segments along L per wave, c timesteps per thread, w waves per workgroup.

@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
                       "(there is no CPU fallback)")
 
 _lib = ctypes.CDLL(_LIB_PATH)
-for _name in ("pararnn_input_projection", "pararnn_residual_norm", "pararnn_set_dense_jacobian", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
+for _name in ("pararnn_input_projection", "pararnn_residual_norm", "pararnn_set_dense_jacobian", "pararnn_device_info", "pararnn_set_dense_products", "pararnn_solve_plan", "pararnn_affine_scan_workspace_bytes"):
     if not hasattr(_lib, _name):
         raise ImportError(f"{_LIB_PATH} is older than this binding ({_name} is missing): rebuild it with "
                           "`python -m paper_2510_21450_amd.build`")
@@ -28,6 +28,8 @@ _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_
 _lib.pararnn_status_string.restype = ctypes.c_char_p
 _lib.pararnn_status_string.argtypes = [_i]
 _lib.pararnn_version.restype = _i
+_lib.pararnn_device_info.restype = _i
+_lib.pararnn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), _i]
 _lib.pararnn_set_tile.argtypes = [_i] * 4
 _lib.pararnn_set_tile.restype = _i
 _lib.pararnn_cell_gates.argtypes = [_i]
@@ -119,6 +121,16 @@ def set_tile(vec: int = 0, ll: int = 0, c: int = 0, w: int = 0) -> None:
 def set_dense_products(mode: int = 0) -> None:
     """pararnn_set_dense_products: 0 fp32 Jacobian products (default), 1 three bf16 terms, 2 one bf16 term."""
     _raise(_lib.pararnn_set_dense_products(int(mode)), "pararnn_set_dense_products")
+
+
+def device_info() -> dict:
+    """pararnn_device_info as a dict (None where the runtime gives no answer)."""
+    buf = (ctypes.c_int * 8)()
+    n = _lib.pararnn_device_info(buf, 8)
+    if n < 6:
+        raise RuntimeError("pararnn_device_info failed")
+    keys = ("compute_units", "clock_khz", "memory_clock_khz", "memory_bus_bits", "l2_bytes", "lds_bytes_per_workgroup")
+    return {k: (int(buf[i]) if buf[i] >= 0 else None) for i, k in enumerate(keys)}
 
 
 def set_dense_jacobian(mode: int = 0) -> None:

@@ -51,6 +51,21 @@ const char *pararnn_status_string(int status)
 
 int pararnn_version(void) { return 100; }
 
+int pararnn_device_info(int *info, int capacity)
+{
+    static const hipDeviceAttribute_t what[] = {hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate,
+                                                hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth,
+                                                hipDeviceAttributeL2CacheSize,
+                                                hipDeviceAttributeMaxSharedMemoryPerBlock};
+    const int n = (int)(sizeof(what) / sizeof(what[0]));
+    int dev = 0;
+    if (!info || capacity < n) return -1;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    for (int i = 0; i < n; ++i)
+        if (hipDeviceGetAttribute(&info[i], what[i], dev) != hipSuccess) info[i] = -1;
+    return n;
+}
+
 int pararnn_set_tile(int vec, int ll, int c, int w)
 {
     int *ov = settings().tile;

@@ -268,3 +268,12 @@ def test_residual_norm_host_checks(lib):
     assert f(0, 0, p, p + 2, None, p, 1, 4, 8, p, None) == 2           # fp32 u at an odd 2-byte address
     assert f(2, 1, p, p, None, p, 1, 4, 64, p, None) == 6              # dense cell: fp32 only
     assert f(2, 0, p, p, None, p, 1, 4, 32, p, None) == 6              # dense cell: H = 64 only
+
+
+def test_device_info_argument_checks(lib):
+    """pararnn_device_info refuses a missing or short buffer (no device is needed for that)."""
+    f = lib.pararnn_device_info
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.c_int]
+    buf = (ctypes.c_int * 8)()
+    assert f(None, 8) == -1 and f(buf, 5) == -1
