@@ -572,18 +572,6 @@ __global__ __launch_bounds__(256, 2) void dense_products_sweep_kernel(const Dens
 int g_dense_products = 0;
 int g_dense_jacobian = 0;       // 0: the full Jacobian (Newton), 1: its diagonal (quasi-Newton)
 
-// h += delta after the linear solve of iteration k, unless that iteration was skipped because an
-// earlier one had met the tolerance (the solve's last workgroup records the iteration it ran as)
-__global__ __launch_bounds__(256) void dense_add_delta_kernel(float *h, const float *delta, size_t n4, const Ctrl *ctrl,
-                                                               int k)
-{
-    if (ctrl->iters != k) return;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
-        f4v hv = reinterpret_cast<const f4v *>(h)[i];
-        hv += reinterpret_cast<const f4v *>(delta)[i];
-        reinterpret_cast<f4v *>(h)[i] = hv;
-    }
-}
 
 void launch_products_sweep(int prod, int blocks, hipStream_t st, const DenseArgs &a, int n_sweep)
 {
@@ -884,32 +872,27 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     const int res_blocks = (int)(res_items < res_cap ? res_items : res_cap);
     if (g_dense_jacobian == 1) {
         // Quasi-Newton: J_l is replaced by its diagonal (1 - F_l^2) * W_ii, so the linear solve is the
-        // diagonal scan over 64 independent channels per sequence; no matrix products.  The update
-        // delta and the scan's carry records live where the chunk products would (always large enough).
+        // diagonal scan over 64 independent channels per sequence; no matrix products.  The scan adds
+        // its result to h itself; its carry records live where the chunk products would (always
+        // large enough).
         const CellInfo ci = {1, 1, 0, -1};
         const Layout sl = make_layout(ci, PARARNN_F32, B, L, DH, false, 4);
-        float *delta = a.Ac;
-        const size_t n = (size_t)B * L * DH;
-        unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_A + r256(n * 4));
-        if (lo.off_A + r256(n * 4) + sl.n_rec * sizeof(unsigned long long) > lo.off_b) return PARARNN_INTERNAL;
+        unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_A);
+        if (lo.off_A + sl.n_rec * sizeof(unsigned long long) > lo.off_b) return PARARNN_INTERNAL;
         if (launch_reset(a.ctrl, rec, sl.n_rec, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
         FwdArgs f;
         memset(&f, 0, sizeof(f));
         f.g = sl.g;
-        f.u = a.r; f.jac = a.d; f.hit = delta;
+        f.u = a.r; f.jac = a.d; f.hit = a.h; f.raw_add = 1;
         f.rec = rec; f.ctrl = a.ctrl;
         f.iters_out = iters; f.trace = delta_trace;
         f.max_iter = max_iter; f.tol = tol;
-        const size_t n4 = n / 4;
-        const size_t add_cap = (size_t)device_cu_count() * 8;
-        const int add_blocks = (int)((n4 + 255) / 256 < add_cap ? (n4 + 255) / 256 : add_cap);
         for (int k = 1; k <= max_iter; ++k) {
             hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 3);
             f.k = k;
             const hipError_t e = Kernels<RawScan<1>, float>::newton_iter(sl.cfg, f, false, st);
             if (e != hipSuccess) return PARARNN_HIP_ERROR;
-            hipLaunchKernelGGL(dense_add_delta_kernel, dim3(add_blocks), dim3(256), 0, st, a.h, delta, n4, a.ctrl, k);
         }
         return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
     }

@@ -55,7 +55,8 @@ struct FwdArgs {
     const void *u;       // [B][L][G][H], fp32 or bf16
     const void *h0;      // [B][S][H] in u's type, or NULL
     const float *jac;    // raw scans only: [B][L][S*S][H]
-    float *hit;          // fp32 iterate [B][L][S][H], updated in place
+    float *hit;          // fp32 iterate [B][L][S][H], updated in place (raw scans: the output delta)
+    int raw_add;         // raw scans only: add delta to what hit holds instead of overwriting it
     float *bnd;          // [2][n_lt][B][S][H]: iterate at each tile's last step
     int bnd_cur;         // which of the two holds the rows of the iterate being read (the other is written)
     unsigned long long *rec; // carry records [n_groups][n_lt][S*S + 2S][CW] of {value, tag}
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 if constexpr (!FIRST) {
 #pragma unroll
                     for (int s = 0; s < S; ++s) {
-                        if constexpr (!kRaw) {
+                        if (!kRaw || a.raw_add) {
                             if constexpr (!kGuard) hor[i][s] = buf_load<float, VEC>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u);
                             else if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
                             else hor[i][s] = zero_raw<float, VEC>();
