@@ -325,3 +325,30 @@ def test_dense_quasi_newton_config_c4(oracle_mod, jacobian_mode):
     assert st == st64 and abs(it - it64) <= 1
     assert relerr(f64(h), h64) <= 1e-5
     assert np.allclose(tr.cpu().numpy()[:min(it, it64)], tr64[:min(it, it64)], rtol=2e-3)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_dense_iteration_control_edge_cases(oracle_mod, jacobian_mode, mode):
+    """The dense cell under both Jacobian modes: max_iter = 0 gives the initial guess, tol = 0 runs
+    to max_iter with NOT_CONVERGED, L = 1 needs one solve with a zero update, a NaN in the input
+    ends the solve with NONFINITE after its first iteration: statuses and counts as the oracle's."""
+    import paper_2510_21450_amd as P
+    B, L, H = 2, 40, 64
+    W = normal(990, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(990, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(990, 3, (B, 1, H), std=0.3, device="cuda")
+    Wn, un, h0n = f64(W), f64(u), f64(h0)
+    jac = "full" if mode == 0 else "diagonal"
+    jacobian_mode(mode)
+    h, iters, _ = P.forward("tanh_dense", W, u, h0, tol=1e-6, max_iter=0)
+    hg = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=1e-6, max_iter=0, jacobian=jac)[0]
+    assert int(iters.cpu()[0]) == 0 and relerr(f64(h), hg) <= 1e-5
+    h, iters, _ = P.forward("tanh_dense", W, u, h0, tol=0.0, max_iter=2)
+    _, ito, sto, _ = oracle_mod.newton("tanh_dense", Wn, un, h0n, tol=0.0, max_iter=2, jacobian=jac)
+    assert tuple(int(x) for x in iters.cpu()) == (ito, sto) == (2, 1)
+    h, iters, tr = P.forward("tanh_dense", W, u[:, :1].contiguous(), h0, tol=0.0, max_iter=5, trace=True)
+    assert tuple(int(x) for x in iters.cpu()) == (1, 0) and float(tr[0]) == 0.0
+    u2 = u.clone(); u2[1, 3, 0, 7] = float("nan")
+    h, iters, _ = P.forward("tanh_dense", W, u2, h0, tol=1e-6, max_iter=5)
+    _, ito, sto, _ = oracle_mod.newton("tanh_dense", Wn, f64(u2), h0n, tol=1e-6, max_iter=5, jacobian=jac)
+    assert tuple(int(x) for x in iters.cpu()) == (ito, sto) == (1, 5)
