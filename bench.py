@@ -63,8 +63,8 @@ def time_events(fn, reps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "X3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
