@@ -17,7 +17,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "pararnn_oracle.c")
 _LIBS = {}
 
-CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4, "rot_tanh": 5, "tri_tanh": 6}
+CELLS = {"gru_diag": 0, "lstm_diag": 1, "tanh_dense": 2, "linear_diag": 3, "paralstm_diag": 4, "rot_tanh": 5, "tri_tanh": 6, "quad_tanh": 7}
 NONLIN = {"sigmoid": 0, "tanh": 1, "identity": 2, "softsign": 3}
 
 
@@ -30,7 +30,7 @@ def cell_id(cell: str) -> int:
 
 
 STATUS = {0: "OK", 1: "NOT_CONVERGED", 2: "INVALID_ARG", 5: "NONFINITE"}
-JAC_KIND = {"diag": 0, "block2": 1, "dense": 2, "block3": 3}
+JAC_KIND = {"diag": 0, "block2": 1, "dense": 2, "block3": 3, "block4": 4}
 
 
 def _lib_path(precision):
@@ -97,7 +97,7 @@ def cell_jacobian(cell, params, hp, u, precision="f64"):
     H = hp_a.shape[-1]
     _, pp = _c(params, precision)
     _, up = _c(u, precision)
-    shape = {0: (H,), 1: (2, 2, H), 2: (H, H), 3: (3, 3, H)}[lib.oracle_jac_kind(cell_id(cell))]
+    shape = {0: (H,), 1: (2, 2, H), 2: (H, H), 3: (3, 3, H), 4: (4, 4, H)}[lib.oracle_jac_kind(cell_id(cell))]
     out = np.empty(shape, dtype=_np_t(precision))
     lib.oracle_cell_jacobian(cell_id(cell), H, pp, hp_p, up, out.ctypes.data_as(ctypes.c_void_p))
     return out

@@ -32,8 +32,8 @@
  *   - Sec. 2.1 (block-diagonal Jacobians): a cell written only to
  *     exercise 2x2 blocks that do not come from an LSTM, a per-channel
  *     rotation-scaling followed by tanh                           -> cell 5
- *     and one with 3x3 blocks (three state values per channel
- *     mixed by a per-channel 3x3 matrix, then tanh)               -> cell 6
+ *     and cells with 3x3 and 4x4 blocks (N state values per channel
+ *     mixed by a per-channel N x N matrix, then tanh)             -> cells 6, 7
  *
  * Precision: REAL is double unless the file is compiled with -DREAL=float
  * (a second build used only to look at fp32 iteration traces).
@@ -64,10 +64,14 @@
 #endif
 
 enum { CELL_GRU_DIAG = 0, CELL_LSTM_DIAG = 1, CELL_TANH_DENSE = 2, CELL_LINEAR_DIAG = 3, CELL_PARALSTM_DIAG = 4,
-       CELL_ROT_TANH = 5, CELL_TRI_TANH = 6, CELL_GRU_NL = 100 /* .. 163 */ };
+       CELL_ROT_TANH = 5, CELL_TRI_TANH = 6, CELL_QUAD_TANH = 7, CELL_GRU_NL = 100 /* .. 163 */ };
 enum { NL_SIGMOID = 0, NL_TANH = 1, NL_IDENTITY = 2, NL_SOFTSIGN = 3 };
 enum { ST_OK = 0, ST_NOT_CONVERGED = 1, ST_INVALID = 2, ST_NONFINITE = 5 };
-enum { JAC_DIAG = 0, JAC_BLOCK2 = 1, JAC_DENSE = 2, JAC_BLOCK3 = 3 };   /* BLOCK3: [3][3][H], J[a][b] = dF_a/dh_b */
+/* BLOCK3 / BLOCK4: [N][N][H] with N = 3 / 4, J[a][b] = dF_a/dh_b */
+enum { JAC_DIAG = 0, JAC_BLOCK2 = 1, JAC_DENSE = 2, JAC_BLOCK3 = 3, JAC_BLOCK4 = 4 };
+static int block_dim(int kind) { return kind == JAC_BLOCK3 ? 3 : kind == JAC_BLOCK4 ? 4 : 0; }
+/* state values per channel of the cells that mix them with a per-channel N x N matrix, else 0 */
+static int mix_dim(int cell);
 
 static REAL sigmoid(REAL x) { return (REAL)1 / ((REAL)1 + (REAL)exp(-(double)x)); }
 static REAL tanh_r(REAL x) { return (REAL)tanh((double)x); }
@@ -102,6 +106,8 @@ int oracle_num_threads(void)
 #endif
 }
 
+static int mix_dim(int cell) { return cell == CELL_TRI_TANH ? 3 : cell == CELL_QUAD_TANH ? 4 : 0; }
+
 int oracle_gates(int cell)
 {
     switch (cell) {
@@ -112,6 +118,7 @@ int oracle_gates(int cell)
     case CELL_PARALSTM_DIAG: return 3;
     case CELL_ROT_TANH: return 2;
     case CELL_TRI_TANH: return 3;
+    case CELL_QUAD_TANH: return 4;
     }
     return is_gru_nl(cell) ? 3 : -1;
 }
@@ -119,7 +126,7 @@ int oracle_gates(int cell)
 int oracle_state(int cell)
 {
     if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG || cell == CELL_ROT_TANH) return 2;
-    if (cell == CELL_TRI_TANH) return 3;
+    if (mix_dim(cell)) return mix_dim(cell);
     return (cell >= 0 && cell <= 3) || is_gru_nl(cell) ? 1 : -1;
 }
 
@@ -128,6 +135,7 @@ int oracle_jac_kind(int cell)
     if (cell == CELL_LSTM_DIAG || cell == CELL_PARALSTM_DIAG || cell == CELL_ROT_TANH) return JAC_BLOCK2;
     if (cell == CELL_TANH_DENSE) return JAC_DENSE;
     if (cell == CELL_TRI_TANH) return JAC_BLOCK3;
+    if (cell == CELL_QUAD_TANH) return JAC_BLOCK4;
     return JAC_DIAG;
 }
 
@@ -136,7 +144,7 @@ static size_t jac_size(int kind, int H)
 {
     if (kind == JAC_DIAG) return (size_t)H;
     if (kind == JAC_BLOCK2) return (size_t)4 * H;       /* [2][2][H] */
-    if (kind == JAC_BLOCK3) return (size_t)9 * H;       /* [3][3][H] */
+    if (block_dim(kind)) return (size_t)block_dim(kind) * block_dim(kind) * H;
     return (size_t)H * H;                               /* [H][H] row-major */
 }
 
@@ -145,7 +153,7 @@ static size_t param_count(int cell, int H)
     if (cell == CELL_TANH_DENSE) return (size_t)H * H;
     if (cell == CELL_PARALSTM_DIAG) return (size_t)8 * H;
     if (cell == CELL_ROT_TANH) return (size_t)2 * H;
-    if (cell == CELL_TRI_TANH) return (size_t)9 * H;
+    if (mix_dim(cell)) return (size_t)mix_dim(cell) * mix_dim(cell) * H;
     return (size_t)2 * oracle_gates(cell) * H;
 }
 
@@ -216,14 +224,15 @@ void oracle_cell_step(int cell, int H, const REAL *params, const REAL *hp, const
             out[j] = tanh_r(a[j] * p - b[j] * q + u[j]);
             out[H + j] = tanh_r(b[j] * p + a[j] * q + u[H + j]);
         }
-    } else if (cell == CELL_TRI_TANH) {
-        /* three state values per channel mixed by that channel's own 3x3 matrix m (params [3][3][H]):
-         * x'_a = tanh(sum_b m_ab x_b + u_a); a cell with 3x3 Jacobian blocks (Sec. 2.1) */
+    } else if (mix_dim(cell)) {
+        /* N state values per channel mixed by that channel's own N x N matrix m (params [N][N][H]):
+         * x'_a = tanh(sum_b m_ab x_b + u_a); a cell with N x N Jacobian blocks (Sec. 2.1), N = 3, 4 */
+        const int N = mix_dim(cell);
         int a, b;
         for (j = 0; j < H; ++j)
-            for (a = 0; a < 3; ++a) {
+            for (a = 0; a < N; ++a) {
                 REAL s = u[a * H + j];
-                for (b = 0; b < 3; ++b) s += params[(3 * a + b) * H + j] * hp[b * H + j];
+                for (b = 0; b < N; ++b) s += params[(N * a + b) * H + j] * hp[b * H + j];
                 out[a * H + j] = tanh_r(s);
             }
     } else if (cell == CELL_TANH_DENSE) {
@@ -321,14 +330,15 @@ void oracle_cell_jacobian(int cell, int H, const REAL *params, const REAL *hp, c
             J[2 * H + j] = d2 * b[j];
             J[3 * H + j] = d2 * a[j];
         }
-    } else if (cell == CELL_TRI_TANH) {
+    } else if (mix_dim(cell)) {
+        const int N = mix_dim(cell);
         int a, b;
         for (j = 0; j < H; ++j)
-            for (a = 0; a < 3; ++a) {
+            for (a = 0; a < N; ++a) {
                 REAL s = u[a * H + j], t;
-                for (b = 0; b < 3; ++b) s += params[(3 * a + b) * H + j] * hp[b * H + j];
+                for (b = 0; b < N; ++b) s += params[(N * a + b) * H + j] * hp[b * H + j];
                 t = tanh_r(s);
-                for (b = 0; b < 3; ++b) J[(3 * a + b) * H + j] = ((REAL)1 - t * t) * params[(3 * a + b) * H + j];
+                for (b = 0; b < N; ++b) J[(N * a + b) * H + j] = ((REAL)1 - t * t) * params[(N * a + b) * H + j];
             }
     } else if (cell == CELL_TANH_DENSE) {
         int i;
@@ -356,11 +366,15 @@ static void jac_apply(int kind, int H, const REAL *J, const REAL *x, REAL *y)
             y[j] = J[0 * H + j] * xc + J[1 * H + j] * xh;
             y[H + j] = J[2 * H + j] * xc + J[3 * H + j] * xh;
         }
-    } else if (kind == JAC_BLOCK3) {
+    } else if (block_dim(kind)) {
+        const int N = block_dim(kind);
+        int q;
         for (j = 0; j < H; ++j)
-            for (i = 0; i < 3; ++i)
-                y[i * H + j] = J[(3 * i + 0) * H + j] * x[j] + J[(3 * i + 1) * H + j] * x[H + j] +
-                               J[(3 * i + 2) * H + j] * x[2 * H + j];
+            for (i = 0; i < N; ++i) {
+                REAL s = J[(N * i) * H + j] * x[j];
+                for (q = 1; q < N; ++q) s += J[(N * i + q) * H + j] * x[q * H + j];
+                y[i * H + j] = s;
+            }
     } else {
         for (i = 0; i < H; ++i) {
             REAL s = 0;
@@ -377,9 +391,10 @@ static void jac_keep_diagonal(int kind, int H, REAL *J)
     int i, j;
     if (kind == JAC_BLOCK2) {
         for (j = 0; j < H; ++j) J[1 * H + j] = J[2 * H + j] = 0;
-    } else if (kind == JAC_BLOCK3) {
-        for (i = 0; i < 9; ++i)
-            if (i % 4 != 0)
+    } else if (block_dim(kind)) {
+        const int N = block_dim(kind);
+        for (i = 0; i < N * N; ++i)
+            if (i % (N + 1) != 0)
                 for (j = 0; j < H; ++j) J[i * H + j] = 0;
     } else if (kind != JAC_DIAG) {
         for (i = 0; i < H; ++i)
@@ -403,13 +418,16 @@ static void jac_mul(int kind, int H, const REAL *A, const REAL *Bm, REAL *C)
             C[2 * H + j] = a10 * b00 + a11 * b10;
             C[3 * H + j] = a10 * b01 + a11 * b11;
         }
-    } else if (kind == JAC_BLOCK3) {
+    } else if (block_dim(kind)) {
+        const int N = block_dim(kind);
+        int q;
         for (j = 0; j < H; ++j)
-            for (i = 0; i < 3; ++i)
-                for (k = 0; k < 3; ++k)
-                    C[(3 * i + k) * H + j] = A[(3 * i + 0) * H + j] * Bm[(0 + k) * H + j] +
-                                             A[(3 * i + 1) * H + j] * Bm[(3 + k) * H + j] +
-                                             A[(3 * i + 2) * H + j] * Bm[(6 + k) * H + j];
+            for (i = 0; i < N; ++i)
+                for (k = 0; k < N; ++k) {
+                    REAL s = A[(N * i) * H + j] * Bm[k * H + j];
+                    for (q = 1; q < N; ++q) s += A[(N * i + q) * H + j] * Bm[(N * q + k) * H + j];
+                    C[(N * i + k) * H + j] = s;
+                }
     } else {
         for (i = 0; i < H; ++i)
             for (j = 0; j < H; ++j) {
@@ -477,7 +495,7 @@ REAL oracle_residual_norm(int cell, int B, int L, int H, const REAL *params, con
  * has no sub-diagonal block).  J [L][jac_size], r and delta [L][S*H]. */
 void oracle_forward_substitution(int kind, int L, int H, const REAL *J, const REAL *r, REAL *delta)
 {
-    const int S = kind == JAC_BLOCK2 ? 2 : kind == JAC_BLOCK3 ? 3 : 1;
+    const int S = kind == JAC_BLOCK2 ? 2 : block_dim(kind) ? block_dim(kind) : 1;
     const size_t n = (size_t)S * H, js = jac_size(kind, H);
     int l;
     size_t j;
@@ -500,7 +518,7 @@ void oracle_forward_substitution(int kind, int L, int H, const REAL *J, const RE
  * of the previous step (two buffers). */
 void oracle_parallel_reduce(int kind, int L, int H, const REAL *J, const REAL *r, REAL *delta)
 {
-    const int S = kind == JAC_BLOCK2 ? 2 : kind == JAC_BLOCK3 ? 3 : 1;
+    const int S = kind == JAC_BLOCK2 ? 2 : block_dim(kind) ? block_dim(kind) : 1;
     const size_t n = (size_t)S * H, js = jac_size(kind, H);
     REAL *A = (REAL *)malloc(sizeof(REAL) * js * L), *A2 = (REAL *)malloc(sizeof(REAL) * js * L);
     REAL *d = (REAL *)malloc(sizeof(REAL) * n * L), *d2 = (REAL *)malloc(sizeof(REAL) * n * L);
@@ -749,21 +767,24 @@ void oracle_backward(int cell, int B, int L, int H, const REAL *params, const RE
                     lprev[j] = a[j] * d1 + bb[j] * d2;
                     lprev[H + j] = -bb[j] * d1 + a[j] * d2;
                 }
-            } else if (cell == CELL_TRI_TANH) {
+            } else if (mix_dim(cell)) {
+                const int N = mix_dim(cell);
                 int a, c;
                 for (j = 0; j < H; ++j) {
-                    REAL d[3];
-                    for (a = 0; a < 3; ++a) {
+                    REAL d[4];
+                    for (a = 0; a < N; ++a) {
                         REAL s = ul[a * H + j], t;
-                        for (c = 0; c < 3; ++c) s += params[(3 * a + c) * H + j] * hp[c * H + j];
+                        for (c = 0; c < N; ++c) s += params[(N * a + c) * H + j] * hp[c * H + j];
                         t = tanh_r(s);
                         d[a] = lam[a * H + j] * ((REAL)1 - t * t);              /* through tanh */
                         dul[a * H + j] = d[a];
-                        for (c = 0; c < 3; ++c) dp[(3 * a + c) * H + j] += d[a] * hp[c * H + j];
+                        for (c = 0; c < N; ++c) dp[(N * a + c) * H + j] += d[a] * hp[c * H + j];
                     }
-                    for (c = 0; c < 3; ++c)
-                        lprev[c * H + j] = params[(0 + c) * H + j] * d[0] + params[(3 + c) * H + j] * d[1] +
-                                           params[(6 + c) * H + j] * d[2];
+                    for (c = 0; c < N; ++c) {
+                        REAL s = params[c * H + j] * d[0];
+                        for (a = 1; a < N; ++a) s += params[(N * a + c) * H + j] * d[a];
+                        lprev[c * H + j] = s;
+                    }
                 }
             } else if (cell == CELL_TANH_DENSE) {
                 const REAL *hl = h + ((size_t)b * L + l) * n;

@@ -13,8 +13,8 @@ import pytest
 NL_CELLS = ["gru_nl:tanh,softsign,identity", "gru_nl:sigmoid,sigmoid,softsign", "gru_nl:softsign,tanh,sigmoid"]
 DIAG_CELLS = ["gru_diag", "linear_diag"] + NL_CELLS
 BLOCK2_CELLS = ["lstm_diag", "paralstm_diag", "rot_tanh"]
-BLOCK3_CELLS = ["tri_tanh"]
-ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag", "rot_tanh", "tri_tanh"] + NL_CELLS
+BLOCK3_CELLS = ["tri_tanh", "quad_tanh"]          # 3x3 and 4x4 blocks
+ALL_CELLS = ["gru_diag", "lstm_diag", "tanh_dense", "linear_diag", "paralstm_diag", "rot_tanh", "tri_tanh", "quad_tanh"] + NL_CELLS
 
 
 def sig(x):
@@ -31,8 +31,8 @@ def rand_params(oracle, cell, H, rng, bound=0.9, bias=True):
         if bias:
             p[5:] = rng.normal(0, 0.3, (3, H))
         return p
-    if cell == "tri_tanh":               # the per-channel 3x3 matrix, [3][3][H] as 9 rows
-        return rng.uniform(-bound / 2, bound / 2, (9, H))
+    if cell in ("tri_tanh", "quad_tanh"):    # the per-channel N x N matrix, [N][N][H] as N*N rows
+        return rng.uniform(-bound / 2, bound / 2, (S * S, H)) * (1.0 if S == 3 else 0.75)
     if cell == "rot_tanh":               # a, b of the per-channel rotation-scaling
         return rng.uniform(-bound / 1.5, bound / 1.5, (2, H))
     p = np.zeros((2, G, H))
@@ -216,8 +216,9 @@ def _rand_system(kind, L, H, rng, scale=0.9):
         return rng.uniform(-scale, scale, (L, H)), rng.normal(0, 1, (L, H))
     if kind == "block2":
         return rng.uniform(-scale, scale, (L, 2, 2, H)), rng.normal(0, 1, (L, 2, H))
-    if kind == "block3":
-        return rng.uniform(-scale / 1.5, scale / 1.5, (L, 3, 3, H)), rng.normal(0, 1, (L, 3, H))
+    if kind in ("block3", "block4"):
+        N = int(kind[-1])
+        return rng.uniform(-scale / 1.5, scale / 1.5, (L, N, N, H)) * 3 / N, rng.normal(0, 1, (L, N, H))
     return rng.normal(0, scale / math.sqrt(H), (L, H, H)), rng.normal(0, 1, (L, H))
 
 
@@ -226,7 +227,7 @@ def _dense_view(kind, J, H):
     L = J.shape[0]
     if kind == "diag":
         return np.stack([np.diag(J[l]) for l in range(L)])
-    if kind in ("block2", "block3"):
+    if kind in ("block2", "block3", "block4"):
         S = J.shape[1]
         out = np.zeros((L, S * H, S * H))
         for l in range(L):
@@ -236,7 +237,7 @@ def _dense_view(kind, J, H):
     return J
 
 
-@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "dense"])
+@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "block4", "dense"])
 def test_forward_substitution_equals_unrolled_sum(oracle_mod, kind):
     """Eq. (5): delta_l = sum_{s<=l} (J_l J_{l-1} ... J_{s+1}) r_s, by brute force."""
     o = oracle_mod
@@ -256,7 +257,7 @@ def test_forward_substitution_equals_unrolled_sum(oracle_mod, kind):
             assert np.allclose(got[l], want, rtol=1e-12, atol=1e-13)
 
 
-@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "dense"])
+@pytest.mark.parametrize("kind", ["diag", "block2", "block3", "block4", "dense"])
 def test_parallel_reduce_equals_dense_solve(oracle_mod, kind):
     """Alg. 1b solves the block bi-diagonal system of Eq. (3): compare with a
     dense LAPACK solve of (I - subdiag(J)) delta = r, for every L up to 70
@@ -313,7 +314,7 @@ def test_linear_cell_one_newton_solve_is_exact(oracle_mod):
     assert np.max(np.abs(h1 - ref)) < 1e-13
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh", "quad_tanh"])
 def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     """Sec. 2.1: convergence in at most L Newton steps is guaranteed because
     after k solves the first k states equal the sequential result, whatever the
@@ -335,7 +336,7 @@ def test_newton_first_k_states_exact_after_k_iterations(oracle_mod, cell):
     assert np.max(np.abs(hL - ref)) < 1e-11
 
 
-@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh"])
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "tanh_dense", "paralstm_diag", "tri_tanh", "quad_tanh"])
 def test_newton_converges_quadratically_to_the_unroll(oracle_mod, cell):
     """App. A: the residual falls to machine precision in a handful of
     iterations; the converged iterate is the sequential result of Eq. (1)."""
@@ -589,35 +590,36 @@ def test_rot_tanh_is_the_dense_cell_with_a_2x2_matrix(oracle_mod):
     assert np.allclose(dpr.ravel(), [dWd[0, 0] + dWd[1, 1], dWd[1, 0] - dWd[0, 1]], rtol=0, atol=1e-13)
 
 
-def test_tri_tanh_is_the_dense_cell_with_a_3x3_matrix_per_channel(oracle_mod):
-    """Each channel of the 3x3-block example cell is h' = tanh(M h + u) with that channel's own
+@pytest.mark.parametrize("cell,N", [("tri_tanh", 3), ("quad_tanh", 4)])
+def test_mixing_cells_are_the_dense_cell_with_an_nxn_matrix_per_channel(oracle_mod, cell, N):
+    """Each channel of the N x N-block example cells is h' = tanh(M h + u) with that channel's own
     matrix M: step, Jacobian, Newton solve (both Jacobian modes) and backward must agree with the
-    dense cell at H = 3, channel by channel (channels do not mix)."""
+    dense cell at H = N, channel by channel (channels do not mix)."""
     o = oracle_mod
     rng = np.random.default_rng(96)
     L, H = 10, 2
-    M = rng.uniform(-0.45, 0.45, (H, 3, 3))                  # M[channel][a][b]
-    pt = np.transpose(M, (1, 2, 0)).reshape(9, H)            # rows m_ab, channels last
-    ut = rng.normal(0, 1, (1, L, 3, H)); h0t = rng.normal(0, 0.3, (1, 3, H)); gt = rng.normal(0, 1, (1, L, 3, H))
-    ht = o.seq_unroll("tri_tanh", pt, ut, h0t)
-    Jt = o.cell_jacobian("tri_tanh", pt, h0t[0], ut[0, 0])
-    nt = o.newton("tri_tanh", pt, ut, h0t, tol=-1.0, max_iter=3)
-    qt = o.newton("tri_tanh", pt, ut, h0t, tol=-1.0, max_iter=3, jacobian="diagonal")
-    dut, dpt, dh0t = o.backward("tri_tanh", pt, ut, h0t, ht, gt)
+    M = rng.uniform(-0.45, 0.45, (H, N, N)) * 3 / N          # M[channel][a][b]
+    pt = np.transpose(M, (1, 2, 0)).reshape(N * N, H)        # rows m_ab, channels last
+    ut = rng.normal(0, 1, (1, L, N, H)); h0t = rng.normal(0, 0.3, (1, N, H)); gt = rng.normal(0, 1, (1, L, N, H))
+    ht = o.seq_unroll(cell, pt, ut, h0t)
+    Jt = o.cell_jacobian(cell, pt, h0t[0], ut[0, 0])
+    nt = o.newton(cell, pt, ut, h0t, tol=-1.0, max_iter=3)
+    qt = o.newton(cell, pt, ut, h0t, tol=-1.0, max_iter=3, jacobian="diagonal")
+    dut, dpt, dh0t = o.backward(cell, pt, ut, h0t, ht, gt)
     for ch in range(H):
         W = M[ch]
-        u = ut[:, :, :, ch].reshape(1, L, 1, 3); h0 = h0t[:, :, ch].reshape(1, 1, 3); g = gt[:, :, :, ch].reshape(1, L, 1, 3)
+        u = ut[:, :, :, ch].reshape(1, L, 1, N); h0 = h0t[:, :, ch].reshape(1, 1, N); g = gt[:, :, :, ch].reshape(1, L, 1, N)
         hd = o.seq_unroll("tanh_dense", W, u, h0)
-        assert np.allclose(ht[0, :, :, ch], hd.reshape(L, 3), rtol=0, atol=1e-15)
+        assert np.allclose(ht[0, :, :, ch], hd.reshape(L, N), rtol=0, atol=1e-15)
         assert np.allclose(Jt[:, :, ch], o.cell_jacobian("tanh_dense", W, h0[0], u[0, 0]), rtol=0, atol=1e-15)
         nd = o.newton("tanh_dense", W, u, h0, tol=-1.0, max_iter=3)
         qd = o.newton("tanh_dense", W, u, h0, tol=-1.0, max_iter=3, jacobian="diagonal")
-        assert np.allclose(nt[0][0, :, :, ch], nd[0].reshape(L, 3), rtol=0, atol=1e-14)
-        assert np.allclose(qt[0][0, :, :, ch], qd[0].reshape(L, 3), rtol=0, atol=1e-14)
+        assert np.allclose(nt[0][0, :, :, ch], nd[0].reshape(L, N), rtol=0, atol=1e-14)
+        assert np.allclose(qt[0][0, :, :, ch], qd[0].reshape(L, N), rtol=0, atol=1e-14)
         dud, dWd, dh0d = o.backward("tanh_dense", W, u, h0, hd, g)
-        assert np.allclose(dut[0, :, :, ch], dud.reshape(L, 3), rtol=0, atol=1e-14)
+        assert np.allclose(dut[0, :, :, ch], dud.reshape(L, N), rtol=0, atol=1e-14)
         assert np.allclose(dh0t[0, :, ch], dh0d.ravel(), rtol=0, atol=1e-14)
-        assert np.allclose(dpt[:, ch].reshape(3, 3), dWd, rtol=0, atol=1e-13)
+        assert np.allclose(dpt[:, ch].reshape(N, N), dWd, rtol=0, atol=1e-13)
 
 
 # ---------------------------------------------------------- input projection
