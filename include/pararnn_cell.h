@@ -14,7 +14,7 @@
  * A cell struct provides
  *
  *     static constexpr int G;    gate pre-activations per step and channel: u is [B][L][G][H]
- *     static constexpr int S;    state values per channel (1: diagonal Jacobian, 2: 2x2 blocks, 3: 3x3 blocks)
+ *     static constexpr int S;    state values per channel (1: diagonal Jacobian; 2, 3, 4: blocks of that size)
  *     static constexpr int P;    parameter rows: params is [P][H] fp32
  *     static constexpr int NC;   coefficients handed from bwd_prep to bwd_emit
  *
@@ -59,7 +59,7 @@ namespace pararnn {
 // optional pre-scaled ("folded") gate arithmetic is not used: u and the parameters reach the
 // cell unchanged.
 template <class Impl> struct UserCell {
-    static_assert(Impl::S >= 1 && Impl::S <= 3, "state values per channel: 1, 2 or 3");
+    static_assert(Impl::S >= 1 && Impl::S <= 4, "state values per channel: 1 to 4");
     static_assert(Impl::G >= 1 && Impl::P >= 1 && Impl::NC >= 1, "G, P and NC must be positive");
     static constexpr int G = Impl::G, S = Impl::S, PR = Impl::P, NC = Impl::NC, PQ = 0;
 

@@ -109,7 +109,7 @@ def _api(cell):
 
 
 def example_cell(name: str) -> UserCell:
-    """One of the example cells shipped under user_cells/ ("gru_softsign", "rot_tanh", "tri_tanh")."""
+    """One of the example cells shipped under user_cells/ ("gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh")."""
     return UserCell(os.path.join(_PKG, f"libpararnn_{name}.so"), name)
 
 

@@ -60,15 +60,16 @@ def build(jobs: int | None = None, extra_flags=(), verbose: bool = False) -> str
     return LIB
 
 
-def build_cell(src: str, out: str | None = None, extra_flags=(), verbose: bool = False) -> str:
+def build_cell(src: str, out: str | None = None, extra_flags=(), verbose: bool = False, obj: str | None = None) -> str:
     """Compile one .hip file that defines a cell (PARARNN_DEFINE_CELL) into a shared
-    library next to libpararnn.so (or at `out`), linked against libpararnn.so."""
+    library next to libpararnn.so (or at `out`), linked against libpararnn.so.
+    `obj`: an object file already compiled from `src` (only the link is done)."""
     if not os.path.exists(LIB):
         raise RuntimeError(f"{LIB} is missing: build the library first")
     os.makedirs(OBJ, exist_ok=True)
     stem = os.path.splitext(os.path.basename(src))[0]
     out = out or os.path.join(PKG, f"libpararnn_{stem}.so")
-    obj = _compile(src, list(extra_flags))
+    obj = obj or _compile(src, list(extra_flags))
     rpath = "$ORIGIN" if os.path.dirname(os.path.abspath(out)) == PKG else PKG
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", out, obj,
            f"-L{PKG}", "-lpararnn", f"-Wl,-rpath,{rpath}"]
@@ -87,6 +88,20 @@ def build_examples(jobs: int | None = None, verbose: bool = False):
         return list(ex.map(lambda s: build_cell(s, verbose=verbose), srcs))
 
 
+def build_all(jobs: int | None = None, verbose: bool = False):
+    """The library and the example cells; the cells' objects compile alongside the library's (they
+    only need the library at link time)."""
+    os.makedirs(OBJ, exist_ok=True)
+    cells = sorted(glob.glob(os.path.join(USER_CELLS, "*.hip")))
+    with cf.ThreadPoolExecutor(max_workers=jobs or min(8, os.cpu_count() or 1)) as ex:
+        # the slowest translation units first
+        cell_objs = [ex.submit(_compile, s, []) for s in reversed(cells)]
+        lib = ex.submit(build, jobs, (), verbose)
+        lib.result()
+        objs = [f.result() for f in cell_objs][::-1]
+    return [build_cell(s, verbose=verbose, obj=o) for s, o in zip(cells, objs)]
+
+
 if __name__ == "__main__":
     import argparse
     ap = argparse.ArgumentParser(description=__doc__)
@@ -96,5 +111,4 @@ if __name__ == "__main__":
     if args.cell:
         build_cell(args.cell, args.out, verbose=True)
     else:
-        build(verbose=True)
-        build_examples(verbose=True)
+        build_all(verbose=True)

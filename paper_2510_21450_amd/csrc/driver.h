@@ -47,7 +47,11 @@ inline TileCfg choose_tile(const CellInfo &ci, int dtype, bool backward, int H, 
     const bool lstm = ci.S >= 2, bf = dtype == PARARNN_BF16;
     if (H <= 8) {
         cfg = {1, 8, 4, 2};                              // 8 channels x 64 steps
-    } else if (ci.S >= 3) {
+    } else if (ci.S >= 4) {
+        // 4x4 blocks: 20 prefix values per step; four steps per thread (a few registers spill in the
+        // fused and backward kernels, the next larger shape spills a hundred)
+        cfg = {1, 1, 4, 8};                              // 64 channels x 32 steps
+    } else if (ci.S == 3) {
         // 3x3 blocks: a step keeps S*S + S prefix values in registers; eight steps per thread is the
         // most that fits without spilling (190-230 registers, two waves per SIMD) and measured
         // fastest forward, fused and backward alike

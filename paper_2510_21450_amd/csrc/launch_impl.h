@@ -14,6 +14,14 @@ template <typename K> static int persistent_grid(K kernel, int threads, int n_ti
     return (int)(n_tiles < cap ? n_tiles : cap);
 }
 
+// Tile shapes instantiated for a cell.  Blocks of 3x3 and larger keep S*S + S prefix values per
+// step in registers: beyond eight (3x3) or four (4x4) steps per thread and one channel per lane the
+// kernels spill by the hundred, so those shapes are not built (the launch reports UNSUPPORTED).
+template <class Cell, int VEC, int C> constexpr bool shape_offered()
+{
+    return Cell::S <= 2 || (VEC == 1 && C <= (Cell::S == 3 ? 8 : 4));
+}
+
 // static LDS of the forward kernels must stay within 64 KiB
 template <class Cell, int VEC, int LL, int W> constexpr bool forward_fits_lds()
 {
@@ -76,7 +84,7 @@ hipError_t Kernels<Cell, UT>::newton_iter(const TileCfg &cfg, const FwdArgs &a, 
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
-        if constexpr (forward_fits_lds<Cell, V, LLv, W>()) {                                   \
+        if constexpr (shape_offered<Cell, V, C>() && forward_fits_lds<Cell, V, LLv, W>()) {    \
             static int grid_cap[2] = {0, 0}; /* per instantiation */                           \
             constexpr bool kFoldGuess = !IsRaw<Cell>::value;                                   \
             const int first = (kFoldGuess && fold_guess) ? 1 : 0;                              \
@@ -105,12 +113,16 @@ hipError_t Kernels<Cell, UT>::newton_fused(const TileCfg &cfg, const FusedArgs &
     } else {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
-        static int grid_cap = 0;                                                               \
-        auto kern = newton_fused_kernel<Cell, V, LLv, C, W, UT>;                               \
-        if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);               \
-        const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                      \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                       \
-        return hipGetLastError();                                                              \
+        if constexpr (shape_offered<Cell, V, C>()) {                                           \
+            static int grid_cap = 0;                                                           \
+            auto kern = newton_fused_kernel<Cell, V, LLv, C, W, UT>;                           \
+            if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \
+            const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                  \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
+            return hipGetLastError();                                                          \
+        } else {                                                                               \
+            return hipErrorInvalidValue;                                                       \
+        }                                                                                      \
     }
         PARARNN_SHAPES(PARARNN_CASE)
 #undef PARARNN_CASE
@@ -123,7 +135,7 @@ hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hip
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
-        if constexpr (backward_fits_lds<Cell, V, LLv, W>()) {                                  \
+        if constexpr (shape_offered<Cell, V, C>() && backward_fits_lds<Cell, V, LLv, W>()) {   \
             static int grid_cap = 0;                                                           \
             auto kern = backward_kernel<Cell, V, LLv, C, W, UT>;                               \
             if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \

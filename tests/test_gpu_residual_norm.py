@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 from workloads import CONFIGS, make_inputs              # noqa: E402
 from workloads.rng import normal, uniform_sym           # noqa: E402
 
-ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh", "tri_tanh": "tri_tanh"}
+ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh", "tri_tanh": "tri_tanh",
+               "quad_tanh": "quad_tanh"}
 
 
 def f64(t):
@@ -38,6 +39,8 @@ def problem(P, cell, B, L, H, seed, dtype=torch.float32, h0=True):
         params = uniform_sym(seed, 2, (2, H), 0.6, device=dev)
     elif name == "tri_tanh":
         params = uniform_sym(seed, 2, (9, H), 0.45, device=dev)
+    elif name == "quad_tanh":
+        params = uniform_sym(seed, 2, (16, H), 0.34, device=dev)
     elif name == "paralstm_diag":
         params = torch.zeros(8, H, device=dev)
         params[:5] = uniform_sym(seed, 2, (5, H), 0.9, device=dev)
@@ -93,7 +96,7 @@ def test_residual_norm_dense(oracle_mod, as_stored, shape):
         P.residual_norm("tanh_dense", params, u.bfloat16(), None, hk.bfloat16())
 
 
-@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh"])
+@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh"])
 def test_residual_norm_user_cells(oracle_mod, as_stored, name):
     import paper_2510_21450_amd as P
     cell = P.example_cell(name)

@@ -1,7 +1,7 @@
 """GPU parity of the cells added through include/pararnn_cell.h (the example
 libraries under paper_2510_21450_amd/user_cells/): the GRU with a softsign state
 nonlinearity (selectable nonlinearities, App. D.3) and from-scratch cells with
-2x2 and with 3x3 Jacobian blocks.  Same bars as the built-in cells: fp32 1e-5 norm-wise
+2x2, 3x3 and 4x4 Jacobian blocks.  Same bars as the built-in cells: fp32 1e-5 norm-wise
 against the fp64 oracle, bf16 storage 2e-2, iteration counts exact where the
 stopping decision has a clear margin."""
 import numpy as np
@@ -15,7 +15,8 @@ from workloads.rng import normal, uniform_sym               # noqa: E402
 TOL_F32 = 1e-5
 TOL_BF16 = 2e-2
 TOL_CHAIN = 3e-5        # forward and backward run by each side on its own: the backward's 1e-5 plus the effect of states that differ by <= 1e-5
-ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh", "tri_tanh": "tri_tanh"}
+ORACLE_NAME = {"gru_softsign": "gru_nl:sigmoid,sigmoid,softsign", "rot_tanh": "rot_tanh", "tri_tanh": "tri_tanh",
+               "quad_tanh": "quad_tanh"}
 
 
 def relerr(got, ref):
@@ -33,6 +34,8 @@ def problem(cell, B, L, H, seed, dtype=torch.float32):
         params = uniform_sym(seed, 2, (2, H), 0.6, device=dev)
     elif cell.name == "tri_tanh":
         params = uniform_sym(seed, 2, (9, H), 0.45, device=dev)
+    elif cell.name == "quad_tanh":
+        params = uniform_sym(seed, 2, (16, H), 0.34, device=dev)
     else:
         params = torch.zeros(2, cell.G, H, device=dev)
         params[0] = uniform_sym(seed, 2, (cell.G, H), 0.9, device=dev)
@@ -46,7 +49,7 @@ def problem(cell, B, L, H, seed, dtype=torch.float32):
 SHAPES = [(1, 1, 8), (2, 33, 1), (2, 100, 24), (3, 257, 68), (2, 1000, 130), (1, 65, 6), (2, 3000, 64)]
 
 
-@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh"])
+@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh"])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_user_cell_forward_backward_f32(oracle_mod, as_stored, name, shape):
     import paper_2510_21450_amd as P
@@ -81,7 +84,7 @@ def test_user_cell_forward_backward_f32(oracle_mod, as_stored, name, shape):
     assert relerr(to_np(dh0), rdh0) <= TOL_F32
 
 
-@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh"])
+@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh"])
 @pytest.mark.parametrize("fused", [True, False])
 def test_user_cell_per_iteration_and_fused_paths_agree(oracle_mod, name, fused):
     """Every launch kind is instantiated for a user cell: fused blocks (default),
@@ -105,7 +108,7 @@ def test_user_cell_per_iteration_and_fused_paths_agree(oracle_mod, name, fused):
         P.set_fused(True)
 
 
-@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh"])
+@pytest.mark.parametrize("name", ["gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh"])
 def test_user_cell_bf16_storage(oracle_mod, as_stored, name):
     import paper_2510_21450_amd as P
     cell = P.example_cell(name)
