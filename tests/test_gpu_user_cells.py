@@ -141,3 +141,24 @@ def test_user_cell_through_autograd(oracle_mod):
     errs = (relerr(to_np(h), ref), relerr(to_np(u.grad), rdu), relerr(to_np(params.grad), rdp), relerr(to_np(h0.grad), rdh0))
     print(f"autograd chain rot_tanh: rel err h, du, dparams, dh0 = {errs}", flush=True)
     assert errs[0] <= TOL_F32 and max(errs[1:]) <= TOL_CHAIN
+
+
+def test_block_cells_refuse_tile_shapes_that_are_not_built():
+    """For 3x3 and 4x4 blocks only the tile shapes with few steps per thread are instantiated: a
+    forced shape outside them is refused by the host (UNSUPPORTED), an offered one works."""
+    import paper_2510_21450_amd as P
+    for name, offered, refused in (("tri_tanh", (1, 1, 4, 8), (1, 1, 16, 8)), ("quad_tanh", (1, 8, 4, 2), (1, 1, 8, 8))):
+        cell = P.example_cell(name)
+        params, u, h0, g = problem(cell, 2, 200, 64, seed=3400)
+        try:
+            P.set_tile(*refused)
+            with pytest.raises(RuntimeError, match="UNSUPPORTED"):
+                P.forward(cell, params, u, h0, tol=1e-5, max_iter=8)
+            with pytest.raises(RuntimeError, match="UNSUPPORTED"):
+                P.backward(cell, params, u, h0, torch.zeros_like(g), g)
+            P.set_tile(*offered)
+            h, iters, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=40)
+            torch.cuda.synchronize()
+            assert int(iters.cpu()[1]) == 0
+        finally:
+            P.set_tile(0)
