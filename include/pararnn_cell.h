@@ -46,6 +46,11 @@
  *     int    name_residual_norm(int dtype, params, u, h0, h, B, L, H, out, hip_stream);
  * with the semantics, status codes and error behaviour of the pararnn_* functions
  * of the same name.
+ *
+ * Tile shapes: the automatic choice depends on S.  For S = 3 (4) only the shapes with one channel
+ * per lane and at most 8 (4) timesteps per thread are instantiated (larger ones would keep more
+ * prefix values per thread than the register file holds); a shape forced with pararnn_set_tile
+ * outside them makes the call return PARARNN_UNSUPPORTED.
  */
 #ifndef PARARNN_CELL_H
 #define PARARNN_CELL_H
