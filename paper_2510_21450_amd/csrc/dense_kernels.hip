@@ -878,7 +878,7 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
         const CellInfo ci = {1, 1, 0, -1};
         const Layout sl = make_layout(ci, PARARNN_F32, B, L, DH, false, 4);
         unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_A);
-        if (lo.off_A + sl.n_rec * sizeof(unsigned long long) > lo.off_b) return PARARNN_INTERNAL;
+        if (lo.off_A + sl.n_rec * sizeof(unsigned long long) > lo.off_b) return PARARNN_WORKSPACE_TOO_SMALL;   // cannot happen: 24 B of records per 64 steps against 16 KB of products per 16
         if (launch_reset(a.ctrl, rec, sl.n_rec, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
         FwdArgs f;
