@@ -191,6 +191,29 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
                     float *delta_trace, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * pararnn_forward for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and status codes as
+ * pararnn_forward without the workspace pair: the scratch memory (control
+ * block, carry records, tile-boundary rows, the fp32 iterate of bf16 storage;
+ * the dense cell's factors and chunk products) is a static device array of
+ * PARARNN_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU the
+ * library runs on, held until the process ends.  The call allocates and frees
+ * nothing; what must start at zero is cleared by a kernel on the stream at the
+ * start of every call.  A problem whose workspace does not fit the array
+ * returns PARARNN_WORKSPACE_TOO_SMALL and enqueues nothing (a solve to a
+ * tolerance first gives up the carry-record slots of its multi-iteration first
+ * launch and runs one launch per iteration; pararnn_workspace_bytes(.., 0) with
+ * pararnn_set_fused(0) is the smallest size that still fits).  All calls on one
+ * GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race, exactly as two pararnn_forward calls that share a workspace.
+ */
+#define PARARNN_NOALLOC_SCRATCH_BYTES (32u << 20)
+int pararnn_forward_noalloc(int cell, int dtype, const float *params, const void *u, const void *h0,
+                            int B, int L, int H, float tol, int max_iter, void *h, int *iters,
+                            float *delta_trace, void *hip_stream);
+
+/*
  * Backward: the adjoint recurrence of Eq. (6) at the forward result h,
  *   lam_L = g_L,  lam_{l-1} = J_l^T lam_l + g_{l-1},  J_l = df/dh at (h_{l-1}, u_l),
  * evaluated as one reverse prefix scan, plus the step-local gradients

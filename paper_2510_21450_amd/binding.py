@@ -45,6 +45,8 @@ _lib.pararnn_solve_plan.restype = _i
 _lib.pararnn_solve_plan.argtypes = [ctypes.c_float, _i, ctypes.POINTER(ctypes.c_int), _i]
 _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.pararnn_forward_noalloc.restype = _i
+_lib.pararnn_forward_noalloc.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp]
 _lib.pararnn_backward.restype = _i
 _lib.pararnn_backward.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.pararnn_dense_chunk_products.restype = _i
@@ -262,6 +264,26 @@ def forward(cell, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, tra
                    _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
     _raise(code, f"{api.what}_forward")
     return h, iters, tr
+
+
+def forward_noalloc(cell, params, u, h0, tol, max_iter, out, iters, delta_trace=None, stream=None):
+    """pararnn_forward_noalloc (built-in cells): the solve of `forward` on the library's static
+    scratch array.  Nothing is allocated here either: `out` [B][L][S][H], `iters` (device int32[2])
+    and, if wanted, `delta_trace` (device float[max_iter]) are the caller's.  Returns the C status
+    code (0 = enqueued); a problem too large for the array gives WORKSPACE_TOO_SMALL (3)."""
+    G, S = cell_dims(cell)
+    B, L, Gu, H = u.shape
+    dt = u.dtype
+    _check(u, "u", dt, (B, L, G, H))
+    _check(params, "params", torch.float32)
+    if h0 is not None:
+        _check(h0, "h0", dt, (B, S, H))
+    _check(out, "h", dt, (B, L, S, H))
+    _check(iters, "iters", torch.int32, (2,))
+    if delta_trace is not None:
+        _check(delta_trace, "delta_trace", torch.float32, (max(max_iter, 1),))
+    return _lib.pararnn_forward_noalloc(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol,
+                                        max_iter, _ptr(out), _ptr(iters), _ptr(delta_trace), _stream(stream))
 
 
 def backward(cell, params, u, h0, h, dL_dh, want_dh0: bool = True, workspace=None, stream=None, out=None):

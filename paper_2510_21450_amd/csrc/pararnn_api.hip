@@ -1,5 +1,7 @@
 // C ABI of the library (see include/pararnn.h) for the built-in cells; the
 // cell-generic host driver is driver.h.  No kernel code here.
+#include <mutex>
+
 #include "dense.h"
 #include "driver.h"
 #include "proj.h"
@@ -16,7 +18,31 @@ Settings &settings()
 
 }  // namespace pararnn
 
+// Scratch of pararnn_forward_noalloc: one copy per GPU the library runs on, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the
+// device address that call returned.
+static __device__ __align__(256) unsigned char scratch[PARARNN_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];    // device address of `scratch` on each device, once looked up
+
+// Device address of the current device's copy of `scratch` (looked up once per device, with that
+// device current), or NULL when the runtime refuses.
+void *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool cell_info(int cell, CellInfo *ci)
 {
@@ -162,6 +188,19 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     }
 #undef PARARNN_FWD
     return PARARNN_INVALID_ARG;
+}
+
+int pararnn_forward_noalloc(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
+                            int H, float tol, int max_iter, void *h, int *iters, float *delta_trace,
+                            void *hip_stream)
+{
+    void *ptr = scratch_on_current_device();
+    if (!ptr) return PARARNN_HIP_ERROR;
+    // the same solve as pararnn_forward with the static array as its workspace: the launch sequence
+    // clears what must start at zero (control block, carry records) with a kernel of its own, and a
+    // problem whose smallest workspace exceeds the array is refused with WORKSPACE_TOO_SMALL
+    return pararnn_forward(cell, dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, ptr,
+                           (size_t)PARARNN_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 int pararnn_backward(int cell, int dtype, const float *params, const void *u, const void *h0, const void *h,
