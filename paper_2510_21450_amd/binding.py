@@ -111,7 +111,8 @@ def _api(cell):
 
 
 def example_cell(name: str) -> UserCell:
-    """One of the example cells shipped under user_cells/ ("gru_softsign", "rot_tanh", "tri_tanh", "quad_tanh")."""
+    """One of the example cells shipped under user_cells/ ("gru_softsign", "gru_sigmoid_identity_tanh",
+    "gru_sigmoid_softsign_identity", "gru_sigmoid_tanh_softsign", "rot_tanh", "tri_tanh", "quad_tanh")."""
     return UserCell(os.path.join(_PKG, f"libpararnn_{name}.so"), name)
 
 

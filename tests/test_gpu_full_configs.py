@@ -16,6 +16,7 @@ import torch
 pytestmark = pytest.mark.gpu
 
 from workloads import ALL_CONFIGS as CONFIGS, make_inputs, cell_dims      # noqa: E402
+from parity_util import elt_err                                             # noqa: E402
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "newton_traces.json")
 N_SAMPLE = 48
@@ -42,6 +43,10 @@ def test_full_size_config(name, oracle_mod, as_stored):
     import paper_2510_21450_amd as P
     w = CONFIGS[name]
     bound = 2e-2 if w.dtype == "bf16" else 1e-5
+    # second metric: element-wise relative error with an absolute floor of 1e-3 * max|ref|.  fp32: 1e-3, i.e.
+    # an absolute error of 1e-6 * max|ref| on the small elements (ten times tighter there than the norm-wise
+    # bound); bf16 storage: 2e-2 (the output's own rounding is 2^-9 of every element)
+    ebound = 2e-2 if w.dtype == "bf16" else 1e-3
     print(f"config {name}: generating inputs", flush=True)
     d = make_inputs(w, device="cuda")
     params, u, h0, g = d["params"], d["u"], d["h0"], d["g"]
@@ -77,7 +82,8 @@ def test_full_size_config(name, oracle_mod, as_stored):
     gn = f64(g.index_select(-1, idx))
     print(f"config {name}: oracle on {len(chans)} channels", flush=True)
     ref = oracle_mod.seq_unroll(w.cell, pn, un, h0n)
-    e_h = relerr(f64(h.index_select(-1, idx)), ref)
+    h_s = f64(h.index_select(-1, idx))
+    e_h, ee_h = relerr(h_s, ref), elt_err(h_s, ref)
     # backward at full size.  Channels are independent, so the sampled ones are evaluated on both
     # sides at the oracle's states (written into h after the forward result was compared).
     hs = as_stored(ref, h)
@@ -86,11 +92,14 @@ def test_full_size_config(name, oracle_mod, as_stored):
     du, dp, dh0 = P.backward(w.cell, params, u, h0, h, g)
     torch.cuda.synchronize()
     rdu, rdp, rdh0 = oracle_mod.backward(w.cell, pn, un, h0n, f64(hs), gn)
-    e_du = relerr(f64(du.index_select(-1, idx)), rdu)
+    du_s, dh0_s = f64(du.index_select(-1, idx)), f64(dh0.index_select(-1, idx))
+    e_du, ee_du = relerr(du_s, rdu), elt_err(du_s, rdu)
     e_dp = relerr(f64(dp.index_select(-1, idx)), rdp)
-    e_dh0 = relerr(f64(dh0.index_select(-1, idx)), rdh0)
-    print(f"config {name}: iters={it} rel err h={e_h:.2e} du={e_du:.2e} dparams={e_dp:.2e} dh0={e_dh0:.2e}", flush=True)
+    e_dh0, ee_dh0 = relerr(dh0_s, rdh0), elt_err(dh0_s, rdh0)
+    print(f"config {name}: iters={it} rel err h={e_h:.2e} du={e_du:.2e} dparams={e_dp:.2e} dh0={e_dh0:.2e}; "
+          f"element-wise (floor 1e-3 max|ref|) h={ee_h:.2e} du={ee_du:.2e} dh0={ee_dh0:.2e}", flush=True)
     assert e_h <= bound and e_du <= bound and e_dp <= bound and e_dh0 <= bound
+    assert ee_h <= ebound and ee_du <= ebound and ee_dh0 <= ebound
     # properties that hold at any size: bounded state, finite outputs everywhere
     hh = h[:, :, -1, :] if w.cell in ("lstm_diag", "paralstm_diag") else h
     assert float(hh.abs().max()) <= 1.0

@@ -161,7 +161,8 @@ def test_host_side_argument_validation(lib):
     assert s(0, 0, p, p, 1, 8, 8, p, p, 16, None) == 3
 
 
-@pytest.mark.parametrize("name,gsp", [("gru_softsign", (3, 1, 6)), ("rot_tanh", (2, 2, 2)), ("tri_tanh", (3, 3, 9)),
+@pytest.mark.parametrize("name,gsp", [("gru_softsign", (3, 1, 6)), ("gru_sigmoid_identity_tanh", (3, 1, 6)),
+                                      ("gru_sigmoid_softsign_identity", (3, 1, 6)), ("gru_sigmoid_tanh_softsign", (3, 1, 6)), ("rot_tanh", (2, 2, 2)), ("tri_tanh", (3, 3, 9)),
                                       ("quad_tanh", (4, 4, 16))])
 def test_user_cell_libraries_export_their_abi(lib, name, gsp):
     """A library made by PARARNN_DEFINE_CELL (include/pararnn_cell.h) exports the functions the
