@@ -135,6 +135,13 @@ int pararnn_set_spin_limit(unsigned int polls);
  * iteration. */
 int pararnn_set_fused(int enable);
 
+/* Test / tuning hook (host, process-wide; default 1): enable = 0 keeps the kernels
+ * from copying their inputs straight from memory into LDS one tile ahead (the
+ * variant used for bf16 storage when rows are 16-byte aligned and H % 8 == 0);
+ * they then load through registers, as for every other storage type.  Same
+ * results either way. */
+int pararnn_set_staging(int enable);
+
 /* Tuning hook (host, process-wide): a solve to a tolerance (tol >= 0) runs its
  * first min(n_iters, max_iter) iterations in ONE launch of the fused kernel (u
  * read once, the iterate kept in registers), then blocks of 1, 2, 4, ...

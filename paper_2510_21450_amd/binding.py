@@ -39,6 +39,7 @@ _lib.pararnn_workspace_bytes.argtypes = [_i] * 6
 _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
+_lib.pararnn_set_staging.argtypes = [_i]
 _lib.pararnn_set_dense_products.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
 _lib.pararnn_solve_plan.restype = _i
@@ -194,6 +195,11 @@ def set_spin_limit(polls: int = 0) -> None:
 def set_fused(enable: bool = True) -> None:
     """pararnn_set_fused: allow (default) or forbid the fused multi-iteration launches."""
     _raise(_lib.pararnn_set_fused(int(enable)), "pararnn_set_fused")
+
+
+def set_staging(enable: bool = True) -> None:
+    """pararnn_set_staging: allow (default) or forbid the kernel variants that stage their inputs through LDS."""
+    _raise(_lib.pararnn_set_staging(int(enable)), "pararnn_set_staging")
 
 
 def solve_plan(tol: float, max_iter: int):

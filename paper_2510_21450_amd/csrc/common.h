@@ -219,6 +219,17 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Workgroup barrier for kernels that keep copies from memory into LDS in flight
+// (buffer loads with an LDS destination): waits for this wave's own LDS
+// instructions only and leaves every vector-memory operation outstanding.  The
+// compiler sees an opaque memory clobber, so it moves no memory access across it;
+// data another wave wrote to LDS with ordinary LDS instructions before its
+// barrier is visible after it.
+__device__ __forceinline__ void lds_barrier_keep_vmem()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Maximum of an unsigned value over the 64 lanes of a wave, returned wave-uniform
 // (in scalar registers).  Four DPP butterfly steps make every row of 16 lanes
 // uniform, then one lane of each row is read.  All lanes must be active.

@@ -27,6 +27,7 @@ struct Settings {
     int fused_head;        // iterations in the first launch of a solve to a tolerance (0 = none)
     int tile[4];           // tile-shape override {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
     unsigned int spin_limit;   // polls of one predecessor before a tile gives up (pararnn_set_spin_limit)
+    int stage_enabled;         // kernels that copy their inputs straight into LDS are allowed (pararnn_set_staging)
 };
 Settings &settings();
 
@@ -385,6 +386,10 @@ int backward_pass(const CellInfo &ci, int dtype, const float *params, const void
     a.part = reinterpret_cast<float *>(ws + lo.off_part);
     a.rec = reinterpret_cast<unsigned long long *>(ws + lo.off_rec);
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
+    // rows that the kernel may copy straight into LDS, 16 bytes per lane: bf16 rows that start on 16-byte
+    // boundaries, and row offsets that stay inside the 32-bit range of a buffer instruction
+    a.stage = settings().stage_enabled && dtype == PARARNN_BF16 && H % 8 == 0 && aligned(u, 16) && aligned(h, 16) &&
+              aligned(dL_dh, 16) && (double)H * 2.0 * (16.0 * ci.G) < 4.0e9;
     return backward_diag<Cell>(ci, dtype, lo, a, st, dL_dparams);
 }
 

@@ -130,16 +130,40 @@ hipError_t Kernels<Cell, UT>::newton_fused(const TileCfg &cfg, const FusedArgs &
     }
 }
 
+// The LDS-staged variant of the backward kernel exists for bf16 storage, one channel per lane, one
+// segment per wave and steps per thread in multiples of 8 (one copy instruction moves 8 rows).
+template <class Cell, int VEC, int LL, int C, typename UT> constexpr bool backward_stage_offered()
+{
+    return !IsRaw<Cell>::value && sizeof(UT) == 2 && VEC == 1 && LL == 1 && C % 8 == 0;
+}
+
+// static LDS of the staged backward kernel: its staging rows on top of the plain kernel's
+template <class Cell, int C, int W> constexpr bool backward_stage_fits_lds()
+{
+    constexpr int S = Cell::S, SS = S * S, PRX = Cell::PR > 0 ? Cell::PR : 1;
+    constexpr int rows = (SS + S) > PRX ? (SS + S) : PRX;
+    return (size_t)(W * rows + S) * kWave * sizeof(float) + (size_t)W * C * (Cell::G + 2 * S) * 128 + 64 <= 65536;
+}
+
 template <class Cell, typename UT>
 hipError_t Kernels<Cell, UT>::backward(const TileCfg &cfg, const BwdArgs &a, hipStream_t st)
 {
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
         if constexpr (shape_offered<Cell, V, C>() && backward_fits_lds<Cell, V, LLv, W>()) {   \
-            static int grid_cap = 0;                                                           \
-            auto kern = backward_kernel<Cell, V, LLv, C, W, UT>;                               \
-            if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \
-            const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                  \
+            static int grid_cap[2] = {0, 0};                                                   \
+            auto kern = backward_kernel<Cell, V, LLv, C, W, UT, false>;                        \
+            int staged = 0;                                                                    \
+            if constexpr (backward_stage_offered<Cell, V, LLv, C, UT>()) {                     \
+                if constexpr (backward_stage_fits_lds<Cell, C, W>()) {                         \
+                    if (a.stage) {                                                             \
+                        kern = backward_kernel<Cell, V, LLv, C, W, UT, true>;                  \
+                        staged = 1;                                                            \
+                    }                                                                          \
+                }                                                                              \
+            }                                                                                  \
+            if (grid_cap[staged] == 0) grid_cap[staged] = persistent_grid(kern, kWave * W, 1 << 30); \
+            const int grid = a.g.n_tiles < grid_cap[staged] ? a.g.n_tiles : grid_cap[staged];  \
             hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
             return hipGetLastError();                                                          \
         } else {                                                                               \

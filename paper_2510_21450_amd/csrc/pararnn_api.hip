@@ -12,7 +12,7 @@ namespace pararnn {
 
 Settings &settings()
 {
-    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit};
+    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1};
     return s;
 }
 
@@ -136,6 +136,12 @@ size_t pararnn_workspace_bytes_fused(int cell, int dtype, int B, int L, int H, i
 int pararnn_set_spin_limit(unsigned int polls)
 {
     settings().spin_limit = polls ? polls : kSpinLimit;
+    return PARARNN_OK;
+}
+
+int pararnn_set_staging(int enable)
+{
+    settings().stage_enabled = enable ? 1 : 0;
     return PARARNN_OK;
 }
 

@@ -91,6 +91,7 @@ struct BwdArgs {
     float *part;         // parameter-gradient partials [n_lt][B][PR][H]
     unsigned long long *rec;
     Ctrl *ctrl;
+    int stage;           // the tensors allow the LDS-staged kernel variant (16-byte aligned rows)
 };
 
 // ------------------------------------------------------------ small matrix ops
@@ -887,6 +888,7 @@ __global__ __launch_bounds__(256) void init_guess_kernel(const FwdArgs a)
     }
 }
 
+
 // ======================================================================
 // Backward (Eq. (6)) as one reverse scan.  With nu_l = J_l^T lam_l the adjoint
 // recurrence lam_{l-1} = J_l^T lam_l + g_{l-1} reads
@@ -895,7 +897,20 @@ __global__ __launch_bounds__(256) void init_guess_kernel(const FwdArgs a)
 // dL/dh0 = nu_1.  Parameter gradients are reduced per tile into `part`
 // and summed by param_reduce_kernel (fixed order: bit-reproducible).
 // ======================================================================
-template <class Cell, int VEC, int LL, int C, int W, typename UT>
+//
+// STAGE = true (bf16 storage, one channel per lane, one segment per wave, C a
+// multiple of 8): the inputs of a tile do not pass through registers on their way
+// from memory.  Every wave copies the rows of its own C steps straight into LDS
+// (buffer loads with the LDS destination: 8 rows of 64 bf16 = 1 KiB per
+// instruction) one tile ahead, so the loads of the next tile are in flight during
+// the whole of the current tile's arithmetic, look-forward and stores, and cost
+// no registers.  A workgroup therefore holds two tickets, the tile it works on
+// and the one it has staged; tickets are still handed out in increasing order
+// and a workgroup works through its own in that order, so the tile with the
+// smallest unfinished ticket never waits for an unfinished one and every wait
+// ends as before.  Tiles at the ragged edges of the tensor and the first tile of
+// a sequence (its h_{l-1} rows start before the sequence) take the register path.
+template <class Cell, int VEC, int LL, int C, int W, typename UT, bool STAGE = false>
 __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 {
     constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR, NC = Cell::NC;
@@ -903,9 +918,16 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
     constexpr bool kRaw = IsRaw<Cell>::value;
     constexpr int PRX = PR > 0 ? PR : 1;
     constexpr int LDSROWS = (SS + S) > PRX ? (SS + S) : PRX;
+    static_assert(!STAGE || (sizeof(UT) == 2 && VEC == 1 && LL == 1 && C % 8 == 0 && !kRaw),
+                  "the staged variant is built for bf16 storage, one channel per lane, C % 8 == 0");
+    // staged rows of one wave, 64 bf16 (32 words) each: u_l (C*G rows), h_{l-1} (C*S), g_l (C*S)
+    constexpr int kRowsU = C * G, kRowsS = C * S;
+    constexpr int kStageWords = STAGE ? (kRowsU + 2 * kRowsS) * 32 : 1;
     __shared__ float s_buf[W][LDSROWS][CW];   // wave aggregates, then gradient partials
     __shared__ float s_carry[S][CW];
     __shared__ unsigned int s_ticket;
+    __shared__ unsigned int s_first[2];
+    __shared__ __attribute__((aligned(16))) unsigned int s_stage[STAGE ? W : 1][kStageWords];
 
     Ctrl *ctrl = a.ctrl;
     const ScanGeom &g = a.g;
@@ -919,12 +941,98 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
     UT *du = static_cast<UT *>(a.du);
     bool internal_error = false;
 
-    for (;;) {
-        if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+    // parameters of the channels this lane owns in channel group cg_
+    auto load_params = [&](int cg_, float (&dst)[VEC][PRX]) {
+#pragma unroll
+        for (int r = 0; r < PRX; ++r) {
+            float tmp[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) tmp[v] = 0.0f;
+            if constexpr (STAGE) {
+                // no branch, so that nothing waits for the value before it is used: channels past the
+                // end read the last channel's parameters and are masked where results are stored
+                const int chn_ = min(cg_ * CW + col, g.H - 1);
+                if (PR > 0) tmp[0] = a.params[(size_t)r * g.H + chn_];
+            } else {
+                if (PR > 0 && cg_ * CW + col < g.H) load_vec<VEC>(a.params + (size_t)r * g.H + cg_ * CW + col, tmp);
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) dst[v][r] = tmp[v];
+        }
+    };
+    float pn[VEC][PRX];      // staged variant: parameters of the next tile
+#pragma unroll
+    for (int v = 0; v < VEC; ++v)
+#pragma unroll
+        for (int r = 0; r < PRX; ++r) pn[v][r] = 0.0f;
+
+    // ---- staged variant: which tiles go through LDS, and the copy of a tile's rows
+    auto stageable = [&](unsigned int t_) -> bool {
+        if constexpr (!STAGE) {
+            return false;
+        } else {
+            if (!a.stage || t_ >= (unsigned int)g.n_tiles) return false;
+            const int grp_ = (int)(t_ % (unsigned int)g.n_groups);
+            const int lt_ = g.n_lt - 1 - (int)(t_ / (unsigned int)g.n_groups);
+            const int cg_ = grp_ % g.n_cg;
+            return lt_ > 0 && (lt_ + 1) * T <= g.L && (cg_ + 1) * CW <= g.H;
+        }
+    };
+    auto stage_tile = [&](unsigned int t_) {
+        if constexpr (STAGE) {
+            typedef __attribute__((address_space(3))) void *lds_ptr;
+            const int grp_ = (int)(t_ % (unsigned int)g.n_groups);
+            const int lt_ = g.n_lt - 1 - (int)(t_ / (unsigned int)g.n_groups);
+            const int b_ = grp_ / g.n_cg, cg_ = grp_ - b_ * g.n_cg;
+            const unsigned int Hn_ = (unsigned int)g.H;
+            const size_t row_ = (size_t)b_ * g.L + (size_t)(lt_ * T + w * C);      // first step of this wave
+            // lane -> one of 8 rows, 16 bytes of its 128
+            const unsigned int voff = (unsigned int)(lane >> 3) * Hn_ * 2u + (unsigned int)(lane & 7) * 16u;
+            const buf_rsrc su = make_rsrc(u + row_ * G * Hn_ + (size_t)cg_ * CW);
+            const buf_rsrc sh = make_rsrc(hres + (row_ - 1) * S * Hn_ + (size_t)cg_ * CW);   // h_{l-1}: lt_ > 0
+            const buf_rsrc sg = make_rsrc(gl + row_ * S * Hn_ + (size_t)cg_ * CW);
+#pragma unroll
+            for (int j = 0; j < kRowsU / 8; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(su, (lds_ptr)&s_stage[w][j * 256], 16, voff,
+                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+#pragma unroll
+            for (int j = 0; j < kRowsS / 8; ++j) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(sh, (lds_ptr)&s_stage[w][(kRowsU / 8 + j) * 256], 16, voff,
+                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(sg, (lds_ptr)&s_stage[w][((kRowsU + kRowsS) / 8 + j) * 256], 16,
+                                                         voff, (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+            }
+        }
+    };
+    unsigned int t = 0, t_next = 0;
+    bool cur_staged = false;
+    if constexpr (STAGE) {
+        if (threadIdx.x == 0) {
+            s_first[0] = atomicAdd(&ctrl->ticket, 1u);
+            s_first[1] = atomicAdd(&ctrl->ticket, 1u);
+        }
         __syncthreads();
-        // the ticket comes through LDS; make it scalar so that the whole tile geometry is computed on the SALU
-        const unsigned int t = __builtin_amdgcn_readfirstlane(s_ticket);
-        if (t >= (unsigned int)g.n_tiles) break;
+        t = __builtin_amdgcn_readfirstlane(s_first[0]);
+        t_next = __builtin_amdgcn_readfirstlane(s_first[1]);
+        cur_staged = stageable(t);
+        if (cur_staged) stage_tile(t);
+        if (t < (unsigned int)g.n_tiles) load_params((int)(t % (unsigned int)g.n_groups) % g.n_cg, pn);
+    }
+
+    for (;;) {
+        if constexpr (STAGE) {
+            // the workgroup's third ticket, read after the first barrier below; the barrier here keeps
+            // the previous tile's reads of s_buf (gradient partials) ahead of this tile's writes
+            lds_barrier();
+            if (t >= (unsigned int)g.n_tiles) break;
+            if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+        } else {
+            if (threadIdx.x == 0) s_ticket = atomicAdd(&ctrl->ticket, 1u);
+            __syncthreads();
+            // the ticket comes through LDS; make it scalar so that the whole tile geometry is computed on the SALU
+            t = __builtin_amdgcn_readfirstlane(s_ticket);
+            if (t >= (unsigned int)g.n_tiles) break;
+        }
         const int grp = (int)(t % (unsigned int)g.n_groups);
         const int lt = g.n_lt - 1 - (int)(t / (unsigned int)g.n_groups);   // from the end of the sequence
         const int b = grp / g.n_cg, cg = grp - b * g.n_cg;
@@ -949,14 +1057,14 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 
         float p[VEC][PRX];
         if constexpr (PR > 0) {
+            if constexpr (STAGE) {
+                // loaded one tile ahead, like the staged rows
 #pragma unroll
-            for (int r = 0; r < PR; ++r) {
-                float tmp[VEC];
+                for (int v = 0; v < VEC; ++v)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) tmp[v] = 0.0f;
-                if (ch_ok) load_vec<VEC>(a.params + (size_t)r * g.H + ch, tmp);
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) p[v][r] = tmp[v];
+                    for (int r = 0; r < PR; ++r) p[v][r] = pn[v][r];
+            } else {
+                load_params(cg, p);
             }
         }
 
@@ -1008,9 +1116,6 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 }
             }
         };
-        if (full_tile) load_inputs(std::false_type{});
-        else load_inputs(std::true_type{});
-
         // ---- thread level, right to left.  For step i keep the map from the
         // value entering the chunk on the right (nu_in) to lam_i:
         //     lam_i = PX_i nu_in + qx_i,   PX_i = prod_{j>i} J_j^T,  qx_i = g_i + q_{i+1}
@@ -1021,51 +1126,91 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
             for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
         }
+        // from_lds: the step's inputs are read from this wave's staged rows as they are needed
+        // (no registers hold them), else from the registers load_inputs filled
+        auto thread_level = [&](auto from_lds) {
+            constexpr bool kLds = decltype(from_lds)::value;
 #pragma unroll
-        for (int i = C - 1; i >= 0; --i) {
-            float uu1[G][VEC], hp1[S][VEC], gg1[S][VEC], jr1[kRaw ? SS : 1][VEC];
-            if constexpr (!kRaw) {
+            for (int i = C - 1; i >= 0; --i) {
+                float uu1[G][VEC], hp1[S][VEC], gg1[S][VEC], jr1[kRaw ? SS : 1][VEC];
+                if constexpr (kLds) {
+                    const unsigned short *sp = reinterpret_cast<const unsigned short *>(&s_stage[w][0]);
 #pragma unroll
-                for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu1[q]);
-            } else {
+                    for (int q = 0; q < G; ++q) uu1[q][0] = bf16_to_f32(sp[(i * G + q) * 64 + lane]);
 #pragma unroll
-                for (int e = 0; e < SS; ++e) raw_to_float<float, VEC>(jrr[i][e], jr1[e]);
-            }
+                    for (int s = 0; s < S; ++s) {
+                        hp1[s][0] = bf16_to_f32(sp[(kRowsU + i * S + s) * 64 + lane]);
+                        gg1[s][0] = bf16_to_f32(sp[(kRowsU + kRowsS + i * S + s) * 64 + lane]);
+                    }
+                } else {
+                    if constexpr (!kRaw) {
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-                raw_to_float<UT, VEC>(hpr[i][s], hp1[s]);
-                raw_to_float<UT, VEC>(ggr[i][s], gg1[s]);
-            }
+                        for (int q = 0; q < G; ++q) raw_to_float<UT, VEC>(uur[i][q], uu1[q]);
+                    } else {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
+                        for (int e = 0; e < SS; ++e) raw_to_float<float, VEC>(jrr[i][e], jr1[e]);
+                    }
 #pragma unroll
-                for (int e = 0; e < SS; ++e) PX[i][v][e] = accA[v][e];
-#pragma unroll
-                for (int s = 0; s < S; ++s) qx[i][v][s] = accB[v][s] + gg1[s][v];
-            }
-            if (l0 + i < g.L) {
+                    for (int s = 0; s < S; ++s) {
+                        raw_to_float<UT, VEC>(hpr[i][s], hp1[s]);
+                        raw_to_float<UT, VEC>(ggr[i][s], gg1[s]);
+                    }
+                }
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    float J[SS], zero[S];
-                    if constexpr (kRaw) {
 #pragma unroll
-                        for (int e = 0; e < SS; ++e) J[e] = jr1[e][v];
-                    } else {
-                        float h1[S], ug[G];
+                    for (int e = 0; e < SS; ++e) PX[i][v][e] = accA[v][e];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) h1[s] = hp1[s][v];
+                    for (int s = 0; s < S; ++s) qx[i][v][s] = accB[v][s] + gg1[s][v];
+                }
+                if (kLds || l0 + i < g.L) {
 #pragma unroll
-                        for (int q = 0; q < G; ++q) ug[q] = uu1[q][v];
-                        Cell::bwd_prep(p[v], h1, ug, J, kk[i][v]);
+                    for (int v = 0; v < VEC; ++v) {
+                        float J[SS], zero[S];
+                        if constexpr (kRaw) {
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) J[e] = jr1[e][v];
+                        } else {
+                            float h1[S], ug[G];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) h1[s] = hp1[s][v];
+#pragma unroll
+                            for (int q = 0; q < G; ++q) ug[q] = uu1[q][v];
+                            Cell::bwd_prep(p[v], h1, ug, J, kk[i][v]);
+                        }
+                        transpose_inplace<S>(J);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) zero[s] = 0.0f;
+                        // nu_i = J^T (g_i + nu_{i+1}):  accB = J^T qx_i,  accA = J^T accA
+                        affine<S>(J, qx[i][v], zero, accB[v]);
+                        mat_mul<S>(J, accA[v], accA[v]);
                     }
-                    transpose_inplace<S>(J);
-#pragma unroll
-                    for (int s = 0; s < S; ++s) zero[s] = 0.0f;
-                    // nu_i = J^T (g_i + nu_{i+1}):  accB = J^T qx_i,  accA = J^T accA
-                    affine<S>(J, qx[i][v], zero, accB[v]);
-                    mat_mul<S>(J, accA[v], accA[v]);
                 }
             }
+        };
+        bool next_staged = false;
+        if constexpr (STAGE) {
+            if (cur_staged) {
+                // this wave's rows were copied by this wave: its own copies have landed once its
+                // outstanding-memory count is zero
+                __builtin_amdgcn_s_waitcnt(0);
+                thread_level(std::true_type{});
+                __builtin_amdgcn_s_waitcnt(0);       // every row has been read before it is overwritten
+            } else {
+                if (full_tile) load_inputs(std::false_type{});
+                else load_inputs(std::true_type{});
+                thread_level(std::false_type{});
+                __builtin_amdgcn_s_waitcnt(0);
+            }
+            // the next tile: its rows on their way into LDS, its parameters into registers, while this
+            // tile goes through the scan levels, the look-forward, the gradient formulas and its stores
+            next_staged = stageable(t_next);
+            if (next_staged) stage_tile(t_next);
+            if (t_next < (unsigned int)g.n_tiles) load_params((int)(t_next % (unsigned int)g.n_groups) % g.n_cg, pn);
+        } else {
+            if (full_tile) load_inputs(std::false_type{});
+            else load_inputs(std::true_type{});
+            thread_level(std::false_type{});
         }
         // chunk aggregate before the wave-level scan overwrites it (nu at the chunk's first step)
         float cA[VEC][SS], cB[VEC][S];
@@ -1116,7 +1261,10 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 for (int s = 0; s < S; ++s) s_buf[w][SS + s][col + v] = accB[v][s];
             }
         }
-        __syncthreads();
+        if constexpr (STAGE) lds_barrier_keep_vmem();
+        else __syncthreads();
+        unsigned int t_after = 0;
+        if constexpr (STAGE) t_after = __builtin_amdgcn_readfirstlane(s_ticket);
         // map of the waves after this one; wave W-1 also forms the tile
         // aggregate and runs the look-forward
         float exA[VEC][SS], exB[VEC][S];
@@ -1188,7 +1336,8 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                     for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
             }
         }
-        __syncthreads();
+        if constexpr (STAGE) lds_barrier_keep_vmem();
+        else __syncthreads();
 
         // ---- back-substitution: lam for every step, then du and the
         // parameter-gradient contributions
@@ -1262,7 +1411,8 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
                     for (int r = 0; r < PR; ++r) s_buf[w][r][col + v] = acc[v][r];
             }
-            __syncthreads();
+            if constexpr (STAGE) lds_barrier_keep_vmem();
+            else __syncthreads();
             for (int idx = threadIdx.x; idx < PR * CW; idx += kWave * W) {
                 const int r = idx / CW, c = idx - r * CW;
                 float s = 0.0f;
@@ -1271,6 +1421,11 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
                 const int chn = cg * CW + c;
                 if (chn < g.H) a.part[(((size_t)lt * g.B + b) * PR + r) * g.H + chn] = s;
             }
+        }
+        if constexpr (STAGE) {
+            t = t_next;
+            t_next = t_after;
+            cur_staged = next_staged;
         }
     }
     if (internal_error && lane == 0) atomicExch(&ctrl->status, kStInternal);

@@ -519,3 +519,34 @@ def test_bf16_stores_round_to_nearest_even_on_ties(P, oracle_mod):
         assert not np.array_equal(want_du.double().numpy(), rdu)
         assert torch.equal(du.cpu().view(torch.int16), want_du.view(torch.int16)), H
         assert torch.equal(dh0.cpu().view(torch.int16), want_dh0.view(torch.int16)), H
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag", "paralstm_diag"])
+def test_backward_inputs_staged_through_lds(P, oracle_mod, as_stored, cell):
+    """bf16 storage: the backward kernel copies the rows of a tile straight from memory into LDS one
+    tile ahead (interior tiles; edge tiles and the first tile of a sequence load through registers).
+    Same arithmetic either way: bit-identical outputs with the staging switched off, and both within
+    the bf16 bound of the oracle.  Shapes with ragged tiles in L and H, and L below one tile."""
+    for (B, L, H), tile in (((2, 1100, 200), None), ((3, 700, 64), None), ((2, 50, 72), None), ((1, 2100, 136), (1, 1, 8, 16)),
+                            ((2, 900, 128), (1, 1, 16, 4))):
+        print(f"staged backward {cell} B={B} L={L} H={H} tile={tile}", flush=True)
+        params, u, h0, g = problem(cell, B, L, H, seed=900 + L, dtype=torch.bfloat16)
+        pn, un, h0n, gn = to_np(params), to_np(u), to_np(h0), to_np(g)
+        hs = as_stored(oracle_mod.seq_unroll(cell, pn, un, h0n), u)
+        outs = []
+        try:
+            if tile:
+                P.set_tile(*tile)
+            for staging in (True, False):
+                P.set_staging(staging)
+                outs.append(P.backward(cell, params, u, h0, hs, g))
+            torch.cuda.synchronize()
+        finally:
+            P.set_staging(True)
+            P.set_tile(0)
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+        rdu, rdp, rdh0 = oracle_mod.backward(cell, pn, un, h0n, to_np(hs), gn)
+        du, dp, dh0 = outs[0]
+        assert relerr(to_np(du), rdu) <= TOL_BF16 and relerr(to_np(dp), rdp) <= TOL_BF16
+        assert relerr(to_np(dh0), rdh0) <= TOL_BF16
