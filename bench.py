@@ -47,7 +47,7 @@ ALGO_BYTES = {
 # thread-level scan step and the back-substitution; +, -, *, / and exp count one each)
 ALGO_FLOPS = {"gru_diag": 49, "lstm_diag": 93, "paralstm_diag": 92}
 COUNTERS_JSON = os.path.join(ROOT, "profiles", "counters.json")
-KERNEL_SOURCES = os.path.join(ROOT, "paper_2510_21450_amd", "csrc")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2510_21450_amd", "csrc"), os.path.join(ROOT, "include", "pararnn")]
 
 
 def note(msg):
@@ -58,10 +58,11 @@ def note(msg):
 def source_hash():
     """Hash of the kernel sources the library is built from: the stamp that ties a counter file to a build."""
     h = hashlib.sha256()
-    for name in sorted(os.listdir(KERNEL_SOURCES)):
-        if name.endswith((".h", ".hip")):
-            h.update(name.encode())
-            h.update(open(os.path.join(KERNEL_SOURCES, name), "rb").read())
+    for folder in KERNEL_SOURCES:
+        for name in sorted(os.listdir(folder)):
+            if name.endswith((".h", ".hip")):
+                h.update(name.encode())
+                h.update(open(os.path.join(folder, name), "rb").read())
     return h.hexdigest()[:16]
 
 

@@ -11,11 +11,20 @@
  * reverse scan with transposed Jacobians (Eq. (6)).
  *
  * All data pointers are DEVICE pointers unless stated otherwise.  The caller
- * owns every buffer; the library allocates nothing, keeps no state between
- * calls and only enqueues work on the given HIP stream (hipStream_t passed as
- * void*, NULL = the default stream).  Results are valid once the stream has
- * been synchronised.  Calls that share a workspace must be ordered on one
- * stream.
+ * owns every buffer; the library allocates nothing and only enqueues work on the
+ * given HIP stream (hipStream_t passed as void*, NULL = the default stream).
+ * Results are valid once the stream has been synchronised.  Calls that share a
+ * workspace must be ordered on one stream.
+ *
+ * State.  A call keeps nothing on the device beyond its workspace.  On the host
+ * the library has a handful of process-wide tuning and test switches (the
+ * pararnn_set_* functions below and the environment variable PARARNN_TILE, read
+ * once): they are plain variables, NOT thread-safe, meant to be set before the
+ * calls they affect and not while another thread is inside the library.  They
+ * change the launch plan and with it the workspace size: query
+ * pararnn_workspace_bytes again after any of them.  Code that wants per-call
+ * choices, or calls from several threads, uses pararnn_forward_ex, whose options
+ * travel with the call.
  *
  * Layouts (H is always the contiguous axis):
  *   u          [B][L][G][H]  pre-activations u_l = B x_l + b of the G gates
@@ -177,6 +186,8 @@ int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity);
  *                   no host synchronisation per iteration) or k = max_iter.
  *
  *   params, u, h0   inputs; h0 may be NULL (= zeros, the paper's h_0 = 0)
+ *   B, L, H         batch, timesteps, channels; H <= 4 194 304 (INVALID_ARG beyond: row
+ *                   offsets inside the kernels are 32-bit)
  *   tol             absolute tolerance on max|delta h|; tol < 0 runs exactly
  *                   max_iter iterations (the paper's fixed N_its) with status OK
  *   max_iter        >= 0; 0 returns the initial guess
@@ -196,6 +207,36 @@ int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity);
 int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0,
                     int B, int L, int H, float tol, int max_iter, void *h, int *iters,
                     float *delta_trace, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * pararnn_forward with per-call choices instead of the process-wide switches
+ * (two threads with different choices do not interfere; nothing is written to
+ * the library's settings).
+ *   first_block  Newton iterations the first launch of a solve to a tolerance
+ *                runs on registers (u read once): -1 the library's setting
+ *                (default 5), 0 one launch per iteration, 1..8.  The paper's
+ *                regime of three iterations (Sec. 2.1, App. A) is first_block = 3:
+ *                the returned h is then the iterate of the third iteration when
+ *                the tolerance is met there, and a solve that needs more goes on
+ *                in further launches.
+ *   fused        -1 the library's setting, 0 never run more than one iteration
+ *                per launch (as pararnn_set_fused(0)), 1 allow it.
+ * options = NULL means all defaults: the call is then pararnn_forward.  Fields
+ * out of range give PARARNN_INVALID_ARG.  The workspace must have
+ * pararnn_workspace_bytes_ex bytes for the same options (0 on invalid
+ * arguments); pararnn_solve_plan_ex is pararnn_solve_plan for given options.
+ */
+typedef struct pararnn_solve_options {
+    int first_block;
+    int fused;
+} pararnn_solve_options_t;
+size_t pararnn_workspace_bytes_ex(int cell, int dtype, int B, int L, int H, const pararnn_solve_options_t *options);
+int pararnn_solve_plan_ex(float tol, int max_iter, const pararnn_solve_options_t *options, int *block_sizes,
+                          int capacity);
+int pararnn_forward_ex(int cell, int dtype, const float *params, const void *u, const void *h0,
+                       int B, int L, int H, float tol, int max_iter, void *h, int *iters,
+                       float *delta_trace, void *workspace, size_t workspace_bytes, void *hip_stream,
+                       const pararnn_solve_options_t *options);
 
 /*
  * pararnn_forward for callers that cannot allocate device memory or hand over
@@ -319,9 +360,12 @@ int pararnn_input_projection_backward(int dtype, const void *x, const float *Wx,
  * on the matrix cores.  W [H][H] row-major, d [B][L][H], A out
  * [B][ceil(L/chunk)][H][H] row-major; only the chunks c = 1 .. n_c-2 that the
  * scan uses are written.  fp32, H = 64 (else UNSUPPORTED).  workspace: 256
- * bytes of device memory, 256-byte aligned.
+ * bytes of device memory, 256-byte aligned.  pararnn_dense_chunk() is the
+ * number of timesteps per chunk.
  */
 int pararnn_dense_chunk(void);
+int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Inexact-Newton switch of the dense path (host, process-wide; default 0).
@@ -359,8 +403,6 @@ int pararnn_set_dense_products(int mode);
  * transposed Jacobian.  Returns PARARNN_INVALID_ARG for any other mode.
  */
 int pararnn_set_dense_jacobian(int mode);
-int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A,
-                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -2,7 +2,7 @@
 // argument checks, workspace layout, tile-shape choice and the enqueue
 // sequence of a forward solve (Sec. 2, Alg. 1a) and of a backward pass (Eq. (6)).
 // Used by the C ABI of the built-in cells and by libraries that add a cell of
-// their own (user_cell.h).  No kernel code here.
+// their own (pararnn_cell.h).  No kernel code here.
 #pragma once
 #include <stdint.h>
 #include <stdio.h>
@@ -11,7 +11,7 @@
 
 #include <initializer_list>
 
-#include "../../include/pararnn.h"
+#include "../pararnn.h"
 #include "launch.h"
 
 namespace pararnn {
@@ -30,6 +30,19 @@ struct Settings {
     int stage_enabled;         // kernels that copy their inputs straight into LDS are allowed (pararnn_set_staging)
 };
 Settings &settings();
+
+// Choices of one forward solve.  The C ABI's plain entry points take them from the process-wide
+// settings; pararnn_forward_ex takes them from its options argument, so that two threads with
+// different wishes do not meet in the settings.
+struct SolveOpts {
+    int fused_enabled;     // launches that run several Newton iterations are allowed
+    int fused_head;        // iterations in the first launch of a solve to a tolerance (0 = none)
+};
+inline SolveOpts default_opts()
+{
+    const Settings &s = settings();
+    return {s.fused_enabled, s.fused_head};
+}
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -127,9 +140,11 @@ inline Layout make_layout(const CellInfo &ci, int dtype, int B, int L, int H, bo
 inline bool dims_ok(int B, int L, int H)
 {
     if (B < 1 || L < 1 || H < 1) return false;
-    // keep every element count inside size_t/int ranges the kernels assume
+    // keep every element count inside size_t/int ranges the kernels assume.  The bound on H keeps the
+    // 32-bit byte offsets of the buffer instructions in range: a wave addresses up to 128 rows of H
+    // elements of 4 bytes from its base (8 segments x 4 steps x 4 gates, or 2 x 16 x 4)
     const double n = (double)B * (double)L * (double)H;
-    return n < 3.0e10 && (double)B * H < 2.0e9 && L < (1 << 30);
+    return n < 3.0e10 && (double)B * H < 2.0e9 && L < (1 << 30) && H <= (1 << 22);
 }
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -148,9 +163,8 @@ inline int align_elems(size_t esz, std::initializer_list<const void *> ptrs)
 
 // Carry-record slots a solve would like to have: the whole solve when the count is fixed
 // (tol < 0) and short enough, else its first fused_head iterations; 0 = no fused launches.
-inline int fused_slots_wanted(float tol, int max_iter)
+inline int fused_slots_wanted(float tol, int max_iter, const SolveOpts &s = default_opts())
 {
-    const Settings &s = settings();
     if (!s.fused_enabled || max_iter < 1) return 0;
     if (tol < 0.0f) return max_iter <= kMaxFused ? max_iter : 0;
     return max_iter < s.fused_head ? max_iter : s.fused_head;
@@ -173,9 +187,9 @@ inline int next_block_size(int done, int launches, int max_iter, int n_fused)
 
 // Workspace size of a forward solve to a tolerance (or of a backward pass); does not depend on
 // pointer alignment: the larger footprint is taken when the layouts differ.
-inline size_t diag_workspace_bytes(const CellInfo &ci, int dtype, int B, int L, int H, bool backward)
+inline size_t diag_workspace_bytes(const CellInfo &ci, int dtype, int B, int L, int H, bool backward,
+                                   const SolveOpts &s = default_opts())
 {
-    const Settings &s = settings();
     size_t need = 0;
     for (int al = 1; al <= 4; al *= 2) {
         const Layout lo = make_layout(ci, dtype, B, L, H, backward, al);
@@ -300,7 +314,7 @@ inline int check_backward_args(int dtype, const float *params, const void *u, co
 template <class Cell>
 int forward_solve(const CellInfo &ci, int dtype, const float *params, const void *u, const void *h0, int B, int L,
                   int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
-                  size_t workspace_bytes, hipStream_t st)
+                  size_t workspace_bytes, hipStream_t st, const SolveOpts &opts = default_opts())
 {
     const size_t esz = dtype == PARARNN_BF16 ? 2 : 4;
     const int status0 = tol < 0.0f ? PARARNN_OK : PARARNN_NOT_CONVERGED;
@@ -311,7 +325,7 @@ int forward_solve(const CellInfo &ci, int dtype, const float *params, const void
     // workspace holds those.
     Layout lo = make_layout(ci, dtype, B, L, H, false, al);
     int n_fused = 0;
-    const int want = fused_slots_wanted(tol, max_iter);
+    const int want = fused_slots_wanted(tol, max_iter, opts);
     if (want > 0) {
         const Layout lf = make_layout(ci, dtype, B, L, H, false, al, true, want);
         if (workspace_bytes >= (tol < 0.0f ? lf.off_bnd : lf.total)) {

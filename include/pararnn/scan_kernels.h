@@ -27,7 +27,7 @@
 #pragma once
 #include <type_traits>
 
-#include "cells.h"
+#include "common.h"
 
 namespace pararnn {
 

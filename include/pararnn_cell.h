@@ -55,8 +55,8 @@
 #ifndef PARARNN_CELL_H
 #define PARARNN_CELL_H
 
-#include "../paper_2510_21450_amd/csrc/driver.h"
-#include "../paper_2510_21450_amd/csrc/launch_impl.h"
+#include "pararnn/driver.h"
+#include "pararnn/launch_impl.h"
 
 namespace pararnn {
 

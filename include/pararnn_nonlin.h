@@ -23,7 +23,7 @@
 #ifndef PARARNN_NONLIN_H
 #define PARARNN_NONLIN_H
 
-#include "../paper_2510_21450_amd/csrc/common.h"
+#include "pararnn/common.h"
 
 namespace pararnn {
 

@@ -46,6 +46,17 @@ _lib.pararnn_solve_plan.restype = _i
 _lib.pararnn_solve_plan.argtypes = [ctypes.c_float, _i, ctypes.POINTER(ctypes.c_int), _i]
 _lib.pararnn_forward.restype = _i
 _lib.pararnn_forward.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+class _SolveOptions(ctypes.Structure):
+    _fields_ = [("first_block", ctypes.c_int), ("fused", ctypes.c_int)]
+
+
+_lib.pararnn_forward_ex.restype = _i
+_lib.pararnn_forward_ex.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp, _sz, _vp,
+                                    ctypes.POINTER(_SolveOptions)]
+_lib.pararnn_workspace_bytes_ex.restype = _sz
+_lib.pararnn_workspace_bytes_ex.argtypes = [_i, _i, _i, _i, _i, ctypes.POINTER(_SolveOptions)]
+_lib.pararnn_solve_plan_ex.restype = _i
+_lib.pararnn_solve_plan_ex.argtypes = [ctypes.c_float, _i, ctypes.POINTER(_SolveOptions), ctypes.POINTER(ctypes.c_int), _i]
 _lib.pararnn_forward_noalloc.restype = _i
 _lib.pararnn_forward_noalloc.argtypes = [_i, _i, _vp, _vp, _vp, _i, _i, _i, _f, _i, _vp, _vp, _vp, _vp]
 _lib.pararnn_backward.restype = _i
@@ -271,6 +282,42 @@ def forward(cell, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, tra
                    _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream))
     _raise(code, f"{api.what}_forward")
     return h, iters, tr
+
+
+def forward_ex(cell, params, u, h0=None, tol: float = 1e-6, max_iter: int = 64, first_block: int = -1, fused: int = -1,
+               trace: bool = False, workspace=None, stream=None, out=None):
+    """pararnn_forward_ex (built-in cells): `forward` with the size of the first fused block and the
+    fused switch as arguments of the call (-1 = the library's setting).  Same return values."""
+    G, S = cell_dims(cell)
+    B, L, Gu, H = u.shape
+    dt = u.dtype
+    _check(u, "u", dt, (B, L, G, H))
+    _check(params, "params", torch.float32)
+    if h0 is not None:
+        _check(h0, "h0", dt, (B, S, H))
+    h = torch.empty((B, L, S, H), dtype=dt, device=u.device) if out is None else out
+    _check(h, "h", dt, (B, L, S, H))
+    iters = torch.empty(2, dtype=torch.int32, device=u.device)
+    tr = torch.zeros(max(max_iter, 1), dtype=torch.float32, device=u.device) if trace else None
+    opt = _SolveOptions(int(first_block), int(fused))
+    need = max(_lib.pararnn_workspace_bytes_ex(CELLS[cell], DTYPES[dt], B, L, H, ctypes.byref(opt)),
+               workspace_bytes_fused(cell, dt, B, L, H, max_iter) if tol < 0 else 0)
+    ws = _workspace(need, u.device, workspace)
+    code = _lib.pararnn_forward_ex(CELLS[cell], DTYPES[dt], _ptr(params), _ptr(u), _ptr(h0), B, L, H, tol, max_iter,
+                                   _ptr(h), _ptr(iters), _ptr(tr), _ptr(ws), ws.numel(), _stream(stream),
+                                   ctypes.byref(opt))
+    _raise(code, "pararnn_forward_ex")
+    return h, iters, tr
+
+
+def solve_plan_ex(tol: float, max_iter: int, first_block: int = -1, fused: int = -1):
+    """pararnn_solve_plan_ex: Newton iterations per launch of a solve with the given options."""
+    buf = (ctypes.c_int * max(1, max_iter))()
+    opt = _SolveOptions(int(first_block), int(fused))
+    n = _lib.pararnn_solve_plan_ex(float(tol), int(max_iter), ctypes.byref(opt), buf, max(1, max_iter))
+    if n < 0:
+        raise ValueError("pararnn_solve_plan_ex: invalid arguments")
+    return [buf[i] for i in range(n)]
 
 
 def forward_noalloc(cell, params, u, h0, tol, max_iter, out, iters, delta_trace=None, stream=None):

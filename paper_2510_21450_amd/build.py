@@ -22,7 +22,8 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpararnn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+INCLUDE = os.path.join(os.path.dirname(PKG), "include")      # public headers: pararnn.h, pararnn_cell.h, pararnn/*.h
+FLAGS = ["--offload-arch=gfx950", f"-I{INCLUDE}", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 VALU forms are kept off for the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-but-set-variable", "-Wno-unknown-warning-option",

@@ -13,7 +13,7 @@
 // bwd_emit maps the incoming adjoint lam (dL/d state_l) to dL/du_l and adds this
 // step's contribution to the PR parameter-gradient accumulators.
 #pragma once
-#include "common.h"
+#include "pararnn/common.h"
 
 namespace pararnn {
 

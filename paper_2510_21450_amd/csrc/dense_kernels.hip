@@ -26,11 +26,11 @@
 // of the next product; the k-pair an instruction consumes is then (row(v,0),
 // row(v,1)), and W is held in registers permuted to supply exactly those
 // columns as the A operand.  No layout change is ever needed between products.
-#include "../../include/pararnn.h"
-#include "common.h"
+#include "pararnn.h"
+#include "pararnn/common.h"
 #include "dense.h"
-#include "driver.h"
-#include "launch.h"
+#include "pararnn/driver.h"
+#include "pararnn/launch.h"
 
 #include <string.h>
 

@@ -1,4 +1,5 @@
 // Kernel instantiations for one cell / storage type (compiled separately to
 // keep build times short).
-#include "launch_impl.h"
+#include "cells.h"
+#include "pararnn/launch_impl.h"
 namespace pararnn { template struct Kernels<RawScan<1>, float>; }

@@ -3,7 +3,8 @@
 #include <mutex>
 
 #include "dense.h"
-#include "driver.h"
+#include "cells.h"
+#include "pararnn/driver.h"
 #include "proj.h"
 
 using namespace pararnn;
@@ -171,9 +172,24 @@ int pararnn_set_fused_head(int n_iters)
     return PARARNN_OK;
 }
 
-int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
-                    int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
-                    size_t workspace_bytes, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// options of pararnn_forward_ex -> the driver's choices; false when a field is out of range
+bool solve_opts(const pararnn_solve_options_t *o, SolveOpts *out)
+{
+    *out = default_opts();
+    if (!o) return true;
+    if (o->first_block < -1 || o->first_block > kMaxFused || o->fused < -1 || o->fused > 1) return false;
+    if (o->first_block >= 0) out->fused_head = o->first_block;
+    if (o->fused >= 0) out->fused_enabled = o->fused;
+    return true;
+}
+
+int forward_with(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L, int H,
+                 float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
+                 size_t workspace_bytes, void *hip_stream, const SolveOpts &opts)
 {
     CellInfo ci;
     if (!cell_info(cell, &ci)) return PARARNN_INVALID_ARG;
@@ -182,7 +198,7 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 #define PARARNN_FWD(Cell)                                                                                   \
     forward_solve<Cell>(ci, dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace, \
-                        workspace_bytes, st)
+                        workspace_bytes, st, opts)
     switch (cell) {
     case PARARNN_TANH_DENSE:
         return dense_forward(dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace,
@@ -194,6 +210,52 @@ int pararnn_forward(int cell, int dtype, const float *params, const void *u, con
     }
 #undef PARARNN_FWD
     return PARARNN_INVALID_ARG;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pararnn_forward(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
+                    int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
+                    size_t workspace_bytes, void *hip_stream)
+{
+    return forward_with(cell, dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace,
+                        workspace_bytes, hip_stream, default_opts());
+}
+
+int pararnn_forward_ex(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,
+                       int H, float tol, int max_iter, void *h, int *iters, float *delta_trace, void *workspace,
+                       size_t workspace_bytes, void *hip_stream, const pararnn_solve_options_t *options)
+{
+    SolveOpts opts;
+    if (!solve_opts(options, &opts)) return PARARNN_INVALID_ARG;
+    return forward_with(cell, dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace,
+                        workspace_bytes, hip_stream, opts);
+}
+
+size_t pararnn_workspace_bytes_ex(int cell, int dtype, int B, int L, int H, const pararnn_solve_options_t *options)
+{
+    CellInfo ci;
+    SolveOpts opts;
+    if (!cell_info(cell, &ci) || (dtype != PARARNN_F32 && dtype != PARARNN_BF16) || !dims_ok(B, L, H)) return 0;
+    if (!solve_opts(options, &opts)) return 0;
+    if (cell == PARARNN_TANH_DENSE) return dense_workspace_bytes(dtype, B, L, H, 0);
+    return diag_workspace_bytes(ci, dtype, B, L, H, false, opts);
+}
+
+int pararnn_solve_plan_ex(float tol, int max_iter, const pararnn_solve_options_t *options, int *block_sizes, int capacity)
+{
+    SolveOpts opts;
+    if (max_iter < 0 || tol != tol || (capacity > 0 && !block_sizes) || !solve_opts(options, &opts)) return -1;
+    const int n_fused = fused_slots_wanted(tol, max_iter, opts);
+    int done = 0, launches = 0;
+    for (; done < max_iter; ++launches) {
+        const int K = next_block_size(done, launches, max_iter, n_fused);
+        if (launches < capacity) block_sizes[launches] = K;
+        done += K;
+    }
+    return launches;
 }
 
 int pararnn_forward_noalloc(int cell, int dtype, const float *params, const void *u, const void *h0, int B, int L,

@@ -21,9 +21,9 @@
 // 32 x 32 accumulators), 64 k per step, both operand tiles in LDS in k-chunk-major
 // order (fragment reads are contiguous), double buffered, the global loads of the
 // next two steps in flight while a step is multiplied.
-#include "../../include/pararnn.h"
-#include "common.h"
-#include "launch.h"
+#include "pararnn.h"
+#include "pararnn/common.h"
+#include "pararnn/launch.h"
 #include "proj.h"
 
 #include <stdint.h>

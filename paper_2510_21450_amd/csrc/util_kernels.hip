@@ -1,5 +1,5 @@
 // Small helper kernels shared by all paths, and their launchers.
-#include "launch.h"
+#include "pararnn/launch.h"
 
 namespace pararnn {
 
@@ -38,6 +38,14 @@ __global__ __launch_bounds__(256) void store_bf16_kernel(const float *src, unsig
         load_vec<4>(src + 4 * i, v);
         store_vec<4>(dst + 4 * i, v);
     }
+}
+
+__global__ __launch_bounds__(256) void store_bf16_scalar_kernel(const float *src, unsigned short *dst, size_t n,
+                                                                const Ctrl *ctrl)
+{
+    if (ctrl && ctrl->h_final) return;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = f32_to_bf16(src[i]);
 }
 
 __global__ void store_bf16_tail_kernel(const float *src, unsigned short *dst, int n, const Ctrl *ctrl)
@@ -100,7 +108,15 @@ hipError_t launch_zero_words(unsigned int *dst, int n, hipStream_t st)
 
 hipError_t launch_store_bf16(const float *src, void *dst, size_t n, const Ctrl *ctrl, hipStream_t st)
 {
-    // n is a multiple of 4 whenever this is used (vec = 4 path) or handled by the tail kernel
+    // four values per thread (16-byte loads, 8-byte stores) where both pointers allow it, else one
+    if (reinterpret_cast<uintptr_t>(dst) % 8 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) {
+        size_t blocks = (n + 255) / 256;
+        const size_t cap = (size_t)device_cu_count() * 32;
+        if (blocks > cap) blocks = cap;
+        hipLaunchKernelGGL(store_bf16_scalar_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src,
+                           static_cast<unsigned short *>(dst), n, ctrl);
+        return hipGetLastError();
+    }
     const size_t n4 = n / 4;
     if (n4) {
         size_t blocks = (n4 + 255) / 256;

@@ -3,8 +3,8 @@
 // state the candidate reads) and a softsign state nonlinearity (App. D.3 makes
 // the nonlinearities parameters of the cell).
 // Exports gru_sigmoid_tanh_softsign_forward / _backward / ...
-#include "../../include/pararnn_cell.h"
-#include "../../include/pararnn_nonlin.h"
+#include "pararnn_cell.h"
+#include "pararnn_nonlin.h"
 
 using GruSigmoidTanhSoftsign = pararnn::GruDiagNl<pararnn::NlSigmoid, pararnn::NlTanh, pararnn::NlSoftsign>;
 PARARNN_DEFINE_CELL(GruSigmoidTanhSoftsign, gru_sigmoid_tanh_softsign)

@@ -5,7 +5,7 @@
 //
 // every channel has its own 4x4 matrix m.  params [16][H]: rows m_00, m_01, m_02, m_03, m_10, ...
 // Exports quad_tanh_forward / quad_tanh_backward / ...
-#include "../../include/pararnn_cell.h"
+#include "pararnn_cell.h"
 
 struct QuadTanh {
     static constexpr int N = 4;

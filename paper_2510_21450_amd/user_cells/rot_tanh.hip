@@ -6,7 +6,7 @@
 //
 // a per-channel rotation-scaling followed by tanh.  params [2][H] = (a, b).
 // Exports rot_tanh_forward / rot_tanh_backward / ...
-#include "../../include/pararnn_cell.h"
+#include "pararnn_cell.h"
 
 struct RotTanh {
     static constexpr int G = 2, S = 2, P = 2, NC = 4;

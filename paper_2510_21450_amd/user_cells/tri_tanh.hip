@@ -6,7 +6,7 @@
 //
 // every channel has its own 3x3 matrix m.  params [9][H]: rows m_00, m_01, m_02, m_10, ...
 // Exports tri_tanh_forward / tri_tanh_backward / ...
-#include "../../include/pararnn_cell.h"
+#include "pararnn_cell.h"
 
 struct TriTanh {
     static constexpr int G = 3, S = 3, P = 9, NC = 6;

@@ -550,3 +550,28 @@ def test_backward_inputs_staged_through_lds(P, oracle_mod, as_stored, cell):
         du, dp, dh0 = outs[0]
         assert relerr(to_np(du), rdu) <= TOL_BF16 and relerr(to_np(dp), rdp) <= TOL_BF16
         assert relerr(to_np(dh0), rdh0) <= TOL_BF16
+
+
+@pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
+def test_forward_ex_options_travel_with_the_call(P, oracle_mod, cell):
+    """pararnn_forward_ex: the first launch runs `first_block` iterations (3 = the paper's fixed
+    count); whichever launch the tolerance is met in, iteration count, status and trace are the
+    oracle's, h is the converged state, and the process-wide settings stay as they were."""
+    B, L, H = 2, 900, 136
+    params, u, h0, _ = problem(cell, B, L, H, seed=515)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    tol, want = well_posed_tol(oracle_mod, cell, pn, un, h0n, max_iter=40)
+    plan_before = P.solve_plan(tol, 40)
+    for first_block, fused in ((3, -1), (1, -1), (0, -1), (8, -1), (-1, 0), (-1, -1)):
+        print(f"forward_ex {cell} first_block={first_block} fused={fused}", flush=True)
+        h, iters, tr = P.forward_ex(cell, params, u, h0, tol=tol, max_iter=40, first_block=first_block, fused=fused,
+                                    trace=True)
+        torch.cuda.synchronize()
+        assert tuple(int(x) for x in iters.cpu()) == (want, 0)
+        assert relerr(to_np(h), ref) <= TOL_F32
+        plan = P.solve_plan_ex(tol, 40, first_block=first_block, fused=fused)
+        assert sum(plan) == 40 and plan[0] == (1 if fused == 0 or first_block == 0 else (5 if first_block < 0 else first_block))
+    assert P.solve_plan(tol, 40) == plan_before
+    with pytest.raises(RuntimeError, match="INVALID_ARG"):
+        P.forward_ex(cell, params, u, h0, tol=tol, max_iter=40, first_block=9)

@@ -279,3 +279,96 @@ def test_device_info_argument_checks(lib):
     f.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.c_int]
     buf = (ctypes.c_int * 8)()
     assert f(None, 8) == -1 and f(buf, 5) == -1
+
+
+class SolveOptions(ctypes.Structure):
+    _fields_ = [("first_block", ctypes.c_int), ("fused", ctypes.c_int)]
+
+
+def test_per_call_solve_options(lib):
+    """pararnn_forward_ex / pararnn_workspace_bytes_ex / pararnn_solve_plan_ex take the size of the first
+    fused block and the fused switch with the call: same plans and sizes as the process-wide setters
+    give, without touching them; fields out of range are refused."""
+    vp, i, fl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    opt_p = ctypes.POINTER(SolveOptions)
+    plan = lib.pararnn_solve_plan_ex
+    plan.restype = i
+    plan.argtypes = [fl, i, opt_p, ctypes.POINTER(i), i]
+    plan0 = lib.pararnn_solve_plan
+    plan0.restype = i
+    plan0.argtypes = [fl, i, ctypes.POINTER(i), i]
+    wsx = lib.pararnn_workspace_bytes_ex
+    wsx.restype = sz
+    wsx.argtypes = [i, i, i, i, i, opt_p]
+    ws = lib.pararnn_workspace_bytes
+    ws.restype = sz
+    ws.argtypes = [i] * 6
+    buf = (i * 64)()
+
+    def blocks(tol, max_iter, **kw):
+        o = SolveOptions(kw.get("first_block", -1), kw.get("fused", -1))
+        n = plan(tol, max_iter, ctypes.byref(o), buf, 64)
+        return [buf[k] for k in range(n)]
+
+    lib.pararnn_set_fused_head(5)
+    lib.pararnn_set_fused(1)
+    # the paper's three iterations as the first launch
+    assert blocks(1e-5, 10, first_block=3) == [3, 1, 2, 3, 1]
+    assert blocks(1e-5, 10) == [5, 1, 2, 2] and blocks(1e-5, 10, first_block=0) == [1] * 10
+    assert blocks(1e-5, 10, fused=0) == [1] * 10 and blocks(-1.0, 3, fused=0) == [1, 1, 1]
+    assert plan(1e-5, 10, None, buf, 64) == plan0(1e-5, 10, buf, 64)
+    # the process-wide settings were not touched
+    n = plan0(1e-5, 10, buf, 64)
+    assert [buf[k] for k in range(n)] == [5, 1, 2, 2]
+    for bad in (SolveOptions(9, -1), SolveOptions(-2, -1), SolveOptions(3, 2), SolveOptions(3, -2)):
+        assert plan(1e-5, 10, ctypes.byref(bad), buf, 64) == -1
+        assert wsx(0, 0, 4, 4096, 256, ctypes.byref(bad)) == 0
+    # workspace: one record slot per iteration of the first block
+    dflt = ws(0, 0, 4, 4096, 256, 0)
+    assert wsx(0, 0, 4, 4096, 256, None) == dflt
+    three, none = wsx(0, 0, 4, 4096, 256, ctypes.byref(SolveOptions(3, -1))), wsx(0, 0, 4, 4096, 256, ctypes.byref(SolveOptions(0, -1)))
+    assert none < three < dflt
+    lib.pararnn_set_fused_head(3)
+    try:
+        assert ws(0, 0, 4, 4096, 256, 0) == three
+        assert wsx(0, 0, 4, 4096, 256, ctypes.byref(SolveOptions(5, -1))) == dflt
+    finally:
+        lib.pararnn_set_fused_head(5)
+    f = lib.pararnn_forward_ex
+    f.restype = i
+    f.argtypes = [i, i, vp, vp, vp, i, i, i, fl, i, vp, vp, vp, vp, sz, vp, opt_p]
+    p = 0x1000
+    assert f(0, 0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None, ctypes.byref(SolveOptions(9, -1))) == 2
+    assert f(0, 0, p, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 16, None, ctypes.byref(SolveOptions(3, -1))) == 3
+    assert f(0, 0, None, p, None, 1, 8, 8, 1e-6, 4, p, p, None, p, 1 << 20, None, None) == 2
+
+
+def test_channel_count_bound(lib):
+    """H beyond 2^22 would overflow the 32-bit row offsets of the kernels' buffer instructions: refused."""
+    ws = lib.pararnn_workspace_bytes
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [ctypes.c_int] * 6
+    assert ws(0, 0, 1, 4, 1 << 22, 0) > 0 and ws(0, 0, 1, 4, (1 << 22) + 64, 0) == 0
+    f = lib.pararnn_forward
+    f.restype = ctypes.c_int
+    vp, i, fl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    f.argtypes = [i, i, vp, vp, vp, i, i, i, fl, i, vp, vp, vp, vp, sz, vp]
+    p = 0x1000
+    assert f(0, 0, p, p, None, 1, 4, (1 << 22) + 64, 1e-6, 4, p, p, None, p, 1 << 30, None) == 2
+
+
+def test_user_cell_builds_from_the_public_headers_alone(tmp_path):
+    """A cell written against include/pararnn_cell.h compiles with nothing but -I include: the
+    headers a cell library needs (driver, kernels, launchers) are shipped under include/pararnn/."""
+    import shutil
+    import subprocess
+    src = tmp_path / "my_cell.hip"
+    shutil.copy(os.path.join(ROOT, "paper_2510_21450_amd", "user_cells", "quad_tanh.hip"), src)
+    cmd = ["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O1", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", f"-I{os.path.join(ROOT, 'include')}",
+           "-c", str(src), "-o", str(tmp_path / "my_cell.o")]
+    r = subprocess.run(cmd, cwd=tmp_path, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    text = open(src).read() + open(os.path.join(ROOT, "include", "pararnn_cell.h")).read() \
+        + open(os.path.join(ROOT, "include", "pararnn_nonlin.h")).read()
+    assert "csrc" not in text and "../" not in text.replace("../pararnn.h", "")
