@@ -404,6 +404,25 @@ int pararnn_set_dense_products(int mode);
  */
 int pararnn_set_dense_jacobian(int mode);
 
+/*
+ * Launch structure of the dense path's forward solves (host, process-wide, not
+ * thread-safe; default 1).  An iteration has four phases (residual; chunk
+ * products and chunk-local sweeps; carry; final sweep).
+ *   1  the first six iterations are enqueued as one launch per phase; whatever is
+ *      left of max_iter runs in ONE persistent launch whose phases are separated
+ *      by grid-wide barriers and which returns at once when the solve has already
+ *      ended.  A solve that converges early (the usual case: Newton needs 3-5
+ *      iterations) costs one idle launch instead of four per iteration up to
+ *      max_iter;
+ *   0  one launch per phase for every iteration up to max_iter (those after
+ *      convergence return at once);
+ *   2  the persistent launch from the first iteration (slower per iteration:
+ *      every phase then runs at the occupancy of the largest one).
+ * Same arithmetic in all three: bit-identical results.  Other values give
+ * PARARNN_INVALID_ARG.
+ */
+int pararnn_set_dense_tail(int mode);
+
 #ifdef __cplusplus
 }
 #endif

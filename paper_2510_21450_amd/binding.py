@@ -153,6 +153,12 @@ def set_dense_jacobian(mode: int = 0) -> None:
     _raise(_lib.pararnn_set_dense_jacobian(int(mode)), "pararnn_set_dense_jacobian")
 
 
+def set_dense_tail(mode: int = 1) -> None:
+    """pararnn_set_dense_tail: 1 launches per phase for six iterations, then one persistent launch (default);
+    0 launches per phase throughout; 2 the persistent launch from the start."""
+    _raise(_lib.pararnn_set_dense_tail(int(mode)), "pararnn_set_dense_tail")
+
+
 def dense_chunk() -> int:
     return _lib.pararnn_dense_chunk()
 

@@ -27,6 +27,9 @@ int dense_chunk();
 int dense_set_products(int mode);
 // Jacobian of the linear solves of forward solves: 0 full (Newton, default), 1 its diagonal (quasi-Newton).
 int dense_set_jacobian(int mode);
+// Launch structure of forward solves: 1 launches per phase for the first iterations, one persistent launch for the
+// rest (default); 0 launches per phase throughout; 2 the persistent launch from the first iteration.
+int dense_set_one_launch(int mode);
 int dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *ctrl_scratch,
                          hipStream_t st);
 

@@ -69,6 +69,8 @@ struct DenseArgs {
     float *du;           // out [B][L][64]: mu
     int rev;             // 1: scan step t of the recurrence is timestep L-1-t
     unsigned int *norm;  // residual max-norm only: bits of the result, zero on entry
+    unsigned int *gmax;  // one-launch solve only: where the final sweep leaves max|delta| of this iteration
+    unsigned int spin_limit;   // one-launch solve only: polls of a grid-wide barrier before a workgroup gives up
 };
 
 // row of the [B][L][64] arrays that scan step t of sequence b touches
@@ -118,9 +120,8 @@ __device__ __forceinline__ void load_w_operand16(const float *W, int w, int n, i
 // mode 1: write the initial guess h = tanh(W h0 + u) (App. A);
 // mode 2: write nothing but max |F - h| over all rows to a.norm (no control block is read);
 // mode 3: as mode 0, but d is the diagonal of the Jacobian, (1 - F^2) * W_ii (quasi-Newton).
-__global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
+__device__ __forceinline__ void residual_body(const DenseArgs &a, int mode)
 {
-    if (mode != 2 && a.ctrl->stop) return;
     float nmax = 0.0f;
     f4v wdiag = {1.0f, 1.0f, 1.0f, 1.0f};
     if (mode == 3) {
@@ -191,6 +192,12 @@ __global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, 
             atomicMax(a.norm, nmax != nmax ? 0x7fc00000u : __float_as_uint(nmax));
         }
     }
+}
+
+__global__ __launch_bounds__(256) void dense_residual_kernel(const DenseArgs a, int mode)
+{
+    if (mode != 2 && a.ctrl->stop) return;
+    residual_body(a, mode);
 }
 
 // ------------------------------------------------------------ chunk products
@@ -467,7 +474,9 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 // final = 0: x starts at 0, only the end value is kept (b_c).
 // final = 1: x starts at x_{c-1}; afterwards h += delta and max|delta|.
 // BWD: the backward recurrence (r_l = d_l * g_l; the final sweep writes mu = dL/du and nothing else).
-template <int FINAL, bool BWD>
+// LATE_H: the iterate's rows are read after the chain instead of before it (48 fewer registers held
+// through the chain; the one-launch solve shares its register budget with the chunk products).
+template <int FINAL, bool BWD, bool LATE_H = false>
 __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
 {
     __shared__ f4v s_x[2][4][64];
@@ -485,7 +494,7 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
     float wa[4][4];
     load_w_operand16(a.W, w, n, g, wa);
     const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    f4v dv[CD], rv[CD], hv[(FINAL && !BWD) ? CD : 1];
+    f4v dv[CD], rv[CD], hv[(FINAL && !BWD && !LATE_H) ? CD : 1];
 #pragma unroll
     for (int i = 0; i < CD; ++i) {
         const int l = ls + i;
@@ -493,7 +502,7 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
         dv[i] = *reinterpret_cast<const f4v *>(a.d + off);
         if (BWD) rv[i] = dv[i] * *reinterpret_cast<const f4v *>(a.g + off);
         else rv[i] = *reinterpret_cast<const f4v *>(a.r + off);
-        if (FINAL && !BWD) hv[i] = *reinterpret_cast<const f4v *>(a.h + off);
+        if (FINAL && !BWD && !LATE_H) hv[i] = *reinterpret_cast<const f4v *>(a.h + off);
         if (!(ok && l < a.L)) { dv[i] = zero; rv[i] = zero; }     // steps past the end leave x = 0
     }
     f4v x = zero;
@@ -535,7 +544,11 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
 #pragma unroll
     for (int i = 0; i < CD; ++i) {
         const int l = ls + i;
-        if (ok && l < a.L) *reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn) = hv[i] + rv[i];
+        if (ok && l < a.L) {
+            f4v *hp = reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn);
+            if (LATE_H) *hp = *hp + rv[i];
+            else *hp = hv[i] + rv[i];
+        }
 #pragma unroll
         for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
     }
@@ -543,7 +556,11 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
     for (int off = 32; off >= 1; off >>= 1) wmax = nanmax(wmax, __shfl_xor(wmax, off, 64));
     if (lane == 0) s_max[w] = wmax;
     __syncthreads();
-    if (threadIdx.x == 0) finish_iteration(a, nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3])));
+    if (threadIdx.x == 0) {
+        const float bm = nanmax(nanmax(s_max[0], s_max[1]), nanmax(s_max[2], s_max[3]));
+        if (a.gmax) atomicMax(a.gmax, __float_as_uint(bm));       // the one-launch solve decides after its barrier
+        else finish_iteration(a, bm);
+    }
 }
 
 // The final sweep of an iteration (or of the backward pass).
@@ -571,6 +588,9 @@ __global__ __launch_bounds__(256, 2) void dense_products_sweep_kernel(const Dens
 // process-wide choice of the product arithmetic of forward solves (pararnn_set_dense_products)
 int g_dense_products = 0;
 int g_dense_jacobian = 0;       // 0: the full Jacobian (Newton), 1: its diagonal (quasi-Newton)
+int g_dense_one_launch = 1;     // 1: the first kDenseHead iterations as launches per phase, the rest in one persistent
+                                // launch; 0: launches per phase throughout; 2: the persistent launch from the start
+constexpr int kDenseHead = 6;
 
 
 void launch_products_sweep(int prod, int blocks, hipStream_t st, const DenseArgs &a, int n_sweep)
@@ -589,13 +609,12 @@ void launch_products_sweep(int prod, int blocks, hipStream_t st, const DenseArgs
 // The matrices of the next DEPTH chunks are in flight meanwhile; the loop body
 // is branch-free around the loads (indices are clamped) and its barrier orders
 // LDS only, so those loads stay outstanding across steps.
-__global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
+__device__ __forceinline__ void carry_body(const DenseArgs &a, int b)
 {
     constexpr int DEPTH = 8;
     __shared__ __attribute__((aligned(16))) float s_x[2][DH];
-    if (a.ctrl->stop) return;
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int row = 16 * w + (lane >> 2), q = lane & 3, b = blockIdx.x;
+    const int row = 16 * w + (lane >> 2), q = lane & 3;
     const float *bcb = a.bc + (size_t)b * a.n_c * DH + row;
     float *xcb = a.xc + (size_t)b * a.n_c * DH + row;
     const float *Ab = a.Ac + ((size_t)b * a.n_c * DH + row) * DH + 4 * q;    // this lane's first columns, chunk 0
@@ -640,6 +659,175 @@ __global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
             lds_barrier();
         }
     }
+}
+
+__global__ __launch_bounds__(256) void dense_carry_kernel(const DenseArgs a)
+{
+    if (a.ctrl->stop) return;
+    carry_body(a, blockIdx.x);
+}
+
+// ------------------------------------------------- the whole solve in one launch
+// Newton iterations of a forward solve in ONE persistent launch: the phases of an
+// iteration (residual; chunk products + chunk-local sweeps; carry; final sweep) are
+// separated by grid-wide barriers instead of kernel boundaries, the stopping test is
+// taken by every workgroup from the same device-wide maximum right after the last
+// barrier of an iteration, and the launch ends with the iteration that met the
+// tolerance: no launch is enqueued for iterations that never run.  The grid is what
+// the device holds at once (every workgroup is resident, so every barrier is reached
+// by all of them); a barrier wait is bounded like the look-back waits of the scan
+// kernels and ends the launch with status INTERNAL if it ever runs out.
+//
+// Words 16.. of the control block: [0], [1] max|delta| bits of odd / even iterations,
+// [2] barrier arrivals (monotone), [3] ticket of the chunk-product workgroup items.
+__device__ __forceinline__ bool grid_barrier(unsigned int *arrivals, unsigned int &generation, unsigned int spin_limit)
+{
+    __shared__ int s_ok;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();                              // this workgroup's writes, before it arrives
+        ++generation;
+        const unsigned int target = generation * gridDim.x;
+        atomicAdd(arrivals, 1u);
+        unsigned int spins = 0;
+        int ok = 1;
+        while (__hip_atomic_load(arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (++spins >= spin_limit) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(16);             // about half a microsecond: hundreds of workgroups poll one word
+        }
+        __threadfence();                              // the others' writes, after all have arrived
+        s_ok = ok;
+    }
+    __syncthreads();
+    return s_ok != 0;
+}
+
+// Each phase is a function of its own (not inlined): the phases keep W and their row addresses
+// in registers in different layouts, and inlined into one body the compiler would carry all of
+// them through the whole iteration loop and spill.  A phase reads the launch's arguments from the
+// kernel-argument block and gets what changes per iteration by value.
+__device__ __attribute__((noinline)) void phase_residual(const DenseArgs *ap, int mode)
+{
+    const DenseArgs a = *ap;
+    residual_body(a, mode);
+}
+
+template <int PROD>
+__device__ __attribute__((noinline)) void phase_products_sweeps(const DenseArgs *ap, unsigned int *ticket, int n_sweep,
+                                                              int n_prod_blocks)
+{
+    __shared__ unsigned int s_t;
+    const DenseArgs a = *ap;
+    // chunk-local sweeps first (sequential chains, bound by latency), then the chunk products,
+    // handed out by a ticket so that the workgroups that swept do not finish last
+    for (int blk = blockIdx.x; blk < n_sweep; blk += gridDim.x) {
+        sweep_body<0, false>(a, blk);
+        __syncthreads();
+    }
+    for (;;) {
+        if (threadIdx.x == 0) s_t = atomicAdd(ticket, 1u);
+        __syncthreads();
+        const unsigned int t = __builtin_amdgcn_readfirstlane(s_t);
+        __syncthreads();
+        if (t >= (unsigned int)n_prod_blocks) break;
+        if (PROD == 0) chunk_products_body(a, (int)t);
+        else chunk_products_bf16_body<PROD == 1 ? 3 : 1>(a, (int)t);
+    }
+}
+
+__device__ __attribute__((noinline)) void phase_carry(const DenseArgs *ap)
+{
+    const DenseArgs a = *ap;
+    for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+        carry_body(a, b);
+        __syncthreads();
+    }
+}
+
+__device__ __attribute__((noinline)) void phase_final_sweep(const DenseArgs *ap, unsigned int *gmax, int n_sweep)
+{
+    DenseArgs a = *ap;
+    a.gmax = gmax;
+    for (int blk = blockIdx.x; blk < n_sweep; blk += gridDim.x) {
+        sweep_body<1, false, true>(a, blk);
+        __syncthreads();
+    }
+}
+
+// k_first = 1: the solve from the initial guess; k_first > 1: iterations k_first .. max_iter of a
+// solve whose earlier iterations ran as separate launches (nothing to do when one of them ended it).
+template <int PROD>
+__global__ __launch_bounds__(256, 2) void dense_newton_kernel(const DenseArgs a, int n_sweep, int n_prod_blocks,
+                                                              int k_first)
+{
+    Ctrl *ctrl = a.ctrl;
+    if (ctrl->stop) return;
+    unsigned int *aux = reinterpret_cast<unsigned int *>(ctrl) + 16;
+    unsigned int generation = 0;
+    bool alive = true;
+    if (k_first == 1) {
+        // initial guess h^0_l = tanh(W h0 + u_l) (App. A); rows are independent
+        phase_residual(&a, 1);
+        alive = grid_barrier(aux + 2, generation, a.spin_limit);
+    }
+    int k = k_first;
+    for (; alive && k <= a.max_iter; ++k) {
+        unsigned int *gmax = aux + (k & 1);
+        phase_residual(&a, 0);
+        if (!(alive = grid_barrier(aux + 2, generation, a.spin_limit))) break;
+        phase_products_sweeps<PROD>(&a, aux + 3, n_sweep, n_prod_blocks);
+        if (!(alive = grid_barrier(aux + 2, generation, a.spin_limit))) break;
+        phase_carry(&a);
+        if (!(alive = grid_barrier(aux + 2, generation, a.spin_limit))) break;
+        phase_final_sweep(&a, gmax, n_sweep);
+        if (!(alive = grid_barrier(aux + 2, generation, a.spin_limit))) break;
+        // every workgroup reads the same maximum and takes the same decision
+        const float mk = __uint_as_float(__hip_atomic_load(gmax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        int status, stop = 0;
+        if (!(mk - mk == 0.0f)) { status = kStNonFinite; stop = 1; }
+        else if (a.tol >= 0.0f && mk <= a.tol) { status = kStOk; stop = 1; }
+        else status = a.tol < 0.0f ? kStOk : kStNotConverged;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            if (a.trace) a.trace[k - 1] = mk;
+            a.iters_out[0] = k;
+            a.iters_out[1] = status;
+            ctrl->iters = k;
+            ctrl->status = status;
+            ctrl->stop = stop;
+            // for the next iteration: its maximum slot was last read two iterations ago, and the
+            // product ticket is not drawn again before two more barriers
+            aux[(k + 1) & 1] = 0u;
+            aux[3] = 0u;
+        }
+        if (stop) break;
+    }
+    if (!alive && threadIdx.x == 0) {
+        atomicExch(&ctrl->status, kStInternal);
+        a.iters_out[1] = kStInternal;
+    }
+}
+
+void launch_newton(int prod, int grid, hipStream_t st, const DenseArgs &a, int n_sweep, int n_prod_blocks, int k_first)
+{
+    if (prod == 1) hipLaunchKernelGGL((dense_newton_kernel<1>), dim3(grid), dim3(256), 0, st, a, n_sweep, n_prod_blocks, k_first);
+    else if (prod == 2) hipLaunchKernelGGL((dense_newton_kernel<2>), dim3(grid), dim3(256), 0, st, a, n_sweep, n_prod_blocks, k_first);
+    else hipLaunchKernelGGL((dense_newton_kernel<0>), dim3(grid), dim3(256), 0, st, a, n_sweep, n_prod_blocks, k_first);
+}
+
+// workgroups of the one-launch solve: what the device holds at once
+int newton_grid(int prod)
+{
+    static int cap[3] = {0, 0, 0};
+    if (cap[prod] == 0) {
+        int per_cu = 0;
+        hipError_t e;
+        if (prod == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_newton_kernel<1>, 256, 0);
+        else if (prod == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_newton_kernel<2>, 256, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_newton_kernel<0>, 256, 0);
+        if (e != hipSuccess || per_cu < 1) per_cu = 1;
+        cap[prod] = per_cu * device_cu_count();
+    }
+    return cap[prod];
 }
 
 // ------------------------------------------------------------ backward extras
@@ -728,6 +916,13 @@ int dense_set_products(int mode)
 {
     if (mode < 0 || mode > 2) return PARARNN_INVALID_ARG;
     g_dense_products = mode;
+    return PARARNN_OK;
+}
+
+int dense_set_one_launch(int mode)
+{
+    if (mode < 0 || mode > 2) return PARARNN_INVALID_ARG;
+    g_dense_one_launch = mode;
     return PARARNN_OK;
 }
 
@@ -897,16 +1092,33 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
         return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
     }
     if (launch_reset(a.ctrl, nullptr, 0, iters, status0, st) != hipSuccess) return PARARNN_HIP_ERROR;
-    hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     const int n_prod = B * (lo.n_c - 2);
     const int n_prod_blocks = n_prod > 0 ? (n_prod + 3) / 4 : 0;
     const int n_sweep = (B * lo.n_c + 15) / 16;       // workgroups: 16 (sequence, chunk) columns each
-    for (int k = 1; k <= max_iter; ++k) {
+    // Launch plan.  The first iterations run as separate launches per phase (each phase at the occupancy
+    // that suits it: that is the fast way while the solve is running); what is left of max_iter runs in ONE
+    // persistent launch that iterates on the device and returns at once when the solve has already ended.
+    // A solve that converges within the head therefore costs one idle launch instead of four per
+    // iteration up to max_iter.
+    // A fixed-count solve (tol < 0) runs every iteration it is given: nothing is idle, so it stays on the fast path.
+    const int head = g_dense_one_launch == 2 ? 0
+                     : (g_dense_one_launch == 0 || tol < 0.0f) ? max_iter
+                     : (max_iter < kDenseHead ? max_iter : kDenseHead);
+    // the initial guess (all a solve of zero iterations returns); the persistent launch makes its own when it starts the solve
+    if (head > 0 || max_iter == 0) hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
+    for (int k = 1; k <= head; ++k) {
         a.k = k;
         hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
         launch_products_sweep(g_dense_products, n_sweep + n_prod_blocks, st, a, n_sweep);
         hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
         hipLaunchKernelGGL(dense_final_sweep_kernel<false>, dim3(n_sweep), dim3(256), 0, st, a);
+    }
+    if (head < max_iter) {
+        a.spin_limit = settings().spin_limit;
+        const int cap = newton_grid(g_dense_products);
+        const size_t most = res_items > (size_t)(n_sweep + n_prod_blocks) ? res_items : (size_t)(n_sweep + n_prod_blocks);
+        const int grid = (int)(most < (size_t)cap ? (most < 1 ? 1 : most) : (size_t)cap);
+        launch_newton(g_dense_products, grid, st, a, n_sweep, n_prod_blocks, head + 1);
     }
     return hipGetLastError() == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }

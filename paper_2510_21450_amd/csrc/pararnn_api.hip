@@ -422,6 +422,8 @@ int pararnn_set_dense_products(int mode) { return dense_set_products(mode); }
 
 int pararnn_set_dense_jacobian(int mode) { return dense_set_jacobian(mode); }
 
+int pararnn_set_dense_tail(int mode) { return dense_set_one_launch(mode); }
+
 int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, int H, float *A, void *workspace,
                                  size_t workspace_bytes, void *hip_stream)
 {

@@ -353,3 +353,79 @@ def test_dense_iteration_control_edge_cases(oracle_mod, jacobian_mode, mode):
     h, iters, _ = P.forward("tanh_dense", W, u2, h0, tol=1e-6, max_iter=5)
     _, ito, sto, _ = oracle_mod.newton("tanh_dense", Wn, f64(u2), h0n, tol=1e-6, max_iter=5, jacobian=jac)
     assert tuple(int(x) for x in iters.cpu()) == (ito, sto) == (1, 5)
+
+
+# ------------------------------------------- launch plans of the forward solve
+
+@pytest.fixture
+def tail_mode():
+    """Sets the launch plan of the dense path's forward solves for one test and always restores the default."""
+    import paper_2510_21450_amd as P
+    yield P.set_dense_tail
+    P.set_dense_tail(1)
+
+
+@pytest.mark.parametrize("shape", [(3, 50), (33, 100), (5, 257)])
+def test_dense_launch_plans_agree(oracle_mod, tail_mode, shape):
+    """The same solve as launches per phase throughout (0), as six iterations of launches per phase and
+    one persistent launch for the rest (1, the default), and as one persistent launch from the start
+    (2): bit-identical states, the same iteration count, status and trace -- for a solve to a tolerance,
+    for one that runs out of iterations inside the persistent launch, for fixed-count solves on both
+    sides of the hand-over, for max_iter = 0 and for a NaN in the input."""
+    import paper_2510_21450_amd as P
+    B, L = shape
+    H = 64
+    W = normal(940 + L, 5, (H, H), std=0.8 / H ** 0.5, device="cuda")
+    u = normal(940 + L, 1, (B, L, 1, H), device="cuda")
+    h0 = normal(940 + L, 3, (B, 1, H), std=0.3, device="cuda")
+    Wn, un, h0n = f64(W), f64(u), f64(h0)
+    tol, want = well_posed_tol(oracle_mod, "tanh_dense", Wn, un, h0n, max_iter=32, probe_tol=1e-4)
+    u_nan = u.clone(); u_nan[0, L // 2, 0, 5] = float("nan")
+    cases = [dict(u=u, tol=tol, max_iter=32), dict(u=u, tol=0.0, max_iter=9), dict(u=u, tol=-1.0, max_iter=3),
+             dict(u=u, tol=-1.0, max_iter=8), dict(u=u, tol=1e-30, max_iter=7), dict(u=u, tol=tol, max_iter=0),
+             dict(u=u_nan, tol=tol, max_iter=32)]
+    for case in cases:
+        got = []
+        for mode in (0, 1, 2):
+            print(f"dense plans B={B} L={L} tol={case['tol']} max_iter={case['max_iter']} mode={mode}", flush=True)
+            tail_mode(mode)
+            h, iters, tr = P.forward("tanh_dense", W, case["u"], h0, tol=case["tol"], max_iter=case["max_iter"], trace=True)
+            torch.cuda.synchronize()
+            got.append((h.clone(), iters.cpu().tolist(), tr.cpu().numpy().copy()))
+        for mode, (h, it, tr) in zip((1, 2), got[1:]):
+            what = (case["tol"], case["max_iter"], mode)
+            assert it == got[0][1], (what, it, got[0][1])
+            assert np.array_equal(tr, got[0][2], equal_nan=True), what
+            # bit for bit, except that a NaN may carry another sign or payload
+            differ = (h.view(torch.int32) != got[0][0].view(torch.int32)) & ~(torch.isnan(h) & torch.isnan(got[0][0]))
+            assert not bool(differ.any()), (what, int(differ.sum()), torch.nonzero(differ)[:6].tolist(),
+                                            h[differ][:6].tolist(), got[0][0][differ][:6].tolist())
+    # and the first case is the oracle's solve
+    tail_mode(1)
+    h, iters, _ = P.forward("tanh_dense", W, u, h0, tol=tol, max_iter=32)
+    assert iters.cpu().tolist() == [want, 0]
+    assert relerr(f64(h), oracle_mod.seq_unroll("tanh_dense", Wn, un, h0n)) <= 1e-5
+
+
+def test_dense_persistent_launch_gives_up_after_a_bounded_wait(tail_mode):
+    """The grid-wide barriers of the persistent launch wait a bounded number of polls.  With the limit
+    forced to one poll a workgroup that is not the last to arrive gives up: every workgroup still
+    exits, the status says INTERNAL (or the solve went through), and the next call works."""
+    import paper_2510_21450_amd as P
+    w = CONFIGS["C4"].scaled(B=16, L=512)
+    d = make_inputs(w, device="cuda")
+    seen = set()
+    try:
+        P.set_spin_limit(1)
+        tail_mode(2)
+        for rep in range(3):
+            _, iters, _ = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=8)
+            torch.cuda.synchronize()
+            seen.add(P.status_string(int(iters.cpu()[1])))
+    finally:
+        P.set_spin_limit(0)
+    print(f"dense persistent launch, one poll: statuses {sorted(seen)}", flush=True)
+    assert seen <= {"OK", "INTERNAL", "NOT_CONVERGED"}
+    h, iters, _ = P.forward(w.cell, d["params"], d["u"], None, tol=w.tol, max_iter=32)
+    torch.cuda.synchronize()
+    assert int(iters.cpu()[1]) == 0

@@ -112,6 +112,12 @@ def test_dense_products_switch(lib):
     assert sp(3) == 2 and sp(-1) == 2
 
 
+def test_dense_tail_switch(lib):
+    st = lib.pararnn_set_dense_tail
+    assert st(0) == 0 and st(2) == 0 and st(1) == 0
+    assert st(3) == 2 and st(-1) == 2
+
+
 def test_dense_jacobian_switch(lib):
     sj = lib.pararnn_set_dense_jacobian
     assert sj(1) == 0 and sj(0) == 0
