@@ -214,195 +214,216 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             }
         }
 
+        // The K iterations.  Interior tiles run the thread-level pass and the back-substitution without
+        // bounds tests (the C cell evaluations of a thread are independent, they read the previous iterate,
+        // and without branches between them the compiler interleaves their dependency chains).  mode 0 / 1:
+        // the whole iteration loop exists in both forms and the choice is made once per tile, which spares
+        // the register shuffling where two forms meet inside the loop (6 % on the GRU); mode 2: one loop
+        // that chooses inside each phase, for cells whose state no longer fits the registers twice over
+        // (2x2 blocks and larger: the doubled loop costs them a wave per SIMD).
+        auto iterations = [&](auto mode) {
+            constexpr int kMode = decltype(mode)::value;
 #pragma unroll 1
-        for (int k = 1; k <= K; ++k) {
-            const unsigned int epoch = (unsigned int)(a.k0 + k);      // unique within the call
-            unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
+            for (int k = 1; k <= K; ++k) {
+                const unsigned int epoch = (unsigned int)(a.k0 + k);      // unique within the call
+                unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
 
-            // ---- thread level
-            float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                set_identity<S>(accA[v]);
-#pragma unroll
-                for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
-            }
-            // interior tiles take the form without bounds tests: the C cell evaluations of a thread are
-            // independent (they read the previous iterate), and without branches between them the
-            // compiler interleaves their dependency chains
-            auto thread_level = [&](auto guard) {
-                constexpr bool kGuard = decltype(guard)::value;
-#pragma unroll
-                for (int i = 0; i < C; ++i) {
-                    if (!kGuard || l0 + i < g.L) {
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-                            float J[SS], r[S], hp[S], ug[G], F[S];
-#pragma unroll
-                            for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
-#pragma unroll
-                            for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
-                            Cell::template fwd<true>(p[v], hp, ug, F, J, pq[v]);
-#pragma unroll
-                            for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
-                            push_step<S>(J, r, accA[v], accB[v]);
-                        }
-                    }
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-                        for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
-#pragma unroll
-                        for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
-                    }
-                }
-            };
-            if (full_tile) thread_level(std::false_type{});
-            else thread_level(std::true_type{});
-
-            // ---- wave level
-            float lexA[VEC][SS], lexB[VEC][S];
-            if constexpr (LL > 1) {
-#pragma unroll
-                for (int d = 1; d < LL; d <<= 1) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        float pA[SS], pB[S];
-#pragma unroll
-                        for (int e = 0; e < SS; ++e) pA[e] = __shfl_up(accA[v][e], d * LPS, 64);
-#pragma unroll
-                        for (int s = 0; s < S; ++s) pB[s] = __shfl_up(accB[v][s], d * LPS, 64);
-                        if (seg >= d) compose_after<S>(pA, pB, accA[v], accB[v]);
-                    }
-                }
+                // ---- thread level
+                float PA[C][VEC][SS], qb[C][VEC][S], accA[VEC][SS], accB[VEC][S];
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
+                    set_identity<S>(accA[v]);
 #pragma unroll
-                    for (int e = 0; e < SS; ++e) lexA[v][e] = __shfl_up(accA[v][e], LPS, 64);
-#pragma unroll
-                    for (int s = 0; s < S; ++s) lexB[v][s] = __shfl_up(accB[v][s], LPS, 64);
-                    if (seg == 0) {
-                        set_identity<S>(lexA[v]);
-#pragma unroll
-                        for (int s = 0; s < S; ++s) lexB[v][s] = 0.0f;
-                    }
+                    for (int s = 0; s < S; ++s) accB[v][s] = 0.0f;
                 }
-            }
-
-            // ---- workgroup level
-            if (seg == LL - 1) {
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-                    for (int e = 0; e < SS; ++e) s_A[w][e][col + v] = accA[v][e];
-#pragma unroll
-                    for (int s = 0; s < S; ++s) s_b[w][s][col + v] = accB[v][s];
-                }
-            }
-            __syncthreads();
-            float exA[VEC][SS], exB[VEC][S];
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                set_identity<S>(exA[v]);
-#pragma unroll
-                for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
-            }
-            const int upto = w == 0 ? W : w;
-            for (int j = 0; j < upto; ++j) {
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    float Aj[SS], bj[S];
-#pragma unroll
-                    for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
-#pragma unroll
-                    for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][col + v];
-                    push_step<S>(Aj, bj, exA[v], exB[v]);
-                }
-            }
-            if (w == 0) {
-                // ---- grid level: look-back within this iteration's record slot
-                float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-                    for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
-#pragma unroll
-                    for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
-                    set_identity<S>(exA[v]);
-                }
-                const bool active = seg == 0;
-                const bool has_next = lt + 1 < g.n_lt;
-                rec_t *rec = reck + ((size_t)grp * g.n_lt + lt) * (NW * CW);
-                if (lt > 0) {
-                    if (has_next) {
-                        float ab[SS + S][VEC];
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-                            for (int e = 0; e < SS; ++e) ab[e][v] = tileA[e][v];
-#pragma unroll
-                            for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
-                        }
-                        publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
-                    }
-                    if (!lookback<S, VEC, CW>(g.spin_limit, reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
-                        internal_error = true;
-                }
-                if (has_next) {
-                    float inc[S][VEC];
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        float A1[SS], x[S], b1[S], y[S];
-#pragma unroll
-                        for (int e = 0; e < SS; ++e) A1[e] = tileA[e][v];
-#pragma unroll
-                        for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
-                        affine<S>(A1, x, b1, y);
-#pragma unroll
-                        for (int s = 0; s < S; ++s) inc[s][v] = y[s];
-                    }
-                    publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
-                }
-                if (active) {
-#pragma unroll
-                    for (int s = 0; s < S; ++s)
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
-                }
-            }
-            __syncthreads();
-
-            // ---- back-substitution; the delta entering the chunk also updates the state before it
-            unsigned int wmax_bits = 0u;
-            auto back_substitute = [&](auto guard) {
-                constexpr bool kGuard = decltype(guard)::value;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    float cin[S], din[S];
-#pragma unroll
-                    for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
-                    affine<S>(exA[v], cin, exB[v], din);
-                    if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
-#pragma unroll
-                    for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
+                auto thread_level = [&](auto gd) {
+                    constexpr bool kG = decltype(gd)::value;
 #pragma unroll
                     for (int i = 0; i < C; ++i) {
-                        float d[S];
-                        affine<S>(PA[i][v], din, qb[i][v], d);
+                        if (!kG || l0 + i < g.L) {
 #pragma unroll
-                        for (int s = 0; s < S; ++s) {
-                            ho[i][s][v] += d[s];
-                            if (!kGuard || (ch_ok && l0 + i < g.L))
-                                wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
+                            for (int v = 0; v < VEC; ++v) {
+                                float J[SS], r[S], hp[S], ug[G], F[S];
+#pragma unroll
+                                for (int s = 0; s < S; ++s) hp[s] = i == 0 ? hprev[s][v] : ho[i - 1][s][v];
+#pragma unroll
+                                for (int q = 0; q < G; ++q) ug[q] = uu[i][q][v];
+                                Cell::template fwd<true>(p[v], hp, ug, F, J, pq[v]);
+#pragma unroll
+                                for (int s = 0; s < S; ++s) r[s] = F[s] - ho[i][s][v];
+                                push_step<S>(J, r, accA[v], accB[v]);
+                            }
+                        }
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) PA[i][v][e] = accA[v][e];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) qb[i][v][s] = accB[v][s];
+                        }
+                    }
+                };
+                if constexpr (kMode == 2) {
+                    if (full_tile) thread_level(std::false_type{});
+                    else thread_level(std::true_type{});
+                } else {
+                    thread_level(std::integral_constant<bool, kMode == 1>{});
+                }
+
+                // ---- wave level
+                float lexA[VEC][SS], lexB[VEC][S];
+                if constexpr (LL > 1) {
+#pragma unroll
+                    for (int d = 1; d < LL; d <<= 1) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            float pA[SS], pB[S];
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) pA[e] = __shfl_up(accA[v][e], d * LPS, 64);
+#pragma unroll
+                            for (int s = 0; s < S; ++s) pB[s] = __shfl_up(accB[v][s], d * LPS, 64);
+                            if (seg >= d) compose_after<S>(pA, pB, accA[v], accB[v]);
+                        }
+                    }
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) lexA[v][e] = __shfl_up(accA[v][e], LPS, 64);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) lexB[v][s] = __shfl_up(accB[v][s], LPS, 64);
+                        if (seg == 0) {
+                            set_identity<S>(lexA[v]);
+#pragma unroll
+                            for (int s = 0; s < S; ++s) lexB[v][s] = 0.0f;
                         }
                     }
                 }
-            };
-            if (full_tile) back_substitute(std::false_type{});
-            else back_substitute(std::true_type{});
-            const unsigned int wave_bits = wave_max_u32(wmax_bits);
-            if (lane == 0) atomicMax(&s_maxk[k - 1], wave_bits);
-            // s_A / s_carry are rewritten only after the next iteration's first barrier
+
+                // ---- workgroup level
+                if (seg == LL - 1) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) s_A[w][e][col + v] = accA[v][e];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) s_b[w][s][col + v] = accB[v][s];
+                    }
+                }
+                __syncthreads();
+                float exA[VEC][SS], exB[VEC][S];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    set_identity<S>(exA[v]);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
+                }
+                const int upto = w == 0 ? W : w;
+                for (int j = 0; j < upto; ++j) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float Aj[SS], bj[S];
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][col + v];
+                        push_step<S>(Aj, bj, exA[v], exB[v]);
+                    }
+                }
+                if (w == 0) {
+                    // ---- grid level: look-back within this iteration's record slot
+                    float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                        for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
+                        set_identity<S>(exA[v]);
+                    }
+                    const bool active = seg == 0;
+                    const bool has_next = lt + 1 < g.n_lt;
+                    rec_t *rec = reck + ((size_t)grp * g.n_lt + lt) * (NW * CW);
+                    if (lt > 0) {
+                        if (has_next) {
+                            float ab[SS + S][VEC];
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                                for (int e = 0; e < SS; ++e) ab[e][v] = tileA[e][v];
+#pragma unroll
+                                for (int s = 0; s < S; ++s) ab[SS + s][v] = tileB[s][v];
+                            }
+                            publish<SS + S, VEC, CW>(rec, ab, epoch * 4u + kFlagAgg, col, active);
+                        }
+                        if (!lookback<S, VEC, CW>(g.spin_limit, reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
+                            internal_error = true;
+                    }
+                    if (has_next) {
+                        float inc[S][VEC];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            float A1[SS], x[S], b1[S], y[S];
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) A1[e] = tileA[e][v];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
+                            affine<S>(A1, x, b1, y);
+#pragma unroll
+                            for (int s = 0; s < S; ++s) inc[s][v] = y[s];
+                        }
+                        publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
+                    }
+                    if (active) {
+#pragma unroll
+                        for (int s = 0; s < S; ++s)
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
+                    }
+                }
+                __syncthreads();
+
+                // ---- back-substitution; the delta entering the chunk also updates the state before it
+                unsigned int wmax_bits = 0u;
+                auto back_substitute = [&](auto gd) {
+                    constexpr bool kG = decltype(gd)::value;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float cin[S], din[S];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
+                        affine<S>(exA[v], cin, exB[v], din);
+                        if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
+#pragma unroll
+                        for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
+#pragma unroll
+                        for (int i = 0; i < C; ++i) {
+                            float d[S];
+                            affine<S>(PA[i][v], din, qb[i][v], d);
+#pragma unroll
+                            for (int s = 0; s < S; ++s) {
+                                ho[i][s][v] += d[s];
+                                if (!kG || (ch_ok && l0 + i < g.L))
+                                    wmax_bits = max(wmax_bits, __float_as_uint(d[s]) & 0x7fffffffu);
+                            }
+                        }
+                    }
+                };
+                if constexpr (kMode == 2) {
+                    if (full_tile) back_substitute(std::false_type{});
+                    else back_substitute(std::true_type{});
+                } else {
+                    back_substitute(std::integral_constant<bool, kMode == 1>{});
+                }
+                const unsigned int wave_bits = wave_max_u32(wmax_bits);
+                if (lane == 0) atomicMax(&s_maxk[k - 1], wave_bits);
+                // s_A / s_carry are rewritten only after the next iteration's first barrier
+            }
+        };
+        if constexpr (S == 1) {
+            if (full_tile) iterations(std::integral_constant<int, 0>{});
+            else iterations(std::integral_constant<int, 1>{});
+        } else {
+            iterations(std::integral_constant<int, 2>{});
         }
 
         // ---- what a following per-iteration launch needs: the fp32 iterate and the tile's last row

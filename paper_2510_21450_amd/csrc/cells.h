@@ -68,12 +68,21 @@ struct GruDiag {
         J = fmaf(p[1], kr, J);
     }
 
+    // The forward pass needs F and J only: J = (1-z) + a_z k_z + a_c k_c (r + a_r r h (1-r)), which
+    // skips k_r as a value of its own (one instruction fewer per evaluation than coefs).
     template <bool FOLD = false>
     __device__ __forceinline__ static void fwd(const float *p, const float *hp, const float *u, float *F, float *J,
                                                const float *q = nullptr)
     {
-        float kz, kr, kc, rh;
-        coefs<FOLD>(p, q, hp[0], u, F[0], J[0], kz, kr, kc, rh);
+        float z, r, rh, c;
+        const float h = hp[0];
+        gates<FOLD>(p, q, h, u, z, r, rh, c);
+        const float cmh = c - h, omz = 1.0f - z;
+        F[0] = fmaf(z, cmh, h);
+        const float kz = cmh * (z * omz);
+        const float ackc = p[2] * (z * fmaf(-c, c, 1.0f));
+        const float t = fmaf(p[1], rh * (1.0f - r), r);
+        J[0] = fmaf(ackc, t, fmaf(p[0], kz, omz));
     }
 
     __device__ __forceinline__ static void bwd_prep(const float *p, const float *hp, const float *u,
