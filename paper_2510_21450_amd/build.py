@@ -26,7 +26,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG), "include")      # public headers: p
 FLAGS = ["--offload-arch=gfx950", f"-I{INCLUDE}", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 VALU forms are kept off for the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-but-set-variable", "-Wno-unknown-warning-option",
+         "-Wall", "-Wno-inline-asm", "-Wno-unused-but-set-variable", "-Wno-unknown-warning-option",
          "-Wno-sometimes-uninitialized", "-Wno-uninitialized"]
 
 

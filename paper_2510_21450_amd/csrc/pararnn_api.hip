@@ -143,7 +143,7 @@ int pararnn_set_spin_limit(unsigned int polls)
 int pararnn_set_staging(int enable)
 {
     settings().stage_enabled = enable ? 1 : 0;
-    return PARARNN_OK;
+    return proj_set_dma(enable);
 }
 
 int pararnn_set_fused(int enable)

@@ -201,6 +201,7 @@ struct GemmArgs {
     long long a_off[2], b_off[2], c_off[2];     // element offsets per unit of z0, z1
     int tiles_m, tiles_n;
     int *tickets;                  // eight counters, zero at launch: the next tile number of each XCD
+    int draw;                      // tile numbers taken per draw (copy-to-LDS kernel)
 };
 
 // Persistent workgroups, each walking a list of output tiles; the (tile, k-step) pairs
@@ -414,6 +415,293 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
                      [&]() { return c_end; });
 }
 
+// ------------------------------- NT product, bf16 operands copied straight into LDS
+// The same product for bf16 storage and K >= 128, built around buffer loads whose destination
+// is LDS: operand tiles never pass through registers, so the prefetch depth costs no registers
+// and a step costs a wave four copy instructions instead of eight loads, eight conversions and
+// eight LDS stores.
+//
+//   tile     256 x 256 outputs per workgroup of eight waves (2 x 4; 128 rows x 64 columns per
+//            wave = eight 32 x 32 accumulators), 32 k per step; one workgroup per CU
+//   LDS      four stages of (256 + 256) rows x 64 bytes = 128 KB.  A copy instruction moves
+//            64 x 16 bytes to consecutive LDS addresses, lane i to base + 16 i: 16 rows of a
+//            stage.  Which 16-byte k-chunk of its row a lane fetches is free, and chosen so
+//            that chunk c of row r lies at position c ^ swz(r) of the row: the four lanes of
+//            a row still read 64 consecutive bytes of memory, and the fragment reads of the
+//            multiply (32 rows, one chunk each) spread over all banks.
+//   step t   F1 <- fragments (t, k 16..31);  multiply k 0..15 from F0;
+//            wait: own copies of step t + 1 landed, own reads done;  barrier;
+//            F0 <- fragments (t + 1, k 0..15);  start the copies of step t + 4 into the
+//            stage step t has just left;  multiply k 16..31 from F1.
+//            One barrier per step, LDS latency behind eight products, memory latency behind
+//            three and a half steps.
+//   waits    the copies are issued from inline assembly, so the compiler neither knows nor
+//            waits for them; the kernel counts: loads of a wave complete in order, and between
+//            the copies of step t + 1 and the wait of step t a wave has issued the copies of
+//            steps t + 2 and t + 3 (four each, at least), so "at most eight memory operations
+//            outstanding" implies that step t + 1 has landed.  Stores of a finished output tile
+//            may be among the outstanding ones; whatever order stores and loads complete in, at
+//            most eight outstanding operations still leave only the youngest eight loads open,
+//            so the same wait is safe (it then also waits for most of the stores, once per tile).
+//   tiles    drawn from the per-XCD counters like above, a few consecutive numbers per draw
+//            (the compiler waits for the atomic's result with every copy in flight, which
+//            stalls the drawing wave; per draw, not per tile), and put into the ring one tile
+//            ahead.
+namespace dma {
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+constexpr int OP = 256 * BK;             // bf16 elements of one operand tile of a stage
+constexpr int STAGE = 2 * OP;            // A tile, then W tile
+}  // namespace dma
+
+__device__ __forceinline__ int dma_swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
+
+__device__ __forceinline__ unsigned int uniform(unsigned int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// buffer descriptor words for the assembly forms: base, no stride, whole 4 GiB window
+__device__ __forceinline__ u4v rsrc_words(const void *p)
+{
+    const unsigned long long v = (unsigned long long)p;
+    const u4v r = {uniform((unsigned int)v), uniform((unsigned int)(v >> 32) & 0xffffu), 0xffffffffu, 0x27000u};
+    return r;
+}
+
+__device__ __forceinline__ unsigned int lds_address(const void *p)
+{
+    return (unsigned int)(unsigned long long)(__attribute__((address_space(3))) const void *)p;
+}
+
+// 64 x 16 bytes (64 x 4 bytes) from rsrc + voff + soff to LDS lds_base + 16 (4) * lane.  The five wait
+// states in front of the load are the ones a vector-memory instruction needs after a vector instruction
+// (v_readfirstlane, v_readlane of a spilled value) has written one of its scalar operands; the compiler
+// inserts them for its own instructions and not for what is inside an asm statement.  They also cover
+// the wait state between the write of M0 and its use.
+__device__ __forceinline__ void copy_to_lds_16(unsigned int lds_base, const u4v &rsrc, unsigned int voff, unsigned int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(uniform(lds_base)), "v"(voff), "s"(rsrc), "s"(uniform(soff)) : "memory", "m0");
+}
+__device__ __forceinline__ void copy_to_lds_4(unsigned int lds_base, const u4v &rsrc, unsigned int voff, unsigned int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(uniform(lds_base)), "v"(voff), "s"(rsrc), "s"(uniform(soff)) : "memory", "m0");
+}
+
+template <bool BIAS>
+__global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
+{
+    constexpr int BM = dma::BM, BN = dma::BN, BK = dma::BK, STAGES = dma::STAGES, OP = dma::OP, STAGE = dma::STAGE;
+    __shared__ __attribute__((aligned(16))) unsigned short s_op[STAGES][STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned short s_epi[8][32 * 32];
+    __shared__ __attribute__((aligned(16))) float s_bias[4][8][64];
+    __shared__ int s_ring[8];
+    const int xcd = blockIdx.x & 7;
+    const int inner_n = a.tiles_n * a.n_batch;
+    // the XCD's (row block, inner) grid in patches of 8 x 8 tiles, as in proj_gemm_nt_kernel
+    const int mx = (a.tiles_m + 7) / 8;
+    int my_rows = a.tiles_m - xcd * mx;
+    if (my_rows > mx) my_rows = mx;
+    if (my_rows <= 0) return;
+    const int n_local = my_rows * inner_n;
+    const int nk = a.K / BK;
+    const int tid = threadIdx.x, lane = tid & 63, w = (int)uniform((unsigned int)tid >> 6), wm = w >> 2, wn = w & 3;
+    const int half = lane >> 5, l32 = lane & 31;
+    if (tid == 0) s_ring[0] = atomicAdd(a.tickets + xcd, a.draw);
+    __syncthreads();
+    const int first = (int)uniform((unsigned int)s_ring[0]);
+    if (first >= n_local) return;
+
+    struct Tile {
+        const unsigned short *A, *Bw;
+        long long coff;
+        int m0, n0;
+    };
+    auto tile_of = [&](int local) {
+        const int pm = local / (8 * inner_n), rem = local - pm * 8 * inner_n;
+        const int hm = min(8, my_rows - 8 * pm);
+        const int pn = rem / (8 * hm), rem2 = rem - pn * 8 * hm;
+        const int hn = min(8, inner_n - 8 * pn);
+        const int mt = xcd * mx + 8 * pm + rem2 / hn, inner = 8 * pn + rem2 % hn;
+        const int nt = inner % a.tiles_n, z = inner / a.tiles_n;
+        const int z0 = z % a.nz0, z1 = z / a.nz0;
+        Tile t;
+        t.A = static_cast<const unsigned short *>(a.A) + z0 * a.a_off[0] + z1 * a.a_off[1];
+        t.Bw = a.Bw + z0 * a.b_off[0] + z1 * a.b_off[1];
+        t.coff = z0 * a.c_off[0] + z1 * a.c_off[1];
+        t.m0 = mt * BM; t.n0 = nt * BN;
+        return t;
+    };
+
+    // ---- the copying side: tile number ln of this workgroup, k-step lks of it
+    const unsigned int lds_op = lds_address(&s_op[0][0]);
+    const int lrow = lane >> 2, lchunk = (lane & 3) ^ dma_swz(lrow);          // row within 16, k-chunk fetched
+    u4v ra, rb, rbias;
+    unsigned int va[2], vb[2], vbias = 0u;
+    int ln = 0, lks = 0;
+    long long seg_base = 0;                // element offset of the current k-segment in a row of A
+    int kin = 0;                           // k within the segment
+    bool l_end = false;
+    auto point_at = [&](const Tile &t) {
+        ra = rsrc_words(t.A + (long long)t.m0 * a.lda);
+        rb = rsrc_words(t.Bw + (long long)t.n0 * a.ldb);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            // rows past the end read the last row (valid memory); their products are never stored
+            const int row = 32 * w + 16 * j + lrow;
+            const int gm = min(t.m0 + row, a.M - 1) - t.m0, gn = min(t.n0 + row, a.N - 1) - t.n0;
+            va[j] = (unsigned int)gm * (unsigned int)a.lda * 2u + (unsigned int)lchunk * 16u;
+            vb[j] = (unsigned int)gn * (unsigned int)a.ldb * 2u + (unsigned int)lchunk * 16u;
+        }
+        if (BIAS) {
+            rbias = rsrc_words(a.bias + t.coff);
+            vbias = (unsigned int)min(t.n0 + 64 * wn + lane, a.N - 1) * 4u;
+        }
+        seg_base = 0; kin = 0;
+    };
+    // thread 0: the numbers drawn and not yet handed out
+    int next_no = first + 1, left = a.draw - 1;
+    auto draw = [&]() {
+        // the number of tile ln + 1 goes into the ring; it is read after at least one barrier
+        if (tid == 0) {
+            if (left == 0) {
+                next_no = atomicAdd(a.tickets + xcd, a.draw);
+                left = a.draw;
+            }
+            s_ring[(ln + 1) & 7] = next_no++;
+            --left;
+        }
+    };
+    // the copies of the next step in stream order, into stage `buf`
+    auto issue = [&](int buf) {
+        if (lks == nk) {
+            const int t = (int)uniform((unsigned int)s_ring[(ln + 1) & 7]);      // published at least a barrier ago
+            if (t >= n_local) {
+                l_end = true;
+                return;
+            }
+            point_at(tile_of(t));
+            ++ln;
+            lks = 0;
+        }
+        if (lks == 0) {
+            draw();
+            if (BIAS) copy_to_lds_4(lds_address(&s_bias[ln & 3][w][0]), rbias, vbias, 0u);
+        }
+        const unsigned int soa = (unsigned int)((seg_base + kin) * 2), sob = (unsigned int)(lks * BK) * 2u;
+        const unsigned int dst = lds_op + (unsigned int)buf * (STAGE * 2u) + (unsigned int)(32 * w) * (BK * 2u);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            copy_to_lds_16(dst + (unsigned int)j * (16u * BK * 2u), ra, va[j], soa);
+            copy_to_lds_16(dst + OP * 2u + (unsigned int)j * (16u * BK * 2u), rb, vb[j], sob);
+        }
+        ++lks;
+        kin += BK;
+        if (kin == a.kseg) {
+            kin = 0;
+            seg_base += a.kseg_stride;
+        }
+    };
+
+    // ---- the multiplying side
+    // byte offset of this lane's fragment piece within a 32-row block, for k 0..15 and k 16..31
+    unsigned int fo[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) fo[kb] = (unsigned int)l32 * 64u + (unsigned int)((2 * kb + half) ^ dma_swz(l32)) * 16u;
+    auto read_frags = [&](int buf, int kb, bf8v (&fa)[4], bf8v (&fw)[2]) {
+        const char *base = reinterpret_cast<const char *>(&s_op[buf][0]) + fo[kb];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) fa[mi] = *reinterpret_cast<const bf8v *>(base + (128 * wm + 32 * mi) * 64);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) fw[ni] = *reinterpret_cast<const bf8v *>(base + OP * 2 + (64 * wn + 32 * ni) * 64);
+    };
+    f16v acc[2][4];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.0f;
+    };
+    // acc[ni][mi] = (W rows)(A rows)^T: a lane owns row l32 of the A block and, per four registers,
+    // four consecutive columns
+    auto multiply = [&](const bf8v (&fa)[4], const bf8v (&fw)[2]) {
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ni], fa[mi], acc[ni][mi], 0, 0, 0);
+    };
+    Tile ct = tile_of(first);
+    int cn = 0, cks = 0;
+    auto epilogue = [&]() {
+        // 32 x 32 blocks through this wave's LDS patch, so that global stores are 64-byte row pieces;
+        // 16-byte chunk c of row r sits at chunk position c ^ (r / 4 % 4)
+        unsigned short *stage = &s_epi[w][0];
+        const int rows_here = a.M - (ct.m0 + 128 * wm);                   // valid rows of this wave's part (may be <= 0)
+        const bool cols_here = ct.n0 + 64 * wn < a.N;                     // N is a multiple of 64: all 64 columns or none
+        unsigned short *C = static_cast<unsigned short *>(a.C) + ct.coff + (long long)(ct.m0 + 128 * wm) * a.ldc + ct.n0 + 64 * wn;
+        const long long valid = (rows_here > 0 && cols_here) ? (long long)(min(rows_here, 128) - 1) * a.ldc * 2 + 128 : 0;
+        const buf_rsrc rc = __builtin_amdgcn_make_buffer_rsrc(C, 0, (int)valid, 0x27000);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+                    if (BIAS) o += *reinterpret_cast<const f4v *>(&s_bias[cn & 3][w][32 * ni + 8 * q + 4 * half]);
+                    store4(stage + l32 * 32 + (q ^ ((l32 >> 2) & 3)) * 8 + 4 * half, o);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int r = 16 * it + (lane >> 2), cc = lane & 3;
+                    const u4v v = *reinterpret_cast<const u4v *>(stage + r * 32 + (cc ^ ((r >> 2) & 3)) * 8);
+                    const unsigned int off = (unsigned int)(32 * mi + r) * (unsigned int)a.ldc * 2u + (unsigned int)(32 * ni + 8 * cc) * 2u;
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rc, off, 0, 0);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+    };
+
+    // ---- prologue: four steps on their way, the first one landed
+    point_at(ct);
+    issue(0); issue(1); issue(2); issue(3);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    asm volatile("s_barrier" ::: "memory");
+    bf8v fa0[4], fw0[2], fa1[4], fw1[2];
+    read_frags(0, 0, fa0, fw0);
+    clear_acc();
+
+    for (int t = 0;; ++t) {
+        const int buf = t & 3;
+        read_frags(buf, 1, fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa0, fw0);
+        __builtin_amdgcn_sched_barrier(0);
+        // own copies of step t + 1 have landed (see "waits" above)
+        if (l_end) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        read_frags((t + 1) & 3, 0, fa0, fw0);
+        if (!l_end) issue(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (++cks == nk) {
+            epilogue();
+            clear_acc();
+            cks = 0;
+            const int nt = (int)uniform((unsigned int)s_ring[++cn & 7]);
+            if (nt >= n_local) break;
+            ct = tile_of(nt);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // --------------------------------------------------- dWx and dbias (TN product)
 struct DwArgs {
     const void *du;        // [M][G][H], storage type AT
@@ -625,6 +913,8 @@ __global__ __launch_bounds__(256) void proj_wt_kernel(const float *Wx, unsigned 
 
 size_t r256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+int g_proj_dma = 1;        // bf16 NT products use the copy-to-LDS kernel where it applies (proj_set_dma)
+
 bool shapes_ok(int dtype, int B, int L, int H, int G, int n_heads)
 {
     if (dtype != PARARNN_F32 && dtype != PARARNN_BF16) return false;
@@ -684,6 +974,31 @@ template <typename AT, typename CT> hipError_t launch_nt(GemmArgs &g, hipStream_
     return hipGetLastError();
 }
 
+// the copy-to-LDS kernel: bf16 storage, at least four 32-k steps per tile, k-segments in whole steps, row
+// offsets of a 256-row tile within 32 bits
+bool nt_dma_ok(const GemmArgs &g)
+{
+    return g.K >= 4 * dma::BK && g.K % dma::BK == 0 && g.kseg % dma::BK == 0 && g.N % 64 == 0 &&
+           g.lda < (1 << 22) && g.ldb < (1 << 22) && g.ldc < (1 << 22) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.ldc % 8 == 0;
+}
+
+hipError_t launch_nt_dma(GemmArgs &g, hipStream_t st)
+{
+    g.tiles_m = (g.M + dma::BM - 1) / dma::BM;
+    g.tiles_n = (g.N + dma::BN - 1) / dma::BN;
+    // one workgroup per compute unit (its LDS allows no more), the same number on every XCD
+    int slots = device_cu_count() / 8;
+    if (slots < 1) slots = 1;
+    if (slots > 64) slots = 64;
+    // numbers per draw: about an eighth of a workgroup's share, four at most (the tail of a launch is then a few
+    // tiles out of hundreds), one where a workgroup gets few tiles
+    const long long per_wg = ((long long)(g.tiles_m + 7) / 8) * g.tiles_n * g.n_batch / slots;
+    g.draw = per_wg >= 32 ? 4 : per_wg >= 16 ? 2 : 1;
+    if (g.bias) hipLaunchKernelGGL((proj_gemm_nt_dma_kernel<true>), dim3((unsigned)(8 * slots)), dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((proj_gemm_nt_dma_kernel<false>), dim3((unsigned)(8 * slots)), dim3(512), 0, st, g);
+    return hipGetLastError();
+}
+
 int elementwise_blocks(size_t n)
 {
     size_t blocks = (n + 255) / 256;
@@ -692,6 +1007,12 @@ int elementwise_blocks(size_t n)
 }
 
 }  // namespace
+
+int proj_set_dma(int on)
+{
+    g_proj_dma = on ? 1 : 0;
+    return PARARNN_OK;
+}
 
 size_t proj_workspace_bytes(int dtype, int B, int L, int H, int G, int n_heads, int backward)
 {
@@ -722,7 +1043,8 @@ int proj_forward(int dtype, const void *x, const float *Wx, const float *bias, i
     g.a_off[0] = 0; g.a_off[1] = dh;                   // columns of x (all gates of a head) are neighbours
     g.b_off[0] = (long long)H * dh; g.b_off[1] = (long long)dh * dh;
     g.c_off[0] = H; g.c_off[1] = dh;
-    const hipError_t e = dtype == PARARNN_BF16 ? launch_nt<unsigned short, unsigned short>(g, st) : launch_nt<float, float>(g, st);
+    const hipError_t e = dtype != PARARNN_BF16 ? launch_nt<float, float>(g, st)
+                         : (g_proj_dma && nt_dma_ok(g)) ? launch_nt_dma(g, st) : launch_nt<unsigned short, unsigned short>(g, st);
     return e == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
 
@@ -751,7 +1073,8 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         g.kseg = dh; g.kseg_stride = H;                 // k = (gate, i): gates are H apart in a row of du
         g.nz0 = n_heads; g.n_batch = n_heads;           // z0 = head
         g.a_off[0] = dh; g.b_off[0] = (long long)dh * G * dh; g.c_off[0] = dh;
-        e = bf ? launch_nt<unsigned short, unsigned short>(g, st) : launch_nt<float, float>(g, st);
+        e = !bf ? launch_nt<float, float>(g, st)
+            : (g_proj_dma && nt_dma_ok(g)) ? launch_nt_dma(g, st) : launch_nt<unsigned short, unsigned short>(g, st);
         if (e != hipSuccess) return PARARNN_HIP_ERROR;
     }
     if (dWx) {
