@@ -417,43 +417,40 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 
 // ------------------------------- NT product, bf16 operands copied straight into LDS
 // The same product for bf16 storage and K >= 128, built around buffer loads whose destination
-// is LDS: operand tiles never pass through registers, so the prefetch depth costs no registers
-// and a step costs a wave four copy instructions instead of eight loads, eight conversions and
-// eight LDS stores.
+// is LDS: operand tiles never pass through registers, and a step costs a wave eight copy
+// instructions instead of loads, conversions and LDS stores.
 //
 //   tile     256 x 256 outputs per workgroup of eight waves (2 x 4; 128 rows x 64 columns per
-//            wave = eight 32 x 32 accumulators), 32 k per step; one workgroup per CU
-//   LDS      four stages of (256 + 256) rows x 64 bytes = 128 KB.  A copy instruction moves
-//            64 x 16 bytes to consecutive LDS addresses, lane i to base + 16 i: 16 rows of a
-//            stage.  Which 16-byte k-chunk of its row a lane fetches is free, and chosen so
-//            that chunk c of row r lies at position c ^ swz(r) of the row: the four lanes of
-//            a row still read 64 consecutive bytes of memory, and the fragment reads of the
-//            multiply (32 rows, one chunk each) spread over all banks.
-//   step t   F1 <- fragments (t, k 16..31);  multiply k 0..15 from F0;
-//            wait: own copies of step t + 1 landed, own reads done;  barrier;
-//            F0 <- fragments (t + 1, k 0..15);  start the copies of step t + 4 into the
-//            stage step t has just left;  multiply k 16..31 from F1.
-//            One barrier per step, LDS latency behind eight products, memory latency behind
-//            three and a half steps.
+//            wave = eight 32 x 32 accumulators), 64 k per step; one workgroup per CU
+//   LDS      two stages of (256 + 256) rows x 128 bytes = 128 KB.  A copy instruction moves
+//            64 x 16 bytes to consecutive LDS addresses, lane i to base + 16 i: 8 rows of a
+//            stage, and 8 whole 128-byte lines of memory (with 32 k per step an instruction
+//            took half of 16 lines, and the other half of every line was fetched again a step
+//            later: the copies alone then took as long as the whole kernel does now).  Which
+//            16-byte k-chunk of its row a lane fetches is free, and chosen so that chunk c of
+//            row r lies at position c ^ swz(r) of the row: the eight lanes of a row still read
+//            one line, and the fragment reads of the multiply (32 rows, one chunk each) spread
+//            over all banks, whether 8 or 16 lanes are served per cycle.
+//   step T   four rounds of (fragments of the next 16 k, eight products of the current 16 k);
+//            before the last round: own copies of step T + 1 landed, own reads of step T done,
+//            barrier; then the first fragments of step T + 1 are read and the copies of step
+//            T + 2 start into the stage step T has just left.  One barrier per step, LDS
+//            latency behind eight products, memory latency behind one step.
 //   waits    the copies are issued from inline assembly, so the compiler neither knows nor
-//            waits for them; the kernel counts: loads of a wave complete in order, and between
-//            the copies of step t + 1 and the wait of step t a wave has issued the copies of
-//            steps t + 2 and t + 3 (four each, at least), so "at most eight memory operations
-//            outstanding" implies that step t + 1 has landed.  Stores of a finished output tile
-//            may be among the outstanding ones; whatever order stores and loads complete in, at
-//            most eight outstanding operations still leave only the youngest eight loads open,
-//            so the same wait is safe (it then also waits for most of the stores, once per tile).
+//            waits for them; at the one wait of a step the copies of step T + 1 are the only
+//            loads the wave has outstanding, so the kernel waits for "no memory operation
+//            outstanding" (the stores of a finished output tile included, once per tile).
 //   tiles    drawn from the per-XCD counters like above, a few consecutive numbers per draw
 //            (the compiler waits for the atomic's result with every copy in flight, which
 //            stalls the drawing wave; per draw, not per tile), and put into the ring one tile
 //            ahead.
 namespace dma {
-constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int OP = 256 * BK;             // bf16 elements of one operand tile of a stage
 constexpr int STAGE = 2 * OP;            // A tile, then W tile
 }  // namespace dma
 
-__device__ __forceinline__ int dma_swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
+__device__ __forceinline__ int dma_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 __device__ __forceinline__ unsigned int uniform(unsigned int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -489,8 +486,8 @@ __device__ __forceinline__ void copy_to_lds_4(unsigned int lds_base, const u4v &
 template <bool BIAS>
 __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
 {
-    constexpr int BM = dma::BM, BN = dma::BN, BK = dma::BK, STAGES = dma::STAGES, OP = dma::OP, STAGE = dma::STAGE;
-    __shared__ __attribute__((aligned(16))) unsigned short s_op[STAGES][STAGE];
+    constexpr int BM = dma::BM, BN = dma::BN, BK = dma::BK, OP = dma::OP, STAGE = dma::STAGE;
+    __shared__ __attribute__((aligned(16))) unsigned short s_op[2][STAGE];
     __shared__ __attribute__((aligned(16))) unsigned short s_epi[8][32 * 32];
     __shared__ __attribute__((aligned(16))) float s_bias[4][8][64];
     __shared__ int s_ring[8];
@@ -531,11 +528,12 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
         return t;
     };
 
-    // ---- the copying side: tile number ln of this workgroup, k-step lks of it
+    // ---- the copying side: tile number ln of this workgroup, k-step lks of it.  A wave copies rows
+    //      32 w .. 32 w + 31 of both operand tiles, eight rows (eight lanes each) per instruction.
     const unsigned int lds_op = lds_address(&s_op[0][0]);
-    const int lrow = lane >> 2, lchunk = (lane & 3) ^ dma_swz(lrow);          // row within 16, k-chunk fetched
+    const int lrow = lane >> 3;
     u4v ra, rb, rbias;
-    unsigned int va[2], vb[2], vbias = 0u;
+    unsigned int va[4], vb[4], vbias = 0u;
     int ln = 0, lks = 0;
     long long seg_base = 0;                // element offset of the current k-segment in a row of A
     int kin = 0;                           // k within the segment
@@ -544,12 +542,13 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
         ra = rsrc_words(t.A + (long long)t.m0 * a.lda);
         rb = rsrc_words(t.Bw + (long long)t.n0 * a.ldb);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < 4; ++j) {
             // rows past the end read the last row (valid memory); their products are never stored
-            const int row = 32 * w + 16 * j + lrow;
+            const int row = 32 * w + 8 * j + lrow;
+            const unsigned int chunk = (unsigned int)((lane & 7) ^ dma_swz(8 * j + lrow));
             const int gm = min(t.m0 + row, a.M - 1) - t.m0, gn = min(t.n0 + row, a.N - 1) - t.n0;
-            va[j] = (unsigned int)gm * (unsigned int)a.lda * 2u + (unsigned int)lchunk * 16u;
-            vb[j] = (unsigned int)gn * (unsigned int)a.ldb * 2u + (unsigned int)lchunk * 16u;
+            va[j] = (unsigned int)gm * (unsigned int)a.lda * 2u + chunk * 16u;
+            vb[j] = (unsigned int)gn * (unsigned int)a.ldb * 2u + chunk * 16u;
         }
         if (BIAS) {
             rbias = rsrc_words(a.bias + t.coff);
@@ -573,7 +572,7 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
     // the copies of the next step in stream order, into stage `buf`
     auto issue = [&](int buf) {
         if (lks == nk) {
-            const int t = (int)uniform((unsigned int)s_ring[(ln + 1) & 7]);      // published at least a barrier ago
+            const int t = (int)uniform((unsigned int)s_ring[(ln + 1) & 7]);      // written at least a barrier ago
             if (t >= n_local) {
                 l_end = true;
                 return;
@@ -589,9 +588,9 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
         const unsigned int soa = (unsigned int)((seg_base + kin) * 2), sob = (unsigned int)(lks * BK) * 2u;
         const unsigned int dst = lds_op + (unsigned int)buf * (STAGE * 2u) + (unsigned int)(32 * w) * (BK * 2u);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            copy_to_lds_16(dst + (unsigned int)j * (16u * BK * 2u), ra, va[j], soa);
-            copy_to_lds_16(dst + OP * 2u + (unsigned int)j * (16u * BK * 2u), rb, vb[j], sob);
+        for (int j = 0; j < 4; ++j) {
+            copy_to_lds_16(dst + (unsigned int)j * (8u * BK * 2u), ra, va[j], soa);
+            copy_to_lds_16(dst + OP * 2u + (unsigned int)j * (8u * BK * 2u), rb, vb[j], sob);
         }
         ++lks;
         kin += BK;
@@ -602,16 +601,16 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
     };
 
     // ---- the multiplying side
-    // byte offset of this lane's fragment piece within a 32-row block, for k 0..15 and k 16..31
-    unsigned int fo[2];
+    // byte offset of this lane's fragment piece within a 32-row block, for the four 16-k rounds of a step
+    unsigned int fo[4];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) fo[kb] = (unsigned int)l32 * 64u + (unsigned int)((2 * kb + half) ^ dma_swz(l32)) * 16u;
+    for (int kb = 0; kb < 4; ++kb) fo[kb] = (unsigned int)l32 * 128u + (unsigned int)((2 * kb + half) ^ dma_swz(l32)) * 16u;
     auto read_frags = [&](int buf, int kb, bf8v (&fa)[4], bf8v (&fw)[2]) {
         const char *base = reinterpret_cast<const char *>(&s_op[buf][0]) + fo[kb];
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) fa[mi] = *reinterpret_cast<const bf8v *>(base + (128 * wm + 32 * mi) * 64);
+        for (int mi = 0; mi < 4; ++mi) fa[mi] = *reinterpret_cast<const bf8v *>(base + (128 * wm + 32 * mi) * (BK * 2));
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) fw[ni] = *reinterpret_cast<const bf8v *>(base + OP * 2 + (64 * wn + 32 * ni) * 64);
+        for (int ni = 0; ni < 2; ++ni) fw[ni] = *reinterpret_cast<const bf8v *>(base + OP * 2 + (64 * wn + 32 * ni) * (BK * 2));
     };
     f16v acc[2][4];
     auto clear_acc = [&]() {
@@ -635,7 +634,8 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
     int cn = 0, cks = 0;
     auto epilogue = [&]() {
         // 32 x 32 blocks through this wave's LDS patch, so that global stores are 64-byte row pieces;
-        // 16-byte chunk c of row r sits at chunk position c ^ (r / 4 % 4)
+        // 16-byte chunk c of row r sits at chunk position c ^ (r / 4 % 4).  Rows and columns past the end
+        // fall outside the buffer descriptor and are dropped.
         unsigned short *stage = &s_epi[w][0];
         const int rows_here = a.M - (ct.m0 + 128 * wm);                   // valid rows of this wave's part (may be <= 0)
         const bool cols_here = ct.n0 + 64 * wn < a.N;                     // N is a multiple of 64: all 64 columns or none
@@ -666,26 +666,34 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
             }
     };
 
-    // ---- prologue: four steps on their way, the first one landed
+    // ---- prologue: two steps on their way, the first one landed
     point_at(ct);
-    issue(0); issue(1); issue(2); issue(3);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    issue(0);
+    issue(1);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // the eight copies of the second step may be outstanding
     asm volatile("s_barrier" ::: "memory");
     bf8v fa0[4], fw0[2], fa1[4], fw1[2];
     read_frags(0, 0, fa0, fw0);
     clear_acc();
 
-    for (int t = 0;; ++t) {
-        const int buf = t & 3;
+    for (int T = 0;; ++T) {
+        const int buf = T & 1;
         read_frags(buf, 1, fa1, fw1);
         __builtin_amdgcn_sched_barrier(0);
         multiply(fa0, fw0);
         __builtin_amdgcn_sched_barrier(0);
-        // own copies of step t + 1 have landed (see "waits" above)
-        if (l_end) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        read_frags((t + 1) & 3, 0, fa0, fw0);
+        read_frags(buf, 2, fa0, fw0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(buf, 3, fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa0, fw0);
+        __builtin_amdgcn_sched_barrier(0);
+        // own copies of step T + 1 have landed, own reads of this stage are done; after the barrier
+        // everybody's
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        read_frags(buf ^ 1, 0, fa0, fw0);
         if (!l_end) issue(buf);
         __builtin_amdgcn_sched_barrier(0);
         multiply(fa1, fw1);
@@ -974,11 +982,11 @@ template <typename AT, typename CT> hipError_t launch_nt(GemmArgs &g, hipStream_
     return hipGetLastError();
 }
 
-// the copy-to-LDS kernel: bf16 storage, at least four 32-k steps per tile, k-segments in whole steps, row
+// the copy-to-LDS kernel: bf16 storage, at least two 64-k steps per tile, k-segments in whole steps, row
 // offsets of a 256-row tile within 32 bits
 bool nt_dma_ok(const GemmArgs &g)
 {
-    return g.K >= 4 * dma::BK && g.K % dma::BK == 0 && g.kseg % dma::BK == 0 && g.N % 64 == 0 &&
+    return g.K >= 2 * dma::BK && g.K % dma::BK == 0 && g.kseg % dma::BK == 0 && g.N % 64 == 0 &&
            g.lda < (1 << 22) && g.ldb < (1 << 22) && g.ldc < (1 << 22) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.ldc % 8 == 0;
 }
 
