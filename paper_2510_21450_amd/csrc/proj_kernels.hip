@@ -439,7 +439,10 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_nt_kernel(const GemmArgs a)
 //   waits    the copies are issued from inline assembly, so the compiler neither knows nor
 //            waits for them; at the one wait of a step the copies of step T + 1 are the only
 //            loads the wave has outstanding, so the kernel waits for "no memory operation
-//            outstanding" (the stores of a finished output tile included, once per tile).
+//            outstanding", or for "at most sixteen" when the sixteen stores of an output tile
+//            were issued after those copies: vector-memory operations of a wave complete in
+//            issue order on this architecture (its single counter is used that way by every
+//            compiled kernel), and waiting for the stores to drain cost a tenth of the time.
 //   tiles    drawn from the per-XCD counters like above, a few consecutive numbers per draw
 //            (the compiler waits for the atomic's result with every copy in flight, which
 //            stalls the drawing wave; per draw, not per tile), and put into the ring one tile
@@ -632,33 +635,50 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
     };
     Tile ct = tile_of(first);
     int cn = 0, cks = 0;
+    bool stores_behind = false;            // an output tile was stored after the copies the next wait is for
     auto epilogue = [&]() {
-        // 32 x 32 blocks through this wave's LDS patch, so that global stores are 64-byte row pieces;
-        // 16-byte chunk c of row r sits at chunk position c ^ (r / 4 % 4).  Rows and columns past the end
-        // fall outside the buffer descriptor and are dropped.
+        // 16 rows x 64 columns at a time through this wave's LDS patch (2 KB), so that a global store
+        // instruction writes eight whole 128-byte lines; 16-byte chunk c of patch row r sits at chunk
+        // position c ^ (r % 8).  Rows and columns past the end fall outside the buffer descriptor and are
+        // dropped, so the number of store instructions never depends on the data: sixteen.
         unsigned short *stage = &s_epi[w][0];
         const int rows_here = a.M - (ct.m0 + 128 * wm);                   // valid rows of this wave's part (may be <= 0)
         const bool cols_here = ct.n0 + 64 * wn < a.N;                     // N is a multiple of 64: all 64 columns or none
         unsigned short *C = static_cast<unsigned short *>(a.C) + ct.coff + (long long)(ct.m0 + 128 * wm) * a.ldc + ct.n0 + 64 * wn;
         const long long valid = (rows_here > 0 && cols_here) ? (long long)(min(rows_here, 128) - 1) * a.ldc * 2 + 128 : 0;
         const buf_rsrc rc = __builtin_amdgcn_make_buffer_rsrc(C, 0, (int)valid, 0x27000);
+        const int r16 = l32 & 15;
+        // this lane's bias values, read once: between the patch writes below the compiler keeps LDS
+        // accesses in order, and every read would wait out the LDS latency by itself
+        f4v bias4[2][4];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                bias4[ni][q] = BIAS ? *reinterpret_cast<const f4v *>(&s_bias[cn & 3][w][32 * ni + 8 * q + 4 * half]) : zero;
+            }
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
+            for (int ph = 0; ph < 2; ++ph) {                              // rows 16 ph .. 16 ph + 15 of the 32-row block
+                if ((l32 >> 4) == ph) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
-                    if (BIAS) o += *reinterpret_cast<const f4v *>(&s_bias[cn & 3][w][32 * ni + 8 * q + 4 * half]);
-                    store4(stage + l32 * 32 + (q ^ ((l32 >> 2) & 3)) * 8 + 4 * half, o);
+                    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+                            if (BIAS) o += bias4[ni][q];
+                            store4(stage + r16 * 64 + ((4 * ni + q) ^ (r16 & 7)) * 8 + 4 * half, o);
+                        }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int it = 0; it < 2; ++it) {
-                    const int r = 16 * it + (lane >> 2), cc = lane & 3;
-                    const u4v v = *reinterpret_cast<const u4v *>(stage + r * 32 + (cc ^ ((r >> 2) & 3)) * 8);
-                    const unsigned int off = (unsigned int)(32 * mi + r) * (unsigned int)a.ldc * 2u + (unsigned int)(32 * ni + 8 * cc) * 2u;
+                    const int r = 8 * it + (lane >> 3), cc = lane & 7;
+                    const u4v v = *reinterpret_cast<const u4v *>(stage + r * 64 + (cc ^ (r & 7)) * 8);
+                    const unsigned int off = (unsigned int)(32 * mi + 16 * ph + r) * (unsigned int)a.ldc * 2u + (unsigned int)cc * 16u;
                     __builtin_amdgcn_raw_buffer_store_b128(v, rc, off, 0, 0);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -691,8 +711,10 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
         multiply(fa0, fw0);
         __builtin_amdgcn_sched_barrier(0);
         // own copies of step T + 1 have landed, own reads of this stage are done; after the barrier
-        // everybody's
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // everybody's.  Behind those copies the wave has issued nothing, or the sixteen stores of an output tile.
+        if (stores_behind) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        stores_behind = false;
         read_frags(buf ^ 1, 0, fa0, fw0);
         if (!l_end) issue(buf);
         __builtin_amdgcn_sched_barrier(0);
@@ -700,6 +722,7 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
         __builtin_amdgcn_sched_barrier(0);
         if (++cks == nk) {
             epilogue();
+            stores_behind = true;
             clear_acc();
             cks = 0;
             const int nt = (int)uniform((unsigned int)s_ring[++cn & 7]);
