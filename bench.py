@@ -148,6 +148,31 @@ class Run:
         return (time.perf_counter() - t0) * 1e3 / steps
 
 
+PROJ_HEADS = 4
+
+
+def projection_applies(w):
+    return w.cell != "tanh_dense" and w.H % (64 * PROJ_HEADS) == 0
+
+
+def projection_calls(run):
+    """Forward and backward of the input projection on the workload's shapes (four heads); the tensors
+    stay alive with the returned closures."""
+    P, torch, w = run.P, run.torch, run.w
+    u = run.d["u"]
+    G, heads = run.G, PROJ_HEADS
+    dh = w.H // heads
+    xin = torch.randn((w.B, w.L, w.H), device="cuda").to(u.dtype)
+    Wx = torch.randn((G, w.H, dh), device="cuda") / dh ** 0.5
+    bx = torch.randn((G, w.H), device="cuda")
+    ws_p = torch.empty(P.input_projection_workspace_bytes(u.dtype, w.B, w.L, w.H, G, heads, True),
+                       dtype=torch.uint8, device="cuda")
+    u_p = torch.empty_like(u)
+    pf = lambda: P.input_projection(xin, Wx, bx, n_heads=heads, workspace=ws_p, out=u_p)
+    pb = lambda: P.input_projection_backward(xin, Wx, u_p, n_heads=heads, workspace=ws_p)
+    return pf, pb, dh
+
+
 def kernel_figures(run, reps, counters):
     """Per-kernel timings of one workload (device events on the launch stream) and its roofline record."""
     P, torch, w, N = run.P, run.torch, run.w, run.N
@@ -314,30 +339,28 @@ def headline_extras(run, rec, reps):
     bpe = (run.G + run.S) * u.element_size()
     rec["residual_norm"] = {"value": float(rn_out.cpu()), "ms": t_rn, "bytes_per_elt": bpe,
                             "gbs": bpe * N / (t_rn * 1e-3) / 1e9}
-    if w.cell != "tanh_dense" and w.H % 256 == 0:
+    if projection_applies(w):
         # not part of the timed step: the input projection u = Bx + b in front of the solve and its
         # derivatives behind the backward pass, four heads (the paper's 400M .. 7B models), same shapes
-        G, heads = run.G, 4
-        dh = w.H // heads
-        xin = torch.randn((w.B, w.L, w.H), device="cuda").to(u.dtype)
-        Wx = torch.randn((G, w.H, dh), device="cuda") / dh ** 0.5
-        bx = torch.randn((G, w.H), device="cuda")
-        ws_p = torch.empty(P.input_projection_workspace_bytes(u.dtype, w.B, w.L, w.H, G, heads, True),
-                           dtype=torch.uint8, device="cuda")
-        u_p = torch.empty_like(u)
-        pf = lambda: P.input_projection(xin, Wx, bx, n_heads=heads, workspace=ws_p, out=u_p)
-        pb = lambda: P.input_projection_backward(xin, Wx, u_p, n_heads=heads, workspace=ws_p)
+        pf, pb, dh = projection_calls(run)
         pf(); pb()
         t_pf, t_pb = mean(time_events(pf, 5)), mean(time_events(pb, 5))
         es = u.element_size()
+        G = run.G
         flops = 2.0 * N * G * dh
-        rec["input_projection"] = {
-            "n_heads": heads, "arithmetic": "bf16 operands, fp32 accumulation",
-            "fwd_ms": t_pf, "fwd_tflops": flops / (t_pf * 1e-3) / 1e12,
-            "fwd_gbs": (N + N * G) * es / (t_pf * 1e-3) / 1e9,
-            "bwd_ms": t_pb, "bwd_tflops": 2 * flops / (t_pb * 1e-3) / 1e12,
-            "bwd_gbs": (2 * N + 2 * N * G) * es / (t_pb * 1e-3) / 1e9}
-        del xin, u_p, ws_p
+        pr = {"n_heads": PROJ_HEADS, "arithmetic": "bf16 operands, fp32 accumulation",
+              "fwd_ms": t_pf, "fwd_tflops": flops / (t_pf * 1e-3) / 1e12,
+              "fwd_gbs": (N + N * G) * es / (t_pf * 1e-3) / 1e9,
+              "bwd_ms": t_pb, "bwd_tflops": 2 * flops / (t_pb * 1e-3) / 1e12,
+              "bwd_gbs": (2 * N + 2 * N * G) * es / (t_pb * 1e-3) / 1e9}
+        # per kernel, from the committed counter passes (null when they were made from other sources)
+        for cname in ("proj_fwd", "proj_dx", "proj_dw"):
+            c = cnt.get(cname)
+            pr[cname] = None if not c else {
+                "kernel": c["kernel"], "avg_us": c["avg_us"], "traffic_bytes": c["traffic_bytes"],
+                "algorithmic_bytes": c.get("algorithmic_bytes"), "tflops": c.get("tflops"),
+                "mfma_busy_frac": c.get("mfma_busy_frac")}
+        rec["input_projection"] = pr
 
 
 def profile_pass(P, torch, name):
@@ -357,6 +380,11 @@ def profile_pass(P, torch, name):
         for _ in range(3):
             run.forward(tol=-1.0, max_iter=3)
         P.set_fused(True)
+        if projection_applies(w):
+            pf, pb, _ = projection_calls(run)
+            for _ in range(3):
+                pf()
+                pb()
     src = torch.empty(1 << 26, dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty_like(src)
     for _ in range(3):

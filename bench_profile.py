@@ -38,7 +38,8 @@ import bench  # noqa: E402  (constants and the source hash; nothing here touches
 PROFILE_NAMES = {"C2": "newton_fused_gru_f32_C2", "C3": "newton_fused_lstm_f32_C3", "C4": "dense_scan_f32_C4",
                  "C5": "newton_fused_gru_bf16_C5", "X3": "newton_fused_paralstm_f32_X3"}
 ISSUE_COUNTERS = {
-    "diag": "SQ_INSTS_VALU SQ_INSTS_VALU_TRANS_F32 SQ_INSTS_SALU SQ_WAVES SQ_BUSY_CYCLES SQ_ACTIVE_INST_VALU GRBM_GUI_ACTIVE",
+    "diag": "SQ_INSTS_VALU SQ_INSTS_VALU_TRANS_F32 SQ_INSTS_SALU SQ_WAVES SQ_BUSY_CYCLES SQ_ACTIVE_INST_VALU "
+            "SQ_VALU_MFMA_BUSY_CYCLES SQ_LDS_BANK_CONFLICT GRBM_GUI_ACTIVE",
     "dense": "SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F32 SQ_WAVES GRBM_GUI_ACTIVE",
 }
 PASS_TIMEOUT_S = 170
@@ -94,7 +95,11 @@ def classes(kind):
                 "final_sweep": (r"^dense_final_sweep_kernel<false>", "work")}
     return {"dominant": (r"^newton_fused_kernel<", "longest"),          # first block of a solve
             "iter": (r"^newton_iter_kernel<.*false>$", "work"),        # one iteration per launch, from the iterate
-            "bwd": (r"^backward_kernel<", "work")}
+            "bwd": (r"^backward_kernel<", "work"),
+            # the input projection in front of the solve (four heads; not part of the timed step)
+            "proj_fwd": (r"^proj_gemm_nt(_dma)?_kernel<.*true>", "work"),
+            "proj_dx": (r"^proj_gemm_nt(_dma)?_kernel<.*false>", "work"),
+            "proj_dw": (r"^proj_dw_kernel<", "work")}
 
 
 def pick(values, how):
@@ -161,6 +166,19 @@ def profile_config(cfg, outdir):
             if c in rec:
                 rec[c]["algorithmic_bytes"] = a
                 rec[c]["traffic_over_algorithmic"] = rec[c]["traffic_bytes"] / a
+        # projection: bytes of x and u (du, dx); flops of one product set
+        from workloads import cell_dims
+        G = cell_dims(w.cell)[0]
+        es = 2.0 if w.dtype == "bf16" else 4.0
+        pflops = 2.0 * N * G * (w.H // bench.PROJ_HEADS)
+        for c in ("proj_fwd", "proj_dx", "proj_dw"):
+            if c in rec:
+                rec[c]["algorithmic_bytes"] = (N + N * G) * es
+                rec[c]["traffic_over_algorithmic"] = rec[c]["traffic_bytes"] / rec[c]["algorithmic_bytes"]
+                rec[c]["flops"] = pflops
+                rec[c]["tflops"] = pflops / (rec[c]["avg_us"] * 1e-6) / 1e12
+                if "SQ_VALU_MFMA_BUSY_CYCLES" in rec[c] and "GRBM_GUI_ACTIVE" in rec[c]:
+                    rec[c]["mfma_busy_frac"] = rec[c]["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024.0 / (rec[c]["GRBM_GUI_ACTIVE"] / 8.0)
         if "dominant" in rec and "SQ_INSTS_VALU" in rec["dominant"]:
             K0 = min(bench.FUSED_HEAD, w.max_iter)
             rec["dominant"]["valu_insts_per_elt_iter"] = rec["dominant"]["SQ_INSTS_VALU"] * 64.0 / (N * K0)
@@ -189,6 +207,8 @@ def profile_config(cfg, outdir):
             s += (f"; algorithmic {r['algorithmic_bytes'] / 1e6:.1f} MB (x{r['traffic_over_algorithmic']:.3f}); "
                   f"{r['algorithmic_bytes'] / r['avg_us'] / 1e3:.0f} GB/s algorithmic = "
                   f"{r['algorithmic_bytes'] / r['avg_us'] / 1e3 / bench.HBM_PEAK_GBS:.3f} of {bench.HBM_PEAK_GBS:.0f}")
+        if "tflops" in r:
+            s += f"; {r['tflops']:.0f} TFLOP/s = {r['tflops'] / 2500.0:.3f} of the 2500 dense bf16 peak"
         lines.append(s)
         extra = [f"{k} {v:.4g}" for k, v in r.items() if k.startswith(("SQ_", "GRBM_"))]
         if extra:
@@ -200,7 +220,7 @@ def profile_config(cfg, outdir):
         if "valu_insts_per_elt_iter" in r:
             lines.append(f"      {r['valu_insts_per_elt_iter']:.1f} vector instructions per timestep-channel and iteration, "
                          f"{r['trans_insts_per_elt_iter']:.1f} of them transcendental")
-        if "SQ_VALU_MFMA_BUSY_CYCLES" in r and "GRBM_GUI_ACTIVE" in r:
+        if r.get("SQ_VALU_MFMA_BUSY_CYCLES", 0) > 0 and "GRBM_GUI_ACTIVE" in r:
             busy = r["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024.0 / (r["GRBM_GUI_ACTIVE"] / 8.0)
             lines.append(f"      matrix pipes busy {busy:.3f} of the launch's cycles")
     lines.append("")
