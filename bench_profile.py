@@ -89,7 +89,7 @@ def counter_rows(prefix):
 def classes(kind):
     """Launch classes of a workload: name -> (kernel-name pattern, which dispatches of it)."""
     if kind == "dense":
-        return {"dominant": (r"^dense_products_sweep_kernel<false>", "work"),
+        return {"dominant": (r"^dense_products_sweep_kernel<false", "work"),
                 "residual": (r"^dense_residual_kernel", "work"),
                 "carry": (r"^dense_carry_kernel", "work"),
                 "final_sweep": (r"^dense_final_sweep_kernel<false>", "work")}
