@@ -283,7 +283,7 @@ def measure(P, torch, name, steps, warmup, reps, counters, headline):
     return run, rec
 
 
-def headline_extras(run, rec, reps):
+def headline_extras(run, rec, reps, counters):
     """Figures beside the timed step, for the headline workload only."""
     P, torch, w, N = run.P, run.torch, run.w, run.N
     u, params, h0 = run.u, run.params, run.h0
@@ -354,6 +354,7 @@ def headline_extras(run, rec, reps):
               "bwd_ms": t_pb, "bwd_tflops": 2 * flops / (t_pb * 1e-3) / 1e12,
               "bwd_gbs": (2 * N + 2 * N * G) * es / (t_pb * 1e-3) / 1e9}
         # per kernel, from the committed counter passes (null when they were made from other sources)
+        cnt = counters.get(run.name, {})
         for cname in ("proj_fwd", "proj_dx", "proj_dw"):
             c = cnt.get(cname)
             pr[cname] = None if not c else {
@@ -421,7 +422,7 @@ def main():
         note(why)
 
     run, rec = measure(P, torch, args.config, args.steps, args.warmup, 10, counters, True)
-    headline_extras(run, rec, 10)
+    headline_extras(run, rec, 10, counters)
     note("headline workload done")
     # what the runtime reports for this device, beside the published figures the rooflines use
     props = torch.cuda.get_device_properties(0)
