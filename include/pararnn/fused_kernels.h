@@ -59,7 +59,6 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
     constexpr int LPS = kWave / LL, CW = LPS * VEC, NW = SS + 2 * S, T = C * LL * W;
     __shared__ float s_A[W][SS][CW];
     __shared__ float s_b[W][S][CW];
-    __shared__ float s_carry[S][CW];
     __shared__ unsigned int s_maxk[kMaxFused];
     __shared__ unsigned int s_ticket;
 
@@ -310,26 +309,36 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                     }
                 }
                 __syncthreads();
-                float exA[VEC][SS], exB[VEC][S];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    set_identity<S>(exA[v]);
-#pragma unroll
-                    for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
-                }
-                const int upto = w == 0 ? W : w;
-                for (int j = 0; j < upto; ++j) {
+                if (w == 0) {
+                    // ---- workgroup level, by wave 0 alone: it walks the waves' aggregates once, leaving in
+                    //      place of each the composition of the waves before it, and ends with the tile's
+                    //      aggregate.  (Every wave used to compose its own prefix from the same values: W/2
+                    //      steps per wave instead of W in all, on the vector ALUs that bound this kernel.)
+                    float exA[VEC][SS], exB[VEC][S];
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        float Aj[SS], bj[S];
+                        set_identity<S>(exA[v]);
 #pragma unroll
-                        for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
-#pragma unroll
-                        for (int s = 0; s < S; ++s) bj[s] = s_b[j][s][col + v];
-                        push_step<S>(Aj, bj, exA[v], exB[v]);
+                        for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
                     }
-                }
-                if (w == 0) {
+#pragma unroll
+                    for (int j = 0; j < W; ++j) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            float Aj[SS], bj[S];
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) {
+                                Aj[e] = s_A[j][e][col + v];
+                                s_A[j][e][col + v] = exA[v][e];
+                            }
+#pragma unroll
+                            for (int s = 0; s < S; ++s) {
+                                bj[s] = s_b[j][s][col + v];
+                                s_b[j][s][col + v] = exB[v][s];
+                            }
+                            push_step<S>(Aj, bj, exA[v], exB[v]);
+                        }
+                    }
                     // ---- grid level: look-back within this iteration's record slot
                     float tileA[SS][VEC], tileB[S][VEC], carry[S][VEC];
 #pragma unroll
@@ -337,8 +346,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 #pragma unroll
                         for (int e = 0; e < SS; ++e) tileA[e][v] = exA[v][e];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; exB[v][s] = 0.0f; carry[s][v] = 0.0f; }
-                        set_identity<S>(exA[v]);
+                        for (int s = 0; s < S; ++s) { tileB[s][v] = exB[v][s]; carry[s][v] = 0.0f; }
                     }
                     const bool active = seg == 0;
                     const bool has_next = lt + 1 < g.n_lt;
@@ -373,11 +381,23 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                         }
                         publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
                     }
-                    if (active) {
+                    // ---- the delta that enters each wave's first step: its prefix applied to the carry
 #pragma unroll
-                        for (int s = 0; s < S; ++s)
+                    for (int j = 0; j < W; ++j) {
 #pragma unroll
-                            for (int v = 0; v < VEC; ++v) s_carry[s][col + v] = carry[s][v];
+                        for (int v = 0; v < VEC; ++v) {
+                            float Aj[SS], bj[S], cin[S], din[S];
+#pragma unroll
+                            for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
+#pragma unroll
+                            for (int s = 0; s < S; ++s) { bj[s] = s_b[j][s][col + v]; cin[s] = carry[s][v]; }
+                            affine<S>(Aj, cin, bj, din);
+                            // the carry lives in the lanes of segment 0 (the others hold the same prefixes)
+                            if (active) {
+#pragma unroll
+                                for (int s = 0; s < S; ++s) s_b[j][s][col + v] = din[s];
+                            }
+                        }
                     }
                 }
                 __syncthreads();
@@ -388,10 +408,9 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                     constexpr bool kG = decltype(gd)::value;
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        float cin[S], din[S];
+                        float din[S];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) cin[s] = s_carry[s][col + v];
-                        affine<S>(exA[v], cin, exB[v], din);
+                        for (int s = 0; s < S; ++s) din[s] = s_b[w][s][col + v];
                         if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
 #pragma unroll
                         for (int s = 0; s < S; ++s) hprev[s][v] += din[s];
@@ -416,7 +435,8 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 }
                 const unsigned int wave_bits = wave_max_u32(wmax_bits);
                 if (lane == 0) atomicMax(&s_maxk[k - 1], wave_bits);
-                // s_A / s_carry are rewritten only after the next iteration's first barrier
+                // a wave rewrites its own s_A / s_b entries before the next iteration's first barrier; wave 0 reads
+                // them all after it
             }
         };
         if constexpr (S == 1) {
