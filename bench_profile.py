@@ -92,7 +92,7 @@ def classes(kind):
         return {"dominant": (r"^dense_products_sweep_kernel<false", "work"),
                 "residual": (r"^dense_residual_kernel", "work"),
                 "carry": (r"^dense_carry_kernel", "work"),
-                "final_sweep": (r"^dense_final_sweep_kernel<false>", "work")}
+                "final_sweep": (r"^dense_final_sweep_kernel<false", "work")}
     return {"dominant": (r"^newton_fused_kernel<", "longest"),          # first block of a solve
             "iter": (r"^newton_iter_kernel<.*false>$", "work"),        # one iteration per launch, from the iterate
             "bwd": (r"^backward_kernel<", "work"),

@@ -58,6 +58,7 @@ struct DenseArgs {
     float *Ac;           // [B][n_c][64][64] row-major chunk products
     float *bc;           // [B][n_c][64] chunk-local end values
     float *xc;           // [B][n_c][64] delta at each chunk's end
+    float *hend;         // [B][n_c][64] the iterate at each chunk's last step, as it was before this iteration's update (or NULL)
     Ctrl *ctrl;
     int *iters_out;
     float *trace;
@@ -119,7 +120,12 @@ __device__ __forceinline__ void load_w_operand16(const float *W, int w, int n, i
 // mode 0: write d = 1 - F^2 and r = F - h for the current iterate;
 // mode 1: write the initial guess h = tanh(W h0 + u) (App. A);
 // mode 2: write nothing but max |F - h| over all rows to a.norm (no control block is read);
-// mode 3: as mode 0, but d is the diagonal of the Jacobian, (1 - F^2) * W_ii (quasi-Newton).
+// mode 3: as mode 0, but d is the diagonal of the Jacobian, (1 - F^2) * W_ii (quasi-Newton);
+// mode 4: modes 1 and 0 in one pass: the initial guess is written, and the residual and row factors of the
+//         first iteration are formed from it.  The guess of the row before, which the residual needs, is
+//         recomputed rather than read (it is tanh(W h0 + u_{l-1}), and W h0 is one product per row's sequence,
+//         shared with the row's own guess): same bits as the two launches, one pass over u instead of two and
+//         none over h.
 __device__ __forceinline__ void residual_body(const DenseArgs &a, int mode)
 {
     float nmax = 0.0f;
@@ -137,11 +143,70 @@ __device__ __forceinline__ void residual_body(const DenseArgs &a, int mode)
     float wa[4][4];
     load_w_operand16(a.W, w, n, g, wa);
     const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    __shared__ f4v s_c[4][64];
     for (size_t item = blockIdx.x; item < n_items; item += gridDim.x) {
         const size_t row = item * 16 + n;
         const bool ok = row < rows;
         const int l = ok ? (int)(row % a.L) : 0;
         const size_t b = ok ? row / a.L : 0;
+        if (mode == 4) {
+            // W h0 of this row's sequence: own part (channels chn ..) and, through LDS, every wave's part
+            f4v cbo = zero, cbk[4] = {zero, zero, zero, zero};
+            f4v h0k[4] = {zero, zero, zero, zero};
+            if (a.h0) {
+#pragma unroll
+                for (int ww = 0; ww < 4; ++ww)
+                    if (ok) h0k[ww] = *reinterpret_cast<const f4v *>(a.h0 + b * DH + 16 * ww + 4 * g);
+                f4v c0 = zero, c1 = zero;
+#pragma unroll
+                for (int ww = 0; ww < 4; ww += 2)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        c0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww][v], h0k[ww][v], c0, 0, 0, 0);
+                        c1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww + 1][v], h0k[ww + 1][v], c1, 0, 0, 0);
+                    }
+                cbo = c0 + c1;
+                __syncthreads();                      // the previous item's reads of s_c
+                s_c[w][lane] = cbo;
+                __syncthreads();
+#pragma unroll
+                for (int ww = 0; ww < 4; ++ww) cbk[ww] = s_c[ww][lane];
+            }
+            f4v uv = zero;
+            f4v xb[4] = {zero, zero, zero, zero};
+            if (ok) {
+                uv = *reinterpret_cast<const f4v *>(a.u + row * DH + chn);
+                if (l == 0) {
+#pragma unroll
+                    for (int ww = 0; ww < 4; ++ww) xb[ww] = h0k[ww];
+                } else {
+#pragma unroll
+                    for (int ww = 0; ww < 4; ++ww) {
+                        const f4v y = cbk[ww] + *reinterpret_cast<const f4v *>(a.u + (row - 1) * DH + 16 * ww + 4 * g);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) xb[ww][v] = fast_tanh(y[v]);
+                    }
+                }
+            }
+            f4v acc0 = zero, acc1 = zero;
+#pragma unroll
+            for (int ww = 0; ww < 4; ww += 2)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww][v], xb[ww][v], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww + 1][v], xb[ww + 1][v], acc1, 0, 0, 0);
+                }
+            if (ok) {
+                const f4v y0 = cbo + uv, y = acc0 + acc1 + uv;
+                f4v hv, F;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) { hv[v] = fast_tanh(y0[v]); F[v] = fast_tanh(y[v]); }
+                *reinterpret_cast<f4v *>(a.h + row * DH + chn) = hv;
+                *reinterpret_cast<f4v *>(a.d + row * DH + chn) = (1.0f - F * F) * wdiag;
+                *reinterpret_cast<f4v *>(a.r + row * DH + chn) = F - hv;
+            }
+            continue;
+        }
         // previous state of this row: h0 (or zero) at l = 0 and for the guess, else the row before
         const float *hp = nullptr;
         if (ok) {
@@ -476,9 +541,20 @@ __device__ __forceinline__ void finish_iteration(const DenseArgs &a, float block
 // BWD: the backward recurrence (r_l = d_l * g_l; the final sweep writes mu = dL/du and nothing else).
 // LATE_H: the iterate's rows are read after the chain instead of before it (48 fewer registers held
 // through the chain; the one-launch solve shares its register budget with the chunk products).
-template <int FINAL, bool BWD, bool LATE_H = false>
+//
+// Forward solves: the delta of a chunk's last step exists twice, as the end of this chain and as the carried
+// value x_c that every later chunk started from; the update takes x_c, so that the iterate at a chunk's last
+// step is (old value + x_c), which the next chunk's column can form by itself.  The chunk-local sweep leaves the
+// old values of those steps in a.hend for that purpose (the final sweeps of neighbouring chunks run side by side
+// and update h in place).
+// NEXT (final forward sweep): the residual and row factors of the NEXT iteration are formed here, from the
+// new rows this column holds, instead of by a launch of their own that would read the iterate again:
+// row l needs the new h_{l-1} (for l = ls: hend + x_{c-1}, or h0) and the new h_l.  Same products in the same
+// order as dense_residual_kernel, so both give the same bits.
+template <int FINAL, bool BWD, bool LATE_H = false, bool NEXT = false>
 __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
 {
+    static_assert(!NEXT || (FINAL && !BWD && !LATE_H), "the next residual belongs to the forward final sweep");
     __shared__ f4v s_x[2][4][64];
     __shared__ float s_max[4];
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -507,6 +583,14 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
     }
     f4v x = zero;
     if (FINAL && ok && c > 0) x = *reinterpret_cast<const f4v *>(a.xc + ((size_t)b * a.n_c + (c - 1)) * DH + chn);
+    // forward: the carried delta of this chunk's last step, and (chunk-local sweep) the iterate there
+    const bool carried_end = !BWD && a.hend && ok && c < a.n_c - 1;
+    f4v xend = zero;
+    if (FINAL && carried_end) xend = *reinterpret_cast<const f4v *>(a.xc + ((size_t)b * a.n_c + c) * DH + chn);
+    if (!FINAL && carried_end)
+        *reinterpret_cast<f4v *>(a.hend + ((size_t)b * a.n_c + c) * DH + chn) =
+            *reinterpret_cast<const f4v *>(a.h + ((size_t)b * a.L + ls + CD - 1) * DH + chn);
+    const f4v xstart = x;
     s_x[0][w][lane] = x;
     lds_barrier();
 #pragma unroll
@@ -540,17 +624,71 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
         }
         return;
     }
+    if (carried_end) rv[CD - 1] = xend;
     float wmax = 0.0f;
+    if constexpr (NEXT) {
+        // u of this column's rows (the registers of the row factors are free now)
+        f4v uv[CD];
 #pragma unroll
-    for (int i = 0; i < CD; ++i) {
-        const int l = ls + i;
-        if (ok && l < a.L) {
-            f4v *hp = reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn);
-            if (LATE_H) *hp = *hp + rv[i];
-            else *hp = hv[i] + rv[i];
+        for (int i = 0; i < CD; ++i)
+            uv[i] = *reinterpret_cast<const f4v *>(a.u + ((size_t)b * a.L + min(ls + i, a.L - 1)) * DH + chn);
+        // the state in front of the column's first row
+        f4v hprev = zero;
+        if (ok) {
+            if (c == 0) {
+                if (a.h0) hprev = *reinterpret_cast<const f4v *>(a.h0 + (size_t)b * DH + chn);
+            } else {
+                hprev = *reinterpret_cast<const f4v *>(a.hend + ((size_t)b * a.n_c + (c - 1)) * DH + chn) + xstart;
+            }
         }
+        // every wave needs all 64 values of each state: slot i holds the state in front of row i
+        __shared__ f4v s_h[CD][4][64];
+        s_h[0][w][lane] = hprev;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
+        for (int i = 0; i < CD; ++i) {
+            const int l = ls + i;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
+            rv[i] = hv[i] + rv[i];                                  // the new row
+            if (ok && l < a.L) *reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn) = rv[i];
+            if (i + 1 < CD) s_h[i + 1][w][lane] = rv[i];
+        }
+        lds_barrier();
+#pragma unroll
+        for (int i = 0; i < CD; ++i) {
+            const int l = ls + i;
+            f4v acc0 = zero, acc1 = zero;
+#pragma unroll
+            for (int ww = 0; ww < 4; ww += 2) {
+                const f4v xa = s_h[i][ww][lane], xb = s_h[i][ww + 1][lane];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww][v], xa[v], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[ww + 1][v], xb[v], acc1, 0, 0, 0);
+                }
+            }
+            if (ok && l < a.L) {
+                const f4v y = acc0 + acc1 + uv[i];
+                f4v F;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) F[v] = fast_tanh(y[v]);
+                const size_t off = ((size_t)b * a.L + l) * DH + chn;
+                *reinterpret_cast<f4v *>(a.d + off) = (1.0f - F * F);
+                *reinterpret_cast<f4v *>(a.r + off) = F - rv[i];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < CD; ++i) {
+            const int l = ls + i;
+            if (ok && l < a.L) {
+                f4v *hp = reinterpret_cast<f4v *>(a.h + ((size_t)b * a.L + l) * DH + chn);
+                if (LATE_H) *hp = *hp + rv[i];
+                else *hp = hv[i] + rv[i];
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wmax = nanmax(wmax, __builtin_fabsf(rv[i][v]));
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) wmax = nanmax(wmax, __shfl_xor(wmax, off, 64));
@@ -563,12 +701,13 @@ __device__ __forceinline__ void sweep_body(const DenseArgs &a, int block)
     }
 }
 
-// The final sweep of an iteration (or of the backward pass).
-template <bool BWD>
+// The final sweep of an iteration (or of the backward pass).  NEXT: it also leaves the residual and the row
+// factors of the next iteration.
+template <bool BWD, bool NEXT = false>
 __global__ __launch_bounds__(256) void dense_final_sweep_kernel(const DenseArgs a)
 {
     if (a.ctrl->stop) return;
-    sweep_body<1, BWD>(a, blockIdx.x);
+    sweep_body<1, BWD, false, NEXT>(a, blockIdx.x);
 }
 
 // Chunk products and chunk-local sweeps need only d and r, and nothing of each
@@ -892,7 +1031,7 @@ __global__ __launch_bounds__(256) void dense_dw_kernel(const DenseArgs a, float 
 
 size_t r256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct DenseLayout { size_t off_d, off_r, off_A, off_b, off_x, total; int n_c; };
+struct DenseLayout { size_t off_d, off_r, off_A, off_b, off_x, off_hend, total; int n_c; };
 
 DenseLayout dense_layout(int B, int L)
 {
@@ -904,6 +1043,7 @@ DenseLayout dense_layout(int B, int L)
     lo.off_A = off; off += r256((size_t)B * lo.n_c * DH * DH * 4);
     lo.off_b = off; off += r256((size_t)B * lo.n_c * DH * 4);
     lo.off_x = off; off += r256((size_t)B * lo.n_c * DH * 4);
+    lo.off_hend = off; off += r256((size_t)B * lo.n_c * DH * 4);
     lo.total = off;
     return lo;
 }
@@ -1057,6 +1197,7 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
     a.Ac = reinterpret_cast<float *>(ws + lo.off_A);
     a.bc = reinterpret_cast<float *>(ws + lo.off_b);
     a.xc = reinterpret_cast<float *>(ws + lo.off_x);
+    a.hend = reinterpret_cast<float *>(ws + lo.off_hend);
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
     a.iters_out = iters; a.trace = delta_trace;
     a.B = B; a.L = L; a.n_c = lo.n_c; a.k = 0; a.max_iter = max_iter; a.tol = tol;
@@ -1105,13 +1246,16 @@ int dense_forward(int dtype, const float *W, const void *u, const void *h0, int 
                      : (g_dense_one_launch == 0 || tol < 0.0f) ? max_iter
                      : (max_iter < kDenseHead ? max_iter : kDenseHead);
     // the initial guess (all a solve of zero iterations returns); the persistent launch makes its own when it starts the solve
-    if (head > 0 || max_iter == 0) hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
+    if (max_iter == 0) hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 1);
     for (int k = 1; k <= head; ++k) {
         a.k = k;
-        hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 0);
+        // the initial guess and the residual of iteration 1 in one launch; the final sweep of an iteration
+        // leaves the next one's
+        if (k == 1) hipLaunchKernelGGL(dense_residual_kernel, dim3(res_blocks), dim3(256), 0, st, a, 4);
         launch_products_sweep(g_dense_products, n_sweep + n_prod_blocks, st, a, n_sweep);
         hipLaunchKernelGGL(dense_carry_kernel, dim3(B), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(dense_final_sweep_kernel<false>, dim3(n_sweep), dim3(256), 0, st, a);
+        if (k < max_iter) hipLaunchKernelGGL((dense_final_sweep_kernel<false, true>), dim3(n_sweep), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((dense_final_sweep_kernel<false, false>), dim3(n_sweep), dim3(256), 0, st, a);
     }
     if (head < max_iter) {
         a.spin_limit = settings().spin_limit;
