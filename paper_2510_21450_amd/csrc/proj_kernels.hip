@@ -741,7 +741,7 @@ struct DwArgs {
     float *dbpart;         // [S][G][H] partial sums of dbias, or NULL
     int M, H, G, heads, dh;
     int S, rows_per_split; // rows_per_split a multiple of BK
-    int tiles;             // 128-wide tiles per dh
+    int tiles;             // tiles per dh (128 wide; 256 wide for the copy-to-LDS kernel)
     int n_blocks, per_xcd; // tiles^2 * G * heads * S workgroups, an eighth of them (rounded up)
 };
 
@@ -918,6 +918,195 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
     }
 }
 
+// ------------------------------- dWx and dbias, bf16 operands copied straight into LDS
+// The same sums for bf16 storage and wide heads: 256 x 256 outputs per workgroup of eight waves
+// (2 x 4; a wave owns 128 output channels i x 64 input channels j), 64 rows m per step, operand rows
+// copied from memory to LDS as they are, 512 bytes of du and of x per row.
+//
+//   LDS      two stages of (64 + 64) rows x 512 bytes = 128 KB.  A copy instruction moves two rows;
+//            16-byte chunk c of row r lies at position c ^ 2 (r % 4) of its row.
+//   reads    the products need, per lane, eight consecutive m of one channel: a column of the
+//            stage.  ds_read_b64_tr_b16 hands a lane four of them: the sixteen lanes of a group read
+//            8 bytes each, four lanes per row over four rows (32 bytes = 16 channels of a row), and
+//            lane i of the group receives the i-th channel of the four rows.  With the chunk
+//            positions above the four rows of a group lie in four different quarters of the banks.
+//   rows     past the end of a range lie beyond the buffer descriptor, which is rebuilt for every
+//            step (base at the step's first row, extent to the end of the range): the copy writes
+//            zeros for them, so they add nothing.  Tile columns past dh hold whatever follows in the
+//            row (a neighbouring head or gate; zeros past the end of the tensor) and their sums are
+//            not stored.
+//   dbias    the column sums of du come from one more product per round, with an operand of ones,
+//            in the tiles of the first column block; the wave with wn = mi does block mi.
+namespace dwd {
+constexpr int BT = 256, BK = 64;
+constexpr int OP = BK * BT;              // bf16 elements of one operand's rows of a step
+constexpr int STAGE = 2 * OP;            // du rows, then x rows
+}  // namespace dwd
+
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef short s8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s4v *lds_s4v_ptr;
+
+__global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
+{
+    constexpr int BT = dwd::BT, BK = dwd::BK, OP = dwd::OP, STAGE = dwd::STAGE;
+    __shared__ __attribute__((aligned(16))) unsigned short s_op[2][STAGE];
+    int id = (int)(blockIdx.x & 7) * a.per_xcd + (int)(blockIdx.x >> 3);
+    if (id >= a.n_blocks) return;
+    const int tj = id % a.tiles; id /= a.tiles;
+    const int ti = id % a.tiles; id /= a.tiles;
+    const int g = id % a.G; id /= a.G;
+    const int head = id % a.heads;
+    const int s = id / a.heads;
+    const int i0 = ti * BT, j0 = tj * BT;
+    const int m_begin = s * a.rows_per_split;
+    const int rows = min(a.M, m_begin + a.rows_per_split) - m_begin;
+    const int nk = (rows + BK - 1) / BK;
+    if (nk <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, w = (int)uniform((unsigned int)tid >> 6), wm = w >> 2, wn = w & 3;
+    const int half = lane >> 5, l32 = lane & 31;
+    const bool do_db = a.dbpart && tj == 0;
+
+    // ---- the copying side: a wave copies rows 8 w .. 8 w + 7 of both operands' steps, two rows per instruction
+    const long long ld_du = (long long)a.G * a.H, ld_x = a.H;
+    const long long col_du = (long long)g * a.H + head * a.dh + i0, col_x = (long long)head * a.dh + j0;
+    unsigned long long p_du = (unsigned long long)(static_cast<const unsigned short *>(a.du) + (long long)m_begin * ld_du + col_du);
+    unsigned long long p_x = (unsigned long long)(static_cast<const unsigned short *>(a.x) + (long long)m_begin * ld_x + col_x);
+    // bytes from there that belong to the range: whole rows, and the tile's columns of the last one
+    long long rem_du = ((long long)(rows - 1) * ld_du + min((long long)BT, ld_du - col_du)) * 2;
+    long long rem_x = ((long long)(rows - 1) * ld_x + min((long long)BT, ld_x - col_x)) * 2;
+    unsigned int va[4], vb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * w + 2 * j + (lane >> 5);
+        const unsigned int chunk = (unsigned int)((lane & 31) ^ (2 * (row & 3)));
+        va[j] = (unsigned int)row * (unsigned int)ld_du * 2u + chunk * 16u;
+        vb[j] = (unsigned int)row * (unsigned int)ld_x * 2u + chunk * 16u;
+    }
+    const unsigned int lds_op = lds_address(&s_op[0][0]);
+    auto words = [&](unsigned long long p, long long rem) {
+        const unsigned int n = rem <= 0 ? 0u : rem > 0xffffffffll ? 0xffffffffu : (unsigned int)rem;
+        const u4v r = {uniform((unsigned int)p), uniform((unsigned int)(p >> 32) & 0xffffu), uniform(n), 0x27000u};
+        return r;
+    };
+    auto issue = [&](int buf) {
+        const u4v ra = words(p_du, rem_du), rb = words(p_x, rem_x);
+        const unsigned int dst = lds_op + (unsigned int)buf * (STAGE * 2u) + (unsigned int)(8 * w) * (BT * 2u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            copy_to_lds_16(dst + (unsigned int)j * (2u * BT * 2u), ra, va[j], 0u);
+            copy_to_lds_16(dst + OP * 2u + (unsigned int)j * (2u * BT * 2u), rb, vb[j], 0u);
+        }
+        p_du += (unsigned long long)(BK * ld_du * 2); rem_du -= BK * ld_du * 2;
+        p_x += (unsigned long long)(BK * ld_x * 2);   rem_x -= BK * ld_x * 2;
+    };
+
+    // ---- the multiplying side
+    // this lane's place in a transposing read: row rr of the four, the 8 bytes at channel 16 hi + 4 (lane % 4) of
+    // the 32-channel block; the block's first chunk is a multiple of four, so the position of the lane's chunk is
+    // (block chunk) ^ sl, which is a sum for even blocks and for odd ones after taking the 4 out
+    const int rr = (lane & 15) >> 2, sl = (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ (2 * rr);
+    const unsigned int rowpart = (unsigned int)(8 * half + rr) * (BT * 2u) + (unsigned int)(lane & 1) * 8u;
+    unsigned int o_du[2], o_x[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const unsigned int pos = (unsigned int)(par ? (4 ^ sl) : sl) * 16u;
+        o_du[par] = lds_op + rowpart + (unsigned int)(128 * wm) * 2u + pos;
+        o_x[par] = lds_op + OP * 2u + rowpart + (unsigned int)(64 * wn) * 2u + pos;
+    }
+    auto read8 = [&](unsigned int addr) {
+        const s4v q0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(addr));
+        const s4v q1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(addr + 4u * BT * 2u));
+        const s8v t = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf8v, t);
+    };
+    auto read_frags = [&](int buf, int kb, bf8v (&fd)[4], bf8v (&fx)[2]) {
+        const unsigned int base = (unsigned int)buf * (STAGE * 2u) + (unsigned int)(16 * kb) * (BT * 2u);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) fd[mi] = read8(o_du[mi & 1] + base + (unsigned int)(mi >> 1) * 128u);
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj) fx[nj] = read8(o_x[nj] + base);
+    };
+    f16v acc[2][4], accdb;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        accdb[v] = 0.0f;
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) acc[nj][mi][v] = 0.0f;
+    }
+    const __bf16 one = (__bf16)1.0f;
+    const bf8v ones = {one, one, one, one, one, one, one, one};
+    // acc[nj][mi] = (x columns)^T (du columns): a lane owns channel l32 of the du block and, per four
+    // registers, four consecutive channels of x
+    auto multiply = [&](const bf8v (&fd)[4], const bf8v (&fx)[2]) {
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+            for (int nj = 0; nj < 2; ++nj)
+                acc[nj][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[nj], fd[mi], acc[nj][mi], 0, 0, 0);
+            if (do_db && wn == mi) accdb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fd[mi], accdb, 0, 0, 0);
+        }
+    };
+
+    // ---- two steps on their way, the first one landed
+    issue(0);
+    if (nk > 1) {
+        issue(1);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // the eight copies of the second step may be outstanding
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_barrier" ::: "memory");
+    bf8v fd0[4], fx0[2], fd1[4], fx1[2];
+    read_frags(0, 0, fd0, fx0);
+    for (int T = 0; T < nk; ++T) {
+        const int buf = T & 1;
+        read_frags(buf, 1, fd1, fx1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fd0, fx0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(buf, 2, fd0, fx0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fd1, fx1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(buf, 3, fd1, fx1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fd0, fx0);
+        __builtin_amdgcn_sched_barrier(0);
+        // own copies of step T + 1 (the only memory operations outstanding) have landed, own reads of this
+        // stage are done; after the barrier everybody's
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        read_frags(buf ^ 1, 0, fd0, fx0);                  // after the last step: stale rows, not used
+        if (T + 2 < nk) issue(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fd1, fx1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    float *out = a.part + (((long long)s * a.G + g) * a.H + (long long)head * a.dh) * a.dh;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int i = i0 + 128 * wm + 32 * mi + l32;
+        if (i >= a.dh) continue;
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + 64 * wn + 32 * nj + 8 * q + 4 * half;       // dh is a multiple of 4
+                if (j >= a.dh) continue;
+                const f4v o = {acc[nj][mi][4 * q], acc[nj][mi][4 * q + 1], acc[nj][mi][4 * q + 2], acc[nj][mi][4 * q + 3]};
+                *reinterpret_cast<f4v *>(out + (long long)i * a.dh + j) = o;
+            }
+    }
+    if (do_db && half == 0) {
+        // every row of the product with ones holds the column sums
+        const int i = i0 + 128 * wm + 32 * wn + l32;
+        if (i < a.dh) a.dbpart[((long long)s * a.G + g) * a.H + (long long)head * a.dh + i] = accdb[0];
+    }
+}
+
 // ------------------------------------------------------------- weight copies
 // Wb = bf16(Wx), same layout [G][H][dh]
 __global__ __launch_bounds__(256) void proj_wb_kernel(const float *Wx, unsigned short *Wb, size_t n, int *tickets)
@@ -967,9 +1156,38 @@ void dw_split(int M, int base_tiles, int *S, int *rows_per_split)
     *S = (M + rps - 1) / rps;
 }
 
+// The same for the copy-to-LDS kernel, one workgroup per compute unit: the number of ranges whose
+// workgroups fill whole rounds of the device best, at least 16 steps per range.
+void dw_dma_split(int M, int base_tiles, int *S, int *rows_per_split)
+{
+    const int cus = device_cu_count() > 0 ? device_cu_count() : 256;
+    int best = 1;
+    double best_score = -1.0;
+    for (int s = 1; s <= 64; ++s) {
+        if (s > 1 && (M + s - 1) / s < 16 * dwd::BK) break;
+        const long long items = (long long)base_tiles * s, rounds = (items + cus - 1) / cus;
+        // busy share of the rounds, with a bonus for several rounds (their tails even out) that ends at four
+        const double score = (double)items / (double)(rounds * cus) * (rounds >= 4 ? 1.0 : 0.85 + 0.05 * (double)(rounds - 1));
+        if (score > best_score + 1e-9) { best_score = score; best = s; }
+    }
+    int rps = (M + best - 1) / best;
+    rps = (rps + dwd::BK - 1) / dwd::BK * dwd::BK;
+    *rows_per_split = rps;
+    *S = (M + rps - 1) / rps;
+}
+
+// the copy-to-LDS kernel's 256-wide tiles against the 128-wide ones: taken where they cover dh with at most
+// half as much again of idle tile area
+bool dw_dma_shape_ok(int H, int G, int dh)
+{
+    const double t2 = (double)((dh + dwd::BT - 1) / dwd::BT * dwd::BT), t1 = (double)((dh + BM - 1) / BM * BM);
+    return dh % 8 == 0 && H % 8 == 0 && (long long)G * H < (1 << 22) && t2 * t2 <= 1.5 * t1 * t1;
+}
+
 struct ProjLayout {
     size_t off_tickets, off_w, off_part, off_db, total;
     int S, rows_per_split, tiles;
+    int S2, rows_per_split2, tiles2;       // the copy-to-LDS dWx kernel's ranges and 256-wide tiles (S2 = 0: not offered)
 };
 
 ProjLayout proj_layout(int B, int L, int H, int G, int n_heads, int backward)
@@ -982,11 +1200,18 @@ ProjLayout proj_layout(int B, int L, int H, int G, int n_heads, int backward)
     lo.off_w = off; off += r256(nw * sizeof(unsigned short));
     lo.tiles = (dh + BM - 1) / BM;
     lo.S = 0; lo.rows_per_split = 0;
+    lo.S2 = 0; lo.rows_per_split2 = 0; lo.tiles2 = 0;
     lo.off_part = lo.off_db = off;
     if (backward) {
         dw_split(B * L, lo.tiles * lo.tiles * G * n_heads, &lo.S, &lo.rows_per_split);
-        lo.off_part = off; off += r256((size_t)lo.S * nw * sizeof(float));
-        lo.off_db = off;   off += r256((size_t)lo.S * G * H * sizeof(float));
+        // room for either kernel's partial sums, so that the size does not depend on proj_set_dma
+        if (dw_dma_shape_ok(H, G, dh)) {
+            lo.tiles2 = (dh + dwd::BT - 1) / dwd::BT;
+            dw_dma_split(B * L, lo.tiles2 * lo.tiles2 * G * n_heads, &lo.S2, &lo.rows_per_split2);
+        }
+        const size_t s_max = (size_t)(lo.S > lo.S2 ? lo.S : lo.S2);
+        lo.off_part = off; off += r256(s_max * nw * sizeof(float));
+        lo.off_db = off;   off += r256(s_max * G * H * sizeof(float));
     }
     lo.total = off < 256 ? 256 : off;
     return lo;
@@ -1115,15 +1340,19 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         a.part = reinterpret_cast<float *>(ws + lo.off_part);
         a.dbpart = dbias ? reinterpret_cast<float *>(ws + lo.off_db) : nullptr;
         a.M = B * L; a.H = H; a.G = G; a.heads = n_heads; a.dh = dh;
-        a.S = lo.S; a.rows_per_split = lo.rows_per_split; a.tiles = lo.tiles;
-        a.n_blocks = lo.tiles * lo.tiles * n_heads * G * lo.S;
+        const bool copy_kernel = bf && g_proj_dma && lo.S2 > 0;
+        a.S = copy_kernel ? lo.S2 : lo.S;
+        a.rows_per_split = copy_kernel ? lo.rows_per_split2 : lo.rows_per_split;
+        a.tiles = copy_kernel ? lo.tiles2 : lo.tiles;
+        a.n_blocks = a.tiles * a.tiles * n_heads * G * a.S;
         a.per_xcd = (a.n_blocks + 7) / 8;
         const int blocks = 8 * a.per_xcd;
-        if (bf) hipLaunchKernelGGL(proj_dw_kernel<unsigned short>, dim3(blocks), dim3(256), 0, st, a);
+        if (copy_kernel) hipLaunchKernelGGL(proj_dw_dma_kernel, dim3(blocks), dim3(512), 0, st, a);
+        else if (bf) hipLaunchKernelGGL(proj_dw_kernel<unsigned short>, dim3(blocks), dim3(256), 0, st, a);
         else hipLaunchKernelGGL(proj_dw_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return PARARNN_HIP_ERROR;
-        if (launch_param_reduce(a.part, dWx, lo.S, (int)nw, st) != hipSuccess) return PARARNN_HIP_ERROR;
-        if (dbias && launch_param_reduce(a.dbpart, dbias, lo.S, G * H, st) != hipSuccess) return PARARNN_HIP_ERROR;
+        if (launch_param_reduce(a.part, dWx, a.S, (int)nw, st) != hipSuccess) return PARARNN_HIP_ERROR;
+        if (dbias && launch_param_reduce(a.dbpart, dbias, a.S, G * H, st) != hipSuccess) return PARARNN_HIP_ERROR;
     }
     return PARARNN_OK;
 }

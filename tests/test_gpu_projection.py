@@ -157,6 +157,31 @@ def test_projection_many_tiles_per_workgroup(oracle_mod, shape):
     assert float((u.float() - u2.float()).abs().max()) <= 2.0 ** -6 * float(u2.float().abs().max())
 
 
+@pytest.mark.parametrize("shape", [(4, 16384, 256, 3, 1), (2, 9999, 1024, 2, 2)])
+def test_projection_weight_gradients_over_long_row_ranges(oracle_mod, shape):
+    """bf16 storage, heads wide enough for the kernel that copies operand rows straight into LDS: hundreds of
+    64-row steps per workgroup, several row ranges whose partial sums are added afterwards, a last
+    step of 15 rows (M = 19 998), two column tiles per head (dh = 512).  dWx and dbias against the
+    oracle on all rows, and against the register-staged kernel (same products, other summation order)."""
+    import paper_2510_21450_amd as P
+    print(f"projection, weight gradients {shape}", flush=True)
+    B, L, H, G, heads = shape
+    x, Wx, _, du = problem(shape, torch.bfloat16, seed=5700 + H)
+    _, dW, db = P.input_projection_backward(x, Wx, du, n_heads=heads, want_dx=False)
+    torch.cuda.synchronize()
+    _, rdW, rdb = oracle_mod.input_projection_backward(rounded(x), rounded(Wx), rounded(du), heads)
+    assert relerr(f64(dW), rdW) <= 1e-5
+    assert relerr(f64(db), rdb) <= 1e-5
+    try:
+        P.set_staging(False)
+        _, dW2, db2 = P.input_projection_backward(x, Wx, du, n_heads=heads, want_dx=False)
+        torch.cuda.synchronize()
+    finally:
+        P.set_staging(True)
+    assert relerr(f64(dW2), rdW) <= 1e-5 and relerr(f64(db2), rdb) <= 1e-5
+    assert float((dW - dW2).abs().max()) <= 1e-5 * float(dW2.abs().max())
+
+
 def test_projection_refuses_what_it_cannot_do():
     import paper_2510_21450_amd as P
     x = torch.zeros(1, 4, 96, device="cuda")
