@@ -99,7 +99,7 @@ def classes(kind):
             # the input projection in front of the solve (four heads; not part of the timed step)
             "proj_fwd": (r"^proj_gemm_nt(_dma)?_kernel<.*true>", "work"),
             "proj_dx": (r"^proj_gemm_nt(_dma)?_kernel<.*false>", "work"),
-            "proj_dw": (r"^proj_dw_kernel<", "work")}
+            "proj_dw": (r"^proj_dw_(dma_)?kernel", "work")}
 
 
 def pick(values, how):

@@ -951,10 +951,16 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
 {
     constexpr int BT = dwd::BT, BK = dwd::BK, OP = dwd::OP, STAGE = dwd::STAGE;
     __shared__ __attribute__((aligned(16))) unsigned short s_op[2][STAGE];
+    // Workgroups go to the eight XCDs round-robin and an XCD runs 32 of its contiguous range at a
+    // time: the tiles of a (gate, head, range) are numbered in strips of four tile rows, down the strip's columns,
+    // so that 32 consecutive ones cover 4 x 8 tiles (8 x panels, 4 du panels) where a head has that many.
     int id = (int)(blockIdx.x & 7) * a.per_xcd + (int)(blockIdx.x >> 3);
     if (id >= a.n_blocks) return;
-    const int tj = id % a.tiles; id /= a.tiles;
-    const int ti = id % a.tiles; id /= a.tiles;
+    const int per_grid = a.tiles * a.tiles;
+    const int in_grid = id % per_grid; id /= per_grid;
+    const int strip = in_grid / (4 * a.tiles), in_strip = in_grid - strip * 4 * a.tiles;
+    const int hs = min(4, a.tiles - 4 * strip);
+    const int tj = in_strip / hs, ti = 4 * strip + in_strip % hs;
     const int g = id % a.G; id /= a.G;
     const int head = id % a.heads;
     const int s = id / a.heads;
@@ -1156,19 +1162,26 @@ void dw_split(int M, int base_tiles, int *S, int *rows_per_split)
     *S = (M + rps - 1) / rps;
 }
 
-// The same for the copy-to-LDS kernel, one workgroup per compute unit: the number of ranges whose
-// workgroups fill whole rounds of the device best, at least 16 steps per range.
-void dw_dma_split(int M, int base_tiles, int *S, int *rows_per_split)
+// The same for the copy-to-LDS kernel, one workgroup per compute unit: the number of ranges with the least
+// estimated time, from the rounds of workgroups the device needs (a step of a 256 x 256 tile takes a compute
+// unit about 2.3 us, a workgroup's start and output tile about 6 us) and the partial sums that have to be
+// written and read again (about 4 TB/s); at least four steps per range.
+void dw_dma_split(int M, int G, int H, int dh, int n_heads, int *S, int *rows_per_split)
 {
     const int cus = device_cu_count() > 0 ? device_cu_count() : 256;
+    const int tiles = (dh + dwd::BT - 1) / dwd::BT;
+    const long long base_tiles = (long long)tiles * tiles * G * n_heads;
+    const double nw = (double)G * H * dh;
     int best = 1;
-    double best_score = -1.0;
+    double best_us = 0.0;
     for (int s = 1; s <= 64; ++s) {
-        if (s > 1 && (M + s - 1) / s < 16 * dwd::BK) break;
-        const long long items = (long long)base_tiles * s, rounds = (items + cus - 1) / cus;
-        // busy share of the rounds, with a bonus for several rounds (their tails even out) that ends at four
-        const double score = (double)items / (double)(rounds * cus) * (rounds >= 4 ? 1.0 : 0.85 + 0.05 * (double)(rounds - 1));
-        if (score > best_score + 1e-9) { best_score = score; best = s; }
+        int rps = (M + s - 1) / s;
+        rps = (rps + dwd::BK - 1) / dwd::BK * dwd::BK;
+        if (s > 1 && rps < 4 * dwd::BK) break;
+        const int ranges = (M + rps - 1) / rps;
+        const long long rounds = (base_tiles * ranges + cus - 1) / cus;
+        const double us = (double)rounds * ((double)(rps / dwd::BK) * 2.3 + 6.0) + (ranges > 1 ? (double)ranges * nw * 8.0 / 4.0e6 : 0.0);
+        if (s == 1 || us < best_us) { best_us = us; best = ranges; }
     }
     int rps = (M + best - 1) / best;
     rps = (rps + dwd::BK - 1) / dwd::BK * dwd::BK;
@@ -1207,7 +1220,7 @@ ProjLayout proj_layout(int B, int L, int H, int G, int n_heads, int backward)
         // room for either kernel's partial sums, so that the size does not depend on proj_set_dma
         if (dw_dma_shape_ok(H, G, dh)) {
             lo.tiles2 = (dh + dwd::BT - 1) / dwd::BT;
-            dw_dma_split(B * L, lo.tiles2 * lo.tiles2 * G * n_heads, &lo.S2, &lo.rows_per_split2);
+            dw_dma_split(B * L, G, H, dh, n_heads, &lo.S2, &lo.rows_per_split2);
         }
         const size_t s_max = (size_t)(lo.S > lo.S2 ? lo.S : lo.S2);
         lo.off_part = off; off += r256(s_max * nw * sizeof(float));
@@ -1342,6 +1355,10 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         a.M = B * L; a.H = H; a.G = G; a.heads = n_heads; a.dh = dh;
         const bool copy_kernel = bf && g_proj_dma && lo.S2 > 0;
         a.S = copy_kernel ? lo.S2 : lo.S;
+        if (a.S == 1) {                                 // one range: its sums are the results
+            a.part = dWx;
+            if (dbias) a.dbpart = dbias;
+        }
         a.rows_per_split = copy_kernel ? lo.rows_per_split2 : lo.rows_per_split;
         a.tiles = copy_kernel ? lo.tiles2 : lo.tiles;
         a.n_blocks = a.tiles * a.tiles * n_heads * G * a.S;
@@ -1351,8 +1368,10 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         else if (bf) hipLaunchKernelGGL(proj_dw_kernel<unsigned short>, dim3(blocks), dim3(256), 0, st, a);
         else hipLaunchKernelGGL(proj_dw_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return PARARNN_HIP_ERROR;
-        if (launch_param_reduce(a.part, dWx, a.S, (int)nw, st) != hipSuccess) return PARARNN_HIP_ERROR;
-        if (dbias && launch_param_reduce(a.dbpart, dbias, a.S, G * H, st) != hipSuccess) return PARARNN_HIP_ERROR;
+        if (a.S > 1) {
+            if (launch_param_reduce(a.part, dWx, a.S, (int)nw, st) != hipSuccess) return PARARNN_HIP_ERROR;
+            if (dbias && launch_param_reduce(a.dbpart, dbias, a.S, G * H, st) != hipSuccess) return PARARNN_HIP_ERROR;
+        }
     }
     return PARARNN_OK;
 }
