@@ -287,7 +287,9 @@ def headline_extras(run, rec, reps, counters):
     """Figures beside the timed step, for the headline workload only."""
     P, torch, w, N = run.P, run.torch, run.w, run.N
     u, params, h0 = run.u, run.params, run.h0
-    rec["launches"] = P.solve_plan(w.tol, w.max_iter) if w.cell != "tanh_dense" else None
+    # blocks of Newton iterations of the plan; the first two are launches of their own, the rest share one
+    rec["blocks"] = P.solve_plan(w.tol, w.max_iter) if w.cell != "tanh_dense" else None
+    rec["launches_per_solve"] = min(len(rec["blocks"]), 3) if rec["blocks"] is not None else None
     if w.cell == "tanh_dense":
         dfac, Aout = run.extra
         # not part of the step (config 4 is forward only): the adjoint scan of the same cell

@@ -170,11 +170,25 @@ int pararnn_set_staging(int enable);
  * iteration). */
 int pararnn_set_fused_head(int n_iters);
 
-/* The launches pararnn_forward enqueues for a solve with these settings when the
- * workspace is of the size pararnn_workspace_bytes reports (host only, no device
- * work): writes the number of Newton iterations of each launch to
- * block_sizes[0 .. capacity) and returns the number of launches (which may
- * exceed capacity), or -1 on invalid arguments.  The sizes add up to max_iter. */
+/* Tuning / test hook (host, process-wide, not thread-safe; default 1): the blocks
+ * of a solve to a tolerance that follow its second launch (the first fused
+ * block, then one iteration of the per-iteration kernel) run in ONE more launch
+ * of the fused kernel, which walks the rest of the plan on the device (grid-wide
+ * barriers between blocks; the grid is what the device holds at once, and a
+ * barrier wait is bounded like the look-back waits: pararnn_set_spin_limit) and
+ * returns at once when the tolerance was met before.  enable = 0: every block is
+ * a launch of its own, and the launches after the one that met the tolerance
+ * return at once.  `iters`, status and delta_trace are the same either way. */
+int pararnn_set_fused_tail(int enable);
+
+/* The blocks of Newton iterations pararnn_forward runs for a solve with these
+ * settings when the workspace is of the size pararnn_workspace_bytes reports
+ * (host only, no device work): writes the number of iterations of each block to
+ * block_sizes[0 .. capacity) and returns the number of blocks (which may exceed
+ * capacity), or -1 on invalid arguments.  The sizes add up to max_iter.  The
+ * stopping test is evaluated for every iteration and acted on between blocks.
+ * The first two blocks are launches of their own; the following ones share one
+ * launch (pararnn_set_fused_tail) or are launches of their own. */
 int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity);
 
 /*

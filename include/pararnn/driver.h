@@ -28,6 +28,7 @@ struct Settings {
     int tile[4];           // tile-shape override {vec, ll, c, w}; vec = 0 none, -1 not yet read from the environment
     unsigned int spin_limit;   // polls of one predecessor before a tile gives up (pararnn_set_spin_limit)
     int stage_enabled;         // kernels that copy their inputs straight into LDS are allowed (pararnn_set_staging)
+    int fused_tail;            // the blocks after a solve's first launch share one persistent launch (pararnn_set_fused_tail)
 };
 Settings &settings();
 
@@ -170,21 +171,6 @@ inline int fused_slots_wanted(float tol, int max_iter, const SolveOpts &s = defa
     return max_iter < s.fused_head ? max_iter : s.fused_head;
 }
 
-// Iterations the next launch of a solve performs: `done` of max_iter are behind it, `n_fused`
-// carry-record slots are available (0: every launch is one iteration).  The first launch takes
-// n_fused, the following ones 1, 2, 4, ... capped by n_fused and by what is left.
-inline int next_block_size(int done, int launches, int max_iter, int n_fused)
-{
-    int K = 1;
-    if (n_fused > 0) {
-        if (launches == 0) K = n_fused;
-        else K = launches - 1 < 30 ? 1 << (launches - 1) : n_fused;
-        if (K > n_fused) K = n_fused;
-    }
-    if (K > max_iter - done) K = max_iter - done;
-    return K;
-}
-
 // Workspace size of a forward solve to a tolerance (or of a backward pass); does not depend on
 // pointer alignment: the larger footprint is taken when the layouts differ.
 inline size_t diag_workspace_bytes(const CellInfo &ci, int dtype, int B, int L, int H, bool backward,
@@ -218,9 +204,11 @@ inline size_t diag_workspace_bytes_fused(const CellInfo &ci, int dtype, int B, i
 // tol < 0: the whole fixed-count solve is one fused launch of n_fused = max_iter iterations.
 // tol >= 0: the solve is a sequence of launches, each checked by the stopping test on the
 // device: a fused block of n_fused iterations from the initial guess, then blocks of 1, 2,
-// 4, ... (at most n_fused) iterations from the iterate; a block of one iteration is the
-// per-iteration kernel.  Launches after the one that met the tolerance return at once, and
-// there are O(max_iter / n_fused) of them instead of max_iter.
+// 4, ... (at most n_fused) iterations from the iterate; a block of one iteration that is a
+// launch of its own is the per-iteration kernel.  With `tail` the blocks after the second share
+// ONE launch of the fused kernel, which returns at once when the tolerance was met before;
+// without it every block is a launch of its own.  Launches after the one that met the
+// tolerance return at once.
 template <class Cell>
 int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hipStream_t st, void *h,
                  int status0, int max_iter, int n_fused)
@@ -246,11 +234,21 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
     f.head = to_tol ? 1 : 0; f.max_iter = max_iter; f.tol = a.tol;
     f.hit = to_tol ? a.hit : nullptr;
     f.bnd = a.bnd;
+    f.n_slots = n_fused; f.spin_limit = settings().spin_limit;
+    const bool tail = settings().fused_tail != 0;
     int done = 0, cur = 0;
     for (int launches = 0; done < max_iter; ++launches) {
         const int K = next_block_size(done, launches, max_iter, n_fused);
+        if (to_tol && n_fused > 0 && launches == 2 && tail) {
+            // everything after the second block in one launch that goes through the plan on the device (the
+            // second block is one iteration, which the per-iteration kernel does faster than a fused block)
+            f.n_iters = K; f.k0 = done; f.bnd_cur = cur; f.tail = 1; f.launch_no = launches;
+            e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
+            if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
+            break;
+        }
         if (n_fused > 0 && (K > 1 || done == 0)) {
-            f.n_iters = K; f.k0 = done; f.bnd_cur = cur;
+            f.n_iters = K; f.k0 = done; f.bnd_cur = cur; f.tail = 0; f.launch_no = launches;
             e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
         } else {
             a.k = done + 1; a.bnd_cur = cur;

@@ -11,7 +11,12 @@
 // flight.  The first block starts from the initial guess (k0 = 0); a later one
 // (k0 > 0) starts from the fp32 iterate and the tile-boundary rows its
 // predecessor left behind, exactly as the per-iteration kernel does, and may be
-// mixed with launches of that kernel.
+// mixed with launches of that kernel.  With `tail` set one launch runs ALL the
+// blocks that are left of a solve (sizes 1, 2, 4, ... as next_block_size gives
+// them), separated by grid-wide barriers: after a block every workgroup learns
+// from the control block whether the solve has ended, and a solve that met the
+// tolerance early costs one such launch instead of a dozen that return at once.  The grid of such a launch is what the device holds at once
+// (as for every launch of this kernel), so every barrier is reached by all.
 //
 // Same tile decomposition and the same look-back as newton_iter_kernel, with one
 // carry-record slot per iteration: tile t at iteration k waits only for tile
@@ -50,7 +55,52 @@ struct FusedArgs {
                              // the output h itself for fp32 storage
     float *bnd;              // [2][n_lt][B][S][H] tile-boundary rows, see FwdArgs
     int bnd_cur;             // buffer read (k0 > 0); the other one is written
+    // tail != 0: after this block the following ones of the plan, in the same launch
+    int tail;
+    int launch_no;           // position of this block in the plan (0 = the first launch of the solve)
+    int n_slots;             // carry-record slots = largest block
+    unsigned int spin_limit; // polls of a grid-wide barrier before it gives up
 };
+
+// Iterations of the next block of a solve: `done` of max_iter are behind it, `n_fused` carry-record
+// slots are available (0: every block is one iteration).  The first block takes n_fused, the
+// following ones 1, 2, 4, ... capped by n_fused and by what is left.
+__host__ __device__ inline int next_block_size(int done, int launches, int max_iter, int n_fused)
+{
+    int K = 1;
+    if (n_fused > 0) {
+        if (launches == 0) K = n_fused;
+        else K = launches - 1 < 30 ? 1 << (launches - 1) : n_fused;
+        if (K > n_fused) K = n_fused;
+    }
+    if (K > max_iter - done) K = max_iter - done;
+    return K;
+}
+
+// All workgroups of the launch meet here; false when the wait ran out (some workgroup never
+// arrived: the launch then ends with status INTERNAL instead of hanging).  `arrivals` counts up over
+// the launch, `generation` is the caller's count of barriers passed.
+__device__ __forceinline__ bool fused_grid_barrier(unsigned int *arrivals, unsigned int &generation, unsigned int spin_limit)
+{
+    __shared__ int s_ok;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();                              // this workgroup's writes, before it arrives
+        ++generation;
+        const unsigned int target = generation * gridDim.x;
+        atomicAdd(arrivals, 1u);
+        unsigned int spins = 0;
+        int ok = 1;
+        while (__hip_atomic_load(arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (++spins >= spin_limit) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(16);
+        }
+        __threadfence();                              // the others' writes, after all have arrived
+        s_ok = ok;
+    }
+    __syncthreads();
+    return s_ok != 0;
+}
 
 template <class Cell, int VEC, int LL, int C, int W, typename UT>
 __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs a)
@@ -70,9 +120,12 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
     const UT *u = static_cast<const UT *>(a.u);
     UT *hout = static_cast<UT *>(a.h);
-    const int K = a.n_iters;
-    const bool resume = a.k0 > 0;
+    int K = a.n_iters, k0 = a.k0, bnd_cur = a.bnd_cur, launch_no = a.launch_no;
+    unsigned int generation = 0;
     bool internal_error = false;
+
+  for (;;) {                              // the blocks of this launch: one, or the rest of the plan (tail)
+    const bool resume = k0 > 0;
     if (threadIdx.x < kMaxFused) s_maxk[threadIdx.x] = 0u;
 
     for (;;) {
@@ -190,7 +243,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
                     if (w == 0 && seg == 0)
-                        load_vec<VEC>(a.bnd + ((((size_t)a.bnd_cur * g.n_lt + (lt - 1)) * g.B + b) * S + s) * g.H + ch, hprev[s]);
+                        load_vec<VEC>(a.bnd + ((((size_t)bnd_cur * g.n_lt + (lt - 1)) * g.B + b) * S + s) * g.H + ch, hprev[s]);
                     else
                         load_vec<VEC>(a.hit + ((seq + l0 - 1) * S + s) * g.H + ch, hprev[s]);
                 }
@@ -224,7 +277,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             constexpr int kMode = decltype(mode)::value;
 #pragma unroll 1
             for (int k = 1; k <= K; ++k) {
-                const unsigned int epoch = (unsigned int)(a.k0 + k);      // unique within the call
+                const unsigned int epoch = (unsigned int)(k0 + k);        // unique within the call
                 unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
 
                 // ---- thread level
@@ -447,7 +500,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         }
 
         // ---- what a following per-iteration launch needs: the fp32 iterate and the tile's last row
-        if (a.head && a.k0 + K < a.max_iter) {
+        if (a.head && k0 + K < a.max_iter) {
             if (a.hit && static_cast<void *>(a.hit) != a.h) {
 #pragma unroll
                 for (int i = 0; i < C; ++i) {
@@ -459,7 +512,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 }
             }
             if (ch_ok && w == W - 1 && seg == LL - 1 && lt + 1 < g.n_lt) {
-                const int nxt = a.bnd_cur ^ 1;
+                const int nxt = bnd_cur ^ 1;
 #pragma unroll
                 for (int s = 0; s < S; ++s)
                     store_vec<VEC>(a.bnd + ((((size_t)nxt * g.n_lt + lt) * g.B + b) * S + s) * g.H + ch, ho[C - 1][s]);
@@ -499,26 +552,43 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             int status = internal ? kStInternal : (a.head ? kStNotConverged : kStOk);
             int iters = K, stop = (a.head && !internal) ? 0 : 1;
             bool ended = false;
-            iters += a.k0;
+            iters += k0;
             for (int k = 0; k < K; ++k) {
                 const float mk = __uint_as_float(atomicExch(&a.gmaxk[k], 0u));   // zero again for the next block
                 if (ended) continue;                  // iterations past the end are not reported
-                if (a.trace) a.trace[a.k0 + k] = mk;
+                if (a.trace) a.trace[k0 + k] = mk;
                 if (internal) continue;
-                if (!(mk - mk == 0.0f)) { status = kStNonFinite; iters = a.k0 + k + 1; stop = 1; ended = true; }
-                else if (a.head && mk <= a.tol) { status = kStOk; iters = a.k0 + k + 1; stop = 1; ended = true; }
+                if (!(mk - mk == 0.0f)) { status = kStNonFinite; iters = k0 + k + 1; stop = 1; ended = true; }
+                else if (a.head && mk <= a.tol) { status = kStOk; iters = k0 + k + 1; stop = 1; ended = true; }
             }
             a.iters_out[0] = iters;
             a.iters_out[1] = status;
             ctrl->iters = iters;
             ctrl->status = status;
             ctrl->stop = stop;
-            ctrl->h_final = (stop || a.k0 + K >= a.max_iter) ? 1 : 0;
+            ctrl->h_final = (stop || k0 + K >= a.max_iter) ? 1 : 0;
             ctrl->ticket = 0u;
             ctrl->done = 0u;
             __threadfence();
         }
     }
+    if (!a.tail) break;
+    // ---- the next block of the plan, if the solve goes on
+    if (!fused_grid_barrier(&ctrl->pad[0], generation, a.spin_limit)) {
+        if (threadIdx.x == 0) {
+            atomicExch(&ctrl->status, kStInternal);
+            a.iters_out[1] = kStInternal;
+            ctrl->stop = 1;
+        }
+        break;
+    }
+    if (__hip_atomic_load(&ctrl->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+    k0 += K;
+    if (k0 >= a.max_iter) break;
+    bnd_cur ^= 1;
+    ++launch_no;
+    K = next_block_size(k0, launch_no, a.max_iter, a.n_slots);
+  }
 }
 
 }  // namespace pararnn

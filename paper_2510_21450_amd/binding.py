@@ -39,6 +39,7 @@ _lib.pararnn_workspace_bytes.argtypes = [_i] * 6
 _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
+_lib.pararnn_set_fused_tail.argtypes = [_i]
 _lib.pararnn_set_staging.argtypes = [_i]
 _lib.pararnn_set_dense_products.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
@@ -226,6 +227,12 @@ def solve_plan(tol: float, max_iter: int):
     if n < 0:
         raise ValueError("pararnn_solve_plan: invalid arguments")
     return [buf[i] for i in range(n)]
+
+
+def set_fused_tail(enable: bool = True) -> None:
+    """pararnn_set_fused_tail: the blocks after a solve's first launch share one persistent launch (default)
+    or are launches of their own."""
+    _raise(_lib.pararnn_set_fused_tail(int(enable)), "pararnn_set_fused_tail")
 
 
 def set_fused_head(n_iters: int = 5) -> None:

@@ -13,7 +13,7 @@ namespace pararnn {
 
 Settings &settings()
 {
-    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1};
+    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1, 1};
     return s;
 }
 
@@ -149,6 +149,12 @@ int pararnn_set_staging(int enable)
 int pararnn_set_fused(int enable)
 {
     settings().fused_enabled = enable ? 1 : 0;
+    return PARARNN_OK;
+}
+
+int pararnn_set_fused_tail(int enable)
+{
+    settings().fused_tail = enable ? 1 : 0;
     return PARARNN_OK;
 }
 

@@ -945,6 +945,7 @@ constexpr int STAGE = 2 * OP;            // du rows, then x rows
 
 typedef short s4v __attribute__((ext_vector_type(4)));
 typedef short s8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char *lds_char_ptr;
 typedef __attribute__((address_space(3))) s4v *lds_s4v_ptr;
 
 __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
@@ -990,6 +991,7 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
         vb[j] = (unsigned int)row * (unsigned int)ld_x * 2u + chunk * 16u;
     }
     const unsigned int lds_op = lds_address(&s_op[0][0]);
+    const lds_char_ptr lds_zero = (lds_char_ptr)&s_op[0][0] - lds_op;       // LDS address 0, as a pointer
     auto words = [&](unsigned long long p, long long rem) {
         const unsigned int n = rem <= 0 ? 0u : rem > 0xffffffffll ? 0xffffffffu : (unsigned int)rem;
         const u4v r = {uniform((unsigned int)p), uniform((unsigned int)(p >> 32) & 0xffffu), uniform(n), 0x27000u};
@@ -1021,8 +1023,8 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
         o_x[par] = lds_op + OP * 2u + rowpart + (unsigned int)(64 * wn) * 2u + pos;
     }
     auto read8 = [&](unsigned int addr) {
-        const s4v q0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(addr));
-        const s4v q1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(addr + 4u * BT * 2u));
+        const s4v q0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(lds_zero + addr));
+        const s4v q1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(lds_zero + addr + 4u * BT * 2u));
         const s8v t = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf8v, t);
     };

@@ -552,6 +552,63 @@ def test_backward_inputs_staged_through_lds(P, oracle_mod, as_stored, cell):
         assert relerr(to_np(dh0), rdh0) <= TOL_BF16
 
 
+@pytest.mark.parametrize("cell,dtype", [("gru_diag", torch.float32), ("lstm_diag", torch.float32), ("gru_diag", torch.bfloat16)])
+def test_blocks_after_the_first_in_one_launch(P, oracle_mod, cell, dtype):
+    """The rest of a solve's plan in one persistent launch (pararnn_set_fused_tail, the default) against one
+    launch per block: a first block of 1, 2 or 3 iterations and the one iteration that follows it leave
+    more to blocks of 2 and 4 that the tail launch separates by grid-wide barriers.  Iteration count, status and trace are the
+    oracle's either way; the traces of the two agree to rounding (a block of one iteration is the fused
+    kernel in the one and the per-iteration kernel in the other), h is the converged state."""
+    B, L, H = 3, 1500, 200
+    params, u, h0, _ = problem(cell, B, L, H, seed=616, dtype=dtype)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    tol, want = well_posed_tol(oracle_mod, cell, pn, un, h0n, max_iter=40)
+    assert want >= 5
+    for first_block in (1, 2, 3):
+        out = {}
+        for tail in (True, False):
+            print(f"tail launch {cell} {dtype} first_block={first_block} tail={tail}", flush=True)
+            try:
+                P.set_fused_tail(tail)
+                h, iters, tr = P.forward_ex(cell, params, u, h0, tol=tol, max_iter=40, first_block=first_block, trace=True)
+                torch.cuda.synchronize()
+            finally:
+                P.set_fused_tail(True)
+            assert tuple(int(x) for x in iters.cpu()) == (want, 0)
+            assert relerr(to_np(h), ref) <= (TOL_F32 if dtype == torch.float32 else TOL_BF16)
+            out[tail] = tr[:want].cpu().numpy().astype(np.float64)
+        big = out[False] > 1e-4                       # above the rounding floor of the updates
+        assert np.all(np.abs(out[True] - out[False])[big] <= 1e-3 * out[False][big])
+
+
+@pytest.mark.gpu
+def test_tail_launch_with_a_full_grid(P, oracle_mod):
+    """The same on config 2's shape, where the persistent grid is as large as the device holds and every
+    workgroup walks many tiles per block: a first block of 1 and the iteration after it leave three or more
+    iterations to the tail launch (blocks of 2 and 4).  Checked against the oracle's sequential unroll on sampled channels."""
+    from workloads import CONFIGS, make_inputs
+    w = CONFIGS["C2"]
+    d = make_inputs(w, device="cuda")
+    params, u, h0 = d["params"], d["u"], d["h0"]
+    res = {}
+    for tail in (True, False):
+        print(f"tail launch, full grid, tail={tail}", flush=True)
+        try:
+            P.set_fused_tail(tail)
+            h, iters, tr = P.forward_ex(w.cell, params, u, h0, tol=w.tol, max_iter=w.max_iter, first_block=1, trace=True)
+            torch.cuda.synchronize()
+        finally:
+            P.set_fused_tail(True)
+        res[tail] = (h, tuple(int(x) for x in iters.cpu()), tr)
+    assert res[True][1] == res[False][1] and res[True][1][1] == 0 and res[True][1][0] >= 4
+    assert float((res[True][0] - res[False][0]).abs().max()) <= 1e-5
+    idx = torch.tensor([0, 1, 63, 64, 500, 1023], device="cuda")
+    ref = oracle_mod.seq_unroll(w.cell, to_np(params.index_select(-1, idx)), to_np(u.index_select(-1, idx)),
+                                None if h0 is None else to_np(h0.index_select(-1, idx)))
+    assert relerr(to_np(res[True][0].index_select(-1, idx)), ref) <= TOL_F32
+
+
 @pytest.mark.parametrize("cell", ["gru_diag", "lstm_diag"])
 def test_forward_ex_options_travel_with_the_call(P, oracle_mod, cell):
     """pararnn_forward_ex: the first launch runs `first_block` iterations (3 = the paper's fixed
