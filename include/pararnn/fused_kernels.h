@@ -84,9 +84,9 @@ __device__ __forceinline__ bool fused_grid_barrier(unsigned int *arrivals, unsig
 {
     __shared__ int s_ok;
     __syncthreads();
+    ++generation;                                     // by every thread: the count stays a scalar
     if (threadIdx.x == 0) {
         __threadfence();                              // this workgroup's writes, before it arrives
-        ++generation;
         const unsigned int target = generation * gridDim.x;
         atomicAdd(arrivals, 1u);
         unsigned int spins = 0;
@@ -99,10 +99,15 @@ __device__ __forceinline__ bool fused_grid_barrier(unsigned int *arrivals, unsig
         s_ok = ok;
     }
     __syncthreads();
-    return s_ok != 0;
+    // as a scalar: a branch on a per-lane value would make the caller's loop variables per-lane values too
+    return __builtin_amdgcn_readfirstlane(s_ok) != 0;
 }
 
-template <class Cell, int VEC, int LL, int C, int W, typename UT>
+// TAIL: the launch goes on with the following blocks of the plan (a.tail is set); a variant of its own
+// because the block's size and position are then loop variables that stay in registers, where the
+// one-block variant re-reads them from the kernel arguments, and the first block of the bf16 GRU
+// sits one register short of losing a wave per SIMD
+template <class Cell, int VEC, int LL, int C, int W, typename UT, bool TAIL = false>
 __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs a)
 {
     constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR;
@@ -572,7 +577,9 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             __threadfence();
         }
     }
-    if (!a.tail) break;
+    if constexpr (!TAIL) {
+        break;
+    } else {
     // ---- the next block of the plan, if the solve goes on
     if (!fused_grid_barrier(&ctrl->pad[0], generation, a.spin_limit)) {
         if (threadIdx.x == 0) {
@@ -582,12 +589,13 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         }
         break;
     }
-    if (__hip_atomic_load(&ctrl->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+    if (__builtin_amdgcn_readfirstlane(__hip_atomic_load(&ctrl->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) break;
     k0 += K;
     if (k0 >= a.max_iter) break;
     bnd_cur ^= 1;
     ++launch_no;
     K = next_block_size(k0, launch_no, a.max_iter, a.n_slots);
+    }
   }
 }
 

@@ -114,10 +114,12 @@ hipError_t Kernels<Cell, UT>::newton_fused(const TileCfg &cfg, const FusedArgs &
 #define PARARNN_CASE(V, LLv, C, W)                                                             \
     if (cfg.vec == V && cfg.ll == LLv && cfg.c == C && cfg.w == W) {                           \
         if constexpr (shape_offered<Cell, V, C>()) {                                           \
-            static int grid_cap = 0;                                                           \
-            auto kern = newton_fused_kernel<Cell, V, LLv, C, W, UT>;                           \
-            if (grid_cap == 0) grid_cap = persistent_grid(kern, kWave * W, 1 << 30);           \
-            const int grid = a.g.n_tiles < grid_cap ? a.g.n_tiles : grid_cap;                  \
+            static int grid_cap[2] = {0, 0};                                                   \
+            const int tl = a.tail ? 1 : 0;                                                     \
+            auto kern = a.tail ? newton_fused_kernel<Cell, V, LLv, C, W, UT, true>             \
+                               : newton_fused_kernel<Cell, V, LLv, C, W, UT, false>;           \
+            if (grid_cap[tl] == 0) grid_cap[tl] = persistent_grid(kern, kWave * W, 1 << 30);   \
+            const int grid = a.g.n_tiles < grid_cap[tl] ? a.g.n_tiles : grid_cap[tl];          \
             hipLaunchKernelGGL(kern, dim3(grid), dim3(kWave * W), 0, st, a);                   \
             return hipGetLastError();                                                          \
         } else {                                                                               \
