@@ -924,12 +924,12 @@ __global__ __launch_bounds__(256, 2) void proj_dw_kernel(const DwArgs a)
 // copied from memory to LDS as they are, 512 bytes of du and of x per row.
 //
 //   LDS      two stages of (64 + 64) rows x 512 bytes = 128 KB.  A copy instruction moves two rows;
-//            16-byte chunk c of row r lies at position c ^ 2 (r % 4) of its row.
+//            16-byte chunk c of row r lies at position c ^ dw_swz(r) of its row.
 //   reads    the products need, per lane, eight consecutive m of one channel: a column of the
 //            stage.  ds_read_b64_tr_b16 hands a lane four of them: the sixteen lanes of a group read
 //            8 bytes each, four lanes per row over four rows (32 bytes = 16 channels of a row), and
 //            lane i of the group receives the i-th channel of the four rows.  With the chunk
-//            positions above the four rows of a group lie in four different quarters of the banks.
+//            positions above the four rows of a group lie in four different parts of the banks.
 //   rows     past the end of a range lie beyond the buffer descriptor, which is rebuilt for every
 //            step (base at the step's first row, extent to the end of the range): the copy writes
 //            zeros for them, so they add nothing.  Tile columns past dh hold whatever follows in the
@@ -942,6 +942,12 @@ constexpr int BT = 256, BK = 64;
 constexpr int OP = BK * BT;              // bf16 elements of one operand's rows of a step
 constexpr int STAGE = 2 * OP;            // du rows, then x rows
 }  // namespace dwd
+
+// position of 16-byte chunk c in stage row r: c ^ dw_swz(r).  Rows r .. r + 3 (r a multiple of four) get
+// four different values both in bits 1-2 and in bits 2-3 of the chunk index: the four rows of a transposing
+// read then lie in different 32-byte quarters of a 128-byte window and in different 64-byte quarters of a
+// 256-byte window of the banks, whichever the LDS serves per cycle.
+__device__ __forceinline__ int dw_swz(int row) { return (0xca60 >> (4 * (row & 3))) & 15; }       // 0, 6, 10, 12
 
 typedef short s4v __attribute__((ext_vector_type(4)));
 typedef short s8v __attribute__((ext_vector_type(8)));
@@ -986,7 +992,7 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int row = 8 * w + 2 * j + (lane >> 5);
-        const unsigned int chunk = (unsigned int)((lane & 31) ^ (2 * (row & 3)));
+        const unsigned int chunk = (unsigned int)((lane & 31) ^ dw_swz(row));
         va[j] = (unsigned int)row * (unsigned int)ld_du * 2u + chunk * 16u;
         vb[j] = (unsigned int)row * (unsigned int)ld_x * 2u + chunk * 16u;
     }
@@ -1011,17 +1017,19 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
 
     // ---- the multiplying side
     // this lane's place in a transposing read: row rr of the four, the 8 bytes at channel 16 hi + 4 (lane % 4) of
-    // the 32-channel block; the block's first chunk is a multiple of four, so the position of the lane's chunk is
-    // (block chunk) ^ sl, which is a sum for even blocks and for odd ones after taking the 4 out
-    const int rr = (lane & 15) >> 2, sl = (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ (2 * rr);
+    // the 32-channel block.  The block's first chunk is a multiple of four and the lane's chunk within the block
+    // is 2 hi + lo, so its position is (block chunk ^ high bits of the row's mask) + ((2 hi + lo) ^ low bits):
+    // one lane offset per value of the block chunk's bits 2-3.
+    const int rr = (lane & 15) >> 2, mask = dw_swz(rr);
+    const int in_block = (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ (mask & 3);
     const unsigned int rowpart = (unsigned int)(8 * half + rr) * (BT * 2u) + (unsigned int)(lane & 1) * 8u;
-    unsigned int o_du[2], o_x[2];
+    unsigned int o_du[4], o_x[2];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const unsigned int pos = (unsigned int)(par ? (4 ^ sl) : sl) * 16u;
-        o_du[par] = lds_op + rowpart + (unsigned int)(128 * wm) * 2u + pos;
-        o_x[par] = lds_op + OP * 2u + rowpart + (unsigned int)(64 * wn) * 2u + pos;
-    }
+    for (int mi = 0; mi < 4; ++mi)
+        o_du[mi] = lds_op + rowpart + (unsigned int)(((16 * wm + 4 * mi) ^ (mask & 12)) + in_block) * 16u;
+#pragma unroll
+    for (int nj = 0; nj < 2; ++nj)
+        o_x[nj] = lds_op + OP * 2u + rowpart + (unsigned int)(((8 * wn + 4 * nj) ^ (mask & 12)) + in_block) * 16u;
     auto read8 = [&](unsigned int addr) {
         const s4v q0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(lds_zero + addr));
         const s4v q1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(lds_zero + addr + 4u * BT * 2u));
@@ -1031,7 +1039,7 @@ __global__ __launch_bounds__(512) void proj_dw_dma_kernel(const DwArgs a)
     auto read_frags = [&](int buf, int kb, bf8v (&fd)[4], bf8v (&fx)[2]) {
         const unsigned int base = (unsigned int)buf * (STAGE * 2u) + (unsigned int)(16 * kb) * (BT * 2u);
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) fd[mi] = read8(o_du[mi & 1] + base + (unsigned int)(mi >> 1) * 128u);
+        for (int mi = 0; mi < 4; ++mi) fd[mi] = read8(o_du[mi] + base);
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj) fx[nj] = read8(o_x[nj] + base);
     };
