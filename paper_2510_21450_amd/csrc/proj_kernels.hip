@@ -733,6 +733,276 @@ __global__ __launch_bounds__(512) void proj_gemm_nt_dma_kernel(const GemmArgs a)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// ------------------------------- NT product, fp32 A and C, operands copied straight into LDS
+// The kernel above for fp32 storage: rows of A arrive as fp32 (32 k = 128 bytes per row and step) and
+// are rounded to bf16 when a lane reads its fragment (two 16-byte reads and four conversions per
+// fragment); W is the bf16 copy, 32 k = 64 bytes per row and step, sixteen rows per copy instruction,
+// 16-byte chunk c of row r at position c ^ (r / 4 % 4): sixteen rows of a fragment read then cover all
+// banks once.  A step is two rounds of eight products; a stage is 32 KB of A and 16 KB of W.  A wave owns
+// 64 rows of A x 128 rows of W (the fp32 fragments are the costly ones in registers: two per round instead
+// of four).  With 32 k per step a step's products last a quarter of a microsecond, far less than a trip to
+// memory, so there are three stages and the copies run two steps ahead; that takes all of LDS, and output
+// tiles leave straight from the registers.
+namespace dmaf {
+constexpr int BK = 32;
+constexpr int OPA = 256 * BK * 4;        // bytes of the A tile of a stage
+constexpr int STAGE = OPA + 256 * BK * 2;  // A tile, then W tile
+}  // namespace dmaf
+
+__device__ __forceinline__ int dmaf_wswz(int row) { return (row >> 2) & 3; }
+
+template <bool BIAS>
+__global__ __launch_bounds__(512) void proj_gemm_nt_dma_f32_kernel(const GemmArgs a)
+{
+    constexpr int BM = dma::BM, BN = dma::BN, BK = dmaf::BK, OPA = dmaf::OPA, STAGE = dmaf::STAGE;
+    __shared__ __attribute__((aligned(16))) unsigned char s_op[3][STAGE];
+    __shared__ __attribute__((aligned(16))) float s_bias[2][8][128];
+    __shared__ int s_ring[8];
+    const int xcd = blockIdx.x & 7;
+    const int inner_n = a.tiles_n * a.n_batch;
+    // the XCD's (row block, inner) grid in patches of 8 x 8 tiles, as in proj_gemm_nt_kernel
+    const int mx = (a.tiles_m + 7) / 8;
+    int my_rows = a.tiles_m - xcd * mx;
+    if (my_rows > mx) my_rows = mx;
+    if (my_rows <= 0) return;
+    const int n_local = my_rows * inner_n;
+    const int nk = a.K / BK;
+    const int tid = threadIdx.x, lane = tid & 63, w = (int)uniform((unsigned int)tid >> 6), wm = w & 3, wn = w >> 2;
+    const int half = lane >> 5, l32 = lane & 31;
+    if (tid == 0) s_ring[0] = atomicAdd(a.tickets + xcd, a.draw);
+    __syncthreads();
+    const int first = (int)uniform((unsigned int)s_ring[0]);
+    if (first >= n_local) return;
+
+    struct Tile {
+        const float *A;
+        const unsigned short *Bw;
+        long long coff;
+        int m0, n0;
+    };
+    auto tile_of = [&](int local) {
+        const int pm = local / (8 * inner_n), rem = local - pm * 8 * inner_n;
+        const int hm = min(8, my_rows - 8 * pm);
+        const int pn = rem / (8 * hm), rem2 = rem - pn * 8 * hm;
+        const int hn = min(8, inner_n - 8 * pn);
+        const int mt = xcd * mx + 8 * pm + rem2 / hn, inner = 8 * pn + rem2 % hn;
+        const int nt = inner % a.tiles_n, z = inner / a.tiles_n;
+        const int z0 = z % a.nz0, z1 = z / a.nz0;
+        Tile t;
+        t.A = static_cast<const float *>(a.A) + z0 * a.a_off[0] + z1 * a.a_off[1];
+        t.Bw = a.Bw + z0 * a.b_off[0] + z1 * a.b_off[1];
+        t.coff = z0 * a.c_off[0] + z1 * a.c_off[1];
+        t.m0 = mt * BM; t.n0 = nt * BN;
+        return t;
+    };
+
+    // ---- the copying side: tile number ln of this workgroup, k-step lks of it.  A wave copies rows
+    //      32 w .. 32 w + 31 of both operand tiles: eight rows of A (eight lanes each) or sixteen rows
+    //      of W (four lanes each) per instruction.
+    const unsigned int lds_op = lds_address(&s_op[0][0]);
+    const int lrow = lane >> 3;
+    u4v ra, rb, rbias;
+    unsigned int va[4], vb[2], vbias[2] = {0u, 0u};
+    int ln = 0, lks = 0;
+    long long seg_base = 0;                // element offset of the current k-segment in a row of A
+    int kin = 0;                           // k within the segment
+    bool l_end = false;
+    auto point_at = [&](const Tile &t) {
+        ra = rsrc_words(t.A + (long long)t.m0 * a.lda);
+        rb = rsrc_words(t.Bw + (long long)t.n0 * a.ldb);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // rows past the end read the last row (valid memory); their products are never stored
+            const int row = 32 * w + 8 * j + lrow;
+            const unsigned int chunk = (unsigned int)((lane & 7) ^ dma_swz(8 * j + lrow));
+            const int gm = min(t.m0 + row, a.M - 1) - t.m0;
+            va[j] = (unsigned int)gm * (unsigned int)a.lda * 4u + chunk * 16u;
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int row = 32 * w + 16 * j + (lane >> 2);
+            const unsigned int chunk = (unsigned int)((lane & 3) ^ dmaf_wswz(row));
+            const int gn = min(t.n0 + row, a.N - 1) - t.n0;
+            vb[j] = (unsigned int)gn * (unsigned int)a.ldb * 2u + chunk * 16u;
+        }
+        if (BIAS) {
+            rbias = rsrc_words(a.bias + t.coff);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) vbias[j] = (unsigned int)min(t.n0 + 128 * wn + 64 * j + lane, a.N - 1) * 4u;
+        }
+        seg_base = 0; kin = 0;
+    };
+    // thread 0: the numbers drawn and not yet handed out
+    int next_no = first + 1, left = a.draw - 1;
+    auto draw = [&]() {
+        // the number of tile ln + 1 goes into the ring; it is read after at least one barrier
+        if (tid == 0) {
+            if (left == 0) {
+                next_no = atomicAdd(a.tickets + xcd, a.draw);
+                left = a.draw;
+            }
+            s_ring[(ln + 1) & 7] = next_no++;
+            --left;
+        }
+    };
+    // the copies of the next step in stream order, into stage `buf`
+    auto issue = [&](int buf) {
+        if (lks == nk) {
+            const int t = (int)uniform((unsigned int)s_ring[(ln + 1) & 7]);      // written at least a barrier ago
+            if (t >= n_local) {
+                l_end = true;
+                return;
+            }
+            point_at(tile_of(t));
+            ++ln;
+            lks = 0;
+        }
+        if (lks == 0) {
+            draw();
+            if (BIAS) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) copy_to_lds_4(lds_address(&s_bias[ln & 1][w][64 * j]), rbias, vbias[j], 0u);
+            }
+        }
+        const unsigned int soa = (unsigned int)((seg_base + kin) * 4), sob = (unsigned int)(lks * BK) * 2u;
+        const unsigned int dst = lds_op + (unsigned int)buf * (unsigned int)STAGE;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) copy_to_lds_16(dst + (unsigned int)(32 * w + 8 * j) * 128u, ra, va[j], soa);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) copy_to_lds_16(dst + OPA + (unsigned int)(32 * w + 16 * j) * 64u, rb, vb[j], sob);
+        ++lks;
+        kin += BK;
+        if (kin == a.kseg) {
+            kin = 0;
+            seg_base += a.kseg_stride;
+        }
+    };
+
+    // ---- the multiplying side
+    // byte offsets of this lane's fragment pieces within a 32-row block, for the two 16-k rounds of a step:
+    // eight fp32 of an A row (two chunks, rounded to bf16 here), eight bf16 of a W row (one chunk)
+    unsigned int foa[2][2], fow[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) foa[kb][e] = (unsigned int)l32 * 128u + (unsigned int)((4 * kb + 2 * half + e) ^ dma_swz(l32)) * 16u;
+        fow[kb] = (unsigned int)OPA + (unsigned int)l32 * 64u + (unsigned int)((2 * kb + half) ^ dmaf_wswz(l32)) * 16u;
+    }
+    auto read_frags = [&](int buf, int kb, bf8v (&fa)[2], bf8v (&fw)[4]) {
+        const unsigned char *base = &s_op[buf][0];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            const unsigned char *row = base + (64 * wm + 32 * mi) * 128;
+            const f4v lo = *reinterpret_cast<const f4v *>(row + foa[kb][0]), hi = *reinterpret_cast<const f4v *>(row + foa[kb][1]);
+            const u4v r = {pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])};
+            fa[mi] = __builtin_bit_cast(bf8v, r);
+        }
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) fw[ni] = *reinterpret_cast<const bf8v *>(base + fow[kb] + (128 * wn + 32 * ni) * 64);
+    };
+    f16v acc[4][2];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.0f;
+    };
+    // acc[ni][mi] = (W rows)(A rows)^T: a lane owns row l32 of the A block and, per four registers,
+    // four consecutive columns
+    auto multiply = [&](const bf8v (&fa)[2], const bf8v (&fw)[4]) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ni], fa[mi], acc[ni][mi], 0, 0, 0);
+    };
+    Tile ct = tile_of(first);
+    int cn = 0, cks = 0;
+    auto epilogue = [&]() {
+        // straight from the registers: a lane owns row l32 of each 32 x 32 block and, per four registers, four
+        // consecutive columns, so a store instruction writes 32 bytes of 32 rows (all of LDS belongs to the
+        // three stages).  Rows and columns past the end fall outside the buffer descriptor and are dropped, so
+        // the number of store instructions never depends on the data: thirty-two.
+        const int rows_here = a.M - (ct.m0 + 64 * wm);                    // valid rows of this wave's part (may be <= 0)
+        const int cols_here = min(a.N - (ct.n0 + 128 * wn), 128);         // valid columns: a multiple of 64 (may be <= 0)
+        float *C = static_cast<float *>(a.C) + ct.coff + (long long)(ct.m0 + 64 * wm) * a.ldc + ct.n0 + 128 * wn;
+        const long long valid = (rows_here > 0 && cols_here > 0) ? (long long)(min(rows_here, 64) - 1) * a.ldc * 4 + 512 : 0;
+        const buf_rsrc rc = __builtin_amdgcn_make_buffer_rsrc(C, 0, (int)valid, 0x27000);
+        const unsigned int lane_off = (unsigned int)l32 * (unsigned int)a.ldc * 4u + (unsigned int)half * 16u;
+        const float *bias_w = &s_bias[cn & 1][w][4 * half];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            // columns past the end (a part that is only half there) go beyond the descriptor too
+            const unsigned int col_off = 32 * ni < cols_here ? (unsigned int)(32 * ni) * 4u : 0x80000000u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                const f4v b4 = BIAS ? *reinterpret_cast<const f4v *>(bias_w + 32 * ni + 8 * q) : zero;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    f4v o = {acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+                    if (BIAS) o += b4;
+                    const unsigned int off = lane_off + (unsigned int)(32 * mi) * (unsigned int)a.ldc * 4u + col_off + (unsigned int)(8 * q) * 4u;
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4v, o), rc, off, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- prologue: three steps on their way, the first one landed
+    point_at(ct);
+    issue(0);
+    issue(1);
+    issue(2);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");      // the copies of the second and third step may be outstanding
+    asm volatile("s_barrier" ::: "memory");
+    bf8v fa0[2], fw0[4], fa1[2], fw1[4];
+    read_frags(0, 0, fa0, fw0);
+    clear_acc();
+
+    // Step T is multiplied from stage T % 3 while the copies of steps T + 1 and T + 2 are under way; after the
+    // barrier of step T its stage takes the copies of step T + 3.  At that barrier the copies of step T + 1 must
+    // have landed; behind them the wave has issued the six copies of step T + 2 (unless the list of steps has
+    // ended) and, for two steps after an output tile, its 32 stores.
+    int st = 0;                            // T % 3
+    int stores_behind = 0;                 // steps for which the stores of an output tile are still behind the copies waited for
+    for (;;) {
+        read_frags(st, 1, fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa0, fw0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (stores_behind) {
+            if (!l_end) asm volatile("s_waitcnt vmcnt(38) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(32) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            --stores_behind;
+        } else {
+            if (!l_end) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+        // the copies first: the arithmetic of a tile change needs the registers the fp32 fragments would hold
+        if (!l_end) issue(st);
+        st = st == 2 ? 0 : st + 1;
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(st, 0, fa0, fw0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa1, fw1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (++cks == nk) {
+            epilogue();
+            stores_behind = 2;
+            clear_acc();
+            cks = 0;
+            const int nt = (int)uniform((unsigned int)s_ring[++cn & 7]);
+            if (nt >= n_local) break;
+            ct = tile_of(nt);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+
 // --------------------------------------------------- dWx and dbias (TN product)
 struct DwArgs {
     const void *du;        // [M][G][H], storage type AT
@@ -1261,6 +1531,27 @@ bool nt_dma_ok(const GemmArgs &g)
            g.lda < (1 << 22) && g.ldb < (1 << 22) && g.ldc < (1 << 22) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.ldc % 8 == 0;
 }
 
+// the same for fp32 A and C: 32-k steps
+bool nt_dma_f32_ok(const GemmArgs &g)
+{
+    return g.K >= 3 * dmaf::BK && g.K % dmaf::BK == 0 && g.kseg % dmaf::BK == 0 && g.N % 64 == 0 &&
+           g.lda < (1 << 22) && g.ldb < (1 << 22) && g.ldc < (1 << 22) && g.lda % 4 == 0 && g.ldb % 8 == 0 && g.ldc % 4 == 0;
+}
+
+hipError_t launch_nt_dma_f32(GemmArgs &g, hipStream_t st)
+{
+    g.tiles_m = (g.M + dma::BM - 1) / dma::BM;
+    g.tiles_n = (g.N + dma::BN - 1) / dma::BN;
+    int slots = device_cu_count() / 8;
+    if (slots < 1) slots = 1;
+    if (slots > 64) slots = 64;
+    const long long per_wg = ((long long)(g.tiles_m + 7) / 8) * g.tiles_n * g.n_batch / slots;
+    g.draw = per_wg >= 32 ? 4 : per_wg >= 16 ? 2 : 1;
+    if (g.bias) hipLaunchKernelGGL((proj_gemm_nt_dma_f32_kernel<true>), dim3((unsigned)(8 * slots)), dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((proj_gemm_nt_dma_f32_kernel<false>), dim3((unsigned)(8 * slots)), dim3(512), 0, st, g);
+    return hipGetLastError();
+}
+
 hipError_t launch_nt_dma(GemmArgs &g, hipStream_t st)
 {
     g.tiles_m = (g.M + dma::BM - 1) / dma::BM;
@@ -1322,7 +1613,8 @@ int proj_forward(int dtype, const void *x, const float *Wx, const float *bias, i
     g.a_off[0] = 0; g.a_off[1] = dh;                   // columns of x (all gates of a head) are neighbours
     g.b_off[0] = (long long)H * dh; g.b_off[1] = (long long)dh * dh;
     g.c_off[0] = H; g.c_off[1] = dh;
-    const hipError_t e = dtype != PARARNN_BF16 ? launch_nt<float, float>(g, st)
+    const hipError_t e = dtype != PARARNN_BF16
+                             ? ((g_proj_dma && nt_dma_f32_ok(g)) ? launch_nt_dma_f32(g, st) : launch_nt<float, float>(g, st))
                          : (g_proj_dma && nt_dma_ok(g)) ? launch_nt_dma(g, st) : launch_nt<unsigned short, unsigned short>(g, st);
     return e == hipSuccess ? PARARNN_OK : PARARNN_HIP_ERROR;
 }
@@ -1352,7 +1644,7 @@ int proj_backward(int dtype, const void *x, const float *Wx, const void *du, int
         g.kseg = dh; g.kseg_stride = H;                 // k = (gate, i): gates are H apart in a row of du
         g.nz0 = n_heads; g.n_batch = n_heads;           // z0 = head
         g.a_off[0] = dh; g.b_off[0] = (long long)dh * G * dh; g.c_off[0] = dh;
-        e = !bf ? launch_nt<float, float>(g, st)
+        e = !bf ? ((g_proj_dma && nt_dma_f32_ok(g)) ? launch_nt_dma_f32(g, st) : launch_nt<float, float>(g, st))
             : (g_proj_dma && nt_dma_ok(g)) ? launch_nt_dma(g, st) : launch_nt<unsigned short, unsigned short>(g, st);
         if (e != hipSuccess) return PARARNN_HIP_ERROR;
     }
