@@ -97,8 +97,8 @@ def classes(kind):
             "iter": (r"^newton_iter_kernel<.*false>$", "work"),        # one iteration per launch, from the iterate
             "bwd": (r"^backward_kernel<", "work"),
             # the input projection in front of the solve (four heads; not part of the timed step)
-            "proj_fwd": (r"^proj_gemm_nt(_dma)?_kernel<.*true>", "work"),
-            "proj_dx": (r"^proj_gemm_nt(_dma)?_kernel<.*false>", "work"),
+            "proj_fwd": (r"^proj_gemm_nt(_dma(_f32)?)?_kernel<.*true>", "work"),
+            "proj_dx": (r"^proj_gemm_nt(_dma(_f32)?)?_kernel<.*false>", "work"),
             "proj_dw": (r"^proj_dw_(dma_)?kernel", "work")}
 
 
