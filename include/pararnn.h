@@ -145,13 +145,13 @@ int pararnn_set_spin_limit(unsigned int polls);
 int pararnn_set_fused(int enable);
 
 /* Test / tuning hook (host, process-wide; default 1): enable = 0 keeps the kernels
- * from copying their inputs straight from memory into LDS one tile ahead (the
- * variant used for bf16 storage when rows are 16-byte aligned and H % 8 == 0:
- * the backward kernel of the diagonal cells, and the forward and dx products
- * of the input projection at d_h >= 128); they then load through registers, as
- * for every other storage type.  The backward kernel gives the same bits
- * either way; the projection's two kernels sum in different orders and agree
- * to fp32 rounding. */
+ * from copying their inputs straight from memory into LDS ahead of their use:
+ * the backward kernel of the diagonal cells (bf16 storage, rows 16-byte
+ * aligned, H % 8 == 0), the forward and dx products of the input projection
+ * (d_h >= 128; either storage type) and its weight-gradient sums (bf16 storage,
+ * d_h = 192, 256, 448 and up).  They then load through registers.  The
+ * backward kernel gives the same bits either way; the projection's kernels sum
+ * in different orders and agree to fp32 rounding. */
 int pararnn_set_staging(int enable);
 
 /* Tuning hook (host, process-wide): a solve to a tolerance (tol >= 0) runs its
