@@ -87,7 +87,7 @@ inline TileCfg choose_tile(const CellInfo &ci, int dtype, bool backward, int H, 
         else if (lstm && !bf) cfg = {1, 2, 8, 8};        // 32 channels x 128 steps (3 % faster than 64 x 128 on config 3)
         else if (lstm) cfg = {1, 1, 16, 8};              // 64 channels x 128 steps
         else if (bf) cfg = {1, 1, 8, 8};                 // 64 channels x 64 steps
-        else cfg = {1, 2, 8, 16};                        // 32 channels x 256 steps
+        else cfg = {1, 1, 8, 16};                        // 64 channels x 128 steps (3-4 % faster than 32 x 256 on config 2)
     }
     int *ov = settings().tile;
     if (ov[0] == -1) {
