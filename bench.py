@@ -290,6 +290,16 @@ def headline_extras(run, rec, reps, counters):
     # blocks of Newton iterations of the plan; the first two are launches of their own, the rest share one
     rec["blocks"] = P.solve_plan(w.tol, w.max_iter) if w.cell != "tanh_dense" else None
     rec["launches_per_solve"] = min(len(rec["blocks"]), 3) if rec["blocks"] is not None else None
+    if w.cell != "tanh_dense":
+        # the same step under pararnn_set_workspace_reuse (the caller's promise that nothing else writes to the
+        # two workspaces between calls: true for this loop): the carry records are not cleared again
+        try:
+            P.set_workspace_reuse(True)
+            ms = run.timed_steps(20, 3)
+        finally:
+            P.set_workspace_reuse(False)
+        rec["workspace_reuse"] = {"ms_per_step": ms, "value": N / (ms * 1e-3),
+                                  "note": "opt-in mode, not the headline: pararnn_set_workspace_reuse(1)"}
     if w.cell == "tanh_dense":
         dfac, Aout = run.extra
         # not part of the step (config 4 is forward only): the adjoint scan of the same cell

@@ -29,6 +29,7 @@ struct Settings {
     unsigned int spin_limit;   // polls of one predecessor before a tile gives up (pararnn_set_spin_limit)
     int stage_enabled;         // kernels that copy their inputs straight into LDS are allowed (pararnn_set_staging)
     int fused_tail;            // the blocks after a solve's first launch share one persistent launch (pararnn_set_fused_tail)
+    int ws_reuse;              // the caller promises that nothing else writes to a workspace between calls (pararnn_set_workspace_reuse)
 };
 Settings &settings();
 
@@ -110,6 +111,27 @@ struct Layout {
     size_t off_rec, n_rec, off_bnd, off_iter, off_part, total;
 };
 
+// What decides where a call's carry records lie and how they are read: two calls with the same
+// signature on the same workspace use every record word for the same thing.  Never 0.
+inline unsigned long long layout_signature(int pass, const CellInfo &ci, int dtype, const Layout &lo, int rec_slots)
+{
+    unsigned long long h = 1469598103934665603ull;
+    const long long v[] = {pass, ci.kind, ci.S, ci.G, ci.PR, dtype, lo.g.B, lo.g.L, lo.g.H, lo.g.T, lo.g.n_lt, lo.g.n_cg,
+                           lo.cfg.vec, lo.cfg.ll, lo.cfg.c, lo.cfg.w, rec_slots, (long long)lo.n_rec,
+                           (long long)lo.off_rec, (long long)lo.total};
+    for (long long x : v) {
+        for (int i = 0; i < 8; ++i) {
+            h ^= (unsigned long long)(x >> (8 * i)) & 0xffull;
+            h *= 1099511628211ull;
+        }
+    }
+    return h ? h : 1ull;
+}
+
+// largest max_iter whose epochs fit below the per-call number in a record tag (tag = epoch * 4 + state,
+// epoch = number * 1024 + iteration)
+constexpr int kMaxIterWithReuse = 1000;
+
 // Workspace: [Ctrl | carry records (rec_slots sets) | boundary rows | fp32 iterate (bf16 forward) |
 // parameter-gradient partials (backward)]
 inline Layout make_layout(const CellInfo &ci, int dtype, int B, int L, int H, bool backward, int align_elems,
@@ -125,6 +147,7 @@ inline Layout make_layout(const CellInfo &ci, int dtype, int B, int L, int H, bo
     g.n_groups = B * g.n_cg;
     g.n_tiles = g.n_groups * g.n_lt;
     g.spin_limit = settings().spin_limit;
+    g.epoch_base = 0;
     const size_t NW = (size_t)ci.S * ci.S + 2 * ci.S;
     size_t off = round256(sizeof(Ctrl));
     lo.n_rec = (size_t)g.n_tiles * NW * CW;
@@ -219,7 +242,11 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
     const bool to_tol = a.tol >= 0.0f;
     hipError_t e;
     a.hit = bf ? reinterpret_cast<float *>(ws + lo.off_iter) : static_cast<float *>(h);
-    e = launch_reset(a.ctrl, a.rec, lo.n_rec * (size_t)(n_fused > 0 ? n_fused : 1), a.iters_out, status0, st);
+    const int slots = n_fused > 0 ? n_fused : 1;
+    bool fill = true;
+    if (max_iter <= kMaxIterWithReuse) a.g.epoch_base = workspace_epoch(ws, layout_signature(0, ci, dtype, lo, slots), st, &fill);
+    else workspace_forget(ws);
+    e = launch_reset(a.ctrl, a.rec, fill ? lo.n_rec * (size_t)slots : 0, a.iters_out, status0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     if (max_iter == 0) {
         // only the initial guess is asked for; otherwise the first iteration computes it on the fly
@@ -272,7 +299,9 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
 template <class Cell>
 int backward_diag(const CellInfo &ci, int dtype, const Layout &lo, BwdArgs &a, hipStream_t st, float *dparams)
 {
-    hipError_t e = launch_reset(a.ctrl, a.rec, lo.n_rec, nullptr, 0, st);
+    bool fill = true;
+    a.g.epoch_base = workspace_epoch(a.ctrl, layout_signature(1, ci, dtype, lo, 1), st, &fill);
+    hipError_t e = launch_reset(a.ctrl, a.rec, fill ? lo.n_rec : 0, nullptr, 0, st);
     if (e != hipSuccess) return PARARNN_HIP_ERROR;
     e = dtype == PARARNN_BF16 ? Kernels<Cell, unsigned short>::backward(lo.cfg, a, st)
                               : Kernels<Cell, float>::backward(lo.cfg, a, st);
@@ -343,7 +372,9 @@ int forward_solve(const CellInfo &ci, int dtype, const float *params, const void
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
     a.iters_out = iters; a.trace = delta_trace;
     a.k = 0; a.max_iter = max_iter; a.tol = tol;
-    return forward_diag<Cell>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
+    const int rc = forward_diag<Cell>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
+    if (rc != PARARNN_OK) workspace_forget(workspace);
+    return rc;
 }
 
 // Residual max-norm of given states (App. A); out is a device float.
@@ -403,7 +434,9 @@ int backward_pass(const CellInfo &ci, int dtype, const float *params, const void
     // boundaries, and row offsets that stay inside the 32-bit range of a buffer instruction
     a.stage = settings().stage_enabled && dtype == PARARNN_BF16 && H % 8 == 0 && aligned(u, 16) && aligned(h, 16) &&
               aligned(dL_dh, 16) && (double)H * 2.0 * (16.0 * ci.G) < 4.0e9;
-    return backward_diag<Cell>(ci, dtype, lo, a, st, dL_dparams);
+    const int rc = backward_diag<Cell>(ci, dtype, lo, a, st, dL_dparams);
+    if (rc != PARARNN_OK) workspace_forget(workspace);
+    return rc;
 }
 
 }  // namespace pararnn

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             constexpr int kMode = decltype(mode)::value;
 #pragma unroll 1
             for (int k = 1; k <= K; ++k) {
-                const unsigned int epoch = (unsigned int)(k0 + k);        // unique within the call
+                const unsigned int epoch = g.epoch_base + (unsigned int)(k0 + k);   // unique within the call
                 unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
 
                 // ---- thread level

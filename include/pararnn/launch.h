@@ -41,4 +41,13 @@ hipError_t launch_zero_words(unsigned int *dst, int n, hipStream_t st);
 hipError_t launch_param_reduce(const float *part, float *out, int n_terms, int n_out, hipStream_t st);
 int device_cu_count();
 
+// Workspaces that are reused across calls (pararnn_set_workspace_reuse).  Returns the number this call adds
+// to the epoch in its record tags and sets *fill to whether the carry records have to be cleared: not when
+// the last call that used this workspace on this device had the same layout signature, in which case its
+// records carry another number and read as empty.  Without the caller's promise, under stream capture (a
+// captured launch sequence would replay one number) and for a new address or signature: 0 / 1 and *fill = true.
+unsigned int workspace_epoch(void *workspace, unsigned long long layout_sig, hipStream_t st, bool *fill);
+// The library no longer knows what this workspace holds (a call on it failed, or ran without a signature).
+void workspace_forget(void *workspace);
+
 }  // namespace pararnn

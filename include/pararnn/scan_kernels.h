@@ -47,6 +47,7 @@ struct ScanGeom {
     int n_groups;  // B * n_cg
     int n_tiles;   // n_groups * n_lt
     unsigned int spin_limit;   // polls of one predecessor before a tile gives up
+    unsigned int epoch_base;   // added to the epoch in every record tag of this call (0 unless the workspace is reused)
 };
 
 struct FwdArgs {
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keep it scalar
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
-    const unsigned int epoch = (unsigned int)a.k;
+    const unsigned int epoch = g.epoch_base + (unsigned int)a.k;
     const UT *u = static_cast<const UT *>(a.u);
     const int cur = a.bnd_cur, nxt = cur ^ 1;
     // max |delta| as its bit pattern: for non-negative floats the unsigned order is the float order, and
@@ -934,7 +935,7 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keep it scalar
     const int seg = lane / LPS, col = (lane % LPS) * VEC;
-    const unsigned int epoch = 1u;
+    const unsigned int epoch = g.epoch_base + 1u;
     const UT *u = static_cast<const UT *>(a.u);
     const UT *hres = static_cast<const UT *>(a.h);
     const UT *gl = static_cast<const UT *>(a.gl);

@@ -40,6 +40,7 @@ _lib.pararnn_workspace_bytes_fused.restype = _sz
 _lib.pararnn_workspace_bytes_fused.argtypes = [_i] * 6
 _lib.pararnn_set_fused.argtypes = [_i]
 _lib.pararnn_set_fused_tail.argtypes = [_i]
+_lib.pararnn_set_workspace_reuse.argtypes = [_i]
 _lib.pararnn_set_staging.argtypes = [_i]
 _lib.pararnn_set_dense_products.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
@@ -227,6 +228,12 @@ def solve_plan(tol: float, max_iter: int):
     if n < 0:
         raise ValueError("pararnn_solve_plan: invalid arguments")
     return [buf[i] for i in range(n)]
+
+
+def set_workspace_reuse(enable: bool = False) -> None:
+    """pararnn_set_workspace_reuse: the caller's promise that nothing else writes to a workspace between the
+    library's calls on it; the carry records are then not cleared again for a call of the same layout."""
+    _raise(_lib.pararnn_set_workspace_reuse(int(enable)), "pararnn_set_workspace_reuse")
 
 
 def set_fused_tail(enable: bool = True) -> None:

@@ -1,6 +1,7 @@
 // C ABI of the library (see include/pararnn.h) for the built-in cells; the
 // cell-generic host driver is driver.h.  No kernel code here.
 #include <mutex>
+#include <unordered_map>
 
 #include "dense.h"
 #include "cells.h"
@@ -13,8 +14,54 @@ namespace pararnn {
 
 Settings &settings()
 {
-    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1, 1};
+    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1, 1, 0};
     return s;
+}
+
+// ---- workspaces the caller has promised to leave alone between calls
+namespace {
+struct WorkspaceNote {
+    unsigned long long sig;    // layout signature of the last call that used the workspace
+    unsigned int number;       // that call's number (1 .. 2^20 - 1)
+};
+std::mutex g_ws_mutex;
+std::unordered_map<unsigned long long, WorkspaceNote> g_ws_notes;      // by device and address
+
+unsigned long long ws_key(const void *workspace)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+    return ((unsigned long long)(unsigned int)dev << 56) ^ (unsigned long long)(uintptr_t)workspace;
+}
+}  // namespace
+
+unsigned int workspace_epoch(void *workspace, unsigned long long layout_sig, hipStream_t st, bool *fill)
+{
+    *fill = true;
+    const unsigned long long key = ws_key(workspace);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+    if (!settings().ws_reuse || capturing) {
+        g_ws_notes.erase(key);
+        return 0u;
+    }
+    WorkspaceNote &n = g_ws_notes[key];                // a new note has sig 0, which no call has
+    if (n.sig == layout_sig && n.number >= 1u && n.number < (1u << 20) - 1u) {
+        ++n.number;
+        *fill = false;
+    } else {
+        n.sig = layout_sig;
+        n.number = 1u;
+    }
+    return n.number << 10;
+}
+
+void workspace_forget(void *workspace)
+{
+    const unsigned long long key = ws_key(workspace);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_ws_notes.erase(key);
 }
 
 }  // namespace pararnn
@@ -158,6 +205,12 @@ int pararnn_set_fused_tail(int enable)
     return PARARNN_OK;
 }
 
+int pararnn_set_workspace_reuse(int enable)
+{
+    settings().ws_reuse = enable ? 1 : 0;
+    return PARARNN_OK;
+}
+
 int pararnn_solve_plan(float tol, int max_iter, int *block_sizes, int capacity)
 {
     if (max_iter < 0 || tol != tol || (capacity > 0 && !block_sizes)) return -1;
@@ -207,6 +260,7 @@ int forward_with(int cell, int dtype, const float *params, const void *u, const 
                         workspace_bytes, st, opts)
     switch (cell) {
     case PARARNN_TANH_DENSE:
+        workspace_forget(workspace);
         return dense_forward(dtype, params, u, h0, B, L, H, tol, max_iter, h, iters, delta_trace, workspace,
                              workspace_bytes, st);
     case PARARNN_GRU_DIAG: return PARARNN_FWD(GruDiag);
@@ -291,6 +345,7 @@ int pararnn_backward(int cell, int dtype, const float *params, const void *u, co
                         workspace_bytes, st)
     switch (cell) {
     case PARARNN_TANH_DENSE:
+        workspace_forget(workspace);
         return dense_backward(dtype, params, u, h0, h, dL_dh, B, L, H, dL_du, dL_dparams, dL_dh0, workspace,
                               workspace_bytes, st);
     case PARARNN_GRU_DIAG: return PARARNN_BWD(GruDiag);
@@ -383,6 +438,7 @@ int pararnn_affine_scan(int kind, int reverse, const float *J, const float *r, i
     const int al = align_elems(4, {J, r, delta});
     const Layout lo = scan_layout(kind, reverse, B, L, H, al);
     if (workspace_bytes < lo.total) return PARARNN_WORKSPACE_TOO_SMALL;
+    workspace_forget(workspace);
     char *ws = static_cast<char *>(workspace);
     Ctrl *ctrl = reinterpret_cast<Ctrl *>(ws);
     unsigned long long *rec = reinterpret_cast<unsigned long long *>(ws + lo.off_rec);
@@ -409,6 +465,7 @@ int pararnn_input_projection(int dtype, const void *x, const float *Wx, const fl
                              int G, int n_heads, void *u, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!x || !Wx || !u || !workspace || !aligned(workspace, 256)) return PARARNN_INVALID_ARG;
+    workspace_forget(workspace);
     return proj_forward(dtype, x, Wx, bias, B, L, H, G, n_heads, u, workspace, workspace_bytes,
                         static_cast<hipStream_t>(hip_stream));
 }
@@ -418,6 +475,7 @@ int pararnn_input_projection_backward(int dtype, const void *x, const float *Wx,
                                       void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!x || !Wx || !du || !workspace || !aligned(workspace, 256) || (dbias && !dWx)) return PARARNN_INVALID_ARG;
+    workspace_forget(workspace);
     return proj_backward(dtype, x, Wx, du, B, L, H, G, n_heads, dx, dWx, dbias, workspace, workspace_bytes,
                          static_cast<hipStream_t>(hip_stream));
 }
@@ -436,6 +494,7 @@ int pararnn_dense_chunk_products(const float *W, const float *d, int B, int L, i
     if (!dims_ok(B, L, H) || !W || !d || !A || !workspace) return PARARNN_INVALID_ARG;
     if (!aligned(workspace, 256)) return PARARNN_INVALID_ARG;
     if (workspace_bytes < 256) return PARARNN_WORKSPACE_TOO_SMALL;
+    workspace_forget(workspace);
     return dense_chunk_products(W, d, B, L, H, A, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
