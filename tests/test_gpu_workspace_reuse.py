@@ -117,3 +117,37 @@ def test_reuse_under_graph_capture_clears_every_time():
             assert same(got, (h_e, it_e.cpu(), du_e, dp_e, dh0_e)), rep
     finally:
         P.set_workspace_reuse(False)
+
+
+def test_reuse_on_the_library_own_scratch():
+    """pararnn_forward_noalloc keeps its workspace inside the library, so the promise holds by itself:
+    the same problem twice (second call: records not cleared), another input, a smaller shape (another
+    layout: cleared), against pararnn_forward on a caller's workspace."""
+    import paper_2510_21450_amd as P
+    from workloads.rng import normal, uniform_sym
+    cell = "gru_diag"
+    G, S = cell_dims(cell)
+
+    def solve(B, L, H, seed, scale):
+        params = torch.zeros(2, G, H, device="cuda")
+        params[0] = uniform_sym(seed, 2, (G, H), 0.9, device="cuda")
+        u = normal(seed, 1, (B, L, G, H), device="cuda") * scale
+        h0 = normal(seed, 3, (B, S, H), std=0.3, device="cuda")
+        P.set_workspace_reuse(False)
+        h_ref, it_ref, _ = P.forward(cell, params, u, h0, tol=1e-5, max_iter=24)
+        torch.cuda.synchronize()
+        P.set_workspace_reuse(True)
+        h = torch.full((B, L, S, H), float("nan"), device="cuda")
+        iters = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+        code = P.forward_noalloc(cell, params, u, h0, 1e-5, 24, h, iters)
+        torch.cuda.synchronize()
+        assert code == 0, P.status_string(code)
+        assert iters.cpu().tolist() == it_ref.cpu().tolist() and torch.equal(h, h_ref)
+
+    try:
+        for B, L, H, seed, scale in ((2, 1200, 128, 71, 1.0), (2, 1200, 128, 71, 1.0), (2, 1200, 128, 72, 1.3),
+                                     (1, 500, 64, 73, 1.0), (2, 1200, 128, 71, 0.7)):
+            print(f"noalloc with reuse B={B} L={L} H={H} seed={seed} scale={scale}", flush=True)
+            solve(B, L, H, seed, scale)
+    finally:
+        P.set_workspace_reuse(False)
