@@ -313,6 +313,33 @@ __device__ __forceinline__ bool lookback(unsigned int spin_limit, const rec_t *r
     }
 }
 
+// One look at the neighbour in direction `dir`: true, and its inclusive value in `carry`, when that is already
+// there.  The tile then has no need to publish its own aggregate (two thirds of a tile's record words): whoever
+// asks this tile will find its inclusive value, which follows at once.  Called like lookback().
+template <int S, int VEC, int CW>
+__device__ __forceinline__ bool neighbour_inclusive(const rec_t *rec_base, int n_lt, int grp, int lt, int dir,
+                                                    unsigned int epoch, int col, bool active, float (&carry)[S][VEC])
+{
+    constexpr int SS = S * S, NW = SS + 2 * S;
+    const unsigned int tag_inc = epoch * 4u + kFlagIncl;
+    const rec_t *rj = rec_base + ((size_t)grp * n_lt + (lt + dir)) * (NW * CW) + col;
+    rec_t wi[S][VEC];
+    bool ok = true;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            wi[s][v] = active ? rec_load(rj + (SS + S + s) * CW + v) : 0;
+            ok = ok && (unsigned int)(wi[s][v] >> 32) == tag_inc;
+        }
+    if (!__all(ok || !active)) return false;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) carry[s][v] = __uint_as_float((unsigned int)wi[s][v]);
+    return true;
+}
+
 template <int N, int VEC, int CW>
 __device__ __forceinline__ void publish(rec_t *rec_rows, const float (&val)[N][VEC], unsigned int tag, int col,
                                         bool active)
@@ -643,7 +670,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
             const bool active = seg == 0;
             const bool has_next = lt + 1 < g.n_lt;
             rec_t *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (NW * CW);
-            if (lt > 0) {
+            if (lt > 0 && !neighbour_inclusive<S, VEC, CW>(a.rec, g.n_lt, grp, lt, -1, epoch, col, active, carry)) {
                 if (has_next) {
                     float ab[SS + S][VEC];
 #pragma unroll
@@ -1300,7 +1327,7 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             const bool active = seg == 0;
             const bool has_next = lt > 0;            // a tile to the left will ask
             rec_t *rec = a.rec + ((size_t)grp * g.n_lt + lt) * (NW * CW);
-            if (lt + 1 < g.n_lt) {
+            if (lt + 1 < g.n_lt && !neighbour_inclusive<S, VEC, CW>(a.rec, g.n_lt, grp, lt, +1, epoch, col, active, carry)) {
                 if (has_next) {
                     float ab[SS + S][VEC];
 #pragma unroll
