@@ -18,7 +18,8 @@ and writes
 
 The byte counters are calibrated on the copy in the same run: a copy of n bytes
 fetches n and writes n, so the factor of each counter is n over what it read.
-Raw rocprofv3 output stays under gpurun_out/.  Run on the GPU machine from the repository root:
+Raw rocprofv3 output goes to an untracked scratch folder (RAW_OUT below), with a second copy of the summaries
+and of counters.json.  Run on the machine with the GPU, from the repository root:
 
     python3 bench_profile.py C5 C2 C3 C4
 """
@@ -32,6 +33,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+RAW_OUT = os.path.join(ROOT, "gpurun_out", "profile")     # raw profiler output and a second copy of the results: not tracked
 sys.path.insert(0, ROOT)
 import bench  # noqa: E402  (constants and the source hash; nothing here touches the GPU)
 
@@ -230,7 +232,7 @@ def profile_config(cfg, outdir):
             continue
         lines.append(f"  {k:96s} {len(v):5d} {mean(v):10.1f} {min(v):10.1f} {max(v):10.1f}")
     fname = PROFILE_NAMES.get(cfg, cfg) + ".txt"
-    # beside the tracked copy, one under gpurun_out/ (the folder that comes back from the GPU machine)
+    # beside the tracked copy, one in the scratch folder of the raw output
     for path in (os.path.join(ROOT, "profiles", fname), os.path.join(outdir, fname)):
         open(path, "w").write("\n".join(lines) + "\n")
         print(f"[profile] wrote {path}", flush=True)
@@ -239,7 +241,7 @@ def profile_config(cfg, outdir):
 
 def main():
     cfgs = sys.argv[1:] or ["C5", "C2", "C3", "C4"]
-    outdir = os.path.join(ROOT, "gpurun_out", "profile")
+    outdir = RAW_OUT
     import ctypes
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2510_21450_amd", "libpararnn.so"))
     path = bench.COUNTERS_JSON
