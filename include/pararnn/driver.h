@@ -270,13 +270,13 @@ int forward_diag(const CellInfo &ci, int dtype, const Layout &lo, FwdArgs &a, hi
         if (to_tol && n_fused > 0 && launches == 2 && tail) {
             // everything after the second block in one launch that goes through the plan on the device (the
             // second block is one iteration, which the per-iteration kernel does faster than a fused block)
-            f.n_iters = K; f.k0 = done; f.bnd_cur = cur; f.tail = 1; f.launch_no = launches;
+            f.n_iters = K; f.k0 = done; f.epoch0 = f.g.epoch_base + (unsigned int)done; f.bnd_cur = cur; f.tail = 1; f.launch_no = launches;
             e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
             if (e != hipSuccess) return e == hipErrorInvalidValue ? PARARNN_UNSUPPORTED : PARARNN_HIP_ERROR;
             break;
         }
         if (n_fused > 0 && (K > 1 || done == 0)) {
-            f.n_iters = K; f.k0 = done; f.bnd_cur = cur; f.tail = 0; f.launch_no = launches;
+            f.n_iters = K; f.k0 = done; f.epoch0 = f.g.epoch_base + (unsigned int)done; f.bnd_cur = cur; f.tail = 0; f.launch_no = launches;
             e = bf ? Kernels<Cell, unsigned short>::newton_fused(lo.cfg, f, st) : Kernels<Cell, float>::newton_fused(lo.cfg, f, st);
         } else {
             a.k = done + 1; a.bnd_cur = cur;

@@ -49,6 +49,7 @@ struct FusedArgs {
     // block of a solve to a tolerance (head != 0)
     int head;
     int k0;                  // iterations performed before this launch
+    unsigned int epoch0;     // g.epoch_base + k0: the record tags' epoch of iteration k of this launch is epoch0 + k
     int max_iter;            // of the whole solve
     float tol;
     float *hit;              // fp32 iterate, read when k0 > 0 and written when more launches may follow;
@@ -282,7 +283,9 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
             constexpr int kMode = decltype(mode)::value;
 #pragma unroll 1
             for (int k = 1; k <= K; ++k) {
-                const unsigned int epoch = g.epoch_base + (unsigned int)(k0 + k);   // unique within the call
+                // unique within the call; the one-block variant takes the sum of the constant part from the kernel
+                // arguments (one more value that lives through the block costs it registers it does not have)
+                const unsigned int epoch = TAIL ? g.epoch_base + (unsigned int)(k0 + k) : a.epoch0 + (unsigned int)k;
                 unsigned long long *reck = a.rec + (size_t)(k - 1) * a.rec_stride;
 
                 // ---- thread level
