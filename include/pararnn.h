@@ -154,6 +154,17 @@ int pararnn_set_fused(int enable);
  * in different orders and agree to fp32 rounding. */
 int pararnn_set_staging(int enable);
 
+/* Test / tuning hook (host, process-wide; default 0).  The kernels that run at
+ * the speed of the memory (one Newton iteration per launch; the backward pass
+ * for bf16 storage) can mark their tile accesses as streamed, which keeps
+ * them out of the way of what the device's memory-side cache holds from the
+ * launch before.  mode 0: chosen per call from the sizes of the tensors (u is
+ * streamed once u and the fp32 iterate together exceed that cache, the iterate
+ * and the backward pass's tensors once they exceed twice its size); 1: never;
+ * 2: always.  The results are the same bits in every mode.  Returns
+ * PARARNN_INVALID_ARG for another mode. */
+int pararnn_set_streaming(int mode);
+
 /* Tuning hook (host, process-wide): a solve to a tolerance (tol >= 0) runs its
  * first min(n_iters, max_iter) iterations in ONE launch of the fused kernel (u
  * read once, the iterate kept in registers), then blocks of 1, 2, 4, ...

@@ -133,24 +133,28 @@ __device__ __forceinline__ void raw_to_float(const typename RawVec<T, VEC>::type
 // so a batch of row loads needs no per-load vector address arithmetic.
 typedef __amdgpu_buffer_rsrc_t buf_rsrc;
 
+// Cache-policy bits of a buffer access (gfx950: 1 = sc0, 2 = nt, 16 = sc1).  nt marks a line as
+// streamed: it is the first to leave the L2 and does not displace what the memory-side cache holds.
+constexpr int kAuxNone = 0, kAuxStream = 2;
+
 __device__ __forceinline__ buf_rsrc make_rsrc(const void *base)
 {
     // raw buffer, no swizzle, whole 4 GiB window from base (tiles are far smaller)
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xffffffffu, 0x27000);
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, int AUX = kAuxNone>
 __device__ __forceinline__ typename RawVec<T, VEC>::type buf_load(buf_rsrc r, unsigned int voff, unsigned int soff)
 {
     using R = typename RawVec<T, VEC>::type;
     constexpr int BYTES = sizeof(T) * VEC;
-    if constexpr (BYTES == 2) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0));
-    else if constexpr (BYTES == 4) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
-    else if constexpr (BYTES == 8) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
-    else return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+    if constexpr (BYTES == 2) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, AUX));
+    else if constexpr (BYTES == 4) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, AUX));
+    else if constexpr (BYTES == 8) return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, AUX));
+    else return __builtin_bit_cast(R, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, AUX));
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, int AUX = kAuxNone>
 __device__ __forceinline__ void buf_store(buf_rsrc r, unsigned int voff, unsigned int soff, const float (&in)[VEC])
 {
     using R = typename RawVec<T, VEC>::type;
@@ -162,14 +166,14 @@ __device__ __forceinline__ void buf_store(buf_rsrc r, unsigned int voff, unsigne
         if constexpr (sizeof(T) == 4) e[i] = in[i];
         else e[i] = f32_to_bf16(in[i]);
     }
-    if constexpr (BYTES == 2) __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), r, voff, soff, 0);
-    else if constexpr (BYTES == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r, voff, soff, 0);
+    if constexpr (BYTES == 2) __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), r, voff, soff, AUX);
+    else if constexpr (BYTES == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r, voff, soff, AUX);
     else if constexpr (BYTES == 8) {
         typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, v), r, voff, soff, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, v), r, voff, soff, AUX);
     } else {
         typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), r, voff, soff, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), r, voff, soff, AUX);
     }
 }
 

@@ -30,6 +30,7 @@ struct Settings {
     int stage_enabled;         // kernels that copy their inputs straight into LDS are allowed (pararnn_set_staging)
     int fused_tail;            // the blocks after a solve's first launch share one persistent launch (pararnn_set_fused_tail)
     int ws_reuse;              // the caller promises that nothing else writes to a workspace between calls (pararnn_set_workspace_reuse)
+    int streaming;             // streamed accesses of the HBM-bound kernels: 0 chosen by size, 1 never, 2 always (pararnn_set_streaming)
 };
 Settings &settings();
 
@@ -47,6 +48,30 @@ inline SolveOpts default_opts()
 }
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// The memory-side cache of the device (256 MiB) keeps what a launch wrote or read for the next one when
+// it is left room.  A per-iteration launch reads u and reads and rewrites the fp32 iterate: u is
+// streamed as soon as the two together exceed that cache (the iterate then has it to itself: measured
+// 8 % on 0.8 GB of u with a 0.27 GB iterate), the iterate too once it is larger than twice the cache,
+// where nothing of it survives until the next launch and streamed accesses are the faster ones (3 %).
+constexpr size_t kMemCacheBytes = (size_t)256 << 20;
+inline int forward_stream_level(size_t u_bytes, size_t iterate_bytes)
+{
+    const int mode = settings().streaming;
+    if (mode == 1) return 0;
+    if (mode == 2) return 2;
+    if (iterate_bytes > 2 * kMemCacheBytes) return 2;
+    return u_bytes + iterate_bytes > kMemCacheBytes ? 1 : 0;
+}
+// The backward kernel for bf16 storage reads and writes every byte once: streamed when its tensors
+// together exceed twice the cache (4 % on 17 GB).  The fp32 kernels gain nothing either way (measured).
+inline int backward_stream(size_t bytes)
+{
+    const int mode = settings().streaming;
+    if (mode == 1) return 0;
+    if (mode == 2) return 1;
+    return bytes > 2 * kMemCacheBytes ? 1 : 0;
+}
 
 // Tile shape for a problem.  The table is the result of sweeps on MI355X over
 // the compiled shapes (fp32 and bf16 storage, forward and backward, GRU and
@@ -372,6 +397,10 @@ int forward_solve(const CellInfo &ci, int dtype, const float *params, const void
     a.ctrl = reinterpret_cast<Ctrl *>(ws);
     a.iters_out = iters; a.trace = delta_trace;
     a.k = 0; a.max_iter = max_iter; a.tol = tol;
+    {
+        const size_t n = (size_t)B * L * H, esz = dtype == PARARNN_BF16 ? 2 : 4;
+        a.stream = forward_stream_level(n * ci.G * esz, n * ci.S * sizeof(float));
+    }
     const int rc = forward_diag<Cell>(ci, dtype, lo, a, st, h, status0, max_iter, n_fused);
     if (rc != PARARNN_OK) workspace_forget(workspace);
     return rc;
@@ -434,6 +463,7 @@ int backward_pass(const CellInfo &ci, int dtype, const float *params, const void
     // boundaries, and row offsets that stay inside the 32-bit range of a buffer instruction
     a.stage = settings().stage_enabled && dtype == PARARNN_BF16 && H % 8 == 0 && aligned(u, 16) && aligned(h, 16) &&
               aligned(dL_dh, 16) && (double)H * 2.0 * (16.0 * ci.G) < 4.0e9;
+    a.stream = dtype == PARARNN_BF16 ? backward_stream((size_t)B * L * H * 2 * (2 * ci.G + 2 * ci.S)) : 0;
     const int rc = backward_diag<Cell>(ci, dtype, lo, a, st, dL_dparams);
     if (rc != PARARNN_OK) workspace_forget(workspace);
     return rc;

@@ -67,6 +67,7 @@ struct FwdArgs {
     int k;               // Newton iteration (1-based); also the flag epoch
     int max_iter;
     float tol;
+    int stream;          // cache policy of interior tiles: 0 plain accesses, 1 u is read as a stream, 2 the iterate as well
 };
 
 // arguments of the residual max-norm (App. A)
@@ -93,6 +94,7 @@ struct BwdArgs {
     unsigned long long *rec;
     Ctrl *ctrl;
     int stage;           // the tensors allow the LDS-staged kernel variant (16-byte aligned rows)
+    int stream;          // bf16 storage: interior tiles read and write their rows as streams
 };
 
 // ------------------------------------------------------------ small matrix ops
@@ -439,15 +441,17 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
         RawF hor[FIRST ? 1 : C][S], jrr[kRaw ? C : 1][kRaw ? SS : 1];
         float hprev[S][VEC];
         const bool full_tile = (lt + 1) * T <= g.L && (cg + 1) * CW <= g.H;
-        auto load_inputs = [&](auto guard) {
+        auto load_inputs = [&](auto guard, auto stream) {
             constexpr bool kGuard = decltype(guard)::value;
+            constexpr int kAuxU = decltype(stream)::value >= 1 ? kAuxStream : kAuxNone;
+            constexpr int kAuxHld = decltype(stream)::value >= 2 ? kAuxStream : kAuxNone;
 #pragma unroll
             for (int i = 0; i < C; ++i) {
                 const int l = l0 + i;
                 const bool ok = !kGuard || (ch_ok && l < g.L);
 #pragma unroll
                 for (int q = 0; q < G; ++q) {
-                    if constexpr (!kGuard) uur[i][q] = buf_load<UT, VEC>(ru, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT));
+                    if constexpr (!kGuard) uur[i][q] = buf_load<UT, VEC, kAuxU>(ru, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT));
                     else if (ok) uur[i][q] = load_raw<UT, VEC>(u + ((seq + l) * G + q) * g.H + ch);
                     else uur[i][q] = zero_raw<UT, VEC>();
                 }
@@ -455,7 +459,7 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
 #pragma unroll
                     for (int s = 0; s < S; ++s) {
                         if (!kRaw || a.raw_add) {
-                            if constexpr (!kGuard) hor[i][s] = buf_load<float, VEC>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u);
+                            if constexpr (!kGuard) hor[i][s] = buf_load<float, VEC, kAuxHld>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u);
                             else if (ok) hor[i][s] = load_raw<float, VEC>(a.hit + ((seq + l) * S + s) * g.H + ch);
                             else hor[i][s] = zero_raw<float, VEC>();
                         } else {
@@ -473,8 +477,12 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 }
             }
         };
-        if (full_tile) load_inputs(std::false_type{});
-        else load_inputs(std::true_type{});
+        // which tensors are streamed is the host's choice (they stay out of the caches' way when the
+        // iteration's working set is larger than the memory-side cache)
+        if (!full_tile) load_inputs(std::true_type{}, std::integral_constant<int, 0>{});
+        else if (a.stream >= 2) load_inputs(std::false_type{}, std::integral_constant<int, 2>{});
+        else if (a.stream == 1) load_inputs(std::false_type{}, std::integral_constant<int, 1>{});
+        else load_inputs(std::false_type{}, std::integral_constant<int, 0>{});
         if constexpr (FIRST) {
 #pragma unroll
             for (int q = 0; q < G; ++q) {
@@ -728,7 +736,12 @@ __global__ __launch_bounds__(kWave *W) void newton_iter_kernel(const FwdArgs a)
                 }
             }
         }
-        if (full_tile) {
+        if (full_tile && a.stream >= 2) {
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+#pragma unroll
+                for (int s = 0; s < S; ++s) buf_store<float, VEC, kAuxStream>(rh, vh, (unsigned int)(i * S + s) * Hn * 4u, ho[i][s]);
+        } else if (full_tile) {
 #pragma unroll
             for (int i = 0; i < C; ++i)
 #pragma unroll
@@ -1006,8 +1019,9 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
             return lt_ > 0 && (lt_ + 1) * T <= g.L && (cg_ + 1) * CW <= g.H;
         }
     };
-    auto stage_tile = [&](unsigned int t_) {
+    auto stage_tile_as = [&](unsigned int t_, auto stream) {
         if constexpr (STAGE) {
+            constexpr int kAux = decltype(stream)::value ? kAuxStream : kAuxNone;
             typedef __attribute__((address_space(3))) void *lds_ptr;
             const int grp_ = (int)(t_ % (unsigned int)g.n_groups);
             const int lt_ = g.n_lt - 1 - (int)(t_ / (unsigned int)g.n_groups);
@@ -1022,15 +1036,19 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
             for (int j = 0; j < kRowsU / 8; ++j)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(su, (lds_ptr)&s_stage[w][j * 256], 16, voff,
-                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, kAux);
 #pragma unroll
             for (int j = 0; j < kRowsS / 8; ++j) {
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(sh, (lds_ptr)&s_stage[w][(kRowsU / 8 + j) * 256], 16, voff,
-                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+                                                         (unsigned int)(j * 8) * Hn_ * 2u, 0, kAux);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(sg, (lds_ptr)&s_stage[w][((kRowsU + kRowsS) / 8 + j) * 256], 16,
-                                                         voff, (unsigned int)(j * 8) * Hn_ * 2u, 0, 0);
+                                                         voff, (unsigned int)(j * 8) * Hn_ * 2u, 0, kAux);
             }
         }
+    };
+    auto stage_tile = [&](unsigned int t_) {
+        if (a.stream) stage_tile_as(t_, std::true_type{});
+        else stage_tile_as(t_, std::false_type{});
     };
     unsigned int t = 0, t_next = 0;
     bool cur_staged = false;
@@ -1402,7 +1420,13 @@ __global__ __launch_bounds__(kWave *W) void backward_kernel(const BwdArgs a)
 #pragma unroll
             for (int s = 0; s < S; ++s) nu0[s][v] = n0[s];
         }
-        if (full_tile) {
+        if (STAGE && full_tile && a.stream) {
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+#pragma unroll
+                for (int q = 0; q < G; ++q)
+                    buf_store<UT, VEC, kAuxStream>(rdu, vu, (unsigned int)(i * G + q) * Hn * (unsigned int)sizeof(UT), duv[i][q]);
+        } else if (full_tile) {
 #pragma unroll
             for (int i = 0; i < C; ++i)
 #pragma unroll

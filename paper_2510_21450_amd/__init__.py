@@ -13,7 +13,7 @@ import importlib
 _BINDING = ["CELLS", "DTYPES", "STATUS", "UserCell", "example_cell", "affine_scan", "backward", "cell_dims",
             "dense_chunk", "dense_chunk_products", "device_info", "forward", "forward_ex", "forward_noalloc", "input_projection", "input_projection_backward",
             "input_projection_workspace_bytes", "lib_path", "residual_norm", "set_dense_jacobian", "set_dense_tail", "set_dense_products", "set_fused", "set_fused_tail", "set_workspace_reuse",
-            "set_fused_head", "set_spin_limit", "set_staging", "set_tile", "solve_plan", "solve_plan_ex", "status_string", "version", "workspace_bytes",
+            "set_fused_head", "set_spin_limit", "set_staging", "set_streaming", "set_tile", "solve_plan", "solve_plan_ex", "status_string", "version", "workspace_bytes",
             "workspace_bytes_fused"]
 _AUTOGRAD = ["rnn_apply", "rnn_layer", "input_projection_apply"]
 __all__ = _AUTOGRAD + _BINDING

@@ -42,6 +42,7 @@ _lib.pararnn_set_fused.argtypes = [_i]
 _lib.pararnn_set_fused_tail.argtypes = [_i]
 _lib.pararnn_set_workspace_reuse.argtypes = [_i]
 _lib.pararnn_set_staging.argtypes = [_i]
+_lib.pararnn_set_streaming.argtypes = [_i]
 _lib.pararnn_set_dense_products.argtypes = [_i]
 _lib.pararnn_set_fused_head.argtypes = [_i]
 _lib.pararnn_solve_plan.restype = _i
@@ -228,6 +229,12 @@ def solve_plan(tol: float, max_iter: int):
     if n < 0:
         raise ValueError("pararnn_solve_plan: invalid arguments")
     return [buf[i] for i in range(n)]
+
+
+def set_streaming(mode: int = 0) -> None:
+    """pararnn_set_streaming: streamed tile accesses of the memory-bound kernels chosen by size (0, default),
+    never (1) or always (2)."""
+    _raise(_lib.pararnn_set_streaming(int(mode)), "pararnn_set_streaming")
 
 
 def set_workspace_reuse(enable: bool = False) -> None:

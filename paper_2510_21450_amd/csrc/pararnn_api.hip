@@ -14,7 +14,7 @@ namespace pararnn {
 
 Settings &settings()
 {
-    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1, 1, 0};
+    static Settings s = {1, 5, {-1, 0, 0, 0}, kSpinLimit, 1, 1, 0, 0};
     return s;
 }
 
@@ -191,6 +191,13 @@ int pararnn_set_staging(int enable)
 {
     settings().stage_enabled = enable ? 1 : 0;
     return proj_set_dma(enable);
+}
+
+int pararnn_set_streaming(int mode)
+{
+    if (mode < 0 || mode > 2) return PARARNN_INVALID_ARG;
+    settings().streaming = mode;
+    return PARARNN_OK;
 }
 
 int pararnn_set_fused(int enable)

@@ -553,6 +553,40 @@ def test_backward_inputs_staged_through_lds(P, oracle_mod, as_stored, cell):
 
 
 @pytest.mark.parametrize("cell,dtype", [("gru_diag", torch.float32), ("lstm_diag", torch.float32), ("gru_diag", torch.bfloat16)])
+def test_streamed_tile_accesses_give_the_same_bits(P, oracle_mod, as_stored, cell, dtype):
+    """pararnn_set_streaming: the per-iteration forward kernel and the bf16 backward kernel with their
+    interior tiles' accesses marked as streamed (mode 2; what large problems get by themselves) against
+    plain accesses (mode 1).  Only the cache policy differs: same bits, iteration count and trace; the
+    plain result is checked against the oracle."""
+    B, L, H = 2, 1100, 200
+    params, u, h0, g = problem(cell, B, L, H, seed=4242, dtype=dtype)
+    pn, un, h0n = to_np(params), to_np(u), to_np(h0)
+    fwd, bwd = [], []
+    try:
+        P.set_fused(False)                      # one launch per iteration: the kernel that takes the flag
+        for mode in (1, 2, 0):
+            print(f"streaming mode {mode} {cell} {dtype}", flush=True)
+            P.set_streaming(mode)
+            h, iters, trace = P.forward(cell, params, u, h0, tol=-1.0, max_iter=6, trace=True)
+            fwd.append((h, trace, iters))
+            bwd.append(P.backward(cell, params, u, h0, h, g))
+        torch.cuda.synchronize()
+    finally:
+        P.set_streaming(0)
+        P.set_fused(True)
+    for other in (1, 2):
+        for a, b in zip(fwd[0], fwd[other]):
+            assert torch.equal(a, b)
+        for a, b in zip(bwd[0], bwd[other]):
+            assert torch.equal(a, b)
+    ref = oracle_mod.seq_unroll(cell, pn, un, h0n)
+    tol_h = TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+    assert relerr(to_np(fwd[0][0]), ref) <= tol_h
+    with pytest.raises(RuntimeError):
+        P.set_streaming(3)
+
+
+@pytest.mark.parametrize("cell,dtype", [("gru_diag", torch.float32), ("lstm_diag", torch.float32), ("gru_diag", torch.bfloat16)])
 def test_blocks_after_the_first_in_one_launch(P, oracle_mod, cell, dtype):
     """The rest of a solve's plan in one persistent launch (pararnn_set_fused_tail, the default) against one
     launch per block: a first block of 1, 2 or 3 iterations and the one iteration that follows it leave
