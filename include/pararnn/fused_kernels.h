@@ -108,13 +108,50 @@ __device__ __forceinline__ bool fused_grid_barrier(unsigned int *arrivals, unsig
 // because the block's size and position are then loop variables that stay in registers, where the
 // one-block variant re-reads them from the kernel arguments, and the first block of the bf16 GRU
 // sits one register short of losing a wave per SIMD
+// S rows of CW record words (8 bytes each, consecutive columns) from memory straight into LDS, 16
+// bytes per lane, past the L2 like every record access (sc1), issued from an asm statement so that
+// the compiler neither tracks nor waits for it: the caller waits (s_waitcnt vmcnt) before it reads
+// dst.  A record word lies inside one aligned 16-byte piece, which the memory system serves in one
+// access, so a word is still seen whole.  M0 holds the LDS address; the wait states are the ones a
+// vector-memory instruction needs after its scalar operands were written.
+template <int S, int CW>
+__device__ __forceinline__ void early_look(rec_t (*dst)[CW], const rec_t *src, int lane)
+{
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const unsigned long long p = (unsigned long long)src;
+    const u4 rsrc = {(unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)p),
+                     (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)(p >> 32)) & 0xffffu, 0xffffffffu, 0x27000u};
+    const unsigned int lds = (unsigned int)(unsigned long long)(__attribute__((address_space(3))) const void *)&dst[0][0];
+    if (lane < CW / 2) {
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen sc1 lds"
+                         ::"s"((unsigned int)__builtin_amdgcn_readfirstlane(lds + (unsigned int)(s * CW * 8))),
+                         "v"((unsigned int)lane * 16u), "s"(rsrc), "s"((unsigned int)(s * CW * 8))
+                         : "memory", "m0");
+    }
+}
+
+// Waves per SIMD the register allocation must leave room for: four (128 registers) for scalar states with
+// chunks of up to 12 steps and two (256) for 2 x 2 blocks, whose default shapes sit at those limits; no
+// demand otherwise.
+template <class Cell, int VEC, int C> constexpr int fused_min_waves()
+{
+    return Cell::S == 1 && VEC == 1 && C <= 12 ? 4 : (Cell::S == 2 && VEC == 1 ? 2 : 1);
+}
+
 template <class Cell, int VEC, int LL, int C, int W, typename UT, bool TAIL = false>
-__global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs a)
+__global__ __launch_bounds__(kWave *W) __attribute__((amdgpu_waves_per_eu(fused_min_waves<Cell, VEC, C>())))
+void newton_fused_kernel(const FusedArgs a)
 {
     constexpr int S = Cell::S, G = Cell::G, SS = S * S, PR = Cell::PR;
     constexpr int LPS = kWave / LL, CW = LPS * VEC, NW = SS + 2 * S, T = C * LL * W;
     __shared__ float s_A[W][SS][CW];
     __shared__ float s_b[W][S][CW];
+    __shared__ float s_carry[S][CW];
+    __shared__ float s_incl[S][CW];
+    constexpr bool kEarly = CW <= 128;                 // a row of records fits one copy instruction (64 lanes x 16 bytes)
+    __shared__ __attribute__((aligned(16))) rec_t s_pre[kEarly ? S : 1][kEarly ? CW : 2];
     __shared__ unsigned int s_maxk[kMaxFused];
     __shared__ unsigned int s_ticket;
 
@@ -281,6 +318,19 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
         // (2x2 blocks and larger: the doubled loop costs them a wave per SIMD).
         auto iterations = [&](auto mode) {
             constexpr int kMode = decltype(mode)::value;
+            // nothing in flight when the loop starts (the inputs have been used by now, what remains are the
+            // last tile's stores): inside the loop the only load a wave may wait for is then the early look
+            // at the predecessor's record, and the thread-level pass runs while it travels
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0) only
+            // ---- the predecessor's inclusive value of an iteration is asked for one iteration ahead (the
+            //      first one here) and looked at when the workgroup level needs it: a tile whose predecessor
+            //      is that far ahead finds its carry waiting instead of paying a round trip to memory, about
+            //      as long as the rest of an iteration, while its other waves wait.  The record rows travel
+            //      straight into LDS (early_look): no register is their destination, so the compiled code
+            //      has no wait for them; wave 0 waits where it reads them.
+            const bool looks_back = kEarly && w == 0 && lt > 0;
+            const rec_t *pre_src = a.rec + ((size_t)grp * g.n_lt + (lt > 0 ? lt - 1 : 0)) * (NW * CW) + (SS + S) * CW;
+            if (looks_back) early_look<S, CW>(s_pre, pre_src, lane);
 #pragma unroll 1
             for (int k = 1; k <= K; ++k) {
                 // unique within the call; the one-block variant takes the sum of the constant part from the kernel
@@ -371,6 +421,21 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 }
                 __syncthreads();
                 if (w == 0) {
+                    // the early look is waited for here, by the only wave that has one in flight (and no
+                    // stores of its own in flight unless it took the slow path below an iteration ago)
+                    rec_t pre[S][VEC];
+                    if constexpr (kEarly) {
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                        for (int s = 0; s < S; ++s)
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) pre[s][v] = s_pre[s][col + v];
+                    } else {
+#pragma unroll
+                        for (int s = 0; s < S; ++s)
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) pre[s][v] = 0;
+                    }
                     // ---- workgroup level, by wave 0 alone: it walks the waves' aggregates once, leaving in
                     //      place of each the composition of the waves before it, and ends with the tile's
                     //      aggregate.  (Every wave used to compose its own prefix from the same values: W/2
@@ -382,22 +447,61 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
 #pragma unroll
                         for (int s = 0; s < S; ++s) exB[v][s] = 0.0f;
                     }
+                    if constexpr (S == 1) {
+                        // the aggregates in batches of JB LDS reads (one latency per batch instead of one per
+                        // wave), composed in registers, the prefixes written back in one batch
+                        constexpr int JB = W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1);
 #pragma unroll
-                    for (int j = 0; j < W; ++j) {
+                        for (int j0 = 0; j0 < W; j0 += JB) {
+                            float Aw[JB][VEC][SS], bw[JB][VEC][S];
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-                            float Aj[SS], bj[S];
+                            for (int j = 0; j < JB; ++j)
 #pragma unroll
-                            for (int e = 0; e < SS; ++e) {
-                                Aj[e] = s_A[j][e][col + v];
-                                s_A[j][e][col + v] = exA[v][e];
+                                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                                    for (int e = 0; e < SS; ++e) Aw[j][v][e] = s_A[j0 + j][e][col + v];
+#pragma unroll
+                                    for (int s = 0; s < S; ++s) bw[j][v][s] = s_b[j0 + j][s][col + v];
+                                }
+#pragma unroll
+                            for (int j = 0; j < JB; ++j)
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    float Aj[SS], bj[S];
+#pragma unroll
+                                    for (int e = 0; e < SS; ++e) { Aj[e] = Aw[j][v][e]; Aw[j][v][e] = exA[v][e]; }
+#pragma unroll
+                                    for (int s = 0; s < S; ++s) { bj[s] = bw[j][v][s]; bw[j][v][s] = exB[v][s]; }
+                                    push_step<S>(Aj, bj, exA[v], exB[v]);
+                                }
+#pragma unroll
+                            for (int j = 0; j < JB; ++j)
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+                                    for (int e = 0; e < SS; ++e) s_A[j0 + j][e][col + v] = Aw[j][v][e];
+#pragma unroll
+                                    for (int s = 0; s < S; ++s) s_b[j0 + j][s][col + v] = bw[j][v][s];
+                                }
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < W; ++j) {
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                float Aj[SS], bj[S];
+#pragma unroll
+                                for (int e = 0; e < SS; ++e) {
+                                    Aj[e] = s_A[j][e][col + v];
+                                    s_A[j][e][col + v] = exA[v][e];
+                                }
+#pragma unroll
+                                for (int s = 0; s < S; ++s) {
+                                    bj[s] = s_b[j][s][col + v];
+                                    s_b[j][s][col + v] = exB[v][s];
+                                }
+                                push_step<S>(Aj, bj, exA[v], exB[v]);
                             }
-#pragma unroll
-                            for (int s = 0; s < S; ++s) {
-                                bj[s] = s_b[j][s][col + v];
-                                s_b[j][s][col + v] = exB[v][s];
-                            }
-                            push_step<S>(Aj, bj, exA[v], exB[v]);
                         }
                     }
                     // ---- grid level: look-back within this iteration's record slot
@@ -412,7 +516,23 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                     const bool active = seg == 0;
                     const bool has_next = lt + 1 < g.n_lt;
                     rec_t *rec = reck + ((size_t)grp * g.n_lt + lt) * (NW * CW);
-                    if (lt > 0) {
+                    bool early = lt > 0;
+#pragma unroll
+                    for (int s = 0; s < S; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            early = early && (unsigned int)(pre[s][v] >> 32) == epoch * 4u + kFlagIncl;
+                            carry[s][v] = __uint_as_float((unsigned int)pre[s][v]);
+                        }
+                    early = kEarly && __all(early || !active) && lt > 0;
+                    if (!early) {                 // also the first tile of a chain: nothing enters it
+#pragma unroll
+                        for (int s = 0; s < S; ++s)
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) carry[s][v] = 0.0f;
+                    }
+                    if (looks_back && k < K) early_look<S, CW>(s_pre, pre_src + (size_t)k * a.rec_stride, lane);
+                    if (lt > 0 && !early) {
                         if (has_next) {
                             float ab[SS + S][VEC];
 #pragma unroll
@@ -427,8 +547,11 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                         if (!lookback<S, VEC, CW>(g.spin_limit, reck, g.n_lt, grp, lt, -1, epoch, col, active, carry))
                             internal_error = true;
                     }
-                    if (has_next) {
-                        float inc[S][VEC];
+                    // ---- the carry, for every wave to apply its own prefix to (it lives in the lanes of segment
+                    //      0), and the tile's inclusive value in the form a look-back over this tile's aggregate
+                    //      would give it (same bits whichever way a successor comes by it), for the last wave to
+                    //      publish
+                    if (active) {
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) {
                             float A1[SS], x[S], b1[S], y[S];
@@ -438,25 +561,9 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                             for (int s = 0; s < S; ++s) { x[s] = carry[s][v]; b1[s] = tileB[s][v]; }
                             affine<S>(A1, x, b1, y);
 #pragma unroll
-                            for (int s = 0; s < S; ++s) inc[s][v] = y[s];
-                        }
-                        publish<S, VEC, CW>(rec + (SS + S) * CW, inc, epoch * 4u + kFlagIncl, col, active);
-                    }
-                    // ---- the delta that enters each wave's first step: its prefix applied to the carry
-#pragma unroll
-                    for (int j = 0; j < W; ++j) {
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-                            float Aj[SS], bj[S], cin[S], din[S];
-#pragma unroll
-                            for (int e = 0; e < SS; ++e) Aj[e] = s_A[j][e][col + v];
-#pragma unroll
-                            for (int s = 0; s < S; ++s) { bj[s] = s_b[j][s][col + v]; cin[s] = carry[s][v]; }
-                            affine<S>(Aj, cin, bj, din);
-                            // the carry lives in the lanes of segment 0 (the others hold the same prefixes)
-                            if (active) {
-#pragma unroll
-                                for (int s = 0; s < S; ++s) s_b[j][s][col + v] = din[s];
+                            for (int s = 0; s < S; ++s) {
+                                s_carry[s][col + v] = carry[s][v];
+                                s_incl[s][col + v] = y[s];
                             }
                         }
                     }
@@ -464,14 +571,30 @@ __global__ __launch_bounds__(kWave *W) void newton_fused_kernel(const FusedArgs 
                 __syncthreads();
 
                 // ---- back-substitution; the delta entering the chunk also updates the state before it
+                // ---- the tile's inclusive value leaves through the last wave, which never waits for a load
+                //      inside the loop: the store's way to memory is then nobody's waiting time (wave 0 would
+                //      meet it at its next wait for the early look)
+                if (w == W - 1 && lt + 1 < g.n_lt) {
+                    float inc[S][VEC];
+#pragma unroll
+                    for (int s = 0; s < S; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) inc[s][v] = s_incl[s][col + v];
+                    publish<S, VEC, CW>(reck + ((size_t)grp * g.n_lt + lt) * (NW * CW) + (SS + S) * CW, inc,
+                                        epoch * 4u + kFlagIncl, col, seg == 0);
+                }
                 unsigned int wmax_bits = 0u;
                 auto back_substitute = [&](auto gd) {
                     constexpr bool kG = decltype(gd)::value;
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        float din[S];
+                        // the delta that enters this wave's first step: its prefix applied to the tile's carry
+                        float din[S], cin[S], Aw[SS], bw[S];
 #pragma unroll
-                        for (int s = 0; s < S; ++s) din[s] = s_b[w][s][col + v];
+                        for (int e = 0; e < SS; ++e) Aw[e] = s_A[w][e][col + v];
+#pragma unroll
+                        for (int s = 0; s < S; ++s) { bw[s] = s_b[w][s][col + v]; cin[s] = s_carry[s][col + v]; }
+                        affine<S>(Aw, cin, bw, din);
                         if constexpr (LL > 1) affine<S>(lexA[v], din, lexB[v], din);
 #pragma unroll
                         for (int s = 0; s < S; ++s) hprev[s][v] += din[s];

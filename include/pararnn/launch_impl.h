@@ -26,7 +26,7 @@ template <class Cell, int VEC, int C> constexpr bool shape_offered()
 template <class Cell, int VEC, int LL, int W> constexpr bool forward_fits_lds()
 {
     constexpr int S = Cell::S, SS = S * S;
-    return (size_t)(W * (SS + S) + S) * (kWave / LL) * VEC * sizeof(float) + 4 * W + 64 <= 65536;
+    return (size_t)(W * (SS + S) + 4 * S) * (kWave / LL) * VEC * sizeof(float) + 4 * W + 64 <= 65536;
 }
 
 // static LDS of the backward kernel must stay within 64 KiB

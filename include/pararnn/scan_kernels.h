@@ -251,16 +251,21 @@ __device__ __forceinline__ bool lookback(unsigned int spin_limit, const rec_t *r
     unsigned int spins = 0;
     for (;;) {
         const rec_t *rj = rec_base + ((size_t)grp * n_lt + j) * (NW * CW) + col;
-        // inclusive value of tile j
-        rec_t wi[S][VEC];
+        // inclusive value and aggregate of tile j, asked for together: one trip to memory per look
+        rec_t wi[S][VEC], wa[SS + S][VEC];
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) wi[s][v] = active ? rec_load(rj + (SS + S + s) * CW + v) : 0;
+#pragma unroll
+        for (int e = 0; e < SS + S; ++e)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) wa[e][v] = active ? rec_load(rj + e * CW + v) : 0;
         bool ok = true;
 #pragma unroll
         for (int s = 0; s < S; ++s)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                wi[s][v] = active ? rec_load(rj + (SS + S + s) * CW + v) : 0;
-                ok = ok && (unsigned int)(wi[s][v] >> 32) == tag_inc;
-            }
+            for (int v = 0; v < VEC; ++v) ok &= (unsigned int)(wi[s][v] >> 32) == tag_inc;
         if (__all(ok || !active)) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
@@ -273,16 +278,11 @@ __device__ __forceinline__ bool lookback(unsigned int spin_limit, const rec_t *r
             }
             return true;
         }
-        // aggregate of tile j
-        rec_t wa[SS + S][VEC];
         ok = true;
 #pragma unroll
         for (int e = 0; e < SS + S; ++e)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                wa[e][v] = active ? rec_load(rj + e * CW + v) : 0;
-                ok = ok && (unsigned int)(wa[e][v] >> 32) == tag_agg;
-            }
+            for (int v = 0; v < VEC; ++v) ok &= (unsigned int)(wa[e][v] >> 32) == tag_agg;
         if (__all(ok || !active)) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
