@@ -31,9 +31,12 @@ sys.path.insert(0, ROOT)
 METRIC = "Newton-solve timesteps*channels/s (fwd+bwd), % HBM roofline, 1 MI355X"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak, published
-# fp32 vector peak of the instructions this build may use: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (FMA).
-# The published 157.3 TFLOP/s needs packed two-wide FMAs, which the build switches off.
-VALU_F32_PEAK_TFLOPS = 78.6
+# fp32 vector peak, published: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz x 2 (FMA).  A SIMD issues a plain
+# (not packed) wave-wide fp32 instruction every 2 cycles and a transcendental one (v_exp_f32, v_rcp_f32)
+# every 8, measured with loops of independent instructions at full occupancy; packed forms are off.
+VALU_F32_PEAK_TFLOPS = 157.3
+VALU_CYCLES_PLAIN, VALU_CYCLES_TRANS = 2.0, 8.0
+SIMDS, CLOCK_HZ = 1024, 2.4e9
 FUSED_HEAD = 5                 # iterations in the first launch of a solve (the library's default)
 # algorithmic bytes per timestep-channel (per-iteration kernel: read u + read iterate + write iterate;
 # fused block: read u + write h, plus the fp32 iterate it leaves for later launches under bf16 storage;
@@ -244,6 +247,17 @@ def kernel_figures(run, reps, counters):
     busy = cnt.get("dominant", {}).get("valu_busy_cycles")
     # share of the launch during which the vector ALUs were issuing (1024 SIMDs at 2.4 GHz)
     out["block_valu_busy_frac"] = busy / (t_block_ms * 1e-3 * 1024 * 2.4e9) if busy else None
+    # the launch's own instruction mix at the issue rates above: the time the vector ALUs need for the
+    # instructions the kernel executes (counted by the profiler), at the nominal clock
+    dom = cnt.get("dominant", {})
+    if dom.get("valu_insts_per_elt_iter") and dom.get("trans_insts_per_elt_iter") is not None:
+        vi, ti = dom["valu_insts_per_elt_iter"], dom["trans_insts_per_elt_iter"]
+        cyc = float(N) * K0 / 64.0 * ((vi - ti) * VALU_CYCLES_PLAIN + ti * VALU_CYCLES_TRANS)
+        t_issue_ms = cyc / (SIMDS * CLOCK_HZ) * 1e3
+        out["block_issue_bound_ms"] = t_issue_ms
+        out["block_issue_bound_frac"] = t_issue_ms / t_block_ms
+    else:
+        out["block_issue_bound_ms"] = out["block_issue_bound_frac"] = None
     out["roofline"] = {"bound": "alu", "kernel": "newton_fused_kernel (first block of a solve)", "achieved": ach,
                        "peak": VALU_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / VALU_F32_PEAK_TFLOPS,
                        "traffic": cnt.get("dominant", {}).get("traffic_bytes")}
