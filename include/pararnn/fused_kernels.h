@@ -104,10 +104,6 @@ __device__ __forceinline__ bool fused_grid_barrier(unsigned int *arrivals, unsig
     return __builtin_amdgcn_readfirstlane(s_ok) != 0;
 }
 
-// TAIL: the launch goes on with the following blocks of the plan (a.tail is set); a variant of its own
-// because the block's size and position are then loop variables that stay in registers, where the
-// one-block variant re-reads them from the kernel arguments, and the first block of the bf16 GRU
-// sits one register short of losing a wave per SIMD
 // S rows of CW record words (8 bytes each, consecutive columns) from memory straight into LDS, 16
 // bytes per lane, past the L2 like every record access (sc1), issued from an asm statement so that
 // the compiler neither tracks nor waits for it: the caller waits (s_waitcnt vmcnt) before it reads
@@ -140,6 +136,10 @@ template <class Cell, int VEC, int C> constexpr int fused_min_waves()
     return Cell::S == 1 && VEC == 1 && C <= 12 ? 4 : (Cell::S == 2 && VEC == 1 ? 2 : 1);
 }
 
+// TAIL: the launch goes on with the following blocks of the plan (a.tail is set); a variant of its own
+// because the block's size and position are then loop variables that stay in registers, where the
+// one-block variant re-reads them from the kernel arguments, and the first block of the bf16 GRU
+// sits one register short of losing a wave per SIMD
 template <class Cell, int VEC, int LL, int C, int W, typename UT, bool TAIL = false>
 __global__ __launch_bounds__(kWave *W) __attribute__((amdgpu_waves_per_eu(fused_min_waves<Cell, VEC, C>())))
 void newton_fused_kernel(const FusedArgs a)
