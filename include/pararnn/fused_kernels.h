@@ -421,6 +421,8 @@ void newton_fused_kernel(const FusedArgs a)
                 }
                 __syncthreads();
                 if (w == 0) {
+                    // seven waves wait at the next barrier for what this one does now: it goes first on its SIMD
+                    __builtin_amdgcn_s_setprio(3);
                     // the early look is waited for here, by the only wave that has one in flight (and no
                     // stores of its own in flight unless it took the slow path below an iteration ago)
                     rec_t pre[S][VEC];
@@ -567,6 +569,7 @@ void newton_fused_kernel(const FusedArgs a)
                             }
                         }
                     }
+                    __builtin_amdgcn_s_setprio(0);
                 }
                 __syncthreads();
 
