@@ -223,6 +223,8 @@ void newton_fused_kernel(const FusedArgs a)
                 }
             }
         };
+        // a new tile's loads go out ahead of the arithmetic of the waves that share the SIMD
+        __builtin_amdgcn_s_setprio(2);
         if (full_tile) load_inputs(std::false_type{});
         else load_inputs(std::true_type{});
 #pragma unroll
@@ -316,6 +318,7 @@ void newton_fused_kernel(const FusedArgs a)
         // the register shuffling where two forms meet inside the loop (6 % on the GRU); mode 2: one loop
         // that chooses inside each phase, for cells whose state no longer fits the registers twice over
         // (2x2 blocks and larger: the doubled loop costs them a wave per SIMD).
+        __builtin_amdgcn_s_setprio(0);
         auto iterations = [&](auto mode) {
             constexpr int kMode = decltype(mode)::value;
             // nothing in flight when the loop starts (the inputs have been used by now, what remains are the
