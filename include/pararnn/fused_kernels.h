@@ -636,6 +636,9 @@ void newton_fused_kernel(const FusedArgs a)
             iterations(std::integral_constant<int, 2>{});
         }
 
+        // from here to the first iteration of the workgroup's next tile (stores, ticket, loads, initial guess)
+        // its waves go ahead of the other workgroup's iterations on the SIMDs they share
+        __builtin_amdgcn_s_setprio(2);
         // ---- what a following per-iteration launch needs: the fp32 iterate and the tile's last row
         if (a.head && k0 + K < a.max_iter) {
             if (a.hit && static_cast<void *>(a.hit) != a.h) {
